@@ -1,0 +1,133 @@
+/*
+ * xnor.h -- C ABI of the MI355X (gfx950) XNOR-Net binary convolution forward pass.
+ *
+ * The calls are the steps of the binary-convolution pipeline of "Optimization of XNOR Convolution
+ * for Binary Convolutional Neural Networks on GPU" (Sec. III-A step list):
+ *
+ *   xnor_binarize_pack  step 1a   sign-binarise and bit-pack along channels      (Eq. 3, Eq. 8)
+ *   xnor_scale_K        step 2a   scaling map K = box filter of mean_c |I|       (Eq. 10)
+ *   xnor_alpha                    per-filter scale alpha = mean |W|              (Eq. 5)
+ *   xnor_conv2d_fwd     steps 1b-1d, 2b, 3: XNOR + popcount convolution, then
+ *                       out = dot * K * alpha                                    (Eq. 11)
+ *
+ * Problem statement (Sec. II): input I of C channels x H x W per image, filters of C x kh x kw with
+ * one alpha each, zero padding.  A batch is N independent images; K is per image.
+ *
+ * Conventions shared by every call
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library allocates nothing,
+ *     frees nothing and keeps no state between calls.  Inputs are never written; outputs are
+ *     overwritten in full.  Outputs must not alias inputs.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue their
+ *     kernels on it and return without synchronising; buffers must stay alive until the stream
+ *     has passed them.
+ *   - Tensors are dense, row-major, in the index order written in each comment.
+ *   - sign(x) = +1 if x >= 0 else -1 (so +0.0 and -0.0 are +1, NaN is -1).  Bit 1 stands for +1,
+ *     bit 0 for -1 (Sec. III-A step 1c).
+ *   - Packed layout: for a tensor x[N][C][H][W] the packed form is uint32 [N][H][W][Cw],
+ *     Cw = ceil(C/32); bit j of word w of a pixel is the sign bit of channel 32w+j; bits of
+ *     channels >= C are 0.  Filters Wt[F][C][kh][kw] are packed by the same call as F "images" of
+ *     kh x kw pixels, giving [F][kh][kw][Cw].
+ *   - Return value: XNOR_OK (0) or a negative xnor_status.  Arguments are validated on the host
+ *     before anything is enqueued; on an error nothing has been launched.  XNOR_E_HIP reports a
+ *     launch failure (text via xnor_strerror / xnor_last_hip_error).
+ */
+#ifndef XNOR_H
+#define XNOR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    XNOR_OK = 0,
+    XNOR_E_NULL = -1,        /* a required pointer is NULL                                        */
+    XNOR_E_SHAPE = -2,       /* a dimension <= 0, stride <= 0, pad < 0, empty output, or a tensor
+                                too large for the kernels' 31-bit pixel / 63-bit byte indexing     */
+    XNOR_E_ALIGN = -3,       /* a pointer is not aligned as the call requires                     */
+    XNOR_E_HIP = -4,         /* the HIP runtime refused a launch                                  */
+    XNOR_E_UNSUPPORTED = -5  /* the requested algorithm cannot run this shape                     */
+} xnor_status;
+
+/* Geometry of one layer (Sec. II problem statement; stride/padding as in Sec. III-B step 1). */
+typedef struct {
+    int N, C, H, W;     /* input   I  [N][C][H][W]  fp32                                          */
+    int F, kh, kw;      /* filters Wt [F][C][kh][kw] fp32                                         */
+    int sh, sw;         /* stride  >= 1                                                           */
+    int ph, pw;         /* zero padding >= 0 (padded taps contribute nothing to dot or K)         */
+} xnor_shape;
+
+/* Which convolution kernel xnor_conv2d_fwd_algo runs. */
+typedef enum {
+    XNOR_ALGO_AUTO = 0,     /* pick per shape (what xnor_conv2d_fwd does)                         */
+    XNOR_ALGO_DIRECT = 1,   /* one thread per output, v_xor + v_bcnt, any shape                   */
+    XNOR_ALGO_TILED = 2,    /* LDS-staged packed halo, wave-uniform filter words, register tile   */
+    XNOR_ALGO_MFMA = 3      /* +-1 expanded to FP4 in LDS, v_mfma_scale_f32_32x32x64_f8f6f4       */
+} xnor_algo;
+
+/* Host helpers (no GPU work). */
+int xnor_out_dim(const xnor_shape *s, int *OH, int *OW); /* OH = (H+2ph-kh)/sh+1, OW likewise      */
+int xnor_packed_words(int C);                            /* ceil(C/32), or XNOR_E_SHAPE if C <= 0  */
+const char *xnor_strerror(int status);                   /* static string, never NULL              */
+const char *xnor_last_hip_error(void);                   /* text of the last XNOR_E_HIP on this
+                                                            thread ("" if none)                    */
+
+/*
+ * Step 1a (Sec. III-A): packed[n][y][x][w] bit j = (x[n][32w+j][y][x] >= 0).
+ *   x       in   fp32 [N][C][H][W]
+ *   packed  out  uint32 [N][H][W][ceil(C/32)], 4-byte aligned
+ * Used for the input (N images) and for the filters (x = Wt, N = F, H = kh, W = kw).
+ */
+int xnor_binarize_pack(const float *x, int N, int C, int H, int W, uint32_t *packed, void *stream);
+
+/*
+ * Eq. 10: A[n][y][x] = (1/C) sum_c |I[n][c][y][x]|, then
+ * K[n][oy][ox] = (1/(kh*kw)) * sum over in-image taps of A[n][oy*sh-ph+ky][ox*sw-pw+kx]
+ * (A is 0 outside the image; the divisor is constant; K uses the convolution's stride and pad).
+ *   I       in   fp32 [N][C][H][W]
+ *   A_work  out  fp32 [N][H][W]   caller-owned workspace; holds A on return
+ *   K       out  fp32 [N][OH][OW]
+ */
+int xnor_scale_K(const float *I, const xnor_shape *s, float *A_work, float *K, void *stream);
+
+/*
+ * Eq. 5: alpha[f] = (1/(C*kh*kw)) sum |Wt[f][c][ky][kx]|.
+ *   Wt     in   fp32 [F][C][kh][kw]
+ *   alpha  out  fp32 [F]
+ */
+int xnor_alpha(const float *Wt, int F, int C, int kh, int kw, float *alpha, void *stream);
+
+/*
+ * Steps 1b-1d and 3 (Sec. III-A), Eq. 11:
+ *   dot[n][f][oy][ox] = sum over in-image taps (ky,kx) and channels c of
+ *                       sign(I[n][c][oy*sh-ph+ky][ox*sw-pw+kx]) * sign(Wt[f][c][ky][kx])
+ *                     = N_valid - 2 * popcount(Ipk xor Wpk)   over the same taps,
+ *                       N_valid = C * (number of in-image taps)
+ *   out = float(dot) * K[n][oy][ox] * alpha[f]
+ *
+ *   Ipk    in   uint32 [N][H][W][Cw]     from xnor_binarize_pack(I)
+ *   Wpk    in   uint32 [F][kh][kw][Cw]   from xnor_binarize_pack(Wt)
+ *   K      in   fp32   [N][OH][OW]
+ *   alpha  in   fp32   [F]
+ *   out    out  fp32   [N][F][OH][OW]
+ *   dot    out  int32  [N][F][OH][OW], or NULL when the raw binary dot products are not wanted
+ * Packed pointers must be 4-byte aligned (16-byte alignment lets the kernels use wider loads).
+ */
+int xnor_conv2d_fwd(const uint32_t *Ipk, const uint32_t *Wpk, const float *K, const float *alpha,
+                    const xnor_shape *s, float *out, int32_t *dot, void *stream);
+
+/* Same, with the kernel chosen by the caller (tests and measurements run every variant).
+ * Returns XNOR_E_UNSUPPORTED if `algo` cannot run this shape; XNOR_ALGO_DIRECT runs every shape. */
+int xnor_conv2d_fwd_algo(const uint32_t *Ipk, const uint32_t *Wpk, const float *K,
+                         const float *alpha, const xnor_shape *s, float *out, int32_t *dot,
+                         int algo, void *stream);
+
+/* The algorithm XNOR_ALGO_AUTO resolves to for this shape (an xnor_algo), or a negative status. */
+int xnor_conv2d_pick_algo(const xnor_shape *s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* XNOR_H */

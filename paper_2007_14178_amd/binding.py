@@ -1,0 +1,178 @@
+"""ctypes binding of the C ABI in include/xnor.h -- argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU, checks dtype / shape /
+contiguity, and passes raw device pointers plus the current HIP stream to the library call of the
+same name.  No step of the pipeline runs in Python or in torch: if the HIP library is missing the
+import of this module fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libxnor_hip.so")
+
+ALGO_AUTO, ALGO_DIRECT, ALGO_TILED, ALGO_MFMA = 0, 1, 2, 3
+ALGO_NAMES = {ALGO_AUTO: "auto", ALGO_DIRECT: "direct", ALGO_TILED: "tiled", ALGO_MFMA: "mfma"}
+E_NULL, E_SHAPE, E_ALIGN, E_HIP, E_UNSUPPORTED = -1, -2, -3, -4, -5
+
+
+class XnorError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib.xnor_strerror(status).decode()
+        if status == E_HIP:
+            msg += ": " + lib.xnor_last_hip_error().decode()
+        super().__init__(f"{where}: {msg} (status {status})")
+
+
+class CShape(ctypes.Structure):
+    _fields_ = [(k, ctypes.c_int) for k in
+                ("N", "C", "H", "W", "F", "kh", "kw", "sh", "sw", "ph", "pw")]
+
+
+@dataclass(frozen=True)
+class Shape:
+    N: int
+    C: int
+    H: int
+    W: int
+    F: int
+    kh: int
+    kw: int
+    sh: int = 1
+    sw: int = 1
+    ph: int = 0
+    pw: int = 0
+
+    def c(self) -> CShape:
+        return CShape(self.N, self.C, self.H, self.W, self.F, self.kh, self.kw,
+                      self.sh, self.sw, self.ph, self.pw)
+
+    @property
+    def Cw(self) -> int:
+        return (self.C + 31) // 32
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2007_14178_amd.build` "
+            "(there is no CPU or PyTorch fallback for the XNOR pipeline)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, ci = ctypes.c_void_p, ctypes.c_int
+    sp = ctypes.POINTER(CShape)
+    L.xnor_out_dim.argtypes = [sp, ctypes.POINTER(ci), ctypes.POINTER(ci)]
+    L.xnor_packed_words.argtypes = [ci]
+    L.xnor_strerror.argtypes = [ci]
+    L.xnor_strerror.restype = ctypes.c_char_p
+    L.xnor_last_hip_error.argtypes = []
+    L.xnor_last_hip_error.restype = ctypes.c_char_p
+    L.xnor_binarize_pack.argtypes = [vp, ci, ci, ci, ci, vp, vp]
+    L.xnor_scale_K.argtypes = [vp, sp, vp, vp, vp]
+    L.xnor_alpha.argtypes = [vp, ci, ci, ci, ci, vp, vp]
+    L.xnor_conv2d_fwd.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp]
+    L.xnor_conv2d_fwd_algo.argtypes = [vp, vp, vp, vp, sp, vp, vp, ci, vp]
+    L.xnor_conv2d_pick_algo.argtypes = [sp]
+    for name in ("xnor_out_dim", "xnor_packed_words", "xnor_binarize_pack", "xnor_scale_K",
+                 "xnor_alpha", "xnor_conv2d_fwd", "xnor_conv2d_fwd_algo", "xnor_conv2d_pick_algo"):
+        getattr(L, name).restype = ci
+    return L
+
+
+lib = _load()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: torch.Tensor, dtype, shape=None, name="tensor") -> int:
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{name}: need a contiguous {dtype} GPU tensor, got {t.dtype} on {t.device}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: shape {tuple(t.shape)} != expected {tuple(shape)}")
+    return t.data_ptr()
+
+
+def _ok(status: int, where: str):
+    if status != 0:
+        raise XnorError(status, where)
+
+
+def xnor_out_dim(s: Shape) -> tuple[int, int]:
+    oh, ow = ctypes.c_int(), ctypes.c_int()
+    _ok(lib.xnor_out_dim(ctypes.byref(s.c()), ctypes.byref(oh), ctypes.byref(ow)), "xnor_out_dim")
+    return oh.value, ow.value
+
+
+def xnor_packed_words(C: int) -> int:
+    r = lib.xnor_packed_words(C)
+    if r < 0:
+        raise XnorError(r, "xnor_packed_words")
+    return r
+
+
+def xnor_binarize_pack(x: torch.Tensor, packed: torch.Tensor | None = None) -> torch.Tensor:
+    """x fp32 [N][C][H][W] -> int32-typed tensor of uint32 words [N][H][W][ceil(C/32)]."""
+    N, C, H, W = x.shape
+    if packed is None:
+        packed = torch.empty((N, H, W, (C + 31) // 32), dtype=torch.int32, device=x.device)
+    _ok(lib.xnor_binarize_pack(_dev(x, torch.float32, name="x"), N, C, H, W,
+                               _dev(packed, torch.int32, (N, H, W, (C + 31) // 32), "packed"),
+                               _stream()), "xnor_binarize_pack")
+    return packed
+
+
+def xnor_scale_K(I: torch.Tensor, s: Shape, A_work: torch.Tensor | None = None,
+                 K: torch.Tensor | None = None) -> tuple[torch.Tensor, torch.Tensor]:
+    """Returns (K [N][OH][OW], A [N][H][W])."""
+    OH, OW = xnor_out_dim(s)
+    if A_work is None:
+        A_work = torch.empty((s.N, s.H, s.W), dtype=torch.float32, device=I.device)
+    if K is None:
+        K = torch.empty((s.N, OH, OW), dtype=torch.float32, device=I.device)
+    _ok(lib.xnor_scale_K(_dev(I, torch.float32, (s.N, s.C, s.H, s.W), "I"), ctypes.byref(s.c()),
+                         _dev(A_work, torch.float32, (s.N, s.H, s.W), "A_work"),
+                         _dev(K, torch.float32, (s.N, OH, OW), "K"), _stream()), "xnor_scale_K")
+    return K, A_work
+
+
+def xnor_alpha(Wt: torch.Tensor, alpha: torch.Tensor | None = None) -> torch.Tensor:
+    F, C, kh, kw = Wt.shape
+    if alpha is None:
+        alpha = torch.empty((F,), dtype=torch.float32, device=Wt.device)
+    _ok(lib.xnor_alpha(_dev(Wt, torch.float32, name="Wt"), F, C, kh, kw,
+                       _dev(alpha, torch.float32, (F,), "alpha"), _stream()), "xnor_alpha")
+    return alpha
+
+
+def xnor_conv2d_pick_algo(s: Shape) -> int:
+    r = lib.xnor_conv2d_pick_algo(ctypes.byref(s.c()))
+    if r < 0:
+        raise XnorError(r, "xnor_conv2d_pick_algo")
+    return r
+
+
+def xnor_conv2d_fwd(Ipk: torch.Tensor, Wpk: torch.Tensor, K: torch.Tensor, alpha: torch.Tensor,
+                    s: Shape, out: torch.Tensor | None = None, dot: torch.Tensor | None = None,
+                    want_dot: bool = False, algo: int = ALGO_AUTO):
+    """Returns (out fp32 [N][F][OH][OW], dot int32 or None)."""
+    OH, OW = xnor_out_dim(s)
+    oshape = (s.N, s.F, OH, OW)
+    if out is None:
+        out = torch.empty(oshape, dtype=torch.float32, device=Ipk.device)
+    if dot is None and want_dot:
+        dot = torch.empty(oshape, dtype=torch.int32, device=Ipk.device)
+    _ok(lib.xnor_conv2d_fwd_algo(
+        _dev(Ipk, torch.int32, (s.N, s.H, s.W, s.Cw), "Ipk"),
+        _dev(Wpk, torch.int32, (s.F, s.kh, s.kw, s.Cw), "Wpk"),
+        _dev(K, torch.float32, (s.N, OH, OW), "K"), _dev(alpha, torch.float32, (s.F,), "alpha"),
+        ctypes.byref(s.c()), _dev(out, torch.float32, oshape, "out"),
+        _dev(dot, torch.int32, oshape, "dot") if dot is not None else None,
+        algo, _stream()), f"xnor_conv2d_fwd[{ALGO_NAMES.get(algo, algo)}]")
+    return out, dot

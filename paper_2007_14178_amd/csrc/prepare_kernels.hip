@@ -1,0 +1,183 @@
+// HBM-streaming stages of the binary-convolution pipeline (Sec. III-A step list):
+//   step 1a  sign-binarise + channel bit-pack          (Eq. 3 / Eq. 8)
+//   step 2a  channel mean of |I| and its box filter K  (Eq. 10)
+//            per-filter alpha = mean |W|               (Eq. 5)
+// All three read fp32 once and write far less than they read, so each is laid out for coalesced
+// 256-byte wavefront reads along the image's fastest axis with many loads in flight per lane.
+#include "xnor_internal.hpp"
+
+namespace xnor {
+
+// ------------------------------------------------------------------------------------------------
+// Step 1a.  One lane owns one pixel and builds WPT packed words from 32*WPT channel planes; the 64
+// lanes of a wave read 64 consecutive pixels of one plane (256 contiguous bytes) per load.
+// The paper sets bits one by one in a register per spatial tile (Alg. 1); packing along channels
+// instead gives every bit of every word a use in the convolution.
+// ------------------------------------------------------------------------------------------------
+template <int WPT>
+__global__ __launch_bounds__(256) void binarize_pack_kernel(const float *__restrict__ x,
+                                                            long long NP, int C, int HW, int Cw,
+                                                            uint32_t *__restrict__ packed)
+{
+    const long long p = (long long)blockIdx.x * 256 + threadIdx.x;
+    const int w0 = blockIdx.y * WPT;
+    if (p >= NP) return;
+    const long long n = p / HW;
+    const int hw = (int)(p - n * HW);
+    const float *src = x + (n * C) * (long long)HW + hw;
+
+    uint32_t words[WPT];
+#pragma unroll
+    for (int k = 0; k < WPT; ++k) {
+        const int cbase = 32 * (w0 + k);
+        uint32_t word = 0;
+        if (cbase + 32 <= C) {
+            float v[32];
+#pragma unroll
+            for (int j = 0; j < 32; ++j) v[j] = __builtin_nontemporal_load(src + (long long)(cbase + j) * HW);
+#pragma unroll
+            for (int j = 0; j < 32; ++j) word |= (v[j] >= 0.0f ? 1u : 0u) << j;
+        } else {
+            for (int j = 0; j < 32 && cbase + j < C; ++j)
+                word |= (src[(long long)(cbase + j) * HW] >= 0.0f ? 1u : 0u) << j;
+        }
+        words[k] = word;
+    }
+    uint32_t *dst = packed + p * Cw + w0;
+    if (WPT == 4 && (Cw & 3) == 0) {
+        *reinterpret_cast<uint4 *>(dst) = make_uint4(words[0], words[1], words[2], words[3]);
+    } else {
+#pragma unroll
+        for (int k = 0; k < WPT; ++k)
+            if (w0 + k < Cw) dst[k] = words[k];
+    }
+}
+
+hipError_t launch_binarize_pack(const float *x, int N, int C, int H, int W, uint32_t *packed,
+                                hipStream_t st)
+{
+    const int HW = H * W, Cw = (C + 31) / 32;
+    const long long NP = (long long)N * HW;
+    const bool vec4 = (Cw % 4 == 0) && ((reinterpret_cast<uintptr_t>(packed) & 15) == 0);
+    if (vec4) {
+        dim3 grid(ceil_div(NP, 256), Cw / 4);
+        binarize_pack_kernel<4><<<grid, 256, 0, st>>>(x, NP, C, HW, Cw, packed);
+    } else {
+        dim3 grid(ceil_div(NP, 256), Cw);
+        binarize_pack_kernel<1><<<grid, 256, 0, st>>>(x, NP, C, HW, Cw, packed);
+    }
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Eq. 10, first half: A = (1/C) sum_c |I_c|.  A block is 64 pixels x S channel slices; each thread
+// adds its slice in double, the slices are combined through LDS in a fixed order (deterministic,
+// and the double accumulation keeps A within one rounding of the exact mean).
+// The paper uses one thread per pixel over all channels; slicing the channels keeps enough loads
+// in flight to stream HBM when N*H*W alone gives too few waves.
+// ------------------------------------------------------------------------------------------------
+constexpr int kMaxSlices = 16;
+
+__global__ __launch_bounds__(64 * kMaxSlices) void channel_mean_abs_kernel(
+    const float *__restrict__ I, long long NP, int C, int HW, int chunk, float *__restrict__ A)
+{
+    __shared__ double part[kMaxSlices][64];
+    const int lane = threadIdx.x, s = threadIdx.y, S = blockDim.y;
+    const long long p = (long long)blockIdx.x * 64 + lane;
+    double acc = 0.0;
+    if (p < NP) {
+        const long long n = p / HW;
+        const int hw = (int)(p - n * HW);
+        const float *src = I + (n * C) * (long long)HW + hw;
+        const int c0 = s * chunk;
+        const int c1 = min(C, c0 + chunk);
+        int c = c0;
+        for (; c + 8 <= c1; c += 8) {
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(src + (long long)(c + j) * HW);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc += (double)fabsf(v[j]);
+        }
+        for (; c < c1; ++c) acc += (double)fabsf(src[(long long)c * HW]);
+    }
+    part[s][lane] = acc;
+    __syncthreads();
+    if (s == 0 && p < NP) {
+        double sum = part[0][lane];
+        for (int k = 1; k < S; ++k) sum += part[k][lane];
+        A[p] = (float)(sum / (double)C);
+    }
+}
+
+hipError_t launch_channel_mean_abs(const float *I, int N, int C, int H, int W, float *A,
+                                   hipStream_t st)
+{
+    const int HW = H * W;
+    const long long NP = (long long)N * HW;
+    int S = 1;
+    while (S < kMaxSlices && C / (2 * S) >= 8) S *= 2;
+    const int chunk = (C + S - 1) / S;
+    channel_mean_abs_kernel<<<dim3(ceil_div(NP, 64)), dim3(64, S), 0, st>>>(I, NP, C, HW, chunk, A);
+    return hipGetLastError();
+}
+
+// Eq. 10, second half: K = A * k with constant taps 1/(kh*kw), at the convolution's output
+// positions; taps outside the image add nothing.  One thread per output pixel (A is C times smaller
+// than I, so this pass is negligible).
+__global__ __launch_bounds__(256) void box_filter_K_kernel(const float *__restrict__ A, Geom g,
+                                                           long long total, float *__restrict__ K)
+{
+    const long long o = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (o >= total) return;
+    const int ox = (int)(o % g.OW);
+    const long long t = o / g.OW;
+    const int oy = (int)(t % g.OH);
+    const long long n = t / g.OH;
+    const float *a = A + n * (long long)g.H * g.W;
+    double sum = 0.0;
+    for (int ky = 0; ky < g.kh; ++ky) {
+        const int iy = oy * g.sh - g.ph + ky;
+        if (iy < 0 || iy >= g.H) continue;
+        for (int kx = 0; kx < g.kw; ++kx) {
+            const int ix = ox * g.sw - g.pw + kx;
+            if (ix < 0 || ix >= g.W) continue;
+            sum += (double)a[iy * g.W + ix];
+        }
+    }
+    K[o] = (float)(sum / (double)(g.kh * g.kw));
+}
+
+hipError_t launch_box_filter_K(const float *A, const Geom &g, float *K, hipStream_t st)
+{
+    const long long total = (long long)g.N * g.OH * g.OW;
+    box_filter_K_kernel<<<ceil_div(total, 256), 256, 0, st>>>(A, g, total, K);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Eq. 5: alpha[f] = ||Wt[f]||_1 / n.  One block per filter, double partial sums, fixed-order tree.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void alpha_kernel(const float *__restrict__ Wt, long long n_red,
+                                                    float *__restrict__ alpha)
+{
+    __shared__ double part[256];
+    const float *w = Wt + (long long)blockIdx.x * n_red;
+    double acc = 0.0;
+    for (long long i = threadIdx.x; i < n_red; i += 256) acc += (double)fabsf(w[i]);
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    for (int step = 128; step > 0; step >>= 1) {
+        if ((int)threadIdx.x < step) part[threadIdx.x] += part[threadIdx.x + step];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) alpha[blockIdx.x] = (float)(part[0] / (double)n_red);
+}
+
+hipError_t launch_alpha(const float *Wt, int F, long long n_red, float *alpha, hipStream_t st)
+{
+    alpha_kernel<<<F, 256, 0, st>>>(Wt, n_red, alpha);
+    return hipGetLastError();
+}
+
+}  // namespace xnor

@@ -1,0 +1,159 @@
+// Host side of the C ABI declared in xnor.h: argument validation, geometry, kernel choice.
+// Nothing here allocates or synchronises; every call enqueues on the caller's stream.
+#include <stdio.h>
+#include <string.h>
+
+#include "xnor_internal.hpp"
+
+namespace {
+
+thread_local char g_hip_err[256] = "";
+
+int hip_status(hipError_t e)
+{
+    if (e == hipSuccess) return XNOR_OK;
+    snprintf(g_hip_err, sizeof g_hip_err, "%s: %s", hipGetErrorName(e), hipGetErrorString(e));
+    return XNOR_E_HIP;
+}
+
+constexpr long long kMaxIndex = 0x7fffffffLL;
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// Validates a layer and fills the derived geometry.
+int make_geom(const xnor_shape *s, xnor::Geom *g)
+{
+    if (!s) return XNOR_E_NULL;
+    if (s->N <= 0 || s->C <= 0 || s->H <= 0 || s->W <= 0 || s->F <= 0 || s->kh <= 0 ||
+        s->kw <= 0 || s->sh <= 0 || s->sw <= 0 || s->ph < 0 || s->pw < 0)
+        return XNOR_E_SHAPE;
+    const long long eh = (long long)s->H + 2LL * s->ph - s->kh;
+    const long long ew = (long long)s->W + 2LL * s->pw - s->kw;
+    if (eh < 0 || ew < 0) return XNOR_E_SHAPE;
+    const long long OH = eh / s->sh + 1, OW = ew / s->sw + 1;
+    const long long Cw = ((long long)s->C + 31) / 32;
+    if ((long long)s->N * s->H * s->W > kMaxIndex || (long long)s->N * OH * OW > kMaxIndex ||
+        (long long)s->H * s->W * Cw > kMaxIndex || (long long)s->F * s->kh * s->kw * Cw > kMaxIndex ||
+        (long long)s->kh * s->kw * s->C > kMaxIndex ||
+        ((long long)s->N * OH * OW) > (kMaxIndex * 256) / s->F ||
+        (long long)s->H + 2LL * s->ph > kMaxIndex || (long long)s->W + 2LL * s->pw > kMaxIndex)
+        return XNOR_E_SHAPE;
+    *g = xnor::Geom{s->N, s->C, s->H, s->W, s->F, s->kh, s->kw, s->sh, s->sw, s->ph, s->pw,
+                    (int)OH, (int)OW, (int)Cw};
+    return XNOR_OK;
+}
+
+int pick_algo(const xnor::Geom &g)
+{
+    if (xnor::conv_mfma_supports(g)) return XNOR_ALGO_MFMA;
+    if (xnor::conv_tiled_supports(g)) return XNOR_ALGO_TILED;
+    return XNOR_ALGO_DIRECT;
+}
+
+}  // namespace
+
+extern "C" {
+
+int xnor_out_dim(const xnor_shape *s, int *OH, int *OW)
+{
+    if (!s || !OH || !OW) return XNOR_E_NULL;
+    xnor::Geom g;
+    const int rc = make_geom(s, &g);
+    if (rc) return rc;
+    *OH = g.OH;
+    *OW = g.OW;
+    return XNOR_OK;
+}
+
+int xnor_packed_words(int C) { return C <= 0 ? XNOR_E_SHAPE : (int)(((long long)C + 31) / 32); }
+
+const char *xnor_strerror(int status)
+{
+    switch (status) {
+        case XNOR_OK: return "ok";
+        case XNOR_E_NULL: return "a required pointer is NULL";
+        case XNOR_E_SHAPE: return "bad shape (non-positive dimension, empty output or tensor too large)";
+        case XNOR_E_ALIGN: return "pointer not aligned as required";
+        case XNOR_E_HIP: return "HIP launch failed (see xnor_last_hip_error)";
+        case XNOR_E_UNSUPPORTED: return "the requested algorithm does not support this shape";
+        default: return "unknown status";
+    }
+}
+
+const char *xnor_last_hip_error(void) { return g_hip_err; }
+
+int xnor_binarize_pack(const float *x, int N, int C, int H, int W, uint32_t *packed, void *stream)
+{
+    if (!x || !packed) return XNOR_E_NULL;
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0) return XNOR_E_SHAPE;
+    const long long Cw = ((long long)C + 31) / 32;
+    if ((long long)N * H * W > kMaxIndex || Cw > 65535 || (long long)H * W > kMaxIndex / Cw)
+        return XNOR_E_SHAPE;
+    if (!aligned(x, 4) || !aligned(packed, 4)) return XNOR_E_ALIGN;
+    return hip_status(xnor::launch_binarize_pack(x, N, C, H, W, packed, (hipStream_t)stream));
+}
+
+int xnor_scale_K(const float *I, const xnor_shape *s, float *A_work, float *K, void *stream)
+{
+    if (!I || !s || !A_work || !K) return XNOR_E_NULL;
+    xnor::Geom g;
+    const int rc = make_geom(s, &g);
+    if (rc) return rc;
+    if (!aligned(I, 4) || !aligned(A_work, 4) || !aligned(K, 4)) return XNOR_E_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = xnor::launch_channel_mean_abs(I, g.N, g.C, g.H, g.W, A_work, st);
+    if (e != hipSuccess) return hip_status(e);
+    return hip_status(xnor::launch_box_filter_K(A_work, g, K, st));
+}
+
+int xnor_alpha(const float *Wt, int F, int C, int kh, int kw, float *alpha, void *stream)
+{
+    if (!Wt || !alpha) return XNOR_E_NULL;
+    if (F <= 0 || C <= 0 || kh <= 0 || kw <= 0) return XNOR_E_SHAPE;
+    const long long n_red = (long long)C * kh * kw;
+    if (n_red > kMaxIndex) return XNOR_E_SHAPE;
+    if (!aligned(Wt, 4) || !aligned(alpha, 4)) return XNOR_E_ALIGN;
+    return hip_status(xnor::launch_alpha(Wt, F, n_red, alpha, (hipStream_t)stream));
+}
+
+int xnor_conv2d_pick_algo(const xnor_shape *s)
+{
+    xnor::Geom g;
+    const int rc = make_geom(s, &g);
+    return rc ? rc : pick_algo(g);
+}
+
+int xnor_conv2d_fwd_algo(const uint32_t *Ipk, const uint32_t *Wpk, const float *K,
+                         const float *alpha, const xnor_shape *s, float *out, int32_t *dot,
+                         int algo, void *stream)
+{
+    if (!Ipk || !Wpk || !K || !alpha || !s || !out) return XNOR_E_NULL;
+    xnor::Geom g;
+    const int rc = make_geom(s, &g);
+    if (rc) return rc;
+    if (!aligned(Ipk, 4) || !aligned(Wpk, 4) || !aligned(K, 4) || !aligned(alpha, 4) ||
+        !aligned(out, 4) || (dot && !aligned(dot, 4)))
+        return XNOR_E_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    if (algo == XNOR_ALGO_AUTO) algo = pick_algo(g);
+    switch (algo) {
+        case XNOR_ALGO_DIRECT:
+            return hip_status(xnor::launch_conv_direct(Ipk, Wpk, K, alpha, g, out, dot, st));
+        case XNOR_ALGO_TILED:
+            if (!xnor::conv_tiled_supports(g)) return XNOR_E_UNSUPPORTED;
+            return hip_status(xnor::launch_conv_tiled(Ipk, Wpk, K, alpha, g, out, dot, st));
+        case XNOR_ALGO_MFMA:
+            if (!xnor::conv_mfma_supports(g)) return XNOR_E_UNSUPPORTED;
+            return hip_status(xnor::launch_conv_mfma(Ipk, Wpk, K, alpha, g, out, dot, st));
+        default:
+            return XNOR_E_UNSUPPORTED;
+    }
+}
+
+int xnor_conv2d_fwd(const uint32_t *Ipk, const uint32_t *Wpk, const float *K, const float *alpha,
+                    const xnor_shape *s, float *out, int32_t *dot, void *stream)
+{
+    return xnor_conv2d_fwd_algo(Ipk, Wpk, K, alpha, s, out, dot, XNOR_ALGO_AUTO, stream);
+}
+
+}  // extern "C"

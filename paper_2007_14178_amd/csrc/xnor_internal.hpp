@@ -1,0 +1,41 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "xnor.h"
+
+namespace xnor {
+
+// Derived geometry, computed once on the host after validation.
+struct Geom {
+    int N, C, H, W, F, kh, kw, sh, sw, ph, pw;
+    int OH, OW, Cw;
+};
+
+inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
+
+// Launchers: enqueue on `st`, return the launch status.  Arguments are already validated.
+hipError_t launch_binarize_pack(const float *x, int N, int C, int H, int W, uint32_t *packed,
+                                hipStream_t st);
+hipError_t launch_channel_mean_abs(const float *I, int N, int C, int H, int W, float *A,
+                                   hipStream_t st);
+hipError_t launch_box_filter_K(const float *A, const Geom &g, float *K, hipStream_t st);
+hipError_t launch_alpha(const float *Wt, int F, long long n_red, float *alpha, hipStream_t st);
+
+hipError_t launch_conv_direct(const uint32_t *Ipk, const uint32_t *Wpk, const float *K,
+                              const float *alpha, const Geom &g, float *out, int32_t *dot,
+                              hipStream_t st);
+
+bool conv_tiled_supports(const Geom &g);
+hipError_t launch_conv_tiled(const uint32_t *Ipk, const uint32_t *Wpk, const float *K,
+                             const float *alpha, const Geom &g, float *out, int32_t *dot,
+                             hipStream_t st);
+
+bool conv_mfma_supports(const Geom &g);
+hipError_t launch_conv_mfma(const uint32_t *Ipk, const uint32_t *Wpk, const float *K,
+                            const float *alpha, const Geom &g, float *out, int32_t *dot,
+                            hipStream_t st);
+
+}  // namespace xnor

@@ -1,0 +1,113 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and turns bad arguments into status codes before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def xb():
+    from paper_2007_14178_amd import binding
+    return binding
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "xnor.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(xnor_[A-Za-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_exported(xb):
+    names = declared_symbols()
+    assert {"xnor_binarize_pack", "xnor_scale_K", "xnor_alpha", "xnor_conv2d_fwd"} <= set(names)
+    raw = ctypes.CDLL(xb.LIB_PATH)
+    for n in names:
+        assert hasattr(raw, n), f"{n} declared in xnor.h but not exported"
+
+
+def test_out_dim_and_words(xb):
+    assert xb.xnor_out_dim(xb.Shape(1, 64, 32, 32, 64, 3, 3, 1, 1, 1, 1)) == (32, 32)
+    assert xb.xnor_out_dim(xb.Shape(1, 128, 28, 28, 256, 3, 3, 2, 2, 1, 1)) == (14, 14)
+    assert xb.xnor_out_dim(xb.Shape(1, 8, 7, 9, 2, 3, 5, 2, 3, 0, 1)) == (3, 3)
+    assert [xb.xnor_packed_words(c) for c in (1, 31, 32, 33, 64, 65, 512)] == [1, 1, 1, 2, 2, 3, 16]
+    with pytest.raises(xb.XnorError):
+        xb.xnor_packed_words(0)
+
+
+def test_strerror_covers_every_status(xb):
+    seen = {xb.lib.xnor_strerror(s) for s in range(0, -6, -1)}
+    assert len(seen) == 6 and all(seen)
+    assert xb.lib.xnor_strerror(-99)
+
+
+BAD_SHAPES = [
+    dict(N=0), dict(C=0), dict(H=-1), dict(W=0), dict(F=0), dict(kh=0), dict(kw=-3), dict(sh=0), dict(sw=-1),
+    dict(ph=-1), dict(pw=-1), dict(kh=40, ph=1), dict(kw=40, pw=0),
+    dict(N=70000, H=300, W=300),                 # N*H*W past 31 bits
+]
+
+
+@pytest.mark.parametrize("bad", BAD_SHAPES, ids=str)
+def test_bad_shapes_rejected(xb, bad):
+    base = dict(N=2, C=64, H=32, W=32, F=8, kh=3, kw=3, sh=1, sw=1, ph=1, pw=1)
+    base.update(bad)
+    s = xb.Shape(**base)
+    oh, ow = ctypes.c_int(), ctypes.c_int()
+    assert xb.lib.xnor_out_dim(ctypes.byref(s.c()), ctypes.byref(oh), ctypes.byref(ow)) == xb.E_SHAPE
+    fake = ctypes.c_void_p(0x1000)
+    assert xb.lib.xnor_scale_K(fake, ctypes.byref(s.c()), fake, fake, None) == xb.E_SHAPE
+    assert xb.lib.xnor_conv2d_fwd(fake, fake, fake, fake, ctypes.byref(s.c()), fake, None, None) == xb.E_SHAPE
+    assert xb.lib.xnor_conv2d_pick_algo(ctypes.byref(s.c())) == xb.E_SHAPE
+
+
+def test_null_and_alignment_rejected(xb):
+    s = xb.Shape(1, 64, 8, 8, 4, 3, 3, 1, 1, 1, 1)
+    sp = ctypes.byref(s.c())
+    ok, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1002)
+    L = xb.lib
+    assert L.xnor_binarize_pack(None, 1, 64, 8, 8, ok, None) == xb.E_NULL
+    assert L.xnor_binarize_pack(ok, 1, 64, 8, 8, None, None) == xb.E_NULL
+    assert L.xnor_binarize_pack(ok, 1, 0, 8, 8, ok, None) == xb.E_SHAPE
+    assert L.xnor_binarize_pack(odd, 1, 64, 8, 8, ok, None) == xb.E_ALIGN
+    assert L.xnor_binarize_pack(ok, 1, 64, 8, 8, odd, None) == xb.E_ALIGN
+    assert L.xnor_scale_K(None, sp, ok, ok, None) == xb.E_NULL
+    assert L.xnor_scale_K(ok, None, ok, ok, None) == xb.E_NULL
+    assert L.xnor_scale_K(ok, sp, None, ok, None) == xb.E_NULL
+    assert L.xnor_scale_K(ok, sp, ok, odd, None) == xb.E_ALIGN
+    assert L.xnor_alpha(None, 4, 64, 3, 3, ok, None) == xb.E_NULL
+    assert L.xnor_alpha(ok, 4, 64, 3, 0, ok, None) == xb.E_SHAPE
+    assert L.xnor_alpha(ok, 4, 64, 3, 3, odd, None) == xb.E_ALIGN
+    for k in range(6):
+        args = [ok, ok, ok, ok, sp, ok]
+        args[k] = None
+        assert L.xnor_conv2d_fwd(*args, None, None) == xb.E_NULL
+    assert L.xnor_conv2d_fwd(odd, ok, ok, ok, sp, ok, None, None) == xb.E_ALIGN
+    assert L.xnor_conv2d_fwd(ok, ok, ok, ok, sp, ok, odd, None) == xb.E_ALIGN
+    assert L.xnor_conv2d_fwd_algo(ok, ok, ok, ok, sp, ok, None, 99, None) == xb.E_UNSUPPORTED
+
+
+def test_binding_refuses_cpu_tensors(xb):
+    import torch
+    with pytest.raises(TypeError):
+        xb.xnor_binarize_pack(torch.zeros(1, 32, 2, 2))
+    with pytest.raises(TypeError):
+        xb.xnor_alpha(torch.zeros(2, 32, 3, 3))
+
+
+def test_workloads_are_seeded_and_shaped():
+    import numpy as np
+    from paper_2007_14178_amd.workloads import LAYERS, make_input, make_weights
+    L = LAYERS["c5"]
+    assert (L.OH, L.OW, L.n_red, L.binary_macs) == (28, 28, 4608, 128 * 512 * 784 * 4608)
+    a, b = make_input(L, 2), make_input(L, 1)
+    assert a.shape == (2, 512, 28, 28) and a.dtype == np.float32 and np.array_equal(a[:1], b)
+    assert 0.04 < (a == 0).mean() < 0.06
+    w = make_weights(LAYERS["c3_s1"])
+    assert w.shape == (256, 256, 3, 3) and abs(w.std() - 0.05) < 0.002
+    u = make_input(LAYERS["c4_conv3"], 1)
+    assert u.min() >= -1 and u.max() <= 1 and abs(u.mean()) < 0.01
+    assert LAYERS["c3_s2"].OH == 14 and LAYERS["c4_conv2"].OH == 27 and LAYERS["c2_k7"].n_red == 6272

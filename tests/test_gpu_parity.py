@@ -1,0 +1,222 @@
+"""GPU parity: every C-ABI call against the CPU oracle, element by element, same seeded inputs.
+
+Bars: packed words and raw binary dot products bit-exact; A, K, alpha and the fp32 output within
+1e-5 relative of the oracle (and exactly 0 where the oracle is 0).
+"""
+import zlib
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2007_14178_amd.workloads import LAYERS, make_input, make_weights, random_layer
+
+pytestmark = pytest.mark.gpu
+
+RTOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def xb():
+    from paper_2007_14178_amd import binding
+    return binding
+
+
+def assert_rel(got: np.ndarray, ref: np.ndarray, what: str):
+    got = got.astype(np.float64); ref = ref.astype(np.float64)
+    assert got.shape == ref.shape, what
+    err = np.abs(got - ref)
+    bad = err > RTOL * np.abs(ref)
+    assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} outside {RTOL} rel; worst {err.max()}"
+    assert np.array_equal(got == 0, ref == 0), f"{what}: zero pattern differs"
+
+
+def dev(a: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def words(t: torch.Tensor) -> np.ndarray:
+    return t.cpu().numpy().view(np.uint32)
+
+
+def run_pipeline(xb, layer, I, Wt, algo, want_dot=True):
+    s = xb.Shape(layer.N, layer.C, layer.H, layer.W, layer.F, layer.kh, layer.kw,
+                 layer.sh, layer.sw, layer.ph, layer.pw)
+    dI, dW = dev(I), dev(Wt)
+    Ipk = xb.xnor_binarize_pack(dI)
+    Wpk = xb.xnor_binarize_pack(dW)
+    K, A = xb.xnor_scale_K(dI, s)
+    alpha = xb.xnor_alpha(dW)
+    out, dot = xb.xnor_conv2d_fwd(Ipk, Wpk, K, alpha, s, want_dot=want_dot, algo=algo)
+    torch.cuda.synchronize()
+    return s, Ipk, Wpk, K, A, alpha, out, dot
+
+
+def oshape(layer):
+    return oracle.Shape(layer.N, layer.C, layer.H, layer.W, layer.F, layer.kh, layer.kw,
+                        layer.sh, layer.sw, layer.ph, layer.pw)
+
+
+_ORACLE_CACHE: dict = {}
+
+
+def oracle_results(key, layer, I, Wt):
+    """The oracle's outputs for one case, computed once and reused across the kernel variants."""
+    if key not in _ORACLE_CACHE:
+        if len(_ORACLE_CACHE) > 4:
+            _ORACLE_CACHE.clear()
+        _ORACLE_CACHE[key] = (oracle.pack(I), oracle.pack(Wt), oracle.channel_mean_abs(I),
+                              *oracle.forward(I, Wt, oshape(layer)))
+    return _ORACLE_CACHE[key]
+
+
+def check_all(xb, layer, I, Wt, algo, key):
+    s, Ipk, Wpk, K, A, alpha, out, dot = run_pipeline(xb, layer, I, Wt, algo)
+    Ipk_ref, Wpk_ref, A_ref, d_ref, K_ref, a_ref, O_ref = oracle_results(key, layer, I, Wt)
+    assert np.array_equal(words(Ipk), Ipk_ref), "Ipk"
+    assert np.array_equal(words(Wpk), Wpk_ref), "Wpk"
+    assert_rel(A.cpu().numpy(), A_ref, "A")
+    assert_rel(K.cpu().numpy(), K_ref, "K")
+    assert_rel(alpha.cpu().numpy(), a_ref, "alpha")
+    assert np.array_equal(dot.cpu().numpy(), d_ref), "dot"
+    assert_rel(out.cpu().numpy(), O_ref, "out")
+
+
+ALGOS = ["direct", "tiled", "mfma", "auto"]   # innermost parameter, so one oracle run serves all four
+
+
+def algo_id(xb, name):
+    return {"auto": xb.ALGO_AUTO, "direct": xb.ALGO_DIRECT, "tiled": xb.ALGO_TILED, "mfma": xb.ALGO_MFMA}[name]
+
+
+def run_or_skip(xb, layer, I, Wt, algo, key):
+    try:
+        check_all(xb, layer, I, Wt, algo_id(xb, algo), key)
+    except xb.XnorError as e:
+        if e.status == xb.E_UNSUPPORTED and algo in ("tiled", "mfma"):
+            pytest.skip(f"{algo} does not take this shape")
+        raise
+
+
+# adversarial shapes: channel tails, even / non-square kernels, strides, oversized padding, odd batch,
+# sizes that are not multiples of any tile, F not a multiple of the filter tile
+#        N   C   H   W   F  kh kw sh sw ph pw
+SHAPES = [
+    (1, 1, 5, 5, 1, 1, 1, 1, 1, 0, 0),
+    (1, 3, 9, 11, 2, 3, 3, 1, 1, 1, 1),
+    (3, 31, 8, 7, 5, 3, 3, 1, 1, 1, 1),
+    (2, 32, 13, 13, 33, 3, 3, 1, 1, 1, 1),
+    (1, 33, 10, 12, 7, 2, 2, 1, 1, 0, 0),
+    (2, 63, 17, 9, 17, 5, 5, 1, 1, 2, 2),
+    (1, 64, 32, 32, 64, 3, 3, 1, 1, 1, 1),
+    (3, 65, 12, 20, 9, 3, 5, 2, 1, 1, 2),
+    (1, 96, 27, 27, 40, 5, 5, 1, 1, 2, 2),
+    (2, 128, 28, 28, 48, 3, 3, 2, 2, 1, 1),
+    (1, 70, 15, 14, 6, 7, 7, 3, 3, 3, 3),
+    (2, 40, 9, 9, 4, 3, 3, 1, 1, 3, 2),        # padding larger than k//2: some windows all padding
+    (5, 256, 14, 14, 70, 3, 3, 1, 1, 1, 1),
+    (1, 512, 28, 28, 96, 3, 3, 1, 1, 1, 1),
+    (2, 128, 56, 56, 32, 7, 7, 1, 1, 3, 3),
+    (1, 160, 6, 40, 130, 1, 3, 1, 2, 0, 1),
+]
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_shapes_vs_oracle(xb, shape, algo):
+    rng = np.random.default_rng(zlib.crc32(str(shape).encode()))
+    layer, I, Wt = random_layer(rng, "t", *shape)
+    print(f"case shape={shape} algo={algo}", flush=True)
+    run_or_skip(xb, layer, I, Wt, algo, shape)
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+@pytest.mark.parametrize("name", ["c1", "c2_k3", "c2_k5", "c2_k7", "c3_s1", "c3_s2",
+                                  "c4_conv2", "c4_conv3", "c4_conv4", "c4_conv5", "c5"])
+def test_benchmark_layers_reduced_batch(xb, name, algo):
+    """Each benchmark layer at its real C, H, W, F, kernel, stride and pad, on its first images
+    (batch cut so that the oracle finishes in seconds)."""
+    full = LAYERS[name]
+    n = 1 if full.binary_macs // full.N > 1.5e9 else min(full.N, 2)
+    layer = full.with_batch(n)
+    I, Wt = make_input(full, n), make_weights(full)
+    print(f"case layer={name} N={n} algo={algo}", flush=True)
+    run_or_skip(xb, layer, I, Wt, algo, name)
+
+
+def test_special_values(xb):
+    """+0.0, -0.0, denormals, infinities -> sign by (x >= 0); NaN -> -1."""
+    vals = np.array([0.0, -0.0, 1e-45, -1e-45, 1e-39, -1e-39, np.inf, -np.inf, np.nan, -np.nan, 2.0, -2.0],
+                    dtype=np.float32)
+    x = np.tile(vals, 96 * 3)[: 96 * 3 * 4].reshape(1, 96, 3, 4).copy()
+    got = words(xb.xnor_binarize_pack(dev(x)))
+    assert np.array_equal(got, oracle.pack(x))
+
+
+def test_determinism(xb):
+    layer = LAYERS["c3_s1"].with_batch(4)
+    I, Wt = make_input(LAYERS["c3_s1"], 4), make_weights(LAYERS["c3_s1"])
+    for algo in ("direct", "tiled", "mfma"):
+        try:
+            r1 = run_pipeline(xb, layer, I, Wt, algo_id(xb, algo))
+            r2 = run_pipeline(xb, layer, I, Wt, algo_id(xb, algo))
+        except xb.XnorError as e:
+            if e.status == xb.E_UNSUPPORTED:
+                continue
+            raise
+        for a, b in zip(r1[1:], r2[1:]):
+            assert torch.equal(a.view(torch.int32), b.view(torch.int32))
+
+
+def test_outputs_do_not_spill(xb):
+    """Canary words around every output buffer stay untouched."""
+    shape = (2, 70, 11, 13, 37, 3, 3, 1, 1, 1, 1)
+    rng = np.random.default_rng(7)
+    layer, I, Wt = random_layer(rng, "canary", *shape)
+    s = xb.Shape(*shape)
+    OH, OW = xb.xnor_out_dim(s)
+    dI, dW = dev(I), dev(Wt)
+    G = 64
+
+    def guarded(n, dtype):
+        buf = torch.full((n + 2 * G,), -7777, dtype=dtype, device="cuda")
+        return buf, buf[G:G + n]
+
+    for algo in ("direct", "tiled", "mfma"):
+        bI, vI = guarded(s.N * s.H * s.W * s.Cw, torch.int32)
+        bW, vW = guarded(s.F * s.kh * s.kw * s.Cw, torch.int32)
+        bA, vA = guarded(s.N * s.H * s.W, torch.float32)
+        bK, vK = guarded(s.N * OH * OW, torch.float32)
+        ba, va = guarded(s.F, torch.float32)
+        bo, vo = guarded(s.N * s.F * OH * OW, torch.float32)
+        bd, vd = guarded(s.N * s.F * OH * OW, torch.int32)
+        Ipk = xb.xnor_binarize_pack(dI, vI.view(s.N, s.H, s.W, s.Cw))
+        Wpk = xb.xnor_binarize_pack(dW, vW.view(s.F, s.kh, s.kw, s.Cw))
+        K, _ = xb.xnor_scale_K(dI, s, vA.view(s.N, s.H, s.W), vK.view(s.N, OH, OW))
+        al = xb.xnor_alpha(dW, va)
+        try:
+            xb.xnor_conv2d_fwd(Ipk, Wpk, K, al, s, vo.view(s.N, s.F, OH, OW), vd.view(s.N, s.F, OH, OW),
+                               algo=algo_id(xb, algo))
+        except xb.XnorError as e:
+            if e.status == xb.E_UNSUPPORTED:
+                continue
+            raise
+        torch.cuda.synchronize()
+        for b in (bI, bW, bA, bK, ba, bo, bd):
+            assert (b[:G] == -7777).all() and (b[-G:] == -7777).all()
+        assert np.array_equal(vd.cpu().numpy().reshape(s.N, s.F, OH, OW), oracle.dot(I, Wt, oshape(layer)))
+
+
+def test_dot_null_gives_same_out(xb):
+    layer = LAYERS["c1"]
+    I, Wt = make_input(layer), make_weights(layer)
+    for algo in ("direct", "tiled", "mfma"):
+        try:
+            a = run_pipeline(xb, layer, I, Wt, algo_id(xb, algo), want_dot=True)
+            b = run_pipeline(xb, layer, I, Wt, algo_id(xb, algo), want_dot=False)
+        except xb.XnorError as e:
+            if e.status == xb.E_UNSUPPORTED:
+                continue
+            raise
+        assert b[-1] is None and torch.equal(a[-2], b[-2])
