@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Benchmark of the XNOR-Net binary convolution forward pass on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of seeded synthetic input that already
+lives in HBM: binarise+pack the input, scaling map K, per-filter alpha, binarise+pack the filters,
+XNOR convolution with the K*alpha epilogue.  Prints ONE JSON line: whole-step throughput in binary
+GMAC/s, the convolution kernel's roofline figures (timed live with events on the launch stream)
+and the CPU oracle timed on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--layer c5] [--algo auto]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X published peaks used as roofline denominators.
+PEAK_FP4_MFMA_TFLOPS = 10100.0      # dense FP4 MFMA, 2 flops per multiply-accumulate
+PEAK_HBM_GBS = 8000.0
+# v_xor_b32 + v_bcnt_u32_b32 retire 32 binary MACs per lane: 256 CU x 4 SIMD x 16 lanes x 2.4 GHz
+# = 3.93e13 lane-ops/s -> 6.29e14 binary MAC/s -> 1258 T binary op/s counting 2 ops per MAC.
+PEAK_VALU_POPCOUNT_TOPS = 256 * 4 * 16 * 2.4e9 / 2 * 32 * 2 / 1e12
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--layer", default="c5", help="workload name (see paper_2007_14178_amd/workloads.py)")
+    ap.add_argument("--algo", default="auto", choices=["auto", "direct", "tiled", "mfma"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
+    return ap.parse_args()
+
+
+def cpu_baseline(layer, Wt, target_s: float):
+    """The oracle as it stands, on the host cores, on the first images of the same workload."""
+    import oracle
+    from paper_2007_14178_amd.workloads import make_input
+
+    def run(n):
+        I = make_input(layer, n)
+        s = oracle.Shape(n, layer.C, layer.H, layer.W, layer.F, layer.kh, layer.kw,
+                         layer.sh, layer.sw, layer.ph, layer.pw)
+        t0 = time.perf_counter()
+        oracle.forward(I, Wt, s)
+        return time.perf_counter() - t0
+
+    t1 = run(1)
+    n = max(1, min(layer.N, int(target_s / max(t1, 1e-3))))
+    t = run(n) if n > 1 else t1
+    macs = layer.binary_macs // layer.N * n
+    return {"value": macs / t / 1e9, "unit": "binary GMAC/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"first {n} of {layer.N} images of {layer.name}, all {layer.F} filters, whole forward "
+                      f"pass (sign conv + K + alpha + rescale), {t:.2f} s"}
+
+
+def main():
+    args = parse()
+    world = int(os.environ.get("WORLD_SIZE", "1"))
+    if args.gpus != 1 or world != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2007_14178_amd import binding as xb
+    from paper_2007_14178_amd.workloads import LAYERS, make_input, make_weights
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    layer = LAYERS[args.layer]
+    algo = {"auto": xb.ALGO_AUTO, "direct": xb.ALGO_DIRECT, "tiled": xb.ALGO_TILED, "mfma": xb.ALGO_MFMA}[args.algo]
+    s = xb.Shape(layer.N, layer.C, layer.H, layer.W, layer.F, layer.kh, layer.kw,
+                 layer.sh, layer.sw, layer.ph, layer.pw)
+    OH, OW = xb.xnor_out_dim(s)
+    used_algo = xb.xnor_conv2d_pick_algo(s) if algo == xb.ALGO_AUTO else algo
+
+    Wt_host = make_weights(layer)
+    dI = torch.from_numpy(make_input(layer)).cuda()
+    dW = torch.from_numpy(Wt_host).cuda()
+    Ipk = torch.empty((s.N, s.H, s.W, s.Cw), dtype=torch.int32, device="cuda")
+    Wpk = torch.empty((s.F, s.kh, s.kw, s.Cw), dtype=torch.int32, device="cuda")
+    A = torch.empty((s.N, s.H, s.W), dtype=torch.float32, device="cuda")
+    K = torch.empty((s.N, OH, OW), dtype=torch.float32, device="cuda")
+    alpha = torch.empty((s.F,), dtype=torch.float32, device="cuda")
+    out = torch.empty((s.N, s.F, OH, OW), dtype=torch.float32, device="cuda")
+
+    names = ["pack_I", "scale_K", "alpha", "pack_W", "conv"]
+
+    def step(events=None):
+        marks = []
+
+        def mark():
+            if events is not None:
+                e = torch.cuda.Event(enable_timing=True)
+                e.record()                      # recorded on the stream the kernels are launched on
+                marks.append(e)
+
+        mark(); xb.xnor_binarize_pack(dI, Ipk)
+        mark(); xb.xnor_scale_K(dI, s, A, K)
+        mark(); xb.xnor_alpha(dW, alpha)
+        mark(); xb.xnor_binarize_pack(dW, Wpk)
+        mark(); xb.xnor_conv2d_fwd(Ipk, Wpk, K, alpha, s, out=out, algo=algo)
+        mark()
+        if events is not None:
+            events.append(marks)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events: list = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    ms_per_step = elapsed / args.steps * 1e3
+    stage_ms = {n: sum(m[i].elapsed_time(m[i + 1]) for m in events) / len(events) for i, n in enumerate(names)}
+    conv_ms = stage_ms["conv"]
+    macs = layer.binary_macs
+    value = macs / (ms_per_step * 1e-3) / 1e9
+
+    ops = 2.0 * macs                                           # algorithmic ops of one conv launch
+    achieved = ops / (conv_ms * 1e-3) / 1e12
+    if used_algo == xb.ALGO_MFMA:
+        roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP4_MFMA_TFLOPS, "unit": "TFLOP/s"}
+    else:
+        roof = {"bound": "alu", "achieved": achieved, "peak": PEAK_VALU_POPCOUNT_TOPS, "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel"] = f"xnor_conv2d_fwd[{xb.ALGO_NAMES[used_algo]}]"
+    roof["kernel_ms"] = conv_ms
+    roof["binary_gmacs"] = macs / (conv_ms * 1e-3) / 1e9
+    roof["frac_of_valu_popcount_peak"] = achieved / PEAK_VALU_POPCOUNT_TOPS
+    # the same launch against the HBM roof: packed operands in, fp32 out
+    conv_bytes = 4.0 * (Ipk.numel() + Wpk.numel() + K.numel() + alpha.numel() + out.numel())
+    roof["hbm_gbs"] = conv_bytes / (conv_ms * 1e-3) / 1e9
+    roof["hbm_frac"] = roof["hbm_gbs"] / PEAK_HBM_GBS
+
+    rec = {
+        "metric": "binary GMAC/s, whole forward pass (pack + K + alpha + XNOR conv + rescale)",
+        "value": value, "unit": "binary GMAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32 bit-packed +-1 (FP4 in the MFMA kernel), int32 dot, fp32 scale",
+        "data": "synthetic (seeded; shapes and value distributions of the benchmark layer)",
+        "config": {"workload": f"{layer.name}: N={layer.N} C={layer.C} {layer.H}x{layer.W} F={layer.F} "
+                               f"{layer.kh}x{layer.kw} stride {layer.sh} pad {layer.ph}",
+                   "binary_macs": macs, "conv_algo": xb.ALGO_NAMES[used_algo],
+                   "buffers": "reused every step (input 205 MB + output 205 MB at c5 fit the 256 MB "
+                              "last-level cache only in part)"},
+        "stage_ms": stage_ms,
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        del dI, out
+        rec["cpu_baseline"] = cpu_baseline(layer, Wt_host, args.cpu_seconds)
+    print(json.dumps(rec), flush=True)
+
+
+if __name__ == "__main__":
+    main()

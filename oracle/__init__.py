@@ -67,6 +67,8 @@ def _load():
         up = ctypes.POINTER(ctypes.c_uint32)
         sp = ctypes.POINTER(_Shape)
         ci = ctypes.c_int
+        lib.oracle_threads.argtypes = []
+        lib.oracle_threads.restype = ci
         lib.oracle_out_dims.argtypes = [sp, ctypes.POINTER(ci), ctypes.POINTER(ci)]
         lib.oracle_out_dims.restype = ci
         lib.oracle_sign.argtypes = [fp, ctypes.c_size_t, fp]
@@ -94,6 +96,11 @@ def _f32(a) -> np.ndarray:
 
 def _ptr(a: np.ndarray, ct):
     return a.ctypes.data_as(ctypes.POINTER(ct))
+
+
+def threads() -> int:
+    """OpenMP threads the (image, filter) loop of ``dot`` runs on."""
+    return _load().oracle_threads()
 
 
 def out_dims(s: Shape) -> tuple[int, int]:

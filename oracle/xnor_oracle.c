@@ -39,12 +39,25 @@
  */
 #include <stdint.h>
 #include <stddef.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 typedef struct {
     int N, C, H, W;      /* input   I  [N][C][H][W]       */
     int F, kh, kw;       /* filters Wt [F][C][kh][kw]     */
     int sh, sw, ph, pw;  /* stride, zero padding          */
 } oracle_shape;
+
+/* Threads the (image, filter) loop of oracle_dot will use. */
+int oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 static int out_dim(int in, int pad, int k, int stride) { return (in + 2 * pad - k) / stride + 1; }
 
