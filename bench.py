@@ -84,7 +84,8 @@ def main():
     s = xb.Shape(layer.N, layer.C, layer.H, layer.W, layer.F, layer.kh, layer.kw,
                  layer.sh, layer.sw, layer.ph, layer.pw)
     OH, OW = xb.xnor_out_dim(s)
-    used_algo = xb.xnor_conv2d_pick_algo(s) if algo == xb.ALGO_AUTO else algo
+    ws_bytes = xb.xnor_conv2d_workspace_bytes(s)
+    used_algo = xb.xnor_conv2d_pick_algo(s, ws_bytes) if algo == xb.ALGO_AUTO else algo
 
     Wt_host = make_weights(layer)
     dI = torch.from_numpy(make_input(layer)).cuda()
@@ -95,6 +96,7 @@ def main():
     K = torch.empty((s.N, OH, OW), dtype=torch.float32, device="cuda")
     alpha = torch.empty((s.F,), dtype=torch.float32, device="cuda")
     out = torch.empty((s.N, s.F, OH, OW), dtype=torch.float32, device="cuda")
+    ws = torch.empty((ws_bytes,), dtype=torch.uint8, device="cuda") if ws_bytes else None
 
     names = ["pack_I", "scale_K", "alpha", "pack_W", "conv"]
 
@@ -111,7 +113,7 @@ def main():
         mark(); xb.xnor_scale_K(dI, s, A, K)
         mark(); xb.xnor_alpha(dW, alpha)
         mark(); xb.xnor_binarize_pack(dW, Wpk)
-        mark(); xb.xnor_conv2d_fwd(Ipk, Wpk, K, alpha, s, out=out, algo=algo)
+        mark(); xb.xnor_conv2d_fwd(Ipk, Wpk, K, alpha, s, out=out, algo=algo, workspace=ws)
         mark()
         if events is not None:
             events.append(marks)

@@ -48,7 +48,8 @@ typedef enum {
                                 too large for the kernels' 31-bit pixel / 63-bit byte indexing     */
     XNOR_E_ALIGN = -3,       /* a pointer is not aligned as the call requires                     */
     XNOR_E_HIP = -4,         /* the HIP runtime refused a launch                                  */
-    XNOR_E_UNSUPPORTED = -5  /* the requested algorithm cannot run this shape                     */
+    XNOR_E_UNSUPPORTED = -5, /* the requested algorithm cannot run this shape                     */
+    XNOR_E_WORKSPACE = -6    /* the requested algorithm needs a (larger) workspace                */
 } xnor_status;
 
 /* Geometry of one layer (Sec. II problem statement; stride/padding as in Sec. III-B step 1). */
@@ -113,19 +114,30 @@ int xnor_alpha(const float *Wt, int F, int C, int kh, int kw, float *alpha, void
  *   alpha  in   fp32   [F]
  *   out    out  fp32   [N][F][OH][OW]
  *   dot    out  int32  [N][F][OH][OW], or NULL when the raw binary dot products are not wanted
+ *   workspace        caller-owned device scratch of `workspace_bytes` bytes, 16-byte aligned, or
+ *                    NULL.  The matrix-core kernel expands the filter bits into it on every call
+ *                    (its contents mean nothing afterwards).  With NULL, or fewer bytes than
+ *                    xnor_conv2d_workspace_bytes reports, the call runs a kernel that needs none.
  * Packed pointers must be 4-byte aligned (16-byte alignment lets the kernels use wider loads).
  */
 int xnor_conv2d_fwd(const uint32_t *Ipk, const uint32_t *Wpk, const float *K, const float *alpha,
-                    const xnor_shape *s, float *out, int32_t *dot, void *stream);
+                    const xnor_shape *s, float *out, int32_t *dot, void *workspace,
+                    size_t workspace_bytes, void *stream);
 
-/* Same, with the kernel chosen by the caller (tests and measurements run every variant).
- * Returns XNOR_E_UNSUPPORTED if `algo` cannot run this shape; XNOR_ALGO_DIRECT runs every shape. */
+/* Bytes of workspace with which xnor_conv2d_fwd can run its fastest kernel on this shape
+ * (0 if no kernel for this shape uses a workspace).  Host only. */
+int xnor_conv2d_workspace_bytes(const xnor_shape *s, size_t *bytes);
+
+/* Same as xnor_conv2d_fwd, with the kernel chosen by the caller (tests and measurements run every
+ * variant).  Returns XNOR_E_UNSUPPORTED if `algo` cannot run this shape, XNOR_E_WORKSPACE if it
+ * needs more workspace than given; XNOR_ALGO_DIRECT runs every shape without workspace. */
 int xnor_conv2d_fwd_algo(const uint32_t *Ipk, const uint32_t *Wpk, const float *K,
                          const float *alpha, const xnor_shape *s, float *out, int32_t *dot,
-                         int algo, void *stream);
+                         void *workspace, size_t workspace_bytes, int algo, void *stream);
 
-/* The algorithm XNOR_ALGO_AUTO resolves to for this shape (an xnor_algo), or a negative status. */
-int xnor_conv2d_pick_algo(const xnor_shape *s);
+/* The algorithm XNOR_ALGO_AUTO resolves to for this shape when given `workspace_bytes` of
+ * workspace (an xnor_algo), or a negative status. */
+int xnor_conv2d_pick_algo(const xnor_shape *s, size_t workspace_bytes);
 
 #ifdef __cplusplus
 }

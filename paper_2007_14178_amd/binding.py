@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libxnor_hip.so")
 
 ALGO_AUTO, ALGO_DIRECT, ALGO_TILED, ALGO_MFMA = 0, 1, 2, 3
 ALGO_NAMES = {ALGO_AUTO: "auto", ALGO_DIRECT: "direct", ALGO_TILED: "tiled", ALGO_MFMA: "mfma"}
-E_NULL, E_SHAPE, E_ALIGN, E_HIP, E_UNSUPPORTED = -1, -2, -3, -4, -5
+E_NULL, E_SHAPE, E_ALIGN, E_HIP, E_UNSUPPORTED, E_WORKSPACE = -1, -2, -3, -4, -5, -6
 
 
 class XnorError(RuntimeError):
@@ -75,11 +75,14 @@ def _load() -> ctypes.CDLL:
     L.xnor_binarize_pack.argtypes = [vp, ci, ci, ci, ci, vp, vp]
     L.xnor_scale_K.argtypes = [vp, sp, vp, vp, vp]
     L.xnor_alpha.argtypes = [vp, ci, ci, ci, ci, vp, vp]
-    L.xnor_conv2d_fwd.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp]
-    L.xnor_conv2d_fwd_algo.argtypes = [vp, vp, vp, vp, sp, vp, vp, ci, vp]
-    L.xnor_conv2d_pick_algo.argtypes = [sp]
+    sz = ctypes.c_size_t
+    L.xnor_conv2d_fwd.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, vp]
+    L.xnor_conv2d_fwd_algo.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, ci, vp]
+    L.xnor_conv2d_pick_algo.argtypes = [sp, sz]
+    L.xnor_conv2d_workspace_bytes.argtypes = [sp, ctypes.POINTER(sz)]
     for name in ("xnor_out_dim", "xnor_packed_words", "xnor_binarize_pack", "xnor_scale_K",
-                 "xnor_alpha", "xnor_conv2d_fwd", "xnor_conv2d_fwd_algo", "xnor_conv2d_pick_algo"):
+                 "xnor_alpha", "xnor_conv2d_fwd", "xnor_conv2d_fwd_algo", "xnor_conv2d_pick_algo",
+                 "xnor_conv2d_workspace_bytes"):
         getattr(L, name).restype = ci
     return L
 
@@ -151,8 +154,14 @@ def xnor_alpha(Wt: torch.Tensor, alpha: torch.Tensor | None = None) -> torch.Ten
     return alpha
 
 
-def xnor_conv2d_pick_algo(s: Shape) -> int:
-    r = lib.xnor_conv2d_pick_algo(ctypes.byref(s.c()))
+def xnor_conv2d_workspace_bytes(s: Shape) -> int:
+    n = ctypes.c_size_t()
+    _ok(lib.xnor_conv2d_workspace_bytes(ctypes.byref(s.c()), ctypes.byref(n)), "xnor_conv2d_workspace_bytes")
+    return n.value
+
+
+def xnor_conv2d_pick_algo(s: Shape, workspace_bytes: int = 0) -> int:
+    r = lib.xnor_conv2d_pick_algo(ctypes.byref(s.c()), workspace_bytes)
     if r < 0:
         raise XnorError(r, "xnor_conv2d_pick_algo")
     return r
@@ -160,19 +169,28 @@ def xnor_conv2d_pick_algo(s: Shape) -> int:
 
 def xnor_conv2d_fwd(Ipk: torch.Tensor, Wpk: torch.Tensor, K: torch.Tensor, alpha: torch.Tensor,
                     s: Shape, out: torch.Tensor | None = None, dot: torch.Tensor | None = None,
-                    want_dot: bool = False, algo: int = ALGO_AUTO):
-    """Returns (out fp32 [N][F][OH][OW], dot int32 or None)."""
+                    want_dot: bool = False, algo: int = ALGO_AUTO,
+                    workspace: torch.Tensor | None | str = "auto"):
+    """Returns (out fp32 [N][F][OH][OW], dot int32 or None).
+
+    ``workspace``: a uint8 GPU tensor, None (run a kernel that needs none), or "auto" (allocate what
+    xnor_conv2d_workspace_bytes asks for -- callers in a timed loop pass their own buffer)."""
     OH, OW = xnor_out_dim(s)
     oshape = (s.N, s.F, OH, OW)
     if out is None:
         out = torch.empty(oshape, dtype=torch.float32, device=Ipk.device)
     if dot is None and want_dot:
         dot = torch.empty(oshape, dtype=torch.int32, device=Ipk.device)
+    if isinstance(workspace, str):
+        nbytes = xnor_conv2d_workspace_bytes(s)
+        workspace = torch.empty((nbytes,), dtype=torch.uint8, device=Ipk.device) if nbytes else None
+    ws_ptr = _dev(workspace, torch.uint8, name="workspace") if workspace is not None else None
+    ws_bytes = workspace.numel() if workspace is not None else 0
     _ok(lib.xnor_conv2d_fwd_algo(
         _dev(Ipk, torch.int32, (s.N, s.H, s.W, s.Cw), "Ipk"),
         _dev(Wpk, torch.int32, (s.F, s.kh, s.kw, s.Cw), "Wpk"),
         _dev(K, torch.float32, (s.N, OH, OW), "K"), _dev(alpha, torch.float32, (s.F,), "alpha"),
         ctypes.byref(s.c()), _dev(out, torch.float32, oshape, "out"),
         _dev(dot, torch.int32, oshape, "dot") if dot is not None else None,
-        algo, _stream()), f"xnor_conv2d_fwd[{ALGO_NAMES.get(algo, algo)}]")
+        ws_ptr, ws_bytes, algo, _stream()), f"xnor_conv2d_fwd[{ALGO_NAMES.get(algo, algo)}]")
     return out, dot

@@ -43,9 +43,10 @@ int make_geom(const xnor_shape *s, xnor::Geom *g)
     return XNOR_OK;
 }
 
-int pick_algo(const xnor::Geom &g)
+int pick_algo(const xnor::Geom &g, size_t workspace_bytes)
 {
-    if (xnor::conv_mfma_supports(g)) return XNOR_ALGO_MFMA;
+    const size_t need = xnor::conv_mfma_workspace_bytes(g);
+    if (need > 0 && workspace_bytes >= need) return XNOR_ALGO_MFMA;
     if (xnor::conv_tiled_supports(g)) return XNOR_ALGO_TILED;
     return XNOR_ALGO_DIRECT;
 }
@@ -76,6 +77,7 @@ const char *xnor_strerror(int status)
         case XNOR_E_ALIGN: return "pointer not aligned as required";
         case XNOR_E_HIP: return "HIP launch failed (see xnor_last_hip_error)";
         case XNOR_E_UNSUPPORTED: return "the requested algorithm does not support this shape";
+        case XNOR_E_WORKSPACE: return "the requested algorithm needs a larger workspace";
         default: return "unknown status";
     }
 }
@@ -116,44 +118,60 @@ int xnor_alpha(const float *Wt, int F, int C, int kh, int kw, float *alpha, void
     return hip_status(xnor::launch_alpha(Wt, F, n_red, alpha, (hipStream_t)stream));
 }
 
-int xnor_conv2d_pick_algo(const xnor_shape *s)
+int xnor_conv2d_pick_algo(const xnor_shape *s, size_t workspace_bytes)
 {
     xnor::Geom g;
     const int rc = make_geom(s, &g);
-    return rc ? rc : pick_algo(g);
+    return rc ? rc : pick_algo(g, workspace_bytes);
+}
+
+int xnor_conv2d_workspace_bytes(const xnor_shape *s, size_t *bytes)
+{
+    if (!s || !bytes) return XNOR_E_NULL;
+    xnor::Geom g;
+    const int rc = make_geom(s, &g);
+    if (rc) return rc;
+    *bytes = xnor::conv_mfma_workspace_bytes(g);
+    return XNOR_OK;
 }
 
 int xnor_conv2d_fwd_algo(const uint32_t *Ipk, const uint32_t *Wpk, const float *K,
                          const float *alpha, const xnor_shape *s, float *out, int32_t *dot,
-                         int algo, void *stream)
+                         void *workspace, size_t workspace_bytes, int algo, void *stream)
 {
     if (!Ipk || !Wpk || !K || !alpha || !s || !out) return XNOR_E_NULL;
     xnor::Geom g;
     const int rc = make_geom(s, &g);
     if (rc) return rc;
     if (!aligned(Ipk, 4) || !aligned(Wpk, 4) || !aligned(K, 4) || !aligned(alpha, 4) ||
-        !aligned(out, 4) || (dot && !aligned(dot, 4)))
+        !aligned(out, 4) || (dot && !aligned(dot, 4)) || (workspace && !aligned(workspace, 16)))
         return XNOR_E_ALIGN;
+    if (!workspace) workspace_bytes = 0;
     hipStream_t st = (hipStream_t)stream;
-    if (algo == XNOR_ALGO_AUTO) algo = pick_algo(g);
+    if (algo == XNOR_ALGO_AUTO) algo = pick_algo(g, workspace_bytes);
     switch (algo) {
         case XNOR_ALGO_DIRECT:
             return hip_status(xnor::launch_conv_direct(Ipk, Wpk, K, alpha, g, out, dot, st));
         case XNOR_ALGO_TILED:
             if (!xnor::conv_tiled_supports(g)) return XNOR_E_UNSUPPORTED;
             return hip_status(xnor::launch_conv_tiled(Ipk, Wpk, K, alpha, g, out, dot, st));
-        case XNOR_ALGO_MFMA:
-            if (!xnor::conv_mfma_supports(g)) return XNOR_E_UNSUPPORTED;
-            return hip_status(xnor::launch_conv_mfma(Ipk, Wpk, K, alpha, g, out, dot, st));
+        case XNOR_ALGO_MFMA: {
+            const size_t need = xnor::conv_mfma_workspace_bytes(g);
+            if (need == 0) return XNOR_E_UNSUPPORTED;
+            if (workspace_bytes < need) return XNOR_E_WORKSPACE;
+            return hip_status(xnor::launch_conv_mfma(Ipk, Wpk, K, alpha, g, out, dot, workspace, st));
+        }
         default:
             return XNOR_E_UNSUPPORTED;
     }
 }
 
 int xnor_conv2d_fwd(const uint32_t *Ipk, const uint32_t *Wpk, const float *K, const float *alpha,
-                    const xnor_shape *s, float *out, int32_t *dot, void *stream)
+                    const xnor_shape *s, float *out, int32_t *dot, void *workspace,
+                    size_t workspace_bytes, void *stream)
 {
-    return xnor_conv2d_fwd_algo(Ipk, Wpk, K, alpha, s, out, dot, XNOR_ALGO_AUTO, stream);
+    return xnor_conv2d_fwd_algo(Ipk, Wpk, K, alpha, s, out, dot, workspace, workspace_bytes,
+                                XNOR_ALGO_AUTO, stream);
 }
 
 }  // extern "C"

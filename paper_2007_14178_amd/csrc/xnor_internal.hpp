@@ -34,8 +34,9 @@ hipError_t launch_conv_tiled(const uint32_t *Ipk, const uint32_t *Wpk, const flo
                              hipStream_t st);
 
 bool conv_mfma_supports(const Geom &g);
+size_t conv_mfma_workspace_bytes(const Geom &g);   // 0 if the shape is not supported
 hipError_t launch_conv_mfma(const uint32_t *Ipk, const uint32_t *Wpk, const float *K,
                             const float *alpha, const Geom &g, float *out, int32_t *dot,
-                            hipStream_t st);
+                            void *workspace, hipStream_t st);
 
 }  // namespace xnor

@@ -39,8 +39,8 @@ def test_out_dim_and_words(xb):
 
 
 def test_strerror_covers_every_status(xb):
-    seen = {xb.lib.xnor_strerror(s) for s in range(0, -6, -1)}
-    assert len(seen) == 6 and all(seen)
+    seen = {xb.lib.xnor_strerror(s) for s in range(0, -7, -1)}
+    assert len(seen) == 7 and all(seen)
     assert xb.lib.xnor_strerror(-99)
 
 
@@ -60,8 +60,10 @@ def test_bad_shapes_rejected(xb, bad):
     assert xb.lib.xnor_out_dim(ctypes.byref(s.c()), ctypes.byref(oh), ctypes.byref(ow)) == xb.E_SHAPE
     fake = ctypes.c_void_p(0x1000)
     assert xb.lib.xnor_scale_K(fake, ctypes.byref(s.c()), fake, fake, None) == xb.E_SHAPE
-    assert xb.lib.xnor_conv2d_fwd(fake, fake, fake, fake, ctypes.byref(s.c()), fake, None, None) == xb.E_SHAPE
-    assert xb.lib.xnor_conv2d_pick_algo(ctypes.byref(s.c())) == xb.E_SHAPE
+    assert xb.lib.xnor_conv2d_fwd(fake, fake, fake, fake, ctypes.byref(s.c()), fake, None, None, 0, None) == xb.E_SHAPE
+    assert xb.lib.xnor_conv2d_pick_algo(ctypes.byref(s.c()), 0) == xb.E_SHAPE
+    nb = ctypes.c_size_t()
+    assert xb.lib.xnor_conv2d_workspace_bytes(ctypes.byref(s.c()), ctypes.byref(nb)) == xb.E_SHAPE
 
 
 def test_null_and_alignment_rejected(xb):
@@ -84,10 +86,18 @@ def test_null_and_alignment_rejected(xb):
     for k in range(6):
         args = [ok, ok, ok, ok, sp, ok]
         args[k] = None
-        assert L.xnor_conv2d_fwd(*args, None, None) == xb.E_NULL
-    assert L.xnor_conv2d_fwd(odd, ok, ok, ok, sp, ok, None, None) == xb.E_ALIGN
-    assert L.xnor_conv2d_fwd(ok, ok, ok, ok, sp, ok, odd, None) == xb.E_ALIGN
-    assert L.xnor_conv2d_fwd_algo(ok, ok, ok, ok, sp, ok, None, 99, None) == xb.E_UNSUPPORTED
+        assert L.xnor_conv2d_fwd(*args, None, None, 0, None) == xb.E_NULL
+    assert L.xnor_conv2d_fwd(odd, ok, ok, ok, sp, ok, None, None, 0, None) == xb.E_ALIGN
+    assert L.xnor_conv2d_fwd(ok, ok, ok, ok, sp, ok, odd, None, 0, None) == xb.E_ALIGN
+    assert L.xnor_conv2d_fwd(ok, ok, ok, ok, sp, ok, None, ctypes.c_void_p(0x1008), 1 << 20, None) == xb.E_ALIGN
+    assert L.xnor_conv2d_fwd_algo(ok, ok, ok, ok, sp, ok, None, None, 0, 99, None) == xb.E_UNSUPPORTED
+    # the matrix-core kernel refuses to run without its workspace; AUTO then picks another kernel
+    assert L.xnor_conv2d_fwd_algo(ok, ok, ok, ok, sp, ok, None, None, 0, xb.ALGO_MFMA, None) == xb.E_WORKSPACE
+    assert L.xnor_conv2d_fwd_algo(ok, ok, ok, ok, sp, ok, None, ok, 16, xb.ALGO_MFMA, None) == xb.E_WORKSPACE
+    need = xb.xnor_conv2d_workspace_bytes(s)
+    assert need > 0 and need % 1024 == 0
+    assert xb.xnor_conv2d_pick_algo(s, need) == xb.ALGO_MFMA
+    assert xb.xnor_conv2d_pick_algo(s, need - 1) != xb.ALGO_MFMA
 
 
 def test_binding_refuses_cpu_tensors(xb):
