@@ -24,6 +24,7 @@
 // logic.  Filter words are expanded once per call into a workspace laid out in A-operand order
 // and stream from L2 straight into registers.
 #include <algorithm>
+#include <atomic>
 
 #include "xnor_internal.hpp"
 
@@ -37,6 +38,8 @@ constexpr int kWM = 2;            // 32-filter tiles per wave
 constexpr int kWN = 4;            // 32-pixel tiles per wave (at most)
 constexpr int kBandPixels = 2 * 32 * kWN;   // 2 wave columns
 constexpr int kFilterTile = 2 * 32 * kWM;   // 2 wave rows
+constexpr int kRing = 4;          // register ring of filter operands: loads run kRing-1 steps ahead
+constexpr int kPatchPitch = 36;    // floats per row of a wave's 32x32 output patch in LDS (144 bytes)
 constexpr int kScaleOne = 0x7f7f7f7f;       // E8M0 exponent 127 = 2^0
 
 // q = n / d for n*d < 2^32 via one mul_hi.
@@ -61,6 +64,8 @@ struct MfmaParams {
     int CH;          // packed words per LDS channel chunk (even)
     int nchunks;
     int pitch16;     // LDS slot pitch in 16-byte units (CH + 1, odd)
+    int chunk_steps; // k-steps the workspace holds per (filter tile, chunk): taps*CH/2 rounded up to
+                     // the ring depth, plus one ring of zero steps for the prefetch overrun
     FastDiv dCHV, dWp, dRH;
 };
 
@@ -92,27 +97,33 @@ __device__ inline uint4 expand_word(uint32_t w, int nvalid)
     return e;
 }
 
-// Filter words -> FP4 in A-operand order: Wx[tile32][tap][step][lane] (one uint4 per lane), lane l
-// = filter 32*tile32 + l%32, packed word 2*step + l/32.  Filters >= F, words >= Cw and channels
-// >= C come out as zeros.
+// Filter words -> FP4 in A-operand order: Wx[tile32][chunk][step][lane] (one uint4 per lane).
+// Within a chunk the steps run tap-major: step = tap * steps_c + s, packed word = chunk*CH + 2*s +
+// lane/32, filter = 32*tile32 + lane%32; so the MFMA loop walks the workspace linearly.  Steps past
+// taps*steps_c (padding up to chunk_steps), filters >= F, words >= Cw and channels >= C are zeros.
 __global__ __launch_bounds__(256) void expand_filters_kernel(const uint32_t *__restrict__ Wpk,
                                                              uint4 *__restrict__ Wx, int F, int C,
-                                                             int Cw, int taps, int S2, long long total)
+                                                             int Cw, int taps, int CH, int nchunks,
+                                                             int chunk_steps, int Cw2, long long total)
 {
     const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
     if (i >= total) return;
     const int lane = (int)(i & 63);
     long long t = i >> 6;
-    const int step = (int)(t % S2);
-    t /= S2;
-    const int tap = (int)(t % taps);
-    const int tile = (int)(t / taps);
-    const int f = tile * 32 + (lane & 31);
-    const int w = 2 * step + (lane >> 5);
+    const int step = (int)(t % chunk_steps);
+    t /= chunk_steps;
+    const int chunk = (int)(t % nchunks);
+    const int tile = (int)(t / nchunks);
+    const int steps_c = min(CH, Cw2 - chunk * CH) >> 1;
     uint4 e = make_uint4(0, 0, 0, 0);
-    if (f < F && w < Cw) {
-        const int nvalid = min(32, C - 32 * w);
-        e = expand_word(Wpk[((long long)f * taps + tap) * Cw + w], nvalid);
+    if (step < taps * steps_c) {
+        const int tap = step / steps_c, s = step - tap * steps_c;
+        const int f = tile * 32 + (lane & 31);
+        const int w = chunk * CH + 2 * s + (lane >> 5);
+        if (f < F && w < Cw) {
+            const int nvalid = min(32, C - 32 * w);
+            e = expand_word(Wpk[((long long)f * taps + tap) * Cw + w], nvalid);
+        }
     }
     Wx[i] = e;
 }
@@ -126,11 +137,85 @@ struct WordVec<2> { typedef uint2 type; };
 template <>
 struct WordVec<4> { typedef uint4 type; };
 
+// One LDS channel chunk: for every tap and every 64-channel step, NTW pixel tiles x kWM filter
+// tiles of MFMAs.  The loop body has no branches: the filter operands are read linearly from the
+// workspace through a register ring (loads run kRing-1 steps ahead; the workspace is zero-padded to
+// a whole number of rings plus one), the pixel operands come from LDS one step ahead, and the
+// (tap, step) cursor of the pixel operand advances with selects.
+template <int NTW>
+__device__ __forceinline__ void contract_chunk(const MfmaParams &p, const uint4 *lds,
+                                               const uint4 *const (&Achunk)[kWM],
+                                               const uint32_t (&baseB)[kWN], v16f (&acc)[kWM][kWN],
+                                               int steps)
+{
+    constexpr int D = kRing;
+    static_assert(D % 2 == 0, "the unrolled body alternates two pixel-operand buffers");
+    const int T = p.kh * p.kw * steps;
+
+    int l_off = 0;
+    uint4 abuf[D][kWM];
+    auto load_a = [&](uint4 (&dst)[kWM]) {
+#pragma unroll
+        for (int i = 0; i < kWM; ++i) dst[i] = Achunk[i][l_off];
+        l_off += 64;
+    };
+#pragma unroll
+    for (int u = 0; u < D - 1; ++u) load_a(abuf[u]);
+
+    // pixel-operand cursor: offset of (tap, step) from the lane's slot, in 16-byte units; past the
+    // last tap it parks on tap 0 (those steps multiply zero filter operands)
+    int b_s = 0, b_kx = 0, b_ky = 0;
+    uint32_t b_off = 0;
+    uint4 bbuf[2][NTW];
+    auto load_b = [&](uint4 (&dst)[NTW]) {
+#pragma unroll
+        for (int j = 0; j < NTW; ++j) dst[j] = lds[baseB[j] + b_off];
+        ++b_s;
+        const bool wrap_s = b_s == steps;
+        b_s = wrap_s ? 0 : b_s;
+        b_kx += wrap_s ? 1 : 0;
+        const bool wrap_x = b_kx == p.kw;
+        b_kx = wrap_x ? 0 : b_kx;
+        b_ky += wrap_x ? 1 : 0;
+        const uint32_t tap_off = b_ky < p.kh ? (uint32_t)((b_ky * p.Wp + b_kx) * p.pitch16) : 0u;
+        b_off = wrap_s ? tap_off : b_off + 2;
+    };
+    load_b(bbuf[0]);
+
+    for (int t = 0; t < T; t += D) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            load_a(abuf[(u + D - 1) % D]);
+            load_b(bbuf[(u + 1) % 2]);
+#pragma unroll
+            for (int i = 0; i < kWM; ++i) {
+                const uint4 va = abuf[u][i];
+                const v8i a = v8i{(int)va.x, (int)va.y, (int)va.z, (int)va.w, 0, 0, 0, 0};
+#pragma unroll
+                for (int j = 0; j < NTW; ++j) {
+                    const uint4 vb = bbuf[u % 2][j];
+                    const v8i b = v8i{(int)vb.x, (int)vb.y, (int)vb.z, (int)vb.w, 0, 0, 0, 0};
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                        a, b, acc[i][j], 4, 4, 0, kScaleOne, 0, kScaleOne);
+                }
+            }
+            // Pin the accumulators between steps (an empty volatile asm that "modifies" them):
+            // left free, the compiler interleaves the MFMAs of all unrolled steps and runs out of
+            // registers for the operands it then has to keep alive.
+#pragma unroll
+            for (int i = 0; i < kWM; ++i)
+#pragma unroll
+                for (int j = 0; j < NTW; ++j) asm volatile("" : "+v"(acc[i][j]));
+        }
+    }
+}
+
 template <int VW>
 __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
 {
     extern __shared__ uint4 lds[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in an SGPR
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, kg = lane >> 5;
     const int OHW = p.OH * p.OW;
@@ -154,30 +239,23 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
     const int my_nt = wn ? NT - nt0 : nt0;
 
     uint32_t baseB[kWN];   // LDS index (16-byte units) of the lane's pixel, tap (0,0), k-group kg
-    bool pix_ok[kWN];
-    int img[kWN], pixoff[kWN], kidx[kWN];
 #pragma unroll
     for (int j = 0; j < kWN; ++j) {
         const int q = (tile0 + j) * 32 + l32;
-        pix_ok[j] = (j < my_nt) && (q < npix);
-        const int qq = pix_ok[j] ? q : 0;
+        const int qq = (j < my_nt && q < npix) ? q : 0;   // idle lanes read pixel 0 and store nothing
         const int Rl = qq / p.OW, ox = qq - Rl * p.OW;
         const int R = R0 + Rl;
         const int n = R / p.OH, oy = R - n * p.OH;
         const int srow = (n == n_first) ? (oy - oy0) * p.sh
                                         : r0 + (n - n_first - 1) * p.RHfull + oy * p.sh;
         baseB[j] = (uint32_t)((srow * p.Wp + ox * p.sw) * p.pitch16 + kg);
-        img[j] = n;
-        pixoff[j] = oy * p.OW + ox;
-        kidx[j] = R * p.OW + ox;
     }
 
-    const int taps = p.kh * p.kw;
-    const uint4 *Aptr[kWM];
+    const uint4 *Aptr[kWM];   // this lane's filter operands, chunk 0, step 0
 #pragma unroll
     for (int i = 0; i < kWM; ++i) {
         const int tile = blockIdx.y * (2 * kWM) + wm * kWM + i;
-        Aptr[i] = p.Wx + ((long long)tile * taps * p.S2) * 64 + lane;
+        Aptr[i] = p.Wx + ((long long)tile * p.nchunks * p.chunk_steps) * 64 + lane;
     }
 
     v16f acc[kWM][kWN];
@@ -248,52 +326,76 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
         __syncthreads();
 
         // ---- contract: taps x 64-channel steps ----
-        for (int ky = 0; ky < p.kh; ++ky)
-            for (int kx = 0; kx < p.kw; ++kx) {
-                const int tap = ky * p.kw + kx;
-                const uint32_t tapoff = (uint32_t)((ky * p.Wp + kx) * p.pitch16);
-                const long long a_off = ((long long)tap * p.S2 + (w_base >> 1)) * 64;
-                for (int s = 0; s < steps; ++s) {
-                    v8i a[kWM], b[kWN];
+        // every wave with work runs all kWN tiles; tiles past the band's end read slot 0 and are
+        // never stored (one code path keeps the accumulators out of scratch)
+        if (my_nt > 0) {
+            const uint4 *Achunk[kWM];
 #pragma unroll
-                    for (int i = 0; i < kWM; ++i) {
-                        const uint4 t = Aptr[i][a_off + (long long)s * 64];
-                        a[i] = v8i{(int)t.x, (int)t.y, (int)t.z, (int)t.w, 0, 0, 0, 0};
-                    }
-#pragma unroll
-                    for (int j = 0; j < kWN; ++j) {
-                        if (j < my_nt) {
-                            const uint4 t = lds[baseB[j] + tapoff + 2 * s];
-                            b[j] = v8i{(int)t.x, (int)t.y, (int)t.z, (int)t.w, 0, 0, 0, 0};
-                        }
-                    }
-#pragma unroll
-                    for (int i = 0; i < kWM; ++i)
-#pragma unroll
-                        for (int j = 0; j < kWN; ++j)
-                            if (j < my_nt)
-                                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                                    a[i], b[j], acc[i][j], 4, 4, 0, kScaleOne, 0, kScaleOne);
-                }
-            }
+            for (int i = 0; i < kWM; ++i) Achunk[i] = Aptr[i] + (long long)c * p.chunk_steps * 64;
+            contract_chunk<kWN>(p, lds, Achunk, baseB, acc, steps);
+        }
     }
 
-    // ---- step 3: out = float(dot) * K * alpha; lanes run along pixels, registers along filters ----
+    // ---- step 3: out = float(dot) * K * alpha ----
+    // The MFMA result has pixels along lanes and filters along registers, which would make every
+    // store a 4-byte-per-lane instruction.  Each wave instead passes its 32x32 tiles through a
+    // private LDS patch and reads them back with four consecutive pixels of one filter per lane,
+    // so that one store instruction writes eight 128-byte runs (16 bytes per lane).
+    __syncthreads();   // all waves are done with the staged input
+    const float *__restrict__ Kp = p.K;
+    const float *__restrict__ alphap = p.alpha;
+    float *__restrict__ outp = p.out;
+    int32_t *__restrict__ dotp = p.dot;
+    float *patch = reinterpret_cast<float *>(lds) + wave * (32 * kPatchPitch);
+    const int p4 = (lane & 7) * 4;      // first of this lane's four pixels within a tile
+    const int fl = lane >> 3;           // filter within a tile, plus 8*k
+    if (my_nt > 0) {
 #pragma unroll
-    for (int j = 0; j < kWN; ++j) {
-        if (!pix_ok[j]) continue;
-        const float kv = p.K[kidx[j]];
+        for (int j = 0; j < kWN; ++j) {
+            if (j >= my_nt) break;
+            // the lane's pixel quad: position, validity, contiguity
+            const int q0 = (tile0 + j) * 32 + p4;
+            const int nv = min(4, npix - q0);                 // valid pixels of the quad (may be <= 0)
+            const int qc = nv > 0 ? q0 : 0;
+            const int Rl = qc / p.OW, ox = qc - Rl * p.OW;
+            const int R = R0 + Rl;
+            const int n = R / p.OH, oy = R - n * p.OH;
+            const int po = oy * p.OW + ox;                    // offset inside the (n, f) plane
+            const bool quad = nv == 4 && po + 3 < OHW;        // four pixels of one image: one 16-byte run
+            const long long kbase = (long long)R * p.OW + ox; // K is dense over (n, oy, ox)
+            float kq[4];
 #pragma unroll
-        for (int i = 0; i < kWM; ++i) {
-            const int f_base = (blockIdx.y * (2 * kWM) + wm * kWM + i) * 32 + kg * 4;
+            for (int e = 0; e < 4; ++e) kq[e] = e < nv ? Kp[kbase + e] : 0.0f;
+            const long long obase = (long long)n * p.F * OHW + po;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int f = f_base + (r >> 2) * 8 + (r & 3);
-                if (f < p.F) {
-                    const long long o = ((long long)img[j] * p.F + f) * OHW + pixoff[j];
-                    const float d = acc[i][j][r];
-                    p.out[o] = d * (kv * p.alpha[f]);
-                    if (p.dot) p.dot[o] = (int32_t)d;
+            for (int i = 0; i < kWM; ++i) {
+                const int f_tile = (blockIdx.y * (2 * kWM) + wm * kWM + i) * 32;
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    patch[((r >> 2) * 8 + kg * 4 + (r & 3)) * kPatchPitch + l32] = acc[i][j][r];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int f = f_tile + fl + 8 * k;
+                    const float4 d = *reinterpret_cast<const float4 *>(&patch[(fl + 8 * k) * kPatchPitch + p4]);
+                    if (f >= p.F || nv <= 0) continue;
+                    const float al = alphap[f];
+                    const long long o = obase + (long long)f * OHW;
+                    const float dd[4] = {d.x, d.y, d.z, d.w};
+                    if (quad) {
+                        *reinterpret_cast<float4 *>(outp + o) =
+                            make_float4(d.x * (kq[0] * al), d.y * (kq[1] * al), d.z * (kq[2] * al), d.w * (kq[3] * al));
+                        if (dotp)
+                            *reinterpret_cast<int4 *>(dotp + o) = make_int4((int)d.x, (int)d.y, (int)d.z, (int)d.w);
+                    } else {
+                        // quad cut by the band's end or by an image boundary: pixel by pixel
+                        for (int e = 0; e < nv; ++e) {
+                            const int Re = (int)((kbase + e) / p.OW), oxe = (int)((kbase + e) - (long long)Re * p.OW);
+                            const int ne = Re / p.OH, oye = Re - ne * p.OH;
+                            const long long oe = ((long long)ne * p.F + f) * OHW + oye * p.OW + oxe;
+                            outp[oe] = dd[e] * (kq[e] * al);
+                            if (dotp) dotp[oe] = (int32_t)dd[e];
+                        }
+                    }
                 }
             }
         }
@@ -303,7 +405,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
 // Tiling chosen on the host for one layer.
 struct MfmaPlan {
     bool ok;
-    int TH, Wp, RHfull, S2, CH, nchunks, pitch16, slots_max, vw;
+    int TH, Wp, RHfull, S2, CH, nchunks, pitch16, slots_max, vw, chunk_steps;
     size_t lds_bytes, ws_bytes;
     int f_tiles;   // workgroup rows of kFilterTile filters
 };
@@ -353,12 +455,14 @@ MfmaPlan make_plan(const Geom &g, const void *Ipk)
         return false;
     };
     if (!fit(kLdsTwoPerCU) && !fit(kLdsMax)) return pl;
+    pl.lds_bytes = std::max(pl.lds_bytes, (size_t)4 * 32 * kPatchPitch * sizeof(float));   // output patches
     if ((long long)slots * pl.CH >= (1 << 20)) return pl;   // fast-division range
     const uintptr_t ip = reinterpret_cast<uintptr_t>(Ipk);
     pl.vw = (g.Cw % 4 == 0 && pl.CH % 4 == 0 && (ip & 15) == 0) ? 4
           : (g.Cw % 2 == 0 && (ip & 7) == 0)                    ? 2 : 1;
     pl.f_tiles = ceil_div(g.F, kFilterTile);
-    pl.ws_bytes = (size_t)pl.f_tiles * (kFilterTile / 32) * g.kh * g.kw * pl.S2 * 64 * sizeof(uint4);
+    pl.chunk_steps = (g.kh * g.kw * (pl.CH / 2) + kRing - 1) / kRing * kRing + kRing;
+    pl.ws_bytes = (size_t)pl.f_tiles * (kFilterTile / 32) * pl.nchunks * pl.chunk_steps * 64 * sizeof(uint4);
     if (ceil_div(total_rows, pl.TH) > 0x7fffffffLL || pl.f_tiles > 65535) return pl;
     pl.ok = true;
     return pl;
@@ -388,8 +492,8 @@ hipError_t launch_conv_mfma(const uint32_t *Ipk, const uint32_t *Wpk, const floa
     // filters -> FP4 in A-operand order (per call: the library keeps no state)
     uint4 *Wx = static_cast<uint4 *>(workspace);
     const long long wx_items = (long long)(pl.ws_bytes / sizeof(uint4));
-    expand_filters_kernel<<<ceil_div(wx_items, 256), 256, 0, st>>>(Wpk, Wx, g.F, g.C, g.Cw, taps,
-                                                                   pl.S2, wx_items);
+    expand_filters_kernel<<<ceil_div(wx_items, 256), 256, 0, st>>>(
+        Wpk, Wx, g.F, g.C, g.Cw, taps, pl.CH, pl.nchunks, pl.chunk_steps, 2 * pl.S2, wx_items);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
@@ -401,16 +505,26 @@ hipError_t launch_conv_mfma(const uint32_t *Ipk, const uint32_t *Wpk, const floa
     p.total_rows = g.N * g.OH;
     p.Wp = pl.Wp; p.RHfull = pl.RHfull; p.S2 = pl.S2; p.CH = pl.CH; p.nchunks = pl.nchunks;
     p.pitch16 = pl.pitch16;
+    p.chunk_steps = pl.chunk_steps;
     p.dCHV = make_fastdiv(pl.CH / pl.vw);
     p.dWp = make_fastdiv(pl.Wp);
     p.dRH = make_fastdiv(pl.RHfull);
 
     const dim3 grid(ceil_div(p.total_rows, pl.TH), pl.f_tiles);
     auto launch = [&](auto kernel) -> hipError_t {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             (int)pl.lds_bytes);
+        // raise the kernel's dynamic-LDS limit to the hardware maximum once per device (the call
+        // is slow on the host); one flag set per template instance
+        static std::atomic<unsigned long long> raised{0};
+        int dev = 0;
+        hipError_t err = hipGetDevice(&dev);
         if (err != hipSuccess) return err;
+        const unsigned long long bit = 1ull << (dev & 63);
+        if (!(raised.load(std::memory_order_acquire) & bit)) {
+            err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax);
+            if (err != hipSuccess) return err;
+            raised.fetch_or(bit, std::memory_order_release);
+        }
         kernel<<<grid, 256, pl.lds_bytes, st>>>(p);
         return hipGetLastError();
     };
