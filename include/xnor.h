@@ -101,6 +101,29 @@ int xnor_scale_K(const float *I, const xnor_shape *s, float *A_work, float *K, v
 int xnor_alpha(const float *Wt, int F, int C, int kh, int kw, float *alpha, void *stream);
 
 /*
+ * Step 1a and Eq. 10 in one pass over I (each input element is read from HBM once): the packed
+ * input of xnor_binarize_pack(I) and the A and K of xnor_scale_K(I), same definitions, same layouts.
+ * The paper computes the bit path and the scale path as separate kernels (Sec. III-C).
+ *   I       in   fp32 [N][C][H][W]
+ *   Ipk     out  uint32 [N][H][W][ceil(C/32)]
+ *   A_work  out  fp32 [N][H][W]   caller-owned workspace; holds A on return
+ *   K       out  fp32 [N][OH][OW]
+ */
+int xnor_input_prepare(const float *I, const xnor_shape *s, uint32_t *Ipk, float *A_work, float *K,
+                       void *stream);
+
+/*
+ * Per-model filter preparation in one pass over Wt: the packed filters of xnor_binarize_pack(Wt)
+ * (step 1a, Eq. 3) and the alpha of xnor_alpha(Wt) (Eq. 5).
+ *   Wt      in   fp32 [F][C][kh][kw]
+ *   Wpk     out  uint32 [F][kh][kw][ceil(C/32)]
+ *   M_work  out  fp32 [F][kh][kw]  caller-owned workspace; holds mean_c |Wt| per tap on return
+ *   alpha   out  fp32 [F]
+ */
+int xnor_filter_prepare(const float *Wt, int F, int C, int kh, int kw, uint32_t *Wpk, float *M_work,
+                        float *alpha, void *stream);
+
+/*
  * Steps 1b-1d and 3 (Sec. III-A), Eq. 11:
  *   dot[n][f][oy][ox] = sum over in-image taps (ky,kx) and channels c of
  *                       sign(I[n][c][oy*sh-ph+ky][ox*sw-pw+kx]) * sign(Wt[f][c][ky][kx])

@@ -75,6 +75,8 @@ def _load() -> ctypes.CDLL:
     L.xnor_binarize_pack.argtypes = [vp, ci, ci, ci, ci, vp, vp]
     L.xnor_scale_K.argtypes = [vp, sp, vp, vp, vp]
     L.xnor_alpha.argtypes = [vp, ci, ci, ci, ci, vp, vp]
+    L.xnor_input_prepare.argtypes = [vp, sp, vp, vp, vp, vp]
+    L.xnor_filter_prepare.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp]
     sz = ctypes.c_size_t
     L.xnor_conv2d_fwd.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, vp]
     L.xnor_conv2d_fwd_algo.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, ci, vp]
@@ -82,7 +84,7 @@ def _load() -> ctypes.CDLL:
     L.xnor_conv2d_workspace_bytes.argtypes = [sp, ctypes.POINTER(sz)]
     for name in ("xnor_out_dim", "xnor_packed_words", "xnor_binarize_pack", "xnor_scale_K",
                  "xnor_alpha", "xnor_conv2d_fwd", "xnor_conv2d_fwd_algo", "xnor_conv2d_pick_algo",
-                 "xnor_conv2d_workspace_bytes"):
+                 "xnor_conv2d_workspace_bytes", "xnor_input_prepare", "xnor_filter_prepare"):
         getattr(L, name).restype = ci
     return L
 
@@ -152,6 +154,41 @@ def xnor_alpha(Wt: torch.Tensor, alpha: torch.Tensor | None = None) -> torch.Ten
     _ok(lib.xnor_alpha(_dev(Wt, torch.float32, name="Wt"), F, C, kh, kw,
                        _dev(alpha, torch.float32, (F,), "alpha"), _stream()), "xnor_alpha")
     return alpha
+
+
+def xnor_input_prepare(I: torch.Tensor, s: Shape, Ipk: torch.Tensor | None = None,
+                       A_work: torch.Tensor | None = None, K: torch.Tensor | None = None):
+    """One pass over I: returns (Ipk, K, A)."""
+    OH, OW = xnor_out_dim(s)
+    if Ipk is None:
+        Ipk = torch.empty((s.N, s.H, s.W, s.Cw), dtype=torch.int32, device=I.device)
+    if A_work is None:
+        A_work = torch.empty((s.N, s.H, s.W), dtype=torch.float32, device=I.device)
+    if K is None:
+        K = torch.empty((s.N, OH, OW), dtype=torch.float32, device=I.device)
+    _ok(lib.xnor_input_prepare(_dev(I, torch.float32, (s.N, s.C, s.H, s.W), "I"), ctypes.byref(s.c()),
+                               _dev(Ipk, torch.int32, (s.N, s.H, s.W, s.Cw), "Ipk"),
+                               _dev(A_work, torch.float32, (s.N, s.H, s.W), "A_work"),
+                               _dev(K, torch.float32, (s.N, OH, OW), "K"), _stream()), "xnor_input_prepare")
+    return Ipk, K, A_work
+
+
+def xnor_filter_prepare(Wt: torch.Tensor, Wpk: torch.Tensor | None = None,
+                        M_work: torch.Tensor | None = None, alpha: torch.Tensor | None = None):
+    """One pass over Wt: returns (Wpk, alpha, M) with M = mean_c |Wt| per tap."""
+    F, C, kh, kw = Wt.shape
+    Cw = (C + 31) // 32
+    if Wpk is None:
+        Wpk = torch.empty((F, kh, kw, Cw), dtype=torch.int32, device=Wt.device)
+    if M_work is None:
+        M_work = torch.empty((F, kh, kw), dtype=torch.float32, device=Wt.device)
+    if alpha is None:
+        alpha = torch.empty((F,), dtype=torch.float32, device=Wt.device)
+    _ok(lib.xnor_filter_prepare(_dev(Wt, torch.float32, name="Wt"), F, C, kh, kw,
+                                _dev(Wpk, torch.int32, (F, kh, kw, Cw), "Wpk"),
+                                _dev(M_work, torch.float32, (F, kh, kw), "M_work"),
+                                _dev(alpha, torch.float32, (F,), "alpha"), _stream()), "xnor_filter_prepare")
+    return Wpk, alpha, M_work
 
 
 def xnor_conv2d_workspace_bytes(s: Shape) -> int:

@@ -122,6 +122,101 @@ hipError_t launch_channel_mean_abs(const float *I, int N, int C, int H, int W, f
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------------
+// Step 1a and the first half of Eq. 10 in ONE pass over the fp32 tensor: every element is read
+// once, its sign goes into the packed word and its magnitude into the channel sum.  (The paper runs
+// the two as separate kernels on two streams; on an HBM-bound pre-stage the second read is the cost.)
+// Block = 64 pixels x S slices; slice s owns packed words s, s+S, ...  The words are collected in
+// LDS and written out as one contiguous run of 64*Cw words; the slices' partial |x| sums (double)
+// are combined in a fixed order.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64 * kMaxSlices) void pack_and_mean_kernel(
+    const float *__restrict__ x, long long NP, int C, int HW, int Cw, int Cwp,
+    uint32_t *__restrict__ packed, float *__restrict__ A)
+{
+    extern __shared__ double pm_smem[];
+    const int lane = threadIdx.x, s = threadIdx.y, S = blockDim.y;
+    double *part = pm_smem;                                              // [S][64]
+    uint32_t *words = reinterpret_cast<uint32_t *>(pm_smem + S * 64);    // [64][Cwp], Cwp odd
+    const long long p0 = (long long)blockIdx.x * 64;
+    const long long p = p0 + lane;
+    double acc = 0.0;
+    if (p < NP) {
+        const long long n = p / HW;
+        const int hw = (int)(p - n * HW);
+        const float *src = x + (n * C) * (long long)HW + hw;
+        for (int w = s; w < Cw; w += S) {
+            const int cbase = 32 * w;
+            uint32_t word = 0;
+            if (cbase + 32 <= C) {
+                float v[32];
+#pragma unroll
+                for (int j = 0; j < 32; ++j) v[j] = __builtin_nontemporal_load(src + (long long)(cbase + j) * HW);
+#pragma unroll
+                for (int j = 0; j < 32; ++j) {
+                    word |= (v[j] >= 0.0f ? 1u : 0u) << j;
+                    acc += (double)fabsf(v[j]);
+                }
+            } else {
+                for (int j = 0; j < 32 && cbase + j < C; ++j) {
+                    const float v = src[(long long)(cbase + j) * HW];
+                    word |= (v >= 0.0f ? 1u : 0u) << j;
+                    acc += (double)fabsf(v);
+                }
+            }
+            words[lane * Cwp + w] = word;
+        }
+    }
+    part[s * 64 + lane] = acc;
+    __syncthreads();
+    if (s == 0 && p < NP) {
+        double sum = part[lane];
+        for (int k = 1; k < S; ++k) sum += part[k * 64 + lane];
+        A[p] = (float)(sum / (double)C);
+    }
+    const int npx = (int)min((long long)64, NP - p0);
+    const int nwords = npx * Cw;
+    uint32_t *dst = packed + p0 * Cw;
+    for (int i = s * 64 + lane; i < nwords; i += 64 * S) {
+        const int px = i / Cw, w = i - px * Cw;
+        dst[i] = words[px * Cwp + w];
+    }
+}
+
+bool pack_and_mean_supports(int C) { return (C + 31) / 32 <= 512; }
+
+hipError_t launch_pack_and_mean(const float *x, int N, int C, int H, int W, uint32_t *packed,
+                                float *A, hipStream_t st)
+{
+    const int HW = H * W, Cw = (C + 31) / 32, Cwp = Cw | 1;
+    const long long NP = (long long)N * HW;
+    int S = 1;
+    while (S < kMaxSlices && 2 * S <= Cw) S *= 2;
+    const size_t smem = (size_t)S * 64 * sizeof(double) + (size_t)64 * Cwp * sizeof(uint32_t);
+    pack_and_mean_kernel<<<dim3(ceil_div(NP, 64)), dim3(64, S), smem, st>>>(x, NP, C, HW, Cw, Cwp,
+                                                                           packed, A);
+    return hipGetLastError();
+}
+
+// Eq. 5 from per-tap channel means: alpha[f] = mean over the kh*kw taps of M[f][tap], where
+// M = mean_c |Wt| is what pack_and_mean_kernel leaves in its A output when run on the filters.
+__global__ __launch_bounds__(256) void alpha_from_tap_means_kernel(const float *__restrict__ M,
+                                                                   int F, int taps,
+                                                                   float *__restrict__ alpha)
+{
+    const int f = blockIdx.x * 256 + threadIdx.x;
+    if (f >= F) return;
+    double sum = 0.0;
+    for (int t = 0; t < taps; ++t) sum += (double)M[(long long)f * taps + t];
+    alpha[f] = (float)(sum / (double)taps);
+}
+
+hipError_t launch_alpha_from_tap_means(const float *M, int F, int taps, float *alpha, hipStream_t st)
+{
+    alpha_from_tap_means_kernel<<<ceil_div(F, 256), 256, 0, st>>>(M, F, taps, alpha);
+    return hipGetLastError();
+}
+
 // Eq. 10, second half: K = A * k with constant taps 1/(kh*kw), at the convolution's output
 // positions; taps outside the image add nothing.  One thread per output pixel (A is C times smaller
 // than I, so this pass is negligible).

@@ -118,6 +118,48 @@ int xnor_alpha(const float *Wt, int F, int C, int kh, int kw, float *alpha, void
     return hip_status(xnor::launch_alpha(Wt, F, n_red, alpha, (hipStream_t)stream));
 }
 
+int xnor_input_prepare(const float *I, const xnor_shape *s, uint32_t *Ipk, float *A_work, float *K,
+                       void *stream)
+{
+    if (!I || !s || !Ipk || !A_work || !K) return XNOR_E_NULL;
+    xnor::Geom g;
+    const int rc = make_geom(s, &g);
+    if (rc) return rc;
+    if (!aligned(I, 4) || !aligned(Ipk, 4) || !aligned(A_work, 4) || !aligned(K, 4)) return XNOR_E_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e;
+    if (xnor::pack_and_mean_supports(g.C)) {
+        e = xnor::launch_pack_and_mean(I, g.N, g.C, g.H, g.W, Ipk, A_work, st);
+    } else {   // more channel words than one block's LDS holds: two passes
+        e = xnor::launch_binarize_pack(I, g.N, g.C, g.H, g.W, Ipk, st);
+        if (e == hipSuccess) e = xnor::launch_channel_mean_abs(I, g.N, g.C, g.H, g.W, A_work, st);
+    }
+    if (e != hipSuccess) return hip_status(e);
+    return hip_status(xnor::launch_box_filter_K(A_work, g, K, st));
+}
+
+int xnor_filter_prepare(const float *Wt, int F, int C, int kh, int kw, uint32_t *Wpk, float *M_work,
+                        float *alpha, void *stream)
+{
+    if (!Wt || !Wpk || !M_work || !alpha) return XNOR_E_NULL;
+    if (F <= 0 || C <= 0 || kh <= 0 || kw <= 0) return XNOR_E_SHAPE;
+    const long long Cw = ((long long)C + 31) / 32;
+    if ((long long)F * kh * kw > kMaxIndex || (long long)C * kh * kw > kMaxIndex || Cw > 65535 ||
+        (long long)F * kh * kw > kMaxIndex / Cw)
+        return XNOR_E_SHAPE;
+    if (!aligned(Wt, 4) || !aligned(Wpk, 4) || !aligned(M_work, 4) || !aligned(alpha, 4)) return XNOR_E_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e;
+    if (xnor::pack_and_mean_supports(C)) {
+        e = xnor::launch_pack_and_mean(Wt, F, C, kh, kw, Wpk, M_work, st);
+        if (e == hipSuccess) e = xnor::launch_alpha_from_tap_means(M_work, F, kh * kw, alpha, st);
+    } else {
+        e = xnor::launch_binarize_pack(Wt, F, C, kh, kw, Wpk, st);
+        if (e == hipSuccess) e = xnor::launch_alpha(Wt, F, (long long)C * kh * kw, alpha, st);
+    }
+    return hip_status(e);
+}
+
 int xnor_conv2d_pick_algo(const xnor_shape *s, size_t workspace_bytes)
 {
     xnor::Geom g;

@@ -21,6 +21,10 @@ hipError_t launch_binarize_pack(const float *x, int N, int C, int H, int W, uint
                                 hipStream_t st);
 hipError_t launch_channel_mean_abs(const float *I, int N, int C, int H, int W, float *A,
                                    hipStream_t st);
+bool pack_and_mean_supports(int C);
+hipError_t launch_pack_and_mean(const float *x, int N, int C, int H, int W, uint32_t *packed,
+                                float *A, hipStream_t st);
+hipError_t launch_alpha_from_tap_means(const float *M, int F, int taps, float *alpha, hipStream_t st);
 hipError_t launch_box_filter_K(const float *A, const Geom &g, float *K, hipStream_t st);
 hipError_t launch_alpha(const float *Wt, int F, long long n_red, float *alpha, hipStream_t st);
 

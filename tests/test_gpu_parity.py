@@ -81,6 +81,16 @@ def check_all(xb, layer, I, Wt, algo, key):
     assert_rel(alpha.cpu().numpy(), a_ref, "alpha")
     assert np.array_equal(dot.cpu().numpy(), d_ref), "dot"
     assert_rel(out.cpu().numpy(), O_ref, "out")
+    # the one-pass variants of the pre-stages give the same packed words, A, K and alpha
+    Ipk2, K2, A2 = xb.xnor_input_prepare(dev(I), s)
+    Wpk2, alpha2, M2 = xb.xnor_filter_prepare(dev(Wt))
+    torch.cuda.synchronize()
+    assert np.array_equal(words(Ipk2), Ipk_ref), "Ipk (one pass)"
+    assert np.array_equal(words(Wpk2), Wpk_ref), "Wpk (one pass)"
+    assert_rel(A2.cpu().numpy(), A_ref, "A (one pass)")
+    assert_rel(K2.cpu().numpy(), K_ref, "K (one pass)")
+    assert_rel(alpha2.cpu().numpy(), a_ref, "alpha (one pass)")
+    assert_rel(M2.cpu().numpy(), oracle.channel_mean_abs(Wt), "mean_c |Wt| (one pass)")
 
 
 ALGOS = ["direct", "tiled", "mfma", "auto"]   # innermost parameter, so one oracle run serves all four
