@@ -1,0 +1,80 @@
+"""Every benchmark layer at its FULL size, in the launch configuration bench.py times (one-pass
+pre-stages, conv with its workspace, kernel picked automatically).
+
+The oracle cannot run 2.4e11 MACs in a test, so the convolution is checked on sampled (image,
+filter) planes that the oracle computes one by one -- bit-exact dots, fp32 outputs within 1e-5 --
+and, over the whole tensor, through properties that hold at any size: |dot| <= N_valid,
+dot = N_valid (mod 2), out = float(dot) * K * alpha recomputed from the library's own dot, K and
+alpha.  Packed words, A, K and alpha are compared with the oracle in full.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2007_14178_amd.workloads import LAYERS, make_input, make_weights
+
+pytestmark = pytest.mark.gpu
+
+RTOL = 1e-5
+
+
+def rel_ok(got, ref):
+    got = got.astype(np.float64); ref = ref.astype(np.float64)
+    return bool((np.abs(got - ref) <= RTOL * np.abs(ref)).all()) and np.array_equal(got == 0, ref == 0)
+
+
+@pytest.mark.parametrize("name", list(LAYERS))
+def test_full_size_layer(name):
+    from paper_2007_14178_amd import binding as xb
+    L = LAYERS[name]
+    print(f"case layer={name} full size N={L.N}", flush=True)
+    I, Wt = make_input(L), make_weights(L)
+    s = xb.Shape(L.N, L.C, L.H, L.W, L.F, L.kh, L.kw, L.sh, L.sw, L.ph, L.pw)
+    OH, OW = xb.xnor_out_dim(s)
+    dI, dW = torch.from_numpy(I).cuda(), torch.from_numpy(Wt).cuda()
+    Ipk, K, A = xb.xnor_input_prepare(dI, s)
+    Wpk, alpha, _ = xb.xnor_filter_prepare(dW)
+    ws_bytes = xb.xnor_conv2d_workspace_bytes(s)
+    ws = torch.empty((ws_bytes,), dtype=torch.uint8, device="cuda") if ws_bytes else None
+    out, dot = xb.xnor_conv2d_fwd(Ipk, Wpk, K, alpha, s, want_dot=True, workspace=ws)
+    torch.cuda.synchronize()
+
+    # pre-stages, whole tensors
+    assert np.array_equal(Ipk.cpu().numpy().view(np.uint32), oracle.pack(I))
+    assert np.array_equal(Wpk.cpu().numpy().view(np.uint32), oracle.pack(Wt))
+    os_ = oracle.Shape(L.N, L.C, L.H, L.W, L.F, L.kh, L.kw, L.sh, L.sw, L.ph, L.pw)
+    K_ref, a_ref = oracle.scale_K(I, os_), oracle.alpha(Wt)
+    assert rel_ok(A.cpu().numpy(), oracle.channel_mean_abs(I))
+    assert rel_ok(K.cpu().numpy(), K_ref)
+    assert rel_ok(alpha.cpu().numpy(), a_ref)
+
+    # convolution, sampled (image, filter) planes against the oracle
+    rng = np.random.default_rng(1234 + L.config)
+    imgs = sorted({0, L.N - 1, *rng.integers(0, L.N, size=2).tolist()})
+    budget = 4e8                                             # MACs the oracle spends per layer
+    nf = int(max(2, min(L.F, budget / (len(imgs) * L.binary_macs / (L.N * L.F)))))
+    fsel = np.unique(np.concatenate([[0, L.F - 1], rng.integers(0, L.F, size=nf)]))[:max(nf, 2)]
+    sub = oracle.Shape(1, L.C, L.H, L.W, len(fsel), L.kh, L.kw, L.sh, L.sw, L.ph, L.pw)
+    dot_h = dot.cpu().numpy()
+    out_h = out.cpu().numpy()
+    for n in imgs:
+        d_ref = oracle.dot(I[n:n + 1], Wt[fsel], sub)
+        assert np.array_equal(dot_h[n, fsel], d_ref[0]), f"dot image {n}"
+        O_ref = oracle.out(d_ref, K_ref[n:n + 1], a_ref[fsel])
+        assert rel_ok(out_h[n, fsel], O_ref[0]), f"out image {n}"
+
+    # convolution, whole tensor: properties
+    vy = np.array([sum(0 <= oy * L.sh - L.ph + ky < L.H for ky in range(L.kh)) for oy in range(OH)])
+    vx = np.array([sum(0 <= ox * L.sw - L.pw + kx < L.W for kx in range(L.kw)) for ox in range(OW)])
+    n_valid = torch.from_numpy((L.C * vy[:, None] * vx[None, :]).astype(np.int32)).cuda()
+    assert bool((dot.abs() <= n_valid).all())
+    assert bool((((dot - n_valid) & 1) == 0).all())
+    recomputed = dot.to(torch.float32) * (K[:, None] * alpha[None, :, None, None])
+    assert torch.equal(out, recomputed)
+    # a sign dot product of N(0,1)-like data is centred with variance close to N_valid
+    interior = dot[:, :, OH // 2, OW // 2].to(torch.float64)
+    count = interior.numel()
+    assert abs(float(interior.mean())) < 5 * (L.n_red / count) ** 0.5
+    if count >= 4096:
+        assert 0.8 < float(interior.var()) / L.n_red < 1.25
