@@ -28,6 +28,7 @@ PEAK_HBM_GBS = 8000.0
 # v_xor_b32 + v_bcnt_u32_b32 retire 32 binary MACs per lane: 256 CU x 4 SIMD x 16 lanes x 2.4 GHz
 # = 3.93e13 lane-ops/s -> 6.29e14 binary MAC/s -> 1258 T binary op/s counting 2 ops per MAC.
 PEAK_VALU_POPCOUNT_TOPS = 256 * 4 * 16 * 2.4e9 / 2 * 32 * 2 / 1e12
+MEASURED_CONV_TRAFFIC_BYTES = {("c5", "mfma"): 61.8e6 + 257.6e6}
 
 
 def parse():
@@ -39,6 +40,9 @@ def parse():
     ap.add_argument("--algo", default="auto", choices=["auto", "direct", "tiled", "mfma"])
     ap.add_argument("--unfused", action="store_true", help="run the four pre-stage calls separately")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run three plain 1 GiB device copies before the timed loop (calibrates the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run against known traffic)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
 
@@ -126,6 +130,14 @@ def main():
         if events is not None:
             events.append(marks)
 
+    if args.copy_probe:
+        src = torch.empty((1 << 28,), dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)                     # 1 GiB read + 1 GiB written per copy
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -149,7 +161,10 @@ def main():
     else:
         roof = {"bound": "alu", "achieved": achieved, "peak": PEAK_VALU_POPCOUNT_TOPS, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    # HBM bytes per conv launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (scaled by a
+    # plain 1 GiB copy): measured offline, see profiles/forward_c5_hbm_traffic_pmc.md; other
+    # workloads / kernels have no counter run yet
+    roof["traffic"] = MEASURED_CONV_TRAFFIC_BYTES.get((layer.name, xb.ALGO_NAMES[used_algo]))
     roof["kernel"] = f"xnor_conv2d_fwd[{xb.ALGO_NAMES[used_algo]}]"
     roof["kernel_ms"] = conv_ms
     roof["binary_gmacs"] = macs / (conv_ms * 1e-3) / 1e9
