@@ -64,8 +64,11 @@ struct MfmaParams {
     int CH;          // packed words per LDS channel chunk (even)
     int nchunks;
     int pitch16;     // LDS slot pitch in 16-byte units (CH + 1, odd)
-    int chunk_steps; // k-steps the workspace holds per (filter tile, chunk): taps*CH/2 rounded up to
-                     // the ring depth, plus one ring of zero steps for the prefetch overrun
+    int buf16;       // distance between the two LDS chunk buffers in 16-byte units (0: one buffer)
+    int tab16;       // start of the two per-chunk step-offset tables in LDS (16-byte units)
+    int tab_len;     // uint32 entries per table (a multiple of 4)
+    int tile_steps;  // k-steps the workspace holds per filter tile: every chunk padded to a whole
+                     // number of rings, plus one ring of zero steps for the prefetch overrun
     FastDiv dCHV, dWp, dRH;
 };
 
@@ -97,32 +100,36 @@ __device__ inline uint4 expand_word(uint32_t w, int nvalid)
     return e;
 }
 
-// Filter words -> FP4 in A-operand order: Wx[tile32][chunk][step][lane] (one uint4 per lane).
-// Within a chunk the steps run tap-major: step = tap * steps_c + s, packed word = chunk*CH + 2*s +
-// lane/32, filter = 32*tile32 + lane%32; so the MFMA loop walks the workspace linearly.  Steps past
-// taps*steps_c (padding up to chunk_steps), filters >= F, words >= Cw and channels >= C are zeros.
+// Filter words -> FP4 in A-operand order: Wx[tile32][step][lane] (one uint4 per lane).  The steps
+// of a tile run chunk-major, then tap-major, each chunk padded with zero steps to a whole number of
+// register rings: step = chunk*chunk_pad + tap*steps_c + s, packed word = chunk*CH + 2*s + lane/32,
+// filter = 32*tile32 + lane%32 -- exactly the order in which the MFMA loop consumes them, so it
+// walks the workspace linearly.  Padding steps, filters >= F, words >= Cw and channels >= C are zeros.
 __global__ __launch_bounds__(256) void expand_filters_kernel(const uint32_t *__restrict__ Wpk,
                                                              uint4 *__restrict__ Wx, int F, int C,
                                                              int Cw, int taps, int CH, int nchunks,
-                                                             int chunk_steps, int Cw2, long long total)
+                                                             int chunk_pad, int tile_steps, int Cw2,
+                                                             long long total)
 {
     const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
     if (i >= total) return;
     const int lane = (int)(i & 63);
-    long long t = i >> 6;
-    const int step = (int)(t % chunk_steps);
-    t /= chunk_steps;
-    const int chunk = (int)(t % nchunks);
-    const int tile = (int)(t / nchunks);
-    const int steps_c = min(CH, Cw2 - chunk * CH) >> 1;
+    const long long t = i >> 6;
+    const int step = (int)(t % tile_steps);
+    const int tile = (int)(t / tile_steps);
+    const int chunk = step / chunk_pad;
     uint4 e = make_uint4(0, 0, 0, 0);
-    if (step < taps * steps_c) {
-        const int tap = step / steps_c, s = step - tap * steps_c;
-        const int f = tile * 32 + (lane & 31);
-        const int w = chunk * CH + 2 * s + (lane >> 5);
-        if (f < F && w < Cw) {
-            const int nvalid = min(32, C - 32 * w);
-            e = expand_word(Wpk[((long long)f * taps + tap) * Cw + w], nvalid);
+    if (chunk < nchunks) {
+        const int rem = step - chunk * chunk_pad;
+        const int steps_c = min(CH, Cw2 - chunk * CH) >> 1;
+        if (rem < taps * steps_c) {
+            const int tap = rem / steps_c, s = rem - tap * steps_c;
+            const int f = tile * 32 + (lane & 31);
+            const int w = chunk * CH + 2 * s + (lane >> 5);
+            if (f < F && w < Cw) {
+                const int nvalid = min(32, C - 32 * w);
+                e = expand_word(Wpk[((long long)f * taps + tap) * Cw + w], nvalid);
+            }
         }
     }
     Wx[i] = e;
@@ -137,79 +144,13 @@ struct WordVec<2> { typedef uint2 type; };
 template <>
 struct WordVec<4> { typedef uint4 type; };
 
-// One LDS channel chunk: for every tap and every 64-channel step, NTW pixel tiles x kWM filter
-// tiles of MFMAs.  The loop body has no branches: the filter operands are read linearly from the
-// workspace through a register ring (loads run kRing-1 steps ahead; the workspace is zero-padded to
-// a whole number of rings plus one), the pixel operands come from LDS one step ahead, and the
-// (tap, step) cursor of the pixel operand advances with selects.
-template <int NTW>
-__device__ __forceinline__ void contract_chunk(const MfmaParams &p, const uint4 *lds,
-                                               const uint4 *const (&Achunk)[kWM],
-                                               const uint32_t (&baseB)[kWN], v16f (&acc)[kWM][kWN],
-                                               int steps)
-{
-    constexpr int D = kRing;
-    static_assert(D % 2 == 0, "the unrolled body alternates two pixel-operand buffers");
-    const int T = p.kh * p.kw * steps;
-
-    int l_off = 0;
-    uint4 abuf[D][kWM];
-    auto load_a = [&](uint4 (&dst)[kWM]) {
-#pragma unroll
-        for (int i = 0; i < kWM; ++i) dst[i] = Achunk[i][l_off];
-        l_off += 64;
-    };
-#pragma unroll
-    for (int u = 0; u < D - 1; ++u) load_a(abuf[u]);
-
-    // pixel-operand cursor: offset of (tap, step) from the lane's slot, in 16-byte units; past the
-    // last tap it parks on tap 0 (those steps multiply zero filter operands)
-    int b_s = 0, b_kx = 0, b_ky = 0;
-    uint32_t b_off = 0;
-    uint4 bbuf[2][NTW];
-    auto load_b = [&](uint4 (&dst)[NTW]) {
-#pragma unroll
-        for (int j = 0; j < NTW; ++j) dst[j] = lds[baseB[j] + b_off];
-        ++b_s;
-        const bool wrap_s = b_s == steps;
-        b_s = wrap_s ? 0 : b_s;
-        b_kx += wrap_s ? 1 : 0;
-        const bool wrap_x = b_kx == p.kw;
-        b_kx = wrap_x ? 0 : b_kx;
-        b_ky += wrap_x ? 1 : 0;
-        const uint32_t tap_off = b_ky < p.kh ? (uint32_t)((b_ky * p.Wp + b_kx) * p.pitch16) : 0u;
-        b_off = wrap_s ? tap_off : b_off + 2;
-    };
-    load_b(bbuf[0]);
-
-    for (int t = 0; t < T; t += D) {
-#pragma unroll
-        for (int u = 0; u < D; ++u) {
-            load_a(abuf[(u + D - 1) % D]);
-            load_b(bbuf[(u + 1) % 2]);
-#pragma unroll
-            for (int i = 0; i < kWM; ++i) {
-                const uint4 va = abuf[u][i];
-                const v8i a = v8i{(int)va.x, (int)va.y, (int)va.z, (int)va.w, 0, 0, 0, 0};
-#pragma unroll
-                for (int j = 0; j < NTW; ++j) {
-                    const uint4 vb = bbuf[u % 2][j];
-                    const v8i b = v8i{(int)vb.x, (int)vb.y, (int)vb.z, (int)vb.w, 0, 0, 0, 0};
-                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                        a, b, acc[i][j], 4, 4, 0, kScaleOne, 0, kScaleOne);
-                }
-            }
-            // Pin the accumulators between steps (an empty volatile asm that "modifies" them):
-            // left free, the compiler interleaves the MFMAs of all unrolled steps and runs out of
-            // registers for the operands it then has to keep alive.
-#pragma unroll
-            for (int i = 0; i < kWM; ++i)
-#pragma unroll
-                for (int j = 0; j < NTW; ++j) asm volatile("" : "+v"(acc[i][j]));
-        }
-    }
-}
-
+// The kernel.  Per workgroup: the band's input words are expanded to FP4 into LDS one channel
+// chunk at a time, double-buffered: while the MFMA loop runs on chunk c, the words of chunk c+1
+// are fetched (at the chunk's start) and expanded into the other buffer (half-way through), so
+// that only chunk 0 is staged with the matrix cores idle.  The MFMA loop is one flat loop over
+// all (chunk, tap, 64-channel step) of the tile; the filter operands stream linearly from the
+// workspace through a register ring that runs kRing-1 steps ahead across chunk boundaries; the
+// pixel operands come from LDS one step ahead.
 template <int VW>
 __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
 {
@@ -251,11 +192,11 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
         baseB[j] = (uint32_t)((srow * p.Wp + ox * p.sw) * p.pitch16 + kg);
     }
 
-    const uint4 *Aptr[kWM];   // this lane's filter operands, chunk 0, step 0
+    const uint4 *Aptr[kWM];   // this lane's filter operands, step 0 of the tile
 #pragma unroll
     for (int i = 0; i < kWM; ++i) {
         const int tile = blockIdx.y * (2 * kWM) + wm * kWM + i;
-        Aptr[i] = p.Wx + ((long long)tile * p.nchunks * p.chunk_steps) * 64 + lane;
+        Aptr[i] = p.Wx + ((long long)tile * p.tile_steps) * 64 + lane;
     }
 
     v16f acc[kWM][kWN];
@@ -266,74 +207,205 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
+    // ---- staging: packed input words of the band's rows -> FP4 in LDS, zeros outside the image ----
+    typedef typename WordVec<VW>::type wvec;
     const int CHV = p.CH / VW;
-    const int items = nslots * CHV;
+    const int items = nslots * CHV;          // one item = VW consecutive words of one slot
     const int Cw2 = 2 * p.S2;
+    constexpr int UP = 2;                    // items per thread fetched ahead into registers
+    wvec sv[UP];
+    int sdst[UP];                            // LDS index inside a buffer, or -1
+    bool slive[UP];
+
+    // where item `it` of chunk `c` comes from and goes to
+    auto locate = [&](int it, int c, int &dst, bool &live) -> const uint32_t * {
+        const bool in_range = it < items;
+        const uint32_t itc = in_range ? (uint32_t)it : 0u;
+        const uint32_t slot = fdiv(itc, p.dCHV);
+        const int wq = (int)(itc - slot * CHV);
+        const uint32_t rowg = fdiv(slot, p.dWp);
+        const int col = (int)(slot - rowg * p.Wp);
+        int n, iy;
+        if ((int)rowg < r0) {
+            n = n_first;
+            iy = oy0 * p.sh - p.ph + (int)rowg;
+        } else {
+            const uint32_t tt = rowg - (uint32_t)r0;
+            const uint32_t sg = fdiv(tt, p.dRH);
+            n = n_first + 1 + (int)sg;
+            iy = (int)(tt - sg * p.RHfull) - p.ph;
+        }
+        const int ix = col - p.pw;
+        const int w = c * p.CH + wq * VW;
+        live = in_range && n < p.N && iy >= 0 && iy < p.H && ix >= 0 && ix < p.W && w < p.Cw;
+        dst = in_range ? (int)(slot * p.pitch16 + wq * VW) : -1;
+        return p.Ipk + (((long long)n * p.H + iy) * p.W + ix) * p.Cw + w;
+    };
+    // outside the image (or past the last channel word) the FP4 image is 0.0, not -1.0
+    auto put = [&](uint4 *buf, int dst, bool live, const wvec &v) {
+        if (dst < 0) return;
+        uint32_t words[VW];
+        if constexpr (VW == 1) { words[0] = v; }
+        if constexpr (VW == 2) { words[0] = v.x; words[1] = v.y; }
+        if constexpr (VW == 4) { words[0] = v.x; words[1] = v.y; words[2] = v.z; words[3] = v.w; }
+#pragma unroll
+        for (int k = 0; k < VW; ++k)
+            buf[dst + k] = live ? expand_word(words[k], 32) : make_uint4(0, 0, 0, 0);
+    };
+    // The first UP items of a thread are the same slots in every chunk: locate them once; a chunk
+    // only shifts the source by its first word.
+    const uint32_t *ssrc[UP];    // source of the item in chunk 0
+    int sw0[UP];                 // first word of the item inside a chunk
+    bool sin[UP];                // the slot is inside an image
+#pragma unroll
+    for (int u = 0; u < UP; ++u) {
+        bool live0;
+        ssrc[u] = locate(u * 256 + tid, 0, sdst[u], live0);
+        const int it = u * 256 + tid;
+        sw0[u] = it < items ? (int)(((uint32_t)it - fdiv((uint32_t)it, p.dCHV) * CHV) * VW) : 0;
+        sin[u] = live0;   // (a word past Cw in chunk 0 is past Cw in every chunk)
+    }
+    auto stage_issue = [&](int c) {
+#pragma unroll
+        for (int u = 0; u < UP; ++u) {
+            slive[u] = sin[u] && (c * p.CH + sw0[u] < p.Cw);
+            wvec z = {};
+            sv[u] = z;
+            if (slive[u]) sv[u] = *reinterpret_cast<const wvec *>(ssrc[u] + c * p.CH);
+        }
+    };
+    // The pixel operand of step t of a chunk sits at (buffer, tap(t), step-in-tap(t)) from the lane's
+    // slot.  That offset is the same for every lane, so it is tabulated once per chunk in LDS
+    // (entry t, in 16-byte units) instead of being tracked with scalar arithmetic in the MFMA loop;
+    // entries of the zero-padded steps and of the prefetch overrun point at tap 0.
+    uint32_t *const tables = reinterpret_cast<uint32_t *>(lds + p.tab16);
+    auto write_table = [&](int c) {
+        const int steps_c = min(p.CH, Cw2 - c * p.CH) >> 1;
+        const int real = p.kh * p.kw * steps_c;
+        uint32_t *tab = tables + (c & 1) * p.tab_len;
+        const uint32_t base = (uint32_t)((c & 1) * p.buf16);
+        for (int tt = tid; tt < p.tab_len; tt += 256) {
+            uint32_t off = base;
+            if (tt < real) {
+                const int tap = tt / steps_c, s = tt - tap * steps_c;
+                const int ky = tap / p.kw, kx = tap - ky * p.kw;
+                off = base + (uint32_t)((ky * p.Wp + kx) * p.pitch16 + 2 * s);
+            }
+            tab[tt] = off;
+        }
+    };
+    auto stage_commit = [&](int c, uint4 *buf) {
+#pragma unroll
+        for (int u = 0; u < UP; ++u) put(buf, sdst[u], slive[u], sv[u]);
+        for (int it = UP * 256 + tid; it < items; it += 256) {   // bands with more items: fetched here
+            int dst;
+            bool live;
+            const uint32_t *src = locate(it, c, dst, live);
+            wvec z = {};
+            wvec v = z;
+            if (live) v = *reinterpret_cast<const wvec *>(src);
+            put(buf, dst, live, v);
+        }
+        write_table(c);
+    };
+    stage_issue(0);
+    stage_commit(0, lds);
+    __syncthreads();
+
+    // ---- contract ----
+    constexpr int D = kRing;
+    static_assert(D % 2 == 0, "the unrolled body alternates two pixel-operand buffers");
+    const int taps = p.kh * p.kw;
+
+    int l_off = 0;
+    uint4 abuf[D][kWM];
+    auto load_a = [&](uint4 (&dst)[kWM]) {
+#pragma unroll
+        for (int i = 0; i < kWM; ++i) dst[i] = Aptr[i][l_off];
+        l_off += 64;
+    };
+#pragma unroll
+    for (int u = 0; u < D - 1; ++u) load_a(abuf[u]);
 
     for (int c = 0; c < p.nchunks; ++c) {
-        const int w_base = c * p.CH;
-        const int steps = min(p.CH, Cw2 - w_base) >> 1;
-        if (c > 0) __syncthreads();   // everyone is done reading the previous chunk
+        const int steps = min(p.CH, Cw2 - c * p.CH) >> 1;   // 64-channel steps per tap in this chunk
+        const int Tp = (taps * steps + D - 1) / D * D;       // steps incl. the zero padding of the workspace
+        const bool more = c + 1 < p.nchunks;
+        if (more) stage_issue(c + 1);                        // fetch the next chunk's words now ...
+        bool committed = !more;
 
-        // ---- stage: packed input words of the band's rows -> FP4 in LDS, zeros outside the image ----
-        constexpr int U = 4;
-        for (int base = 0; base < items; base += 256 * U) {
-            typename WordVec<VW>::type v[U];
-            int dst[U];
-            bool live[U];
+        // pixel operands: offsets come from the chunk's table, read two steps ahead of the operands
+        // they address (which are themselves read one step ahead of their MFMAs)
+        const uint32_t *tab = tables + (c & 1) * p.tab_len;
+        uint4 bbuf[2][kWN];
+        uint32_t boff[2];
+        int t_next = 0;                                       // step whose operands are loaded next
+        auto load_b = [&](uint4 (&dst)[kWN], uint32_t &off) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int it = base + u * 256 + tid;
-                const bool in_range = it < items;
-                const uint32_t itc = in_range ? (uint32_t)it : 0u;
-                const uint32_t slot = fdiv(itc, p.dCHV);
-                const int wq = (int)(itc - slot * CHV);
-                const uint32_t rowg = fdiv(slot, p.dWp);
-                const int col = (int)(slot - rowg * p.Wp);
-                int n, iy;
-                if ((int)rowg < r0) {
-                    n = n_first;
-                    iy = oy0 * p.sh - p.ph + (int)rowg;
-                } else {
-                    const uint32_t t = rowg - (uint32_t)r0;
-                    const uint32_t sg = fdiv(t, p.dRH);
-                    n = n_first + 1 + (int)sg;
-                    iy = (int)(t - sg * p.RHfull) - p.ph;
+            for (int j = 0; j < kWN; ++j) dst[j] = lds[baseB[j] + off];
+            off = tab[t_next + 2];
+            ++t_next;
+        };
+        boff[0] = tab[0];
+        boff[1] = tab[1];
+        load_b(bbuf[0], boff[0]);
+
+        for (int g = 0; g < Tp; g += D) {
+#pragma unroll
+            for (int u = 0; u < D; ++u) {
+                // one step, no branches: next filter operands (ring), next pixel operands, 8 MFMAs
+                load_a(abuf[(u + D - 1) % D]);
+                load_b(bbuf[(u + 1) % 2], boff[(u + 1) % 2]);
+#pragma unroll
+                for (int i = 0; i < kWM; ++i) {
+                    const uint4 va = abuf[u][i];
+                    const v8i a = v8i{(int)va.x, (int)va.y, (int)va.z, (int)va.w, 0, 0, 0, 0};
+#pragma unroll
+                    for (int j = 0; j < kWN; ++j) {
+                        const uint4 vb = bbuf[u % 2][j];
+                        const v8i b = v8i{(int)vb.x, (int)vb.y, (int)vb.z, (int)vb.w, 0, 0, 0, 0};
+                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                            a, b, acc[i][j], 4, 4, 0, kScaleOne, 0, kScaleOne);
+                    }
                 }
-                const int ix = col - p.pw;
-                const int w = w_base + wq * VW;
-                live[u] = in_range && n < p.N && iy >= 0 && iy < p.H && ix >= 0 && ix < p.W && w < p.Cw;
-                dst[u] = in_range ? (int)(slot * p.pitch16 + wq * VW) : -1;
-                typename WordVec<VW>::type z = {};
-                v[u] = z;
-                if (live[u])
-                    v[u] = *reinterpret_cast<const typename WordVec<VW>::type *>(
-                        p.Ipk + (((long long)n * p.H + iy) * p.W + ix) * p.Cw + w);
+                // A lone wave issues in order: scalar and memory instructions placed in front of the
+                // MFMA block would leave the matrix pipe idle while they issue.  Ask for them to be
+                // spread between the MFMAs instead (mask 8 = MFMA, 0x100 = LDS read, 0x20 = VMEM
+                // read, 4 = SALU, 2 = VALU).
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x004, 4, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x004, 4, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x004, 4, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x004, 4, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x004, 4, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                // Pin the accumulators between steps (an empty volatile asm that "modifies" them):
+                // left free, the compiler interleaves the MFMAs of all unrolled steps and runs out
+                // of registers for the operands it then has to keep alive.
+#pragma unroll
+                for (int i = 0; i < kWM; ++i)
+#pragma unroll
+                    for (int j = 0; j < kWN; ++j) asm volatile("" : "+v"(acc[i][j]));
             }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (dst[u] < 0) continue;
-                // outside the image (or past the last channel word) the FP4 image is 0.0, not -1.0
-                uint32_t words[VW];
-                if constexpr (VW == 1) { words[0] = v[u]; }
-                if constexpr (VW == 2) { words[0] = v[u].x; words[1] = v[u].y; }
-                if constexpr (VW == 4) { words[0] = v[u].x; words[1] = v[u].y; words[2] = v[u].z; words[3] = v[u].w; }
-#pragma unroll
-                for (int k = 0; k < VW; ++k)
-                    lds[dst[u] + k] = live[u] ? expand_word(words[k], 32) : make_uint4(0, 0, 0, 0);
+            // ... and expand them into the other buffer half-way through this chunk
+            if (!committed && 2 * (g + D) >= Tp) {
+                stage_commit(c + 1, lds + ((c + 1) & 1) * p.buf16);
+                committed = true;
             }
         }
-        __syncthreads();
-
-        // ---- contract: taps x 64-channel steps ----
-        // every wave with work runs all kWN tiles; tiles past the band's end read slot 0 and are
-        // never stored (one code path keeps the accumulators out of scratch)
-        if (my_nt > 0) {
-            const uint4 *Achunk[kWM];
-#pragma unroll
-            for (int i = 0; i < kWM; ++i) Achunk[i] = Aptr[i] + (long long)c * p.chunk_steps * 64;
-            contract_chunk<kWN>(p, lds, Achunk, baseB, acc, steps);
-        }
+        if (more) __syncthreads();   // chunk c+1 is complete in its buffer; chunk c's buffer is free
     }
 
     // ---- step 3: out = float(dot) * K * alpha ----
@@ -350,23 +422,38 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
     const int p4 = (lane & 7) * 4;      // first of this lane's four pixels within a tile
     const int fl = lane >> 3;           // filter within a tile, plus 8*k
     if (my_nt > 0) {
+        // the lane's pixel quads (one per tile): position, validity, contiguity; K and alpha are
+        // fetched for all tiles first so that no load latency sits inside the store loop
+        int nvq[kWN];
+        bool quadq[kWN];
+        long long kbaseq[kWN], obaseq[kWN];
+        float kq[kWN][4], al[kWM][4];
 #pragma unroll
         for (int j = 0; j < kWN; ++j) {
-            if (j >= my_nt) break;
-            // the lane's pixel quad: position, validity, contiguity
             const int q0 = (tile0 + j) * 32 + p4;
-            const int nv = min(4, npix - q0);                 // valid pixels of the quad (may be <= 0)
-            const int qc = nv > 0 ? q0 : 0;
+            nvq[j] = j < my_nt ? min(4, npix - q0) : 0;       // valid pixels of the quad (may be <= 0)
+            const int qc = nvq[j] > 0 ? q0 : 0;
             const int Rl = qc / p.OW, ox = qc - Rl * p.OW;
             const int R = R0 + Rl;
             const int n = R / p.OH, oy = R - n * p.OH;
             const int po = oy * p.OW + ox;                    // offset inside the (n, f) plane
-            const bool quad = nv == 4 && po + 3 < OHW;        // four pixels of one image: one 16-byte run
-            const long long kbase = (long long)R * p.OW + ox; // K is dense over (n, oy, ox)
-            float kq[4];
+            quadq[j] = nvq[j] == 4 && po + 3 < OHW;           // four pixels of one image: one 16-byte run
+            kbaseq[j] = (long long)R * p.OW + ox;             // K is dense over (n, oy, ox)
+            obaseq[j] = (long long)n * p.F * OHW + po;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) kq[e] = e < nv ? Kp[kbase + e] : 0.0f;
-            const long long obase = (long long)n * p.F * OHW + po;
+            for (int e = 0; e < 4; ++e) kq[j][e] = e < nvq[j] ? Kp[kbaseq[j] + e] : 0.0f;
+        }
+#pragma unroll
+        for (int i = 0; i < kWM; ++i)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int f = (blockIdx.y * (2 * kWM) + wm * kWM + i) * 32 + fl + 8 * k;
+                al[i][k] = f < p.F ? alphap[f] : 0.0f;
+            }
+#pragma unroll
+        for (int j = 0; j < kWN; ++j) {
+            if (j >= my_nt) break;
+            const int nv = nvq[j];
 #pragma unroll
             for (int i = 0; i < kWM; ++i) {
                 const int f_tile = (blockIdx.y * (2 * kWM) + wm * kWM + i) * 32;
@@ -378,21 +465,22 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
                     const int f = f_tile + fl + 8 * k;
                     const float4 d = *reinterpret_cast<const float4 *>(&patch[(fl + 8 * k) * kPatchPitch + p4]);
                     if (f >= p.F || nv <= 0) continue;
-                    const float al = alphap[f];
-                    const long long o = obase + (long long)f * OHW;
+                    const float a = al[i][k];
+                    const long long o = obaseq[j] + (long long)f * OHW;
                     const float dd[4] = {d.x, d.y, d.z, d.w};
-                    if (quad) {
-                        *reinterpret_cast<float4 *>(outp + o) =
-                            make_float4(d.x * (kq[0] * al), d.y * (kq[1] * al), d.z * (kq[2] * al), d.w * (kq[3] * al));
+                    if (quadq[j]) {
+                        *reinterpret_cast<float4 *>(outp + o) = make_float4(
+                            d.x * (kq[j][0] * a), d.y * (kq[j][1] * a), d.z * (kq[j][2] * a), d.w * (kq[j][3] * a));
                         if (dotp)
                             *reinterpret_cast<int4 *>(dotp + o) = make_int4((int)d.x, (int)d.y, (int)d.z, (int)d.w);
                     } else {
                         // quad cut by the band's end or by an image boundary: pixel by pixel
                         for (int e = 0; e < nv; ++e) {
-                            const int Re = (int)((kbase + e) / p.OW), oxe = (int)((kbase + e) - (long long)Re * p.OW);
+                            const int Re = (int)((kbaseq[j] + e) / p.OW);
+                            const int oxe = (int)((kbaseq[j] + e) - (long long)Re * p.OW);
                             const int ne = Re / p.OH, oye = Re - ne * p.OH;
                             const long long oe = ((long long)ne * p.F + f) * OHW + oye * p.OW + oxe;
-                            outp[oe] = dd[e] * (kq[e] * al);
+                            outp[oe] = dd[e] * (kq[j][e] * a);
                             if (dotp) dotp[oe] = (int32_t)dd[e];
                         }
                     }
@@ -405,7 +493,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
 // Tiling chosen on the host for one layer.
 struct MfmaPlan {
     bool ok;
-    int TH, Wp, RHfull, S2, CH, nchunks, pitch16, slots_max, vw, chunk_steps;
+    int TH, Wp, RHfull, S2, CH, nchunks, pitch16, buf16, tab16, tab_len, slots_max, vw, chunk_pad, tile_steps;
     size_t lds_bytes, ws_bytes;
     int f_tiles;   // workgroup rows of kFilterTile filters
 };
@@ -439,15 +527,26 @@ MfmaPlan make_plan(const Geom &g, const void *Ipk)
     const long long slots = max_rows * wp;
     if (slots > (1 << 16)) return pl;
     pl.slots_max = (int)slots;
-    // fewest channel chunks whose staged band fits the LDS budget (two workgroups per CU if possible)
+    // Channel chunks: one chunk in one LDS buffer if the whole band fits, else the fewest chunks
+    // whose two buffers (double buffering) fit; first within the budget that lets two workgroups
+    // share a CU, then within all of LDS.  A chunk must span a few rings of steps so that the
+    // "fetch next chunk / expand next chunk" hand-offs inside the MFMA loop stay in order.
+    const int taps = g.kh * g.kw;
     auto fit = [&](size_t budget) -> bool {
         for (int nch = 1; nch <= pl.S2; ++nch) {
             const int CH = 2 * ((pl.S2 + nch - 1) / nch);
-            const size_t bytes = (size_t)slots * (CH + 1) * 16;
+            const int nchunks = (Cw2 + CH - 1) / CH;
+            const size_t one = (size_t)slots * (CH + 1) * 16;
+            const int tab_len = ((taps * (CH / 2) + kRing - 1) / kRing * kRing + kRing + 3) & ~3;
+            const size_t data = nchunks > 1 ? 2 * one : one;
+            const size_t bytes = data + 2 * (size_t)tab_len * sizeof(uint32_t);
             if (bytes <= budget) {
                 pl.CH = CH;
-                pl.nchunks = (Cw2 + CH - 1) / CH;
+                pl.nchunks = nchunks;
                 pl.pitch16 = CH + 1;
+                pl.buf16 = nchunks > 1 ? (int)(one / 16) : 0;
+                pl.tab16 = (int)(data / 16);
+                pl.tab_len = tab_len;
                 pl.lds_bytes = bytes;
                 return true;
             }
@@ -461,8 +560,9 @@ MfmaPlan make_plan(const Geom &g, const void *Ipk)
     pl.vw = (g.Cw % 4 == 0 && pl.CH % 4 == 0 && (ip & 15) == 0) ? 4
           : (g.Cw % 2 == 0 && (ip & 7) == 0)                    ? 2 : 1;
     pl.f_tiles = ceil_div(g.F, kFilterTile);
-    pl.chunk_steps = (g.kh * g.kw * (pl.CH / 2) + kRing - 1) / kRing * kRing + kRing;
-    pl.ws_bytes = (size_t)pl.f_tiles * (kFilterTile / 32) * pl.nchunks * pl.chunk_steps * 64 * sizeof(uint4);
+    pl.chunk_pad = (taps * (pl.CH / 2) + kRing - 1) / kRing * kRing;
+    pl.tile_steps = pl.nchunks * pl.chunk_pad + kRing;
+    pl.ws_bytes = (size_t)pl.f_tiles * (kFilterTile / 32) * pl.tile_steps * 64 * sizeof(uint4);
     if (ceil_div(total_rows, pl.TH) > 0x7fffffffLL || pl.f_tiles > 65535) return pl;
     pl.ok = true;
     return pl;
@@ -493,7 +593,8 @@ hipError_t launch_conv_mfma(const uint32_t *Ipk, const uint32_t *Wpk, const floa
     uint4 *Wx = static_cast<uint4 *>(workspace);
     const long long wx_items = (long long)(pl.ws_bytes / sizeof(uint4));
     expand_filters_kernel<<<ceil_div(wx_items, 256), 256, 0, st>>>(
-        Wpk, Wx, g.F, g.C, g.Cw, taps, pl.CH, pl.nchunks, pl.chunk_steps, 2 * pl.S2, wx_items);
+        Wpk, Wx, g.F, g.C, g.Cw, taps, pl.CH, pl.nchunks, pl.chunk_pad, pl.tile_steps, 2 * pl.S2,
+        wx_items);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
@@ -505,7 +606,10 @@ hipError_t launch_conv_mfma(const uint32_t *Ipk, const uint32_t *Wpk, const floa
     p.total_rows = g.N * g.OH;
     p.Wp = pl.Wp; p.RHfull = pl.RHfull; p.S2 = pl.S2; p.CH = pl.CH; p.nchunks = pl.nchunks;
     p.pitch16 = pl.pitch16;
-    p.chunk_steps = pl.chunk_steps;
+    p.buf16 = pl.buf16;
+    p.tab16 = pl.tab16;
+    p.tab_len = pl.tab_len;
+    p.tile_steps = pl.tile_steps;
     p.dCHV = make_fastdiv(pl.CH / pl.vw);
     p.dWp = make_fastdiv(pl.Wp);
     p.dRH = make_fastdiv(pl.RHfull);
