@@ -1,6 +1,247 @@
+// XNOR + popcount convolution on the vector ALU (Sec. III-A steps 1b-1d and 3, Eq. 11), tiled.
+//
+// Two lane-ops retire 32 binary MACs: v_xor_b32 with the filter word as a wave-uniform SGPR operand,
+// then v_bcnt_u32_b32, which adds the popcount into its accumulator.  Everything else is arranged so
+// that little more than those two instructions issues in the inner loop:
+//   * a workgroup stages the packed words of a 2-D input tile (with halo) once in LDS, zero outside
+//     the image, and walks over 4 waves x Q filters per pass with that tile resident;
+//   * a lane owns P output pixels and Q filter accumulators per pass (P*Q independent v_bcnt chains);
+//     each LDS read of 4 channel words feeds 4*Q xor/bcnt pairs;
+//   * filter words are fetched with scalar loads (one s_load_dwordx4 per filter and word quad).
+// Zero padding: a zero-filled halo word makes popcount(0 xor w) = popcount(w) instead of nothing, so
+// border pixels subtract the popcounts of the filter words of their out-of-image taps afterwards
+// (a table of per-(filter, tap) popcounts, built only by tiles that touch the border).  Then
+//   dot = C * (#in-image taps) - 2 * popcount,   out = float(dot) * K * alpha.
+// The paper's kernel keeps one channel's 8x4 spatial tile per register and masks all but kh*kw
+// bits of every popcount; here every bit of every word is a channel of the contraction.
+#include <algorithm>
+
 #include "xnor_internal.hpp"
+
 namespace xnor {
-bool conv_tiled_supports(const Geom &) { return false; }
-hipError_t launch_conv_tiled(const uint32_t *, const uint32_t *, const float *, const float *,
-                             const Geom &, float *, int32_t *, hipStream_t) { return hipErrorNotSupported; }
+namespace {
+
+constexpr int kP = 4;             // pixels per lane
+constexpr int kQ = 8;             // filters per wave and pass
+constexpr int kTilePixels = 64 * kP;
+constexpr int kPassFilters = 4 * kQ;
+constexpr size_t kLdsBudget = 64 * 1024;
+
+struct TiledParams {
+    int N, C, H, W, F, kh, kw, sh, sw, ph, pw, OH, OW, Cw;
+    int TH, TW;          // output tile
+    int RH, RW;          // staged input rows / columns = (T-1)*stride + k
+    int tiles_x, tiles_y;
+    int pitch;           // LDS words per staged pixel
+    int f_per_wg;        // filters handled by one workgroup (a multiple of kPassFilters)
+    int popw_off;        // LDS word offset of the per-(filter, tap) popcount table
+};
+
+template <int VW>
+__global__ __launch_bounds__(256) void conv_tiled_kernel(
+    // separate __restrict__ arguments (not struct members): only then may the compiler fetch the
+    // filter words with scalar loads while the kernel also stores to `out`
+    const uint32_t *__restrict__ Ipk, const uint32_t *__restrict__ Wpk, const float *__restrict__ K,
+    const float *__restrict__ alpha, float *__restrict__ out, int32_t *__restrict__ dot, TiledParams p)
+{
+    extern __shared__ uint32_t smem[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int taps = p.kh * p.kw;
+
+    // ---- tile ----
+    int b = blockIdx.x;
+    const int tx = b % p.tiles_x; b /= p.tiles_x;
+    const int ty = b % p.tiles_y;
+    const int n = b / p.tiles_y;
+    const int oy0 = ty * p.TH, ox0 = tx * p.TW;
+    const int iy0 = oy0 * p.sh - p.ph, ix0 = ox0 * p.sw - p.pw;
+    const bool border = iy0 < 0 || ix0 < 0 || iy0 + p.RH > p.H || ix0 + p.RW > p.W;
+
+    // ---- stage the input tile (packed words, zero outside the image) ----
+    const uint32_t *img = Ipk + (long long)n * p.H * p.W * p.Cw;
+    const int nslots = p.RH * p.RW;
+    for (int it = tid; it < nslots * p.Cw; it += 256) {
+        const int slot = it / p.Cw, w = it - slot * p.Cw;
+        const int ry = slot / p.RW, rx = slot - ry * p.RW;
+        const int iy = iy0 + ry, ix = ix0 + rx;
+        uint32_t v = 0;
+        if (iy >= 0 && iy < p.H && ix >= 0 && ix < p.W) v = img[((long long)iy * p.W + ix) * p.Cw + w];
+        smem[slot * p.pitch + w] = v;
+    }
+
+    // ---- the lane's pixels ----
+    int base[kP], oyv[kP], oxv[kP];
+    bool ok[kP];
+#pragma unroll
+    for (int k = 0; k < kP; ++k) {
+        const int q = lane + 64 * k;
+        const int ly = q / p.TW, lx = q - ly * p.TW;
+        oyv[k] = oy0 + ly;
+        oxv[k] = ox0 + lx;
+        ok[k] = ly < p.TH && oyv[k] < p.OH && oxv[k] < p.OW;
+        base[k] = ok[k] ? (ly * p.sh * p.RW + lx * p.sw) * p.pitch : 0;
+    }
+    uint32_t *popw = smem + p.popw_off;   // [kPassFilters][taps]
+
+    const int f_wg0 = blockIdx.y * p.f_per_wg;
+    for (int f_pass = f_wg0; f_pass < min(p.F, f_wg0 + p.f_per_wg); f_pass += kPassFilters) {
+        __syncthreads();   // staged tile ready / previous pass done with the popcount table
+        if (border) {
+            for (int e = tid; e < kPassFilters * taps; e += 256) {
+                const int fl = e / taps, tap = e - fl * taps;
+                const int f = f_pass + fl;
+                uint32_t s = 0;
+                if (f < p.F) {
+                    const uint32_t *w = Wpk + ((long long)f * taps + tap) * p.Cw;
+                    for (int k = 0; k < p.Cw; ++k) s += __popc(w[k]);
+                }
+                popw[e] = s;
+            }
+            __syncthreads();
+        }
+        const int f0 = f_pass + wave * kQ;   // this wave's filters (wave-uniform)
+        uint32_t acc[kP][kQ];
+#pragma unroll
+        for (int k = 0; k < kP; ++k)
+#pragma unroll
+            for (int q = 0; q < kQ; ++q) acc[k][q] = 0;
+
+        if (f0 < p.F) {
+            for (int ky = 0; ky < p.kh; ++ky)
+                for (int kx = 0; kx < p.kw; ++kx) {
+                    const int tap = ky * p.kw + kx;
+                    const int toff = (ky * p.RW + kx) * p.pitch;
+                    for (int w = 0; w < p.Cw; w += VW) {
+                        uint32_t x[kP][VW];
+#pragma unroll
+                        for (int k = 0; k < kP; ++k) {
+                            if constexpr (VW == 4) {
+                                const uint4 v = *reinterpret_cast<const uint4 *>(&smem[base[k] + toff + w]);
+                                x[k][0] = v.x; x[k][1] = v.y; x[k][2] = v.z; x[k][3] = v.w;
+                            } else {
+                                x[k][0] = smem[base[k] + toff + w];
+                            }
+                        }
+#pragma unroll
+                        for (int q = 0; q < kQ; ++q) {
+                            // filters past F re-read the last filter (their sums are never stored)
+                            const int f = min(f0 + q, p.F - 1);
+                            const uint32_t *wp = Wpk + ((long long)f * taps + tap) * p.Cw + w;
+                            uint32_t wv[VW];
+                            if constexpr (VW == 4) {
+                                const uint4 v = *reinterpret_cast<const uint4 *>(wp);   // scalar load
+                                wv[0] = v.x; wv[1] = v.y; wv[2] = v.z; wv[3] = v.w;
+                            } else {
+                                wv[0] = *wp;
+                            }
+#pragma unroll
+                            for (int k = 0; k < kP; ++k)
+#pragma unroll
+                                for (int e = 0; e < VW; ++e) acc[k][q] += __popc(x[k][e] ^ wv[e]);
+                        }
+                    }
+                }
+        }
+
+        // ---- step 3: border correction, dot, rescale ----
+#pragma unroll
+        for (int k = 0; k < kP; ++k) {
+            if (!ok[k] || f0 >= p.F) continue;
+            const int oy = oyv[k], ox = oxv[k];
+            const int ky_lo = max(0, p.ph - oy * p.sh), ky_hi = min(p.kh, p.H + p.ph - oy * p.sh);
+            const int kx_lo = max(0, p.pw - ox * p.sw), kx_hi = min(p.kw, p.W + p.pw - ox * p.sw);
+            const int valid = max(0, ky_hi - ky_lo) * max(0, kx_hi - kx_lo);
+            uint32_t corr[kQ];
+#pragma unroll
+            for (int q = 0; q < kQ; ++q) corr[q] = 0;
+            if (valid != taps) {
+                for (int ky = 0; ky < p.kh; ++ky)
+                    for (int kx = 0; kx < p.kw; ++kx) {
+                        if (ky >= ky_lo && ky < ky_hi && kx >= kx_lo && kx < kx_hi) continue;
+#pragma unroll
+                        for (int q = 0; q < kQ; ++q) corr[q] += popw[(wave * kQ + q) * taps + ky * p.kw + kx];
+                    }
+            }
+            const float kv = K[((long long)n * p.OH + oy) * p.OW + ox];
+#pragma unroll
+            for (int q = 0; q < kQ; ++q) {
+                const int f = f0 + q;
+                if (f >= p.F) break;
+                const int d = p.C * valid - 2 * (int)(acc[k][q] - corr[q]);
+                const long long o = (((long long)n * p.F + f) * p.OH + oy) * p.OW + ox;
+                out[o] = (float)d * (kv * alpha[f]);
+                if (dot) dot[o] = d;
+            }
+        }
+    }
 }
+
+struct TiledPlan {
+    bool ok;
+    int TH, TW, RH, RW, tiles_x, tiles_y, pitch, vw, f_per_wg, popw_off;
+    size_t lds_bytes;
+};
+
+TiledPlan make_plan(const Geom &g, const void *Ipk, const void *Wpk)
+{
+    TiledPlan pl{};
+    pl.TW = std::min(g.OW, 64);
+    pl.TH = std::max(1, std::min(g.OH, kTilePixels / pl.TW));
+    const uintptr_t al = reinterpret_cast<uintptr_t>(Ipk) | reinterpret_cast<uintptr_t>(Wpk);
+    pl.vw = (g.Cw % 4 == 0 && (al & 15) == 0) ? 4 : 1;
+    // LDS words per staged pixel: an odd number of 16-byte units (VW = 4) or an odd number of words
+    pl.pitch = pl.vw == 4 ? (g.Cw | 4) : (g.Cw | 1);
+    const int taps = g.kh * g.kw;
+    // shrink the tile until it fits LDS (wide channels / big kernels)
+    for (;;) {
+        pl.RH = (pl.TH - 1) * g.sh + g.kh;
+        pl.RW = (pl.TW - 1) * g.sw + g.kw;
+        const size_t words = (size_t)pl.RH * pl.RW * pl.pitch + (size_t)kPassFilters * taps + 4;
+        if (words * 4 <= kLdsBudget) {
+            pl.popw_off = (pl.RH * pl.RW * pl.pitch + 3) & ~3;
+            pl.lds_bytes = ((size_t)pl.popw_off + (size_t)kPassFilters * taps) * 4;
+            break;
+        }
+        if (pl.TH > 1) pl.TH = (pl.TH + 1) / 2;
+        else if (pl.TW > 1) pl.TW = (pl.TW + 1) / 2;
+        else return pl;   // one pixel's receptive field does not fit: the direct kernel takes it
+    }
+    pl.tiles_x = ceil_div(g.OW, pl.TW);
+    pl.tiles_y = ceil_div(g.OH, pl.TH);
+    const long long tiles = (long long)g.N * pl.tiles_x * pl.tiles_y;
+    if (tiles > 0x7fffffffLL) return pl;
+    // split the filters over workgroups until the grid has a few workgroups per CU
+    const int passes = ceil_div(g.F, kPassFilters);
+    int split = 1;
+    while (split < passes && tiles * split < 4 * 256) ++split;
+    pl.f_per_wg = ceil_div(passes, split) * kPassFilters;
+    pl.ok = true;
+    return pl;
+}
+
+}  // namespace
+
+bool conv_tiled_supports(const Geom &g) { return make_plan(g, nullptr, nullptr).ok; }
+
+hipError_t launch_conv_tiled(const uint32_t *Ipk, const uint32_t *Wpk, const float *K,
+                             const float *alpha, const Geom &g, float *out, int32_t *dot,
+                             hipStream_t st)
+{
+    const TiledPlan pl = make_plan(g, Ipk, Wpk);
+    if (!pl.ok) return hipErrorInvalidValue;
+    TiledParams p{};
+    p.N = g.N; p.C = g.C; p.H = g.H; p.W = g.W; p.F = g.F; p.kh = g.kh; p.kw = g.kw;
+    p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw; p.OH = g.OH; p.OW = g.OW; p.Cw = g.Cw;
+    p.TH = pl.TH; p.TW = pl.TW; p.RH = pl.RH; p.RW = pl.RW;
+    p.tiles_x = pl.tiles_x; p.tiles_y = pl.tiles_y;
+    p.pitch = pl.pitch; p.f_per_wg = pl.f_per_wg; p.popw_off = pl.popw_off;
+    const dim3 grid(g.N * pl.tiles_x * pl.tiles_y, ceil_div(g.F, pl.f_per_wg));
+    if (pl.vw == 4)
+        conv_tiled_kernel<4><<<grid, 256, pl.lds_bytes, st>>>(Ipk, Wpk, K, alpha, out, dot, p);
+    else
+        conv_tiled_kernel<1><<<grid, 256, pl.lds_bytes, st>>>(Ipk, Wpk, K, alpha, out, dot, p);
+    return hipGetLastError();
+}
+
+}  // namespace xnor
