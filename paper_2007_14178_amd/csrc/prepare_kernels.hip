@@ -4,6 +4,8 @@
 //            per-filter alpha = mean |W|               (Eq. 5)
 // All three read fp32 once and write far less than they read, so each is laid out for coalesced
 // 256-byte wavefront reads along the image's fastest axis with many loads in flight per lane.
+#include <algorithm>
+
 #include "xnor_internal.hpp"
 
 namespace xnor {
@@ -130,7 +132,11 @@ hipError_t launch_channel_mean_abs(const float *I, int N, int C, int H, int W, f
 // LDS and written out as one contiguous run of 64*Cw words; the slices' partial |x| sums (double)
 // are combined in a fixed order.
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64 * kMaxSlices) void pack_and_mean_kernel(
+// Up to 4 slices: measured equal to 8 and faster than 16 (a 1024-thread block leaves one block per
+// CU and nothing to overlap its final barrier and write-out with).
+constexpr int kPackMeanSlices = 4;
+
+__global__ __launch_bounds__(64 * kPackMeanSlices) void pack_and_mean_kernel(
     const float *__restrict__ x, long long NP, int C, int HW, int Cw, int Cwp,
     uint32_t *__restrict__ packed, float *__restrict__ A)
 {
@@ -191,7 +197,7 @@ hipError_t launch_pack_and_mean(const float *x, int N, int C, int H, int W, uint
     const int HW = H * W, Cw = (C + 31) / 32, Cwp = Cw | 1;
     const long long NP = (long long)N * HW;
     int S = 1;
-    while (S < kMaxSlices && 2 * S <= Cw) S *= 2;
+    while (S < kPackMeanSlices && 2 * S <= Cw) S *= 2;
     const size_t smem = (size_t)S * 64 * sizeof(double) + (size_t)64 * Cwp * sizeof(uint32_t);
     pack_and_mean_kernel<<<dim3(ceil_div(NP, 64)), dim3(64, S), smem, st>>>(x, NP, C, HW, Cw, Cwp,
                                                                            packed, A);
@@ -214,6 +220,79 @@ __global__ __launch_bounds__(256) void alpha_from_tap_means_kernel(const float *
 hipError_t launch_alpha_from_tap_means(const float *M, int F, int taps, float *alpha, hipStream_t st)
 {
     alpha_from_tap_means_kernel<<<ceil_div(F, 256), 256, 0, st>>>(M, F, taps, alpha);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Filters: step 1a (Eq. 3) and Eq. 5 in one pass, one workgroup per filter.  A filter's C*kh*kw
+// floats are contiguous, so the workgroup reads them as one coalesced run into LDS (a chunk of CH
+// channels at a time, CH a multiple of 32), then one thread per (tap, channel word) gathers its 32
+// channel values from LDS (consecutive threads = consecutive taps = consecutive LDS words), builds
+// the word and the |w| sum of its 32 channels.  Sums are combined in double in a fixed order:
+// M[f][tap] = mean_c |Wt[f][c][tap]|, alpha[f] = mean over everything.
+// ------------------------------------------------------------------------------------------------
+constexpr int kFilterStageFloats = 8192;   // 32 KB of LDS for the staged chunk
+
+__global__ __launch_bounds__(256) void filter_pack_mean_kernel(
+    const float *__restrict__ Wt, int C, int taps, int Cw, int CH, uint32_t *__restrict__ Wpk,
+    float *__restrict__ M, float *__restrict__ alpha)
+{
+    extern __shared__ double fp_smem[];
+    const int tid = threadIdx.x, f = blockIdx.x;
+    const int WH = CH / 32;                                        // channel words per chunk
+    double *part = fp_smem;                                         // [WH][taps]
+    float *stage = reinterpret_cast<float *>(fp_smem + WH * taps);  // [CH][taps]
+    const float *src = Wt + (long long)f * C * taps;
+    uint32_t *dst = Wpk + (long long)f * taps * Cw;
+    double tap_total = 0.0;                                         // thread t < taps owns tap t
+    for (int c0 = 0; c0 < C; c0 += CH) {
+        const int nch = min(CH, C - c0);
+        const int nfl = nch * taps;
+        __syncthreads();                                            // previous chunk fully consumed
+        for (int i = tid; i < nfl; i += 256) stage[i] = src[(long long)c0 * taps + i];
+        __syncthreads();
+        const int nw = (nch + 31) / 32;
+        for (int it = tid; it < nw * taps; it += 256) {
+            const int w = it / taps, tap = it - w * taps;
+            const int nb = min(32, nch - 32 * w);
+            uint32_t word = 0;
+            double acc = 0.0;
+            for (int j = 0; j < nb; ++j) {
+                const float v = stage[(32 * w + j) * taps + tap];
+                word |= (v >= 0.0f ? 1u : 0u) << j;
+                acc += (double)fabsf(v);
+            }
+            dst[tap * Cw + c0 / 32 + w] = word;
+            part[it] = acc;
+        }
+        __syncthreads();
+        if (tid < taps)
+            for (int w = 0; w < nw; ++w) tap_total += part[w * taps + tid];
+    }
+    __syncthreads();
+    if (tid < taps) {
+        M[(long long)f * taps + tid] = (float)(tap_total / (double)C);
+        part[tid] = tap_total;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double sum = 0.0;
+        for (int t = 0; t < taps; ++t) sum += part[t];
+        alpha[f] = (float)(sum / ((double)C * (double)taps));
+    }
+}
+
+bool filter_pack_mean_supports(int taps) { return taps <= 256; }
+
+hipError_t launch_filter_pack_mean(const float *Wt, int F, int C, int taps, uint32_t *Wpk, float *M,
+                                   float *alpha, hipStream_t st)
+{
+    const int Cw = (C + 31) / 32;
+    int CH = kFilterStageFloats / taps / 32 * 32;                   // >= 32 since taps <= 256
+    CH = std::min(CH, Cw * 32);
+    const int WH = CH / 32;
+    const size_t smem = (size_t)WH * taps * sizeof(double) + (size_t)CH * taps * sizeof(float);
+    filter_pack_mean_kernel<<<F, 256, smem, st>>>(Wt, C, taps, Cw, CH, Wpk, M, alpha);
     return hipGetLastError();
 }
 

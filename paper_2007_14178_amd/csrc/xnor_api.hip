@@ -150,7 +150,9 @@ int xnor_filter_prepare(const float *Wt, int F, int C, int kh, int kw, uint32_t 
     if (!aligned(Wt, 4) || !aligned(Wpk, 4) || !aligned(M_work, 4) || !aligned(alpha, 4)) return XNOR_E_ALIGN;
     hipStream_t st = (hipStream_t)stream;
     hipError_t e;
-    if (xnor::pack_and_mean_supports(C)) {
+    if (xnor::filter_pack_mean_supports(kh * kw)) {
+        e = xnor::launch_filter_pack_mean(Wt, F, C, kh * kw, Wpk, M_work, alpha, st);
+    } else if (xnor::pack_and_mean_supports(C)) {
         e = xnor::launch_pack_and_mean(Wt, F, C, kh, kw, Wpk, M_work, st);
         if (e == hipSuccess) e = xnor::launch_alpha_from_tap_means(M_work, F, kh * kw, alpha, st);
     } else {

@@ -24,6 +24,9 @@ hipError_t launch_channel_mean_abs(const float *I, int N, int C, int H, int W, f
 bool pack_and_mean_supports(int C);
 hipError_t launch_pack_and_mean(const float *x, int N, int C, int H, int W, uint32_t *packed,
                                 float *A, hipStream_t st);
+bool filter_pack_mean_supports(int taps);
+hipError_t launch_filter_pack_mean(const float *Wt, int F, int C, int taps, uint32_t *Wpk, float *M,
+                                   float *alpha, hipStream_t st);
 hipError_t launch_alpha_from_tap_means(const float *M, int F, int taps, float *alpha, hipStream_t st);
 hipError_t launch_box_filter_K(const float *A, const Geom &g, float *K, hipStream_t st);
 hipError_t launch_alpha(const float *Wt, int F, long long n_red, float *alpha, hipStream_t st);
