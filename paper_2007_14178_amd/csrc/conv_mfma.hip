@@ -31,7 +31,7 @@
 namespace xnor {
 namespace {
 
-typedef int v8i __attribute__((ext_vector_type(8)));
+typedef int v4i __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kWM = 2;            // 32-filter tiles per wave
@@ -41,6 +41,7 @@ constexpr int kFilterTile = 2 * 32 * kWM;   // 2 wave rows
 constexpr int kRing = 4;          // register ring of filter operands: loads run kRing-1 steps ahead
 constexpr int kPatchPitch = 36;    // floats per row of a wave's 32x32 output patch in LDS (144 bytes)
 constexpr int kScaleOne = 0x7f7f7f7f;       // E8M0 exponent 127 = 2^0
+constexpr int kXcdShift = 3, kXcds = 1 << kXcdShift;   // MI355X: 8 XCDs of 32 CUs
 
 // q = n / d for n*d < 2^32 via one mul_hi.
 struct FastDiv {
@@ -70,6 +71,7 @@ struct MfmaParams {
     int tile_steps;  // k-steps the workspace holds per filter tile: every chunk padded to a whole
                      // number of rings, plus one ring of zero steps for the prefetch overrun
     FastDiv dCHV, dWp, dRH;
+    int nbands, bands_per_xcd;
 };
 
 // 8 sign bits -> 8 FP4 codes (bit 1 -> 0x2 = +1.0, bit 0 -> 0xA = -1.0); channel i -> nibble i.
@@ -140,9 +142,9 @@ struct WordVec;
 template <>
 struct WordVec<1> { typedef uint32_t type; };
 template <>
-struct WordVec<2> { typedef uint2 type; };
+struct WordVec<2> { typedef uint32_t type __attribute__((ext_vector_type(2))); };
 template <>
-struct WordVec<4> { typedef uint4 type; };
+struct WordVec<4> { typedef uint32_t type __attribute__((ext_vector_type(4))); };
 
 // The kernel.  Per workgroup: the band's input words are expanded to FP4 into LDS one channel
 // chunk at a time, double-buffered: while the MFMA loop runs on chunk c, the words of chunk c+1
@@ -161,14 +163,26 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
     const int l32 = lane & 31, kg = lane >> 5;
     const int OHW = p.OH * p.OW;
 
+    // ---- which (band, filter tile): workgroups are handed to the 8 XCDs round-robin by their id,
+    // and each XCD has its own L2.  XCD x takes a contiguous range of bands and runs through them
+    // once per filter tile, so that a band's input rows (and its neighbours' shared halo rows) are
+    // fetched into that one L2 once and found there by the other filter tiles' workgroups.
+    const int xcd = blockIdx.x & (kXcds - 1);
+    const int seq = blockIdx.x >> kXcdShift;
+    // (a division by a run-time value goes through the vector ALU: bring the wave-uniform quotient
+    // back into a scalar register, or everything derived from it occupies vector registers)
+    const int ftile = __builtin_amdgcn_readfirstlane(seq / p.bands_per_xcd);
+    const int band = xcd * p.bands_per_xcd + (seq - ftile * p.bands_per_xcd);
+    if (band >= p.nbands) return;   // padding of the last XCD's range (uniform over the workgroup)
+
     // ---- the band: TH rows of the batch's output rows, numbered R = n*OH + oy ----
-    const int R0 = blockIdx.x * p.TH;
+    const int R0 = band * p.TH;
     const int rows = min(p.TH, p.total_rows - R0);
     const int npix = rows * p.OW;
-    const int n_first = R0 / p.OH, oy0 = R0 - n_first * p.OH;
+    const int n_first = __builtin_amdgcn_readfirstlane(R0 / p.OH), oy0 = R0 - n_first * p.OH;
     const int r0 = (p.OH - 1 - oy0) * p.sh + p.kh;   // staged rows of the first image if it runs to its end
     const int R_last = R0 + rows - 1;
-    const int n_last = R_last / p.OH, oy_last = R_last - n_last * p.OH;
+    const int n_last = __builtin_amdgcn_readfirstlane(R_last / p.OH), oy_last = R_last - n_last * p.OH;
     const int srows = (n_last == n_first) ? (oy_last - oy0) * p.sh + p.kh
                                           : r0 + (n_last - n_first - 1) * p.RHfull + oy_last * p.sh + p.kh;
     const int nslots = srows * p.Wp;
@@ -179,7 +193,8 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
     const int tile0 = wn ? nt0 : 0;
     const int my_nt = wn ? NT - nt0 : nt0;
 
-    uint32_t baseB[kWN];   // LDS index (16-byte units) of the lane's pixel, tap (0,0), k-group kg
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)lds;
+    uint32_t bB[kWN];   // LDS byte address of the lane's pixel, tap (0,0), k-group kg
 #pragma unroll
     for (int j = 0; j < kWN; ++j) {
         const int q = (tile0 + j) * 32 + l32;
@@ -189,14 +204,14 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
         const int n = R / p.OH, oy = R - n * p.OH;
         const int srow = (n == n_first) ? (oy - oy0) * p.sh
                                         : r0 + (n - n_first - 1) * p.RHfull + oy * p.sh;
-        baseB[j] = (uint32_t)((srow * p.Wp + ox * p.sw) * p.pitch16 + kg);
+        bB[j] = lds_base + (uint32_t)((srow * p.Wp + ox * p.sw) * p.pitch16 + kg) * 16u;
     }
 
-    const uint4 *Aptr[kWM];   // this lane's filter operands, step 0 of the tile
+    const uint4 *Abase[kWM];   // filter operands of this wave's tiles, step 0 (wave-uniform)
 #pragma unroll
     for (int i = 0; i < kWM; ++i) {
-        const int tile = blockIdx.y * (2 * kWM) + wm * kWM + i;
-        Aptr[i] = p.Wx + ((long long)tile * p.tile_steps) * 64 + lane;
+        const int tile = ftile * (2 * kWM) + wm * kWM + i;
+        Abase[i] = p.Wx + ((long long)tile * p.tile_steps) * 64;
     }
 
     v16f acc[kWM][kWN];
@@ -214,11 +229,11 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
     const int Cw2 = 2 * p.S2;
     constexpr int UP = 2;                    // items per thread fetched ahead into registers
     wvec sv[UP];
-    int sdst[UP];                            // LDS index inside a buffer, or -1
-    bool slive[UP];
+    // all offsets into Ipk are taken from the band's first image (32 bits are enough, see make_plan)
+    const uint32_t *const band_base = p.Ipk + (long long)n_first * p.H * p.W * p.Cw;
 
-    // where item `it` of chunk `c` comes from and goes to
-    auto locate = [&](int it, int c, int &dst, bool &live) -> const uint32_t * {
+    // where item `it` of chunk `c` comes from (word offset from band_base) and goes to
+    auto locate = [&](int it, int c, int &dst, bool &live) -> uint32_t {
         const bool in_range = it < items;
         const uint32_t itc = in_range ? (uint32_t)it : 0u;
         const uint32_t slot = fdiv(itc, p.dCHV);
@@ -239,7 +254,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
         const int w = c * p.CH + wq * VW;
         live = in_range && n < p.N && iy >= 0 && iy < p.H && ix >= 0 && ix < p.W && w < p.Cw;
         dst = in_range ? (int)(slot * p.pitch16 + wq * VW) : -1;
-        return p.Ipk + (((long long)n * p.H + iy) * p.W + ix) * p.Cw + w;
+        return live ? (uint32_t)((((n - n_first) * p.H + iy) * p.W + ix) * p.Cw + w) : 0u;
     };
     // outside the image (or past the last channel word) the FP4 image is 0.0, not -1.0
     auto put = [&](uint4 *buf, int dst, bool live, const wvec &v) {
@@ -252,31 +267,44 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
         for (int k = 0; k < VW; ++k)
             buf[dst + k] = live ? expand_word(words[k], 32) : make_uint4(0, 0, 0, 0);
     };
-    // The first UP items of a thread are the same slots in every chunk: locate them once; a chunk
-    // only shifts the source by its first word.
-    const uint32_t *ssrc[UP];    // source of the item in chunk 0
-    int sw0[UP];                 // first word of the item inside a chunk
-    bool sin[UP];                // the slot is inside an image
-#pragma unroll
-    for (int u = 0; u < UP; ++u) {
-        bool live0;
-        ssrc[u] = locate(u * 256 + tid, 0, sdst[u], live0);
-        const int it = u * 256 + tid;
-        sw0[u] = it < items ? (int)(((uint32_t)it - fdiv((uint32_t)it, p.dCHV) * CHV) * VW) : 0;
-        sin[u] = live0;   // (a word past Cw in chunk 0 is past Cw in every chunk)
-    }
+    // A thread's first UP items are fetched into registers at a chunk's start and expanded half-way
+    // through it.  Where an item comes from and goes to is worked out again at both points from
+    // a copy of the thread id that the compiler cannot see through: it would otherwise compute
+    // all of it once, ahead of the MFMA loop, and hold it in registers the loop needs.
+    auto opaque_tid = [&]() -> int {
+        int t = tid;
+        asm volatile("" : "+v"(t));
+        return t;
+    };
+    // VW words at word offset `off` from band_base into `v`, as an asm statement (see stage_issue)
+    auto fetch_words = [&](wvec &v, uint32_t off) {
+        const uint32_t off_b = off * 4u;
+        if constexpr (VW == 4)
+            asm volatile("global_load_dwordx4 %0, %1, %2" : "+v"(v) : "v"(off_b), "s"(band_base));
+        else if constexpr (VW == 2)
+            asm volatile("global_load_dwordx2 %0, %1, %2" : "+v"(v) : "v"(off_b), "s"(band_base));
+        else
+            asm volatile("global_load_dword %0, %1, %2" : "+v"(v) : "v"(off_b), "s"(band_base));
+    };
     auto stage_issue = [&](int c) {
+        const int t = opaque_tid();
 #pragma unroll
         for (int u = 0; u < UP; ++u) {
-            slive[u] = sin[u] && (c * p.CH + sw0[u] < p.Cw);
+            int dst;
+            bool live;
+            const uint32_t off = locate(u * 256 + t, c, dst, live);
             wvec z = {};
             sv[u] = z;
-            if (slive[u]) sv[u] = *reinterpret_cast<const wvec *>(ssrc[u] + c * p.CH);
+            // The load is an asm statement so that the compiler keeps no count of it: its own wait
+            // for these words (vmcnt(0), it knows of no younger loads) would drain the filter-operand
+            // ring of the MFMA loop.  stage_commit waits with the right count instead.  "+v": the
+            // load lands in the register that already holds the zeros of a dead item.
+            if (live) fetch_words(sv[u], off);
         }
     };
     // The pixel operand of step t of a chunk sits at (buffer, tap(t), step-in-tap(t)) from the lane's
     // slot.  That offset is the same for every lane, so it is tabulated once per chunk in LDS
-    // (entry t, in 16-byte units) instead of being tracked with scalar arithmetic in the MFMA loop;
+    // (entry t, in bytes) instead of being tracked with scalar arithmetic in the MFMA loop;
     // entries of the zero-padded steps and of the prefetch overrun point at tap 0.
     uint32_t *const tables = reinterpret_cast<uint32_t *>(lds + p.tab16);
     auto write_table = [&](int c) {
@@ -285,47 +313,94 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
         uint32_t *tab = tables + (c & 1) * p.tab_len;
         const uint32_t base = (uint32_t)((c & 1) * p.buf16);
         for (int tt = tid; tt < p.tab_len; tt += 256) {
-            uint32_t off = base;
+            uint32_t off = base;   // 16-byte units here, bytes in the table
             if (tt < real) {
                 const int tap = tt / steps_c, s = tt - tap * steps_c;
                 const int ky = tap / p.kw, kx = tap - ky * p.kw;
                 off = base + (uint32_t)((ky * p.Wp + kx) * p.pitch16 + 2 * s);
             }
-            tab[tt] = off;
+            tab[tt] = off * 16u;
         }
     };
-    auto stage_commit = [&](int c, uint4 *buf) {
+    // `in_loop`: called from inside the MFMA loop at least kRing steps after stage_issue, i.e. with
+    // at least 2*kRing filter-operand loads issued after the words were fetched (loads return in
+    // order); otherwise everything in flight is waited for.
+    auto stage_commit = [&](int c, uint4 *buf, bool in_loop) {
+        const int t = opaque_tid();
+        static_assert(UP == 2, "the wait below names both fetched items");
+        // (the words pass through the asm: their expansion cannot move above the wait)
+        if (in_loop) asm volatile("s_waitcnt vmcnt(6)" : "+v"(sv[0]), "+v"(sv[1]));
+        else asm volatile("s_waitcnt vmcnt(0)" : "+v"(sv[0]), "+v"(sv[1]));
 #pragma unroll
-        for (int u = 0; u < UP; ++u) put(buf, sdst[u], slive[u], sv[u]);
-        for (int it = UP * 256 + tid; it < items; it += 256) {   // bands with more items: fetched here
+        for (int u = 0; u < UP; ++u) {
             int dst;
             bool live;
-            const uint32_t *src = locate(it, c, dst, live);
+            locate(u * 256 + t, c, dst, live);
+            put(buf, dst, live, sv[u]);
+        }
+        for (int it = UP * 256 + t; it < items; it += 256) {   // bands with more items: fetched here
+            int dst;
+            bool live;
+            const uint32_t off = locate(it, c, dst, live);
             wvec z = {};
             wvec v = z;
-            if (live) v = *reinterpret_cast<const wvec *>(src);
+            if (live) fetch_words(v, off);
+            asm volatile("s_waitcnt vmcnt(0)" : "+v"(v));   // (this drains the MFMA loop's ring too)
             put(buf, dst, live, v);
         }
         write_table(c);
     };
     stage_issue(0);
-    stage_commit(0, lds);
+    stage_commit(0, lds, false);
     __syncthreads();
 
     // ---- contract ----
+    // The steady-state loop is written as a fixed sequence of single-instruction asm statements
+    // (volatile, so they stay in this order) with its own s_waitcnt counts: left to the compiler's
+    // scheduler the operand loads end up right in front of the MFMAs that use them and a lone wave
+    // then waits out every LDS and L2 latency with the matrix pipe idle.  Per 64-channel step and
+    // wave: 8 MFMAs; between them the 4 pixel-operand reads for the NEXT step (LDS, ~7 MFMAs =
+    // 220 cycles ahead of their first use), the table entry two steps ahead, and the 2 filter-
+    // operand loads for the step THREE ahead (L2, ring of kRing register sets).
+    //   LDS queue order per step:  T, B0, B1, B2, B3   (returns are in order: lgkmcnt(3) before
+    //                              the MFMA on Bj leaves the three younger requests in flight)
+    //   VMEM order per step:       A0, A1 of step s+3  (vmcnt(5) before the first use of A0(s),
+    //                              vmcnt(4) before A1(s))
+    // The compiler does not know about loads issued inside asm statements, so nothing it emits may
+    // sit between a load and the wait that covers it other than address arithmetic, and every
+    // register with a load in flight stays an operand of a later statement until it is drained.
     constexpr int D = kRing;
-    static_assert(D % 2 == 0, "the unrolled body alternates two pixel-operand buffers");
+    static_assert(D == 4, "the wait counts below are written for a ring of four");
     const int taps = p.kh * p.kw;
+    const int scale = kScaleOne;
 
-    int l_off = 0;
-    uint4 abuf[D][kWM];
-    auto load_a = [&](uint4 (&dst)[kWM]) {
+#define XNOR_MFMA(ACC, A, B)                                                                         \
+    asm volatile("v_mfma_scale_f32_32x32x64_f8f6f4 %0, %1, %2, %0, %3, %3 op_sel_hi:[0,0,0] cbsz:4 blgp:4" \
+                 : "+v"(ACC) : "v"(A), "v"(B), "v"(scale))
+#define XNOR_LDS128(DST, ADDR) asm volatile("ds_read_b128 %0, %1" : "=v"(DST) : "v"(ADDR))
+#define XNOR_LDS32(DST, ADDR, OFF) asm volatile("ds_read_b32 %0, %1 offset:" #OFF : "=v"(DST) : "v"(ADDR))
+#define XNOR_GLD(DST, VOFF, SBASE, OFF) \
+    asm volatile("global_load_dwordx4 %0, %1, %2 offset:" #OFF : "=v"(DST) : "v"(VOFF), "s"(SBASE))
+#define XNOR_ADD(DST, X, Y) asm volatile("v_add_u32 %0, %1, %2" : "=v"(DST) : "v"(X), "v"(Y))
+#define XNOR_WAIT(S) asm volatile("s_waitcnt " S)
+
+    v4i A[D][kWM], B[2][kWN];
+    uint32_t a_off = (uint32_t)lane * 16u;   // byte offset of this lane's operand of the next step to load
+
+    // ring fill: filter operands of steps 0..2 (ordinary loads; the compiler waits for them at the pins)
 #pragma unroll
-        for (int i = 0; i < kWM; ++i) dst[i] = Aptr[i][l_off];
-        l_off += 64;
-    };
+    for (int u = 0; u < D - 1; ++u) {
 #pragma unroll
-    for (int u = 0; u < D - 1; ++u) load_a(abuf[u]);
+        for (int i = 0; i < kWM; ++i)
+            A[u][i] = *reinterpret_cast<const v4i *>(reinterpret_cast<const char *>(Abase[i]) + a_off);
+        a_off += 1024;
+    }
+#pragma unroll
+    for (int u = 0; u < D - 1; ++u)
+#pragma unroll
+        for (int i = 0; i < kWM; ++i) asm volatile("" : "+v"(A[u][i]));
+#pragma unroll
+    for (int i = 0; i < kWM; ++i) A[D - 1][i] = v4i{0, 0, 0, 0};
 
     for (int c = 0; c < p.nchunks; ++c) {
         const int steps = min(p.CH, Cw2 - c * p.CH) >> 1;   // 64-channel steps per tap in this chunk
@@ -334,79 +409,88 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
         if (more) stage_issue(c + 1);                        // fetch the next chunk's words now ...
         bool committed = !more;
 
-        // pixel operands: offsets come from the chunk's table, read two steps ahead of the operands
-        // they address (which are themselves read one step ahead of their MFMAs)
-        const uint32_t *tab = tables + (c & 1) * p.tab_len;
-        uint4 bbuf[2][kWN];
-        uint32_t boff[2];
-        int t_next = 0;                                       // step whose operands are loaded next
-        auto load_b = [&](uint4 (&dst)[kWN], uint32_t &off) {
+        // prime: table entries 0 and 1, then the pixel operands of step 0 (the loop's first wait
+        // covers them)
+        uint32_t boff[2], tmp[kWN];
+        uint32_t tab_addr = lds_base + (uint32_t)(p.tab16 * 16 + (c & 1) * p.tab_len * 4);
+        XNOR_LDS32(boff[0], tab_addr, 0);
+        XNOR_LDS32(boff[1], tab_addr, 4);
+        tab_addr += 8;                                       // entry 2 is read in step 0
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(boff[0]), "+v"(boff[1]));
 #pragma unroll
-            for (int j = 0; j < kWN; ++j) dst[j] = lds[baseB[j] + off];
-            off = tab[t_next + 2];
-            ++t_next;
-        };
-        boff[0] = tab[0];
-        boff[1] = tab[1];
-        load_b(bbuf[0], boff[0]);
+        for (int j = 0; j < kWN; ++j) {
+            XNOR_ADD(tmp[j], bB[j], boff[0]);
+            XNOR_LDS128(B[0][j], tmp[j]);
+        }
+        if (c == 0) {
+#pragma unroll
+            for (int j = 0; j < kWN; ++j) B[1][j] = v4i{0, 0, 0, 0};
+        }
 
         for (int g = 0; g < Tp; g += D) {
 #pragma unroll
             for (int u = 0; u < D; ++u) {
-                // one step, no branches: next filter operands (ring), next pixel operands, 8 MFMAs
-                load_a(abuf[(u + D - 1) % D]);
-                load_b(bbuf[(u + 1) % 2], boff[(u + 1) % 2]);
-#pragma unroll
-                for (int i = 0; i < kWM; ++i) {
-                    const uint4 va = abuf[u][i];
-                    const v8i a = v8i{(int)va.x, (int)va.y, (int)va.z, (int)va.w, 0, 0, 0, 0};
-#pragma unroll
-                    for (int j = 0; j < kWN; ++j) {
-                        const uint4 vb = bbuf[u % 2][j];
-                        const v8i b = v8i{(int)vb.x, (int)vb.y, (int)vb.z, (int)vb.w, 0, 0, 0, 0};
-                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                            a, b, acc[i][j], 4, 4, 0, kScaleOne, 0, kScaleOne);
-                    }
-                }
-                // A lone wave issues in order: scalar and memory instructions placed in front of the
-                // MFMA block would leave the matrix pipe idle while they issue.  Ask for them to be
-                // spread between the MFMAs instead (mask 8 = MFMA, 0x100 = LDS read, 0x20 = VMEM
-                // read, 4 = SALU, 2 = VALU).
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x004, 4, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x004, 4, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x004, 4, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x004, 4, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x004, 4, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                // Pin the accumulators between steps (an empty volatile asm that "modifies" them):
-                // left free, the compiler interleaves the MFMAs of all unrolled steps and runs out
-                // of registers for the operands it then has to keep alive.
-#pragma unroll
-                for (int i = 0; i < kWM; ++i)
-#pragma unroll
-                    for (int j = 0; j < kWN; ++j) asm volatile("" : "+v"(acc[i][j]));
+                // step s = g + u uses A[u], B[u%2]; loads B[(u+1)%2] for s+1 at boff[(u+1)%2],
+                // table entry s+2 into boff[u%2], A[(u+3)%4] for s+3
+                XNOR_WAIT("vmcnt(5) lgkmcnt(3)");
+                XNOR_MFMA(acc[0][0], A[u][0], B[u % 2][0]);
+                if (u == 0) XNOR_LDS32(boff[u % 2], tab_addr, 0);
+                if (u == 1) XNOR_LDS32(boff[u % 2], tab_addr, 4);
+                if (u == 2) XNOR_LDS32(boff[u % 2], tab_addr, 8);
+                if (u == 3) XNOR_LDS32(boff[u % 2], tab_addr, 12);
+                XNOR_ADD(tmp[0], bB[0], boff[(u + 1) % 2]);
+                XNOR_WAIT("lgkmcnt(3)");
+                XNOR_MFMA(acc[0][1], A[u][0], B[u % 2][1]);
+                XNOR_LDS128(B[(u + 1) % 2][0], tmp[0]);
+                XNOR_ADD(tmp[1], bB[1], boff[(u + 1) % 2]);
+                XNOR_WAIT("lgkmcnt(3)");
+                XNOR_MFMA(acc[0][2], A[u][0], B[u % 2][2]);
+                XNOR_LDS128(B[(u + 1) % 2][1], tmp[1]);
+                XNOR_ADD(tmp[2], bB[2], boff[(u + 1) % 2]);
+                XNOR_WAIT("lgkmcnt(3)");
+                XNOR_MFMA(acc[0][3], A[u][0], B[u % 2][3]);
+                XNOR_LDS128(B[(u + 1) % 2][2], tmp[2]);
+                XNOR_ADD(tmp[3], bB[3], boff[(u + 1) % 2]);
+                XNOR_WAIT("vmcnt(4)");
+                XNOR_MFMA(acc[1][0], A[u][1], B[u % 2][0]);
+                XNOR_LDS128(B[(u + 1) % 2][3], tmp[3]);
+                XNOR_MFMA(acc[1][1], A[u][1], B[u % 2][1]);
+                if (u == 0) XNOR_GLD(A[(u + 3) % D][0], a_off, Abase[0], 0);
+                if (u == 1) XNOR_GLD(A[(u + 3) % D][0], a_off, Abase[0], 1024);
+                if (u == 2) XNOR_GLD(A[(u + 3) % D][0], a_off, Abase[0], 2048);
+                if (u == 3) XNOR_GLD(A[(u + 3) % D][0], a_off, Abase[0], 3072);
+                XNOR_MFMA(acc[1][2], A[u][1], B[u % 2][2]);
+                if (u == 0) XNOR_GLD(A[(u + 3) % D][1], a_off, Abase[1], 0);
+                if (u == 1) XNOR_GLD(A[(u + 3) % D][1], a_off, Abase[1], 1024);
+                if (u == 2) XNOR_GLD(A[(u + 3) % D][1], a_off, Abase[1], 2048);
+                if (u == 3) XNOR_GLD(A[(u + 3) % D][1], a_off, Abase[1], 3072);
+                XNOR_MFMA(acc[1][3], A[u][1], B[u % 2][3]);
             }
+            a_off += 4096;
+            tab_addr += 16;
             // ... and expand them into the other buffer half-way through this chunk
             if (!committed && 2 * (g + D) >= Tp) {
-                stage_commit(c + 1, lds + ((c + 1) & 1) * p.buf16);
+                stage_commit(c + 1, lds + ((c + 1) & 1) * p.buf16, true);
                 committed = true;
             }
         }
+        // The reads issued for the step past the chunk's end land in B[0] / boff: drain them while
+        // those registers are still operands, then they may be reused.
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(B[0][0]), "+v"(B[0][1]), "+v"(B[0][2]), "+v"(B[0][3]), "+v"(B[1][0]), "+v"(B[1][1]),
+                       "+v"(B[1][2]), "+v"(B[1][3]), "+v"(boff[0]), "+v"(boff[1]));
         if (more) __syncthreads();   // chunk c+1 is complete in its buffer; chunk c's buffer is free
     }
+    // the ring has run three (all-zero) steps ahead: let those loads land before the registers are reused
+    asm volatile("s_waitcnt vmcnt(0)"
+                 : "+v"(A[0][0]), "+v"(A[0][1]), "+v"(A[1][0]), "+v"(A[1][1]), "+v"(A[2][0]), "+v"(A[2][1]),
+                   "+v"(A[3][0]), "+v"(A[3][1]));
+#undef XNOR_MFMA
+#undef XNOR_LDS128
+#undef XNOR_LDS32
+#undef XNOR_GLD
+#undef XNOR_ADD
+#undef XNOR_WAIT
 
     // ---- step 3: out = float(dot) * K * alpha ----
     // The MFMA result has pixels along lanes and filters along registers, which would make every
@@ -419,8 +503,13 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
     float *__restrict__ outp = p.out;
     int32_t *__restrict__ dotp = p.dot;
     float *patch = reinterpret_cast<float *>(lds) + wave * (32 * kPatchPitch);
-    const int p4 = (lane & 7) * 4;      // first of this lane's four pixels within a tile
-    const int fl = lane >> 3;           // filter within a tile, plus 8*k
+    // lane-derived indices of this phase are formed from a copy of the lane id that the compiler
+    // cannot see through, or it computes them at kernel start and holds them across the MFMA loop
+    int lane_e = lane;
+    asm volatile("" : "+v"(lane_e));
+    const int p4 = (lane_e & 7) * 4;    // first of this lane's four pixels within a tile
+    const int fl = lane_e >> 3;         // filter within a tile, plus 8*k
+    const int l32e = lane_e & 31, kge = lane_e >> 5;
     if (my_nt > 0) {
         // the lane's pixel quads (one per tile): position, validity, contiguity; K and alpha are
         // fetched for all tiles first so that no load latency sits inside the store loop
@@ -447,7 +536,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
         for (int i = 0; i < kWM; ++i)
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const int f = (blockIdx.y * (2 * kWM) + wm * kWM + i) * 32 + fl + 8 * k;
+                const int f = (ftile * (2 * kWM) + wm * kWM + i) * 32 + fl + 8 * k;
                 al[i][k] = f < p.F ? alphap[f] : 0.0f;
             }
 #pragma unroll
@@ -456,10 +545,10 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
             const int nv = nvq[j];
 #pragma unroll
             for (int i = 0; i < kWM; ++i) {
-                const int f_tile = (blockIdx.y * (2 * kWM) + wm * kWM + i) * 32;
+                const int f_tile = (ftile * (2 * kWM) + wm * kWM + i) * 32;
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    patch[((r >> 2) * 8 + kg * 4 + (r & 3)) * kPatchPitch + l32] = acc[i][j][r];
+                    patch[((r >> 2) * 8 + kge * 4 + (r & 3)) * kPatchPitch + l32e] = acc[i][j][r];
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     const int f = f_tile + fl + 8 * k;
@@ -556,6 +645,8 @@ MfmaPlan make_plan(const Geom &g, const void *Ipk)
     if (!fit(kLdsTwoPerCU) && !fit(kLdsMax)) return pl;
     pl.lds_bytes = std::max(pl.lds_bytes, (size_t)4 * 32 * kPatchPitch * sizeof(float));   // output patches
     if ((long long)slots * pl.CH >= (1 << 20)) return pl;   // fast-division range
+    // staging addresses are 32-bit byte offsets from the band's first image
+    if ((long long)(pl.TH / g.OH + 2) * g.H * g.W * g.Cw >= (1LL << 30)) return pl;
     const uintptr_t ip = reinterpret_cast<uintptr_t>(Ipk);
     pl.vw = (g.Cw % 4 == 0 && pl.CH % 4 == 0 && (ip & 15) == 0) ? 4
           : (g.Cw % 2 == 0 && (ip & 7) == 0)                    ? 2 : 1;
@@ -563,7 +654,8 @@ MfmaPlan make_plan(const Geom &g, const void *Ipk)
     pl.chunk_pad = (taps * (pl.CH / 2) + kRing - 1) / kRing * kRing;
     pl.tile_steps = pl.nchunks * pl.chunk_pad + kRing;
     pl.ws_bytes = (size_t)pl.f_tiles * (kFilterTile / 32) * pl.tile_steps * 64 * sizeof(uint4);
-    if (ceil_div(total_rows, pl.TH) > 0x7fffffffLL || pl.f_tiles > 65535) return pl;
+    // (bands padded to a multiple of 8) x filter tiles is the grid
+    if ((ceil_div(total_rows, pl.TH) + 8) * pl.f_tiles > (1LL << 30)) return pl;
     pl.ok = true;
     return pl;
 }
@@ -614,7 +706,9 @@ hipError_t launch_conv_mfma(const uint32_t *Ipk, const uint32_t *Wpk, const floa
     p.dWp = make_fastdiv(pl.Wp);
     p.dRH = make_fastdiv(pl.RHfull);
 
-    const dim3 grid(ceil_div(p.total_rows, pl.TH), pl.f_tiles);
+    p.nbands = ceil_div(p.total_rows, pl.TH);
+    p.bands_per_xcd = ceil_div(p.nbands, kXcds);
+    const dim3 grid(kXcds * p.bands_per_xcd * pl.f_tiles);
     auto launch = [&](auto kernel) -> hipError_t {
         // raise the kernel's dynamic-LDS limit to the hardware maximum once per device (the call
         // is slow on the host); one flag set per template instance
