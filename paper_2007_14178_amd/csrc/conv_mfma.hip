@@ -502,7 +502,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
     const float *__restrict__ alphap = p.alpha;
     float *__restrict__ outp = p.out;
     int32_t *__restrict__ dotp = p.dot;
-    float *patch = reinterpret_cast<float *>(lds) + wave * (32 * kPatchPitch);
+    float *patch = reinterpret_cast<float *>(lds) + wave * (32 * kPatchPitch);   // + 4 waves' worth: the second patch
     // lane-derived indices of this phase are formed from a copy of the lane id that the compiler
     // cannot see through, or it computes them at kernel start and holds them across the MFMA loop
     int lane_e = lane;
@@ -516,6 +516,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
         int nvq[kWN];
         bool quadq[kWN];
         long long kbaseq[kWN], obaseq[kWN];
+        int poq[kWN];
         float kq[kWN][4], al[kWM][4];
 #pragma unroll
         for (int j = 0; j < kWN; ++j) {
@@ -526,6 +527,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
             const int R = R0 + Rl;
             const int n = R / p.OH, oy = R - n * p.OH;
             const int po = oy * p.OW + ox;                    // offset inside the (n, f) plane
+            poq[j] = po;
             quadq[j] = nvq[j] == 4 && po + 3 < OHW;           // four pixels of one image: one 16-byte run
             kbaseq[j] = (long long)R * p.OW + ox;             // K is dense over (n, oy, ox)
             obaseq[j] = (long long)n * p.F * OHW + po;
@@ -539,39 +541,66 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
                 const int f = (ftile * (2 * kWM) + wm * kWM + i) * 32 + fl + 8 * k;
                 al[i][k] = f < p.F ? alphap[f] : 0.0f;
             }
+        // Touch every preloaded value here, so that the compiler waits for these loads once, now.
+        // Otherwise it re-inserts "wait for all vector memory operations" in front of later uses
+        // (on paths where it cannot prove the loads have landed), and since stores share that
+        // counter every tile would wait for the previous tile's stores to reach memory.
 #pragma unroll
-        for (int j = 0; j < kWN; ++j) {
+        for (int j = 0; j < kWN; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) asm volatile("" : "+v"(kq[j][e]));
+#pragma unroll
+        for (int i = 0; i < kWM; ++i)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) asm volatile("" : "+v"(al[i][k]));
+        // Tiles go through two patches in turn: tile t+1 is written while the rows of tile t are on
+        // their way back from LDS (LDS executes a wave's requests in order, so a patch can be
+        // rewritten right after the reads of its previous tile were issued).
+        auto write_patch = [&](int t, const v16f &a) {
+            float *pt = patch + (t & 1) * (4 * 32 * kPatchPitch);
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                pt[((r >> 2) * 8 + kge * 4 + (r & 3)) * kPatchPitch + l32e] = a[r];
+        };
+        constexpr int T = kWN * kWM;   // tile t = j * kWM + i
+        write_patch(0, acc[0][0]);
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const int j = t / kWM, i = t % kWM;
             if (j >= my_nt) break;
+            if (t + 1 < T && (t + 1) / kWM < my_nt) write_patch(t + 1, acc[(t + 1) % kWM][(t + 1) / kWM]);
+            const float *pt = patch + (t & 1) * (4 * 32 * kPatchPitch);
+            float4 d4[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                d4[k] = *reinterpret_cast<const float4 *>(&pt[(fl + 8 * k) * kPatchPitch + p4]);
             const int nv = nvq[j];
+            const int f_tile = (ftile * (2 * kWM) + wm * kWM + i) * 32;
 #pragma unroll
-            for (int i = 0; i < kWM; ++i) {
-                const int f_tile = (ftile * (2 * kWM) + wm * kWM + i) * 32;
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    patch[((r >> 2) * 8 + kge * 4 + (r & 3)) * kPatchPitch + l32e] = acc[i][j][r];
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const int f = f_tile + fl + 8 * k;
-                    const float4 d = *reinterpret_cast<const float4 *>(&patch[(fl + 8 * k) * kPatchPitch + p4]);
-                    if (f >= p.F || nv <= 0) continue;
-                    const float a = al[i][k];
-                    const long long o = obaseq[j] + (long long)f * OHW;
+            for (int k = 0; k < 4; ++k) {
+                const int f = f_tile + fl + 8 * k;
+                if (f >= p.F || nv <= 0) continue;
+                const float4 d = d4[k];
+                const float a = al[i][k];
+                const long long o = obaseq[j] + (long long)f * OHW;
+                if (quadq[j]) {
+                    *reinterpret_cast<float4 *>(outp + o) = make_float4(
+                        d.x * (kq[j][0] * a), d.y * (kq[j][1] * a), d.z * (kq[j][2] * a), d.w * (kq[j][3] * a));
+                    if (dotp)
+                        *reinterpret_cast<int4 *>(dotp + o) = make_int4((int)d.x, (int)d.y, (int)d.z, (int)d.w);
+                } else {
+                    // quad cut by the band's end or running over image boundaries: pixel e lies m
+                    // images further on (m <= 3), i.e. m*(F-1) planes beyond o + e
                     const float dd[4] = {d.x, d.y, d.z, d.w};
-                    if (quadq[j]) {
-                        *reinterpret_cast<float4 *>(outp + o) = make_float4(
-                            d.x * (kq[j][0] * a), d.y * (kq[j][1] * a), d.z * (kq[j][2] * a), d.w * (kq[j][3] * a));
-                        if (dotp)
-                            *reinterpret_cast<int4 *>(dotp + o) = make_int4((int)d.x, (int)d.y, (int)d.z, (int)d.w);
-                    } else {
-                        // quad cut by the band's end or by an image boundary: pixel by pixel
-                        for (int e = 0; e < nv; ++e) {
-                            const int Re = (int)((kbaseq[j] + e) / p.OW);
-                            const int oxe = (int)((kbaseq[j] + e) - (long long)Re * p.OW);
-                            const int ne = Re / p.OH, oye = Re - ne * p.OH;
-                            const long long oe = ((long long)ne * p.F + f) * OHW + oye * p.OW + oxe;
-                            outp[oe] = dd[e] * (kq[j][e] * a);
-                            if (dotp) dotp[oe] = (int32_t)dd[e];
-                        }
+                    const long long plane_skip = (long long)(p.F - 1) * OHW;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (e >= nv) break;
+                        const int pe = poq[j] + e;
+                        const int m = (pe >= OHW) + (pe >= 2 * OHW) + (pe >= 3 * OHW);
+                        const long long oe = o + e + m * plane_skip;
+                        outp[oe] = dd[e] * (kq[j][e] * a);
+                        if (dotp) dotp[oe] = (int32_t)dd[e];
                     }
                 }
             }
@@ -643,7 +672,7 @@ MfmaPlan make_plan(const Geom &g, const void *Ipk)
         return false;
     };
     if (!fit(kLdsTwoPerCU) && !fit(kLdsMax)) return pl;
-    pl.lds_bytes = std::max(pl.lds_bytes, (size_t)4 * 32 * kPatchPitch * sizeof(float));   // output patches
+    pl.lds_bytes = std::max(pl.lds_bytes, (size_t)2 * 4 * 32 * kPatchPitch * sizeof(float));   // output patches
     if ((long long)slots * pl.CH >= (1 << 20)) return pl;   // fast-division range
     // staging addresses are 32-bit byte offsets from the band's first image
     if ((long long)(pl.TH / g.OH + 2) * g.H * g.W * g.Cw >= (1LL << 30)) return pl;
