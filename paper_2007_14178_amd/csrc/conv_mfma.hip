@@ -66,8 +66,10 @@ struct MfmaParams {
     int nchunks;
     int pitch16;     // LDS slot pitch in 16-byte units (CH + 1, odd)
     int buf16;       // distance between the two LDS chunk buffers in 16-byte units (0: one buffer)
-    int tab16;       // start of the two per-chunk step-offset tables in LDS (16-byte units)
-    int tab_len;     // uint32 entries per table (a multiple of 4)
+    int tab16;       // start of the step-offset table in LDS (16-byte units)
+    int tab_len;     // its uint32 entries: one per step of the tile, a multiple of 4
+    int chunk_pad;   // steps per chunk in the workspace and the table (a whole number of rings)
+    int ragged;      // the last chunk has fewer than CH words
     int tile_steps;  // k-steps the workspace holds per filter tile: every chunk padded to a whole
                      // number of rings, plus one ring of zero steps for the prefetch overrun
     FastDiv dCHV, dWp, dRH;
@@ -256,29 +258,11 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
         dst = in_range ? (int)(slot * p.pitch16 + wq * VW) : -1;
         return live ? (uint32_t)((((n - n_first) * p.H + iy) * p.W + ix) * p.Cw + w) : 0u;
     };
-    // outside the image (or past the last channel word) the FP4 image is 0.0, not -1.0
-    auto put = [&](uint4 *buf, int dst, bool live, const wvec &v) {
-        if (dst < 0) return;
-        uint32_t words[VW];
-        if constexpr (VW == 1) { words[0] = v; }
-        if constexpr (VW == 2) { words[0] = v.x; words[1] = v.y; }
-        if constexpr (VW == 4) { words[0] = v.x; words[1] = v.y; words[2] = v.z; words[3] = v.w; }
-#pragma unroll
-        for (int k = 0; k < VW; ++k)
-            buf[dst + k] = live ? expand_word(words[k], 32) : make_uint4(0, 0, 0, 0);
-    };
-    // A thread's first UP items are fetched into registers at a chunk's start and expanded half-way
-    // through it.  Where an item comes from and goes to is worked out again at both points from
-    // a copy of the thread id that the compiler cannot see through: it would otherwise compute
-    // all of it once, ahead of the MFMA loop, and hold it in registers the loop needs.
-    auto opaque_tid = [&]() -> int {
-        int t = tid;
-        asm volatile("" : "+v"(t));
-        return t;
-    };
-    // VW words at word offset `off` from band_base into `v`, as an asm statement (see stage_issue)
-    auto fetch_words = [&](wvec &v, uint32_t off) {
-        const uint32_t off_b = off * 4u;
+    // VW words at byte offset `off_b` from band_base into `v`.  The load is an asm statement so that
+    // the compiler keeps no count of it: its own wait for these words (vmcnt(0), it knows of no
+    // younger loads) would drain the filter-operand ring of the MFMA loop; stage_commit waits with
+    // the right count instead.  "+v": the load lands in the register that holds a dead item's zeros.
+    auto fetch_words = [&](wvec &v, uint32_t off_b) {
         if constexpr (VW == 4)
             asm volatile("global_load_dwordx4 %0, %1, %2" : "+v"(v) : "v"(off_b), "s"(band_base));
         else if constexpr (VW == 2)
@@ -286,72 +270,105 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
         else
             asm volatile("global_load_dword %0, %1, %2" : "+v"(v) : "v"(off_b), "s"(band_base));
     };
-    auto stage_issue = [&](int c) {
-        const int t = opaque_tid();
+    // one item's words -> FP4 at byte offset `dst_b` of a chunk buffer; a dead item is FP4 zeros
+    // (outside the image, or past the last channel word, the +-1 tensor is 0.0, not -1.0)
+    char *const lds_bytes = reinterpret_cast<char *>(lds);
+    auto put = [&](uint32_t buf_b, uint32_t dst_b, bool live, const wvec &v) {
+        uint32_t words[VW];
+        if constexpr (VW == 1) { words[0] = v; }
+        if constexpr (VW == 2) { words[0] = v.x; words[1] = v.y; }
+        if constexpr (VW == 4) { words[0] = v.x; words[1] = v.y; words[2] = v.z; words[3] = v.w; }
+        uint4 *dst = reinterpret_cast<uint4 *>(lds_bytes + buf_b + dst_b);
+        if (live) {
 #pragma unroll
-        for (int u = 0; u < UP; ++u) {
-            int dst;
-            bool live;
-            const uint32_t off = locate(u * 256 + t, c, dst, live);
-            wvec z = {};
-            sv[u] = z;
-            // The load is an asm statement so that the compiler keeps no count of it: its own wait
-            // for these words (vmcnt(0), it knows of no younger loads) would drain the filter-operand
-            // ring of the MFMA loop.  stage_commit waits with the right count instead.  "+v": the
-            // load lands in the register that already holds the zeros of a dead item.
-            if (live) fetch_words(sv[u], off);
+            for (int k = 0; k < VW; ++k) dst[k] = expand_word(words[k], 32);
+        } else {
+#pragma unroll
+            for (int k = 0; k < VW; ++k) dst[k] = make_uint4(0, 0, 0, 0);
         }
     };
-    // The pixel operand of step t of a chunk sits at (buffer, tap(t), step-in-tap(t)) from the lane's
-    // slot.  That offset is the same for every lane, so it is tabulated once per chunk in LDS
-    // (entry t, in bytes) instead of being tracked with scalar arithmetic in the MFMA loop;
-    // entries of the zero-padded steps and of the prefetch overrun point at tap 0.
-    uint32_t *const tables = reinterpret_cast<uint32_t *>(lds + p.tab16);
-    auto write_table = [&](int c) {
-        const int steps_c = min(p.CH, Cw2 - c * p.CH) >> 1;
-        const int real = p.kh * p.kw * steps_c;
-        uint32_t *tab = tables + (c & 1) * p.tab_len;
-        const uint32_t base = (uint32_t)((c & 1) * p.buf16);
-        for (int tt = tid; tt < p.tab_len; tt += 256) {
-            uint32_t off = base;   // 16-byte units here, bytes in the table
-            if (tt < real) {
-                const int tap = tt / steps_c, s = tt - tap * steps_c;
-                const int ky = tap / p.kw, kx = tap - ky * p.kw;
-                off = base + (uint32_t)((ky * p.Wp + kx) * p.pitch16 + 2 * s);
-            }
-            tab[tt] = off * 16u;
+    // A thread's first UP items are the same slots in every chunk, a chunk only shifts the source
+    // by its first word: per item two registers are kept across the MFMA loop, the byte offset of
+    // its words in chunk 0 (kDead: slot outside every image) and where it goes in a chunk buffer
+    // (byte offset | first word within the chunk << 18; kNoItem: the thread has no such item).
+    constexpr uint32_t kDead = 0xffffffffu, kNoItem = 0xffffffffu;
+    uint32_t soff[UP], spk[UP];
+#pragma unroll
+    for (int u = 0; u < UP; ++u) {
+        const int it = u * 256 + tid;
+        int dst;
+        bool live0;
+        const uint32_t off = locate(it, 0, dst, live0);
+        const uint32_t w0 = it < items ? ((uint32_t)it - fdiv((uint32_t)it, p.dCHV) * CHV) * VW : 0u;
+        soff[u] = live0 ? off * 4u : kDead;   // (a word past Cw in chunk 0 is past Cw in every chunk)
+        spk[u] = dst < 0 ? kNoItem : ((uint32_t)dst * 16u) | (w0 << 18);
+    }
+    // chunks whose word range is cut by Cw exist only if CH does not divide Cw
+    auto item_live = [&](int u, int c) -> bool {
+        return soff[u] != kDead && (!p.ragged || c * p.CH + (int)(spk[u] >> 18) < p.Cw);
+    };
+    auto stage_issue = [&](int c) {
+#pragma unroll
+        for (int u = 0; u < UP; ++u) {
+            wvec z = {};
+            sv[u] = z;
+            if (item_live(u, c)) fetch_words(sv[u], soff[u] + (uint32_t)(c * p.CH) * 4u);
         }
     };
     // `in_loop`: called from inside the MFMA loop at least kRing steps after stage_issue, i.e. with
     // at least 2*kRing filter-operand loads issued after the words were fetched (loads return in
-    // order); otherwise everything in flight is waited for.
-    auto stage_commit = [&](int c, uint4 *buf, bool in_loop) {
-        const int t = opaque_tid();
+    // order); otherwise everything in flight is waited for.  `zero_dead`: dead items are written
+    // (as zeros) too; slots outside the image stay zero from the first fill of either buffer, so
+    // later chunks skip them unless channel words can die with the chunk (p.ragged).
+    auto stage_commit = [&](int c, uint32_t buf_b, bool in_loop, bool zero_dead) {
         static_assert(UP == 2, "the wait below names both fetched items");
         // (the words pass through the asm: their expansion cannot move above the wait)
         if (in_loop) asm volatile("s_waitcnt vmcnt(6)" : "+v"(sv[0]), "+v"(sv[1]));
         else asm volatile("s_waitcnt vmcnt(0)" : "+v"(sv[0]), "+v"(sv[1]));
 #pragma unroll
         for (int u = 0; u < UP; ++u) {
-            int dst;
-            bool live;
-            locate(u * 256 + t, c, dst, live);
-            put(buf, dst, live, sv[u]);
+            if (spk[u] == kNoItem) continue;
+            const bool live = item_live(u, c);
+            if (live || zero_dead) put(buf_b, spk[u] & 0x3ffffu, live, sv[u]);
         }
-        for (int it = UP * 256 + t; it < items; it += 256) {   // bands with more items: fetched here
+        for (int it = UP * 256 + tid; it < items; it += 256) {   // bands with more items: fetched here
             int dst;
             bool live;
             const uint32_t off = locate(it, c, dst, live);
             wvec z = {};
             wvec v = z;
-            if (live) fetch_words(v, off);
+            if (live) fetch_words(v, off * 4u);
             asm volatile("s_waitcnt vmcnt(0)" : "+v"(v));   // (this drains the MFMA loop's ring too)
-            put(buf, dst, live, v);
+            put(buf_b, (uint32_t)dst * 16u, live, v);
         }
-        write_table(c);
     };
+    // The pixel operand of step t sits at (chunk buffer, tap(t), step-in-tap(t)) from the lane's
+    // slot.  That offset is the same for every lane, so it is tabulated once per workgroup in LDS
+    // (one entry per step of the tile in workspace order, in bytes) instead of being tracked with
+    // scalar arithmetic in the MFMA loop; zero-padded steps and the prefetch overrun point at tap 0.
+    uint32_t *const table = reinterpret_cast<uint32_t *>(lds + p.tab16);
+    for (int tt = tid; tt < p.tab_len; tt += 256) {
+        const int c = min(tt / p.chunk_pad, p.nchunks - 1), t = tt - c * p.chunk_pad;
+        const int steps_c = min(p.CH, Cw2 - c * p.CH) >> 1;
+        uint32_t off = (uint32_t)((c & 1) * p.buf16);   // 16-byte units here, bytes in the table
+        if (t < p.kh * p.kw * steps_c) {
+            const int tap = t / steps_c, s = t - tap * steps_c;
+            const int ky = tap / p.kw, kx = tap - ky * p.kw;
+            off += (uint32_t)((ky * p.Wp + kx) * p.pitch16 + 2 * s);
+        }
+        table[tt] = off * 16u;
+    }
     stage_issue(0);
-    stage_commit(0, lds, false);
+    stage_commit(0, 0u, false, true);
+    if (p.nchunks > 1) {
+        // the second buffer's slots outside the image: zero once, no chunk writes them again
+#pragma unroll
+        for (int u = 0; u < UP; ++u)
+            if (spk[u] != kNoItem && soff[u] == kDead) {
+                wvec z = {};
+                put((uint32_t)p.buf16 * 16u, spk[u] & 0x3ffffu, false, z);
+            }
+    }
     __syncthreads();
 
     // ---- contract ----
@@ -412,7 +429,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
         // prime: table entries 0 and 1, then the pixel operands of step 0 (the loop's first wait
         // covers them)
         uint32_t boff[2], tmp[kWN];
-        uint32_t tab_addr = lds_base + (uint32_t)(p.tab16 * 16 + (c & 1) * p.tab_len * 4);
+        uint32_t tab_addr = lds_base + (uint32_t)(p.tab16 * 16 + c * p.chunk_pad * 4);
         XNOR_LDS32(boff[0], tab_addr, 0);
         XNOR_LDS32(boff[1], tab_addr, 4);
         tab_addr += 8;                                       // entry 2 is read in step 0
@@ -470,7 +487,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
             tab_addr += 16;
             // ... and expand them into the other buffer half-way through this chunk
             if (!committed && 2 * (g + D) >= Tp) {
-                stage_commit(c + 1, lds + ((c + 1) & 1) * p.buf16, true);
+                stage_commit(c + 1, (uint32_t)(((c + 1) & 1) * p.buf16) * 16u, true, p.ragged != 0);
                 committed = true;
             }
         }
@@ -655,16 +672,17 @@ MfmaPlan make_plan(const Geom &g, const void *Ipk)
             const int CH = 2 * ((pl.S2 + nch - 1) / nch);
             const int nchunks = (Cw2 + CH - 1) / CH;
             const size_t one = (size_t)slots * (CH + 1) * 16;
-            const int tab_len = ((taps * (CH / 2) + kRing - 1) / kRing * kRing + kRing + 3) & ~3;
+            const long long chunk_pad = ((long long)taps * (CH / 2) + kRing - 1) / kRing * kRing;
+            const long long tab_len = (nchunks * chunk_pad + kRing + 3) & ~3LL;   // = tile_steps, rounded up
             const size_t data = nchunks > 1 ? 2 * one : one;
-            const size_t bytes = data + 2 * (size_t)tab_len * sizeof(uint32_t);
+            const size_t bytes = data + (size_t)tab_len * sizeof(uint32_t);
             if (bytes <= budget) {
                 pl.CH = CH;
                 pl.nchunks = nchunks;
                 pl.pitch16 = CH + 1;
                 pl.buf16 = nchunks > 1 ? (int)(one / 16) : 0;
                 pl.tab16 = (int)(data / 16);
-                pl.tab_len = tab_len;
+                pl.tab_len = (int)tab_len;
                 pl.lds_bytes = bytes;
                 return true;
             }
@@ -730,6 +748,8 @@ hipError_t launch_conv_mfma(const uint32_t *Ipk, const uint32_t *Wpk, const floa
     p.buf16 = pl.buf16;
     p.tab16 = pl.tab16;
     p.tab_len = pl.tab_len;
+    p.chunk_pad = pl.chunk_pad;
+    p.ragged = g.Cw % pl.CH != 0;
     p.tile_steps = pl.tile_steps;
     p.dCHV = make_fastdiv(pl.CH / pl.vw);
     p.dWp = make_fastdiv(pl.Wp);
