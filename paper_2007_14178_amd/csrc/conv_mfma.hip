@@ -66,6 +66,7 @@ struct MfmaParams {
     int nchunks;
     int pitch16;     // LDS slot pitch in 16-byte units (CH + 1, odd)
     int buf16;       // distance between the two LDS chunk buffers in 16-byte units (0: one buffer)
+    int kl16;        // start of the K / alpha area in LDS (16-byte units): behind table and patches
     int tab16;       // start of the step-offset table in LDS (16-byte units)
     int tab_len;     // its uint32 entries: one per step of the tile, a multiple of 4
     int chunk_pad;   // steps per chunk in the workspace and the table (a whole number of rings)
@@ -195,35 +196,6 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
     const int tile0 = wn ? nt0 : 0;
     const int my_nt = wn ? NT - nt0 : nt0;
 
-    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)lds;
-    uint32_t bB[kWN];   // LDS byte address of the lane's pixel, tap (0,0), k-group kg
-#pragma unroll
-    for (int j = 0; j < kWN; ++j) {
-        const int q = (tile0 + j) * 32 + l32;
-        const int qq = (j < my_nt && q < npix) ? q : 0;   // idle lanes read pixel 0 and store nothing
-        const int Rl = qq / p.OW, ox = qq - Rl * p.OW;
-        const int R = R0 + Rl;
-        const int n = R / p.OH, oy = R - n * p.OH;
-        const int srow = (n == n_first) ? (oy - oy0) * p.sh
-                                        : r0 + (n - n_first - 1) * p.RHfull + oy * p.sh;
-        bB[j] = lds_base + (uint32_t)((srow * p.Wp + ox * p.sw) * p.pitch16 + kg) * 16u;
-    }
-
-    const uint4 *Abase[kWM];   // filter operands of this wave's tiles, step 0 (wave-uniform)
-#pragma unroll
-    for (int i = 0; i < kWM; ++i) {
-        const int tile = ftile * (2 * kWM) + wm * kWM + i;
-        Abase[i] = p.Wx + ((long long)tile * p.tile_steps) * 64;
-    }
-
-    v16f acc[kWM][kWN];
-#pragma unroll
-    for (int i = 0; i < kWM; ++i)
-#pragma unroll
-        for (int j = 0; j < kWN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
     // ---- staging: packed input words of the band's rows -> FP4 in LDS, zeros outside the image ----
     typedef typename WordVec<VW>::type wvec;
     const int CHV = p.CH / VW;
@@ -342,6 +314,56 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
             put(buf_b, (uint32_t)dst * 16u, live, v);
         }
     };
+    // the band's K values and this workgroup's 128 alphas go to LDS for the last phase: fetched
+    // here, written once the staged words have been waited for anyway
+    float *const Kl = reinterpret_cast<float *>(lds + p.kl16);   // [kBandPixels], zeros past the band
+    float *const Al = Kl + kBandPixels;                            // [kFilterTile], zeros past F
+    // Fetch first, compute afterwards: the first chunk's words, the filter operands of steps 0..2,
+    // K and alpha are requested here; the table, the lane's LDS addresses and the accumulators are
+    // set up while those loads are in flight.
+    stage_issue(0);
+    float k_mine = 0.0f, a_mine = 0.0f;
+    if (tid < npix) k_mine = p.K[(long long)R0 * p.OW + tid];
+    if (tid < kFilterTile && ftile * kFilterTile + tid < p.F) a_mine = p.alpha[ftile * kFilterTile + tid];
+    v4i A[kRing][kWM];
+    uint32_t a_off = (uint32_t)lane * 16u;   // byte offset of this lane's operand of the next step to load
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)lds;
+    uint32_t bB[kWN];   // LDS byte address of the lane's pixel, tap (0,0), k-group kg
+#pragma unroll
+    for (int j = 0; j < kWN; ++j) {
+        const int q = (tile0 + j) * 32 + l32;
+        const int qq = (j < my_nt && q < npix) ? q : 0;   // idle lanes read pixel 0 and store nothing
+        const int Rl = qq / p.OW, ox = qq - Rl * p.OW;
+        const int R = R0 + Rl;
+        const int n = R / p.OH, oy = R - n * p.OH;
+        const int srow = (n == n_first) ? (oy - oy0) * p.sh
+                                        : r0 + (n - n_first - 1) * p.RHfull + oy * p.sh;
+        bB[j] = lds_base + (uint32_t)((srow * p.Wp + ox * p.sw) * p.pitch16 + kg) * 16u;
+    }
+
+    const uint4 *Abase[kWM];   // filter operands of this wave's tiles, step 0 (wave-uniform)
+#pragma unroll
+    for (int i = 0; i < kWM; ++i) {
+        const int tile = ftile * (2 * kWM) + wm * kWM + i;
+        Abase[i] = p.Wx + ((long long)tile * p.tile_steps) * 64;
+    }
+
+    v16f acc[kWM][kWN];
+#pragma unroll
+    for (int i = 0; i < kWM; ++i)
+#pragma unroll
+        for (int j = 0; j < kWN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    // ring fill: filter operands of steps 0..2 (ordinary loads; the compiler waits for them at the pins)
+#pragma unroll
+    for (int u = 0; u < kRing - 1; ++u) {
+#pragma unroll
+        for (int i = 0; i < kWM; ++i)
+            A[u][i] = *reinterpret_cast<const v4i *>(reinterpret_cast<const char *>(Abase[i]) + a_off);
+        a_off += 1024;
+    }
     // The pixel operand of step t sits at (chunk buffer, tap(t), step-in-tap(t)) from the lane's
     // slot.  That offset is the same for every lane, so it is tabulated once per workgroup in LDS
     // (one entry per step of the tile in workspace order, in bytes) instead of being tracked with
@@ -358,8 +380,9 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
         }
         table[tt] = off * 16u;
     }
-    stage_issue(0);
     stage_commit(0, 0u, false, true);
+    Kl[tid] = k_mine;
+    if (tid < kFilterTile) Al[tid] = a_mine;
     if (p.nchunks > 1) {
         // the second buffer's slots outside the image: zero once, no chunk writes them again
 #pragma unroll
@@ -401,17 +424,8 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
 #define XNOR_ADD(DST, X, Y) asm volatile("v_add_u32 %0, %1, %2" : "=v"(DST) : "v"(X), "v"(Y))
 #define XNOR_WAIT(S) asm volatile("s_waitcnt " S)
 
-    v4i A[D][kWM], B[2][kWN];
-    uint32_t a_off = (uint32_t)lane * 16u;   // byte offset of this lane's operand of the next step to load
+    v4i B[2][kWN];
 
-    // ring fill: filter operands of steps 0..2 (ordinary loads; the compiler waits for them at the pins)
-#pragma unroll
-    for (int u = 0; u < D - 1; ++u) {
-#pragma unroll
-        for (int i = 0; i < kWM; ++i)
-            A[u][i] = *reinterpret_cast<const v4i *>(reinterpret_cast<const char *>(Abase[i]) + a_off);
-        a_off += 1024;
-    }
 #pragma unroll
     for (int u = 0; u < D - 1; ++u)
 #pragma unroll
@@ -511,12 +525,11 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
 
     // ---- step 3: out = float(dot) * K * alpha ----
     // The MFMA result has pixels along lanes and filters along registers, which would make every
-    // store a 4-byte-per-lane instruction.  Each wave instead passes its 32x32 tiles through a
-    // private LDS patch and reads them back with four consecutive pixels of one filter per lane,
-    // so that one store instruction writes eight 128-byte runs (16 bytes per lane).
+    // store a 4-byte-per-lane instruction.  Each wave instead passes its 32x32 tiles through
+    // private LDS patches and reads them back with four consecutive pixels of one filter per lane,
+    // so that one store instruction writes eight 128-byte runs (16 bytes per lane).  The band's K
+    // and the tile's alpha wait in LDS since the kernel's start (no global-load latency here).
     __syncthreads();   // all waves are done with the staged input
-    const float *__restrict__ Kp = p.K;
-    const float *__restrict__ alphap = p.alpha;
     float *__restrict__ outp = p.out;
     int32_t *__restrict__ dotp = p.dot;
     float *patch = reinterpret_cast<float *>(lds) + wave * (32 * kPatchPitch);   // + 4 waves' worth: the second patch
@@ -528,13 +541,12 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
     const int fl = lane_e >> 3;         // filter within a tile, plus 8*k
     const int l32e = lane_e & 31, kge = lane_e >> 5;
     if (my_nt > 0) {
-        // the lane's pixel quads (one per tile): position, validity, contiguity; K and alpha are
-        // fetched for all tiles first so that no load latency sits inside the store loop
-        int nvq[kWN];
+        // the lane's pixel quads (one per tile column): position, validity, contiguity, K
+        int nvq[kWN], poq[kWN];
         bool quadq[kWN];
-        long long kbaseq[kWN], obaseq[kWN];
-        int poq[kWN];
-        float kq[kWN][4], al[kWM][4];
+        long long obaseq[kWN];
+        float4 kq[kWN];
+        float al[kWM][4];
 #pragma unroll
         for (int j = 0; j < kWN; ++j) {
             const int q0 = (tile0 + j) * 32 + p4;
@@ -546,30 +558,14 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
             const int po = oy * p.OW + ox;                    // offset inside the (n, f) plane
             poq[j] = po;
             quadq[j] = nvq[j] == 4 && po + 3 < OHW;           // four pixels of one image: one 16-byte run
-            kbaseq[j] = (long long)R * p.OW + ox;             // K is dense over (n, oy, ox)
             obaseq[j] = (long long)n * p.F * OHW + po;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) kq[j][e] = e < nvq[j] ? Kp[kbaseq[j] + e] : 0.0f;
+            kq[j] = *reinterpret_cast<const float4 *>(&Kl[qc]);   // (entries past the band are zeros)
         }
 #pragma unroll
         for (int i = 0; i < kWM; ++i)
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int f = (ftile * (2 * kWM) + wm * kWM + i) * 32 + fl + 8 * k;
-                al[i][k] = f < p.F ? alphap[f] : 0.0f;
-            }
-        // Touch every preloaded value here, so that the compiler waits for these loads once, now.
-        // Otherwise it re-inserts "wait for all vector memory operations" in front of later uses
-        // (on paths where it cannot prove the loads have landed), and since stores share that
-        // counter every tile would wait for the previous tile's stores to reach memory.
-#pragma unroll
-        for (int j = 0; j < kWN; ++j)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) asm volatile("" : "+v"(kq[j][e]));
-#pragma unroll
-        for (int i = 0; i < kWM; ++i)
-#pragma unroll
-            for (int k = 0; k < 4; ++k) asm volatile("" : "+v"(al[i][k]));
+            for (int k = 0; k < 4; ++k) al[i][k] = Al[(wm * kWM + i) * 32 + fl + 8 * k];
+
         // Tiles go through two patches in turn: tile t+1 is written while the rows of tile t are on
         // their way back from LDS (LDS executes a wave's requests in order, so a patch can be
         // rewritten right after the reads of its previous tile were issued).
@@ -580,6 +576,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
                 pt[((r >> 2) * 8 + kge * 4 + (r & 3)) * kPatchPitch + l32e] = a[r];
         };
         constexpr int T = kWN * kWM;   // tile t = j * kWM + i
+        const long long plane8 = 8LL * OHW;
         write_patch(0, acc[0][0]);
 #pragma unroll
         for (int t = 0; t < T; ++t) {
@@ -587,36 +584,47 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
             if (j >= my_nt) break;
             if (t + 1 < T && (t + 1) / kWM < my_nt) write_patch(t + 1, acc[(t + 1) % kWM][(t + 1) / kWM]);
             const float *pt = patch + (t & 1) * (4 * 32 * kPatchPitch);
-            float4 d4[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k)
-                d4[k] = *reinterpret_cast<const float4 *>(&pt[(fl + 8 * k) * kPatchPitch + p4]);
-            const int nv = nvq[j];
             const int f_tile = (ftile * (2 * kWM) + wm * kWM + i) * 32;
+            const long long o0 = obaseq[j] + (long long)(f_tile + fl) * OHW;
+            // every lane of the wave has a whole quad inside one image and a real filter: straight code
+            const bool lane_fast = quadq[j] && f_tile + 32 <= p.F;
+            if (__builtin_amdgcn_ballot_w64(!lane_fast) == 0) {
+                float4 d4[4];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int f = f_tile + fl + 8 * k;
-                if (f >= p.F || nv <= 0) continue;
-                const float4 d = d4[k];
-                const float a = al[i][k];
-                const long long o = obaseq[j] + (long long)f * OHW;
-                if (quadq[j]) {
-                    *reinterpret_cast<float4 *>(outp + o) = make_float4(
-                        d.x * (kq[j][0] * a), d.y * (kq[j][1] * a), d.z * (kq[j][2] * a), d.w * (kq[j][3] * a));
+                for (int k = 0; k < 4; ++k)
+                    d4[k] = *reinterpret_cast<const float4 *>(&pt[(fl + 8 * k) * kPatchPitch + p4]);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const float4 d = d4[k];
+                    const float a = al[i][k];
+                    const long long o = o0 + k * plane8;
+                    *reinterpret_cast<float4 *>(outp + o) =
+                        make_float4(d.x * (kq[j].x * a), d.y * (kq[j].y * a), d.z * (kq[j].z * a), d.w * (kq[j].w * a));
                     if (dotp)
                         *reinterpret_cast<int4 *>(dotp + o) = make_int4((int)d.x, (int)d.y, (int)d.z, (int)d.w);
-                } else {
-                    // quad cut by the band's end or running over image boundaries: pixel e lies m
-                    // images further on (m <= 3), i.e. m*(F-1) planes beyond o + e
+                }
+            } else {
+                // tiles cut by the band's end, by an image boundary or by F: lane by lane, pixel by
+                // pixel; pixel e of a quad lies m images further on (m <= 3), i.e. m*(F-1) planes
+                // beyond o + e
+                const int nv = nvq[j];
+                const float kk[4] = {kq[j].x, kq[j].y, kq[j].z, kq[j].w};
+                const long long plane_skip = (long long)(p.F - 1) * OHW;
+#pragma nounroll
+                for (int k = 0; k < 4; ++k) {
+                    const int f = f_tile + fl + 8 * k;
+                    const float4 d = *reinterpret_cast<const float4 *>(&pt[(fl + 8 * k) * kPatchPitch + p4]);
+                    if (f >= p.F || nv <= 0) continue;
+                    const float a = Al[(wm * kWM + i) * 32 + fl + 8 * k];
+                    const long long o = o0 + k * plane8;
                     const float dd[4] = {d.x, d.y, d.z, d.w};
-                    const long long plane_skip = (long long)(p.F - 1) * OHW;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         if (e >= nv) break;
                         const int pe = poq[j] + e;
                         const int m = (pe >= OHW) + (pe >= 2 * OHW) + (pe >= 3 * OHW);
                         const long long oe = o + e + m * plane_skip;
-                        outp[oe] = dd[e] * (kq[j][e] * a);
+                        outp[oe] = dd[e] * (kk[e] * a);
                         if (dotp) dotp[oe] = (int32_t)dd[e];
                     }
                 }
@@ -628,11 +636,12 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
 // Tiling chosen on the host for one layer.
 struct MfmaPlan {
     bool ok;
-    int TH, Wp, RHfull, S2, CH, nchunks, pitch16, buf16, tab16, tab_len, slots_max, vw, chunk_pad, tile_steps;
+    int TH, Wp, RHfull, S2, CH, nchunks, pitch16, buf16, tab16, tab_len, kl16, slots_max, vw, chunk_pad, tile_steps;
     size_t lds_bytes, ws_bytes;
     int f_tiles;   // workgroup rows of kFilterTile filters
 };
 
+constexpr size_t kKAlphaBytes = (kBandPixels + kFilterTile) * sizeof(float);
 constexpr size_t kLdsTwoPerCU = 80 * 1024;
 constexpr size_t kLdsMax = 160 * 1024;
 
@@ -675,7 +684,7 @@ MfmaPlan make_plan(const Geom &g, const void *Ipk)
             const long long chunk_pad = ((long long)taps * (CH / 2) + kRing - 1) / kRing * kRing;
             const long long tab_len = (nchunks * chunk_pad + kRing + 3) & ~3LL;   // = tile_steps, rounded up
             const size_t data = nchunks > 1 ? 2 * one : one;
-            const size_t bytes = data + (size_t)tab_len * sizeof(uint32_t);
+            const size_t bytes = data + (size_t)tab_len * sizeof(uint32_t) + kKAlphaBytes;
             if (bytes <= budget) {
                 pl.CH = CH;
                 pl.nchunks = nchunks;
@@ -690,7 +699,10 @@ MfmaPlan make_plan(const Geom &g, const void *Ipk)
         return false;
     };
     if (!fit(kLdsTwoPerCU) && !fit(kLdsMax)) return pl;
-    pl.lds_bytes = std::max(pl.lds_bytes, (size_t)2 * 4 * 32 * kPatchPitch * sizeof(float));   // output patches
+    // K and alpha sit behind the staging area and behind the output patches (which reuse its start)
+    const size_t ka_off = std::max(pl.lds_bytes - kKAlphaBytes, (size_t)2 * 4 * 32 * kPatchPitch * sizeof(float));
+    pl.kl16 = (int)(ka_off / 16);
+    pl.lds_bytes = ka_off + kKAlphaBytes;
     if ((long long)slots * pl.CH >= (1 << 20)) return pl;   // fast-division range
     // staging addresses are 32-bit byte offsets from the band's first image
     if ((long long)(pl.TH / g.OH + 2) * g.H * g.W * g.Cw >= (1LL << 30)) return pl;
@@ -748,6 +760,7 @@ hipError_t launch_conv_mfma(const uint32_t *Ipk, const uint32_t *Wpk, const floa
     p.buf16 = pl.buf16;
     p.tab16 = pl.tab16;
     p.tab_len = pl.tab_len;
+    p.kl16 = pl.kl16;
     p.chunk_pad = pl.chunk_pad;
     p.ragged = g.Cw % pl.CH != 0;
     p.tile_steps = pl.tile_steps;
