@@ -151,6 +151,25 @@ int xnor_conv2d_fwd(const uint32_t *Ipk, const uint32_t *Wpk, const float *K, co
  * (0 if no kernel for this shape uses a workspace).  Host only. */
 int xnor_conv2d_workspace_bytes(const xnor_shape *s, size_t *bytes);
 
+/*
+ * The matrix-core kernel of xnor_conv2d_fwd in two calls, for callers whose filters stay the same
+ * over many inputs (inference): xnor_filter_expand is per-model work like xnor_filter_prepare,
+ * xnor_conv2d_fwd_expanded is the per-input convolution (steps 1b-1d and 3, Eq. 11) and computes
+ * exactly what xnor_conv2d_fwd computes.
+ *   xnor_filter_expand        writes the filters' +-1 values in the kernel's operand order into
+ *                             `workspace` (xnor_conv2d_workspace_bytes bytes, 16-byte aligned);
+ *                             the contents stay valid for this shape until overwritten.
+ *   xnor_conv2d_fwd_expanded  reads that workspace instead of Wpk; it must have been filled for the
+ *                             same shape.  Other arguments as in xnor_conv2d_fwd.
+ * Both return XNOR_E_UNSUPPORTED where xnor_conv2d_workspace_bytes reports 0 and XNOR_E_WORKSPACE
+ * for a workspace that is too small.
+ */
+int xnor_filter_expand(const uint32_t *Wpk, const xnor_shape *s, void *workspace,
+                       size_t workspace_bytes, void *stream);
+int xnor_conv2d_fwd_expanded(const uint32_t *Ipk, const void *workspace, size_t workspace_bytes,
+                             const float *K, const float *alpha, const xnor_shape *s, float *out,
+                             int32_t *dot, void *stream);
+
 /* Same as xnor_conv2d_fwd, with the kernel chosen by the caller (tests and measurements run every
  * variant).  Returns XNOR_E_UNSUPPORTED if `algo` cannot run this shape, XNOR_E_WORKSPACE if it
  * needs more workspace than given; XNOR_ALGO_DIRECT runs every shape without workspace. */

@@ -80,11 +80,14 @@ def _load() -> ctypes.CDLL:
     sz = ctypes.c_size_t
     L.xnor_conv2d_fwd.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, vp]
     L.xnor_conv2d_fwd_algo.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, ci, vp]
+    L.xnor_filter_expand.argtypes = [vp, sp, vp, sz, vp]
+    L.xnor_conv2d_fwd_expanded.argtypes = [vp, vp, sz, vp, vp, sp, vp, vp, vp]
     L.xnor_conv2d_pick_algo.argtypes = [sp, sz]
     L.xnor_conv2d_workspace_bytes.argtypes = [sp, ctypes.POINTER(sz)]
     for name in ("xnor_out_dim", "xnor_packed_words", "xnor_binarize_pack", "xnor_scale_K",
                  "xnor_alpha", "xnor_conv2d_fwd", "xnor_conv2d_fwd_algo", "xnor_conv2d_pick_algo",
-                 "xnor_conv2d_workspace_bytes", "xnor_input_prepare", "xnor_filter_prepare"):
+                 "xnor_conv2d_workspace_bytes", "xnor_input_prepare", "xnor_filter_prepare",
+                 "xnor_filter_expand", "xnor_conv2d_fwd_expanded"):
         getattr(L, name).restype = ci
     return L
 
@@ -230,4 +233,32 @@ def xnor_conv2d_fwd(Ipk: torch.Tensor, Wpk: torch.Tensor, K: torch.Tensor, alpha
         ctypes.byref(s.c()), _dev(out, torch.float32, oshape, "out"),
         _dev(dot, torch.int32, oshape, "dot") if dot is not None else None,
         ws_ptr, ws_bytes, algo, _stream()), f"xnor_conv2d_fwd[{ALGO_NAMES.get(algo, algo)}]")
+    return out, dot
+
+
+def xnor_filter_expand(Wpk: torch.Tensor, s: Shape, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """Per-model half of the matrix-core convolution: fills (and returns) the workspace."""
+    if workspace is None:
+        workspace = torch.empty((xnor_conv2d_workspace_bytes(s),), dtype=torch.uint8, device=Wpk.device)
+    _ok(lib.xnor_filter_expand(_dev(Wpk, torch.int32, (s.F, s.kh, s.kw, s.Cw), "Wpk"), ctypes.byref(s.c()),
+                               _dev(workspace, torch.uint8, name="workspace"), workspace.numel(), _stream()),
+        "xnor_filter_expand")
+    return workspace
+
+
+def xnor_conv2d_fwd_expanded(Ipk: torch.Tensor, workspace: torch.Tensor, K: torch.Tensor, alpha: torch.Tensor,
+                             s: Shape, out: torch.Tensor | None = None, dot: torch.Tensor | None = None,
+                             want_dot: bool = False):
+    """Per-input half: the convolution on a workspace filled by xnor_filter_expand for this shape."""
+    OH, OW = xnor_out_dim(s)
+    oshape = (s.N, s.F, OH, OW)
+    if out is None:
+        out = torch.empty(oshape, dtype=torch.float32, device=Ipk.device)
+    if dot is None and want_dot:
+        dot = torch.empty(oshape, dtype=torch.int32, device=Ipk.device)
+    _ok(lib.xnor_conv2d_fwd_expanded(
+        _dev(Ipk, torch.int32, (s.N, s.H, s.W, s.Cw), "Ipk"), _dev(workspace, torch.uint8, name="workspace"),
+        workspace.numel(), _dev(K, torch.float32, (s.N, OH, OW), "K"), _dev(alpha, torch.float32, (s.F,), "alpha"),
+        ctypes.byref(s.c()), _dev(out, torch.float32, oshape, "out"),
+        _dev(dot, torch.int32, oshape, "dot") if dot is not None else None, _stream()), "xnor_conv2d_fwd_expanded")
     return out, dot

@@ -732,22 +732,24 @@ size_t conv_mfma_workspace_bytes(const Geom &g)
     return pl.ok ? pl.ws_bytes : 0;
 }
 
-hipError_t launch_conv_mfma(const uint32_t *Ipk, const uint32_t *Wpk, const float *K,
-                            const float *alpha, const Geom &g, float *out, int32_t *dot,
-                            void *workspace, hipStream_t st)
+hipError_t launch_expand_filters(const uint32_t *Wpk, const Geom &g, void *workspace, hipStream_t st)
+{
+    const MfmaPlan pl = make_plan(g, nullptr);   // the workspace layout does not depend on alignment
+    if (!pl.ok) return hipErrorInvalidValue;
+    const long long wx_items = (long long)(pl.ws_bytes / sizeof(uint4));
+    expand_filters_kernel<<<ceil_div(wx_items, 256), 256, 0, st>>>(
+        Wpk, static_cast<uint4 *>(workspace), g.F, g.C, g.Cw, g.kh * g.kw, pl.CH, pl.nchunks, pl.chunk_pad,
+        pl.tile_steps, 2 * pl.S2, wx_items);
+    return hipGetLastError();
+}
+
+hipError_t launch_conv_mfma_expanded(const uint32_t *Ipk, const float *K, const float *alpha,
+                                     const Geom &g, float *out, int32_t *dot, const void *workspace,
+                                     hipStream_t st)
 {
     const MfmaPlan pl = make_plan(g, Ipk);
     if (!pl.ok) return hipErrorInvalidValue;
-    const int taps = g.kh * g.kw;
-
-    // filters -> FP4 in A-operand order (per call: the library keeps no state)
-    uint4 *Wx = static_cast<uint4 *>(workspace);
-    const long long wx_items = (long long)(pl.ws_bytes / sizeof(uint4));
-    expand_filters_kernel<<<ceil_div(wx_items, 256), 256, 0, st>>>(
-        Wpk, Wx, g.F, g.C, g.Cw, taps, pl.CH, pl.nchunks, pl.chunk_pad, pl.tile_steps, 2 * pl.S2,
-        wx_items);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    const uint4 *Wx = static_cast<const uint4 *>(workspace);
 
     MfmaParams p{};
     p.Ipk = Ipk; p.Wx = Wx; p.K = K; p.alpha = alpha; p.out = out; p.dot = dot;
@@ -793,6 +795,19 @@ hipError_t launch_conv_mfma(const uint32_t *Ipk, const uint32_t *Wpk, const floa
         case 2: return launch(conv_mfma_kernel<2>);
         default: return launch(conv_mfma_kernel<1>);
     }
+}
+
+}  // namespace xnor
+
+namespace xnor {
+
+hipError_t launch_conv_mfma(const uint32_t *Ipk, const uint32_t *Wpk, const float *K,
+                            const float *alpha, const Geom &g, float *out, int32_t *dot,
+                            void *workspace, hipStream_t st)
+{
+    // filters -> FP4 in A-operand order, then the convolution
+    const hipError_t e = launch_expand_filters(Wpk, g, workspace, st);
+    return e != hipSuccess ? e : launch_conv_mfma_expanded(Ipk, K, alpha, g, out, dot, workspace, st);
 }
 
 }  // namespace xnor

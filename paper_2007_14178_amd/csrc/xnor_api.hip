@@ -210,6 +210,37 @@ int xnor_conv2d_fwd_algo(const uint32_t *Ipk, const uint32_t *Wpk, const float *
     }
 }
 
+int xnor_filter_expand(const uint32_t *Wpk, const xnor_shape *s, void *workspace,
+                       size_t workspace_bytes, void *stream)
+{
+    if (!Wpk || !s || !workspace) return XNOR_E_NULL;
+    xnor::Geom g;
+    const int rc = make_geom(s, &g);
+    if (rc) return rc;
+    if (!aligned(Wpk, 4) || !aligned(workspace, 16)) return XNOR_E_ALIGN;
+    const size_t need = xnor::conv_mfma_workspace_bytes(g);
+    if (need == 0) return XNOR_E_UNSUPPORTED;
+    if (workspace_bytes < need) return XNOR_E_WORKSPACE;
+    return hip_status(xnor::launch_expand_filters(Wpk, g, workspace, (hipStream_t)stream));
+}
+
+int xnor_conv2d_fwd_expanded(const uint32_t *Ipk, const void *workspace, size_t workspace_bytes,
+                             const float *K, const float *alpha, const xnor_shape *s, float *out,
+                             int32_t *dot, void *stream)
+{
+    if (!Ipk || !workspace || !K || !alpha || !s || !out) return XNOR_E_NULL;
+    xnor::Geom g;
+    const int rc = make_geom(s, &g);
+    if (rc) return rc;
+    if (!aligned(Ipk, 4) || !aligned(K, 4) || !aligned(alpha, 4) || !aligned(out, 4) ||
+        (dot && !aligned(dot, 4)) || !aligned(workspace, 16))
+        return XNOR_E_ALIGN;
+    const size_t need = xnor::conv_mfma_workspace_bytes(g);
+    if (need == 0) return XNOR_E_UNSUPPORTED;
+    if (workspace_bytes < need) return XNOR_E_WORKSPACE;
+    return hip_status(xnor::launch_conv_mfma_expanded(Ipk, K, alpha, g, out, dot, workspace, (hipStream_t)stream));
+}
+
 int xnor_conv2d_fwd(const uint32_t *Ipk, const uint32_t *Wpk, const float *K, const float *alpha,
                     const xnor_shape *s, float *out, int32_t *dot, void *workspace,
                     size_t workspace_bytes, void *stream)

@@ -98,6 +98,14 @@ def test_null_and_alignment_rejected(xb):
     assert need > 0 and need % 1024 == 0
     assert xb.xnor_conv2d_pick_algo(s, need) == xb.ALGO_MFMA
     assert xb.xnor_conv2d_pick_algo(s, need - 1) != xb.ALGO_MFMA
+    # the two-call form of the matrix-core path
+    assert L.xnor_filter_expand(None, sp, ok, need, None) == xb.E_NULL
+    assert L.xnor_filter_expand(ok, sp, None, need, None) == xb.E_NULL
+    assert L.xnor_filter_expand(ok, sp, ctypes.c_void_p(0x1008), need, None) == xb.E_ALIGN
+    assert L.xnor_filter_expand(ok, sp, ok, need - 1, None) == xb.E_WORKSPACE
+    assert L.xnor_conv2d_fwd_expanded(ok, None, need, ok, ok, sp, ok, None, None) == xb.E_NULL
+    assert L.xnor_conv2d_fwd_expanded(ok, ok, need - 1, ok, ok, sp, ok, None, None) == xb.E_WORKSPACE
+    assert L.xnor_conv2d_fwd_expanded(odd, ok, need, ok, ok, sp, ok, None, None) == xb.E_ALIGN
 
 
 def test_binding_refuses_cpu_tensors(xb):

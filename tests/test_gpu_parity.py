@@ -230,3 +230,26 @@ def test_dot_null_gives_same_out(xb):
                 continue
             raise
         assert b[-1] is None and torch.equal(a[-2], b[-2])
+
+
+@pytest.mark.parametrize("shape", [(2, 96, 27, 27, 40, 5, 5, 1, 1, 2, 2), (3, 512, 14, 14, 130, 3, 3, 1, 1, 1, 1),
+                                   (1, 64, 32, 32, 64, 3, 3, 2, 2, 1, 1)], ids=lambda s: "x".join(map(str, s)))
+def test_two_call_matrix_core_path(xb, shape):
+    """xnor_filter_expand once, xnor_conv2d_fwd_expanded on two different inputs: bit-exact dots and
+    outputs within 1e-5 of the oracle, and the same bits as the one-call form."""
+    print(f"case two-call shape={shape}", flush=True)
+    rng = np.random.default_rng(zlib.crc32(("two" + str(shape)).encode()))
+    layer, I1, Wt = random_layer(rng, "t", *shape)
+    _, I2, _ = random_layer(rng, "t", *shape)
+    s = xb.Shape(*shape)
+    Wpk, alpha, _ = xb.xnor_filter_prepare(dev(Wt))
+    ws = xb.xnor_filter_expand(Wpk, s)
+    for I in (I1, I2):
+        Ipk, K, _ = xb.xnor_input_prepare(dev(I), s)
+        out, dot = xb.xnor_conv2d_fwd_expanded(Ipk, ws, K, alpha, s, want_dot=True)
+        out1, dot1 = xb.xnor_conv2d_fwd(Ipk, Wpk, K, alpha, s, want_dot=True, algo=xb.ALGO_MFMA)
+        torch.cuda.synchronize()
+        d_ref, K_ref, a_ref, O_ref = oracle.forward(I, Wt, oshape(layer))
+        assert np.array_equal(dot.cpu().numpy(), d_ref), "dot"
+        assert_rel(out.cpu().numpy(), O_ref, "out")
+        assert torch.equal(out, out1) and torch.equal(dot, dot1)
