@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--algo", default="auto", choices=["auto", "direct", "tiled", "mfma"])
     ap.add_argument("--unfused", action="store_true", help="run the four pre-stage calls separately")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="not the benchmark line: one JSON line per (layer, conv kernel) for all 11 layers, no CPU baseline")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run three plain 1 GiB device copies before the timed loop (calibrates the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run against known traffic)")
@@ -70,24 +72,8 @@ def cpu_baseline(layer, Wt, target_s: float):
                       f"pass (sign conv + K + alpha + rescale), {t:.2f} s"}
 
 
-def main():
-    args = parse()
-    world = int(os.environ.get("WORLD_SIZE", "1"))
-    if args.gpus != 1 or world != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
-              "run it with --gpus 1", file=sys.stderr)
-        sys.exit(2)
-
-    import torch
-    from paper_2007_14178_amd import binding as xb
-    from paper_2007_14178_amd.workloads import LAYERS, make_input, make_weights
-
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(2)
-    torch.cuda.set_device(0)
-    layer = LAYERS[args.layer]
-    algo = {"auto": xb.ALGO_AUTO, "direct": xb.ALGO_DIRECT, "tiled": xb.ALGO_TILED, "mfma": xb.ALGO_MFMA}[args.algo]
+def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
+    algo = {"auto": xb.ALGO_AUTO, "direct": xb.ALGO_DIRECT, "tiled": xb.ALGO_TILED, "mfma": xb.ALGO_MFMA}[algo_name]
     s = xb.Shape(layer.N, layer.C, layer.H, layer.W, layer.F, layer.kh, layer.kw,
                  layer.sh, layer.sw, layer.ph, layer.pw)
     OH, OW = xb.xnor_out_dim(s)
@@ -157,6 +143,34 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
+    # The small layers finish faster than the host can issue five launches: with --sweep the step is
+    # also captured into a HIP graph (the library allocates nothing and records no memset), each
+    # replay is checked against the eager result, and the replay time is reported beside the eager one.
+    graph_ms, graph_ok = None, None
+    if args.sweep:
+        eager = out.clone()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.current_stream().wait_stream(side)
+        graph_ok = True
+        for _ in range(3):
+            out.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            graph_ok = graph_ok and bool(torch.equal(out, eager))
+        g0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - g0) / args.steps * 1e3
+        del graph
+
     ms_per_step = elapsed / args.steps * 1e3
     stage_ms = {n: sum(m[i].elapsed_time(m[i + 1]) for m in events) / len(events) for i, n in enumerate(names)}
     conv_ms = stage_ms["conv"]
@@ -193,13 +207,45 @@ def main():
         "config": {"workload": f"{layer.name}: N={layer.N} C={layer.C} {layer.H}x{layer.W} F={layer.F} "
                                f"{layer.kh}x{layer.kw} stride {layer.sh} pad {layer.ph}",
                    "binary_macs": macs, "conv_algo": xb.ALGO_NAMES[used_algo],
-                   "buffers": "reused every step (input 205 MB + output 205 MB at c5 fit the 256 MB "
-                              "last-level cache only in part)"},
+                   "buffers": f"reused every step (fp32 input {dI.numel() * 4 / 1e6:.1f} MB, output "
+                              f"{out.numel() * 4 / 1e6:.1f} MB; the last-level cache holds 256 MB)"},
         "stage_ms": stage_ms,
+        **({"graph_ms_per_step": graph_ms, "graph_replays_match_eager": graph_ok} if args.sweep else {}),
         "roofline": roof,
     }
+    rec["_Wt_host"] = Wt_host
+    del dI, out
+    return rec
+
+
+def main():
+    args = parse()
+    world = int(os.environ.get("WORLD_SIZE", "1"))
+    if args.gpus != 1 or world != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2007_14178_amd import binding as xb
+    from paper_2007_14178_amd.workloads import LAYERS, make_input, make_weights
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    layers = list(LAYERS) if args.sweep else [args.layer]
+    algos = ["tiled", "mfma"] if args.sweep else [args.algo]
+    for lname in layers:
+        for aname in algos:
+            rec = run_layer(args, xb, torch, LAYERS[lname], aname, make_input, make_weights)
+            Wt_host = rec.pop("_Wt_host")
+            if args.sweep:
+                print(json.dumps(rec), flush=True)
+    if args.sweep:
+        return
+    layer = LAYERS[args.layer]
     if not args.no_cpu_baseline:
-        del dI, out
         rec["cpu_baseline"] = cpu_baseline(layer, Wt_host, args.cpu_seconds)
     print(json.dumps(rec), flush=True)
 
