@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true",
                     help="not the benchmark line: one JSON line per (layer, conv kernel) for all 11 layers, no CPU baseline")
+    ap.add_argument("--chain", action="store_true",
+                    help="not the benchmark line: time the layer as a chained one (K from a given A, convolution with "
+                         "packed-sign + channel-mean output; no fp32 tensor read or written)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run three plain 1 GiB device copies before the timed loop (calibrates the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run against known traffic)")
@@ -94,9 +97,18 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
     M = torch.empty((s.F, s.kh, s.kw), dtype=torch.float32, device="cuda")
     # with the matrix-core kernel the convolution is two calls, so that the timed "conv" stage is
     # that one kernel launch (what the roofline figures are about)
-    two_phase = used_algo == xb.ALGO_MFMA
-    names = (["pack_I", "scale_K", "alpha", "pack_W"] if args.unfused else ["input_prepare", "filter_prepare"]) + \
-            (["filter_expand", "conv"] if two_phase else ["conv"])
+    two_phase = used_algo == xb.ALGO_MFMA and not args.chain
+    if args.chain:
+        xb.xnor_input_prepare(dI, s, Ipk, A, K)
+        xb.xnor_filter_prepare(dW, Wpk, M, alpha)
+        Opk = torch.empty((s.N, OH, OW, (s.F + 31) // 32), dtype=torch.int32, device="cuda")
+        A_next = torch.empty((s.N, OH, OW), dtype=torch.float32, device="cuda")
+        ws = torch.empty((xb.xnor_conv2d_chain_workspace_bytes(s),), dtype=torch.uint8, device="cuda")
+    if args.chain:
+        names = ["box_filter_K", "conv"]
+    else:
+        names = (["pack_I", "scale_K", "alpha", "pack_W"] if args.unfused else ["input_prepare", "filter_prepare"]) + \
+                (["filter_expand", "conv"] if two_phase else ["conv"])
 
     def step(events=None):
         marks = []
@@ -107,6 +119,13 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
                 e.record()                      # recorded on the stream the kernels are launched on
                 marks.append(e)
 
+        if args.chain:
+            mark(); xb.xnor_box_filter_K(A, s, K)
+            mark(); xb.xnor_conv2d_fwd_chain(Ipk, Wpk, K, alpha, s, Opk, A_next, ws)
+            mark()
+            if events is not None:
+                events.append(marks)
+            return
         if args.unfused:
             mark(); xb.xnor_binarize_pack(dI, Ipk)
             mark(); xb.xnor_scale_K(dI, s, A, K)
@@ -198,7 +217,8 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
     roof["hbm_frac"] = roof["hbm_gbs"] / PEAK_HBM_GBS
 
     rec = {
-        "metric": "binary GMAC/s, whole forward pass (pack + K + alpha + XNOR conv + rescale)",
+        "metric": ("binary GMAC/s, chained layer (K from A + XNOR conv emitting packed signs and channel mean)" if args.chain
+                   else "binary GMAC/s, whole forward pass (pack + K + alpha + XNOR conv + rescale)"),
         "pre_stages": "separate calls" if args.unfused else "one pass over I, one pass over Wt",
         "value": value, "unit": "binary GMAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,

@@ -170,6 +170,33 @@ int xnor_conv2d_fwd_expanded(const uint32_t *Ipk, const void *workspace, size_t 
                              const float *K, const float *alpha, const xnor_shape *s, float *out,
                              int32_t *dot, void *stream);
 
+/*
+ * Chained layers (the paper's closing proposal, Sec. V: "passing the binary outputs to the next
+ * kernel without integer conversion").  When the consumer of this layer's output O (Eq. 11) is
+ * another binary convolution, all it needs of O is what xnor_input_prepare would compute from it:
+ * the packed signs of O along its channels (= this layer's filters) and the channel mean of |O|
+ * (Eq. 10).  xnor_conv2d_fwd_chain produces exactly these and never writes the fp32 O:
+ *   Opk     out  uint32 [N][OH][OW][ceil(F/32)]  = xnor_binarize_pack(O): bit = (O >= 0) with
+ *                O = float(dot) * (K * alpha) formed in fp32 as in xnor_conv2d_fwd; tail bits 0
+ *   A_next  out  fp32   [N][OH][OW]              = (1/F) sum_f |O[n][f][oy][ox]|
+ *   workspace    caller-owned, 16-byte aligned, xnor_conv2d_chain_workspace_bytes bytes (filter
+ *                expansion plus per-filter-tile partial sums); contents mean nothing afterwards.
+ * The next layer continues with xnor_box_filter_K(A_next, its shape, K) and a convolution on Opk.
+ * Runs on the matrix-core kernel only: XNOR_E_UNSUPPORTED where
+ * xnor_conv2d_chain_workspace_bytes reports 0, XNOR_E_WORKSPACE for a workspace that is too small.
+ */
+int xnor_conv2d_chain_workspace_bytes(const xnor_shape *s, size_t *bytes);
+int xnor_conv2d_fwd_chain(const uint32_t *Ipk, const uint32_t *Wpk, const float *K, const float *alpha,
+                          const xnor_shape *s, uint32_t *Opk, float *A_next, void *workspace,
+                          size_t workspace_bytes, void *stream);
+
+/*
+ * Second half of Eq. 10 on its own: K = box filter of a given A (taps 1/(kh*kw), zero outside the
+ * image, the convolution's stride and padding), for callers that already hold A (chained layers).
+ *   A  in   fp32 [N][H][W]      K  out  fp32 [N][OH][OW]      (s->C and s->F are not used)
+ */
+int xnor_box_filter_K(const float *A, const xnor_shape *s, float *K, void *stream);
+
 /* Same as xnor_conv2d_fwd, with the kernel chosen by the caller (tests and measurements run every
  * variant).  Returns XNOR_E_UNSUPPORTED if `algo` cannot run this shape, XNOR_E_WORKSPACE if it
  * needs more workspace than given; XNOR_ALGO_DIRECT runs every shape without workspace. */

@@ -82,12 +82,16 @@ def _load() -> ctypes.CDLL:
     L.xnor_conv2d_fwd_algo.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, ci, vp]
     L.xnor_filter_expand.argtypes = [vp, sp, vp, sz, vp]
     L.xnor_conv2d_fwd_expanded.argtypes = [vp, vp, sz, vp, vp, sp, vp, vp, vp]
+    L.xnor_box_filter_K.argtypes = [vp, sp, vp, vp]
+    L.xnor_conv2d_chain_workspace_bytes.argtypes = [sp, ctypes.POINTER(sz)]
+    L.xnor_conv2d_fwd_chain.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, vp]
     L.xnor_conv2d_pick_algo.argtypes = [sp, sz]
     L.xnor_conv2d_workspace_bytes.argtypes = [sp, ctypes.POINTER(sz)]
     for name in ("xnor_out_dim", "xnor_packed_words", "xnor_binarize_pack", "xnor_scale_K",
                  "xnor_alpha", "xnor_conv2d_fwd", "xnor_conv2d_fwd_algo", "xnor_conv2d_pick_algo",
                  "xnor_conv2d_workspace_bytes", "xnor_input_prepare", "xnor_filter_prepare",
-                 "xnor_filter_expand", "xnor_conv2d_fwd_expanded"):
+                 "xnor_filter_expand", "xnor_conv2d_fwd_expanded", "xnor_box_filter_K",
+                 "xnor_conv2d_chain_workspace_bytes", "xnor_conv2d_fwd_chain"):
         getattr(L, name).restype = ci
     return L
 
@@ -262,3 +266,39 @@ def xnor_conv2d_fwd_expanded(Ipk: torch.Tensor, workspace: torch.Tensor, K: torc
         ctypes.byref(s.c()), _dev(out, torch.float32, oshape, "out"),
         _dev(dot, torch.int32, oshape, "dot") if dot is not None else None, _stream()), "xnor_conv2d_fwd_expanded")
     return out, dot
+
+
+def xnor_box_filter_K(A: torch.Tensor, s: Shape, K: torch.Tensor | None = None) -> torch.Tensor:
+    """K [N][OH][OW] from a given A [N][H][W] (second half of Eq. 10)."""
+    OH, OW = xnor_out_dim(s)
+    if K is None:
+        K = torch.empty((s.N, OH, OW), dtype=torch.float32, device=A.device)
+    _ok(lib.xnor_box_filter_K(_dev(A, torch.float32, (s.N, s.H, s.W), "A"), ctypes.byref(s.c()),
+                              _dev(K, torch.float32, (s.N, OH, OW), "K"), _stream()), "xnor_box_filter_K")
+    return K
+
+
+def xnor_conv2d_chain_workspace_bytes(s: Shape) -> int:
+    n = ctypes.c_size_t()
+    _ok(lib.xnor_conv2d_chain_workspace_bytes(ctypes.byref(s.c()), ctypes.byref(n)), "xnor_conv2d_chain_workspace_bytes")
+    return n.value
+
+
+def xnor_conv2d_fwd_chain(Ipk: torch.Tensor, Wpk: torch.Tensor, K: torch.Tensor, alpha: torch.Tensor, s: Shape,
+                          Opk: torch.Tensor | None = None, A_next: torch.Tensor | None = None,
+                          workspace: torch.Tensor | None = None):
+    """Returns (Opk int32-typed words [N][OH][OW][ceil(F/32)], A_next fp32 [N][OH][OW])."""
+    OH, OW = xnor_out_dim(s)
+    Cwn = (s.F + 31) // 32
+    if Opk is None:
+        Opk = torch.empty((s.N, OH, OW, Cwn), dtype=torch.int32, device=Ipk.device)
+    if A_next is None:
+        A_next = torch.empty((s.N, OH, OW), dtype=torch.float32, device=Ipk.device)
+    if workspace is None:
+        workspace = torch.empty((xnor_conv2d_chain_workspace_bytes(s),), dtype=torch.uint8, device=Ipk.device)
+    _ok(lib.xnor_conv2d_fwd_chain(
+        _dev(Ipk, torch.int32, (s.N, s.H, s.W, s.Cw), "Ipk"), _dev(Wpk, torch.int32, (s.F, s.kh, s.kw, s.Cw), "Wpk"),
+        _dev(K, torch.float32, (s.N, OH, OW), "K"), _dev(alpha, torch.float32, (s.F,), "alpha"), ctypes.byref(s.c()),
+        _dev(Opk, torch.int32, (s.N, OH, OW, Cwn), "Opk"), _dev(A_next, torch.float32, (s.N, OH, OW), "A_next"),
+        _dev(workspace, torch.uint8, name="workspace"), workspace.numel(), _stream()), "xnor_conv2d_fwd_chain")
+    return Opk, A_next

@@ -56,6 +56,9 @@ struct MfmaParams {
     const float *K, *alpha;
     float *out;
     int32_t *dot;
+    uint32_t *Opk;   // chained form: packed signs of the output [N][OH][OW][Cwn] ...
+    float *P;        // ... and per (pixel, filter tile) sums of |out| [N*OH*OW][f_tiles]
+    int Cwn, f_tiles;
     int N, C, H, W, F, kh, kw, sh, sw, ph, pw, OH, OW, Cw;
     int TH;          // output rows (of the whole batch) per band
     int total_rows;  // N*OH
@@ -156,7 +159,7 @@ struct WordVec<4> { typedef uint32_t type __attribute__((ext_vector_type(4))); }
 // all (chunk, tap, 64-channel step) of the tile; the filter operands stream linearly from the
 // workspace through a register ring that runs kRing-1 steps ahead across chunk boundaries; the
 // pixel operands come from LDS one step ahead.
-template <int VW>
+template <int VW, bool CHAIN>
 __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
 {
     extern __shared__ uint4 lds[];
@@ -530,6 +533,72 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
     // so that one store instruction writes eight 128-byte runs (16 bytes per lane).  The band's K
     // and the tile's alpha wait in LDS since the kernel's start (no global-load latency here).
     __syncthreads();   // all waves are done with the staged input
+    if constexpr (CHAIN) {
+        // Chained form (the paper's closing proposal, Sec. V: hand the binary output to the next
+        // layer without the conversion to real values).  The next layer needs of this output O only
+        // sign(O) packed along its channels (= these filters) and the channel mean of |O| (Eq. 10).
+        // Both come straight from the accumulators: lane l holds pixel l%32 of a tile and, in
+        // register r, filter 8*(r/4) + 4*(l/32) + r%4, so a lane builds half of a 32-filter word,
+        // its partner lane l^32 the other half.  o = float(dot) * (K * alpha) is formed exactly as
+        // in the fp32 output, the bit is (o >= 0) and |o| is summed in double.
+        int lane_c = lane;
+        asm volatile("" : "+v"(lane_c));
+        const int l32c = lane_c & 31, kgc = lane_c >> 5;
+        const float *Kl = reinterpret_cast<const float *>(lds + p.kl16);
+        const float *Al = Kl + kBandPixels;
+        double *Ps = reinterpret_cast<double *>(lds);          // [2 wave rows][kBandPixels]
+        float al[kWM][16];
+#pragma unroll
+        for (int i = 0; i < kWM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) al[i][r] = Al[(wm * kWM + i) * 32 + 8 * (r >> 2) + 4 * kgc + (r & 3)];
+#pragma unroll
+        for (int j = 0; j < kWN; ++j) {
+            if (j >= my_nt) break;
+            const int q = (tile0 + j) * 32 + l32c;
+            const bool valid = q < npix;
+            const float kv = Kl[valid ? q : 0];
+            double asum = 0.0;
+            uint32_t word[kWM];
+#pragma unroll
+            for (int i = 0; i < kWM; ++i) {
+                const int f_tile = (ftile * (2 * kWM) + wm * kWM + i) * 32;
+                uint32_t w = 0;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = 8 * (r >> 2) + 4 * kgc + (r & 3);
+                    const float o = acc[i][j][r] * (kv * al[i][r]);
+                    if (f_tile + row < p.F) {              // bits and sums of filters that exist only
+                        w |= (o >= 0.0f ? 1u : 0u) << row;
+                        asum += (double)fabsf(o);
+                    }
+                }
+                word[i] = w | (uint32_t)__shfl_xor((int)w, 32);
+            }
+            asum += __shfl_xor(asum, 32);
+            if (valid && kgc == 0) {
+                const long long pix = (long long)R0 * p.OW + q;      // pixels of a band are consecutive
+#pragma unroll
+                for (int i = 0; i < kWM; ++i) {
+                    const int wi = ftile * (2 * kWM) + wm * kWM + i;
+                    if (wi < p.Cwn) p.Opk[pix * p.Cwn + wi] = word[i];
+                }
+                Ps[wm * kBandPixels + q] = asum;
+            }
+        }
+        __syncthreads();
+        if (wm == 0) {
+#pragma unroll
+            for (int j = 0; j < kWN; ++j) {
+                if (j >= my_nt) break;
+                const int q = (tile0 + j) * 32 + l32c;
+                if (q < npix && kgc == 0)
+                    p.P[((long long)R0 * p.OW + q) * p.f_tiles + ftile] =
+                        (float)(Ps[q] + Ps[kBandPixels + q]);
+            }
+        }
+        return;
+    }
     float *__restrict__ outp = p.out;
     int32_t *__restrict__ dotp = p.dot;
     float *patch = reinterpret_cast<float *>(lds) + wave * (32 * kPatchPitch);   // + 4 waves' worth: the second patch
@@ -743,9 +812,9 @@ hipError_t launch_expand_filters(const uint32_t *Wpk, const Geom &g, void *works
     return hipGetLastError();
 }
 
-hipError_t launch_conv_mfma_expanded(const uint32_t *Ipk, const float *K, const float *alpha,
-                                     const Geom &g, float *out, int32_t *dot, const void *workspace,
-                                     hipStream_t st)
+static hipError_t launch_mfma(const uint32_t *Ipk, const float *K, const float *alpha, const Geom &g,
+                              float *out, int32_t *dot, uint32_t *Opk, float *P, const void *workspace,
+                              hipStream_t st)
 {
     const MfmaPlan pl = make_plan(g, Ipk);
     if (!pl.ok) return hipErrorInvalidValue;
@@ -753,6 +822,7 @@ hipError_t launch_conv_mfma_expanded(const uint32_t *Ipk, const float *K, const 
 
     MfmaParams p{};
     p.Ipk = Ipk; p.Wx = Wx; p.K = K; p.alpha = alpha; p.out = out; p.dot = dot;
+    p.Opk = Opk; p.P = P; p.Cwn = (g.F + 31) / 32; p.f_tiles = pl.f_tiles;
     p.N = g.N; p.C = g.C; p.H = g.H; p.W = g.W; p.F = g.F; p.kh = g.kh; p.kw = g.kw;
     p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw; p.OH = g.OH; p.OW = g.OW; p.Cw = g.Cw;
     p.TH = pl.TH;
@@ -790,11 +860,59 @@ hipError_t launch_conv_mfma_expanded(const uint32_t *Ipk, const float *K, const 
         kernel<<<grid, 256, pl.lds_bytes, st>>>(p);
         return hipGetLastError();
     };
-    switch (pl.vw) {
-        case 4: return launch(conv_mfma_kernel<4>);
-        case 2: return launch(conv_mfma_kernel<2>);
-        default: return launch(conv_mfma_kernel<1>);
+    if (Opk) {
+        switch (pl.vw) {
+            case 4: return launch(conv_mfma_kernel<4, true>);
+            case 2: return launch(conv_mfma_kernel<2, true>);
+            default: return launch(conv_mfma_kernel<1, true>);
+        }
     }
+    switch (pl.vw) {
+        case 4: return launch(conv_mfma_kernel<4, false>);
+        case 2: return launch(conv_mfma_kernel<2, false>);
+        default: return launch(conv_mfma_kernel<1, false>);
+    }
+}
+
+hipError_t launch_conv_mfma_expanded(const uint32_t *Ipk, const float *K, const float *alpha,
+                                     const Geom &g, float *out, int32_t *dot, const void *workspace,
+                                     hipStream_t st)
+{
+    return launch_mfma(Ipk, K, alpha, g, out, dot, nullptr, nullptr, workspace, st);
+}
+
+// Eq. 10's channel mean for the next layer from the per-filter-tile sums: A[pix] = sum_t P[pix][t] / F
+__global__ __launch_bounds__(256) void chain_mean_kernel(const float *__restrict__ P, long long npix,
+                                                         int f_tiles, int F, float *__restrict__ A)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= npix) return;
+    double sum = 0.0;
+    for (int t = 0; t < f_tiles; ++t) sum += (double)P[i * f_tiles + t];
+    A[i] = (float)(sum / (double)F);
+}
+
+size_t conv_mfma_chain_workspace_bytes(const Geom &g)
+{
+    const MfmaPlan pl = make_plan(g, nullptr);
+    if (!pl.ok) return 0;
+    return pl.ws_bytes + (size_t)g.N * g.OH * g.OW * pl.f_tiles * sizeof(float);
+}
+
+hipError_t launch_conv_mfma_chain(const uint32_t *Ipk, const uint32_t *Wpk, const float *K,
+                                  const float *alpha, const Geom &g, uint32_t *Opk, float *A_next,
+                                  void *workspace, hipStream_t st)
+{
+    const MfmaPlan pl = make_plan(g, nullptr);
+    if (!pl.ok) return hipErrorInvalidValue;
+    float *P = reinterpret_cast<float *>(static_cast<char *>(workspace) + pl.ws_bytes);
+    hipError_t e = launch_expand_filters(Wpk, g, workspace, st);
+    if (e != hipSuccess) return e;
+    e = launch_mfma(Ipk, K, alpha, g, nullptr, nullptr, Opk, P, workspace, st);
+    if (e != hipSuccess) return e;
+    const long long npix = (long long)g.N * g.OH * g.OW;
+    chain_mean_kernel<<<ceil_div(npix, 256), 256, 0, st>>>(P, npix, pl.f_tiles, g.F, A_next);
+    return hipGetLastError();
 }
 
 }  // namespace xnor

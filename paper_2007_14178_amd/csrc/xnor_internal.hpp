@@ -46,6 +46,10 @@ hipError_t launch_expand_filters(const uint32_t *Wpk, const Geom &g, void *works
 hipError_t launch_conv_mfma_expanded(const uint32_t *Ipk, const float *K, const float *alpha,
                                      const Geom &g, float *out, int32_t *dot, const void *workspace,
                                      hipStream_t st);
+size_t conv_mfma_chain_workspace_bytes(const Geom &g);   // 0 if the shape is not supported
+hipError_t launch_conv_mfma_chain(const uint32_t *Ipk, const uint32_t *Wpk, const float *K,
+                                  const float *alpha, const Geom &g, uint32_t *Opk, float *A_next,
+                                  void *workspace, hipStream_t st);
 hipError_t launch_conv_mfma(const uint32_t *Ipk, const uint32_t *Wpk, const float *K,
                             const float *alpha, const Geom &g, float *out, int32_t *dot,
                             void *workspace, hipStream_t st);

@@ -4,7 +4,7 @@ conv_mfma_kernel issues its operand loads from inline-asm statements and waits f
 own s_waitcnt counts.  The compiler does not know that those registers have loads in flight, so
 the kernel is only correct if no compiler-generated instruction reads one of them before the asm
 statement that waits.  This test compiles the kernel to assembly and checks exactly that, for the
-three staging widths: inside the MFMA loop region
+three staging widths and both epilogues: inside the MFMA loop region
 
   * no instruction outside the asm statements reads a register that an MFMA uses as an A / B operand
     (the filter ring, the pixel operands), and
@@ -57,9 +57,10 @@ def asm_text():
         return open(out).read()
 
 
+@pytest.mark.parametrize("chain", [0, 1])
 @pytest.mark.parametrize("vw", [4, 2, 1])
-def test_no_compiler_read_of_registers_with_loads_in_flight(asm_text, vw):
-    name = f"conv_mfma_kernelILi{vw}EEE"
+def test_no_compiler_read_of_registers_with_loads_in_flight(asm_text, vw, chain):
+    name = f"conv_mfma_kernelILi{vw}ELb{chain}EEE"
     start = next(m.start() for m in re.finditer(r"^_ZN\S*" + name + r"\S*:", asm_text, re.M))
     body = asm_text[start:asm_text.index("s_endpgm", start)]
     lines = body.split("\n")
