@@ -106,6 +106,15 @@ def test_null_and_alignment_rejected(xb):
     assert L.xnor_conv2d_fwd_expanded(ok, None, need, ok, ok, sp, ok, None, None) == xb.E_NULL
     assert L.xnor_conv2d_fwd_expanded(ok, ok, need - 1, ok, ok, sp, ok, None, None) == xb.E_WORKSPACE
     assert L.xnor_conv2d_fwd_expanded(odd, ok, need, ok, ok, sp, ok, None, None) == xb.E_ALIGN
+    # chained form
+    cneed = xb.xnor_conv2d_chain_workspace_bytes(s)
+    assert cneed > need
+    assert L.xnor_conv2d_fwd_chain(ok, ok, ok, ok, sp, None, ok, ok, cneed, None) == xb.E_NULL
+    assert L.xnor_conv2d_fwd_chain(ok, ok, ok, ok, sp, ok, ok, None, cneed, None) == xb.E_NULL
+    assert L.xnor_conv2d_fwd_chain(ok, ok, ok, ok, sp, ok, ok, ok, cneed - 1, None) == xb.E_WORKSPACE
+    assert L.xnor_conv2d_fwd_chain(ok, ok, ok, ok, sp, odd, ok, ok, cneed, None) == xb.E_ALIGN
+    assert L.xnor_box_filter_K(None, sp, ok, None) == xb.E_NULL
+    assert L.xnor_box_filter_K(ok, sp, odd, None) == xb.E_ALIGN
 
 
 def test_binding_refuses_cpu_tensors(xb):
