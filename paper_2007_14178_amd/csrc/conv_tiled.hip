@@ -1,17 +1,19 @@
 // XNOR + popcount convolution on the vector ALU (Sec. III-A steps 1b-1d and 3, Eq. 11), tiled.
 //
 // Two lane-ops retire 32 binary MACs: v_xor_b32 with the filter word as a wave-uniform SGPR operand,
-// then v_bcnt_u32_b32, which adds the popcount into its accumulator.  Everything else is arranged so
-// that little more than those two instructions issues in the inner loop:
-//   * a workgroup stages the packed words of a 2-D input tile (with halo) once in LDS, zero outside
-//     the image, and walks over 4 waves x Q filters per pass with that tile resident;
+// then v_bcnt_u32_b32, which adds the popcount into its accumulator.  Everything else is arranged so that little more than those two
+// instructions issues in the inner loop:
+//   * a workgroup stages the packed words of a 2-D input tile (with halo) once in LDS and walks
+//     over 4 waves x Q filters per pass with that tile resident;
 //   * a lane owns P output pixels and Q filter accumulators per pass (P*Q independent v_bcnt chains);
 //     each LDS read of 4 channel words feeds 4*Q xor/bcnt pairs;
 //   * filter words are fetched with scalar loads (one s_load_dwordx4 per filter and word quad).
 // Zero padding: a zero-filled halo word makes popcount(0 xor w) = popcount(w) instead of nothing, so
-// border pixels subtract the popcounts of the filter words of their out-of-image taps afterwards
-// (a table of per-(filter, tap) popcounts, built only by tiles that touch the border).  Then
+// after each tap the pixels for which it lies outside the image subtract that tap's popcount(w),
+// which the scalar ALU sums on the side from the same scalar-loaded filter words.  Then
 //   dot = C * (#in-image taps) - 2 * popcount,   out = float(dot) * K * alpha.
+// P is chosen per layer (3, 4 or 7) so that whole tile rows fill the 64*P pixel slots well
+// (28x28 -> 14 rows of 28 in 448 slots, 13x13 -> 169 of 192, 56x56 -> 8 rows of 56 in 448).
 // The paper's kernel keeps one channel's 8x4 spatial tile per register and masks all but kh*kw
 // bits of every popcount; here every bit of every word is a channel of the contraction.
 #include <algorithm>
@@ -21,9 +23,7 @@
 namespace xnor {
 namespace {
 
-constexpr int kP = 4;             // pixels per lane
 constexpr int kQ = 8;             // filters per wave and pass
-constexpr int kTilePixels = 64 * kP;
 constexpr int kPassFilters = 4 * kQ;
 constexpr size_t kLdsBudget = 64 * 1024;
 
@@ -34,17 +34,16 @@ struct TiledParams {
     int tiles_x, tiles_y;
     int pitch;           // LDS words per staged pixel
     int f_per_wg;        // filters handled by one workgroup (a multiple of kPassFilters)
-    int popw_off;        // LDS word offset of the per-(filter, tap) popcount table
 };
 
-template <int VW>
+template <int VW, int kP>
 __global__ __launch_bounds__(256) void conv_tiled_kernel(
     // separate __restrict__ arguments (not struct members): only then may the compiler fetch the
     // filter words with scalar loads while the kernel also stores to `out`
     const uint32_t *__restrict__ Ipk, const uint32_t *__restrict__ Wpk, const float *__restrict__ K,
     const float *__restrict__ alpha, float *__restrict__ out, int32_t *__restrict__ dot, TiledParams p)
 {
-    extern __shared__ uint32_t smem[];
+    extern __shared__ __align__(16) uint32_t smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int taps = p.kh * p.kw;
@@ -72,6 +71,7 @@ __global__ __launch_bounds__(256) void conv_tiled_kernel(
 
     // ---- the lane's pixels ----
     int base[kP], oyv[kP], oxv[kP];
+    int klo_y[kP], khi_y[kP], klo_x[kP], khi_x[kP];   // the taps of pixel k that lie inside the image
     bool ok[kP];
 #pragma unroll
     for (int k = 0; k < kP; ++k) {
@@ -81,25 +81,13 @@ __global__ __launch_bounds__(256) void conv_tiled_kernel(
         oxv[k] = ox0 + lx;
         ok[k] = ly < p.TH && oyv[k] < p.OH && oxv[k] < p.OW;
         base[k] = ok[k] ? (ly * p.sh * p.RW + lx * p.sw) * p.pitch : 0;
+        klo_y[k] = max(0, p.ph - oyv[k] * p.sh); khi_y[k] = min(p.kh, p.H + p.ph - oyv[k] * p.sh);
+        klo_x[k] = max(0, p.pw - oxv[k] * p.sw); khi_x[k] = min(p.kw, p.W + p.pw - oxv[k] * p.sw);
     }
-    uint32_t *popw = smem + p.popw_off;   // [kPassFilters][taps]
+    __syncthreads();   // staged tile ready
 
     const int f_wg0 = blockIdx.y * p.f_per_wg;
     for (int f_pass = f_wg0; f_pass < min(p.F, f_wg0 + p.f_per_wg); f_pass += kPassFilters) {
-        __syncthreads();   // staged tile ready / previous pass done with the popcount table
-        if (border) {
-            for (int e = tid; e < kPassFilters * taps; e += 256) {
-                const int fl = e / taps, tap = e - fl * taps;
-                const int f = f_pass + fl;
-                uint32_t s = 0;
-                if (f < p.F) {
-                    const uint32_t *w = Wpk + ((long long)f * taps + tap) * p.Cw;
-                    for (int k = 0; k < p.Cw; ++k) s += __popc(w[k]);
-                }
-                popw[e] = s;
-            }
-            __syncthreads();
-        }
         const int f0 = f_pass + wave * kQ;   // this wave's filters (wave-uniform)
         uint32_t acc[kP][kQ];
 #pragma unroll
@@ -108,67 +96,86 @@ __global__ __launch_bounds__(256) void conv_tiled_kernel(
             for (int q = 0; q < kQ; ++q) acc[k][q] = 0;
 
         if (f0 < p.F) {
+            // this wave's filters: words of filter q from fbase[q], [tap][Cw] contiguous; filters
+            // past F re-read the last filter (their sums are never stored)
+            const uint32_t *fbase[kQ];
+#pragma unroll
+            for (int q = 0; q < kQ; ++q) fbase[q] = Wpk + (long long)min(f0 + q, p.F - 1) * taps * p.Cw;
+            typedef uint32_t wvec __attribute__((ext_vector_type(VW)));
+            auto load_w = [&](int q, int woff) -> wvec { return *reinterpret_cast<const wvec *>(fbase[q] + woff); };
+            // The filter words of step i+1 are requested (scalar loads) before the lane-ops of step
+            // i are issued, so that their latency hides behind 2*P*Q*VW vector instructions.
+            const int last_woff = taps * p.Cw - VW;
+            wvec nxt[kQ];
+#pragma unroll
+            for (int q = 0; q < kQ; ++q) nxt[q] = load_w(q, 0);
+            int woff = 0;
             for (int ky = 0; ky < p.kh; ++ky)
                 for (int kx = 0; kx < p.kw; ++kx) {
-                    const int tap = ky * p.kw + kx;
                     const int toff = (ky * p.RW + kx) * p.pitch;
+                    uint32_t spop[kQ];   // popcount of this tap's words of filter q (scalar ALU)
+#pragma unroll
+                    for (int q = 0; q < kQ; ++q) spop[q] = 0;
                     for (int w = 0; w < p.Cw; w += VW) {
                         uint32_t x[kP][VW];
 #pragma unroll
                         for (int k = 0; k < kP; ++k) {
                             if constexpr (VW == 4) {
-                                const uint4 v = *reinterpret_cast<const uint4 *>(&smem[base[k] + toff + w]);
+                                // (index arithmetic in 16-byte units: the type then carries the alignment
+                                // that lets this be one ds_read_b128; pitch is a multiple of 4 words here)
+                                const uint4 v = reinterpret_cast<const uint4 *>(smem)[(base[k] >> 2) + (toff >> 2) + (w >> 2)];
                                 x[k][0] = v.x; x[k][1] = v.y; x[k][2] = v.z; x[k][3] = v.w;
                             } else {
                                 x[k][0] = smem[base[k] + toff + w];
                             }
                         }
+                        wvec cur[kQ];
+                        woff = min(woff + VW, last_woff);
 #pragma unroll
                         for (int q = 0; q < kQ; ++q) {
-                            // filters past F re-read the last filter (their sums are never stored)
-                            const int f = min(f0 + q, p.F - 1);
-                            const uint32_t *wp = Wpk + ((long long)f * taps + tap) * p.Cw + w;
+                            cur[q] = nxt[q];
+                            nxt[q] = load_w(q, woff);
+                        }
+#pragma unroll
+                        for (int q = 0; q < kQ; ++q) {
                             uint32_t wv[VW];
-                            if constexpr (VW == 4) {
-                                const uint4 v = *reinterpret_cast<const uint4 *>(wp);   // scalar load
-                                wv[0] = v.x; wv[1] = v.y; wv[2] = v.z; wv[3] = v.w;
-                            } else {
-                                wv[0] = *wp;
-                            }
+                            if constexpr (VW == 4) { wv[0] = cur[q].x; wv[1] = cur[q].y; wv[2] = cur[q].z; wv[3] = cur[q].w; }
+                            else { wv[0] = cur[q][0]; }
 #pragma unroll
                             for (int k = 0; k < kP; ++k)
 #pragma unroll
                                 for (int e = 0; e < VW; ++e) acc[k][q] += __popc(x[k][e] ^ wv[e]);
+#pragma unroll
+                            for (int e = 0; e < VW; ++e) spop[q] += __popc(wv[e]);
+                        }
+                    }
+                    // Zero padding: the staged halo words are 0, so an out-of-image tap has just
+                    // added popcount(0 xor w) = popcount(w); take it back for the pixels concerned
+                    // (tiles that touch the image border only: 2 lane-ops per accumulator and tap
+                    // against 2 * Cw in the loop above).
+                    if (border) {
+#pragma unroll
+                        for (int k = 0; k < kP; ++k) {
+                            const bool inside = ky >= klo_y[k] && ky < khi_y[k] && kx >= klo_x[k] && kx < khi_x[k];
+#pragma unroll
+                            for (int q = 0; q < kQ; ++q) acc[k][q] -= inside ? 0u : spop[q];
                         }
                     }
                 }
         }
 
-        // ---- step 3: border correction, dot, rescale ----
+        // ---- step 3: dot, rescale ----
 #pragma unroll
         for (int k = 0; k < kP; ++k) {
             if (!ok[k] || f0 >= p.F) continue;
             const int oy = oyv[k], ox = oxv[k];
-            const int ky_lo = max(0, p.ph - oy * p.sh), ky_hi = min(p.kh, p.H + p.ph - oy * p.sh);
-            const int kx_lo = max(0, p.pw - ox * p.sw), kx_hi = min(p.kw, p.W + p.pw - ox * p.sw);
-            const int valid = max(0, ky_hi - ky_lo) * max(0, kx_hi - kx_lo);
-            uint32_t corr[kQ];
-#pragma unroll
-            for (int q = 0; q < kQ; ++q) corr[q] = 0;
-            if (valid != taps) {
-                for (int ky = 0; ky < p.kh; ++ky)
-                    for (int kx = 0; kx < p.kw; ++kx) {
-                        if (ky >= ky_lo && ky < ky_hi && kx >= kx_lo && kx < kx_hi) continue;
-#pragma unroll
-                        for (int q = 0; q < kQ; ++q) corr[q] += popw[(wave * kQ + q) * taps + ky * p.kw + kx];
-                    }
-            }
+            const int valid = max(0, khi_y[k] - klo_y[k]) * max(0, khi_x[k] - klo_x[k]);
             const float kv = K[((long long)n * p.OH + oy) * p.OW + ox];
 #pragma unroll
             for (int q = 0; q < kQ; ++q) {
                 const int f = f0 + q;
                 if (f >= p.F) break;
-                const int d = p.C * valid - 2 * (int)(acc[k][q] - corr[q]);
+                const int d = p.C * valid - 2 * (int)acc[k][q];
                 const long long o = (((long long)n * p.F + f) * p.OH + oy) * p.OW + ox;
                 out[o] = (float)d * (kv * alpha[f]);
                 if (dot) dot[o] = d;
@@ -179,45 +186,55 @@ __global__ __launch_bounds__(256) void conv_tiled_kernel(
 
 struct TiledPlan {
     bool ok;
-    int TH, TW, RH, RW, tiles_x, tiles_y, pitch, vw, f_per_wg, popw_off;
+    int kp, TH, TW, RH, RW, tiles_x, tiles_y, pitch, vw, f_per_wg;
     size_t lds_bytes;
 };
 
+constexpr int kPixelsPerLane[] = {3, 4, 7};   // the instantiated values of P
+
 TiledPlan make_plan(const Geom &g, const void *Ipk, const void *Wpk)
 {
-    TiledPlan pl{};
-    pl.TW = std::min(g.OW, 64);
-    pl.TH = std::max(1, std::min(g.OH, kTilePixels / pl.TW));
+    TiledPlan best{};
     const uintptr_t al = reinterpret_cast<uintptr_t>(Ipk) | reinterpret_cast<uintptr_t>(Wpk);
-    pl.vw = (g.Cw % 4 == 0 && (al & 15) == 0) ? 4 : 1;
+    const int vw = (g.Cw % 4 == 0 && (al & 15) == 0) ? 4 : 1;
     // LDS words per staged pixel: an odd number of 16-byte units (VW = 4) or an odd number of words
-    pl.pitch = pl.vw == 4 ? (g.Cw | 4) : (g.Cw | 1);
-    const int taps = g.kh * g.kw;
-    // shrink the tile until it fits LDS (wide channels / big kernels)
-    for (;;) {
-        pl.RH = (pl.TH - 1) * g.sh + g.kh;
-        pl.RW = (pl.TW - 1) * g.sw + g.kw;
-        const size_t words = (size_t)pl.RH * pl.RW * pl.pitch + (size_t)kPassFilters * taps + 4;
-        if (words * 4 <= kLdsBudget) {
-            pl.popw_off = (pl.RH * pl.RW * pl.pitch + 3) & ~3;
-            pl.lds_bytes = ((size_t)pl.popw_off + (size_t)kPassFilters * taps) * 4;
-            break;
+    const int pitch = vw == 4 ? (g.Cw | 4) : (g.Cw | 1);
+    double best_fill = 0.0;
+    for (const int kp : kPixelsPerLane) {
+        TiledPlan pl{};
+        pl.kp = kp; pl.vw = vw; pl.pitch = pitch;
+        pl.TW = std::min(g.OW, 64);
+        pl.TH = std::max(1, std::min(g.OH, 64 * kp / pl.TW));
+        pl.TH = ceil_div(g.OH, ceil_div(g.OH, pl.TH));   // same number of tiles, rows spread evenly
+        // shrink the tile until it fits LDS (wide channels / big kernels)
+        bool fits = true;
+        for (;;) {
+            pl.RH = (pl.TH - 1) * g.sh + g.kh;
+            pl.RW = (pl.TW - 1) * g.sw + g.kw;
+            pl.lds_bytes = (size_t)pl.RH * pl.RW * pitch * 4;
+            if (pl.lds_bytes <= kLdsBudget) break;
+            if (pl.TH > 1) pl.TH = (pl.TH + 1) / 2;
+            else if (pl.TW > 1) pl.TW = (pl.TW + 1) / 2;
+            else { fits = false; break; }   // one pixel's receptive field does not fit
         }
-        if (pl.TH > 1) pl.TH = (pl.TH + 1) / 2;
-        else if (pl.TW > 1) pl.TW = (pl.TW + 1) / 2;
-        else return pl;   // one pixel's receptive field does not fit: the direct kernel takes it
+        if (!fits) continue;
+        pl.tiles_x = ceil_div(g.OW, pl.TW);
+        pl.tiles_y = ceil_div(g.OH, pl.TH);
+        const long long tiles = (long long)g.N * pl.tiles_x * pl.tiles_y;
+        if (tiles > 0x7fffffffLL) continue;
+        // fraction of the pixel slots that hold an output pixel; ties go to the smaller P
+        const double fill = (double)g.OH * g.OW / ((double)pl.tiles_x * pl.tiles_y * 64 * kp);
+        if (fill <= best_fill + 1e-9) continue;
+        // split the filters over workgroups until the grid has a few workgroups per CU
+        const int passes = ceil_div(g.F, kPassFilters);
+        int split = 1;
+        while (split < passes && tiles * split < 4 * 256) ++split;
+        pl.f_per_wg = ceil_div(passes, split) * kPassFilters;
+        pl.ok = true;
+        best = pl;
+        best_fill = fill;
     }
-    pl.tiles_x = ceil_div(g.OW, pl.TW);
-    pl.tiles_y = ceil_div(g.OH, pl.TH);
-    const long long tiles = (long long)g.N * pl.tiles_x * pl.tiles_y;
-    if (tiles > 0x7fffffffLL) return pl;
-    // split the filters over workgroups until the grid has a few workgroups per CU
-    const int passes = ceil_div(g.F, kPassFilters);
-    int split = 1;
-    while (split < passes && tiles * split < 4 * 256) ++split;
-    pl.f_per_wg = ceil_div(passes, split) * kPassFilters;
-    pl.ok = true;
-    return pl;
+    return best;
 }
 
 }  // namespace
@@ -235,13 +252,24 @@ hipError_t launch_conv_tiled(const uint32_t *Ipk, const uint32_t *Wpk, const flo
     p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw; p.OH = g.OH; p.OW = g.OW; p.Cw = g.Cw;
     p.TH = pl.TH; p.TW = pl.TW; p.RH = pl.RH; p.RW = pl.RW;
     p.tiles_x = pl.tiles_x; p.tiles_y = pl.tiles_y;
-    p.pitch = pl.pitch; p.f_per_wg = pl.f_per_wg; p.popw_off = pl.popw_off;
+    p.pitch = pl.pitch; p.f_per_wg = pl.f_per_wg;
     const dim3 grid(g.N * pl.tiles_x * pl.tiles_y, ceil_div(g.F, pl.f_per_wg));
-    if (pl.vw == 4)
-        conv_tiled_kernel<4><<<grid, 256, pl.lds_bytes, st>>>(Ipk, Wpk, K, alpha, out, dot, p);
-    else
-        conv_tiled_kernel<1><<<grid, 256, pl.lds_bytes, st>>>(Ipk, Wpk, K, alpha, out, dot, p);
-    return hipGetLastError();
+    auto launch = [&](auto kernel) {
+        kernel<<<grid, 256, pl.lds_bytes, st>>>(Ipk, Wpk, K, alpha, out, dot, p);
+        return hipGetLastError();
+    };
+    if (pl.vw == 4) {
+        switch (pl.kp) {
+            case 3: return launch(conv_tiled_kernel<4, 3>);
+            case 4: return launch(conv_tiled_kernel<4, 4>);
+            default: return launch(conv_tiled_kernel<4, 7>);
+        }
+    }
+    switch (pl.kp) {
+        case 3: return launch(conv_tiled_kernel<1, 3>);
+        case 4: return launch(conv_tiled_kernel<1, 4>);
+        default: return launch(conv_tiled_kernel<1, 7>);
+    }
 }
 
 }  // namespace xnor
