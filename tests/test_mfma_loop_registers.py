@@ -75,7 +75,14 @@ def test_no_compiler_read_of_registers_with_loads_in_flight(asm_text, vw, chain)
 
     # region: from the barrier that ends the first staging to the last MFMA
     region_start = max(i for i in range(mfma[0]) if lines[i].strip().startswith("s_barrier"))
-    in_asm, fetch_in_flight, fetched = False, False, set()
+    # Linear scan in program order.  A register is "loaded" from the asm load that writes it until a
+    # compiler-generated instruction overwrites it (the compiler reuses the pixel / ring registers as
+    # temporaries while they are dead, which is fine: nothing is in flight to them then); reading a
+    # "loaded" register outside the asm statements is the offence.  At the region's start every
+    # operand register counts as loaded.
+    in_asm = False
+    loaded = set(operand_regs)
+    fetched = set()                                    # staged input words with a fetch in flight
     offenders = []
     for i in range(region_start, mfma[-1] + 1):
         text = lines[i].strip()
@@ -88,17 +95,21 @@ def test_no_compiler_read_of_registers_with_loads_in_flight(asm_text, vw, chain)
         if not text or text.startswith(";") or text.endswith(":") or text.startswith("."):
             continue
         if in_asm:
-            if text.startswith("global_load"):
+            if text.startswith(("global_load", "ds_read")):
                 dst = _regs(text.split(",")[0])
-                if not dst & operand_regs:             # staged input words, not the filter ring
-                    fetched |= dst
-                    fetch_in_flight = True
+                if text.startswith("global_load") and not dst & operand_regs:
+                    fetched |= dst                     # staged input words, not the filter ring
+                else:
+                    loaded |= dst
             elif text.startswith("s_waitcnt") and ("vmcnt(6)" in text or "vmcnt(0)" in text):
-                fetch_in_flight, fetched = False, set()
+                fetched = set()
             continue
         src = _sources(text)
-        if i >= mfma[0] and src & operand_regs:
-            offenders.append((i, text, "reads an MFMA operand register"))
-        if fetch_in_flight and src & fetched:
+        if i >= mfma[0] and src & loaded:
+            offenders.append((i, text, "reads a register loaded by an asm statement"))
+        if src & fetched:
             offenders.append((i, text, "reads a staged-word register before its wait"))
+        parts = text.split(None, 1)
+        if len(parts) == 2 and not parts[0].startswith(("ds_write", "global_store", "scratch_store", "s_", "v_cmp")):
+            loaded -= _regs(parts[1].split(",")[0])    # overwritten by the compiler: a temporary now
     assert not offenders, offenders[:10]
