@@ -257,10 +257,24 @@ __global__ __launch_bounds__(256) void filter_pack_mean_kernel(
             const int nb = min(32, nch - 32 * w);
             uint32_t word = 0;
             double acc = 0.0;
-            for (int j = 0; j < nb; ++j) {
-                const float v = stage[(32 * w + j) * taps + tap];
-                word |= (v >= 0.0f ? 1u : 0u) << j;
-                acc += (double)fabsf(v);
+            if (nb == 32) {
+                // whole word: all 32 LDS reads in flight at once, four independent partial sums
+                float v[32];
+#pragma unroll
+                for (int j = 0; j < 32; ++j) v[j] = stage[(32 * w + j) * taps + tap];
+                double a4[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+                for (int j = 0; j < 32; ++j) {
+                    word |= (v[j] >= 0.0f ? 1u : 0u) << j;
+                    a4[j & 3] += (double)fabsf(v[j]);
+                }
+                acc = (a4[0] + a4[1]) + (a4[2] + a4[3]);
+            } else {
+                for (int j = 0; j < nb; ++j) {
+                    const float v = stage[(32 * w + j) * taps + tap];
+                    word |= (v >= 0.0f ? 1u : 0u) << j;
+                    acc += (double)fabsf(v);
+                }
             }
             dst[tap * Cw + c0 / 32 + w] = word;
             part[it] = acc;
