@@ -50,8 +50,13 @@ class Shape:
     pw: int = 0
 
     def c(self) -> CShape:
-        return CShape(self.N, self.C, self.H, self.W, self.F, self.kh, self.kw,
-                      self.sh, self.sw, self.ph, self.pw)
+        # (built once per Shape: the struct is read-only on the C side)
+        cs = self.__dict__.get("_c")
+        if cs is None:
+            cs = CShape(self.N, self.C, self.H, self.W, self.F, self.kh, self.kw,
+                        self.sh, self.sw, self.ph, self.pw)
+            object.__setattr__(self, "_c", cs)
+        return cs
 
     @property
     def Cw(self) -> int:
@@ -117,9 +122,13 @@ def _ok(status: int, where: str):
 
 
 def xnor_out_dim(s: Shape) -> tuple[int, int]:
-    oh, ow = ctypes.c_int(), ctypes.c_int()
-    _ok(lib.xnor_out_dim(ctypes.byref(s.c()), ctypes.byref(oh), ctypes.byref(ow)), "xnor_out_dim")
-    return oh.value, ow.value
+    dims = s.__dict__.get("_out_dim")       # asked on every call: remembered per Shape
+    if dims is None:
+        oh, ow = ctypes.c_int(), ctypes.c_int()
+        _ok(lib.xnor_out_dim(ctypes.byref(s.c()), ctypes.byref(oh), ctypes.byref(ow)), "xnor_out_dim")
+        dims = (oh.value, ow.value)
+        object.__setattr__(s, "_out_dim", dims)
+    return dims
 
 
 def xnor_packed_words(C: int) -> int:

@@ -1,7 +1,8 @@
 """GPU parity: every C-ABI call against the CPU oracle, element by element, same seeded inputs.
 
 Bars: packed words and raw binary dot products bit-exact; A, K, alpha and the fp32 output within
-1e-5 relative of the oracle (and exactly 0 where the oracle is 0).
+1e-5 relative of the oracle (one fp32 subnormal spacing where that is larger; exactly 0 where the
+oracle is 0).
 """
 import zlib
 
@@ -27,7 +28,9 @@ def assert_rel(got: np.ndarray, ref: np.ndarray, what: str):
     got = got.astype(np.float64); ref = ref.astype(np.float64)
     assert got.shape == ref.shape, what
     err = np.abs(got - ref)
-    bad = err > RTOL * np.abs(ref)
+    # below fp32's normal range the spacing of representable values (2^-149) exceeds RTOL*|ref|:
+    # there the bar is the nearest representable value
+    bad = err > np.maximum(RTOL * np.abs(ref), 2.0 ** -149)
     assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} outside {RTOL} rel; worst {err.max()}"
     assert np.array_equal(got == 0, ref == 0), f"{what}: zero pattern differs"
 
@@ -129,6 +132,8 @@ SHAPES = [
     (1, 512, 28, 28, 96, 3, 3, 1, 1, 1, 1),
     (2, 128, 56, 56, 32, 7, 7, 1, 1, 3, 3),
     (1, 160, 6, 40, 130, 1, 3, 1, 2, 0, 1),
+    (1, 1, 256, 256, 1, 3, 3, 1, 1, 1, 1),     # the paper's own workload shape (Tables I-III): one channel, one filter
+    (2, 3, 300, 200, 2, 3, 3, 1, 1, 1, 1),     # rows wider than one band of the matrix-core kernel
 ]
 
 
