@@ -197,6 +197,27 @@ int xnor_conv2d_fwd_chain(const uint32_t *Ipk, const uint32_t *Wpk, const float 
  */
 int xnor_box_filter_K(const float *A, const xnor_shape *s, float *K, void *stream);
 
+/*
+ * The whole forward pass in one call for images with few channels: first layers, and the workload
+ * the paper times (Sec. IV, Tables I-III: one channel, a 3x3 filter, 256^2 ... 2048^2 pixels).
+ * Computes exactly what xnor_input_prepare + xnor_conv2d_fwd compute -- the signs of I (step 1a),
+ * K (Eq. 10, steps 2a-2b), the binary dot products over spatially packed windows (Sec. III-B,
+ * steps 1b-1d) and the rescale (step 3, Eq. 11) -- from one read of the fp32 image, with nothing
+ * intermediate written to memory.
+ *   I      in   fp32 [N][C][H][W]
+ *   Wpk    in   uint32 [F][kh][kw][1]   packed filter signs (xnor_filter_prepare / xnor_binarize_pack)
+ *   alpha  in   fp32 [F]
+ *   out    out  fp32 [N][F][OH][OW]
+ *   dot    out  int32 [N][F][OH][OW] or NULL
+ * Takes 1 <= C <= 4, kh = kw in {3, 5, 7}, stride 1, any padding; XNOR_E_UNSUPPORTED otherwise
+ * (xnor_forward_image_supported: 1 if the shape is taken, 0 if not, negative status for a bad shape).
+ * K is formed in fp32 from fp32 partial sums (row sums, then their sum): within kw*C + kh roundings
+ * of the exact value.
+ */
+int xnor_forward_image_supported(const xnor_shape *s);
+int xnor_forward_image(const float *I, const uint32_t *Wpk, const float *alpha, const xnor_shape *s,
+                       float *out, int32_t *dot, void *stream);
+
 /* Same as xnor_conv2d_fwd, with the kernel chosen by the caller (tests and measurements run every
  * variant).  Returns XNOR_E_UNSUPPORTED if `algo` cannot run this shape, XNOR_E_WORKSPACE if it
  * needs more workspace than given; XNOR_ALGO_DIRECT runs every shape without workspace. */

@@ -90,13 +90,16 @@ def _load() -> ctypes.CDLL:
     L.xnor_box_filter_K.argtypes = [vp, sp, vp, vp]
     L.xnor_conv2d_chain_workspace_bytes.argtypes = [sp, ctypes.POINTER(sz)]
     L.xnor_conv2d_fwd_chain.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, vp]
+    L.xnor_forward_image_supported.argtypes = [sp]
+    L.xnor_forward_image.argtypes = [vp, vp, vp, sp, vp, vp, vp]
     L.xnor_conv2d_pick_algo.argtypes = [sp, sz]
     L.xnor_conv2d_workspace_bytes.argtypes = [sp, ctypes.POINTER(sz)]
     for name in ("xnor_out_dim", "xnor_packed_words", "xnor_binarize_pack", "xnor_scale_K",
                  "xnor_alpha", "xnor_conv2d_fwd", "xnor_conv2d_fwd_algo", "xnor_conv2d_pick_algo",
                  "xnor_conv2d_workspace_bytes", "xnor_input_prepare", "xnor_filter_prepare",
                  "xnor_filter_expand", "xnor_conv2d_fwd_expanded", "xnor_box_filter_K",
-                 "xnor_conv2d_chain_workspace_bytes", "xnor_conv2d_fwd_chain"):
+                 "xnor_conv2d_chain_workspace_bytes", "xnor_conv2d_fwd_chain",
+                 "xnor_forward_image_supported", "xnor_forward_image"):
         getattr(L, name).restype = ci
     return L
 
@@ -274,6 +277,30 @@ def xnor_conv2d_fwd_expanded(Ipk: torch.Tensor, workspace: torch.Tensor, K: torc
         workspace.numel(), _dev(K, torch.float32, (s.N, OH, OW), "K"), _dev(alpha, torch.float32, (s.F,), "alpha"),
         ctypes.byref(s.c()), _dev(out, torch.float32, oshape, "out"),
         _dev(dot, torch.int32, oshape, "dot") if dot is not None else None, _stream()), "xnor_conv2d_fwd_expanded")
+    return out, dot
+
+
+def xnor_forward_image_supported(s: Shape) -> bool:
+    rc = lib.xnor_forward_image_supported(ctypes.byref(s.c()))
+    if rc < 0:
+        _ok(rc, "xnor_forward_image_supported")
+    return bool(rc)
+
+
+def xnor_forward_image(I: torch.Tensor, Wpk: torch.Tensor, alpha: torch.Tensor, s: Shape,
+                       out: torch.Tensor | None = None, dot: torch.Tensor | None = None,
+                       want_dot: bool = False):
+    """Whole forward pass for a few-channel image in one kernel. Returns (out, dot or None)."""
+    OH, OW = xnor_out_dim(s)
+    oshape = (s.N, s.F, OH, OW)
+    if out is None:
+        out = torch.empty(oshape, dtype=torch.float32, device=I.device)
+    if dot is None and want_dot:
+        dot = torch.empty(oshape, dtype=torch.int32, device=I.device)
+    _ok(lib.xnor_forward_image(
+        _dev(I, torch.float32, (s.N, s.C, s.H, s.W), "I"), _dev(Wpk, torch.int32, (s.F, s.kh, s.kw, s.Cw), "Wpk"),
+        _dev(alpha, torch.float32, (s.F,), "alpha"), ctypes.byref(s.c()), _dev(out, torch.float32, oshape, "out"),
+        _dev(dot, torch.int32, oshape, "dot") if dot is not None else None, _stream()), "xnor_forward_image")
     return out, dot
 
 

@@ -220,6 +220,29 @@ int xnor_box_filter_K(const float *A, const xnor_shape *s, float *K, void *strea
     return hip_status(xnor::launch_box_filter_K(A, g, K, (hipStream_t)stream));
 }
 
+int xnor_forward_image_supported(const xnor_shape *s)
+{
+    if (!s) return XNOR_E_NULL;
+    xnor::Geom g;
+    const int rc = make_geom(s, &g);
+    if (rc) return rc;
+    return xnor::conv_image_supports(g) ? 1 : 0;
+}
+
+int xnor_forward_image(const float *I, const uint32_t *Wpk, const float *alpha, const xnor_shape *s,
+                       float *out, int32_t *dot, void *stream)
+{
+    if (!I || !Wpk || !alpha || !s || !out) return XNOR_E_NULL;
+    xnor::Geom g;
+    const int rc = make_geom(s, &g);
+    if (rc) return rc;
+    if (!aligned(I, 4) || !aligned(Wpk, 4) || !aligned(alpha, 4) || !aligned(out, 4) ||
+        (dot && !aligned(dot, 4)))
+        return XNOR_E_ALIGN;
+    if (!xnor::conv_image_supports(g)) return XNOR_E_UNSUPPORTED;
+    return hip_status(xnor::launch_conv_image(I, Wpk, alpha, g, out, dot, (hipStream_t)stream));
+}
+
 int xnor_conv2d_chain_workspace_bytes(const xnor_shape *s, size_t *bytes)
 {
     if (!s || !bytes) return XNOR_E_NULL;

@@ -40,6 +40,10 @@ hipError_t launch_conv_tiled(const uint32_t *Ipk, const uint32_t *Wpk, const flo
                              const float *alpha, const Geom &g, float *out, int32_t *dot,
                              hipStream_t st);
 
+bool conv_image_supports(const Geom &g);
+hipError_t launch_conv_image(const float *I, const uint32_t *Wpk, const float *alpha, const Geom &g,
+                             float *out, int32_t *dot, hipStream_t st);
+
 bool conv_mfma_supports(const Geom &g);
 size_t conv_mfma_workspace_bytes(const Geom &g);   // 0 if the shape is not supported
 hipError_t launch_expand_filters(const uint32_t *Wpk, const Geom &g, void *workspace, hipStream_t st);

@@ -115,6 +115,19 @@ def test_null_and_alignment_rejected(xb):
     assert L.xnor_conv2d_fwd_chain(ok, ok, ok, ok, sp, odd, ok, ok, cneed, None) == xb.E_ALIGN
     assert L.xnor_box_filter_K(None, sp, ok, None) == xb.E_NULL
     assert L.xnor_box_filter_K(ok, sp, odd, None) == xb.E_ALIGN
+    # the one-kernel pass for few-channel images: this 64-channel shape is not its business
+    assert not xb.xnor_forward_image_supported(s)
+    assert L.xnor_forward_image(ok, ok, ok, sp, ok, None, None) == xb.E_UNSUPPORTED
+    img = xb.Shape(1, 1, 256, 256, 1, 3, 3, 1, 1, 1, 1)
+    ip = ctypes.byref(img.c())
+    assert xb.xnor_forward_image_supported(img)
+    assert xb.xnor_forward_image_supported(xb.Shape(2, 4, 30, 30, 9, 7, 7, 1, 1, 0, 0))
+    assert not xb.xnor_forward_image_supported(xb.Shape(1, 1, 256, 256, 1, 3, 3, 2, 2, 1, 1))
+    assert L.xnor_forward_image(None, ok, ok, ip, ok, None, None) == xb.E_NULL
+    assert L.xnor_forward_image(ok, ok, ok, ip, None, None, None) == xb.E_NULL
+    assert L.xnor_forward_image(ok, ok, ok, ip, odd, None, None) == xb.E_ALIGN
+    assert L.xnor_forward_image(ok, ok, ok, ip, ok, odd, None) == xb.E_ALIGN
+    assert L.xnor_forward_image_supported(None) == xb.E_NULL
 
 
 def test_binding_refuses_cpu_tensors(xb):
