@@ -39,7 +39,8 @@ struct ImageParams {
     int32_t *dot;
     int N, H, W, F, OH, OW, ph, pw;
     int rows_per_band, bands, xtiles;
-    long long waves;     // N * bands * xtiles
+    int group, fgroups;  // filters per wave, ceil(F / group)
+    long long waves;     // N * fgroups * bands * xtiles
     float kscale;        // 1 / (C * kh * kw)
 };
 
@@ -63,8 +64,7 @@ __global__ __launch_bounds__(kThreads) void conv_image_kernel(ImageParams p)
 
     // filter windows in the window's bit order: row r of the filter sits at bit (r % RPW) * RB of
     // word r / RPW, tap kx at kx * C inside the row, channel c at bit c of the tap
-    for (int f = threadIdx.x; f < p.F; f += kThreads) {
-        uint32_t w[NW];
+    auto filter_window = [&](int f, uint32_t (&w)[NW]) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < NW; ++i) w[i] = 0;
 #pragma unroll
@@ -73,11 +73,17 @@ __global__ __launch_bounds__(kThreads) void conv_image_kernel(ImageParams p)
             for (int kx = 0; kx < K; ++kx)
                 w[r / RPW] |= (p.Wpk[((size_t)f * K + r) * K + kx] & G::kChanMask)
                               << ((r % RPW) * RB + kx * C);
+    };
+    if (!ONE_FILTER) {
+        for (int f = threadIdx.x; f < p.F; f += kThreads) {
+            uint32_t w[NW];
+            filter_window(f, w);
 #pragma unroll
-        for (int i = 0; i < NW; ++i) wf[(size_t)f * NW + i] = w[i];
-        al[f] = p.alpha[f];
+            for (int i = 0; i < NW; ++i) wf[(size_t)f * NW + i] = w[i];
+            al[f] = p.alpha[f];
+        }
+        __syncthreads();
     }
-    __syncthreads();
 
     const int lane = threadIdx.x & 63;
     const long long gw = (long long)blockIdx.x * kWaves + (threadIdx.x >> 6);
@@ -85,7 +91,10 @@ __global__ __launch_bounds__(kThreads) void conv_image_kernel(ImageParams p)
     const int xt = __builtin_amdgcn_readfirstlane((int)(gw % p.xtiles));
     const long long t = gw / p.xtiles;
     const int band = __builtin_amdgcn_readfirstlane((int)(t % p.bands));
-    const int n = __builtin_amdgcn_readfirstlane((int)(t / p.bands));
+    const long long u = t / p.bands;
+    const int f0 = __builtin_amdgcn_readfirstlane((int)(u % p.fgroups)) * p.group;
+    const int f1 = min(p.F, f0 + p.group);
+    const int n = __builtin_amdgcn_readfirstlane((int)(u / p.fgroups));
     const int x = xt * 64 + lane;
     if (x >= p.OW) return;
 
@@ -115,14 +124,6 @@ __global__ __launch_bounds__(kThreads) void conv_image_kernel(ImageParams p)
     const float *src = p.I + (size_t)n * C * HW + (x - p.pw);   // only dereferenced where valid
     const size_t OHW = (size_t)p.OH * p.OW;
 
-    uint32_t fw[NW];
-    float a0 = 0.f;
-    if (ONE_FILTER) {
-#pragma unroll
-        for (int i = 0; i < NW; ++i) fw[i] = wf[i];
-        a0 = al[0];
-    }
-
     float pre[D][RB];
     auto issue = [&](int slot, int i) __attribute__((always_inline)) {
         const int yin = yb + i;
@@ -142,6 +143,15 @@ __global__ __launch_bounds__(kThreads) void conv_image_kernel(ImageParams p)
 
 #pragma unroll
     for (int d = 0; d < D; ++d) issue(d, d);
+
+    // a single filter stays in registers: its words come through wave-uniform loads that are in
+    // flight together with the first image rows, and no workgroup barrier is needed
+    uint32_t fw[NW];
+    float a0 = 0.f;
+    if (ONE_FILTER) {
+        filter_window(0, fw);
+        a0 = p.alpha[0];
+    }
 
     for (int i0 = 0; i0 < nin; i0 += D) {
 #pragma unroll
@@ -202,7 +212,7 @@ __global__ __launch_bounds__(kThreads) void conv_image_kernel(ImageParams p)
                 p.out[o] = (float)d1 * (kk * a0);
                 if (p.dot) p.dot[o] = d1;
             } else {
-                for (int f = 0; f < p.F; ++f) {
+                for (int f = f0; f < f1; ++f) {
                     int pop = 0;
 #pragma unroll
                     for (int w = 0; w < NW; ++w)
@@ -257,20 +267,28 @@ hipError_t launch_conv_image(const float *I, const uint32_t *Wpk, const float *a
     p.I = I; p.Wpk = Wpk; p.alpha = alpha; p.out = out; p.dot = dot;
     p.N = g.N; p.H = g.H; p.W = g.W; p.F = g.F; p.OH = g.OH; p.OW = g.OW; p.ph = g.ph; p.pw = g.pw;
     p.xtiles = ceil_div(g.OW, 64);
-    // band height: tall bands re-read fewer halo rows, short ones give more waves; halve from 64
-    // until the chip has about eight waves per SIMD or the halo reaches a quarter of the band
-    const int min_rows = 4 * (g.kh - 1);
+    // Band height: tall bands re-read fewer halo rows, short ones give more waves.  Halve from 64
+    // until the chip has about eight waves per SIMD; an image too small for that even with bands
+    // of 8 rows is bound by the chain of load latencies down a band, so it gets bands of 4.
+    // (Measured, one channel, 3x3: 4096^2 is fastest with 32 rows, 2048^2 with 16 or 8, 1024^2
+    // with 8, 512^2 and below with 4.)
+    auto waves_with = [&](int rows) { return (long long)g.N * p.xtiles * ceil_div(g.OH, rows); };
     int rows = 64;
-    while (rows > min_rows &&
-           (long long)g.N * p.xtiles * ceil_div(g.OH, rows) < 256LL * 4 * 8)
-        rows /= 2;
+    while (rows > 8 && waves_with(rows) < 256LL * 4 * 8) rows /= 2;
+    if (waves_with(rows) < 256LL * 4 * 2) rows = 4;
     p.rows_per_band = std::max(1, std::min(rows, g.OH));
     p.bands = ceil_div(g.OH, p.rows_per_band);
-    p.waves = (long long)g.N * p.bands * p.xtiles;
+    // With many filters and a small image the filters are shared out over waves as well (each
+    // wave rebuilds the window, which costs little next to the work of its filters).
+    p.group = g.F;
+    while (p.group > 4 && waves_with(p.rows_per_band) * ceil_div(g.F, p.group) < 256LL * 4 * 4)
+        p.group = (p.group + 1) / 2;
+    p.fgroups = ceil_div(g.F, p.group);
+    p.waves = waves_with(p.rows_per_band) * p.fgroups;
     p.kscale = 1.0f / (float)(g.C * g.kh * g.kw);
     const long long blocks = (p.waves + kWaves - 1) / kWaves;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    const size_t lds = (size_t)g.F * (window_words(g.kh, g.C) + 1) * 4;
+    const size_t lds = g.F == 1 ? 0 : (size_t)g.F * (window_words(g.kh, g.C) + 1) * 4;
     const dim3 grid((unsigned)blocks);
     switch (g.kh) {
         case 3: return launch_k<3>(g.C, p, grid, lds, st);
