@@ -49,6 +49,10 @@ def parse():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run three plain 1 GiB device copies before the timed loop (calibrates the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run against known traffic)")
+    ap.add_argument("--image", action="store_true",
+                    help="the paper's own workload (Tables I-III): one channel, one 3x3 filter, zero padding, "
+                         "square images of 256, 512, 1024 and 2048 pixels; one JSON line per size, latency in ms")
+    ap.add_argument("--image-sides", default="256,512,1024,2048")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
 
@@ -238,6 +242,105 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
     return rec
 
 
+# Table III's "GPU" column for the XNOR convolution (GTX 1080 Ti, mean of 100 runs, compute only), ms
+PAPER_GPU_XNOR_MS = {256: 0.0237, 512: 0.0692, 1024: 0.2519, 2048: 0.9859}
+
+
+def run_image(args, xb, torch, side):
+    """One channel, one 3x3 filter, pad 1 (the paper times nothing else): filter_prepare (per-model)
+    + xnor_forward_image (per image: signs, K, XNOR convolution, rescale in one kernel)."""
+    import numpy as np
+    import oracle
+
+    rng = np.random.default_rng(20200714 * 100 + side)
+    I = rng.standard_normal(size=(1, 1, side, side), dtype=np.float32)
+    Wt = rng.standard_normal(size=(1, 1, 3, 3), dtype=np.float32)
+    s = xb.Shape(1, 1, side, side, 1, 3, 3, 1, 1, 1, 1)
+    dI, dW = torch.from_numpy(I).cuda(), torch.from_numpy(Wt).cuda()
+    Wpk = torch.empty((1, 3, 3, 1), dtype=torch.int32, device="cuda")
+    alpha = torch.empty((1,), dtype=torch.float32, device="cuda")
+    M = torch.empty((1, 3, 3), dtype=torch.float32, device="cuda")
+    out = torch.empty((1, 1, side, side), dtype=torch.float32, device="cuda")
+
+    def step():
+        xb.xnor_filter_prepare(dW, Wpk=Wpk, M_work=M, alpha=alpha)
+        xb.xnor_forward_image(dI, Wpk, alpha, s, out=out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) / args.steps * 1e3
+    eager = out.clone()
+
+    # The kernels are shorter than the host's launch path, so the GPU's own time comes from HIP
+    # graphs (the library allocates nothing and records no memset): one graph of the step, and one
+    # of 20 back-to-back launches of the image kernel alone, timed with events on the launch stream.
+    side_stream = torch.cuda.Stream()
+    side_stream.wait_stream(torch.cuda.current_stream())
+    reps = 20
+    with torch.cuda.stream(side_stream):
+        g_step, g_kernel = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g_step, stream=side_stream):
+            step()
+        with torch.cuda.graph(g_kernel, stream=side_stream):
+            for _ in range(reps):
+                xb.xnor_forward_image(dI, Wpk, alpha, s, out=out)
+    torch.cuda.current_stream().wait_stream(side_stream)
+    ok = True
+    for g in (g_step, g_kernel, g_step):
+        out.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        ok = ok and bool(torch.equal(out, eager))
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        g_step.replay()
+    torch.cuda.synchronize()
+    graph_ms = (time.perf_counter() - t0) / args.steps * 1e3
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        g_kernel.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    kernel_ms = e0.elapsed_time(e1) / (args.steps * reps)
+
+    bytes_alg = 8.0 * side * side                       # 4 B read + 4 B written per pixel
+    gbs = bytes_alg / (kernel_ms * 1e-3) / 1e9
+    rec = {
+        "metric": "XNOR convolution latency, one image (signs + K + XNOR conv + rescale; filter packing and alpha included)",
+        "value": ms_per_step, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": ms_per_step / PAPER_GPU_XNOR_MS[side] if side in PAPER_GPU_XNOR_MS else None,
+        "baseline_note": "Table III, GPU column (GTX 1080 Ti, compute only, mean of 100 runs); the paper does not say "
+                         "how many filters it timed (one assumed) nor whether binarisation is inside its figure",
+        "dtype": "fp32 in, sign bits in spatially packed windows, int32 dot, fp32 scale",
+        "data": "synthetic (seeded N(0,1) image and filter; the paper's images are not specified)",
+        "config": {"workload": f"image {side}x{side}: N=1 C=1 F=1 3x3 stride 1 pad 1 (Tables I-III)",
+                   "binary_macs": 9 * side * side},
+        "graph_ms_per_step": graph_ms, "graph_replays_match_eager": ok,
+        "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+                     "traffic": None, "kernel": "conv_image_kernel (xnor_forward_image)", "kernel_ms": kernel_ms,
+                     "timing": f"{reps} back-to-back launches per graph replay, events on the launch stream"},
+    }
+    if not args.no_cpu_baseline:
+        osh = oracle.Shape(1, 1, side, side, 1, 3, 3, 1, 1, 1, 1)
+        oracle.forward(I, Wt, osh)
+        n, t0 = 0, time.perf_counter()
+        while n < 3 or time.perf_counter() - t0 < 1.0:
+            oracle.forward(I, Wt, osh)
+            n += 1
+        t = (time.perf_counter() - t0) / n
+        rec["cpu_baseline"] = {"value": t * 1e3, "unit": "ms", "cores": oracle.threads(), "kind": "oracle",
+                               "sample": f"the same {side}x{side} image, whole forward pass, mean of {n} runs"}
+    return rec
+
+
 def main():
     args = parse()
     world = int(os.environ.get("WORLD_SIZE", "1"))
@@ -254,6 +357,10 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    if args.image:
+        for side in (int(v) for v in args.image_sides.split(",")):
+            print(json.dumps(run_image(args, xb, torch, side)), flush=True)
+        return
     layers = list(LAYERS) if args.sweep else [args.layer]
     algos = ["tiled", "mfma"] if args.sweep else [args.algo]
     for lname in layers:
