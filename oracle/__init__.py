@@ -6,7 +6,8 @@ All arithmetic lives in the C file; this file only compiles it (gcc, ``-O2 -fope
 with ctypes and marshals numpy arrays.
 
 Function names follow the paper's pipeline (Sec. III-A step list): ``sign`` / ``pack`` (step 1a),
-``dot`` (steps 1b-1d), ``scale_K`` (Eq. 10), ``alpha`` (Eq. 5), ``out`` / ``forward`` (Eq. 11).
+``dot`` (steps 1b-1d), ``scale_K`` (Eq. 10), ``alpha`` (Eq. 5), ``out`` / ``forward`` (Eq. 11);
+``bwn`` is the Binary-Weight-Network layer of Sec. II-A (Eq. 1).
 """
 from __future__ import annotations
 
@@ -85,6 +86,8 @@ def _load():
         lib.oracle_alpha.restype = None
         lib.oracle_out.argtypes = [ip, fp, fp, ci, ci, ci, ci, fp]
         lib.oracle_out.restype = None
+        lib.oracle_bwn.argtypes = [fp, fp, sp, fp, fp, dp]
+        lib.oracle_bwn.restype = ci
         _lib = lib
     return _lib
 
@@ -190,3 +193,20 @@ def forward(I, Wt, s: Shape):
     K = scale_K(I, s)
     a = alpha(Wt)
     return d, K, a, out(d, K, a)
+
+
+def bwn(I, Wt, s: Shape, want_scale: bool = False):
+    """Binary-Weight-Network layer (Eq. 1): O = alpha * (I (+) sign(Wt)), fp32 [N][F][OH][OW].
+
+    With ``want_scale`` also returns S[N][OH][OW] = sum |I| over each output's in-image taps (double)."""
+    I, Wt = _f32(I), _f32(Wt)
+    _check(I, Wt, s)
+    OH, OW = out_dims(s)
+    a = alpha(Wt)
+    O = np.empty((s.N, s.F, OH, OW), dtype=np.float32)
+    S = np.empty((s.N, OH, OW), dtype=np.float64) if want_scale else None
+    if _load().oracle_bwn(_ptr(I, ctypes.c_float), _ptr(Wt, ctypes.c_float), ctypes.byref(s.c()),
+                          _ptr(a, ctypes.c_float), _ptr(O, ctypes.c_float),
+                          _ptr(S, ctypes.c_double) if want_scale else None):
+        raise ValueError(f"bad shape {s}")
+    return (O, S) if want_scale else O

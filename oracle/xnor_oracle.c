@@ -16,6 +16,8 @@
  *   - pipeline order (binarise, xnor, sum with 0 == -1,
  *     to float, channel sum, K*alpha, multiply)        : Sec. III-A step list
  *   - bit encoding: bit 1 <=> +1, bit 0 <=> -1         : Sec. III-A step 1c
+ *   - Binary-Weight-Network layer, real input and
+ *     binary weights: (I (+) B) alpha, B = sign(W)     : Sec. II-A, Eq. 1 (with Eq. 5 for alpha)
  *
  * The method reaches its target exactly (the bit encoding is a trick, not an approximation of the
  * sign convolution), so the oracle is the plain definition: a direct float convolution on +-1
@@ -203,6 +205,49 @@ void oracle_out(const int32_t *dot, const float *K, const float *alpha, int N, i
                 O[o] = (float)((double)dot[o] * (double)K[(size_t)n * OH * OW + p] *
                                (double)alpha[f]);
             }
+}
+
+/*
+ * Binary-Weight-Network convolution (Sec. II-A, Eq. 1): the input keeps its real values, the
+ * weights are B = sign(W), and the "convolution without multiplication" adds or subtracts each
+ * input value according to its weight's sign; the per-filter alpha of Eq. 5 scales the sum:
+ *     O[n][f][oy][ox] = alpha[f] * sum_{in-image taps, c} (B = +1 ? +I : -I).
+ * No K: the input is not binarised.  Same padding, stride and cross-correlation readings as the
+ * XNOR path.  Accumulated in double in the plain loop order (c, ky, kx), multiplied by alpha in
+ * double, rounded once to float.  S (optional) receives sum |I| over the same taps, in double: the
+ * scale against which a float implementation's summation error is measured.
+ */
+int oracle_bwn(const float *I, const float *Wt, const oracle_shape *s, const float *alpha, float *O,
+               double *S)
+{
+    int OH, OW;
+    if (oracle_out_dims(s, &OH, &OW)) return -1;
+    const int N = s->N, C = s->C, H = s->H, W = s->W, F = s->F, kh = s->kh, kw = s->kw;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int f = 0; f < F; ++f)
+            for (int oy = 0; oy < OH; ++oy)
+                for (int ox = 0; ox < OW; ++ox) {
+                    double acc = 0.0, mag = 0.0;
+                    for (int c = 0; c < C; ++c)
+                        for (int ky = 0; ky < kh; ++ky) {
+                            const int iy = oy * s->sh - s->ph + ky;
+                            if (iy < 0 || iy >= H) continue;
+                            for (int kx = 0; kx < kw; ++kx) {
+                                const int ix = ox * s->sw - s->pw + kx;
+                                if (ix < 0 || ix >= W) continue;
+                                const double v = (double)I[(((size_t)n * C + c) * H + iy) * W + ix];
+                                if (Wt[(((size_t)f * C + c) * kh + ky) * kw + kx] >= 0.0f)
+                                    acc += v;
+                                else
+                                    acc -= v;
+                                mag += v < 0.0 ? -v : v;
+                            }
+                        }
+                    O[(((size_t)n * F + f) * OH + oy) * OW + ox] = (float)(acc * (double)alpha[f]);
+                    if (S && f == 0) S[((size_t)n * OH + oy) * OW + ox] = mag;
+                }
+    return 0;
 }
 
 /* Whole forward pass in the pipeline's order; any of dot/K/alpha/O may be NULL except dot, K and

@@ -124,6 +124,7 @@ def test_hand_worked_fixture(case):
     assert np.array_equal(oracle.channel_mean_abs(I), np.array(case["A"], dtype=np.float64))
     np.testing.assert_allclose(K, np.array(case["K"]), rtol=1e-7)
     np.testing.assert_allclose(O, np.array(case["O"]), rtol=2e-7)
+    assert np.array_equal(oracle.bwn(I, Wt, s), np.array(case["O_bwn"], dtype=np.float32))
 
 
 # ----------------------------------------------------------------------------------------------
@@ -327,3 +328,89 @@ def test_benchmark_layer_one_image_identity(name):
     dref = torch.nn.functional.conv2d(torch.where(tI >= 0, one, -one), torch.where(tW >= 0, one, -one),
                                       stride=(s.sh, s.sw), padding=(s.ph, s.pw))
     assert np.array_equal(d, dref.numpy().astype(np.int32))
+
+
+# ----------------------------------------------------------------------------------------------
+# 8. Binary-Weight-Network layer (Sec. II-A, Eq. 1): real input, sign weights, alpha
+# ----------------------------------------------------------------------------------------------
+def brute_bwn_im2col(I, Wt, s: Shape):
+    """Zero-padded real tensor, unfolded, one float64 matrix product with the +-1 filters, then
+    alpha = mean |Wt| per filter (nothing here calls the oracle)."""
+    OH, OW = out_hw(s)
+    P = np.zeros((s.N, s.C, s.H + 2 * s.ph, s.W + 2 * s.pw), dtype=np.float64)
+    P[:, :, s.ph:s.ph + s.H, s.pw:s.pw + s.W] = I
+    cols = np.empty((s.N, OH, OW, s.C, s.kh, s.kw), dtype=np.float64)
+    for oy in range(OH):
+        for ox in range(OW):
+            cols[:, oy, ox] = P[:, :, oy * s.sh:oy * s.sh + s.kh, ox * s.sw:ox * s.sw + s.kw]
+    M = cols.reshape(s.N * OH * OW, -1) @ np_sign(Wt).reshape(s.F, -1).T.astype(np.float64)
+    a = np.abs(Wt.astype(np.float64)).reshape(s.F, -1).mean(1)
+    return M.reshape(s.N, OH, OW, s.F).transpose(0, 3, 1, 2) * a[None, :, None, None]
+
+
+def window_l1(I, s: Shape):
+    return np_K(I, s) * (s.C * s.kh * s.kw)
+
+
+@pytest.mark.parametrize("s", ASYM_SHAPES, ids=str)
+def test_bwn_matches_bruteforce(s):
+    I, Wt = rand_case(_h(("bwn", s)), s)
+    O, S = oracle.bwn(I, Wt, s, want_scale=True)
+    ref = brute_bwn_im2col(I, Wt, s)
+    l1 = window_l1(I, s)
+    np.testing.assert_allclose(S, l1, rtol=1e-12, atol=1e-300)
+    # both sides sum in double; the only difference is the order and the final rounding to fp32
+    assert (np.abs(O - ref) <= 2.0 ** -23 * np.abs(ref) + 1e-13 * l1[:, None]).all()
+
+
+@pytest.mark.parametrize("s", ASYM_SHAPES, ids=str)
+def test_bwn_against_torch_cpu(s):
+    I, Wt = rand_case(_h(("bwn-torch", s)), s)
+    B = torch.from_numpy(np.where(Wt >= 0, 1.0, -1.0))
+    ref = torch.nn.functional.conv2d(torch.from_numpy(I.astype(np.float64)), B, stride=(s.sh, s.sw),
+                                     padding=(s.ph, s.pw)).numpy()
+    ref = ref * torch.from_numpy(Wt.astype(np.float64)).abs().mean((1, 2, 3)).numpy()[None, :, None, None]
+    O = oracle.bwn(I, Wt, s)
+    l1 = window_l1(I, s)
+    assert (np.abs(O - ref) <= 2.0 ** -23 * np.abs(ref) + 1e-13 * l1[:, None]).all()
+
+
+def test_bwn_on_binary_input_is_the_xnor_dot_times_alpha():
+    """With I in {+1,-1} the real-input convolution is the sign convolution (Eq. 1 vs Eq. 11)."""
+    s = Shape(2, 37, 6, 5, 4, 3, 2, 2, 1, 1, 1)
+    I, Wt = rand_case(77, s, zeros=False)
+    I = np.where(I >= 0, 1.0, -1.0).astype(np.float32)
+    O = oracle.bwn(I, Wt, s)
+    expect = oracle.dot(I, Wt, s).astype(np.float64) * oracle.alpha(Wt).astype(np.float64)[None, :, None, None]
+    assert np.array_equal(O, expect.astype(np.float32))
+
+
+def test_bwn_closed_forms_and_invariants():
+    s = Shape(2, 5, 6, 7, 3, 3, 3, 1, 1, 1, 1)
+    OH, OW = out_hw(s)
+    ones_I = np.full((s.N, s.C, s.H, s.W), 2.5, dtype=np.float32)
+    ones_W = np.ones((s.F, s.C, s.kh, s.kw), dtype=np.float32)
+    v = np_K(np.ones_like(ones_I), s) * 9                      # number of in-image taps
+    assert np.array_equal(oracle.bwn(ones_I, ones_W, s), np.broadcast_to((2.5 * s.C * v)[:, None], (s.N, s.F, OH, OW)).astype(np.float32))
+    assert np.array_equal(oracle.bwn(ones_I, -3 * ones_W, s), (-3 * 2.5 * s.C * np.broadcast_to(v[:, None], (s.N, s.F, OH, OW))).astype(np.float32))
+    I, Wt = rand_case(5, s)
+    O = oracle.bwn(I, Wt, s).astype(np.float64)
+    l1 = window_l1(I, s)[:, None]
+    a = oracle.alpha(Wt).astype(np.float64)[None, :, None, None]
+    tol = 2.0 ** -22 * np.abs(O) + 1e-12 * l1
+    # negating a filter negates its plane; scaling a filter by c > 0 scales its plane by c
+    Wt0 = Wt.copy(); Wt0[Wt0 == 0] = 0.25                      # sign(-0) = sign(+0) = +1 does not negate
+    O0 = oracle.bwn(I, Wt0, s).astype(np.float64)
+    W2 = Wt0.copy(); W2[1] = -W2[1]; W2[2] = 4 * W2[2]
+    O2 = oracle.bwn(I, W2, s).astype(np.float64)
+    assert (np.abs(O2[:, 0] - O0[:, 0]) <= tol[:, 0]).all()
+    assert (np.abs(O2[:, 1] + O0[:, 1]) <= tol[:, 1]).all()
+    assert (np.abs(O2[:, 2] - 4 * O0[:, 2]) <= 4 * tol[:, 2]).all()
+    # linear in the input
+    I2, _ = rand_case(6, s)
+    lhs = oracle.bwn((2 * I + 0.5 * I2).astype(np.float32), Wt, s).astype(np.float64)
+    rhs = 2 * O + 0.5 * oracle.bwn(I2, Wt, s).astype(np.float64)
+    scale = a * (2 * l1 + 0.5 * window_l1(I2, s)[:, None])
+    assert (np.abs(lhs - rhs) <= 2.0 ** -21 * scale).all()
+    # |O| <= alpha * sum |I| over the window
+    assert (np.abs(O) <= a * l1 * (1 + 1e-6)).all()
