@@ -218,6 +218,27 @@ int xnor_forward_image_supported(const xnor_shape *s);
 int xnor_forward_image(const float *I, const uint32_t *Wpk, const float *alpha, const xnor_shape *s,
                        float *out, int32_t *dot, void *stream);
 
+/*
+ * Binary-Weight-Network convolution (Sec. II-A, Eq. 1, with alpha from Eq. 5): real-valued input,
+ * binary weights B = sign(W), "convolution without multiplication":
+ *     out[n][f][oy][ox] = alpha[f] * sum over in-image taps and channels of (B = +1 ? +I : -I).
+ * The input is not binarised and there is no K.  Zero padding, stride and cross-correlation as in
+ * xnor_conv2d_fwd.
+ *   I      in   fp32 [N][C][H][W]
+ *   Wpk    in   uint32 [F][kh][kw][ceil(C/32)]   packed filter signs, bit 1 = +1
+ *   alpha  in   fp32 [F]
+ *   out    out  fp32 [N][F][OH][OW]
+ * The sum is formed in fp32 (fp32 matrix-core accumulation, or a short chain of fp32 partial sums
+ * in the one-thread-per-output kernel); its rounding error is relative to alpha * sum |I| over the
+ * window, not to |out|.  No workspace.  xnor_bwn_conv2d_fwd_algo: XNOR_ALGO_AUTO, XNOR_ALGO_DIRECT
+ * (any shape) or XNOR_ALGO_MFMA (XNOR_E_UNSUPPORTED where a pixel band of the input does not fit in
+ * LDS or kh*kw > 64); other values XNOR_E_UNSUPPORTED.
+ */
+int xnor_bwn_conv2d_fwd(const float *I, const uint32_t *Wpk, const float *alpha, const xnor_shape *s,
+                        float *out, void *stream);
+int xnor_bwn_conv2d_fwd_algo(const float *I, const uint32_t *Wpk, const float *alpha,
+                             const xnor_shape *s, float *out, int algo, void *stream);
+
 /* Same as xnor_conv2d_fwd, with the kernel chosen by the caller (tests and measurements run every
  * variant).  Returns XNOR_E_UNSUPPORTED if `algo` cannot run this shape, XNOR_E_WORKSPACE if it
  * needs more workspace than given; XNOR_ALGO_DIRECT runs every shape without workspace. */

@@ -92,6 +92,8 @@ def _load() -> ctypes.CDLL:
     L.xnor_conv2d_fwd_chain.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, vp]
     L.xnor_forward_image_supported.argtypes = [sp]
     L.xnor_forward_image.argtypes = [vp, vp, vp, sp, vp, vp, vp]
+    L.xnor_bwn_conv2d_fwd.argtypes = [vp, vp, vp, sp, vp, vp]
+    L.xnor_bwn_conv2d_fwd_algo.argtypes = [vp, vp, vp, sp, vp, ci, vp]
     L.xnor_conv2d_pick_algo.argtypes = [sp, sz]
     L.xnor_conv2d_workspace_bytes.argtypes = [sp, ctypes.POINTER(sz)]
     for name in ("xnor_out_dim", "xnor_packed_words", "xnor_binarize_pack", "xnor_scale_K",
@@ -99,7 +101,8 @@ def _load() -> ctypes.CDLL:
                  "xnor_conv2d_workspace_bytes", "xnor_input_prepare", "xnor_filter_prepare",
                  "xnor_filter_expand", "xnor_conv2d_fwd_expanded", "xnor_box_filter_K",
                  "xnor_conv2d_chain_workspace_bytes", "xnor_conv2d_fwd_chain",
-                 "xnor_forward_image_supported", "xnor_forward_image"):
+                 "xnor_forward_image_supported", "xnor_forward_image",
+                 "xnor_bwn_conv2d_fwd", "xnor_bwn_conv2d_fwd_algo"):
         getattr(L, name).restype = ci
     return L
 
@@ -302,6 +305,20 @@ def xnor_forward_image(I: torch.Tensor, Wpk: torch.Tensor, alpha: torch.Tensor, 
         _dev(alpha, torch.float32, (s.F,), "alpha"), ctypes.byref(s.c()), _dev(out, torch.float32, oshape, "out"),
         _dev(dot, torch.int32, oshape, "dot") if dot is not None else None, _stream()), "xnor_forward_image")
     return out, dot
+
+
+def xnor_bwn_conv2d_fwd(I: torch.Tensor, Wpk: torch.Tensor, alpha: torch.Tensor, s: Shape,
+                        out: torch.Tensor | None = None, algo: int = ALGO_AUTO) -> torch.Tensor:
+    """Binary-Weight-Network layer (Eq. 1): real input, packed sign weights, alpha. Returns out."""
+    OH, OW = xnor_out_dim(s)
+    oshape = (s.N, s.F, OH, OW)
+    if out is None:
+        out = torch.empty(oshape, dtype=torch.float32, device=I.device)
+    _ok(lib.xnor_bwn_conv2d_fwd_algo(
+        _dev(I, torch.float32, (s.N, s.C, s.H, s.W), "I"), _dev(Wpk, torch.int32, (s.F, s.kh, s.kw, s.Cw), "Wpk"),
+        _dev(alpha, torch.float32, (s.F,), "alpha"), ctypes.byref(s.c()), _dev(out, torch.float32, oshape, "out"),
+        algo, _stream()), f"xnor_bwn_conv2d_fwd[{ALGO_NAMES.get(algo, algo)}]")
+    return out
 
 
 def xnor_box_filter_K(A: torch.Tensor, s: Shape, K: torch.Tensor | None = None) -> torch.Tensor:

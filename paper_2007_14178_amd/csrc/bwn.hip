@@ -1,0 +1,254 @@
+// Binary-Weight-Network convolution (Sec. II-A, Eq. 1): the input keeps its real values, the
+// weights are their signs, and the per-filter alpha of Eq. 5 scales the sum:
+//     O[n][f][oy][ox] = alpha[f] * sum_{in-image taps, c} (B[f][c][ky][kx] = +1 ? +I : -I).
+// No input binarisation and no K.  The filter signs come packed (xnor_filter_prepare /
+// xnor_binarize_pack: bit 1 = +1).
+//
+// The paper describes this as a convolution of additions and subtractions.  On this chip the
+// cheapest way to add or subtract 4608 fp32 values per output is a dense fp32 contraction on the
+// matrix cores with +-1.0 as one operand: v_mfma_f32_32x32x2_f32 retires 2048 of them per
+// instruction, and a product with +-1.0 is exact, so the result is the fp32 sum.
+//
+//   bwn_mfma_kernel: rows of the MFMA = 32 filters, columns = 32 consecutive output pixels of one
+//   image, reduction = channel pairs at a fixed tap.  A workgroup (4 waves = 4 filter tiles) owns
+//   up to 7 pixel tiles; per chunk of channels it stages the input rows under them once in LDS as
+//   fp32, zero where the image ends (that is the zero padding), and the chunk's filter words.  The
+//   B operand of each MFMA is one LDS dword per lane (lane = pixel, its channel = pair member);
+//   the A operand is +-1.0 made from the lane's filter word with three integer instructions per
+//   NT MFMAs.  The accumulator layout gives each lane 16 filters of one pixel, so stores run
+//   along the pixels of a filter plane.
+//   bwn_direct_kernel: one thread per output, any shape; the fallback and the cross-check.
+#include <algorithm>
+
+#include "xnor_internal.hpp"
+
+namespace xnor {
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kThreads = 256;
+constexpr int kFiltersPerWg = 128;   // 4 waves x 32 rows
+constexpr int kMaxTiles = 7;         // pixel tiles (of 32) per workgroup: 7 x 16 accumulator registers
+constexpr size_t kLdsBudget = 64 * 1024;
+
+struct BwnParams {
+    const float *I;
+    const uint32_t *Wpk;
+    const float *alpha;
+    float *out;
+    int N, C, H, W, F, kh, kw, sh, sw, ph, pw, OH, OW, Cw;
+    int tiles;          // pixel tiles per workgroup
+    int groups;         // workgroups along the pixels of one image
+    int fgroups;        // workgroups along the filters
+    int chan;           // channels per chunk: 32, 16 or 8 (a chunk never straddles a packed word)
+    int rows_max;       // staged input rows (upper bound over the pixel groups)
+    int pitch;          // staged floats per row = W + 2*pw
+};
+
+__global__ __launch_bounds__(kThreads, 2) void bwn_mfma_kernel(BwnParams p)
+{
+    extern __shared__ float lds[];
+    // [chan][rows][pitch] input, then [taps][128] filter words
+    const int plane = p.rows_max * p.pitch;
+    float *tile = lds;
+    uint32_t *fw = reinterpret_cast<uint32_t *>(lds + (size_t)p.chan * plane);
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & 31, half = lane >> 5;
+    int b = blockIdx.x;
+    const int h = b % p.fgroups; b /= p.fgroups;
+    const int g = b % p.groups;
+    const int n = b / p.groups;
+
+    const int OHW = p.OH * p.OW;
+    const int p0 = g * p.tiles * 32;
+    const int p1 = min(OHW, p0 + p.tiles * 32);
+    const int nt = (p1 - p0 + 31) >> 5;                 // tiles this workgroup really has
+    const int oy0 = p0 / p.OW, oy1 = (p1 - 1) / p.OW;
+    const int iy0 = oy0 * p.sh - p.ph;
+    const int rows = (oy1 - oy0) * p.sh + p.kh;         // <= rows_max
+    const int taps = p.kh * p.kw;
+    const int fbase = h * kFiltersPerWg;
+
+    // per pixel tile: this lane's LDS float index of tap (0,0), channel `half`, chunk start
+    int base[kMaxTiles];
+#pragma unroll
+    for (int j = 0; j < kMaxTiles; ++j) {
+        const int px = min(p0 + 32 * j + col, p1 - 1);
+        const int oy = px / p.OW, ox = px - oy * p.OW;
+        base[j] = half * plane + (oy - oy0) * p.sh * p.pitch + ox * p.sw;
+    }
+
+    floatx16 acc[kMaxTiles];
+#pragma unroll
+    for (int j = 0; j < kMaxTiles; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+
+    const int chunks_per_word = 32 / p.chan;
+    const int nchunks = (p.C + p.chan - 1) / p.chan;
+    const float *img = p.I + (size_t)n * p.C * p.H * p.W;
+    for (int ch = 0; ch < nchunks; ++ch) {
+        const int c0 = ch * p.chan;
+        const int cw = ch / chunks_per_word;
+        const int bit0 = (ch % chunks_per_word) * p.chan;
+        __syncthreads();                                 // the previous chunk has been read
+        for (int i = threadIdx.x; i < p.chan * rows * p.pitch; i += kThreads) {
+            const int c = i / (rows * p.pitch);
+            const int rem = i - c * (rows * p.pitch);
+            const int r = rem / p.pitch;
+            const int xw = rem - r * p.pitch;
+            const int iy = iy0 + r, ix = xw - p.pw, cg = c0 + c;
+            const bool in = cg < p.C && iy >= 0 && iy < p.H && ix >= 0 && ix < p.W;
+            tile[c * plane + r * p.pitch + xw] = in ? img[((size_t)cg * p.H + iy) * p.W + ix] : 0.f;
+        }
+        for (int i = threadIdx.x; i < taps * kFiltersPerWg; i += kThreads) {
+            const int t = i / kFiltersPerWg, fi = i - t * kFiltersPerWg;
+            const int f = fbase + fi;
+            fw[i] = f < p.F ? p.Wpk[((size_t)f * taps + t) * p.Cw + cw] >> bit0 : 0u;
+        }
+        __syncthreads();
+
+        for (int ky = 0; ky < p.kh; ++ky)
+            for (int kx = 0; kx < p.kw; ++kx) {
+                const uint32_t word = fw[(ky * p.kw + kx) * kFiltersPerWg + wave * 32 + col] >> half;
+                const int toff = ky * p.pitch + kx;
+                for (int q = 0; q < p.chan / 8; ++q) {       // four channel pairs at a time
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int cp = 4 * q + u;
+                        // bit (2*cp + half) of the chunk: 1 -> +1.0f, 0 -> -1.0f
+                        const float a = __uint_as_float(0xBF800000u ^ (((word >> (2 * cp)) & 1u) << 31));
+                        const int off = toff + 2 * cp * plane;
+#pragma unroll
+                        for (int j = 0; j < kMaxTiles; ++j)
+                            if (j < nt)
+                                acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, tile[base[j] + off], acc[j], 0, 0, 0);
+                    }
+                }
+            }
+    }
+
+    // accumulator register r of a lane: filter row 8*(r/4) + 4*half + r%4 of the wave's tile,
+    // pixel column `col`
+    float al[16];
+    int fr[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        fr[r] = fbase + wave * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+        al[r] = fr[r] < p.F ? p.alpha[fr[r]] : 0.f;
+    }
+    float *dst = p.out + (size_t)n * p.F * OHW;
+#pragma unroll
+    for (int j = 0; j < kMaxTiles; ++j) {
+        const int px = p0 + 32 * j + col;
+        if (j < nt && px < p1) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (fr[r] < p.F) dst[(size_t)fr[r] * OHW + px] = acc[j][r] * al[r];
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void bwn_direct_kernel(const float *__restrict__ I,
+                                                         const uint32_t *__restrict__ Wpk,
+                                                         const float *__restrict__ alpha, Geom g,
+                                                         long long total, float *__restrict__ out)
+{
+    const long long o = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (o >= total) return;
+    const int ox = (int)(o % g.OW);
+    long long t = o / g.OW;
+    const int oy = (int)(t % g.OH);
+    t /= g.OH;
+    const int f = (int)(t % g.F);
+    const long long n = t / g.F;
+    const size_t HW = (size_t)g.H * g.W;
+    const float *img = I + n * g.C * HW;
+    const uint32_t *flt = Wpk + (size_t)f * g.kh * g.kw * g.Cw;
+    float acc = 0.f;
+    for (int ky = 0; ky < g.kh; ++ky) {
+        const int iy = oy * g.sh - g.ph + ky;
+        if (iy < 0 || iy >= g.H) continue;
+        for (int kx = 0; kx < g.kw; ++kx) {
+            const int ix = ox * g.sw - g.pw + kx;
+            if (ix < 0 || ix >= g.W) continue;
+            const float *src = img + (size_t)iy * g.W + ix;
+            float tap = 0.f;                      // per-tap partial sums keep the adder chain short
+            for (int w = 0; w < g.Cw; ++w) {
+                const uint32_t bits = flt[(ky * g.kw + kx) * g.Cw + w];
+                const int cn = min(32, g.C - 32 * w);
+                float part = 0.f;
+                for (int j = 0; j < cn; ++j) {
+                    const float v = src[(size_t)(32 * w + j) * HW];
+                    part += ((bits >> j) & 1u) ? v : -v;
+                }
+                tap += part;
+            }
+            acc += tap;
+        }
+    }
+    out[o] = acc * alpha[f];
+}
+
+struct Plan {
+    bool ok;
+    int tiles, chan, rows_max, pitch;
+    size_t lds;
+};
+
+Plan make_plan(const Geom &g)
+{
+    Plan pl{};
+    const long long OHW = (long long)g.OH * g.OW;
+    if (g.kh * g.kw > 64 || OHW > (1 << 24)) return pl;
+    pl.pitch = g.W + 2 * g.pw;
+    for (int tiles = (int)std::min<long long>(kMaxTiles, (OHW + 31) / 32); tiles >= 1; --tiles) {
+        // 32*tiles consecutive pixels span at most this many output rows
+        const int orows = (int)std::min<long long>(g.OH, (32LL * tiles + g.OW - 2) / g.OW + 1);
+        const int rows = (orows - 1) * g.sh + g.kh;
+        // no more channels per chunk than the layer has (rounded up to 8)
+        for (int chan = g.C > 16 ? 32 : g.C > 8 ? 16 : 8; chan >= 8; chan /= 2) {
+            const size_t lds = ((size_t)chan * rows * pl.pitch + (size_t)g.kh * g.kw * kFiltersPerWg) * 4;
+            if (lds <= kLdsBudget) {
+                pl.ok = true; pl.tiles = tiles; pl.chan = chan; pl.rows_max = rows; pl.lds = lds;
+                return pl;
+            }
+        }
+    }
+    return pl;
+}
+
+}  // namespace
+
+bool bwn_mfma_supports(const Geom &g) { return make_plan(g).ok; }
+
+hipError_t launch_bwn_mfma(const float *I, const uint32_t *Wpk, const float *alpha, const Geom &g,
+                           float *out, hipStream_t st)
+{
+    const Plan pl = make_plan(g);
+    if (!pl.ok) return hipErrorInvalidValue;
+    BwnParams p;
+    p.I = I; p.Wpk = Wpk; p.alpha = alpha; p.out = out;
+    p.N = g.N; p.C = g.C; p.H = g.H; p.W = g.W; p.F = g.F; p.kh = g.kh; p.kw = g.kw;
+    p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw; p.OH = g.OH; p.OW = g.OW; p.Cw = g.Cw;
+    p.tiles = pl.tiles; p.chan = pl.chan; p.rows_max = pl.rows_max; p.pitch = pl.pitch;
+    const long long OHW = (long long)g.OH * g.OW;
+    p.groups = ceil_div(OHW, 32LL * pl.tiles);
+    p.fgroups = ceil_div(g.F, kFiltersPerWg);
+    const long long blocks = (long long)g.N * p.groups * p.fgroups;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    bwn_mfma_kernel<<<dim3((unsigned)blocks), dim3(kThreads), pl.lds, st>>>(p);
+    return hipGetLastError();
+}
+
+hipError_t launch_bwn_direct(const float *I, const uint32_t *Wpk, const float *alpha, const Geom &g,
+                             float *out, hipStream_t st)
+{
+    const long long total = (long long)g.N * g.F * g.OH * g.OW;
+    bwn_direct_kernel<<<ceil_div(total, 256), 256, 0, st>>>(I, Wpk, alpha, g, total, out);
+    return hipGetLastError();
+}
+
+}  // namespace xnor

@@ -243,6 +243,32 @@ int xnor_forward_image(const float *I, const uint32_t *Wpk, const float *alpha, 
     return hip_status(xnor::launch_conv_image(I, Wpk, alpha, g, out, dot, (hipStream_t)stream));
 }
 
+int xnor_bwn_conv2d_fwd_algo(const float *I, const uint32_t *Wpk, const float *alpha,
+                             const xnor_shape *s, float *out, int algo, void *stream)
+{
+    if (!I || !Wpk || !alpha || !s || !out) return XNOR_E_NULL;
+    xnor::Geom g;
+    const int rc = make_geom(s, &g);
+    if (rc) return rc;
+    if (!aligned(I, 4) || !aligned(Wpk, 4) || !aligned(alpha, 4) || !aligned(out, 4)) return XNOR_E_ALIGN;
+    if (algo == XNOR_ALGO_AUTO) algo = xnor::bwn_mfma_supports(g) ? XNOR_ALGO_MFMA : XNOR_ALGO_DIRECT;
+    switch (algo) {
+        case XNOR_ALGO_DIRECT:
+            return hip_status(xnor::launch_bwn_direct(I, Wpk, alpha, g, out, (hipStream_t)stream));
+        case XNOR_ALGO_MFMA:
+            if (!xnor::bwn_mfma_supports(g)) return XNOR_E_UNSUPPORTED;
+            return hip_status(xnor::launch_bwn_mfma(I, Wpk, alpha, g, out, (hipStream_t)stream));
+        default:
+            return XNOR_E_UNSUPPORTED;
+    }
+}
+
+int xnor_bwn_conv2d_fwd(const float *I, const uint32_t *Wpk, const float *alpha, const xnor_shape *s,
+                        float *out, void *stream)
+{
+    return xnor_bwn_conv2d_fwd_algo(I, Wpk, alpha, s, out, XNOR_ALGO_AUTO, stream);
+}
+
 int xnor_conv2d_chain_workspace_bytes(const xnor_shape *s, size_t *bytes)
 {
     if (!s || !bytes) return XNOR_E_NULL;

@@ -44,6 +44,12 @@ bool conv_image_supports(const Geom &g);
 hipError_t launch_conv_image(const float *I, const uint32_t *Wpk, const float *alpha, const Geom &g,
                              float *out, int32_t *dot, hipStream_t st);
 
+bool bwn_mfma_supports(const Geom &g);
+hipError_t launch_bwn_mfma(const float *I, const uint32_t *Wpk, const float *alpha, const Geom &g,
+                           float *out, hipStream_t st);
+hipError_t launch_bwn_direct(const float *I, const uint32_t *Wpk, const float *alpha, const Geom &g,
+                             float *out, hipStream_t st);
+
 bool conv_mfma_supports(const Geom &g);
 size_t conv_mfma_workspace_bytes(const Geom &g);   // 0 if the shape is not supported
 hipError_t launch_expand_filters(const uint32_t *Wpk, const Geom &g, void *workspace, hipStream_t st);
