@@ -46,7 +46,12 @@ struct BwnParams {
     int pitch;          // staged floats per row = W + 2*pw
 };
 
-__global__ __launch_bounds__(kThreads, 2) void bwn_mfma_kernel(BwnParams p)
+// The work of one workgroup with NT pixel tiles.  NT is a template parameter so that the MFMA
+// loop is one basic block (operands of the next MFMAs are loaded ahead of the current ones) and
+// the accumulators are NT x 16 fixed registers.
+template <int NT>
+__device__ __attribute__((always_inline)) void bwn_workgroup(const BwnParams &p, int n, int fbase,
+                                                              int p0, int p1)
 {
     extern __shared__ float lds[];
     // [chan][rows][pitch] input, then [taps][128] filter words
@@ -56,33 +61,24 @@ __global__ __launch_bounds__(kThreads, 2) void bwn_mfma_kernel(BwnParams p)
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 31, half = lane >> 5;
-    int b = blockIdx.x;
-    const int h = b % p.fgroups; b /= p.fgroups;
-    const int g = b % p.groups;
-    const int n = b / p.groups;
-
     const int OHW = p.OH * p.OW;
-    const int p0 = g * p.tiles * 32;
-    const int p1 = min(OHW, p0 + p.tiles * 32);
-    const int nt = (p1 - p0 + 31) >> 5;                 // tiles this workgroup really has
     const int oy0 = p0 / p.OW, oy1 = (p1 - 1) / p.OW;
     const int iy0 = oy0 * p.sh - p.ph;
     const int rows = (oy1 - oy0) * p.sh + p.kh;         // <= rows_max
     const int taps = p.kh * p.kw;
-    const int fbase = h * kFiltersPerWg;
 
     // per pixel tile: this lane's LDS float index of tap (0,0), channel `half`, chunk start
-    int base[kMaxTiles];
+    int base[NT];
 #pragma unroll
-    for (int j = 0; j < kMaxTiles; ++j) {
+    for (int j = 0; j < NT; ++j) {
         const int px = min(p0 + 32 * j + col, p1 - 1);
         const int oy = px / p.OW, ox = px - oy * p.OW;
         base[j] = half * plane + (oy - oy0) * p.sh * p.pitch + ox * p.sw;
     }
 
-    floatx16 acc[kMaxTiles];
+    floatx16 acc[NT];
 #pragma unroll
-    for (int j = 0; j < kMaxTiles; ++j)
+    for (int j = 0; j < NT; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
 
@@ -94,14 +90,29 @@ __global__ __launch_bounds__(kThreads, 2) void bwn_mfma_kernel(BwnParams p)
         const int cw = ch / chunks_per_word;
         const int bit0 = (ch % chunks_per_word) * p.chan;
         __syncthreads();                                 // the previous chunk has been read
-        for (int i = threadIdx.x; i < p.chan * rows * p.pitch; i += kThreads) {
-            const int c = i / (rows * p.pitch);
-            const int rem = i - c * (rows * p.pitch);
-            const int r = rem / p.pitch;
-            const int xw = rem - r * p.pitch;
-            const int iy = iy0 + r, ix = xw - p.pw, cg = c0 + c;
-            const bool in = cg < p.C && iy >= 0 && iy < p.H && ix >= 0 && ix < p.W;
-            tile[c * plane + r * p.pitch + xw] = in ? img[((size_t)cg * p.H + iy) * p.W + ix] : 0.f;
+        // input rows of the chunk: 32 lanes along a row, 8 (channel, row) segments per pass, eight
+        // passes' loads in flight before their LDS writes
+        const int nseg = p.chan * rows;
+        for (int xw0 = 0; xw0 < p.pitch; xw0 += 32) {
+            const int xw = xw0 + (threadIdx.x & 31), ix = xw - p.pw;
+            const bool colok = xw < p.pitch && ix >= 0 && ix < p.W;
+            for (int sg = threadIdx.x >> 5; sg < nseg; sg += 64) {
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int s2 = sg + 8 * u;
+                    const int c = s2 / rows, r = s2 - c * rows;
+                    const int iy = iy0 + r, cg = c0 + c;
+                    const bool in = s2 < nseg && colok && cg < p.C && iy >= 0 && iy < p.H;
+                    v[u] = in ? img[((size_t)cg * p.H + iy) * p.W + ix] : 0.f;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int s2 = sg + 8 * u;
+                    const int c = s2 / rows, r = s2 - c * rows;
+                    if (s2 < nseg && xw < p.pitch) tile[c * plane + r * p.pitch + xw] = v[u];
+                }
+            }
         }
         for (int i = threadIdx.x; i < taps * kFiltersPerWg; i += kThreads) {
             const int t = i / kFiltersPerWg, fi = i - t * kFiltersPerWg;
@@ -122,9 +133,8 @@ __global__ __launch_bounds__(kThreads, 2) void bwn_mfma_kernel(BwnParams p)
                         const float a = __uint_as_float(0xBF800000u ^ (((word >> (2 * cp)) & 1u) << 31));
                         const int off = toff + 2 * cp * plane;
 #pragma unroll
-                        for (int j = 0; j < kMaxTiles; ++j)
-                            if (j < nt)
-                                acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, tile[base[j] + off], acc[j], 0, 0, 0);
+                        for (int j = 0; j < NT; ++j)
+                            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, tile[base[j] + off], acc[j], 0, 0, 0);
                     }
                 }
             }
@@ -141,13 +151,33 @@ __global__ __launch_bounds__(kThreads, 2) void bwn_mfma_kernel(BwnParams p)
     }
     float *dst = p.out + (size_t)n * p.F * OHW;
 #pragma unroll
-    for (int j = 0; j < kMaxTiles; ++j) {
+    for (int j = 0; j < NT; ++j) {
         const int px = p0 + 32 * j + col;
-        if (j < nt && px < p1) {
+        if (px < p1) {
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 if (fr[r] < p.F) dst[(size_t)fr[r] * OHW + px] = acc[j][r] * al[r];
         }
+    }
+}
+
+__global__ __launch_bounds__(kThreads, 2) void bwn_mfma_kernel(BwnParams p)
+{
+    int b = blockIdx.x;
+    const int h = b % p.fgroups; b /= p.fgroups;
+    const int g = b % p.groups;
+    const int n = b / p.groups;
+    const int p0 = g * p.tiles * 32;
+    const int p1 = min(p.OH * p.OW, p0 + p.tiles * 32);
+    const int fbase = h * kFiltersPerWg;
+    switch ((p1 - p0 + 31) >> 5) {                       // tiles this workgroup really has
+        case 1: bwn_workgroup<1>(p, n, fbase, p0, p1); break;
+        case 2: bwn_workgroup<2>(p, n, fbase, p0, p1); break;
+        case 3: bwn_workgroup<3>(p, n, fbase, p0, p1); break;
+        case 4: bwn_workgroup<4>(p, n, fbase, p0, p1); break;
+        case 5: bwn_workgroup<5>(p, n, fbase, p0, p1); break;
+        case 6: bwn_workgroup<6>(p, n, fbase, p0, p1); break;
+        default: bwn_workgroup<7>(p, n, fbase, p0, p1); break;
     }
 }
 
@@ -204,7 +234,11 @@ Plan make_plan(const Geom &g)
     const long long OHW = (long long)g.OH * g.OW;
     if (g.kh * g.kw > 64 || OHW > (1 << 24)) return pl;
     pl.pitch = g.W + 2 * g.pw;
-    for (int tiles = (int)std::min<long long>(kMaxTiles, (OHW + 31) / 32); tiles >= 1; --tiles) {
+    // fewer pixel tiles per workgroup when the launch would otherwise leave compute units idle
+    int most = (int)std::min<long long>(kMaxTiles, (OHW + 31) / 32);
+    while (most > 2 && (long long)g.N * ceil_div(g.F, kFiltersPerWg) * ceil_div(OHW, 32LL * most) < 512)
+        --most;
+    for (int tiles = most; tiles >= 1; --tiles) {
         // 32*tiles consecutive pixels span at most this many output rows
         const int orows = (int)std::min<long long>(g.OH, (32LL * tiles + g.OW - 2) / g.OW + 1);
         const int rows = (orows - 1) * g.sh + g.kh;
