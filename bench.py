@@ -49,6 +49,9 @@ def parse():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run three plain 1 GiB device copies before the timed loop (calibrates the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run against known traffic)")
+    ap.add_argument("--bwn", action="store_true",
+                    help="the Binary-Weight-Network layer (Eq. 1: real input, binary weights) on --layer "
+                         "(or on every layer with --sweep): filter_prepare + xnor_bwn_conv2d_fwd")
     ap.add_argument("--image", action="store_true",
                     help="the paper's own workload (Tables I-III): one channel, one 3x3 filter, zero padding, "
                          "square images of 256, 512, 1024 and 2048 pixels; one JSON line per size, latency in ms")
@@ -242,6 +245,81 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
     return rec
 
 
+PEAK_FP32_MFMA_TFLOPS = 157.3
+
+
+def run_bwn(args, xb, torch, layer, make_input, make_weights):
+    """Eq. 1 on a benchmark layer: one step = filter_prepare (signs + alpha, one pass over Wt) and
+    the BWN convolution reading the fp32 input directly (no input stage: nothing is binarised)."""
+    import oracle
+
+    s = xb.Shape(layer.N, layer.C, layer.H, layer.W, layer.F, layer.kh, layer.kw,
+                 layer.sh, layer.sw, layer.ph, layer.pw)
+    OH, OW = xb.xnor_out_dim(s)
+    Wt_host = make_weights(layer)
+    dI = torch.from_numpy(make_input(layer)).cuda()
+    dW = torch.from_numpy(Wt_host).cuda()
+    Wpk = torch.empty((s.F, s.kh, s.kw, s.Cw), dtype=torch.int32, device="cuda")
+    M = torch.empty((s.F, s.kh, s.kw), dtype=torch.float32, device="cuda")
+    alpha = torch.empty((s.F,), dtype=torch.float32, device="cuda")
+    out = torch.empty((s.N, s.F, OH, OW), dtype=torch.float32, device="cuda")
+    algo = {"auto": xb.ALGO_AUTO, "direct": xb.ALGO_DIRECT, "mfma": xb.ALGO_MFMA}[args.algo]
+
+    def step(events=None):
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(3)] if events is not None else None
+        if marks: marks[0].record()
+        xb.xnor_filter_prepare(dW, Wpk, M, alpha)
+        if marks: marks[1].record()
+        xb.xnor_bwn_conv2d_fwd(dI, Wpk, alpha, s, out=out, algo=algo)
+        if marks:
+            marks[2].record()
+            events.append(marks)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events: list = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) / args.steps * 1e3
+    stage_ms = {n: sum(m[i].elapsed_time(m[i + 1]) for m in events) / len(events)
+                for i, n in enumerate(["filter_prepare", "conv"])}
+    macs = layer.binary_macs
+    conv_ms = stage_ms["conv"]
+    achieved = 2.0 * macs / (conv_ms * 1e-3) / 1e12
+    rec = {
+        "metric": "GMAC/s (real input x binary weight), Binary-Weight-Network layer (sign + alpha of the filters, add/subtract convolution, rescale)",
+        "value": macs / (ms_per_step * 1e-3) / 1e9, "unit": "GMAC/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "fp32 input, 1-bit weights, fp32 accumulate (v_mfma_f32_32x32x2_f32)",
+        "data": "synthetic (seeded; shapes and value distributions of the benchmark layer)",
+        "config": {"workload": f"{layer.name} as a BWN layer: N={layer.N} C={layer.C} {layer.H}x{layer.W} F={layer.F} "
+                               f"{layer.kh}x{layer.kw} stride {layer.sh} pad {layer.ph}", "macs": macs},
+        "stage_ms": stage_ms,
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                     "kernel": "bwn_mfma_kernel (xnor_bwn_conv2d_fwd)" if args.algo != "direct" else "bwn_direct_kernel",
+                     "kernel_ms": conv_ms},
+    }
+    if not args.no_cpu_baseline and not args.sweep:
+        def run(n):
+            I = make_input(layer, n)
+            osh = oracle.Shape(n, layer.C, layer.H, layer.W, layer.F, layer.kh, layer.kw,
+                               layer.sh, layer.sw, layer.ph, layer.pw)
+            t0 = time.perf_counter()
+            oracle.bwn(I, Wt_host, osh)
+            return time.perf_counter() - t0
+        t1 = run(1)
+        n = max(1, min(layer.N, int(args.cpu_seconds / max(t1, 1e-3))))
+        t = run(n) if n > 1 else t1
+        rec["cpu_baseline"] = {"value": macs // layer.N * n / t / 1e9, "unit": "GMAC/s", "cores": oracle.threads(),
+                               "kind": "oracle", "sample": f"first {n} of {layer.N} images of {layer.name}, all "
+                                                           f"{layer.F} filters, oracle.bwn, {t:.2f} s"}
+    return rec
+
+
 # Table III's "GPU" column for the XNOR convolution (GTX 1080 Ti, mean of 100 runs, compute only), ms
 PAPER_GPU_XNOR_MS = {256: 0.0237, 512: 0.0692, 1024: 0.2519, 2048: 0.9859}
 
@@ -360,6 +438,10 @@ def main():
     if args.image:
         for side in (int(v) for v in args.image_sides.split(",")):
             print(json.dumps(run_image(args, xb, torch, side)), flush=True)
+        return
+    if args.bwn:
+        for lname in (list(LAYERS) if args.sweep else [args.layer]):
+            print(json.dumps(run_bwn(args, xb, torch, LAYERS[lname], make_input, make_weights)), flush=True)
         return
     layers = list(LAYERS) if args.sweep else [args.layer]
     algos = ["tiled", "mfma"] if args.sweep else [args.algo]

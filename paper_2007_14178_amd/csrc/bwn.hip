@@ -11,7 +11,7 @@
 //
 //   bwn_mfma_kernel: rows of the MFMA = 32 filters, columns = 32 consecutive output pixels of one
 //   image, reduction = channel pairs at a fixed tap.  A workgroup (4 waves = 4 filter tiles) owns
-//   up to 7 pixel tiles; per chunk of channels it stages the input rows under them once in LDS as
+//   up to 6 pixel tiles; per chunk of channels it stages the input rows under them once in LDS as
 //   fp32, zero where the image ends (that is the zero padding), and the chunk's filter words.  The
 //   B operand of each MFMA is one LDS dword per lane (lane = pixel, its channel = pair member);
 //   the A operand is +-1.0 made from the lane's filter word with three integer instructions per
@@ -29,8 +29,10 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;
 constexpr int kFiltersPerWg = 128;   // 4 waves x 32 rows
-constexpr int kMaxTiles = 7;         // pixel tiles (of 32) per workgroup: 7 x 16 accumulator registers
+constexpr int kMaxTiles = 6;         // pixel tiles (of 32) per workgroup: 6 x 16 accumulator registers
 constexpr size_t kLdsBudget = 64 * 1024;
+constexpr int kPre = 32;             // input values a thread fetches ahead per chunk
+constexpr int kPreWords = 8;         // filter words a thread fetches ahead per chunk (kh*kw <= 16)
 
 struct BwnParams {
     const float *I;
@@ -85,56 +87,103 @@ __device__ __attribute__((always_inline)) void bwn_workgroup(const BwnParams &p,
     const int chunks_per_word = 32 / p.chan;
     const int nchunks = (p.C + p.chan - 1) / p.chan;
     const float *img = p.I + (size_t)n * p.C * p.H * p.W;
-    for (int ch = 0; ch < nchunks; ++ch) {
+
+    // Staging.  The chunk's input rows are fetched into registers one chunk ahead, while the
+    // previous chunk's MFMAs run, and written to LDS between two barriers.  Thread layout: 32
+    // lanes along a row, the 8 half-waves on 8 channels; the q-th value of a thread is column
+    // block m, channel group kc, row r in the order the counters below step through.
+    const int kcn = p.chan >> 3;
+    const int nq = ((p.pitch + 31) >> 5) * kcn * rows;        // <= kPre (the host's plan sees to it)
+    const bool words_ahead = taps * kFiltersPerWg <= kPreWords * kThreads;
+    float nxt[kPre];
+    uint32_t nxw[kPreWords];
+    // (xl and sub pass through an empty asm in each call: otherwise the per-value offsets, which do
+    // not change from chunk to chunk, are all kept in registers across the MFMA loop)
+    auto prefetch = [&](int ch) __attribute__((always_inline)) {
         const int c0 = ch * p.chan;
-        const int cw = ch / chunks_per_word;
-        const int bit0 = (ch % chunks_per_word) * p.chan;
-        __syncthreads();                                 // the previous chunk has been read
-        // input rows of the chunk: 32 lanes along a row, 8 (channel, row) segments per pass, eight
-        // passes' loads in flight before their LDS writes
-        const int nseg = p.chan * rows;
-        for (int xw0 = 0; xw0 < p.pitch; xw0 += 32) {
-            const int xw = xw0 + (threadIdx.x & 31), ix = xw - p.pw;
-            const bool colok = xw < p.pitch && ix >= 0 && ix < p.W;
-            for (int sg = threadIdx.x >> 5; sg < nseg; sg += 64) {
-                float v[8];
+        int xl = threadIdx.x & 31, sub = threadIdx.x >> 5;
+        asm volatile("" : "+v"(xl), "+v"(sub));
+        int m = 0, kc = 0, r = 0;
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int s2 = sg + 8 * u;
-                    const int c = s2 / rows, r = s2 - c * rows;
-                    const int iy = iy0 + r, cg = c0 + c;
-                    const bool in = s2 < nseg && colok && cg < p.C && iy >= 0 && iy < p.H;
-                    v[u] = in ? img[((size_t)cg * p.H + iy) * p.W + ix] : 0.f;
-                }
+        for (int q = 0; q < kPre; ++q) {
+            float v = 0.f;
+            if (q < nq) {
+                const int xw = 32 * m + xl, ix = xw - p.pw, cg = c0 + sub + 8 * kc, iy = iy0 + r;
+                if (xw < p.pitch && ix >= 0 && ix < p.W && cg < p.C && iy >= 0 && iy < p.H)
+                    v = img[(unsigned)((cg * p.H + iy) * p.W + ix)];   // one image: below 2^30 floats
+            }
+            nxt[q] = v;
+            if (++r == rows) { r = 0; if (++kc == kcn) { kc = 0; ++m; } }
+        }
+        if (words_ahead) {
+            const int cw = ch / chunks_per_word, bit0 = (ch % chunks_per_word) * p.chan;
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int s2 = sg + 8 * u;
-                    const int c = s2 / rows, r = s2 - c * rows;
-                    if (s2 < nseg && xw < p.pitch) tile[c * plane + r * p.pitch + xw] = v[u];
-                }
+            for (int q = 0; q < kPreWords; ++q) {
+                const int i = q * kThreads + threadIdx.x;
+                const int t = i / kFiltersPerWg, f = fbase + (i - t * kFiltersPerWg);
+                nxw[q] = (i < taps * kFiltersPerWg && f < p.F)
+                             ? p.Wpk[((size_t)f * taps + t) * p.Cw + cw] >> bit0 : 0u;
             }
         }
-        for (int i = threadIdx.x; i < taps * kFiltersPerWg; i += kThreads) {
-            const int t = i / kFiltersPerWg, fi = i - t * kFiltersPerWg;
-            const int f = fbase + fi;
-            fw[i] = f < p.F ? p.Wpk[((size_t)f * taps + t) * p.Cw + cw] >> bit0 : 0u;
+    };
+    auto commit = [&](int ch) __attribute__((always_inline)) {
+        int xl = threadIdx.x & 31, sub = threadIdx.x >> 5;
+        asm volatile("" : "+v"(xl), "+v"(sub));
+        int m = 0, kc = 0, r = 0;
+#pragma unroll
+        for (int q = 0; q < kPre; ++q) {
+            const int xw = 32 * m + xl;
+            if (q < nq && xw < p.pitch) tile[(sub + 8 * kc) * plane + r * p.pitch + xw] = nxt[q];
+            if (++r == rows) { r = 0; if (++kc == kcn) { kc = 0; ++m; } }
         }
+        if (words_ahead) {
+#pragma unroll
+            for (int q = 0; q < kPreWords; ++q) {
+                const int i = q * kThreads + threadIdx.x;
+                if (i < taps * kFiltersPerWg) fw[i] = nxw[q];
+            }
+        } else {
+            const int cw = ch / chunks_per_word, bit0 = (ch % chunks_per_word) * p.chan;
+            for (int i = threadIdx.x; i < taps * kFiltersPerWg; i += kThreads) {
+                const int t = i / kFiltersPerWg, f = fbase + (i - t * kFiltersPerWg);
+                fw[i] = f < p.F ? p.Wpk[((size_t)f * taps + t) * p.Cw + cw] >> bit0 : 0u;
+            }
+        }
+    };
+
+    prefetch(0);
+    for (int ch = 0; ch < nchunks; ++ch) {
+        __syncthreads();                                 // the previous chunk has been read
+        commit(ch);
         __syncthreads();
+        if (ch + 1 < nchunks) prefetch(ch + 1);
 
         for (int ky = 0; ky < p.kh; ++ky)
             for (int kx = 0; kx < p.kw; ++kx) {
                 const uint32_t word = fw[(ky * p.kw + kx) * kFiltersPerWg + wave * 32 + col] >> half;
                 const int toff = ky * p.pitch + kx;
+                // B operands are read one step (NT MFMAs) ahead of their use; the scheduling
+                // barriers keep the compiler from moving each read back next to its MFMA
+                const int ncp = p.chan / 2;
+                float bc[NT], bn[NT];
+#pragma unroll
+                for (int j = 0; j < NT; ++j) bc[j] = tile[base[j] + toff];
                 for (int q = 0; q < p.chan / 8; ++q) {       // four channel pairs at a time
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
                         const int cp = 4 * q + u;
+                        const int off = toff + 2 * min(cp + 1, ncp - 1) * plane;
+#pragma unroll
+                        for (int j = 0; j < NT; ++j) bn[j] = tile[base[j] + off];
+                        __builtin_amdgcn_sched_barrier(0);
                         // bit (2*cp + half) of the chunk: 1 -> +1.0f, 0 -> -1.0f
                         const float a = __uint_as_float(0xBF800000u ^ (((word >> (2 * cp)) & 1u) << 31));
-                        const int off = toff + 2 * cp * plane;
 #pragma unroll
                         for (int j = 0; j < NT; ++j)
-                            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, tile[base[j] + off], acc[j], 0, 0, 0);
+                            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bc[j], acc[j], 0, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                        for (int j = 0; j < NT; ++j) bc[j] = bn[j];
                     }
                 }
             }
@@ -176,8 +225,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwn_mfma_kernel(BwnParams p)
         case 3: bwn_workgroup<3>(p, n, fbase, p0, p1); break;
         case 4: bwn_workgroup<4>(p, n, fbase, p0, p1); break;
         case 5: bwn_workgroup<5>(p, n, fbase, p0, p1); break;
-        case 6: bwn_workgroup<6>(p, n, fbase, p0, p1); break;
-        default: bwn_workgroup<7>(p, n, fbase, p0, p1); break;
+        default: bwn_workgroup<6>(p, n, fbase, p0, p1); break;
     }
 }
 
@@ -232,12 +280,23 @@ Plan make_plan(const Geom &g)
 {
     Plan pl{};
     const long long OHW = (long long)g.OH * g.OW;
-    if (g.kh * g.kw > 64 || OHW > (1 << 24)) return pl;
+    if (g.kh * g.kw > 64 || OHW > (1 << 24) || (long long)g.C * g.H * g.W >= (1LL << 30)) return pl;
     pl.pitch = g.W + 2 * g.pw;
-    // fewer pixel tiles per workgroup when the launch would otherwise leave compute units idle
-    int most = (int)std::min<long long>(kMaxTiles, (OHW + 31) / 32);
-    while (most > 2 && (long long)g.N * ceil_div(g.F, kFiltersPerWg) * ceil_div(OHW, 32LL * most) < 512)
-        --most;
+    // Pixel tiles per workgroup.  The matrix pipe of a compute unit is shared by the workgroups on
+    // it, so a launch takes about ceil(workgroups / 256 CUs) x (tiles per workgroup + a fixed
+    // per-workgroup cost of about one tile), and a compute unit with a single workgroup (one wave
+    // per SIMD) cannot hide its own stalls, which counts like a second one: take the tile count
+    // that minimises that, tiles shared out evenly over the image's workgroups; ties go to more
+    // tiles (more reuse of each A operand).
+    const int total = (int)((OHW + 31) / 32);
+    int most = 1;
+    long long best = -1;
+    for (int t = 1; t <= std::min(kMaxTiles, total); ++t) {
+        const int groups = ceil_div(total, t), even = ceil_div(total, groups);
+        const long long blocks = (long long)g.N * ceil_div(g.F, kFiltersPerWg) * groups;
+        const long long cost = std::max<long long>(2, (blocks + 255) / 256) * (even + 1);
+        if (best < 0 || cost <= best) { best = cost; most = even; }
+    }
     for (int tiles = most; tiles >= 1; --tiles) {
         // 32*tiles consecutive pixels span at most this many output rows
         const int orows = (int)std::min<long long>(g.OH, (32LL * tiles + g.OW - 2) / g.OW + 1);
@@ -245,7 +304,8 @@ Plan make_plan(const Geom &g)
         // no more channels per chunk than the layer has (rounded up to 8)
         for (int chan = g.C > 16 ? 32 : g.C > 8 ? 16 : 8; chan >= 8; chan /= 2) {
             const size_t lds = ((size_t)chan * rows * pl.pitch + (size_t)g.kh * g.kw * kFiltersPerWg) * 4;
-            if (lds <= kLdsBudget) {
+            const int ahead = ((pl.pitch + 31) / 32) * (chan / 8) * rows;   // values per thread and chunk
+            if (lds <= kLdsBudget && ahead <= kPre) {
                 pl.ok = true; pl.tiles = tiles; pl.chan = chan; pl.rows_max = rows; pl.lds = lds;
                 return pl;
             }
