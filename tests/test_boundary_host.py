@@ -128,6 +128,14 @@ def test_null_and_alignment_rejected(xb):
     assert L.xnor_forward_image(ok, ok, ok, ip, odd, None, None) == xb.E_ALIGN
     assert L.xnor_forward_image(ok, ok, ok, ip, ok, odd, None) == xb.E_ALIGN
     assert L.xnor_forward_image_supported(None) == xb.E_NULL
+    # Binary-Weight-Network layer
+    assert L.xnor_bwn_conv2d_fwd(None, ok, ok, sp, ok, None) == xb.E_NULL
+    assert L.xnor_bwn_conv2d_fwd(ok, ok, ok, sp, None, None) == xb.E_NULL
+    assert L.xnor_bwn_conv2d_fwd(ok, odd, ok, sp, ok, None) == xb.E_ALIGN
+    assert L.xnor_bwn_conv2d_fwd_algo(ok, ok, ok, sp, ok, xb.ALGO_TILED, None) == xb.E_UNSUPPORTED
+    assert L.xnor_bwn_conv2d_fwd_algo(ok, ok, ok, sp, ok, 99, None) == xb.E_UNSUPPORTED
+    wide = xb.Shape(1, 64, 8, 4000, 8, 3, 3, 1, 1, 1, 1)      # rows too wide for the matrix-core kernel's LDS band
+    assert L.xnor_bwn_conv2d_fwd_algo(ok, ok, ok, ctypes.byref(wide.c()), ok, xb.ALGO_MFMA, None) == xb.E_UNSUPPORTED
 
 
 def test_binding_refuses_cpu_tensors(xb):
