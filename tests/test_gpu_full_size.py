@@ -78,3 +78,43 @@ def test_full_size_layer(name):
     assert abs(float(interior.mean())) < 5 * (L.n_red / count) ** 0.5
     if count >= 4096:
         assert 0.8 < float(interior.var()) / L.n_red < 1.25
+
+
+@pytest.mark.parametrize("name", ["c5", "c4_conv2", "c2_k7"])
+def test_full_size_bwn_layer(name):
+    """The Binary-Weight-Network layer at full size, as bench.py --bwn launches it: sampled (image,
+    filter) planes against the oracle at the bar |got - ref| <= 1e-5 * alpha * sum|I| over the window;
+    over the whole tensor the bound |out| <= alpha * sum|I| and agreement of the two kernels."""
+    from paper_2007_14178_amd import binding as xb
+    L = LAYERS[name]
+    print(f"case bwn layer={name} full size N={L.N}", flush=True)
+    I, Wt = make_input(L), make_weights(L)
+    full = (L.N, L.C, L.H, L.W, L.F, L.kh, L.kw, L.sh, L.sw, L.ph, L.pw)
+    s = xb.Shape(*full)
+    dI, dW = torch.from_numpy(I).cuda(), torch.from_numpy(Wt).cuda()
+    Wpk, alpha, _ = xb.xnor_filter_prepare(dW)
+    out = xb.xnor_bwn_conv2d_fwd(dI, Wpk, alpha, s)
+    torch.cuda.synchronize()
+    out_h = out.cpu().numpy().astype(np.float64)
+
+    rng = np.random.default_rng(4321 + L.config)
+    imgs = sorted({0, L.N - 1, int(rng.integers(0, L.N))})
+    budget = 6e8
+    nf = int(max(2, min(L.F, budget / (len(imgs) * L.binary_macs / (L.N * L.F)))))
+    fsel = np.unique(np.concatenate([[0, L.F - 1], rng.integers(0, L.F, size=nf)]))[:max(nf, 2)]
+    sub = oracle.Shape(1, L.C, L.H, L.W, len(fsel), L.kh, L.kw, L.sh, L.sw, L.ph, L.pw)
+    a_ref = oracle.alpha(Wt).astype(np.float64)
+    for n in imgs:
+        O_ref, S = oracle.bwn(I[n:n + 1], Wt[fsel], sub, want_scale=True)
+        bar = RTOL * a_ref[fsel][None, :, None, None] * S[:, None]
+        assert (np.abs(out_h[n:n + 1, fsel] - O_ref) <= bar).all(), f"image {n}"
+
+    # whole tensor: |O| <= alpha * S with S from the library's own channel mean and box filter
+    _, K, _ = xb.xnor_input_prepare(dI, s)
+    S_all = K.to(torch.float64) * (L.C * L.kh * L.kw)
+    bound = alpha.to(torch.float64)[None, :, None, None] * S_all[:, None] * (1 + 1e-4)
+    assert bool((out.to(torch.float64).abs() <= bound).all())
+    if name != "c5":                                      # the one-thread-per-output kernel: minutes at c5
+        ref = xb.xnor_bwn_conv2d_fwd(dI, Wpk, alpha, s, algo=xb.ALGO_DIRECT)
+        torch.cuda.synchronize()
+        assert bool(((out - ref).to(torch.float64).abs() <= 2e-6 * bound).all())
