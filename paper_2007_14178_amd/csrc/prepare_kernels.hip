@@ -36,7 +36,7 @@ __global__ __launch_bounds__(256) void binarize_pack_kernel(const float *__restr
         if (cbase + 32 <= C) {
             float v[32];
 #pragma unroll
-            for (int j = 0; j < 32; ++j) v[j] = __builtin_nontemporal_load(src + (long long)(cbase + j) * HW);
+            for (int j = 0; j < 32; ++j) v[j] = src[(long long)(cbase + j) * HW];
 #pragma unroll
             for (int j = 0; j < 32; ++j) word |= (v[j] >= 0.0f ? 1u : 0u) << j;
         } else {
@@ -157,7 +157,7 @@ __global__ __launch_bounds__(64 * kPackMeanSlices) void pack_and_mean_kernel(
             if (cbase + 32 <= C) {
                 float v[32];
 #pragma unroll
-                for (int j = 0; j < 32; ++j) v[j] = __builtin_nontemporal_load(src + (long long)(cbase + j) * HW);
+                for (int j = 0; j < 32; ++j) v[j] = src[(long long)(cbase + j) * HW];
 #pragma unroll
                 for (int j = 0; j < 32; ++j) {
                     word |= (v[j] >= 0.0f ? 1u : 0u) << j;
@@ -189,6 +189,84 @@ __global__ __launch_bounds__(64 * kPackMeanSlices) void pack_and_mean_kernel(
     }
 }
 
+// The same pass with four consecutive pixels per lane (one 16-byte load per lane and channel, 1 KB
+// contiguous per wave and load instruction): measured 6.7 TB/s for this access pattern against
+// 5.5 TB/s with one pixel per lane.  Needs H*W to be a multiple of 4 (so that a lane's four pixels
+// share an image) and 16-byte aligned x and A.  Block = 256 pixels x S slices.
+constexpr int kPack4Slices = 8;
+constexpr int kPack4Batch = 8;      // channels whose loads are in flight together
+
+__global__ __launch_bounds__(64 * kPack4Slices) void pack_and_mean4_kernel(
+    const float *__restrict__ x, long long NP, int C, int HW, int Cw, int Cwp,
+    uint32_t *__restrict__ packed, float *__restrict__ A)
+{
+    extern __shared__ double pm_smem[];
+    const int lane = threadIdx.x, s = threadIdx.y, S = blockDim.y;
+    double *part = pm_smem;                                               // [S][4][64]
+    uint32_t *words = reinterpret_cast<uint32_t *>(pm_smem + S * 256);    // [4][64][Cwp], Cwp odd
+    const long long p0 = (long long)blockIdx.x * 256;
+    const long long p = p0 + 4 * lane;
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    if (p < NP) {
+        const long long n = p / HW;
+        const int hw = (int)(p - n * HW);
+        const float *src = x + (n * C) * (long long)HW + hw;
+        // batches of kPack4Batch channels; the next batch's loads are issued before the current
+        // batch's values are used, so that a wave always has loads in flight
+        auto fetch = [&](int w, int b, float4 (&v)[kPack4Batch]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int j = 0; j < kPack4Batch; ++j) {
+                const int c = 32 * w + b + j;
+                v[j] = (w < Cw && c < C) ? *reinterpret_cast<const float4 *>(src + (long long)c * HW)
+                                         : make_float4(-1.f, -1.f, -1.f, -1.f);   // tail channels: bit 0
+            }
+        };
+        float4 cur[kPack4Batch], nxt[kPack4Batch];
+        fetch(s, 0, cur);
+        for (int w = s; w < Cw; w += S) {
+            uint32_t word[4] = {0u, 0u, 0u, 0u};
+            const int cbase = 32 * w;
+#pragma unroll
+            for (int b = 0; b < 32; b += kPack4Batch) {
+                if (b + kPack4Batch < 32) fetch(w, b + kPack4Batch, nxt);
+                else fetch(w + S, 0, nxt);
+#pragma unroll
+                for (int j = 0; j < kPack4Batch; ++j) {
+                    const bool live = cbase + b + j < C;
+                    const float e[4] = {cur[j].x, cur[j].y, cur[j].z, cur[j].w};
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        word[k] |= (e[k] >= 0.0f ? 1u : 0u) << (b + j);
+                        acc[k] += live ? (double)fabsf(e[k]) : 0.0;
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < kPack4Batch; ++j) cur[j] = nxt[j];
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) words[(k * 64 + lane) * Cwp + w] = word[k];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) part[(s * 4 + k) * 64 + lane] = acc[k];
+    __syncthreads();
+    // pixel 4*lane + k: slice k % S adds up the slices' sums (fixed order) when S >= 4
+    for (int k = s; k < 4; k += S) {
+        if (p + k < NP) {
+            double sum = part[k * 64 + lane];
+            for (int t = 1; t < S; ++t) sum += part[(t * 4 + k) * 64 + lane];
+            A[p + k] = (float)(sum / (double)C);
+        }
+    }
+    const int npx = (int)min((long long)256, NP - p0);
+    const int nwords = npx * Cw;
+    uint32_t *dst = packed + p0 * Cw;
+    for (int i = s * 64 + lane; i < nwords; i += 64 * S) {
+        const int px = i / Cw, w = i - px * Cw;
+        dst[i] = words[((px & 3) * 64 + (px >> 2)) * Cwp + w];
+    }
+}
+
 bool pack_and_mean_supports(int C) { return (C + 31) / 32 <= 512; }
 
 hipError_t launch_pack_and_mean(const float *x, int N, int C, int H, int W, uint32_t *packed,
@@ -196,6 +274,16 @@ hipError_t launch_pack_and_mean(const float *x, int N, int C, int H, int W, uint
 {
     const int HW = H * W, Cw = (C + 31) / 32, Cwp = Cw | 1;
     const long long NP = (long long)N * HW;
+    if (HW % 4 == 0 && ((uintptr_t)x & 15) == 0 && NP >= 256 * 256) {
+        int S4 = 1;
+        while (S4 < kPack4Slices && 2 * S4 <= Cw) S4 *= 2;
+        const size_t smem4 = (size_t)S4 * 256 * sizeof(double) + (size_t)256 * Cwp * sizeof(uint32_t);
+        if (smem4 <= 64 * 1024) {
+            pack_and_mean4_kernel<<<dim3(ceil_div(NP, 256)), dim3(64, S4), smem4, st>>>(x, NP, C, HW, Cw,
+                                                                                      Cwp, packed, A);
+            return hipGetLastError();
+        }
+    }
     int S = 1;
     while (S < kPackMeanSlices && 2 * S <= Cw) S *= 2;
     const size_t smem = (size_t)S * 64 * sizeof(double) + (size_t)64 * Cwp * sizeof(uint32_t);

@@ -258,3 +258,21 @@ def test_two_call_matrix_core_path(xb, shape):
         assert np.array_equal(dot.cpu().numpy(), d_ref), "dot"
         assert_rel(out.cpu().numpy(), O_ref, "out")
         assert torch.equal(out, out1) and torch.equal(dot, dot1)
+
+
+@pytest.mark.parametrize("shape", [(3, 40, 148, 150), (1, 33, 260, 256), (2, 8, 200, 180), (1, 100, 256, 257)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_input_prepare_on_large_images(xb, shape):
+    """Images large enough for the four-pixels-per-lane pass of xnor_input_prepare (H*W a multiple of
+    4 and at least 65536 pixels in the batch), with channel tails and a ragged last block; the last
+    shape has an odd H*W and takes the one-pixel-per-lane pass at the same size."""
+    N, C, H, W = shape
+    print(f"case input_prepare shape={shape}", flush=True)
+    rng = np.random.default_rng(zlib.crc32(("prep" + str(shape)).encode()))
+    _, I, _ = random_layer(rng, "t", N, C, H, W, 1, 3, 3, 1, 1, 1, 1)
+    s = xb.Shape(N, C, H, W, 1, 3, 3, 1, 1, 1, 1)
+    Ipk, K, A = xb.xnor_input_prepare(dev(I), s)
+    torch.cuda.synchronize()
+    assert np.array_equal(words(Ipk), oracle.pack(I)), "Ipk"
+    assert_rel(A.cpu().numpy(), oracle.channel_mean_abs(I), "A")
+    assert_rel(K.cpu().numpy(), oracle.scale_K(I, oracle.Shape(N, C, H, W, 1, 3, 3, 1, 1, 1, 1)), "K")
