@@ -263,9 +263,8 @@ def test_two_call_matrix_core_path(xb, shape):
 @pytest.mark.parametrize("shape", [(3, 40, 148, 150), (1, 33, 260, 256), (2, 8, 200, 180), (1, 100, 256, 257)],
                          ids=lambda s: "x".join(map(str, s)))
 def test_input_prepare_on_large_images(xb, shape):
-    """Images large enough for the four-pixels-per-lane pass of xnor_input_prepare (H*W a multiple of
-    4 and at least 65536 pixels in the batch), with channel tails and a ragged last block; the last
-    shape has an odd H*W and takes the one-pixel-per-lane pass at the same size."""
+    """xnor_input_prepare on images of 40 000 to 66 000 pixels, with channel tails and a ragged last
+    block (H*W odd and even)."""
     N, C, H, W = shape
     print(f"case input_prepare shape={shape}", flush=True)
     rng = np.random.default_rng(zlib.crc32(("prep" + str(shape)).encode()))
