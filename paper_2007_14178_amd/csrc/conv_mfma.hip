@@ -39,7 +39,6 @@ constexpr int kWN = 4;            // 32-pixel tiles per wave (at most)
 constexpr int kBandPixels = 2 * 32 * kWN;   // 2 wave columns
 constexpr int kFilterTile = 2 * 32 * kWM;   // 2 wave rows
 constexpr int kRing = 4;          // register ring of filter operands: loads run kRing-1 steps ahead
-constexpr int kPatchPitch = 36;    // floats per row of a wave's 32x32 output patch in LDS (144 bytes)
 constexpr int kScaleOne = 0x7f7f7f7f;       // E8M0 exponent 127 = 2^0
 constexpr int kXcdShift = 3, kXcds = 1 << kXcdShift;   // MI355X: 8 XCDs of 32 CUs
 
@@ -69,7 +68,7 @@ struct MfmaParams {
     int nchunks;
     int pitch16;     // LDS slot pitch in 16-byte units (CH + 1, odd)
     int buf16;       // distance between the two LDS chunk buffers in 16-byte units (0: one buffer)
-    int kl16;        // start of the K / alpha area in LDS (16-byte units): behind table and patches
+    int kl16;        // start of the K / alpha area in LDS (16-byte units): behind the step table
     int tab16;       // start of the step-offset table in LDS (16-byte units)
     int tab_len;     // its uint32 entries: one per step of the tile, a multiple of 4
     int chunk_pad;   // steps per chunk in the workspace and the table (a whole number of rings)
@@ -527,11 +526,6 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
 #undef XNOR_WAIT
 
     // ---- step 3: out = float(dot) * K * alpha ----
-    // The MFMA result has pixels along lanes and filters along registers, which would make every
-    // store a 4-byte-per-lane instruction.  Each wave instead passes its 32x32 tiles through
-    // private LDS patches and reads them back with four consecutive pixels of one filter per lane,
-    // so that one store instruction writes eight 128-byte runs (16 bytes per lane).  The band's K
-    // and the tile's alpha wait in LDS since the kernel's start (no global-load latency here).
     __syncthreads();   // all waves are done with the staged input
     if constexpr (CHAIN) {
         // Chained form (the paper's closing proposal, Sec. V: hand the binary output to the next
@@ -599,103 +593,48 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
         }
         return;
     }
+    // fp32 output straight from the accumulators: lane l holds pixel l%32 of a tile and, in register
+    // r, filter 8*(r/4) + 4*(l/32) + r%4, so one store instruction writes 32 consecutive pixels of
+    // two filter planes (two 128-byte runs).  The band's K and the tile's alpha wait in LDS since
+    // the kernel's start (no global-load latency here).
     float *__restrict__ outp = p.out;
     int32_t *__restrict__ dotp = p.dot;
-    float *patch = reinterpret_cast<float *>(lds) + wave * (32 * kPatchPitch);   // + 4 waves' worth: the second patch
     // lane-derived indices of this phase are formed from a copy of the lane id that the compiler
     // cannot see through, or it computes them at kernel start and holds them across the MFMA loop
     int lane_e = lane;
     asm volatile("" : "+v"(lane_e));
-    const int p4 = (lane_e & 7) * 4;    // first of this lane's four pixels within a tile
-    const int fl = lane_e >> 3;         // filter within a tile, plus 8*k
     const int l32e = lane_e & 31, kge = lane_e >> 5;
-    if (my_nt > 0) {
-        // the lane's pixel quads (one per tile column): position, validity, contiguity, K
-        int nvq[kWN], poq[kWN];
-        bool quadq[kWN];
-        long long obaseq[kWN];
-        float4 kq[kWN];
-        float al[kWM][4];
+    float al[kWM][16];
 #pragma unroll
-        for (int j = 0; j < kWN; ++j) {
-            const int q0 = (tile0 + j) * 32 + p4;
-            nvq[j] = j < my_nt ? min(4, npix - q0) : 0;       // valid pixels of the quad (may be <= 0)
-            const int qc = nvq[j] > 0 ? q0 : 0;
-            const int Rl = qc / p.OW, ox = qc - Rl * p.OW;
-            const int R = R0 + Rl;
-            const int n = R / p.OH, oy = R - n * p.OH;
-            const int po = oy * p.OW + ox;                    // offset inside the (n, f) plane
-            poq[j] = po;
-            quadq[j] = nvq[j] == 4 && po + 3 < OHW;           // four pixels of one image: one 16-byte run
-            obaseq[j] = (long long)n * p.F * OHW + po;
-            kq[j] = *reinterpret_cast<const float4 *>(&Kl[qc]);   // (entries past the band are zeros)
-        }
+    for (int i = 0; i < kWM; ++i)
 #pragma unroll
-        for (int i = 0; i < kWM; ++i)
+        for (int r = 0; r < 16; ++r) al[i][r] = Al[(wm * kWM + i) * 32 + 8 * (r >> 2) + 4 * kge + (r & 3)];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) al[i][k] = Al[(wm * kWM + i) * 32 + fl + 8 * k];
-
-        // Tiles go through two patches in turn: tile t+1 is written while the rows of tile t are on
-        // their way back from LDS (LDS executes a wave's requests in order, so a patch can be
-        // rewritten right after the reads of its previous tile were issued).
-        auto write_patch = [&](int t, const v16f &a) {
-            float *pt = patch + (t & 1) * (4 * 32 * kPatchPitch);
+    for (int j = 0; j < kWN; ++j) {
+        if (j >= my_nt) break;
+        const int q = (tile0 + j) * 32 + l32e;                // pixel within the band
+        if (q >= npix) continue;
+        const int Rl = q / p.OW, ox = q - Rl * p.OW;
+        const int R = R0 + Rl;
+        const int n = R / p.OH, oy = R - n * p.OH;
+        const float kv = Kl[q];
+        const long long ob = (long long)n * p.F * OHW + oy * p.OW + ox;
 #pragma unroll
-            for (int r = 0; r < 16; ++r)
-                pt[((r >> 2) * 8 + kge * 4 + (r & 3)) * kPatchPitch + l32e] = a[r];
-        };
-        constexpr int T = kWN * kWM;   // tile t = j * kWM + i
-        const long long plane8 = 8LL * OHW;
-        write_patch(0, acc[0][0]);
+        for (int i = 0; i < kWM; ++i) {
+            const int f0 = (ftile * (2 * kWM) + wm * kWM + i) * 32 + 4 * kge;   // this lane's first filter
+            float *po = outp + ob + (long long)f0 * OHW;
+            const bool whole = f0 - 4 * kge + 32 <= p.F;                        // uniform: all 32 filters exist
 #pragma unroll
-        for (int t = 0; t < T; ++t) {
-            const int j = t / kWM, i = t % kWM;
-            if (j >= my_nt) break;
-            if (t + 1 < T && (t + 1) / kWM < my_nt) write_patch(t + 1, acc[(t + 1) % kWM][(t + 1) / kWM]);
-            const float *pt = patch + (t & 1) * (4 * 32 * kPatchPitch);
-            const int f_tile = (ftile * (2 * kWM) + wm * kWM + i) * 32;
-            const long long o0 = obaseq[j] + (long long)(f_tile + fl) * OHW;
-            // every lane of the wave has a whole quad inside one image and a real filter: straight code
-            const bool lane_fast = quadq[j] && f_tile + 32 <= p.F;
-            if (__builtin_amdgcn_ballot_w64(!lane_fast) == 0) {
-                float4 d4[4];
+            for (int r = 0; r < 16; ++r) {
+                const int df = 8 * (r >> 2) + (r & 3);
+                if (whole || f0 + df < p.F) po[(long long)df * OHW] = acc[i][j][r] * (kv * al[i][r]);
+            }
+            if (dotp) {
+                int32_t *pd = dotp + ob + (long long)f0 * OHW;
 #pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    d4[k] = *reinterpret_cast<const float4 *>(&pt[(fl + 8 * k) * kPatchPitch + p4]);
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const float4 d = d4[k];
-                    const float a = al[i][k];
-                    const long long o = o0 + k * plane8;
-                    *reinterpret_cast<float4 *>(outp + o) =
-                        make_float4(d.x * (kq[j].x * a), d.y * (kq[j].y * a), d.z * (kq[j].z * a), d.w * (kq[j].w * a));
-                    if (dotp)
-                        *reinterpret_cast<int4 *>(dotp + o) = make_int4((int)d.x, (int)d.y, (int)d.z, (int)d.w);
-                }
-            } else {
-                // tiles cut by the band's end, by an image boundary or by F: lane by lane, pixel by
-                // pixel; pixel e of a quad lies m images further on (m <= 3), i.e. m*(F-1) planes
-                // beyond o + e
-                const int nv = nvq[j];
-                const float kk[4] = {kq[j].x, kq[j].y, kq[j].z, kq[j].w};
-                const long long plane_skip = (long long)(p.F - 1) * OHW;
-#pragma nounroll
-                for (int k = 0; k < 4; ++k) {
-                    const int f = f_tile + fl + 8 * k;
-                    const float4 d = *reinterpret_cast<const float4 *>(&pt[(fl + 8 * k) * kPatchPitch + p4]);
-                    if (f >= p.F || nv <= 0) continue;
-                    const float a = Al[(wm * kWM + i) * 32 + fl + 8 * k];
-                    const long long o = o0 + k * plane8;
-                    const float dd[4] = {d.x, d.y, d.z, d.w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        if (e >= nv) break;
-                        const int pe = poq[j] + e;
-                        const int m = (pe >= OHW) + (pe >= 2 * OHW) + (pe >= 3 * OHW);
-                        const long long oe = o + e + m * plane_skip;
-                        outp[oe] = dd[e] * (kk[e] * a);
-                        if (dotp) dotp[oe] = (int32_t)dd[e];
-                    }
+                for (int r = 0; r < 16; ++r) {
+                    const int df = 8 * (r >> 2) + (r & 3);
+                    if (whole || f0 + df < p.F) pd[(long long)df * OHW] = (int32_t)acc[i][j][r];
                 }
             }
         }
@@ -768,8 +707,9 @@ MfmaPlan make_plan(const Geom &g, const void *Ipk)
         return false;
     };
     if (!fit(kLdsTwoPerCU) && !fit(kLdsMax)) return pl;
-    // K and alpha sit behind the staging area and behind the output patches (which reuse its start)
-    const size_t ka_off = std::max(pl.lds_bytes - kKAlphaBytes, (size_t)2 * 4 * 32 * kPatchPitch * sizeof(float));
+    // K and alpha sit behind the staging area; the chained epilogue reuses the area's start for its
+    // per-pixel sums (2 x kBandPixels doubles)
+    const size_t ka_off = std::max(pl.lds_bytes - kKAlphaBytes, (size_t)2 * kBandPixels * sizeof(double));
     pl.kl16 = (int)(ka_off / 16);
     pl.lds_bytes = ka_off + kKAlphaBytes;
     if ((long long)slots * pl.CH >= (1 << 20)) return pl;   // fast-division range
