@@ -231,8 +231,8 @@ int xnor_forward_image(const float *I, const uint32_t *Wpk, const float *alpha, 
  * The sum is formed in fp32 (fp32 matrix-core accumulation, or a short chain of fp32 partial sums
  * in the one-thread-per-output kernel); its rounding error is relative to alpha * sum |I| over the
  * window, not to |out|.  No workspace.  xnor_bwn_conv2d_fwd_algo: XNOR_ALGO_AUTO, XNOR_ALGO_DIRECT
- * (any shape) or XNOR_ALGO_MFMA (XNOR_E_UNSUPPORTED where a pixel band of the input does not fit in
- * LDS or kh*kw > 64); other values XNOR_E_UNSUPPORTED.
+ * (any shape) or XNOR_ALGO_MFMA (XNOR_E_UNSUPPORTED where the input rows under 32 output pixels do not
+ * fit in 128 KB of LDS, or kh*kw > 64); other values XNOR_E_UNSUPPORTED.
  */
 int xnor_bwn_conv2d_fwd(const float *I, const uint32_t *Wpk, const float *alpha, const xnor_shape *s,
                         float *out, void *stream);

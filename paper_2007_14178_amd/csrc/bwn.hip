@@ -19,6 +19,7 @@
 //   along the pixels of a filter plane.
 //   bwn_direct_kernel: one thread per output, any shape; the fallback and the cross-check.
 #include <algorithm>
+#include <atomic>
 
 #include "xnor_internal.hpp"
 
@@ -30,7 +31,8 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 constexpr int kThreads = 256;
 constexpr int kFiltersPerWg = 128;   // 4 waves x 32 rows
 constexpr int kMaxTiles = 6;         // pixel tiles (of 32) per workgroup: 6 x 16 accumulator registers
-constexpr size_t kLdsBudget = 64 * 1024;
+constexpr size_t kLdsBudget = 64 * 1024;   // two workgroups per compute unit
+constexpr size_t kLdsWide = 128 * 1024;    // wide rows, staged synchronously: one workgroup per compute unit
 constexpr int kPre = 32;             // input values a thread fetches ahead per chunk
 constexpr int kPreWords = 8;         // filter words a thread fetches ahead per chunk (kh*kw <= 16)
 
@@ -51,7 +53,7 @@ struct BwnParams {
 // The work of one workgroup with NT pixel tiles.  NT is a template parameter so that the MFMA
 // loop is one basic block (operands of the next MFMAs are loaded ahead of the current ones) and
 // the accumulators are NT x 16 fixed registers.
-template <int NT>
+template <int NT, bool AHEAD>
 __device__ __attribute__((always_inline)) void bwn_workgroup(const BwnParams &p, int n, int fbase,
                                                               int p0, int p1)
 {
@@ -94,7 +96,7 @@ __device__ __attribute__((always_inline)) void bwn_workgroup(const BwnParams &p,
     // block m, channel group kc, row r in the order the counters below step through.
     const int kcn = p.chan >> 3;
     const int nq = ((p.pitch + 31) >> 5) * kcn * rows;        // <= kPre (the host's plan sees to it)
-    const bool words_ahead = taps * kFiltersPerWg <= kPreWords * kThreads;
+    const bool words_ahead = AHEAD && taps * kFiltersPerWg <= kPreWords * kThreads;
     float nxt[kPre];
     uint32_t nxw[kPreWords];
     // (xl and sub pass through an empty asm in each call: otherwise the per-value offsets, which do
@@ -133,7 +135,7 @@ __device__ __attribute__((always_inline)) void bwn_workgroup(const BwnParams &p,
 #pragma unroll
         for (int q = 0; q < kPre; ++q) {
             const int xw = 32 * m + xl;
-            if (q < nq && xw < p.pitch) tile[(sub + 8 * kc) * plane + r * p.pitch + xw] = nxt[q];
+            if (AHEAD && q < nq && xw < p.pitch) tile[(sub + 8 * kc) * plane + r * p.pitch + xw] = nxt[q];
             if (++r == rows) { r = 0; if (++kc == kcn) { kc = 0; ++m; } }
         }
         if (words_ahead) {
@@ -151,12 +153,41 @@ __device__ __attribute__((always_inline)) void bwn_workgroup(const BwnParams &p,
         }
     };
 
-    prefetch(0);
+    // Rows too wide for the registers set aside above (more than kPre values per thread and chunk)
+    // are staged the plain way, global -> LDS between the two barriers, eight loads in flight.
+    auto stage_now = [&](int ch) __attribute__((always_inline)) {
+        const int c0 = ch * p.chan;
+        const int nseg = p.chan * rows;
+        for (int xw0 = 0; xw0 < p.pitch; xw0 += 32) {
+            const int xw = xw0 + (threadIdx.x & 31), ix = xw - p.pw;
+            const bool colok = xw < p.pitch && ix >= 0 && ix < p.W;
+            for (int sg = threadIdx.x >> 5; sg < nseg; sg += 64) {
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int s2 = sg + 8 * u;
+                    const int c = s2 / rows, r = s2 - c * rows;
+                    const int iy = iy0 + r, cg = c0 + c;
+                    const bool in = s2 < nseg && colok && cg < p.C && iy >= 0 && iy < p.H;
+                    v[u] = in ? img[(unsigned)((cg * p.H + iy) * p.W + ix)] : 0.f;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int s2 = sg + 8 * u;
+                    const int c = s2 / rows, r = s2 - c * rows;
+                    if (s2 < nseg && xw < p.pitch) tile[c * plane + r * p.pitch + xw] = v[u];
+                }
+            }
+        }
+    };
+
+    if (AHEAD) prefetch(0);
     for (int ch = 0; ch < nchunks; ++ch) {
         __syncthreads();                                 // the previous chunk has been read
+        if (!AHEAD) stage_now(ch);
         commit(ch);
         __syncthreads();
-        if (ch + 1 < nchunks) prefetch(ch + 1);
+        if (AHEAD && ch + 1 < nchunks) prefetch(ch + 1);
 
         for (int ky = 0; ky < p.kh; ++ky)
             for (int kx = 0; kx < p.kw; ++kx) {
@@ -210,6 +241,7 @@ __device__ __attribute__((always_inline)) void bwn_workgroup(const BwnParams &p,
     }
 }
 
+template <bool AHEAD>
 __global__ __launch_bounds__(kThreads, 2) void bwn_mfma_kernel(BwnParams p)
 {
     int b = blockIdx.x;
@@ -219,13 +251,20 @@ __global__ __launch_bounds__(kThreads, 2) void bwn_mfma_kernel(BwnParams p)
     const int p0 = g * p.tiles * 32;
     const int p1 = min(p.OH * p.OW, p0 + p.tiles * 32);
     const int fbase = h * kFiltersPerWg;
-    switch ((p1 - p0 + 31) >> 5) {                       // tiles this workgroup really has
-        case 1: bwn_workgroup<1>(p, n, fbase, p0, p1); break;
-        case 2: bwn_workgroup<2>(p, n, fbase, p0, p1); break;
-        case 3: bwn_workgroup<3>(p, n, fbase, p0, p1); break;
-        case 4: bwn_workgroup<4>(p, n, fbase, p0, p1); break;
-        case 5: bwn_workgroup<5>(p, n, fbase, p0, p1); break;
-        default: bwn_workgroup<6>(p, n, fbase, p0, p1); break;
+    const int nt = (p1 - p0 + 31) >> 5;                  // tiles this workgroup really has
+    if (AHEAD) {
+        switch (nt) {
+            case 1: bwn_workgroup<1, AHEAD>(p, n, fbase, p0, p1); break;
+            case 2: bwn_workgroup<2, AHEAD>(p, n, fbase, p0, p1); break;
+            case 3: bwn_workgroup<3, AHEAD>(p, n, fbase, p0, p1); break;
+            case 4: bwn_workgroup<4, AHEAD>(p, n, fbase, p0, p1); break;
+            case 5: bwn_workgroup<5, AHEAD>(p, n, fbase, p0, p1); break;
+            default: bwn_workgroup<6, AHEAD>(p, n, fbase, p0, p1); break;
+        }
+    } else {
+        // wide rows: few tiles per workgroup anyway; two specialisations are enough
+        if (nt <= 2) bwn_workgroup<2, AHEAD>(p, n, fbase, p0, p1);
+        else bwn_workgroup<6, AHEAD>(p, n, fbase, p0, p1);
     }
 }
 
@@ -271,7 +310,7 @@ __global__ __launch_bounds__(256) void bwn_direct_kernel(const float *__restrict
 }
 
 struct Plan {
-    bool ok;
+    bool ok, ahead;
     int tiles, chan, rows_max, pitch;
     size_t lds;
 };
@@ -306,7 +345,19 @@ Plan make_plan(const Geom &g)
             const size_t lds = ((size_t)chan * rows * pl.pitch + (size_t)g.kh * g.kw * kFiltersPerWg) * 4;
             const int ahead = ((pl.pitch + 31) / 32) * (chan / 8) * rows;   // values per thread and chunk
             if (lds <= kLdsBudget && ahead <= kPre) {
-                pl.ok = true; pl.tiles = tiles; pl.chan = chan; pl.rows_max = rows; pl.lds = lds;
+                pl.ok = true; pl.ahead = true; pl.tiles = tiles; pl.chan = chan; pl.rows_max = rows; pl.lds = lds;
+                return pl;
+            }
+        }
+    }
+    // wide rows: the same search without the register limit (the kernel then stages synchronously)
+    for (int tiles = most; tiles >= 1; --tiles) {
+        const int orows = (int)std::min<long long>(g.OH, (32LL * tiles + g.OW - 2) / g.OW + 1);
+        const int rows = (orows - 1) * g.sh + g.kh;
+        for (int chan = g.C > 16 ? 32 : g.C > 8 ? 16 : 8; chan >= 8; chan /= 2) {
+            const size_t lds = ((size_t)chan * rows * pl.pitch + (size_t)g.kh * g.kw * kFiltersPerWg) * 4;
+            if (lds <= kLdsWide) {
+                pl.ok = true; pl.ahead = false; pl.tiles = tiles; pl.chan = chan; pl.rows_max = rows; pl.lds = lds;
                 return pl;
             }
         }
@@ -333,7 +384,24 @@ hipError_t launch_bwn_mfma(const float *I, const uint32_t *Wpk, const float *alp
     p.fgroups = ceil_div(g.F, kFiltersPerWg);
     const long long blocks = (long long)g.N * p.groups * p.fgroups;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    bwn_mfma_kernel<<<dim3((unsigned)blocks), dim3(kThreads), pl.lds, st>>>(p);
+    if (pl.ahead) {
+        bwn_mfma_kernel<true><<<dim3((unsigned)blocks), dim3(kThreads), pl.lds, st>>>(p);
+    } else {
+        if (pl.lds > 64 * 1024) {
+            // raise the kernel's dynamic-LDS limit once per device
+            static std::atomic<unsigned long long> raised{0};
+            int dev = 0;
+            if (hipGetDevice(&dev) != hipSuccess) return hipGetLastError();
+            const unsigned long long bit = 1ull << (dev & 63);
+            if (!(raised.load() & bit)) {
+                const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&bwn_mfma_kernel<false>),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsWide);
+                if (e != hipSuccess) return e;
+                raised.fetch_or(bit);
+            }
+        }
+        bwn_mfma_kernel<false><<<dim3((unsigned)blocks), dim3(kThreads), pl.lds, st>>>(p);
+    }
     return hipGetLastError();
 }
 

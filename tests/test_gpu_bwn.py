@@ -79,6 +79,7 @@ SHAPES = [
     (5, 256, 14, 14, 130, 3, 3, 2, 2, 1, 1),
     (1, 8, 64, 64, 16, 3, 3, 1, 1, 1, 1),
     (1, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3),      # a ResNet-style first layer
+    (1, 24, 6, 500, 5, 3, 3, 1, 1, 1, 1),        # rows too wide to be fetched a chunk ahead
 ]
 
 
