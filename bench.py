@@ -117,14 +117,20 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
         names = (["pack_I", "scale_K", "alpha", "pack_W"] if args.unfused else ["input_prepare", "filter_prepare"]) + \
                 (["filter_expand", "conv"] if two_phase else ["conv"])
 
-    def step(events=None):
+    n_marks = len(names) + 1
+
+    def step(events=None, conv_only=False):
         marks = []
 
         def mark():
-            if events is not None:
-                e = torch.cuda.Event(enable_timing=True)
-                e.record()                      # recorded on the stream the kernels are launched on
-                marks.append(e)
+            if events is None:
+                return
+            if conv_only and len(marks) < n_marks - 2:
+                marks.append(None)              # only the two events that bracket the convolution (the last stage)
+                return
+            e = torch.cuda.Event(enable_timing=True)
+            e.record()                          # recorded on the stream the kernels are launched on
+            marks.append(e)
 
         if args.chain:
             mark(); xb.xnor_box_filter_K(A, s, K)
@@ -162,12 +168,20 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    # Timed region: K steps, with one pair of events per step around the convolution launch (the
+    # roofline figure).  The other stages' times come from a second, untimed pass with an event
+    # after every call: five event records per step cost the host about as much as the launches.
     events: list = []
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step(events)
+        step(events, conv_only=True)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    conv_events = [(m[-2], m[-1]) for m in events]
+    events = []
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
 
     # The small layers finish faster than the host can issue five launches: with --sweep the step is
     # also captured into a HIP graph (the library allocates nothing and records no memset), each
@@ -199,6 +213,7 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
 
     ms_per_step = elapsed / args.steps * 1e3
     stage_ms = {n: sum(m[i].elapsed_time(m[i + 1]) for m in events) / len(events) for i, n in enumerate(names)}
+    stage_ms["conv"] = sum(a.elapsed_time(b) for a, b in conv_events) / len(conv_events)
     conv_ms = stage_ms["conv"]
     macs = layer.binary_macs
     value = macs / (ms_per_step * 1e-3) / 1e9
