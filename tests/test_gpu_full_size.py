@@ -118,3 +118,43 @@ def test_full_size_bwn_layer(name):
         ref = xb.xnor_bwn_conv2d_fwd(dI, Wpk, alpha, s, algo=xb.ALGO_DIRECT)
         torch.cuda.synchronize()
         assert bool(((out - ref).to(torch.float64).abs() <= 2e-6 * bound).all())
+
+
+def test_output_larger_than_2_to_31_elements():
+    """Offsets into the output must be 64-bit: 1800 filter planes of 1100x1100 pixels are 2.18e9
+    elements (8.7 GB).  A 1x1 kernel keeps the arithmetic small; planes below and above element
+    2^31 are compared with the oracle run on those filters alone."""
+    from paper_2007_14178_amd import binding as xb
+    N, C, H, W, F = 1, 32, 1100, 1100, 1800
+    assert N * F * H * W > 2 ** 31
+    print(f"case large output F={F} {H}x{W}", flush=True)
+    rng = np.random.default_rng(99)
+    I = rng.standard_normal((N, C, H, W), dtype=np.float32)
+    Wt = rng.standard_normal((F, C, 1, 1), dtype=np.float32)
+    s = xb.Shape(N, C, H, W, F, 1, 1, 1, 1, 0, 0)
+    dI, dW = torch.from_numpy(I).cuda(), torch.from_numpy(Wt).cuda()
+    Ipk, K, _ = xb.xnor_input_prepare(dI, s)
+    Wpk, alpha, _ = xb.xnor_filter_prepare(dW)
+    out, _ = xb.xnor_conv2d_fwd(Ipk, Wpk, K, alpha, s, workspace=None)
+    torch.cuda.synchronize()
+    fsel = [0, 1774, 1775, 1799]                      # element 2^31 lies in plane 1774
+    sub = oracle.Shape(N, C, H, W, len(fsel), 1, 1, 1, 1, 0, 0)
+    _, _, _, O_ref = oracle.forward(I, Wt[fsel], sub)
+    got = out[:, fsel].cpu().numpy()
+    assert rel_ok(got, O_ref)
+    # every plane was written: an output of this input is 0 only where dot is 0 (C even: possible) or
+    # K is 0 (never here), so a plane left unwritten (filled with a sentinel before) would show
+    out.fill_(float("nan"))
+    xb.xnor_conv2d_fwd(Ipk, Wpk, K, alpha, s, out=out, workspace=None)
+    torch.cuda.synchronize()
+    assert not bool(torch.isnan(out).any())
+    # the Binary-Weight-Network kernels on the same shape
+    for algo in (xb.ALGO_AUTO, xb.ALGO_DIRECT):
+        out.fill_(float("nan"))
+        xb.xnor_bwn_conv2d_fwd(dI, Wpk, alpha, s, out=out, algo=algo)
+        torch.cuda.synchronize()
+        O_bwn, S = oracle.bwn(I, Wt[fsel], sub, want_scale=True)
+        a = oracle.alpha(Wt[fsel]).astype(np.float64)
+        err = np.abs(out[:, fsel].cpu().numpy().astype(np.float64) - O_bwn)
+        assert (err <= RTOL * a[None, :, None, None] * S[:, None]).all()
+        assert not bool(torch.isnan(out).any())
