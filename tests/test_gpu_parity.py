@@ -275,3 +275,50 @@ def test_input_prepare_on_large_images(xb, shape):
     assert np.array_equal(words(Ipk), oracle.pack(I)), "Ipk"
     assert_rel(A.cpu().numpy(), oracle.channel_mean_abs(I), "A")
     assert_rel(K.cpu().numpy(), oracle.scale_K(I, oracle.Shape(N, C, H, W, 1, 3, 3, 1, 1, 1, 1)), "K")
+
+
+@pytest.mark.parametrize("offset_words", [1, 2, 3])
+def test_buffers_that_are_only_4_or_8_byte_aligned(xb, offset_words):
+    """Every buffer placed 4, 8 or 12 bytes past a 16-byte boundary: the kernels that use 16-byte
+    accesses on aligned operands must take their narrower paths and give the same results."""
+    shape = (2, 128, 28, 28, 64, 3, 3, 1, 1, 1, 1)
+    print(f"case misaligned offset={offset_words} words shape={shape}", flush=True)
+    rng = np.random.default_rng(offset_words)
+    layer, I, Wt = random_layer(rng, "t", *shape)
+    s = xb.Shape(*shape)
+    OH, OW = xb.xnor_out_dim(s)
+
+    def shifted(n, dtype):
+        buf = torch.empty((n + 4,), dtype=dtype, device="cuda")
+        v = buf[offset_words:offset_words + n]
+        assert v.data_ptr() % 16 == 4 * offset_words
+        return v
+
+    dI = shifted(I.size, torch.float32); dI.copy_(torch.from_numpy(I).reshape(-1).cuda()); dI = dI.view(I.shape)
+    dW = shifted(Wt.size, torch.float32); dW.copy_(torch.from_numpy(Wt).reshape(-1).cuda()); dW = dW.view(Wt.shape)
+    Ipk = shifted(s.N * s.H * s.W * s.Cw, torch.int32).view(s.N, s.H, s.W, s.Cw)
+    Wpk = shifted(s.F * 9 * s.Cw, torch.int32).view(s.F, 3, 3, s.Cw)
+    A = shifted(s.N * s.H * s.W, torch.float32).view(s.N, s.H, s.W)
+    K = shifted(s.N * OH * OW, torch.float32).view(s.N, OH, OW)
+    alpha = shifted(s.F, torch.float32)
+    M = shifted(s.F * 9, torch.float32).view(s.F, 3, 3)
+    out = shifted(s.N * s.F * OH * OW, torch.float32).view(s.N, s.F, OH, OW)
+    dot = shifted(s.N * s.F * OH * OW, torch.int32).view(s.N, s.F, OH, OW)
+    xb.xnor_input_prepare(dI, s, Ipk, A, K)
+    xb.xnor_filter_prepare(dW, Wpk, M, alpha)
+    d_ref, K_ref, a_ref, O_ref = oracle.forward(I, Wt, oshape(layer))
+    assert np.array_equal(words(Ipk), oracle.pack(I)) and np.array_equal(words(Wpk), oracle.pack(Wt))
+    assert_rel(K.cpu().numpy(), K_ref, "K")
+    assert_rel(alpha.cpu().numpy(), a_ref, "alpha")
+    for algo in ("direct", "tiled", "mfma"):
+        out.zero_(); dot.zero_()
+        xb.xnor_conv2d_fwd(Ipk, Wpk, K, alpha, s, out=out, dot=dot, algo=algo_id(xb, algo))
+        torch.cuda.synchronize()
+        assert np.array_equal(dot.cpu().numpy(), d_ref), f"dot ({algo})"
+        assert_rel(out.cpu().numpy(), O_ref, f"out ({algo})")
+    # the Binary-Weight-Network layer on the same shifted buffers
+    O_bwn, S = oracle.bwn(I, Wt, oshape(layer), want_scale=True)
+    xb.xnor_bwn_conv2d_fwd(dI, Wpk, alpha, s, out=out)
+    torch.cuda.synchronize()
+    err = np.abs(out.cpu().numpy().astype(np.float64) - O_bwn)
+    assert (err <= RTOL * a_ref.astype(np.float64)[None, :, None, None] * S[:, None]).all()
