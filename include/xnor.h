@@ -209,7 +209,7 @@ int xnor_box_filter_K(const float *A, const xnor_shape *s, float *K, void *strea
  *   alpha  in   fp32 [F]
  *   out    out  fp32 [N][F][OH][OW]
  *   dot    out  int32 [N][F][OH][OW] or NULL
- * Takes 1 <= C <= 4, kh = kw in {3, 5, 7}, stride 1, any padding; XNOR_E_UNSUPPORTED otherwise
+ * Takes 1 <= C <= 4, kh = kw in {3, 5, 7}, any stride and padding; XNOR_E_UNSUPPORTED otherwise
  * (xnor_forward_image_supported: 1 if the shape is taken, 0 if not, negative status for a bad shape).
  * K is formed in fp32 from fp32 partial sums (row sums, then their sum): within kw*C + kh roundings
  * of the exact value.

@@ -6,7 +6,8 @@
 // through HBM, not arithmetic.  So nothing intermediate is written: steps 1a-1d, 2a-2b and 3 of
 // Sec. III-A (Eq. 10, Eq. 11) run on registers between one read of the fp32 image and one write of
 // the fp32 output.
-//   * A lane owns one output column of a band of rows and slides down it.  For every input row it
+//   * A lane owns one output column of a band of rows and slides down it (with a vertical stride an
+//     output is due every sh-th input row).  For every input row it
 //     loads the kw*C values under its window, forms their kw*C sign bits (bit = x >= 0) and the sum
 //     of their magnitudes, and keeps the last kh of both: the spatially packed window of Sec. III-B
 //     (kh*kw*C bits, rows side by side in as few 32-bit words as hold them) and the kh row sums
@@ -37,7 +38,7 @@ struct ImageParams {
     const float *alpha;
     float *out;
     int32_t *dot;
-    int N, H, W, F, OH, OW, ph, pw;
+    int N, H, W, F, OH, OW, ph, pw, sh, sw;
     int rows_per_band, bands, xtiles;
     int group, fgroups;  // filters per wave, ceil(F / group)
     long long waves;     // N * fgroups * bands * xtiles
@@ -53,9 +54,10 @@ struct Cfg {
     static constexpr uint32_t kChanMask = (1u << C) - 1u;
 };
 
-template <int K, int C, bool ONE_FILTER>
+template <int K, int C, bool ONE_FILTER, bool UNIT_STRIDE>
 __global__ __launch_bounds__(kThreads) void conv_image_kernel(ImageParams p)
 {
+    const int sh = UNIT_STRIDE ? 1 : p.sh, sw = UNIT_STRIDE ? 1 : p.sw;   // stride 1 is compiled in
     using G = Cfg<K, C>;
     constexpr int RB = G::kRowBits, NW = G::kWords, RPW = G::kRowsPerWord, D = G::kAhead;
     extern __shared__ uint32_t lds[];        // filter windows [F][NW], then alpha [F]
@@ -103,7 +105,7 @@ __global__ __launch_bounds__(kThreads) void conv_image_kernel(ImageParams p)
     uint32_t row_mask = 0;
 #pragma unroll
     for (int kx = 0; kx < K; ++kx) {
-        const int xin = x - p.pw + kx;
+        const int xin = x * sw - p.pw + kx;
         cv[kx] = xin >= 0 && xin < p.W;
         row_mask |= cv[kx] ? (G::kChanMask << (kx * C)) : 0u;
     }
@@ -118,10 +120,10 @@ __global__ __launch_bounds__(kThreads) void conv_image_kernel(ImageParams p)
 
     const int y0 = band * p.rows_per_band;
     const int y1 = min(p.OH, y0 + p.rows_per_band);
-    const int nin = (y1 - y0) + K - 1;      // input rows this band walks through
-    const int yb = y0 - p.ph;               // the first of them (negative: above the image)
+    const int nin = (y1 - y0 - 1) * sh + K;   // input rows this band walks through
+    const int yb = y0 * sh - p.ph;            // the first of them (negative: above the image)
     const size_t HW = (size_t)p.H * p.W;
-    const float *src = p.I + (size_t)n * C * HW + (x - p.pw);   // only dereferenced where valid
+    const float *src = p.I + (size_t)n * C * HW + (x * sw - p.pw);   // only dereferenced where valid
     const size_t OHW = (size_t)p.OH * p.OW;
 
     float pre[D][RB];
@@ -153,6 +155,7 @@ __global__ __launch_bounds__(kThreads) void conv_image_kernel(ImageParams p)
         a0 = p.alpha[0];
     }
 
+    int skip = 1;                           // input rows until the next output row is due
     for (int i0 = 0; i0 < nin; i0 += D) {
 #pragma unroll
         for (int d = 0; d < D; ++d) {
@@ -173,16 +176,19 @@ __global__ __launch_bounds__(kThreads) void conv_image_kernel(ImageParams p)
             for (int r = 0; r + 1 < K; ++r) { rw[r] = rw[r + 1]; hs[r] = hs[r + 1]; }
             rw[K - 1] = bits;
             hs[K - 1] = hsum;
+            // an output row is complete when its last window row has arrived: every sh-th row
             if (i < K - 1) continue;
+            if (--skip > 0) continue;
+            skip = sh;
 
-            const int y = y0 + i - (K - 1);
+            const int y = y0 + (i - (K - 1)) / sh;
             uint32_t win[NW], m[NW];
 #pragma unroll
             for (int w = 0; w < NW; ++w) win[w] = 0;
 #pragma unroll
             for (int r = 0; r < K; ++r) win[r / RPW] |= rw[r] << ((r % RPW) * RB);
             int nvalid;
-            const int ytop = y - p.ph;
+            const int ytop = y * sh - p.ph;
             if (ytop >= 0 && ytop + K - 1 < p.H) {
 #pragma unroll
                 for (int w = 0; w < NW; ++w) m[w] = full_mask[w];
@@ -229,10 +235,15 @@ __global__ __launch_bounds__(kThreads) void conv_image_kernel(ImageParams p)
 template <int K, int C>
 hipError_t launch_kc(const ImageParams &p, dim3 grid, size_t lds, hipStream_t st)
 {
-    if (p.F == 1)
-        conv_image_kernel<K, C, true><<<grid, dim3(kThreads), lds, st>>>(p);
+    const bool unit = p.sh == 1 && p.sw == 1;
+    if (p.F == 1 && unit)
+        conv_image_kernel<K, C, true, true><<<grid, dim3(kThreads), lds, st>>>(p);
+    else if (p.F == 1)
+        conv_image_kernel<K, C, true, false><<<grid, dim3(kThreads), lds, st>>>(p);
+    else if (unit)
+        conv_image_kernel<K, C, false, true><<<grid, dim3(kThreads), lds, st>>>(p);
     else
-        conv_image_kernel<K, C, false><<<grid, dim3(kThreads), lds, st>>>(p);
+        conv_image_kernel<K, C, false, false><<<grid, dim3(kThreads), lds, st>>>(p);
     return hipGetLastError();
 }
 
@@ -255,7 +266,6 @@ bool conv_image_supports(const Geom &g)
 {
     if (g.C < 1 || g.C > 4) return false;
     if (g.kh != g.kw || (g.kh != 3 && g.kh != 5 && g.kh != 7)) return false;
-    if (g.sh != 1 || g.sw != 1) return false;
     if ((size_t)g.F * (window_words(g.kh, g.C) + 1) * 4 > kLdsBudget) return false;
     return true;
 }
@@ -265,7 +275,7 @@ hipError_t launch_conv_image(const float *I, const uint32_t *Wpk, const float *a
 {
     ImageParams p;
     p.I = I; p.Wpk = Wpk; p.alpha = alpha; p.out = out; p.dot = dot;
-    p.N = g.N; p.H = g.H; p.W = g.W; p.F = g.F; p.OH = g.OH; p.OW = g.OW; p.ph = g.ph; p.pw = g.pw;
+    p.N = g.N; p.H = g.H; p.W = g.W; p.F = g.F; p.OH = g.OH; p.OW = g.OW; p.ph = g.ph; p.pw = g.pw; p.sh = g.sh; p.sw = g.sw;
     p.xtiles = ceil_div(g.OW, 64);
     // Band height: tall bands re-read fewer halo rows, short ones give more waves.  Halve from 64
     // until the chip has about eight waves per SIMD; an image too small for that even with bands

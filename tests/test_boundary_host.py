@@ -122,7 +122,8 @@ def test_null_and_alignment_rejected(xb):
     ip = ctypes.byref(img.c())
     assert xb.xnor_forward_image_supported(img)
     assert xb.xnor_forward_image_supported(xb.Shape(2, 4, 30, 30, 9, 7, 7, 1, 1, 0, 0))
-    assert not xb.xnor_forward_image_supported(xb.Shape(1, 1, 256, 256, 1, 3, 3, 2, 2, 1, 1))
+    assert xb.xnor_forward_image_supported(xb.Shape(1, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3))
+    assert not xb.xnor_forward_image_supported(xb.Shape(1, 1, 256, 256, 1, 3, 5, 1, 1, 1, 2))
     assert L.xnor_forward_image(None, ok, ok, ip, ok, None, None) == xb.E_NULL
     assert L.xnor_forward_image(ok, ok, ok, ip, None, None, None) == xb.E_NULL
     assert L.xnor_forward_image(ok, ok, ok, ip, odd, None, None) == xb.E_ALIGN

@@ -3,7 +3,7 @@
 The expected values are the oracle's forward pass on the same fp32 tensors: binary dot products bit
 for bit, the fp32 output within 1e-5 relative (one fp32 subnormal spacing where that is larger) and
 zero exactly where the oracle is zero.  The shapes cover every template of the kernel (kernel size
-3 / 5 / 7, one to four channels, one and several filters), images narrower than a wave and wider
+3 / 5 / 7, one to four channels, one and several filters, strides), images narrower than a wave and wider
 than several, heights below one band and across bands, padding from none to more than the kernel,
 and the paper's own sizes (Tables I-III: one channel, one 3x3 filter, 256^2 ... 2048^2).
 """
@@ -40,8 +40,9 @@ def assert_out(got, ref, what):
 
 
 def run_case(xb, shape, tag=""):
-    N, C, H, W, F, k, pad = shape
-    full = (N, C, H, W, F, k, k, 1, 1, pad, pad)
+    N, C, H, W, F, k, pad = shape[:7]
+    sh, sw = shape[7:] if len(shape) > 7 else (1, 1)
+    full = (N, C, H, W, F, k, k, sh, sw, pad, pad)
     rng = np.random.default_rng(zlib.crc32(("image" + tag + str(shape)).encode()))
     layer, I, Wt = random_layer(rng, "t", *full)
     s = xb.Shape(*full)
@@ -83,6 +84,12 @@ SHAPES = [
     (1, 1, 300, 300, 1, 3, 1),
     (1, 3, 224, 224, 16, 3, 1),     # an ImageNet-sized three-channel input
     (1, 1, 64, 64, 600, 3, 1),      # many filters
+    # strides (sh, sw)
+    (1, 3, 224, 224, 8, 7, 3, 2, 2),    # a ResNet-style first layer
+    (2, 1, 50, 131, 2, 3, 1, 2, 1),
+    (1, 2, 41, 70, 3, 5, 0, 1, 3),
+    (1, 4, 33, 65, 2, 3, 1, 3, 2),
+    (1, 1, 9, 9, 1, 7, 3, 4, 4),
 ]
 
 
@@ -124,7 +131,6 @@ def test_two_calls_in_a_row_do_not_interfere(xb):
     (1, 5, 16, 16, 1, 3, 3, 1, 1, 1, 1),      # too many channels
     (1, 1, 16, 16, 1, 3, 5, 1, 1, 1, 2),      # not square
     (1, 1, 16, 16, 1, 4, 4, 1, 1, 1, 1),      # even kernel
-    (1, 1, 16, 16, 1, 3, 3, 2, 2, 1, 1),      # stride
     (1, 1, 16, 16, 1, 9, 9, 1, 1, 4, 4),      # kernel too large
 ])
 def test_shapes_the_kernel_does_not_take(xb, full):
