@@ -48,6 +48,7 @@ struct BwnParams {
     int chan;           // channels per chunk: 32, 16 or 8 (a chunk never straddles a packed word)
     int rows_max;       // staged input rows (upper bound over the pixel groups)
     int pitch;          // staged floats per row = W + 2*pw
+    uint32_t inv_plane, inv_pitch;   // ceil(2^32 / (rows_max * pitch)), ceil(2^32 / pitch): exact quotients below 2^16
 };
 
 // The work of one workgroup with NT pixel tiles.  NT is a template parameter so that the MFMA
@@ -91,37 +92,40 @@ __device__ __attribute__((always_inline)) void bwn_workgroup(const BwnParams &p,
     const float *img = p.I + (size_t)n * p.C * p.H * p.W;
 
     // Staging.  The chunk's input rows are fetched into registers one chunk ahead, while the
-    // previous chunk's MFMAs run, and written to LDS between two barriers.  Thread layout: 32
-    // lanes along a row, the 8 half-waves on 8 channels; the q-th value of a thread is column
-    // block m, channel group kc, row r in the order the counters below step through.
-    const int kcn = p.chan >> 3;
-    const int nq = ((p.pitch + 31) >> 5) * kcn * rows;        // <= kPre (the host's plan sees to it)
+    // previous chunk's MFMAs run, and written to LDS between two barriers.  The staged block is
+    // walked as one flat array [chan][rows_max][pitch]: thread t owns elements t, t + 256, ...;
+    // channel, row and column come from two multiply-high divisions (constants from the host);
+    // every load is issued unconditionally (from element 0 of the image where the slot lies outside
+    // it or past the band's rows) and zeroed by a select, so there is no divergent code.
+    const int nelem = p.chan * plane;                          // <= kPre * 256 (the host's plan sees to it)
     const bool words_ahead = AHEAD && taps * kFiltersPerWg <= kPreWords * kThreads;
     float nxt[kPre];
     uint32_t nxw[kPreWords];
-    // (xl and sub pass through an empty asm in each call: otherwise the per-value offsets, which do
-    // not change from chunk to chunk, are all kept in registers across the MFMA loop)
+    // (the thread index passes through an empty asm in each call: otherwise the per-element offsets,
+    // which do not change from chunk to chunk, are all kept in registers across the MFMA loop)
     auto prefetch = [&](int ch) __attribute__((always_inline)) {
         const int c0 = ch * p.chan;
-        int xl = threadIdx.x & 31, sub = threadIdx.x >> 5;
-        asm volatile("" : "+v"(xl), "+v"(sub));
-        int m = 0, kc = 0, r = 0;
+        int t0 = threadIdx.x;
+        asm volatile("" : "+v"(t0));
 #pragma unroll
         for (int q = 0; q < kPre; ++q) {
-            float v = 0.f;
-            if (q < nq) {
-                const int xw = 32 * m + xl, ix = xw - p.pw, cg = c0 + sub + 8 * kc, iy = iy0 + r;
-                if (xw < p.pitch && ix >= 0 && ix < p.W && cg < p.C && iy >= 0 && iy < p.H)
-                    v = img[(unsigned)((cg * p.H + iy) * p.W + ix)];   // one image: below 2^30 floats
-            }
-            nxt[q] = v;
-            if (++r == rows) { r = 0; if (++kc == kcn) { kc = 0; ++m; } }
+            if (q * kThreads >= nelem) break;                  // uniform
+            const uint32_t e = (uint32_t)(q * kThreads + t0);
+            const uint32_t c = __umulhi(e, p.inv_plane);
+            const uint32_t rem = e - c * (uint32_t)plane;
+            const uint32_t r = __umulhi(rem, p.inv_pitch);
+            const int xw = (int)(rem - r * (uint32_t)p.pitch);
+            const int iy = iy0 + (int)r, ix = xw - p.pw, cg = c0 + (int)c;
+            const bool ok = (int)c < p.chan && (int)r < rows && (unsigned)iy < (unsigned)p.H &&
+                            (unsigned)ix < (unsigned)p.W && cg < p.C;
+            const float v = img[ok ? (unsigned)((cg * p.H + iy) * p.W + ix) : 0u];   // one image: below 2^30 floats
+            nxt[q] = ok ? v : 0.f;
         }
         if (words_ahead) {
             const int cw = ch / chunks_per_word, bit0 = (ch % chunks_per_word) * p.chan;
 #pragma unroll
             for (int q = 0; q < kPreWords; ++q) {
-                const int i = q * kThreads + threadIdx.x;
+                const int i = q * kThreads + t0;
                 const int t = i / kFiltersPerWg, f = fbase + (i - t * kFiltersPerWg);
                 nxw[q] = (i < taps * kFiltersPerWg && f < p.F)
                              ? p.Wpk[((size_t)f * taps + t) * p.Cw + cw] >> bit0 : 0u;
@@ -129,14 +133,15 @@ __device__ __attribute__((always_inline)) void bwn_workgroup(const BwnParams &p,
         }
     };
     auto commit = [&](int ch) __attribute__((always_inline)) {
-        int xl = threadIdx.x & 31, sub = threadIdx.x >> 5;
-        asm volatile("" : "+v"(xl), "+v"(sub));
-        int m = 0, kc = 0, r = 0;
+        int t0 = threadIdx.x;
+        asm volatile("" : "+v"(t0));
+        if (AHEAD) {
 #pragma unroll
-        for (int q = 0; q < kPre; ++q) {
-            const int xw = 32 * m + xl;
-            if (AHEAD && q < nq && xw < p.pitch) tile[(sub + 8 * kc) * plane + r * p.pitch + xw] = nxt[q];
-            if (++r == rows) { r = 0; if (++kc == kcn) { kc = 0; ++m; } }
+            for (int q = 0; q < kPre; ++q) {
+                if (q * kThreads >= nelem) break;              // uniform
+                const int e = q * kThreads + t0;
+                if (e < nelem) tile[e] = nxt[q];
+            }
         }
         if (words_ahead) {
 #pragma unroll
@@ -343,8 +348,8 @@ Plan make_plan(const Geom &g)
         // no more channels per chunk than the layer has (rounded up to 8)
         for (int chan = g.C > 16 ? 32 : g.C > 8 ? 16 : 8; chan >= 8; chan /= 2) {
             const size_t lds = ((size_t)chan * rows * pl.pitch + (size_t)g.kh * g.kw * kFiltersPerWg) * 4;
-            const int ahead = ((pl.pitch + 31) / 32) * (chan / 8) * rows;   // values per thread and chunk
-            if (lds <= kLdsBudget && ahead <= kPre) {
+            const long long elems = (long long)chan * rows * pl.pitch;      // staged values per chunk
+            if (lds <= kLdsBudget && elems <= (long long)kPre * kThreads && elems < (1 << 16)) {
                 pl.ok = true; pl.ahead = true; pl.tiles = tiles; pl.chan = chan; pl.rows_max = rows; pl.lds = lds;
                 return pl;
             }
@@ -380,6 +385,9 @@ hipError_t launch_bwn_mfma(const float *I, const uint32_t *Wpk, const float *alp
     p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw; p.OH = g.OH; p.OW = g.OW; p.Cw = g.Cw;
     p.tiles = pl.tiles; p.chan = pl.chan; p.rows_max = pl.rows_max; p.pitch = pl.pitch;
     const long long OHW = (long long)g.OH * g.OW;
+    p.inv_plane = (uint32_t)(((1ULL << 32) + (unsigned long long)pl.rows_max * pl.pitch - 1) /
+                             ((unsigned long long)pl.rows_max * pl.pitch));
+    p.inv_pitch = (uint32_t)(((1ULL << 32) + pl.pitch - 1) / pl.pitch);
     p.groups = ceil_div(OHW, 32LL * pl.tiles);
     p.fgroups = ceil_div(g.F, kFiltersPerWg);
     const long long blocks = (long long)g.N * p.groups * p.fgroups;
