@@ -151,12 +151,17 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
             mark(); xb.xnor_alpha(dW, alpha)
             mark(); xb.xnor_binarize_pack(dW, Wpk)
         else:
-            mark(); xb.xnor_input_prepare(dI, s, Ipk, A, K)
+            # with the matrix-core kernel K is formed inside the convolution from A (same arithmetic
+            # as the box-filter kernel, bit-identical output): one launch less per step
+            mark(); xb.xnor_input_prepare(dI, s, Ipk, A, K, want_K=not two_phase)
             mark(); xb.xnor_filter_prepare(dW, Wpk, M, alpha)
         if two_phase:
             # per-model work ends with the filters in the matrix-core kernel's operand order
             mark(); xb.xnor_filter_expand(Wpk, s, ws)
-            mark(); xb.xnor_conv2d_fwd_expanded(Ipk, ws, K, alpha, s, out=out)
+            if args.unfused:
+                mark(); xb.xnor_conv2d_fwd_expanded(Ipk, ws, K, alpha, s, out=out)
+            else:
+                mark(); xb.xnor_conv2d_fwd_expanded_from_A(Ipk, ws, A, alpha, s, out=out)
         else:
             mark(); xb.xnor_conv2d_fwd(Ipk, Wpk, K, alpha, s, out=out, algo=algo, workspace=ws)
         mark()
@@ -236,7 +241,7 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
     # plain 1 GiB copy): measured offline, see profiles/forward_c5_hbm_traffic_pmc.md; other
     # workloads / kernels have no counter run yet
     roof["traffic"] = MEASURED_CONV_TRAFFIC_BYTES.get((layer.name, xb.ALGO_NAMES[used_algo]))
-    roof["kernel"] = "conv_mfma_kernel (xnor_conv2d_fwd_expanded)" if two_phase else f"xnor_conv2d_fwd[{xb.ALGO_NAMES[used_algo]}]"
+    roof["kernel"] = ("conv_mfma_kernel (xnor_conv2d_fwd_expanded" + ("" if args.unfused else "_from_A") + ")") if two_phase else f"xnor_conv2d_fwd[{xb.ALGO_NAMES[used_algo]}]"
     roof["kernel_ms"] = conv_ms                                # mean over the timed steps (what `achieved` uses)
     roof["kernel_ms_median"] = conv_times[len(conv_times) // 2]
     roof["kernel_ms_min"] = conv_times[0]

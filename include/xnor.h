@@ -107,7 +107,8 @@ int xnor_alpha(const float *Wt, int F, int C, int kh, int kw, float *alpha, void
  *   I       in   fp32 [N][C][H][W]
  *   Ipk     out  uint32 [N][H][W][ceil(C/32)]
  *   A_work  out  fp32 [N][H][W]   caller-owned workspace; holds A on return
- *   K       out  fp32 [N][OH][OW]
+ *   K       out  fp32 [N][OH][OW], or NULL: then only Ipk and A are produced (for
+ *                xnor_conv2d_fwd_expanded_from_A, which forms K itself)
  */
 int xnor_input_prepare(const float *I, const xnor_shape *s, uint32_t *Ipk, float *A_work, float *K,
                        void *stream);
@@ -169,6 +170,15 @@ int xnor_filter_expand(const uint32_t *Wpk, const xnor_shape *s, void *workspace
 int xnor_conv2d_fwd_expanded(const uint32_t *Ipk, const void *workspace, size_t workspace_bytes,
                              const float *K, const float *alpha, const xnor_shape *s, float *out,
                              int32_t *dot, void *stream);
+/*
+ * The same convolution taking the channel mean A [N][H][W] (Eq. 10, first half) instead of K: each
+ * workgroup forms the K of its own output pixels from A while its first operands are on their way
+ * (same sum, order and rounding as xnor_box_filter_K, so the outputs are bit-identical), which
+ * saves the box-filter launch between the input pass and the convolution.
+ */
+int xnor_conv2d_fwd_expanded_from_A(const uint32_t *Ipk, const void *workspace, size_t workspace_bytes,
+                                    const float *A, const float *alpha, const xnor_shape *s, float *out,
+                                    int32_t *dot, void *stream);
 
 /*
  * Chained layers (the paper's closing proposal, Sec. V: "passing the binary outputs to the next

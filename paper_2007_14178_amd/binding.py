@@ -87,6 +87,7 @@ def _load() -> ctypes.CDLL:
     L.xnor_conv2d_fwd_algo.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, ci, vp]
     L.xnor_filter_expand.argtypes = [vp, sp, vp, sz, vp]
     L.xnor_conv2d_fwd_expanded.argtypes = [vp, vp, sz, vp, vp, sp, vp, vp, vp]
+    L.xnor_conv2d_fwd_expanded_from_A.argtypes = [vp, vp, sz, vp, vp, sp, vp, vp, vp]
     L.xnor_box_filter_K.argtypes = [vp, sp, vp, vp]
     L.xnor_conv2d_chain_workspace_bytes.argtypes = [sp, ctypes.POINTER(sz)]
     L.xnor_conv2d_fwd_chain.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, vp]
@@ -102,7 +103,8 @@ def _load() -> ctypes.CDLL:
                  "xnor_filter_expand", "xnor_conv2d_fwd_expanded", "xnor_box_filter_K",
                  "xnor_conv2d_chain_workspace_bytes", "xnor_conv2d_fwd_chain",
                  "xnor_forward_image_supported", "xnor_forward_image",
-                 "xnor_bwn_conv2d_fwd", "xnor_bwn_conv2d_fwd_algo"):
+                 "xnor_bwn_conv2d_fwd", "xnor_bwn_conv2d_fwd_algo",
+                 "xnor_conv2d_fwd_expanded_from_A"):
         getattr(L, name).restype = ci
     return L
 
@@ -179,19 +181,20 @@ def xnor_alpha(Wt: torch.Tensor, alpha: torch.Tensor | None = None) -> torch.Ten
 
 
 def xnor_input_prepare(I: torch.Tensor, s: Shape, Ipk: torch.Tensor | None = None,
-                       A_work: torch.Tensor | None = None, K: torch.Tensor | None = None):
-    """One pass over I: returns (Ipk, K, A)."""
+                       A_work: torch.Tensor | None = None, K: torch.Tensor | None = None, want_K: bool = True):
+    """One pass over I: returns (Ipk, K, A); with want_K=False K is not computed (returned as None)."""
     OH, OW = xnor_out_dim(s)
     if Ipk is None:
         Ipk = torch.empty((s.N, s.H, s.W, s.Cw), dtype=torch.int32, device=I.device)
     if A_work is None:
         A_work = torch.empty((s.N, s.H, s.W), dtype=torch.float32, device=I.device)
-    if K is None:
+    if K is None and want_K:
         K = torch.empty((s.N, OH, OW), dtype=torch.float32, device=I.device)
     _ok(lib.xnor_input_prepare(_dev(I, torch.float32, (s.N, s.C, s.H, s.W), "I"), ctypes.byref(s.c()),
                                _dev(Ipk, torch.int32, (s.N, s.H, s.W, s.Cw), "Ipk"),
                                _dev(A_work, torch.float32, (s.N, s.H, s.W), "A_work"),
-                               _dev(K, torch.float32, (s.N, OH, OW), "K"), _stream()), "xnor_input_prepare")
+                               _dev(K, torch.float32, (s.N, OH, OW), "K") if want_K else None, _stream()),
+        "xnor_input_prepare")
     return Ipk, K, A_work
 
 
@@ -319,6 +322,24 @@ def xnor_bwn_conv2d_fwd(I: torch.Tensor, Wpk: torch.Tensor, alpha: torch.Tensor,
         _dev(alpha, torch.float32, (s.F,), "alpha"), ctypes.byref(s.c()), _dev(out, torch.float32, oshape, "out"),
         algo, _stream()), f"xnor_bwn_conv2d_fwd[{ALGO_NAMES.get(algo, algo)}]")
     return out
+
+
+def xnor_conv2d_fwd_expanded_from_A(Ipk: torch.Tensor, workspace: torch.Tensor, A: torch.Tensor, alpha: torch.Tensor,
+                                    s: Shape, out: torch.Tensor | None = None, dot: torch.Tensor | None = None,
+                                    want_dot: bool = False):
+    """xnor_conv2d_fwd_expanded with K formed inside the kernel from the channel mean A [N][H][W]."""
+    OH, OW = xnor_out_dim(s)
+    oshape = (s.N, s.F, OH, OW)
+    if out is None:
+        out = torch.empty(oshape, dtype=torch.float32, device=Ipk.device)
+    if dot is None and want_dot:
+        dot = torch.empty(oshape, dtype=torch.int32, device=Ipk.device)
+    _ok(lib.xnor_conv2d_fwd_expanded_from_A(
+        _dev(Ipk, torch.int32, (s.N, s.H, s.W, s.Cw), "Ipk"), _dev(workspace, torch.uint8, name="workspace"),
+        workspace.numel(), _dev(A, torch.float32, (s.N, s.H, s.W), "A"), _dev(alpha, torch.float32, (s.F,), "alpha"),
+        ctypes.byref(s.c()), _dev(out, torch.float32, oshape, "out"),
+        _dev(dot, torch.int32, oshape, "dot") if dot is not None else None, _stream()), "xnor_conv2d_fwd_expanded_from_A")
+    return out, dot
 
 
 def xnor_box_filter_K(A: torch.Tensor, s: Shape, K: torch.Tensor | None = None) -> torch.Tensor:

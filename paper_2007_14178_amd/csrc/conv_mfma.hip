@@ -53,6 +53,7 @@ struct MfmaParams {
     const uint32_t *Ipk;
     const uint4 *Wx;
     const float *K, *alpha;
+    const float *A;  // if not null: K is not given but formed here from A (second half of Eq. 10)
     float *out;
     int32_t *dot;
     uint32_t *Opk;   // chained form: packed signs of the output [N][OH][OW][Cwn] ...
@@ -325,7 +326,32 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
     // set up while those loads are in flight.
     stage_issue(0);
     float k_mine = 0.0f, a_mine = 0.0f;
-    if (tid < npix) k_mine = p.K[(long long)R0 * p.OW + tid];
+    if (tid < npix) {
+        if (p.A) {
+            // K of this band's pixel `tid` from the channel mean A: the same sum, order and rounding
+            // as the stand-alone box filter (double accumulation over the in-image taps, one divide)
+            const int Rl = tid / p.OW, ox = tid - Rl * p.OW;
+            const int R = R0 + Rl;
+            const int n = R / p.OH, oy = R - n * p.OH;
+            const float *a = p.A + (long long)n * p.H * p.W;
+            // no branches around the loads (out-of-image taps read a clamped address and add 0), so
+            // that the unrolled loop has all its loads in flight at once
+            double sum = 0.0;
+            const int iy0 = oy * p.sh - p.ph, ix0 = ox * p.sw - p.pw;
+            int ky = 0, kx = 0;
+#pragma unroll 9
+            for (int t = 0; t < p.kh * p.kw; ++t) {
+                const int iy = iy0 + ky, ix = ix0 + kx;
+                const bool in = (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
+                const float v = a[in ? iy * p.W + ix : 0];
+                sum += in ? (double)v : 0.0;
+                if (++kx == p.kw) { kx = 0; ++ky; }
+            }
+            k_mine = (float)(sum / (double)(p.kh * p.kw));
+        } else {
+            k_mine = p.K[(long long)R0 * p.OW + tid];
+        }
+    }
     if (tid < kFilterTile && ftile * kFilterTile + tid < p.F) a_mine = p.alpha[ftile * kFilterTile + tid];
     v4i A[kRing][kWM];
     uint32_t a_off = (uint32_t)lane * 16u;   // byte offset of this lane's operand of the next step to load
@@ -752,16 +778,16 @@ hipError_t launch_expand_filters(const uint32_t *Wpk, const Geom &g, void *works
     return hipGetLastError();
 }
 
-static hipError_t launch_mfma(const uint32_t *Ipk, const float *K, const float *alpha, const Geom &g,
-                              float *out, int32_t *dot, uint32_t *Opk, float *P, const void *workspace,
-                              hipStream_t st)
+static hipError_t launch_mfma(const uint32_t *Ipk, const float *K, const float *A, const float *alpha,
+                              const Geom &g, float *out, int32_t *dot, uint32_t *Opk, float *P,
+                              const void *workspace, hipStream_t st)
 {
     const MfmaPlan pl = make_plan(g, Ipk);
     if (!pl.ok) return hipErrorInvalidValue;
     const uint4 *Wx = static_cast<const uint4 *>(workspace);
 
     MfmaParams p{};
-    p.Ipk = Ipk; p.Wx = Wx; p.K = K; p.alpha = alpha; p.out = out; p.dot = dot;
+    p.Ipk = Ipk; p.Wx = Wx; p.K = K; p.A = A; p.alpha = alpha; p.out = out; p.dot = dot;
     p.Opk = Opk; p.P = P; p.Cwn = (g.F + 31) / 32; p.f_tiles = pl.f_tiles;
     p.N = g.N; p.C = g.C; p.H = g.H; p.W = g.W; p.F = g.F; p.kh = g.kh; p.kw = g.kw;
     p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw; p.OH = g.OH; p.OW = g.OW; p.Cw = g.Cw;
@@ -818,7 +844,14 @@ hipError_t launch_conv_mfma_expanded(const uint32_t *Ipk, const float *K, const 
                                      const Geom &g, float *out, int32_t *dot, const void *workspace,
                                      hipStream_t st)
 {
-    return launch_mfma(Ipk, K, alpha, g, out, dot, nullptr, nullptr, workspace, st);
+    return launch_mfma(Ipk, K, nullptr, alpha, g, out, dot, nullptr, nullptr, workspace, st);
+}
+
+hipError_t launch_conv_mfma_expanded_from_A(const uint32_t *Ipk, const float *A, const float *alpha,
+                                            const Geom &g, float *out, int32_t *dot,
+                                            const void *workspace, hipStream_t st)
+{
+    return launch_mfma(Ipk, nullptr, A, alpha, g, out, dot, nullptr, nullptr, workspace, st);
 }
 
 // Eq. 10's channel mean for the next layer from the per-filter-tile sums: A[pix] = sum_t P[pix][t] / F
@@ -848,7 +881,7 @@ hipError_t launch_conv_mfma_chain(const uint32_t *Ipk, const uint32_t *Wpk, cons
     float *P = reinterpret_cast<float *>(static_cast<char *>(workspace) + pl.ws_bytes);
     hipError_t e = launch_expand_filters(Wpk, g, workspace, st);
     if (e != hipSuccess) return e;
-    e = launch_mfma(Ipk, K, alpha, g, nullptr, nullptr, Opk, P, workspace, st);
+    e = launch_mfma(Ipk, K, nullptr, alpha, g, nullptr, nullptr, Opk, P, workspace, st);
     if (e != hipSuccess) return e;
     const long long npix = (long long)g.N * g.OH * g.OW;
     chain_mean_kernel<<<ceil_div(npix, 256), 256, 0, st>>>(P, npix, pl.f_tiles, g.F, A_next);

@@ -104,7 +104,7 @@ int xnor_scale_K(const float *I, const xnor_shape *s, float *A_work, float *K, v
     if (!aligned(I, 4) || !aligned(A_work, 4) || !aligned(K, 4)) return XNOR_E_ALIGN;
     hipStream_t st = (hipStream_t)stream;
     hipError_t e = xnor::launch_channel_mean_abs(I, g.N, g.C, g.H, g.W, A_work, st);
-    if (e != hipSuccess) return hip_status(e);
+    if (e != hipSuccess || !K) return hip_status(e);
     return hip_status(xnor::launch_box_filter_K(A_work, g, K, st));
 }
 
@@ -121,11 +121,11 @@ int xnor_alpha(const float *Wt, int F, int C, int kh, int kw, float *alpha, void
 int xnor_input_prepare(const float *I, const xnor_shape *s, uint32_t *Ipk, float *A_work, float *K,
                        void *stream)
 {
-    if (!I || !s || !Ipk || !A_work || !K) return XNOR_E_NULL;
+    if (!I || !s || !Ipk || !A_work) return XNOR_E_NULL;   // K may be NULL: then only Ipk and A are produced
     xnor::Geom g;
     const int rc = make_geom(s, &g);
     if (rc) return rc;
-    if (!aligned(I, 4) || !aligned(Ipk, 4) || !aligned(A_work, 4) || !aligned(K, 4)) return XNOR_E_ALIGN;
+    if (!aligned(I, 4) || !aligned(Ipk, 4) || !aligned(A_work, 4) || (K && !aligned(K, 4))) return XNOR_E_ALIGN;
     hipStream_t st = (hipStream_t)stream;
     hipError_t e;
     if (xnor::pack_and_mean_supports(g.C)) {
@@ -134,7 +134,7 @@ int xnor_input_prepare(const float *I, const xnor_shape *s, uint32_t *Ipk, float
         e = xnor::launch_binarize_pack(I, g.N, g.C, g.H, g.W, Ipk, st);
         if (e == hipSuccess) e = xnor::launch_channel_mean_abs(I, g.N, g.C, g.H, g.W, A_work, st);
     }
-    if (e != hipSuccess) return hip_status(e);
+    if (e != hipSuccess || !K) return hip_status(e);
     return hip_status(xnor::launch_box_filter_K(A_work, g, K, st));
 }
 
@@ -326,6 +326,24 @@ int xnor_conv2d_fwd_expanded(const uint32_t *Ipk, const void *workspace, size_t 
     if (need == 0) return XNOR_E_UNSUPPORTED;
     if (workspace_bytes < need) return XNOR_E_WORKSPACE;
     return hip_status(xnor::launch_conv_mfma_expanded(Ipk, K, alpha, g, out, dot, workspace, (hipStream_t)stream));
+}
+
+int xnor_conv2d_fwd_expanded_from_A(const uint32_t *Ipk, const void *workspace, size_t workspace_bytes,
+                                    const float *A, const float *alpha, const xnor_shape *s, float *out,
+                                    int32_t *dot, void *stream)
+{
+    if (!Ipk || !workspace || !A || !alpha || !s || !out) return XNOR_E_NULL;
+    xnor::Geom g;
+    const int rc = make_geom(s, &g);
+    if (rc) return rc;
+    if (!aligned(Ipk, 4) || !aligned(A, 4) || !aligned(alpha, 4) || !aligned(out, 4) ||
+        (dot && !aligned(dot, 4)) || !aligned(workspace, 16))
+        return XNOR_E_ALIGN;
+    const size_t need = xnor::conv_mfma_workspace_bytes(g);
+    if (need == 0) return XNOR_E_UNSUPPORTED;
+    if (workspace_bytes < need) return XNOR_E_WORKSPACE;
+    return hip_status(xnor::launch_conv_mfma_expanded_from_A(Ipk, A, alpha, g, out, dot, workspace,
+                                                             (hipStream_t)stream));
 }
 
 int xnor_conv2d_fwd(const uint32_t *Ipk, const uint32_t *Wpk, const float *K, const float *alpha,

@@ -322,3 +322,28 @@ def test_buffers_that_are_only_4_or_8_byte_aligned(xb, offset_words):
     torch.cuda.synchronize()
     err = np.abs(out.cpu().numpy().astype(np.float64) - O_bwn)
     assert (err <= RTOL * a_ref.astype(np.float64)[None, :, None, None] * S[:, None]).all()
+
+
+@pytest.mark.parametrize("shape", [(2, 64, 28, 28, 96, 3, 3, 1, 1, 1, 1), (3, 40, 13, 13, 130, 5, 5, 1, 1, 2, 2),
+                                   (2, 32, 20, 31, 33, 3, 3, 2, 2, 1, 1), (1, 128, 9, 9, 64, 3, 3, 1, 1, 3, 3)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_conv_that_forms_K_itself(xb, shape):
+    """xnor_input_prepare without K + xnor_conv2d_fwd_expanded_from_A: the workgroups form K from A
+    with the box filter's own arithmetic, so dots and outputs equal the staged path bit for bit."""
+    print(f"case K-from-A shape={shape}", flush=True)
+    rng = np.random.default_rng(zlib.crc32(("fromA" + str(shape)).encode()))
+    layer, I, Wt = random_layer(rng, "t", *shape)
+    s = xb.Shape(*shape)
+    dI = dev(I)
+    Ipk, none, A = xb.xnor_input_prepare(dI, s, want_K=False)
+    assert none is None
+    Wpk, alpha, _ = xb.xnor_filter_prepare(dev(Wt))
+    ws = xb.xnor_filter_expand(Wpk, s)
+    out, dot = xb.xnor_conv2d_fwd_expanded_from_A(Ipk, ws, A, alpha, s, want_dot=True)
+    _, K, _ = xb.xnor_input_prepare(dI, s)
+    out2, dot2 = xb.xnor_conv2d_fwd_expanded(Ipk, ws, K, alpha, s, want_dot=True)
+    torch.cuda.synchronize()
+    assert torch.equal(dot, dot2) and torch.equal(out, out2)
+    d_ref, K_ref, a_ref, O_ref = oracle.forward(I, Wt, oshape(layer))
+    assert np.array_equal(dot.cpu().numpy(), d_ref)
+    assert_rel(out.cpu().numpy(), O_ref, "out")
