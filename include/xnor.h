@@ -199,6 +199,12 @@ int xnor_conv2d_chain_workspace_bytes(const xnor_shape *s, size_t *bytes);
 int xnor_conv2d_fwd_chain(const uint32_t *Ipk, const uint32_t *Wpk, const float *K, const float *alpha,
                           const xnor_shape *s, uint32_t *Opk, float *A_next, void *workspace,
                           size_t workspace_bytes, void *stream);
+/* The same, taking this layer's channel mean A [N][H][W] (what the previous chained layer left as
+ * its A_next) instead of K: K is formed inside the kernel as in xnor_conv2d_fwd_expanded_from_A, so
+ * a chain of layers needs no xnor_box_filter_K calls in between.  Bit-identical results. */
+int xnor_conv2d_fwd_chain_from_A(const uint32_t *Ipk, const uint32_t *Wpk, const float *A, const float *alpha,
+                                 const xnor_shape *s, uint32_t *Opk, float *A_next, void *workspace,
+                                 size_t workspace_bytes, void *stream);
 
 /*
  * Second half of Eq. 10 on its own: K = box filter of a given A (taps 1/(kh*kw), zero outside the

@@ -91,6 +91,7 @@ def _load() -> ctypes.CDLL:
     L.xnor_box_filter_K.argtypes = [vp, sp, vp, vp]
     L.xnor_conv2d_chain_workspace_bytes.argtypes = [sp, ctypes.POINTER(sz)]
     L.xnor_conv2d_fwd_chain.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, vp]
+    L.xnor_conv2d_fwd_chain_from_A.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, vp]
     L.xnor_forward_image_supported.argtypes = [sp]
     L.xnor_forward_image.argtypes = [vp, vp, vp, sp, vp, vp, vp]
     L.xnor_bwn_conv2d_fwd.argtypes = [vp, vp, vp, sp, vp, vp]
@@ -104,7 +105,7 @@ def _load() -> ctypes.CDLL:
                  "xnor_conv2d_chain_workspace_bytes", "xnor_conv2d_fwd_chain",
                  "xnor_forward_image_supported", "xnor_forward_image",
                  "xnor_bwn_conv2d_fwd", "xnor_bwn_conv2d_fwd_algo",
-                 "xnor_conv2d_fwd_expanded_from_A"):
+                 "xnor_conv2d_fwd_expanded_from_A", "xnor_conv2d_fwd_chain_from_A"):
         getattr(L, name).restype = ci
     return L
 
@@ -375,4 +376,24 @@ def xnor_conv2d_fwd_chain(Ipk: torch.Tensor, Wpk: torch.Tensor, K: torch.Tensor,
         _dev(K, torch.float32, (s.N, OH, OW), "K"), _dev(alpha, torch.float32, (s.F,), "alpha"), ctypes.byref(s.c()),
         _dev(Opk, torch.int32, (s.N, OH, OW, Cwn), "Opk"), _dev(A_next, torch.float32, (s.N, OH, OW), "A_next"),
         _dev(workspace, torch.uint8, name="workspace"), workspace.numel(), _stream()), "xnor_conv2d_fwd_chain")
+    return Opk, A_next
+
+
+def xnor_conv2d_fwd_chain_from_A(Ipk: torch.Tensor, Wpk: torch.Tensor, A: torch.Tensor, alpha: torch.Tensor, s: Shape,
+                                 Opk: torch.Tensor | None = None, A_next: torch.Tensor | None = None,
+                                 workspace: torch.Tensor | None = None):
+    """xnor_conv2d_fwd_chain taking this layer's channel mean A [N][H][W] instead of K."""
+    OH, OW = xnor_out_dim(s)
+    Cwn = (s.F + 31) // 32
+    if Opk is None:
+        Opk = torch.empty((s.N, OH, OW, Cwn), dtype=torch.int32, device=Ipk.device)
+    if A_next is None:
+        A_next = torch.empty((s.N, OH, OW), dtype=torch.float32, device=Ipk.device)
+    if workspace is None:
+        workspace = torch.empty((xnor_conv2d_chain_workspace_bytes(s),), dtype=torch.uint8, device=Ipk.device)
+    _ok(lib.xnor_conv2d_fwd_chain_from_A(
+        _dev(Ipk, torch.int32, (s.N, s.H, s.W, s.Cw), "Ipk"), _dev(Wpk, torch.int32, (s.F, s.kh, s.kw, s.Cw), "Wpk"),
+        _dev(A, torch.float32, (s.N, s.H, s.W), "A"), _dev(alpha, torch.float32, (s.F,), "alpha"), ctypes.byref(s.c()),
+        _dev(Opk, torch.int32, (s.N, OH, OW, Cwn), "Opk"), _dev(A_next, torch.float32, (s.N, OH, OW), "A_next"),
+        _dev(workspace, torch.uint8, name="workspace"), workspace.numel(), _stream()), "xnor_conv2d_fwd_chain_from_A")
     return Opk, A_next

@@ -872,7 +872,7 @@ size_t conv_mfma_chain_workspace_bytes(const Geom &g)
     return pl.ws_bytes + (size_t)g.N * g.OH * g.OW * pl.f_tiles * sizeof(float);
 }
 
-hipError_t launch_conv_mfma_chain(const uint32_t *Ipk, const uint32_t *Wpk, const float *K,
+hipError_t launch_conv_mfma_chain(const uint32_t *Ipk, const uint32_t *Wpk, const float *K, const float *A,
                                   const float *alpha, const Geom &g, uint32_t *Opk, float *A_next,
                                   void *workspace, hipStream_t st)
 {
@@ -881,7 +881,7 @@ hipError_t launch_conv_mfma_chain(const uint32_t *Ipk, const uint32_t *Wpk, cons
     float *P = reinterpret_cast<float *>(static_cast<char *>(workspace) + pl.ws_bytes);
     hipError_t e = launch_expand_filters(Wpk, g, workspace, st);
     if (e != hipSuccess) return e;
-    e = launch_mfma(Ipk, K, nullptr, alpha, g, nullptr, nullptr, Opk, P, workspace, st);
+    e = launch_mfma(Ipk, K, A, alpha, g, nullptr, nullptr, Opk, P, workspace, st);   // K or A, the other null
     if (e != hipSuccess) return e;
     const long long npix = (long long)g.N * g.OH * g.OW;
     chain_mean_kernel<<<ceil_div(npix, 256), 256, 0, st>>>(P, npix, pl.f_tiles, g.F, A_next);

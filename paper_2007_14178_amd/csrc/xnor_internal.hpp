@@ -60,9 +60,9 @@ hipError_t launch_conv_mfma_expanded_from_A(const uint32_t *Ipk, const float *A,
                                             const Geom &g, float *out, int32_t *dot,
                                             const void *workspace, hipStream_t st);
 size_t conv_mfma_chain_workspace_bytes(const Geom &g);   // 0 if the shape is not supported
-hipError_t launch_conv_mfma_chain(const uint32_t *Ipk, const uint32_t *Wpk, const float *K,
+hipError_t launch_conv_mfma_chain(const uint32_t *Ipk, const uint32_t *Wpk, const float *K, const float *A,
                                   const float *alpha, const Geom &g, uint32_t *Opk, float *A_next,
-                                  void *workspace, hipStream_t st);
+                                  void *workspace, hipStream_t st);   // exactly one of K, A is given
 hipError_t launch_conv_mfma(const uint32_t *Ipk, const uint32_t *Wpk, const float *K,
                             const float *alpha, const Geom &g, float *out, int32_t *dot,
                             void *workspace, hipStream_t st);

@@ -55,10 +55,13 @@ def test_chain_outputs_vs_oracle(xb, shape):
     layer, I, Wt = random_layer(rng, "t", *shape)
     s = xb.Shape(*shape)
     osh = oracle.Shape(*shape)
-    Ipk, K, _ = xb.xnor_input_prepare(dev(I), s)
+    Ipk, K, A = xb.xnor_input_prepare(dev(I), s)
     Wpk, alpha, _ = xb.xnor_filter_prepare(dev(Wt))
     Opk, A_next = xb.xnor_conv2d_fwd_chain(Ipk, Wpk, K, alpha, s)
+    # the form that takes the channel mean and forms K itself gives the same bits
+    Opk2, A_next2 = xb.xnor_conv2d_fwd_chain_from_A(Ipk, Wpk, A, alpha, s)
     torch.cuda.synchronize()
+    assert torch.equal(Opk, Opk2) and torch.equal(A_next, A_next2)
     d_ref, K_ref, a_ref, O_ref = oracle.forward(I, Wt, osh)
     assert np.array_equal(Opk.cpu().numpy().view(np.uint32), oracle.pack(O_ref)), "packed signs of the output"
     A_ref = oracle.channel_mean_abs(O_ref)
