@@ -47,6 +47,8 @@ def parse():
     ap.add_argument("--algo", default="auto", choices=["auto", "direct", "tiled", "mfma"])
     ap.add_argument("--unfused", action="store_true", help="run the four pre-stage calls separately")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--separate-prepare", action="store_true",
+                    help="xnor_input_prepare and xnor_filter_prepare as two calls instead of xnor_prepare")
     ap.add_argument("--sweep", action="store_true",
                     help="not the benchmark line: one JSON line per (layer, conv kernel) for all 11 layers, no CPU baseline")
     ap.add_argument("--chain", action="store_true",
@@ -117,10 +119,13 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
         Opk = torch.empty((s.N, OH, OW, (s.F + 31) // 32), dtype=torch.int32, device="cuda")
         A_next = torch.empty((s.N, OH, OW), dtype=torch.float32, device="cuda")
         ws = torch.empty((xb.xnor_conv2d_chain_workspace_bytes(s),), dtype=torch.uint8, device="cuda")
+    # input side and filter side as one call (one launch where the shapes allow it)
+    one_prepare = not (args.chain or args.unfused or args.separate_prepare)
     if args.chain:
         names = ["conv"]
     else:
-        names = (["pack_I", "scale_K", "alpha", "pack_W"] if args.unfused else ["input_prepare", "filter_prepare"]) + \
+        names = (["pack_I", "scale_K", "alpha", "pack_W"] if args.unfused else
+                 ["prepare"] if one_prepare else ["input_prepare", "filter_prepare"]) + \
                 (["filter_expand", "conv"] if two_phase else ["conv"])
 
     n_marks = len(names) + 1
@@ -153,8 +158,11 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
         else:
             # with the matrix-core kernel K is formed inside the convolution from A (same arithmetic
             # as the box-filter kernel, bit-identical output): one launch less per step
-            mark(); xb.xnor_input_prepare(dI, s, Ipk, A, K, want_K=not two_phase)
-            mark(); xb.xnor_filter_prepare(dW, Wpk, M, alpha)
+            if one_prepare:
+                mark(); xb.xnor_prepare(dI, dW, s, Ipk, A, K, Wpk, M, alpha, want_K=not two_phase)
+            else:
+                mark(); xb.xnor_input_prepare(dI, s, Ipk, A, K, want_K=not two_phase)
+                mark(); xb.xnor_filter_prepare(dW, Wpk, M, alpha)
         if two_phase:
             # per-model work ends with the filters in the matrix-core kernel's operand order
             mark(); xb.xnor_filter_expand(Wpk, s, ws)
@@ -255,7 +263,8 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
     rec = {
         "metric": ("binary GMAC/s, chained layer (XNOR conv taking packed signs + channel mean, emitting the same for the next layer)" if args.chain
                    else "binary GMAC/s, whole forward pass (pack + K + alpha + XNOR conv + rescale)"),
-        "pre_stages": "separate calls" if args.unfused else "one pass over I, one pass over Wt",
+        "pre_stages": ("separate calls" if args.unfused else
+                       "one pass over I, one pass over Wt" + (", issued as one call" if one_prepare else "")),
         "value": value, "unit": "binary GMAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u32 bit-packed +-1 (FP4 in the MFMA kernel), int32 dot, fp32 scale",

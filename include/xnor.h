@@ -114,6 +114,16 @@ int xnor_input_prepare(const float *I, const xnor_shape *s, uint32_t *Ipk, float
                        void *stream);
 
 /*
+ * xnor_input_prepare and xnor_filter_prepare (declared below) as ONE call, for a layer whose input
+ * and filters are both new (the benchmark step; a first inference).  Same outputs, same
+ * definitions; where the shapes allow it (H*W a multiple of 4, at least 256 channels, a large
+ * batch) both sides run in a single launch, the filter blocks beside the HBM-bound input blocks.
+ * K may be NULL as in xnor_input_prepare.
+ */
+int xnor_prepare(const float *I, const float *Wt, const xnor_shape *s, uint32_t *Ipk, float *A_work,
+                 float *K, uint32_t *Wpk, float *M_work, float *alpha, void *stream);
+
+/*
  * Per-model filter preparation in one pass over Wt: the packed filters of xnor_binarize_pack(Wt)
  * (step 1a, Eq. 3) and the alpha of xnor_alpha(Wt) (Eq. 5).
  *   Wt      in   fp32 [F][C][kh][kw]

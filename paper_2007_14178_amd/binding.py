@@ -82,6 +82,7 @@ def _load() -> ctypes.CDLL:
     L.xnor_alpha.argtypes = [vp, ci, ci, ci, ci, vp, vp]
     L.xnor_input_prepare.argtypes = [vp, sp, vp, vp, vp, vp]
     L.xnor_filter_prepare.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp]
+    L.xnor_prepare.argtypes = [vp, vp, sp, vp, vp, vp, vp, vp, vp, vp]
     sz = ctypes.c_size_t
     L.xnor_conv2d_fwd.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, vp]
     L.xnor_conv2d_fwd_algo.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, ci, vp]
@@ -105,7 +106,7 @@ def _load() -> ctypes.CDLL:
                  "xnor_conv2d_chain_workspace_bytes", "xnor_conv2d_fwd_chain",
                  "xnor_forward_image_supported", "xnor_forward_image",
                  "xnor_bwn_conv2d_fwd", "xnor_bwn_conv2d_fwd_algo",
-                 "xnor_conv2d_fwd_expanded_from_A", "xnor_conv2d_fwd_chain_from_A"):
+                 "xnor_conv2d_fwd_expanded_from_A", "xnor_conv2d_fwd_chain_from_A", "xnor_prepare"):
         getattr(L, name).restype = ci
     return L
 
@@ -197,6 +198,34 @@ def xnor_input_prepare(I: torch.Tensor, s: Shape, Ipk: torch.Tensor | None = Non
                                _dev(K, torch.float32, (s.N, OH, OW), "K") if want_K else None, _stream()),
         "xnor_input_prepare")
     return Ipk, K, A_work
+
+
+def xnor_prepare(I: torch.Tensor, Wt: torch.Tensor, s: Shape, Ipk: torch.Tensor | None = None,
+                 A_work: torch.Tensor | None = None, K: torch.Tensor | None = None, Wpk: torch.Tensor | None = None,
+                 M_work: torch.Tensor | None = None, alpha: torch.Tensor | None = None, want_K: bool = True):
+    """Input side and filter side in one call: returns (Ipk, K or None, A, Wpk, alpha, M)."""
+    OH, OW = xnor_out_dim(s)
+    dev = I.device
+    if Ipk is None:
+        Ipk = torch.empty((s.N, s.H, s.W, s.Cw), dtype=torch.int32, device=dev)
+    if A_work is None:
+        A_work = torch.empty((s.N, s.H, s.W), dtype=torch.float32, device=dev)
+    if K is None and want_K:
+        K = torch.empty((s.N, OH, OW), dtype=torch.float32, device=dev)
+    if Wpk is None:
+        Wpk = torch.empty((s.F, s.kh, s.kw, s.Cw), dtype=torch.int32, device=dev)
+    if M_work is None:
+        M_work = torch.empty((s.F, s.kh, s.kw), dtype=torch.float32, device=dev)
+    if alpha is None:
+        alpha = torch.empty((s.F,), dtype=torch.float32, device=dev)
+    _ok(lib.xnor_prepare(_dev(I, torch.float32, (s.N, s.C, s.H, s.W), "I"), _dev(Wt, torch.float32, (s.F, s.C, s.kh, s.kw), "Wt"),
+                         ctypes.byref(s.c()), _dev(Ipk, torch.int32, (s.N, s.H, s.W, s.Cw), "Ipk"),
+                         _dev(A_work, torch.float32, (s.N, s.H, s.W), "A_work"),
+                         _dev(K, torch.float32, (s.N, OH, OW), "K") if want_K else None,
+                         _dev(Wpk, torch.int32, (s.F, s.kh, s.kw, s.Cw), "Wpk"),
+                         _dev(M_work, torch.float32, (s.F, s.kh, s.kw), "M_work"),
+                         _dev(alpha, torch.float32, (s.F,), "alpha"), _stream()), "xnor_prepare")
+    return Ipk, (K if want_K else None), A_work, Wpk, alpha, M_work
 
 
 def xnor_filter_prepare(Wt: torch.Tensor, Wpk: torch.Tensor | None = None,

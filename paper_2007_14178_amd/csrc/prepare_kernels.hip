@@ -197,15 +197,14 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int kPack4Slices = 8;
 constexpr int kPack4Batch = 8;      // channels whose loads are in flight together
 
-__global__ __launch_bounds__(64 * kPack4Slices) void pack_and_mean4_kernel(
+__device__ __attribute__((always_inline)) void pack_and_mean4_block(
     const float *__restrict__ x, long long NP, int C, int HW, int Cw, int Cwp,
-    uint32_t *__restrict__ packed, float *__restrict__ A)
+    uint32_t *__restrict__ packed, float *__restrict__ A, long long block, double *pm_smem)
 {
-    extern __shared__ double pm_smem[];
     const int lane = threadIdx.x, s = threadIdx.y, S = blockDim.y;
     double *part = pm_smem;                                               // [S][4][64]
     uint32_t *words = reinterpret_cast<uint32_t *>(pm_smem + S * 256);    // [4][64][Cwp], Cwp odd
-    const long long p0 = (long long)blockIdx.x * 256;
+    const long long p0 = block * 256;
     const long long p = p0 + 4 * lane;
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
     if (p < NP) {
@@ -273,6 +272,14 @@ __global__ __launch_bounds__(64 * kPack4Slices) void pack_and_mean4_kernel(
     }
 }
 
+__global__ __launch_bounds__(64 * kPack4Slices) void pack_and_mean4_kernel(
+    const float *__restrict__ x, long long NP, int C, int HW, int Cw, int Cwp,
+    uint32_t *__restrict__ packed, float *__restrict__ A)
+{
+    extern __shared__ double pm_smem[];
+    pack_and_mean4_block(x, NP, C, HW, Cw, Cwp, packed, A, blockIdx.x, pm_smem);
+}
+
 bool pack_and_mean_supports(int C) { return (C + 31) / 32 <= 512; }
 
 hipError_t launch_pack_and_mean(const float *x, int N, int C, int H, int W, uint32_t *packed,
@@ -327,12 +334,10 @@ hipError_t launch_alpha_from_tap_means(const float *M, int F, int taps, float *a
 // ------------------------------------------------------------------------------------------------
 constexpr int kFilterStageFloats = 8192;   // 32 KB of LDS for the staged chunk
 
-__global__ __launch_bounds__(256) void filter_pack_mean_kernel(
+__device__ __attribute__((always_inline)) void filter_pack_mean_block(
     const float *__restrict__ Wt, int C, int taps, int Cw, int CH, uint32_t *__restrict__ Wpk,
-    float *__restrict__ M, float *__restrict__ alpha)
+    float *__restrict__ M, float *__restrict__ alpha, int f, int tid, int nthr, double *fp_smem)
 {
-    extern __shared__ double fp_smem[];
-    const int tid = threadIdx.x, f = blockIdx.x;
     const int WH = CH / 32;                                        // channel words per chunk
     double *part = fp_smem;                                         // [WH][taps]
     float *stage = reinterpret_cast<float *>(fp_smem + WH * taps);  // [CH][taps]
@@ -343,10 +348,10 @@ __global__ __launch_bounds__(256) void filter_pack_mean_kernel(
         const int nch = min(CH, C - c0);
         const int nfl = nch * taps;
         __syncthreads();                                            // previous chunk fully consumed
-        for (int i = tid; i < nfl; i += 256) stage[i] = src[(long long)c0 * taps + i];
+        for (int i = tid; i < nfl; i += nthr) stage[i] = src[(long long)c0 * taps + i];
         __syncthreads();
         const int nw = (nch + 31) / 32;
-        for (int it = tid; it < nw * taps; it += 256) {
+        for (int it = tid; it < nw * taps; it += nthr) {
             const int w = it / taps, tap = it - w * taps;
             const int nb = min(32, nch - 32 * w);
             uint32_t word = 0;
@@ -390,6 +395,35 @@ __global__ __launch_bounds__(256) void filter_pack_mean_kernel(
     }
 }
 
+__global__ __launch_bounds__(256) void filter_pack_mean_kernel(
+    const float *__restrict__ Wt, int C, int taps, int Cw, int CH, uint32_t *__restrict__ Wpk,
+    float *__restrict__ M, float *__restrict__ alpha)
+{
+    extern __shared__ double fp_smem[];
+    filter_pack_mean_block(Wt, C, taps, Cw, CH, Wpk, M, alpha, blockIdx.x, threadIdx.x, 256, fp_smem);
+}
+
+// Input side and filter side of a layer in ONE launch: the first blocks each pack 256 pixels of the
+// input (pack_and_mean4_block), the last F blocks each prepare one filter (filter_pack_mean_block).
+// The two sides do not depend on each other.  A compute unit holds one of these 512-thread blocks
+// at a time, and the input blocks rarely fill a whole number of rounds (c5: 392 blocks on 256
+// units): the filter blocks, dispatched last, run on the units the last round leaves idle instead
+// of costing another launch in front of the convolution.
+__global__ __launch_bounds__(64 * kPack4Slices) void prepare_both_kernel(
+    const float *__restrict__ x, long long NP, int C, int HW, int Cw, int Cwp,
+    uint32_t *__restrict__ packed, float *__restrict__ A,
+    const float *__restrict__ Wt, int F, int taps, int CH, uint32_t *__restrict__ Wpk,
+    float *__restrict__ M, float *__restrict__ alpha)
+{
+    extern __shared__ double both_smem[];
+    const long long nb_in = (NP + 255) / 256;
+    if ((long long)blockIdx.x < nb_in)
+        pack_and_mean4_block(x, NP, C, HW, Cw, Cwp, packed, A, blockIdx.x, both_smem);
+    else
+        filter_pack_mean_block(Wt, C, taps, Cw, CH, Wpk, M, alpha, (int)(blockIdx.x - nb_in),
+                               threadIdx.y * 64 + threadIdx.x, 64 * blockDim.y, both_smem);
+}
+
 bool filter_pack_mean_supports(int taps) { return taps <= 256; }
 
 hipError_t launch_filter_pack_mean(const float *Wt, int F, int C, int taps, uint32_t *Wpk, float *M,
@@ -401,6 +435,34 @@ hipError_t launch_filter_pack_mean(const float *Wt, int F, int C, int taps, uint
     const int WH = CH / 32;
     const size_t smem = (size_t)WH * taps * sizeof(double) + (size_t)CH * taps * sizeof(float);
     filter_pack_mean_kernel<<<F, 256, smem, st>>>(Wt, C, taps, Cw, CH, Wpk, M, alpha);
+    return hipGetLastError();
+}
+
+// One launch for both sides, where the four-pixel input pass applies with full-size blocks; the
+// caller falls back to the two separate launches otherwise.
+bool prepare_both_supports(const float *x, int N, int C, int H, int W, int taps)
+{
+    const int HW = H * W, Cw = (C + 31) / 32;
+    return HW % 4 == 0 && ((uintptr_t)x & 15) == 0 && (long long)N * HW >= 256 * 256 &&
+           Cw >= kPack4Slices && Cw <= 512 && taps <= 256;
+}
+
+hipError_t launch_prepare_both(const float *x, int N, int C, int H, int W, uint32_t *packed, float *A,
+                               const float *Wt, int F, int taps, uint32_t *Wpk, float *M, float *alpha,
+                               hipStream_t st)
+{
+    const int HW = H * W, Cw = (C + 31) / 32, Cwp = Cw | 1;
+    const long long NP = (long long)N * HW;
+    const size_t smem4 = (size_t)kPack4Slices * 256 * sizeof(double) + (size_t)256 * Cwp * sizeof(uint32_t);
+    int CH = kFilterStageFloats / taps / 32 * 32;
+    CH = std::min(CH, Cw * 32);
+    const size_t smemf = (size_t)(CH / 32) * taps * sizeof(double) + (size_t)CH * taps * sizeof(float);
+    const size_t smem = std::max(smem4, smemf);
+    if (smem > 64 * 1024) return hipErrorInvalidValue;
+    const long long blocks = (long long)F + ceil_div(NP, 256);
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    prepare_both_kernel<<<dim3((unsigned)blocks), dim3(64, kPack4Slices), smem, st>>>(
+        x, NP, C, HW, Cw, Cwp, packed, A, Wt, F, taps, CH, Wpk, M, alpha);
     return hipGetLastError();
 }
 

@@ -27,6 +27,10 @@ hipError_t launch_pack_and_mean(const float *x, int N, int C, int H, int W, uint
 bool filter_pack_mean_supports(int taps);
 hipError_t launch_filter_pack_mean(const float *Wt, int F, int C, int taps, uint32_t *Wpk, float *M,
                                    float *alpha, hipStream_t st);
+bool prepare_both_supports(const float *x, int N, int C, int H, int W, int taps);
+hipError_t launch_prepare_both(const float *x, int N, int C, int H, int W, uint32_t *packed, float *A,
+                               const float *Wt, int F, int taps, uint32_t *Wpk, float *M, float *alpha,
+                               hipStream_t st);
 hipError_t launch_alpha_from_tap_means(const float *M, int F, int taps, float *alpha, hipStream_t st);
 hipError_t launch_box_filter_K(const float *A, const Geom &g, float *K, hipStream_t st);
 hipError_t launch_alpha(const float *Wt, int F, long long n_red, float *alpha, hipStream_t st);

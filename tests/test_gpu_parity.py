@@ -347,3 +347,27 @@ def test_conv_that_forms_K_itself(xb, shape):
     d_ref, K_ref, a_ref, O_ref = oracle.forward(I, Wt, oshape(layer))
     assert np.array_equal(dot.cpu().numpy(), d_ref)
     assert_rel(out.cpu().numpy(), O_ref, "out")
+
+
+@pytest.mark.parametrize("shape", [(90, 256, 28, 28, 70, 3, 3, 1, 1, 1, 1),      # one launch for both sides
+                                   (84, 288, 28, 28, 33, 5, 5, 1, 1, 2, 2),      # the same, ragged blocks, channel words 9
+                                   (2, 64, 13, 13, 40, 3, 3, 1, 1, 1, 1)],       # falls back to two launches
+                         ids=lambda s: "x".join(map(str, s)))
+def test_prepare_both_sides_in_one_call(xb, shape):
+    """xnor_prepare gives bit for bit what xnor_input_prepare and xnor_filter_prepare give."""
+    print(f"case prepare shape={shape}", flush=True)
+    rng = np.random.default_rng(zlib.crc32(("both" + str(shape)).encode()))
+    layer, I, Wt = random_layer(rng, "t", *shape)
+    s = xb.Shape(*shape)
+    dI, dW = dev(I), dev(Wt)
+    Ipk, K, A, Wpk, alpha, M = xb.xnor_prepare(dI, dW, s)
+    Ipk2, K2, A2 = xb.xnor_input_prepare(dI, s)
+    Wpk2, alpha2, M2 = xb.xnor_filter_prepare(dW)
+    torch.cuda.synchronize()
+    for a, b, what in ((Ipk, Ipk2, "Ipk"), (K, K2, "K"), (A, A2, "A"), (Wpk, Wpk2, "Wpk"), (alpha, alpha2, "alpha"), (M, M2, "M")):
+        assert torch.equal(a, b), what
+    assert np.array_equal(words(Ipk), oracle.pack(I)) and np.array_equal(words(Wpk), oracle.pack(Wt))
+    assert_rel(alpha.cpu().numpy(), oracle.alpha(Wt), "alpha")
+    assert_rel(A.cpu().numpy(), oracle.channel_mean_abs(I), "A")
+    _, none, _, _, _, _ = xb.xnor_prepare(dI, dW, s, want_K=False)
+    assert none is None
