@@ -126,7 +126,7 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
     else:
         names = (["pack_I", "scale_K", "alpha", "pack_W"] if args.unfused else
                  ["prepare"] if one_prepare else ["input_prepare", "filter_prepare"]) + \
-                (["filter_expand", "conv"] if two_phase else ["conv"])
+                (["conv"] if one_prepare or not two_phase else ["filter_expand", "conv"])
 
     n_marks = len(names) + 1
 
@@ -159,13 +159,16 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
             # with the matrix-core kernel K is formed inside the convolution from A (same arithmetic
             # as the box-filter kernel, bit-identical output): one launch less per step
             if one_prepare:
-                mark(); xb.xnor_prepare(dI, dW, s, Ipk, A, K, Wpk, M, alpha, want_K=not two_phase)
+                # (with the matrix-core kernel the call also leaves the filters expanded in `ws`)
+                mark(); xb.xnor_prepare(dI, dW, s, Ipk, A, K, Wpk, M, alpha, want_K=not two_phase,
+                                        workspace=ws if two_phase else None)
             else:
                 mark(); xb.xnor_input_prepare(dI, s, Ipk, A, K, want_K=not two_phase)
                 mark(); xb.xnor_filter_prepare(dW, Wpk, M, alpha)
         if two_phase:
             # per-model work ends with the filters in the matrix-core kernel's operand order
-            mark(); xb.xnor_filter_expand(Wpk, s, ws)
+            if not one_prepare:
+                mark(); xb.xnor_filter_expand(Wpk, s, ws)
             if args.unfused:
                 mark(); xb.xnor_conv2d_fwd_expanded(Ipk, ws, K, alpha, s, out=out)
             else:

@@ -114,14 +114,17 @@ int xnor_input_prepare(const float *I, const xnor_shape *s, uint32_t *Ipk, float
                        void *stream);
 
 /*
- * xnor_input_prepare and xnor_filter_prepare (declared below) as ONE call, for a layer whose input
- * and filters are both new (the benchmark step; a first inference).  Same outputs, same
- * definitions; where the shapes allow it (H*W a multiple of 4, at least 256 channels, a large
- * batch) both sides run in a single launch, the filter blocks beside the HBM-bound input blocks.
- * K may be NULL as in xnor_input_prepare.
+ * xnor_input_prepare, xnor_filter_prepare and (with a workspace) xnor_filter_expand, all declared
+ * below, as ONE call, for a layer whose input and filters are both new (the benchmark step; a first
+ * inference).  Same outputs, same definitions; where the shapes allow it (H*W a multiple of 4, at
+ * least 256 channels, a large batch) all of it runs in a single launch, the filter blocks beside the
+ * HBM-bound input blocks.  K may be NULL as in xnor_input_prepare.  workspace may be NULL; if given
+ * it is filled for xnor_conv2d_fwd_expanded* (XNOR_E_UNSUPPORTED / XNOR_E_WORKSPACE as in
+ * xnor_filter_expand).
  */
 int xnor_prepare(const float *I, const float *Wt, const xnor_shape *s, uint32_t *Ipk, float *A_work,
-                 float *K, uint32_t *Wpk, float *M_work, float *alpha, void *stream);
+                 float *K, uint32_t *Wpk, float *M_work, float *alpha, void *workspace,
+                 size_t workspace_bytes, void *stream);
 
 /*
  * Per-model filter preparation in one pass over Wt: the packed filters of xnor_binarize_pack(Wt)

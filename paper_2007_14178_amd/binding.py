@@ -82,8 +82,8 @@ def _load() -> ctypes.CDLL:
     L.xnor_alpha.argtypes = [vp, ci, ci, ci, ci, vp, vp]
     L.xnor_input_prepare.argtypes = [vp, sp, vp, vp, vp, vp]
     L.xnor_filter_prepare.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp]
-    L.xnor_prepare.argtypes = [vp, vp, sp, vp, vp, vp, vp, vp, vp, vp]
     sz = ctypes.c_size_t
+    L.xnor_prepare.argtypes = [vp, vp, sp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.xnor_conv2d_fwd.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, vp]
     L.xnor_conv2d_fwd_algo.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, ci, vp]
     L.xnor_filter_expand.argtypes = [vp, sp, vp, sz, vp]
@@ -202,8 +202,10 @@ def xnor_input_prepare(I: torch.Tensor, s: Shape, Ipk: torch.Tensor | None = Non
 
 def xnor_prepare(I: torch.Tensor, Wt: torch.Tensor, s: Shape, Ipk: torch.Tensor | None = None,
                  A_work: torch.Tensor | None = None, K: torch.Tensor | None = None, Wpk: torch.Tensor | None = None,
-                 M_work: torch.Tensor | None = None, alpha: torch.Tensor | None = None, want_K: bool = True):
-    """Input side and filter side in one call: returns (Ipk, K or None, A, Wpk, alpha, M)."""
+                 M_work: torch.Tensor | None = None, alpha: torch.Tensor | None = None, want_K: bool = True,
+                 workspace: torch.Tensor | None = None):
+    """Input side and filter side in one call: returns (Ipk, K or None, A, Wpk, alpha, M).
+    With ``workspace`` (uint8, xnor_conv2d_workspace_bytes) the expanded filters are left in it."""
     OH, OW = xnor_out_dim(s)
     dev = I.device
     if Ipk is None:
@@ -224,7 +226,9 @@ def xnor_prepare(I: torch.Tensor, Wt: torch.Tensor, s: Shape, Ipk: torch.Tensor 
                          _dev(K, torch.float32, (s.N, OH, OW), "K") if want_K else None,
                          _dev(Wpk, torch.int32, (s.F, s.kh, s.kw, s.Cw), "Wpk"),
                          _dev(M_work, torch.float32, (s.F, s.kh, s.kw), "M_work"),
-                         _dev(alpha, torch.float32, (s.F,), "alpha"), _stream()), "xnor_prepare")
+                         _dev(alpha, torch.float32, (s.F,), "alpha"),
+                         _dev(workspace, torch.uint8, name="workspace") if workspace is not None else None,
+                         workspace.numel() if workspace is not None else 0, _stream()), "xnor_prepare")
     return Ipk, (K if want_K else None), A_work, Wpk, alpha, M_work
 
 

@@ -26,6 +26,7 @@
 #include <algorithm>
 #include <atomic>
 
+#include "fp4_expand.hpp"
 #include "xnor_internal.hpp"
 
 namespace xnor {
@@ -80,34 +81,6 @@ struct MfmaParams {
     int nbands, bands_per_xcd;
 };
 
-// 8 sign bits -> 8 FP4 codes (bit 1 -> 0x2 = +1.0, bit 0 -> 0xA = -1.0); channel i -> nibble i.
-// Two bits select one byte of a four-entry table through v_perm_b32.
-__device__ inline uint32_t expand8(uint32_t b)
-{
-    uint32_t t = b | (b << 6);
-    t |= t << 12;
-    t &= 0x03030303u;
-    return __builtin_amdgcn_perm(0u, 0x222AA2AAu, t);
-}
-
-// One packed word -> 32 FP4 values; `nvalid` channels are real, the rest become FP4 zero.
-__device__ inline uint4 expand_word(uint32_t w, int nvalid)
-{
-    uint4 e;
-    e.x = expand8(w & 0xffu);
-    e.y = expand8((w >> 8) & 0xffu);
-    e.z = expand8((w >> 16) & 0xffu);
-    e.w = expand8(w >> 24);
-    if (nvalid < 32) {
-        auto m = [&](int d) -> uint32_t {
-            const int nv = nvalid - 8 * d;
-            return nv >= 8 ? 0xffffffffu : (nv <= 0 ? 0u : ((1u << (4 * nv)) - 1u));
-        };
-        e.x &= m(0); e.y &= m(1); e.z &= m(2); e.w &= m(3);
-    }
-    return e;
-}
-
 // Filter words -> FP4 in A-operand order: Wx[tile32][step][lane] (one uint4 per lane).  The steps
 // of a tile run chunk-major, then tap-major, each chunk padded with zero steps to a whole number of
 // register rings: step = chunk*chunk_pad + tap*steps_c + s, packed word = chunk*CH + 2*s + lane/32,
@@ -125,21 +98,14 @@ __global__ __launch_bounds__(256) void expand_filters_kernel(const uint32_t *__r
     const long long t = i >> 6;
     const int step = (int)(t % tile_steps);
     const int tile = (int)(t / tile_steps);
-    const int chunk = step / chunk_pad;
+    ExpandLayout L;
+    L.ok = 1; L.CH = CH; L.nchunks = nchunks; L.chunk_pad = chunk_pad; L.tile_steps = tile_steps; L.Cw2 = Cw2;
+    L.ws_bytes = 0;
+    const int f = tile * 32 + (lane & 31);
     uint4 e = make_uint4(0, 0, 0, 0);
-    if (chunk < nchunks) {
-        const int rem = step - chunk * chunk_pad;
-        const int steps_c = min(CH, Cw2 - chunk * CH) >> 1;
-        if (rem < taps * steps_c) {
-            const int tap = rem / steps_c, s = rem - tap * steps_c;
-            const int f = tile * 32 + (lane & 31);
-            const int w = chunk * CH + 2 * s + (lane >> 5);
-            if (f < F && w < Cw) {
-                const int nvalid = min(32, C - 32 * w);
-                e = expand_word(Wpk[((long long)f * taps + tap) * Cw + w], nvalid);
-            }
-        }
-    }
+    if (f < F)
+        e = expanded_entry(L, step, lane >> 5, taps, Cw, C,
+                           [&](int tap, int w) { return Wpk[((long long)f * taps + tap) * Cw + w]; });
     Wx[i] = e;
 }
 
@@ -759,6 +725,16 @@ MfmaPlan make_plan(const Geom &g, const void *Ipk)
 bool conv_mfma_supports(const Geom &g)
 {
     return make_plan(g, nullptr).ok;
+}
+
+ExpandLayout conv_mfma_expand_layout(const Geom &g)
+{
+    const MfmaPlan pl = make_plan(g, nullptr);   // the workspace layout does not depend on alignment
+    ExpandLayout L{};
+    L.ok = pl.ok ? 1 : 0;
+    L.CH = pl.CH; L.nchunks = pl.nchunks; L.chunk_pad = pl.chunk_pad; L.tile_steps = pl.tile_steps;
+    L.Cw2 = 2 * pl.S2; L.ws_bytes = pl.ws_bytes;
+    return L;
 }
 
 size_t conv_mfma_workspace_bytes(const Geom &g)

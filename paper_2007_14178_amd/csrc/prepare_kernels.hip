@@ -336,11 +336,16 @@ constexpr int kFilterStageFloats = 8192;   // 32 KB of LDS for the staged chunk
 
 __device__ __attribute__((always_inline)) void filter_pack_mean_block(
     const float *__restrict__ Wt, int C, int taps, int Cw, int CH, uint32_t *__restrict__ Wpk,
-    float *__restrict__ M, float *__restrict__ alpha, int f, int tid, int nthr, double *fp_smem)
+    float *__restrict__ M, float *__restrict__ alpha, int f, int tid, int nthr, double *fp_smem,
+    uint4 *__restrict__ Wx = nullptr, ExpandLayout L = ExpandLayout{}, int F = 0)
 {
+    // With Wx the block also writes its filter's rows of the matrix-core kernel's expanded
+    // workspace (what xnor_filter_expand would make of Wpk): the packed words are kept in LDS
+    // ([taps][Cw] behind the staging area) and expanded once the filter is complete.
     const int WH = CH / 32;                                        // channel words per chunk
     double *part = fp_smem;                                         // [WH][taps]
     float *stage = reinterpret_cast<float *>(fp_smem + WH * taps);  // [CH][taps]
+    uint32_t *kept = reinterpret_cast<uint32_t *>(stage + (size_t)CH * taps);   // [taps][Cw], only with Wx
     const float *src = Wt + (long long)f * C * taps;
     uint32_t *dst = Wpk + (long long)f * taps * Cw;
     double tap_total = 0.0;                                         // thread t < taps owns tap t
@@ -376,6 +381,7 @@ __device__ __attribute__((always_inline)) void filter_pack_mean_block(
                 }
             }
             dst[tap * Cw + c0 / 32 + w] = word;
+            if (Wx) kept[tap * Cw + c0 / 32 + w] = word;
             part[it] = acc;
         }
         __syncthreads();
@@ -392,6 +398,26 @@ __device__ __attribute__((always_inline)) void filter_pack_mean_block(
         double sum = 0.0;
         for (int t = 0; t < taps; ++t) sum += part[t];
         alpha[f] = (float)(sum / ((double)C * (double)taps));
+    }
+    if (Wx) {
+        // (the barriers above have made every kept word visible)
+        const int tile = f >> 5, row = f & 31;
+        uint4 *rows = Wx + (size_t)tile * L.tile_steps * 64;
+        for (int e = tid; e < 2 * L.tile_steps; e += nthr) {
+            const int step = e >> 1, kg = e & 1;
+            rows[(size_t)step * 64 + row + 32 * kg] =
+                expanded_entry(L, step, kg, taps, Cw, C, [&](int tap, int w) { return kept[tap * Cw + w]; });
+        }
+        if (f == F - 1) {
+            // rows past the last filter are zeros: the rest of this tile and the tiles after it (the
+            // workspace holds whole workgroup rows of 128 filters)
+            const size_t first = ((size_t)tile * L.tile_steps * 64), end = L.ws_bytes / sizeof(uint4);
+            for (size_t i = first + tid; i < end; i += nthr) {
+                const int lane = (int)(i & 63);
+                const size_t t = (i >> 6) / L.tile_steps;          // tile of entry i
+                if (t > (size_t)tile || (lane & 31) > row) Wx[i] = make_uint4(0, 0, 0, 0);
+            }
+        }
     }
 }
 
@@ -413,7 +439,7 @@ __global__ __launch_bounds__(64 * kPack4Slices) void prepare_both_kernel(
     const float *__restrict__ x, long long NP, int C, int HW, int Cw, int Cwp,
     uint32_t *__restrict__ packed, float *__restrict__ A,
     const float *__restrict__ Wt, int F, int taps, int CH, uint32_t *__restrict__ Wpk,
-    float *__restrict__ M, float *__restrict__ alpha)
+    float *__restrict__ M, float *__restrict__ alpha, uint4 *__restrict__ Wx, ExpandLayout L)
 {
     extern __shared__ double both_smem[];
     const long long nb_in = (NP + 255) / 256;
@@ -421,7 +447,7 @@ __global__ __launch_bounds__(64 * kPack4Slices) void prepare_both_kernel(
         pack_and_mean4_block(x, NP, C, HW, Cw, Cwp, packed, A, blockIdx.x, both_smem);
     else
         filter_pack_mean_block(Wt, C, taps, Cw, CH, Wpk, M, alpha, (int)(blockIdx.x - nb_in),
-                               threadIdx.y * 64 + threadIdx.x, 64 * blockDim.y, both_smem);
+                               threadIdx.y * 64 + threadIdx.x, 64 * blockDim.y, both_smem, Wx, L, F);
 }
 
 bool filter_pack_mean_supports(int taps) { return taps <= 256; }
@@ -447,22 +473,26 @@ bool prepare_both_supports(const float *x, int N, int C, int H, int W, int taps)
            Cw >= kPack4Slices && Cw <= 512 && taps <= 256;
 }
 
+// `Wx` (may be null): the matrix-core kernel's filter workspace, filled as by launch_expand_filters.
+bool prepare_both_can_expand(int C, int taps) { return (long long)taps * ((C + 31) / 32) <= 4096; }
+
 hipError_t launch_prepare_both(const float *x, int N, int C, int H, int W, uint32_t *packed, float *A,
                                const float *Wt, int F, int taps, uint32_t *Wpk, float *M, float *alpha,
-                               hipStream_t st)
+                               void *Wx, const ExpandLayout &L, hipStream_t st)
 {
     const int HW = H * W, Cw = (C + 31) / 32, Cwp = Cw | 1;
     const long long NP = (long long)N * HW;
     const size_t smem4 = (size_t)kPack4Slices * 256 * sizeof(double) + (size_t)256 * Cwp * sizeof(uint32_t);
     int CH = kFilterStageFloats / taps / 32 * 32;
     CH = std::min(CH, Cw * 32);
-    const size_t smemf = (size_t)(CH / 32) * taps * sizeof(double) + (size_t)CH * taps * sizeof(float);
+    const size_t smemf = (size_t)(CH / 32) * taps * sizeof(double) + (size_t)CH * taps * sizeof(float) +
+                         (Wx ? (size_t)taps * Cw * sizeof(uint32_t) : 0);
     const size_t smem = std::max(smem4, smemf);
     if (smem > 64 * 1024) return hipErrorInvalidValue;
     const long long blocks = (long long)F + ceil_div(NP, 256);
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     prepare_both_kernel<<<dim3((unsigned)blocks), dim3(64, kPack4Slices), smem, st>>>(
-        x, NP, C, HW, Cw, Cwp, packed, A, Wt, F, taps, CH, Wpk, M, alpha);
+        x, NP, C, HW, Cw, Cwp, packed, A, Wt, F, taps, CH, Wpk, M, alpha, static_cast<uint4 *>(Wx), L);
     return hipGetLastError();
 }
 

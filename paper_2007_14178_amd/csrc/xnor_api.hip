@@ -139,22 +139,34 @@ int xnor_input_prepare(const float *I, const xnor_shape *s, uint32_t *Ipk, float
 }
 
 int xnor_prepare(const float *I, const float *Wt, const xnor_shape *s, uint32_t *Ipk, float *A_work,
-                 float *K, uint32_t *Wpk, float *M_work, float *alpha, void *stream)
+                 float *K, uint32_t *Wpk, float *M_work, float *alpha, void *workspace,
+                 size_t workspace_bytes, void *stream)
 {
     if (!I || !Wt || !s || !Ipk || !A_work || !Wpk || !M_work || !alpha) return XNOR_E_NULL;
     xnor::Geom g;
     const int rc = make_geom(s, &g);
     if (rc) return rc;
     if (!aligned(I, 4) || !aligned(Wt, 4) || !aligned(Ipk, 4) || !aligned(A_work, 4) || (K && !aligned(K, 4)) ||
-        !aligned(Wpk, 4) || !aligned(M_work, 4) || !aligned(alpha, 4))
+        !aligned(Wpk, 4) || !aligned(M_work, 4) || !aligned(alpha, 4) || (workspace && !aligned(workspace, 16)))
         return XNOR_E_ALIGN;
-    if (!xnor::prepare_both_supports(I, g.N, g.C, g.H, g.W, g.kh * g.kw)) {
-        const int r1 = xnor_input_prepare(I, s, Ipk, A_work, K, stream);
-        return r1 ? r1 : xnor_filter_prepare(Wt, g.F, g.C, g.kh, g.kw, Wpk, M_work, alpha, stream);
+    xnor::ExpandLayout L{};
+    if (workspace) {
+        L = xnor::conv_mfma_expand_layout(g);
+        if (!L.ok) return XNOR_E_UNSUPPORTED;
+        if (workspace_bytes < L.ws_bytes) return XNOR_E_WORKSPACE;
     }
     hipStream_t st = (hipStream_t)stream;
-    const hipError_t e = xnor::launch_prepare_both(I, g.N, g.C, g.H, g.W, Ipk, A_work, Wt, g.F, g.kh * g.kw, Wpk,
-                                                   M_work, alpha, st);
+    const int taps = g.kh * g.kw;
+    if (!xnor::prepare_both_supports(I, g.N, g.C, g.H, g.W, taps)) {
+        int r = xnor_input_prepare(I, s, Ipk, A_work, K, stream);
+        if (!r) r = xnor_filter_prepare(Wt, g.F, g.C, g.kh, g.kw, Wpk, M_work, alpha, stream);
+        if (!r && workspace) r = hip_status(xnor::launch_expand_filters(Wpk, g, workspace, st));
+        return r;
+    }
+    const bool expand_here = workspace && xnor::prepare_both_can_expand(g.C, taps);
+    hipError_t e = xnor::launch_prepare_both(I, g.N, g.C, g.H, g.W, Ipk, A_work, Wt, g.F, taps, Wpk, M_work, alpha,
+                                             expand_here ? workspace : nullptr, L, st);
+    if (e == hipSuccess && workspace && !expand_here) e = xnor::launch_expand_filters(Wpk, g, workspace, st);
     if (e != hipSuccess || !K) return hip_status(e);
     return hip_status(xnor::launch_box_filter_K(A_work, g, K, st));
 }

@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "xnor.h"
+#include "fp4_expand.hpp"
 
 namespace xnor {
 
@@ -28,9 +29,10 @@ bool filter_pack_mean_supports(int taps);
 hipError_t launch_filter_pack_mean(const float *Wt, int F, int C, int taps, uint32_t *Wpk, float *M,
                                    float *alpha, hipStream_t st);
 bool prepare_both_supports(const float *x, int N, int C, int H, int W, int taps);
+bool prepare_both_can_expand(int C, int taps);
 hipError_t launch_prepare_both(const float *x, int N, int C, int H, int W, uint32_t *packed, float *A,
                                const float *Wt, int F, int taps, uint32_t *Wpk, float *M, float *alpha,
-                               hipStream_t st);
+                               void *Wx, const ExpandLayout &L, hipStream_t st);
 hipError_t launch_alpha_from_tap_means(const float *M, int F, int taps, float *alpha, hipStream_t st);
 hipError_t launch_box_filter_K(const float *A, const Geom &g, float *K, hipStream_t st);
 hipError_t launch_alpha(const float *Wt, int F, long long n_red, float *alpha, hipStream_t st);
@@ -56,6 +58,7 @@ hipError_t launch_bwn_direct(const float *I, const uint32_t *Wpk, const float *a
 
 bool conv_mfma_supports(const Geom &g);
 size_t conv_mfma_workspace_bytes(const Geom &g);   // 0 if the shape is not supported
+ExpandLayout conv_mfma_expand_layout(const Geom &g);
 hipError_t launch_expand_filters(const uint32_t *Wpk, const Geom &g, void *workspace, hipStream_t st);
 hipError_t launch_conv_mfma_expanded(const uint32_t *Ipk, const float *K, const float *alpha,
                                      const Geom &g, float *out, int32_t *dot, const void *workspace,

@@ -371,3 +371,11 @@ def test_prepare_both_sides_in_one_call(xb, shape):
     assert_rel(A.cpu().numpy(), oracle.channel_mean_abs(I), "A")
     _, none, _, _, _, _ = xb.xnor_prepare(dI, dW, s, want_K=False)
     assert none is None
+    # with a workspace the expanded filters are what xnor_filter_expand makes of Wpk, byte for byte
+    nbytes = xb.xnor_conv2d_workspace_bytes(s)
+    assert nbytes > 0
+    ws = torch.full((nbytes,), 0x5A, dtype=torch.uint8, device="cuda")
+    xb.xnor_prepare(dI, dW, s, workspace=ws)
+    ws2 = xb.xnor_filter_expand(Wpk2, s)
+    torch.cuda.synchronize()
+    assert torch.equal(ws, ws2)
