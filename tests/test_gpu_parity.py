@@ -379,3 +379,57 @@ def test_prepare_both_sides_in_one_call(xb, shape):
     ws2 = xb.xnor_filter_expand(Wpk2, s)
     torch.cuda.synchronize()
     assert torch.equal(ws, ws2)
+
+
+def test_step_replays_from_a_hip_graph(xb):
+    """The library allocates nothing and records no memset, so a whole step can be captured into a HIP
+    graph: every replay (with eager work and synchronisations in between) equals the eager result."""
+    shape = (8, 256, 28, 28, 96, 3, 3, 1, 1, 1, 1)
+    print(f"case graph shape={shape}", flush=True)
+    rng = np.random.default_rng(5)
+    layer, I, Wt = random_layer(rng, "t", *shape)
+    s = xb.Shape(*shape)
+    OH, OW = xb.xnor_out_dim(s)
+    dI, dW = dev(I), dev(Wt)
+    ws = torch.empty((xb.xnor_conv2d_workspace_bytes(s),), dtype=torch.uint8, device="cuda")
+    Ipk, _, A, Wpk, alpha, M = xb.xnor_prepare(dI, dW, s, want_K=False, workspace=ws)
+    out = torch.empty((s.N, s.F, OH, OW), dtype=torch.float32, device="cuda")
+    Opk = torch.empty((s.N, OH, OW, (s.F + 31) // 32), dtype=torch.int32, device="cuda")
+    A_next = torch.empty((s.N, OH, OW), dtype=torch.float32, device="cuda")
+    cws = torch.empty((xb.xnor_conv2d_chain_workspace_bytes(s),), dtype=torch.uint8, device="cuda")
+    img_out = torch.empty((1, 1, 64, 64), dtype=torch.float32, device="cuda")
+    img = torch.randn((1, 1, 64, 64), device="cuda")
+    ishape = xb.Shape(1, 1, 64, 64, 1, 3, 3, 1, 1, 1, 1)
+    iW = torch.randn((1, 1, 3, 3), device="cuda")
+    iWpk, ialpha, _ = xb.xnor_filter_prepare(iW)
+    bwn_out = torch.empty_like(out)
+
+    def step():
+        xb.xnor_prepare(dI, dW, s, Ipk, A, None, Wpk, M, alpha, want_K=False, workspace=ws)
+        xb.xnor_conv2d_fwd_expanded_from_A(Ipk, ws, A, alpha, s, out=out)
+        xb.xnor_conv2d_fwd_chain_from_A(Ipk, Wpk, A, alpha, s, Opk, A_next, cws)
+        xb.xnor_forward_image(img, iWpk, ialpha, ishape, out=img_out)
+        xb.xnor_bwn_conv2d_fwd(dI, Wpk, alpha, s, out=bwn_out)
+
+    step()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (out, Opk, A_next, img_out, bwn_out)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        for t in (out, A_next, img_out, bwn_out):
+            t.fill_(float("nan"))
+        Opk.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref, what in zip((out, Opk, A_next, img_out, bwn_out), want, ("out", "Opk", "A_next", "image", "bwn")):
+            assert torch.equal(got, ref), f"replay {rep}: {what}"
+    d_ref, _, _, O_ref = oracle.forward(I, Wt, oshape(layer))
+    assert_rel(out.cpu().numpy(), O_ref, "out")
