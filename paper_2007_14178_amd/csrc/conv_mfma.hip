@@ -25,6 +25,7 @@
 // and stream from L2 straight into registers.
 #include <algorithm>
 #include <atomic>
+#include <type_traits>
 
 #include "fp4_expand.hpp"
 #include "xnor_internal.hpp"
@@ -588,7 +589,11 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
     // fp32 output straight from the accumulators: lane l holds pixel l%32 of a tile and, in register
     // r, filter 8*(r/4) + 4*(l/32) + r%4, so one store instruction writes 32 consecutive pixels of
     // two filter planes (two 128-byte runs).  The band's K and the tile's alpha wait in LDS since
-    // the kernel's start (no global-load latency here).
+    // the kernel's start (no global-load latency here).  This phase is bound by its own instruction
+    // stream (a wave issues its 128 stores one after the other), so a store costs two multiplies and
+    // one 64-bit add: the address walks the lane's 16 filter planes (one plane on, after every
+    // fourth five planes on) instead of being formed from the plane index each time, and tiles
+    // whose 32 filters all exist (uniform per tile) carry no per-store predicate.
     float *__restrict__ outp = p.out;
     int32_t *__restrict__ dotp = p.dot;
     // lane-derived indices of this phase are formed from a copy of the lane id that the compiler
@@ -601,6 +606,30 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
     for (int i = 0; i < kWM; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) al[i][r] = Al[(wm * kWM + i) * 32 + 8 * (r >> 2) + 4 * kge + (r & 3)];
+    const long long plane1 = (long long)OHW * 4, plane5 = 5 * plane1;   // bytes between filter planes
+    auto store_tile = [&](auto *base, bool all, int nfilt, auto value) {
+        // base: the lane's pixel in its first filter plane; value(r): what register r's filter gets
+        // (a pointer that has passed through an asm statement is a generic one to the compiler: the
+        // stores name the global address space themselves)
+        char *pr = reinterpret_cast<char *>(base);
+        typedef typename std::remove_pointer<decltype(base)>::type elem_t;
+        typedef __attribute__((address_space(1))) elem_t *ptr_t;
+        if (all) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                *(ptr_t)pr = value(r);
+                pr += (r & 3) == 3 ? plane5 : plane1;
+                asm volatile("" : "+v"(pr));   // (keeps the walk: one add per store)
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                if (4 * kge + 8 * (r >> 2) + (r & 3) < nfilt) *(ptr_t)pr = value(r);
+                pr += (r & 3) == 3 ? plane5 : plane1;
+                asm volatile("" : "+v"(pr));
+            }
+        }
+    };
 #pragma unroll
     for (int j = 0; j < kWN; ++j) {
         if (j >= my_nt) break;
@@ -613,22 +642,14 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
         const long long ob = (long long)n * p.F * OHW + oy * p.OW + ox;
 #pragma unroll
         for (int i = 0; i < kWM; ++i) {
-            const int f0 = (ftile * (2 * kWM) + wm * kWM + i) * 32 + 4 * kge;   // this lane's first filter
-            float *po = outp + ob + (long long)f0 * OHW;
-            const bool whole = f0 - 4 * kge + 32 <= p.F;                        // uniform: all 32 filters exist
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int df = 8 * (r >> 2) + (r & 3);
-                if (whole || f0 + df < p.F) po[(long long)df * OHW] = acc[i][j][r] * (kv * al[i][r]);
-            }
-            if (dotp) {
-                int32_t *pd = dotp + ob + (long long)f0 * OHW;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int df = 8 * (r >> 2) + (r & 3);
-                    if (whole || f0 + df < p.F) pd[(long long)df * OHW] = (int32_t)acc[i][j][r];
-                }
-            }
+            const int ft = (ftile * (2 * kWM) + wm * kWM + i) * 32;   // the tile's first filter (uniform)
+            const int nfilt = p.F - ft;                                  // how many of its 32 exist
+            const long long fo = ob + (long long)(ft + 4 * kge) * OHW;  // this lane's first filter plane
+            store_tile(outp + fo, nfilt >= 32, nfilt,
+                       [&](int r) -> float { return acc[i][j][r] * (kv * al[i][r]); });
+            if (dotp)
+                store_tile(dotp + fo, nfilt >= 32, nfilt,
+                           [&](int r) -> int32_t { return (int32_t)acc[i][j][r]; });
         }
     }
 }

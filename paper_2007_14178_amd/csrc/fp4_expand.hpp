@@ -8,28 +8,34 @@
 
 namespace xnor {
 
-// 8 sign bits -> 8 FP4 codes (bit 1 -> 0x2 = +1.0, bit 0 -> 0xA = -1.0); channel i -> nibble i.
-// Two bits select one byte of a four-entry table through v_perm_b32.
-__device__ inline uint32_t expand8(uint32_t b)
+// Four bit pairs (one per byte of `sel`, values 0..3) -> four bytes of two FP4 codes each
+// (bit 1 -> 0x2 = +1.0, bit 0 -> 0xA = -1.0; the pair's low bit is the low nibble): a four-entry
+// byte table looked up through v_perm_b32.
+__device__ inline uint32_t pair_codes(uint32_t sel)
 {
-    uint32_t t = b | (b << 6);
-    t |= t << 12;
-    t &= 0x03030303u;
-    return __builtin_amdgcn_perm(0u, 0x222AA2AAu, t);
+    return __builtin_amdgcn_perm(0u, 0x222AA2AAu, sel);
 }
 
-// One packed word -> 32 FP4 values; `nvalid` channels are real, the rest become FP4 zero.
+// One packed word -> 32 FP4 values in four registers; `nvalid` channels are real, the rest become
+// FP4 zero.  Register j, byte k holds channels 8k+2j (low nibble) and 8k+2j+1 (high nibble) of the
+// word, which costs a shift, a mask and a lookup per register.  The order of the 32 values inside
+// a register quad is free: both MFMA operands are expanded by this one function, so value i of a
+// pixel always meets value i of a filter, and the sum of the products does not depend on i's order.
 __device__ inline uint4 expand_word(uint32_t w, int nvalid)
 {
     uint4 e;
-    e.x = expand8(w & 0xffu);
-    e.y = expand8((w >> 8) & 0xffu);
-    e.z = expand8((w >> 16) & 0xffu);
-    e.w = expand8(w >> 24);
+    e.x = pair_codes(w & 0x03030303u);
+    e.y = pair_codes((w >> 2) & 0x03030303u);
+    e.z = pair_codes((w >> 4) & 0x03030303u);
+    e.w = pair_codes((w >> 6) & 0x03030303u);
     if (nvalid < 32) {
-        auto m = [&](int d) -> uint32_t {
-            const int nv = nvalid - 8 * d;
-            return nv >= 8 ? 0xffffffffu : (nv <= 0 ? 0u : ((1u << (4 * nv)) - 1u));
+        auto m = [&](int j) -> uint32_t {
+            uint32_t keep = 0;
+            for (int k = 0; k < 4; ++k) {
+                if (8 * k + 2 * j < nvalid) keep |= 0x0fu << (8 * k);
+                if (8 * k + 2 * j + 1 < nvalid) keep |= 0xf0u << (8 * k);
+            }
+            return keep;
         };
         e.x &= m(0); e.y &= m(1); e.z &= m(2); e.w &= m(3);
     }
