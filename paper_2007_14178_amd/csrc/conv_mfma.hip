@@ -76,6 +76,7 @@ struct MfmaParams {
     int tab_len;     // its uint32 entries: one per step of the tile, a multiple of 4
     int chunk_pad;   // steps per chunk in the workspace and the table (a whole number of rings)
     int ragged;      // the last chunk has fewer than CH words
+    int near_out;    // a band's outputs lie within 2^31 bytes of its first image's first filter plane of a tile
     int tile_steps;  // k-steps the workspace holds per filter tile: every chunk padded to a whole
                      // number of rings, plus one ring of zero steps for the prefetch overrun
     FastDiv dCHV, dWp, dRH;
@@ -607,29 +608,35 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
 #pragma unroll
         for (int r = 0; r < 16; ++r) al[i][r] = Al[(wm * kWM + i) * 32 + 8 * (r >> 2) + 4 * kge + (r & 3)];
     const long long plane1 = (long long)OHW * 4, plane5 = 5 * plane1;   // bytes between filter planes
-    auto store_tile = [&](auto *base, bool all, int nfilt, auto value) {
-        // base: the lane's pixel in its first filter plane; value(r): what register r's filter gets
-        // (a pointer that has passed through an asm statement is a generic one to the compiler: the
-        // stores name the global address space themselves)
-        char *pr = reinterpret_cast<char *>(base);
-        typedef typename std::remove_pointer<decltype(base)>::type elem_t;
+    // `tile0` (uniform): the band's first image, the tile's first filter plane; `voff`: the lane's
+    // byte offset from there (its image, its 4*kg-th plane, its pixel).  While that offset fits 32
+    // bits (p.near_out, decided on the host) a store is "scalar base + lane offset": the walk over
+    // the planes is scalar arithmetic and the vector ALU only multiplies.
+    auto store_tile = [&](auto *tile0, long long voff, bool all, int nfilt, auto value) {
+        typedef typename std::remove_pointer<decltype(tile0)>::type elem_t;
         typedef __attribute__((address_space(1))) elem_t *ptr_t;
-        if (all) {
+        const char *ub = reinterpret_cast<const char *>(tile0);
+        if (p.near_out && all) {
+            uint32_t v32 = (uint32_t)voff;
+            asm volatile("" : "+v"(v32));
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                *(ptr_t)pr = value(r);
-                pr += (r & 3) == 3 ? plane5 : plane1;
-                asm volatile("" : "+v"(pr));   // (keeps the walk: one add per store)
+                *(ptr_t)(ub + v32) = value(r);
+                ub += (r & 3) == 3 ? plane5 : plane1;
             }
-        } else {
+            return;
+        }
+        // the general walk: one 64-bit vector add per store (a pointer that has passed through an
+        // asm statement is a generic one to the compiler: the stores name the address space)
+        char *pr = const_cast<char *>(ub) + voff;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                if (4 * kge + 8 * (r >> 2) + (r & 3) < nfilt) *(ptr_t)pr = value(r);
-                pr += (r & 3) == 3 ? plane5 : plane1;
-                asm volatile("" : "+v"(pr));
-            }
+        for (int r = 0; r < 16; ++r) {
+            if (all || 4 * kge + 8 * (r >> 2) + (r & 3) < nfilt) *(ptr_t)pr = value(r);
+            pr += (r & 3) == 3 ? plane5 : plane1;
+            asm volatile("" : "+v"(pr));   // (keeps the walk: one add per store)
         }
     };
+    const int n_first_e = __builtin_amdgcn_readfirstlane(R0 / p.OH);
 #pragma unroll
     for (int j = 0; j < kWN; ++j) {
         if (j >= my_nt) break;
@@ -639,16 +646,17 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
         const int R = R0 + Rl;
         const int n = R / p.OH, oy = R - n * p.OH;
         const float kv = Kl[q];
-        const long long ob = (long long)n * p.F * OHW + oy * p.OW + ox;
+        // elements from (first image, tile's first filter) to (this image, 4*kg filters on, this pixel)
+        const long long lane_el = ((long long)(n - n_first_e) * p.F + 4 * kge) * OHW + oy * p.OW + ox;
 #pragma unroll
         for (int i = 0; i < kWM; ++i) {
             const int ft = (ftile * (2 * kWM) + wm * kWM + i) * 32;   // the tile's first filter (uniform)
             const int nfilt = p.F - ft;                                  // how many of its 32 exist
-            const long long fo = ob + (long long)(ft + 4 * kge) * OHW;  // this lane's first filter plane
-            store_tile(outp + fo, nfilt >= 32, nfilt,
+            const long long tile_el = ((long long)n_first_e * p.F + ft) * OHW;   // (uniform)
+            store_tile(outp + tile_el, lane_el * 4, nfilt >= 32, nfilt,
                        [&](int r) -> float { return acc[i][j][r] * (kv * al[i][r]); });
             if (dotp)
-                store_tile(dotp + fo, nfilt >= 32, nfilt,
+                store_tile(dotp + tile_el, lane_el * 4, nfilt >= 32, nfilt,
                            [&](int r) -> int32_t { return (int32_t)acc[i][j][r]; });
         }
     }
@@ -798,6 +806,8 @@ static hipError_t launch_mfma(const uint32_t *Ipk, const float *K, const float *
     p.kl16 = pl.kl16;
     p.chunk_pad = pl.chunk_pad;
     p.ragged = g.Cw % pl.CH != 0;
+    // a band touches at most TH/OH + 2 images; a lane's offset also spans the tile's 32 planes
+    p.near_out = ((long long)(pl.TH / g.OH + 2) * g.F + 32) * g.OH * g.OW * 4 < (1LL << 31);
     p.tile_steps = pl.tile_steps;
     p.dCHV = make_fastdiv(pl.CH / pl.vw);
     p.dWp = make_fastdiv(pl.Wp);
