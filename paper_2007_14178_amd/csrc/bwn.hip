@@ -49,7 +49,13 @@ struct BwnParams {
     int rows_max;       // staged input rows (upper bound over the pixel groups)
     int pitch;          // staged floats per row = W + 2*pw
     uint32_t inv_plane, inv_pitch;   // ceil(2^32 / (rows_max * pitch)), ceil(2^32 / pitch): exact quotients below 2^16
+                                     // (0 for a divisor of 1, whose reciprocal does not fit: see quot())
 };
+
+// n / d through one multiply-high with inv = ceil(2^32 / d), exact for n*d < 2^32; d = 1 has no
+// such 32-bit reciprocal (2^32) and is flagged by inv = 0 (uniform: a scalar select).
+__device__ inline uint32_t quot(uint32_t n, uint32_t inv) { return inv == 0 ? n : __umulhi(n, inv); }
+uint32_t reciprocal(unsigned long long d) { return d == 1 ? 0u : (uint32_t)(((1ULL << 32) + d - 1) / d); }
 
 // The work of one workgroup with NT pixel tiles.  NT is a template parameter so that the MFMA
 // loop is one basic block (operands of the next MFMAs are loaded ahead of the current ones) and
@@ -111,9 +117,9 @@ __device__ __attribute__((always_inline)) void bwn_workgroup(const BwnParams &p,
         for (int q = 0; q < kPre; ++q) {
             if (q * kThreads >= nelem) break;                  // uniform
             const uint32_t e = (uint32_t)(q * kThreads + t0);
-            const uint32_t c = __umulhi(e, p.inv_plane);
+            const uint32_t c = quot(e, p.inv_plane);
             const uint32_t rem = e - c * (uint32_t)plane;
-            const uint32_t r = __umulhi(rem, p.inv_pitch);
+            const uint32_t r = quot(rem, p.inv_pitch);
             const int xw = (int)(rem - r * (uint32_t)p.pitch);
             const int iy = iy0 + (int)r, ix = xw - p.pw, cg = c0 + (int)c;
             const bool ok = (int)c < p.chan && (int)r < rows && (unsigned)iy < (unsigned)p.H &&
@@ -385,9 +391,8 @@ hipError_t launch_bwn_mfma(const float *I, const uint32_t *Wpk, const float *alp
     p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw; p.OH = g.OH; p.OW = g.OW; p.Cw = g.Cw;
     p.tiles = pl.tiles; p.chan = pl.chan; p.rows_max = pl.rows_max; p.pitch = pl.pitch;
     const long long OHW = (long long)g.OH * g.OW;
-    p.inv_plane = (uint32_t)(((1ULL << 32) + (unsigned long long)pl.rows_max * pl.pitch - 1) /
-                             ((unsigned long long)pl.rows_max * pl.pitch));
-    p.inv_pitch = (uint32_t)(((1ULL << 32) + pl.pitch - 1) / pl.pitch);
+    p.inv_plane = reciprocal((unsigned long long)pl.rows_max * pl.pitch);
+    p.inv_pitch = reciprocal((unsigned long long)pl.pitch);
     p.groups = ceil_div(OHW, 32LL * pl.tiles);
     p.fgroups = ceil_div(g.F, kFiltersPerWg);
     const long long blocks = (long long)g.N * p.groups * p.fgroups;

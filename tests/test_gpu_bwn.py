@@ -78,6 +78,8 @@ SHAPES = [
     (1, 130, 14, 14, 40, 7, 7, 1, 1, 3, 3),
     (5, 256, 14, 14, 130, 3, 3, 2, 2, 1, 1),
     (1, 8, 64, 64, 16, 3, 3, 1, 1, 1, 1),
+    (3, 129, 31, 1, 2, 1, 1, 1, 2, 3, 0),        # staged rows one value wide (a divisor of 1 in the staging index math)
+    (2, 40, 1, 1, 5, 1, 1, 1, 1, 0, 0),          # a staged plane of a single value
     (1, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3),      # a ResNet-style first layer
     (1, 24, 6, 500, 5, 3, 3, 1, 1, 1, 1),        # rows too wide to be fetched a chunk ahead
 ]

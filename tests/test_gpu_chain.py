@@ -32,7 +32,7 @@ def dev(a):
 def assert_rel(got, ref, what, rtol=RTOL):
     got = got.astype(np.float64); ref = ref.astype(np.float64)
     err = np.abs(got - ref)
-    bad = err > rtol * np.abs(ref)
+    bad = err > np.maximum(rtol * np.abs(ref), 2.0 ** -149)   # (one subnormal spacing where that is larger)
     assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} outside {rtol} rel; worst {err.max()}"
 
 
