@@ -6,8 +6,9 @@ tile sizes, kernel / stride / padding combinations, images narrower and wider th
 sends each through: the four separate calls with every convolution kernel, the fused step
 (`xnor_prepare` with the expanded-filter workspace + the convolution that forms K itself), the
 chained form, the Binary-Weight-Network layer and, where it takes the shape, the one-kernel image
-pass.  Bars as everywhere: dots and packed words bit-exact, fp32 within 1e-5 relative (one
-subnormal spacing where that is larger), BWN within 1e-5 * alpha * sum|I|.
+pass.  Bars as everywhere: dots and packed words bit-exact, fp32 within 1e-5 relative (in fp32's
+subnormal range: what the fp32 roundings of the pipeline amount to there), BWN within
+1e-5 * alpha * sum|I|.
 """
 import zlib
 
@@ -33,13 +34,23 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def assert_rel(got, ref, what):
+def assert_rel(got, ref, what, floor=2.0 ** -149):
     got = got.astype(np.float64); ref = ref.astype(np.float64)
     assert got.shape == ref.shape, what
     err = np.abs(got - ref)
-    bad = err > np.maximum(RTOL * np.abs(ref), 2.0 ** -149)
+    bad = err > np.maximum(RTOL * np.abs(ref), floor)
     assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} outside {RTOL} rel; worst {err.max()}"
     assert np.array_equal(got == 0, ref == 0), f"{what}: zero pattern differs"
+
+
+def out_floor(dot_ref, alpha_ref):
+    """Absolute error the fp32 pipeline can make on an output that lies in fp32's subnormal range,
+    in the oracle's own terms: K reaches the convolution as an fp32 value (half a subnormal spacing
+    off, times |dot| * alpha), K * alpha is rounded again (half a spacing, times |dot|) and so is
+    the product.  In the normal range the relative bar is far larger than this."""
+    d = np.abs(dot_ref.astype(np.float64))
+    a = alpha_ref.astype(np.float64)[None, :, None, None]
+    return (0.5 * d * (a + 1.0) + 1.0) * 2.0 ** -149
 
 
 def draw_shape(rng):
@@ -99,7 +110,7 @@ def test_random_shape_all_forms(xb, shape):
             continue
         torch.cuda.synchronize()
         assert np.array_equal(dot.cpu().numpy(), d_ref), f"dot ({name})"
-        assert_rel(out.cpu().numpy(), O_ref, f"out ({name})")
+        assert_rel(out.cpu().numpy(), O_ref, f"out ({name})", out_floor(d_ref, a_ref))
         outs[name] = out
     # every kernel forms the output with the same expression from the same exact dot
     for name, out in outs.items():
@@ -116,7 +127,7 @@ def test_random_shape_all_forms(xb, shape):
         assert K2 is None
         assert torch.equal(Ipk2, Ipk) and torch.equal(Wpk2, Wpk), "packed words (fused prepare)"
         assert np.array_equal(dot2.cpu().numpy(), d_ref), "dot (fused step)"
-        assert_rel(out2.cpu().numpy(), O_ref, "out (fused step)")
+        assert_rel(out2.cpu().numpy(), O_ref, "out (fused step)", out_floor(d_ref, a_ref))
 
         # chained form: packed signs and channel mean of the output
         Opk, A_next = xb.xnor_conv2d_fwd_chain_from_A(Ipk, Wpk, A, alpha, s)
@@ -124,7 +135,8 @@ def test_random_shape_all_forms(xb, shape):
         assert np.array_equal(Opk.cpu().numpy().view(np.uint32), oracle.pack(O_ref)), "packed signs of the output"
         An_ref = oracle.channel_mean_abs(O_ref)
         got = A_next.cpu().numpy()
-        assert_rel(got, An_ref, "channel mean of |out|")
+        # (the mean over the filters of errors that each stay inside out_floor, and its own rounding)
+        assert_rel(got, An_ref, "channel mean of |out|", out_floor(d_ref, a_ref).mean(axis=1) + 2.0 ** -149)
 
     # Binary-Weight-Network layer
     O_b, S = oracle.bwn(I, Wt, osh, want_scale=True)
@@ -144,4 +156,5 @@ def test_random_shape_all_forms(xb, shape):
         oi, di = xb.xnor_forward_image(dI, Wpk, alpha, s, want_dot=True)
         torch.cuda.synchronize()
         assert np.array_equal(di.cpu().numpy(), d_ref), "dot (image pass)"
-        assert_rel(oi.cpu().numpy(), O_ref, "out (image pass)")
+        # (this kernel sums K in fp32: kw*C + kh roundings instead of one)
+        assert_rel(oi.cpu().numpy(), O_ref, "out (image pass)", out_floor(d_ref, a_ref * (shape[6] * shape[1] + shape[5])))
