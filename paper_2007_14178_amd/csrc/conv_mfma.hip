@@ -608,57 +608,77 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
 #pragma unroll
         for (int r = 0; r < 16; ++r) al[i][r] = Al[(wm * kWM + i) * 32 + 8 * (r >> 2) + 4 * kge + (r & 3)];
     const long long plane1 = (long long)OHW * 4, plane5 = 5 * plane1;   // bytes between filter planes
-    // `tile0` (uniform): the band's first image, the tile's first filter plane; `voff`: the lane's
-    // byte offset from there (its image, its 4*kg-th plane, its pixel).  While that offset fits 32
-    // bits (p.near_out, decided on the host) a store is "scalar base + lane offset": the walk over
-    // the planes is scalar arithmetic and the vector ALU only multiplies.
-    auto store_tile = [&](auto *tile0, long long voff, bool all, int nfilt, auto value) {
-        typedef typename std::remove_pointer<decltype(tile0)>::type elem_t;
-        typedef __attribute__((address_space(1))) elem_t *ptr_t;
-        const char *ub = reinterpret_cast<const char *>(tile0);
-        if (p.near_out && all) {
-            uint32_t v32 = (uint32_t)voff;
-            asm volatile("" : "+v"(v32));
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                *(ptr_t)(ub + v32) = value(r);
-                ub += (r & 3) == 3 ? plane5 : plane1;
-            }
-            return;
-        }
-        // the general walk: one 64-bit vector add per store (a pointer that has passed through an
-        // asm statement is a generic one to the compiler: the stores name the address space)
-        char *pr = const_cast<char *>(ub) + voff;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            if (all || 4 * kge + 8 * (r >> 2) + (r & 3) < nfilt) *(ptr_t)pr = value(r);
-            pr += (r & 3) == 3 ? plane5 : plane1;
-            asm volatile("" : "+v"(pr));   // (keeps the walk: one add per store)
-        }
-    };
+    // Per pixel tile of the wave: the lane's byte offset from (the band's first image, a filter
+    // tile's first plane) to (its image, its 4*kg-th plane, its pixel), and its K.
     const int n_first_e = __builtin_amdgcn_readfirstlane(R0 / p.OH);
+    long long lane_b[kWN];
+    float kvs[kWN];
+    bool lane_ok[kWN];
 #pragma unroll
     for (int j = 0; j < kWN; ++j) {
-        if (j >= my_nt) break;
         const int q = (tile0 + j) * 32 + l32e;                // pixel within the band
-        if (q >= npix) continue;
-        const int Rl = q / p.OW, ox = q - Rl * p.OW;
+        lane_ok[j] = j < my_nt && q < npix;
+        const int qq = lane_ok[j] ? q : 0;
+        const int Rl = qq / p.OW, ox = qq - Rl * p.OW;
         const int R = R0 + Rl;
         const int n = R / p.OH, oy = R - n * p.OH;
-        const float kv = Kl[q];
-        // elements from (first image, tile's first filter) to (this image, 4*kg filters on, this pixel)
-        const long long lane_el = ((long long)(n - n_first_e) * p.F + 4 * kge) * OHW + oy * p.OW + ox;
+        kvs[j] = Kl[qq];
+        lane_b[j] = (((long long)(n - n_first_e) * p.F + 4 * kge) * OHW + oy * p.OW + ox) * 4;
+    }
+    // tiles of this wave whose 32 pixels all exist (uniform): only the band's last tile can be ragged
+    const int nfull = max(0, min(my_nt, (npix - tile0 * 32) >> 5));
+    // One filter tile (32 planes) of the wave's pixel tiles.  While a band's outputs lie within
+    // 2 GiB (p.near_out, decided on the host) a store is "scalar base + 32-bit lane offset": the
+    // walk over the planes is scalar arithmetic and the vector ALU only multiplies.  The whole
+    // tiles go plane by plane, the wave's tiles of one plane back to back: they are consecutive
+    // pixels, so the cache lines that two tiles share are completed by consecutive stores.
+    auto store_filter_tile = [&](auto *tile_base, int nfilt, auto value) {
+        typedef typename std::remove_pointer<decltype(tile_base)>::type elem_t;
+        typedef __attribute__((address_space(1))) elem_t *ptr_t;
+        const bool all = nfilt >= 32;
+        int first_slow = 0;
+        if (p.near_out && all) {
+            uint32_t v32[kWN];
 #pragma unroll
-        for (int i = 0; i < kWM; ++i) {
-            const int ft = (ftile * (2 * kWM) + wm * kWM + i) * 32;   // the tile's first filter (uniform)
-            const int nfilt = p.F - ft;                                  // how many of its 32 exist
-            const long long tile_el = ((long long)n_first_e * p.F + ft) * OHW;   // (uniform)
-            store_tile(outp + tile_el, lane_el * 4, nfilt >= 32, nfilt,
-                       [&](int r) -> float { return acc[i][j][r] * (kv * al[i][r]); });
-            if (dotp)
-                store_tile(dotp + tile_el, lane_el * 4, nfilt >= 32, nfilt,
-                           [&](int r) -> int32_t { return (int32_t)acc[i][j][r]; });
+            for (int j = 0; j < kWN; ++j) {
+                v32[j] = (uint32_t)lane_b[j];
+                asm volatile("" : "+v"(v32[j]));
+            }
+            const char *ub = reinterpret_cast<const char *>(tile_base);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+#pragma unroll
+                for (int j = 0; j < kWN; ++j)
+                    if (j < nfull) *(ptr_t)(ub + v32[j]) = value(j, r);
+                ub += (r & 3) == 3 ? plane5 : plane1;
+            }
+            first_slow = nfull;
         }
+        // ragged tiles, partial filter tiles, far outputs: one 64-bit vector add per store (a pointer
+        // that has passed through an asm statement is a generic one to the compiler: the stores
+        // name the address space)
+#pragma unroll
+        for (int j = 0; j < kWN; ++j) {
+            if (j < first_slow || !lane_ok[j]) continue;
+            char *pr = const_cast<char *>(reinterpret_cast<const char *>(tile_base)) + lane_b[j];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                if (all || 4 * kge + 8 * (r >> 2) + (r & 3) < nfilt) *(ptr_t)pr = value(j, r);
+                pr += (r & 3) == 3 ? plane5 : plane1;
+                asm volatile("" : "+v"(pr));   // (keeps the walk: one add per store)
+            }
+        }
+    };
+#pragma unroll
+    for (int i = 0; i < kWM; ++i) {
+        const int ft = (ftile * (2 * kWM) + wm * kWM + i) * 32;   // the tile's first filter (uniform)
+        const int nfilt = p.F - ft;                                  // how many of its 32 exist
+        const long long tile_el = ((long long)n_first_e * p.F + ft) * OHW;   // (uniform)
+        store_filter_tile(outp + tile_el, nfilt,
+                          [&](int j, int r) -> float { return acc[i][j][r] * (kvs[j] * al[i][r]); });
+        if (dotp)
+            store_filter_tile(dotp + tile_el, nfilt,
+                              [&](int j, int r) -> int32_t { return (int32_t)acc[i][j][r]; });
     }
 }
 
