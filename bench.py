@@ -35,7 +35,7 @@ PEAK_HBM_GBS = 8000.0
 # v_xor_b32 + v_bcnt_u32_b32 retire 32 binary MACs per lane: 256 CU x 4 SIMD x 16 lanes x 2.4 GHz
 # = 3.93e13 lane-ops/s -> 6.29e14 binary MAC/s -> 1258 T binary op/s counting 2 ops per MAC.
 PEAK_VALU_POPCOUNT_TOPS = 256 * 4 * 16 * 2.4e9 / 2 * 32 * 2 / 1e12
-MEASURED_CONV_TRAFFIC_BYTES = {("c5", "mfma"): 49.0e6 + 262.5e6}
+MEASURED_CONV_TRAFFIC_BYTES = {("c5", "mfma"): 42.6e6 + 213.2e6}
 
 
 def parse():
