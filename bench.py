@@ -64,6 +64,10 @@ def parse():
                     help="the paper's own workload (Tables I-III): one channel, one 3x3 filter, zero padding, "
                          "square images of 256, 512, 1024 and 2048 pixels; one JSON line per size, latency in ms")
     ap.add_argument("--image-sides", default="256,512,1024,2048")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="skip the HIP-graph replay of the step (its time is reported beside the eager one)")
+    ap.add_argument("--conv-events-every", type=int, default=1,
+                    help="bracket the convolution launch with events on every n-th timed step only (0: never)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
 
@@ -195,8 +199,11 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
     # after every call: five event records per step cost the host about as much as the launches.
     events: list = []
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(events, conv_only=True)
+    for k in range(args.steps):
+        if args.conv_events_every and k % args.conv_events_every == 0:
+            step(events, conv_only=True)
+        else:
+            step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     conv_events = [(m[-2], m[-1]) for m in events]
@@ -205,11 +212,12 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
         step(events)
     torch.cuda.synchronize()
 
-    # The small layers finish faster than the host can issue five launches: with --sweep the step is
+    # An eager step pays the host's launches and the dispatch gaps between dependent kernels (the small
+    # layers finish faster than the host can issue their launches): unless --no-graph, the step is
     # also captured into a HIP graph (the library allocates nothing and records no memset), each
     # replay is checked against the eager result, and the replay time is reported beside the eager one.
     graph_ms, graph_ok = None, None
-    if args.sweep:
+    if not args.no_graph and not args.copy_probe:
         eager = out.clone()
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
@@ -278,7 +286,7 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
                    "buffers": f"reused every step (fp32 input {dI.numel() * 4 / 1e6:.1f} MB, output "
                               f"{out.numel() * 4 / 1e6:.1f} MB; the last-level cache holds 256 MB)"},
         "stage_ms": stage_ms,
-        **({"graph_ms_per_step": graph_ms, "graph_replays_match_eager": graph_ok} if args.sweep else {}),
+        **({"graph_ms_per_step": graph_ms, "graph_replays_match_eager": graph_ok} if graph_ms is not None else {}),
         "roofline": roof,
     }
     rec["_Wt_host"] = Wt_host
