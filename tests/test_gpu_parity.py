@@ -443,3 +443,42 @@ def test_step_replays_from_a_hip_graph(xb):
             assert torch.equal(got, ref), f"replay {rep}: {what}"
     d_ref, _, a_ref, O_ref = oracle.forward(I, Wt, oshape(layer))
     assert_rel(out.cpu().numpy(), O_ref, "out", out_floor(d_ref, a_ref))
+
+
+def test_two_streams_at_once(xb):
+    """Every call enqueues on the caller's stream and the library keeps no state between calls: two
+    different layers issued alternately on two streams (default priority), several rounds in flight
+    at once, give the bits that each gives alone."""
+    shapes = [(6, 256, 28, 28, 130, 3, 3, 1, 1, 1, 1), (9, 96, 27, 27, 64, 5, 5, 1, 1, 2, 2)]
+    print(f"case two streams shapes={shapes}", flush=True)
+    jobs = []
+    for k, shape in enumerate(shapes):
+        rng = np.random.default_rng(70 + k)
+        layer, I, Wt = random_layer(rng, "t", *shape)
+        s = xb.Shape(*shape)
+        OH, OW = xb.xnor_out_dim(s)
+        dI, dW = dev(I), dev(Wt)
+        ws = torch.empty((xb.xnor_conv2d_workspace_bytes(s),), dtype=torch.uint8, device="cuda")
+        Ipk, _, A, Wpk, alpha, M = xb.xnor_prepare(dI, dW, s, want_K=False, workspace=ws)
+        out = torch.empty((s.N, s.F, OH, OW), dtype=torch.float32, device="cuda")
+        bwn = torch.empty_like(out)
+
+        def run(dI=dI, dW=dW, s=s, Ipk=Ipk, A=A, Wpk=Wpk, M=M, alpha=alpha, ws=ws, out=out, bwn=bwn):
+            xb.xnor_prepare(dI, dW, s, Ipk, A, None, Wpk, M, alpha, want_K=False, workspace=ws)
+            xb.xnor_conv2d_fwd_expanded_from_A(Ipk, ws, A, alpha, s, out=out)
+            xb.xnor_bwn_conv2d_fwd(dI, Wpk, alpha, s, out=bwn)
+
+        run()
+        torch.cuda.synchronize()
+        jobs.append((run, out, bwn, out.clone(), bwn.clone(), torch.cuda.Stream()))
+    for run, out, bwn, *_ in jobs:
+        out.fill_(float("nan")); bwn.fill_(float("nan"))
+    torch.cuda.synchronize()
+    for _ in range(4):
+        for run, *_, stream in jobs:
+            with torch.cuda.stream(stream):
+                run()
+    torch.cuda.synchronize()
+    for k, (run, out, bwn, out_ref, bwn_ref, _) in enumerate(jobs):
+        assert torch.equal(out, out_ref), f"layer {k}: out"
+        assert torch.equal(bwn, bwn_ref), f"layer {k}: bwn"
