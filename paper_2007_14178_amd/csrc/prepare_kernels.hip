@@ -227,22 +227,37 @@ __device__ __attribute__((always_inline)) void pack_and_mean4_block(
             }
         };
         float4 cur[kPack4Batch], nxt[kPack4Batch];
-        fetch(s, 0, cur);
+        // A word's channels are taken from the last batch down to the first and, within a batch, from
+        // the last channel down: the word is built by shifting the next lower channel's bit in at the
+        // bottom, which is one compare (0 <= x: true for +0.0 and -0.0, false for NaN) and one
+        // add-with-carry (word + word + bit) per value instead of compare, select and shift-or.
+        constexpr int kLastBatch = 32 - kPack4Batch;
+        fetch(s, kLastBatch, cur);
         for (int w = s; w < Cw; w += S) {
             uint32_t word[4] = {0u, 0u, 0u, 0u};
             const int cbase = 32 * w;
+            const bool whole = cbase + 32 <= C;               // (uniform) no tail channels in this word
 #pragma unroll
-            for (int b = 0; b < 32; b += kPack4Batch) {
-                if (b + kPack4Batch < 32) fetch(w, b + kPack4Batch, nxt);
-                else fetch(w + S, 0, nxt);
+            for (int b = kLastBatch; b >= 0; b -= kPack4Batch) {
+                if (b > 0) fetch(w, b - kPack4Batch, nxt);
+                else fetch(w + S, kLastBatch, nxt);
 #pragma unroll
-                for (int j = 0; j < kPack4Batch; ++j) {
-                    const bool live = cbase + b + j < C;
+                for (int j = kPack4Batch - 1; j >= 0; --j) {
                     const float e[4] = {cur[j].x, cur[j].y, cur[j].z, cur[j].w};
+                    if (whole) {
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        word[k] |= (e[k] >= 0.0f ? 1u : 0u) << (b + j);
-                        acc[k] += live ? (double)fabsf(e[k]) : 0.0;
+                        for (int k = 0; k < 4; ++k) {
+                            asm("v_cmp_le_f32 vcc, 0, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc"
+                                : "+v"(word[k]) : "v"(e[k]) : "vcc");
+                            acc[k] += (double)fabsf(e[k]);
+                        }
+                    } else {
+                        const bool live = cbase + b + j < C;  // (tail channels were fetched as -1: bit 0)
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            word[k] = (word[k] << 1) | (e[k] >= 0.0f ? 1u : 0u);
+                            acc[k] += live ? (double)fabsf(e[k]) : 0.0;
+                        }
                     }
                 }
 #pragma unroll
