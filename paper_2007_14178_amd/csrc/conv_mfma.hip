@@ -80,6 +80,7 @@ struct MfmaParams {
     int tile_steps;  // k-steps the workspace holds per filter tile: every chunk padded to a whole
                      // number of rings, plus one ring of zero steps for the prefetch overrun
     FastDiv dCHV, dWp, dRH;
+    FastDiv dOW, dOH;   // for a pixel of the band (below 2^9) and a row counted from the band's first image (below 2^13)
     int nbands, bands_per_xcd;
 };
 
@@ -155,8 +156,8 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
     const int npix = rows * p.OW;
     const int n_first = __builtin_amdgcn_readfirstlane(R0 / p.OH), oy0 = R0 - n_first * p.OH;
     const int r0 = (p.OH - 1 - oy0) * p.sh + p.kh;   // staged rows of the first image if it runs to its end
-    const int R_last = R0 + rows - 1;
-    const int n_last = __builtin_amdgcn_readfirstlane(R_last / p.OH), oy_last = R_last - n_last * p.OH;
+    const int dn_last = (int)fdiv((uint32_t)(oy0 + rows - 1), p.dOH);   // (uniform)
+    const int n_last = n_first + dn_last, oy_last = oy0 + rows - 1 - dn_last * p.OH;
     const int srows = (n_last == n_first) ? (oy_last - oy0) * p.sh + p.kh
                                           : r0 + (n_last - n_first - 1) * p.RHfull + oy_last * p.sh + p.kh;
     const int nslots = srows * p.Wp;
@@ -298,9 +299,9 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
         if (p.A) {
             // K of this band's pixel `tid` from the channel mean A: the same sum, order and rounding
             // as the stand-alone box filter (double accumulation over the in-image taps, one divide)
-            const int Rl = tid / p.OW, ox = tid - Rl * p.OW;
-            const int R = R0 + Rl;
-            const int n = R / p.OH, oy = R - n * p.OH;
+            const int Rl = (int)fdiv((uint32_t)tid, p.dOW), ox = tid - Rl * p.OW;
+            const int dn = (int)fdiv((uint32_t)(oy0 + Rl), p.dOH);
+            const int n = n_first + dn, oy = oy0 + Rl - dn * p.OH;
             const float *a = p.A + (long long)n * p.H * p.W;
             // no branches around the loads (out-of-image taps read a clamped address and add 0), so
             // that the unrolled loop has all its loads in flight at once
@@ -329,9 +330,9 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
     for (int j = 0; j < kWN; ++j) {
         const int q = (tile0 + j) * 32 + l32;
         const int qq = (j < my_nt && q < npix) ? q : 0;   // idle lanes read pixel 0 and store nothing
-        const int Rl = qq / p.OW, ox = qq - Rl * p.OW;
-        const int R = R0 + Rl;
-        const int n = R / p.OH, oy = R - n * p.OH;
+        const int Rl = (int)fdiv((uint32_t)qq, p.dOW), ox = qq - Rl * p.OW;
+        const int dn = (int)fdiv((uint32_t)(oy0 + Rl), p.dOH);
+        const int n = n_first + dn, oy = oy0 + Rl - dn * p.OH;
         const int srow = (n == n_first) ? (oy - oy0) * p.sh
                                         : r0 + (n - n_first - 1) * p.RHfull + oy * p.sh;
         bB[j] = lds_base + (uint32_t)((srow * p.Wp + ox * p.sw) * p.pitch16 + kg) * 16u;
@@ -619,9 +620,10 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
         const int q = (tile0 + j) * 32 + l32e;                // pixel within the band
         lane_ok[j] = j < my_nt && q < npix;
         const int qq = lane_ok[j] ? q : 0;
-        const int Rl = qq / p.OW, ox = qq - Rl * p.OW;
-        const int R = R0 + Rl;
-        const int n = R / p.OH, oy = R - n * p.OH;
+        const int Rl = (int)fdiv((uint32_t)qq, p.dOW), ox = qq - Rl * p.OW;
+        const int oy0_e = R0 - n_first_e * p.OH;
+        const int dn = (int)fdiv((uint32_t)(oy0_e + Rl), p.dOH);
+        const int n = n_first_e + dn, oy = oy0_e + Rl - dn * p.OH;
         kvs[j] = Kl[qq];
         lane_b[j] = (((long long)(n - n_first_e) * p.F + 4 * kge) * OHW + oy * p.OW + ox) * 4;
     }
@@ -832,6 +834,8 @@ static hipError_t launch_mfma(const uint32_t *Ipk, const float *K, const float *
     p.dCHV = make_fastdiv(pl.CH / pl.vw);
     p.dWp = make_fastdiv(pl.Wp);
     p.dRH = make_fastdiv(pl.RHfull);
+    p.dOW = make_fastdiv(g.OW);
+    p.dOH = make_fastdiv(g.OH);
 
     p.nbands = ceil_div(p.total_rows, pl.TH);
     p.bands_per_xcd = ceil_div(p.nbands, kXcds);
