@@ -136,15 +136,14 @@ hipError_t launch_channel_mean_abs(const float *I, int N, int C, int H, int W, f
 // CU and nothing to overlap its final barrier and write-out with).
 constexpr int kPackMeanSlices = 4;
 
-__global__ __launch_bounds__(64 * kPackMeanSlices) void pack_and_mean_kernel(
+__device__ __attribute__((always_inline)) void pack_and_mean_block(
     const float *__restrict__ x, long long NP, int C, int HW, int Cw, int Cwp,
-    uint32_t *__restrict__ packed, float *__restrict__ A)
+    uint32_t *__restrict__ packed, float *__restrict__ A, long long block, double *pm_smem)
 {
-    extern __shared__ double pm_smem[];
     const int lane = threadIdx.x, s = threadIdx.y, S = blockDim.y;
     double *part = pm_smem;                                              // [S][64]
     uint32_t *words = reinterpret_cast<uint32_t *>(pm_smem + S * 64);    // [64][Cwp], Cwp odd
-    const long long p0 = (long long)blockIdx.x * 64;
+    const long long p0 = block * 64;
     const long long p = p0 + lane;
     double acc = 0.0;
     if (p < NP) {
@@ -187,6 +186,14 @@ __global__ __launch_bounds__(64 * kPackMeanSlices) void pack_and_mean_kernel(
         const int px = i / Cw, w = i - px * Cw;
         dst[i] = words[px * Cwp + w];
     }
+}
+
+__global__ __launch_bounds__(64 * kPackMeanSlices) void pack_and_mean_kernel(
+    const float *__restrict__ x, long long NP, int C, int HW, int Cw, int Cwp,
+    uint32_t *__restrict__ packed, float *__restrict__ A)
+{
+    extern __shared__ double pm_smem[];
+    pack_and_mean_block(x, NP, C, HW, Cw, Cwp, packed, A, blockIdx.x, pm_smem);
 }
 
 // The same pass with four consecutive pixels per lane (one 16-byte load per lane and channel, 1 KB
@@ -465,6 +472,24 @@ __global__ __launch_bounds__(64 * kPack4Slices) void prepare_both_kernel(
                                threadIdx.y * 64 + threadIdx.x, 64 * blockDim.y, both_smem, Wx, L, F);
 }
 
+// The same with the one-pixel-per-lane input pass (64 pixels per block): for inputs whose H*W is not
+// a multiple of 4, that are not 16-byte aligned, or that are too small to fill the chip with
+// 256-pixel blocks.
+__global__ __launch_bounds__(64 * kPackMeanSlices) void prepare_both1_kernel(
+    const float *__restrict__ x, long long NP, int C, int HW, int Cw, int Cwp,
+    uint32_t *__restrict__ packed, float *__restrict__ A,
+    const float *__restrict__ Wt, int F, int taps, int CH, uint32_t *__restrict__ Wpk,
+    float *__restrict__ M, float *__restrict__ alpha, uint4 *__restrict__ Wx, ExpandLayout L)
+{
+    extern __shared__ double both_smem[];
+    const long long nb_in = (NP + 63) / 64;
+    if ((long long)blockIdx.x < nb_in)
+        pack_and_mean_block(x, NP, C, HW, Cw, Cwp, packed, A, blockIdx.x, both_smem);
+    else
+        filter_pack_mean_block(Wt, C, taps, Cw, CH, Wpk, M, alpha, (int)(blockIdx.x - nb_in),
+                               threadIdx.y * 64 + threadIdx.x, 64 * blockDim.y, both_smem, Wx, L, F);
+}
+
 bool filter_pack_mean_supports(int taps) { return taps <= 256; }
 
 hipError_t launch_filter_pack_mean(const float *Wt, int F, int C, int taps, uint32_t *Wpk, float *M,
@@ -479,13 +504,37 @@ hipError_t launch_filter_pack_mean(const float *Wt, int F, int C, int taps, uint
     return hipGetLastError();
 }
 
-// One launch for both sides, where the four-pixel input pass applies with full-size blocks; the
-// caller falls back to the two separate launches otherwise.
-bool prepare_both_supports(const float *x, int N, int C, int H, int W, int taps)
+// One launch for both sides: with the four-pixel input pass where it applies with full-size blocks,
+// else with the one-pixel pass; the caller falls back to separate launches where neither fits.
+static bool four_pixel_pass(const float *x, int N, int C, int H, int W)
 {
     const int HW = H * W, Cw = (C + 31) / 32;
-    return HW % 4 == 0 && ((uintptr_t)x & 15) == 0 && (long long)N * HW >= 256 * 256 &&
-           Cw >= kPack4Slices && Cw <= 512 && taps <= 256;
+    return HW % 4 == 0 && ((uintptr_t)x & 15) == 0 && (long long)N * HW >= 256 * 256 && Cw >= kPack4Slices;
+}
+
+static size_t filter_block_smem(int C, int taps, bool expand, int *CH_out)
+{
+    const int Cw = (C + 31) / 32;
+    int CH = kFilterStageFloats / taps / 32 * 32;
+    CH = std::min(CH, Cw * 32);
+    *CH_out = CH;
+    return (size_t)(CH / 32) * taps * sizeof(double) + (size_t)CH * taps * sizeof(float) +
+           (expand ? (size_t)taps * Cw * sizeof(uint32_t) : 0);
+}
+
+bool prepare_both_supports(const float *x, int N, int C, int H, int W, int taps)
+{
+    const int Cw = (C + 31) / 32, Cwp = Cw | 1;
+    if (Cw > 512 || taps > 256) return false;
+    if (four_pixel_pass(x, N, C, H, W)) return true;
+    // (the one-pixel pass: its words of 64 pixels and the filter block's staging must fit 64 KB, and
+    // the filter block gives every tap a thread of its own)
+    int S = 1;
+    while (S < kPackMeanSlices && 2 * S <= Cw) S *= 2;
+    if (64 * S < taps) return false;
+    int CH;
+    const size_t smem1 = (size_t)kPackMeanSlices * 64 * sizeof(double) + (size_t)64 * Cwp * sizeof(uint32_t);
+    return std::max(smem1, filter_block_smem(C, taps, true, &CH)) <= 64 * 1024;
 }
 
 // `Wx` (may be null): the matrix-core kernel's filter workspace, filled as by launch_expand_filters.
@@ -497,16 +546,26 @@ hipError_t launch_prepare_both(const float *x, int N, int C, int H, int W, uint3
 {
     const int HW = H * W, Cw = (C + 31) / 32, Cwp = Cw | 1;
     const long long NP = (long long)N * HW;
-    const size_t smem4 = (size_t)kPack4Slices * 256 * sizeof(double) + (size_t)256 * Cwp * sizeof(uint32_t);
-    int CH = kFilterStageFloats / taps / 32 * 32;
-    CH = std::min(CH, Cw * 32);
-    const size_t smemf = (size_t)(CH / 32) * taps * sizeof(double) + (size_t)CH * taps * sizeof(float) +
-                         (Wx ? (size_t)taps * Cw * sizeof(uint32_t) : 0);
-    const size_t smem = std::max(smem4, smemf);
+    int CH;
+    const size_t smemf = filter_block_smem(C, taps, Wx != nullptr, &CH);
+    if (four_pixel_pass(x, N, C, H, W)) {
+        const size_t smem4 = (size_t)kPack4Slices * 256 * sizeof(double) + (size_t)256 * Cwp * sizeof(uint32_t);
+        const size_t smem = std::max(smem4, smemf);
+        if (smem > 64 * 1024) return hipErrorInvalidValue;
+        const long long blocks = (long long)F + ceil_div(NP, 256);
+        if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+        prepare_both_kernel<<<dim3((unsigned)blocks), dim3(64, kPack4Slices), smem, st>>>(
+            x, NP, C, HW, Cw, Cwp, packed, A, Wt, F, taps, CH, Wpk, M, alpha, static_cast<uint4 *>(Wx), L);
+        return hipGetLastError();
+    }
+    int S = 1;
+    while (S < kPackMeanSlices && 2 * S <= Cw) S *= 2;
+    const size_t smem1 = (size_t)S * 64 * sizeof(double) + (size_t)64 * Cwp * sizeof(uint32_t);
+    const size_t smem = std::max(smem1, smemf);
     if (smem > 64 * 1024) return hipErrorInvalidValue;
-    const long long blocks = (long long)F + ceil_div(NP, 256);
+    const long long blocks = (long long)F + ceil_div(NP, 64);
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    prepare_both_kernel<<<dim3((unsigned)blocks), dim3(64, kPack4Slices), smem, st>>>(
+    prepare_both1_kernel<<<dim3((unsigned)blocks), dim3(64, S), smem, st>>>(
         x, NP, C, HW, Cw, Cwp, packed, A, Wt, F, taps, CH, Wpk, M, alpha, static_cast<uint4 *>(Wx), L);
     return hipGetLastError();
 }
