@@ -116,9 +116,10 @@ int xnor_input_prepare(const float *I, const xnor_shape *s, uint32_t *Ipk, float
 /*
  * xnor_input_prepare, xnor_filter_prepare and (with a workspace) xnor_filter_expand, all declared
  * below, as ONE call, for a layer whose input and filters are both new (the benchmark step; a first
- * inference).  Same outputs, same definitions; where the shapes allow it (H*W a multiple of 4, at
- * least 256 channels, a large batch) all of it runs in a single launch, the filter blocks beside the
- * HBM-bound input blocks.  K may be NULL as in xnor_input_prepare.  workspace may be NULL; if given
+ * inference).  Same outputs, same definitions; but for extreme shapes (more than 256 taps or 16384
+ * channels, filters too large for one workgroup's LDS) all of it runs in a single launch, the filter
+ * blocks beside the HBM-bound input blocks (a second launch forms K where it is asked for).  K may
+ * be NULL as in xnor_input_prepare.  workspace may be NULL; if given
  * it is filled for xnor_conv2d_fwd_expanded* (XNOR_E_UNSUPPORTED / XNOR_E_WORKSPACE as in
  * xnor_filter_expand).
  */
