@@ -157,9 +157,11 @@ __device__ __attribute__((always_inline)) void pack_and_mean_block(
                 float v[32];
 #pragma unroll
                 for (int j = 0; j < 32; ++j) v[j] = __builtin_nontemporal_load(src + (long long)(cbase + j) * HW);
+                // from the highest channel down, each bit shifted in at the bottom: one compare (0 <= x:
+                // true for +0.0 and -0.0, false for NaN) and one add-with-carry (word + word + bit)
 #pragma unroll
-                for (int j = 0; j < 32; ++j) {
-                    word |= (v[j] >= 0.0f ? 1u : 0u) << j;
+                for (int j = 31; j >= 0; --j) {
+                    asm("v_cmp_le_f32 vcc, 0, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc" : "+v"(word) : "v"(v[j]) : "vcc");
                     acc += (double)fabsf(v[j]);
                 }
             } else {
