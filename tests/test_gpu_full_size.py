@@ -158,3 +158,36 @@ def test_output_larger_than_2_to_31_elements():
         err = np.abs(out[:, fsel].cpu().numpy().astype(np.float64) - O_bwn)
         assert (err <= RTOL * a[None, :, None, None] * S[:, None]).all()
         assert not bool(torch.isnan(out).any())
+
+
+def test_matrix_core_kernel_with_outputs_spread_over_more_than_2_gib():
+    """The matrix-core kernel addresses a band's outputs with a 32-bit lane offset from a scalar base
+    while they lie within 2 GiB of the band's first plane, and with 64-bit lane addresses otherwise:
+    1100 filter planes of 1000x256 pixels (1.13 GB per image; the library's bound allows a band to
+    touch three images, 3.4 GB) take the second way.  Planes at both ends and in the
+    partial last filter tile are compared with the oracle run on those filters alone."""
+    from paper_2007_14178_amd import binding as xb
+    N, C, H, W, F = 1, 32, 1000, 256, 1100
+    print(f"case far outputs F={F} {H}x{W}", flush=True)
+    rng = np.random.default_rng(101)
+    I = rng.standard_normal((N, C, H, W), dtype=np.float32)
+    Wt = rng.standard_normal((F, C, 1, 1), dtype=np.float32)
+    s = xb.Shape(N, C, H, W, F, 1, 1, 1, 1, 0, 0)
+    assert ((1 + 2) * F + 32) * H * W * 4 >= 2 ** 31          # (how the library decides)
+    dI, dW = torch.from_numpy(I).cuda(), torch.from_numpy(Wt).cuda()
+    Ipk, K, A = xb.xnor_input_prepare(dI, s)
+    Wpk, alpha, _ = xb.xnor_filter_prepare(dW)
+    out = torch.full((N, F, H, W), float("nan"), dtype=torch.float32, device="cuda")
+    xb.xnor_conv2d_fwd(Ipk, Wpk, K, alpha, s, out=out, algo=xb.ALGO_MFMA)
+    torch.cuda.synchronize()
+    assert not bool(torch.isnan(out).any())
+    fsel = [0, 31, 127, 128, 1055, 1056, 1087, 1088, 1099]
+    sub = oracle.Shape(N, C, H, W, len(fsel), 1, 1, 1, 1, 0, 0)
+    d_ref, _, _, O_ref = oracle.forward(I, Wt[fsel], sub)
+    assert rel_ok(out[:, fsel].cpu().numpy(), O_ref)
+    # the same through the form that makes K itself, with the raw dots
+    ws = xb.xnor_filter_expand(Wpk, s)
+    out2, dot2 = xb.xnor_conv2d_fwd_expanded_from_A(Ipk, ws, A, alpha, s, want_dot=True)
+    torch.cuda.synchronize()
+    assert torch.equal(out2, out)
+    assert np.array_equal(dot2[:, fsel].cpu().numpy(), d_ref)
