@@ -219,6 +219,14 @@ int xnor_conv2d_fwd_chain(const uint32_t *Ipk, const uint32_t *Wpk, const float 
 int xnor_conv2d_fwd_chain_from_A(const uint32_t *Ipk, const uint32_t *Wpk, const float *A, const float *alpha,
                                  const xnor_shape *s, uint32_t *Opk, float *A_next, void *workspace,
                                  size_t workspace_bytes, void *stream);
+/* xnor_conv2d_fwd_chain_from_A for filters that do not change from call to call (every layer of a
+ * chained network at inference): the caller has run xnor_filter_expand (or xnor_prepare) on this
+ * same workspace, whose first xnor_conv2d_workspace_bytes bytes therefore hold the expanded filters
+ * and are only read here; the rest (up to xnor_conv2d_chain_workspace_bytes) is the scratch for the
+ * per-filter-tile sums.  Same results bit for bit, one launch less per layer. */
+int xnor_conv2d_fwd_chain_expanded_from_A(const uint32_t *Ipk, const float *A, const float *alpha,
+                                          const xnor_shape *s, uint32_t *Opk, float *A_next, void *workspace,
+                                          size_t workspace_bytes, void *stream);
 
 /*
  * Second half of Eq. 10 on its own: K = box filter of a given A (taps 1/(kh*kw), zero outside the

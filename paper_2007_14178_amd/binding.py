@@ -93,6 +93,7 @@ def _load() -> ctypes.CDLL:
     L.xnor_conv2d_chain_workspace_bytes.argtypes = [sp, ctypes.POINTER(sz)]
     L.xnor_conv2d_fwd_chain.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, vp]
     L.xnor_conv2d_fwd_chain_from_A.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, vp]
+    L.xnor_conv2d_fwd_chain_expanded_from_A.argtypes = [vp, vp, vp, sp, vp, vp, vp, sz, vp]
     L.xnor_forward_image_supported.argtypes = [sp]
     L.xnor_forward_image.argtypes = [vp, vp, vp, sp, vp, vp, vp]
     L.xnor_bwn_conv2d_fwd.argtypes = [vp, vp, vp, sp, vp, vp]
@@ -106,7 +107,8 @@ def _load() -> ctypes.CDLL:
                  "xnor_conv2d_chain_workspace_bytes", "xnor_conv2d_fwd_chain",
                  "xnor_forward_image_supported", "xnor_forward_image",
                  "xnor_bwn_conv2d_fwd", "xnor_bwn_conv2d_fwd_algo",
-                 "xnor_conv2d_fwd_expanded_from_A", "xnor_conv2d_fwd_chain_from_A", "xnor_prepare"):
+                 "xnor_conv2d_fwd_expanded_from_A", "xnor_conv2d_fwd_chain_from_A",
+                 "xnor_conv2d_fwd_chain_expanded_from_A", "xnor_prepare"):
         getattr(L, name).restype = ci
     return L
 
@@ -429,4 +431,24 @@ def xnor_conv2d_fwd_chain_from_A(Ipk: torch.Tensor, Wpk: torch.Tensor, A: torch.
         _dev(A, torch.float32, (s.N, s.H, s.W), "A"), _dev(alpha, torch.float32, (s.F,), "alpha"), ctypes.byref(s.c()),
         _dev(Opk, torch.int32, (s.N, OH, OW, Cwn), "Opk"), _dev(A_next, torch.float32, (s.N, OH, OW), "A_next"),
         _dev(workspace, torch.uint8, name="workspace"), workspace.numel(), _stream()), "xnor_conv2d_fwd_chain_from_A")
+    return Opk, A_next
+
+
+def xnor_conv2d_fwd_chain_expanded_from_A(Ipk: torch.Tensor, A: torch.Tensor, alpha: torch.Tensor, s: Shape,
+                                          workspace: torch.Tensor, Opk: torch.Tensor | None = None,
+                                          A_next: torch.Tensor | None = None):
+    """xnor_conv2d_fwd_chain_from_A with the filters already expanded at the start of `workspace`
+    (xnor_filter_expand / xnor_prepare on a buffer of xnor_conv2d_chain_workspace_bytes bytes)."""
+    OH, OW = xnor_out_dim(s)
+    Cwn = (s.F + 31) // 32
+    if Opk is None:
+        Opk = torch.empty((s.N, OH, OW, Cwn), dtype=torch.int32, device=Ipk.device)
+    if A_next is None:
+        A_next = torch.empty((s.N, OH, OW), dtype=torch.float32, device=Ipk.device)
+    _ok(lib.xnor_conv2d_fwd_chain_expanded_from_A(
+        _dev(Ipk, torch.int32, (s.N, s.H, s.W, s.Cw), "Ipk"), _dev(A, torch.float32, (s.N, s.H, s.W), "A"),
+        _dev(alpha, torch.float32, (s.F,), "alpha"), ctypes.byref(s.c()),
+        _dev(Opk, torch.int32, (s.N, OH, OW, Cwn), "Opk"), _dev(A_next, torch.float32, (s.N, OH, OW), "A_next"),
+        _dev(workspace, torch.uint8, name="workspace"), workspace.numel(), _stream()),
+        "xnor_conv2d_fwd_chain_expanded_from_A")
     return Opk, A_next

@@ -910,7 +910,8 @@ hipError_t launch_conv_mfma_chain(const uint32_t *Ipk, const uint32_t *Wpk, cons
     const MfmaPlan pl = make_plan(g, nullptr);
     if (!pl.ok) return hipErrorInvalidValue;
     float *P = reinterpret_cast<float *>(static_cast<char *>(workspace) + pl.ws_bytes);
-    hipError_t e = launch_expand_filters(Wpk, g, workspace, st);
+    // (no Wpk: the caller has left the expanded filters at the start of the workspace)
+    hipError_t e = Wpk ? launch_expand_filters(Wpk, g, workspace, st) : hipSuccess;
     if (e != hipSuccess) return e;
     e = launch_mfma(Ipk, K, A, alpha, g, nullptr, nullptr, Opk, P, workspace, st);   // K or A, the other null
     if (e != hipSuccess) return e;

@@ -312,15 +312,16 @@ int xnor_conv2d_chain_workspace_bytes(const xnor_shape *s, size_t *bytes)
     return XNOR_OK;
 }
 
+// (Wpk null: the expanded form, whose filters are already in the workspace)
 static int conv_chain(const uint32_t *Ipk, const uint32_t *Wpk, const float *K, const float *A, const float *alpha,
                           const xnor_shape *s, uint32_t *Opk, float *A_next, void *workspace,
                           size_t workspace_bytes, void *stream)
 {
-    if (!Ipk || !Wpk || (!K && !A) || !alpha || !s || !Opk || !A_next || !workspace) return XNOR_E_NULL;
+    if (!Ipk || (!K && !A) || !alpha || !s || !Opk || !A_next || !workspace) return XNOR_E_NULL;
     xnor::Geom g;
     const int rc = make_geom(s, &g);
     if (rc) return rc;
-    if (!aligned(Ipk, 4) || !aligned(Wpk, 4) || (K && !aligned(K, 4)) || (A && !aligned(A, 4)) || !aligned(alpha, 4) || !aligned(Opk, 4) ||
+    if (!aligned(Ipk, 4) || (Wpk && !aligned(Wpk, 4)) || (K && !aligned(K, 4)) || (A && !aligned(A, 4)) || !aligned(alpha, 4) || !aligned(Opk, 4) ||
         !aligned(A_next, 4) || !aligned(workspace, 16))
         return XNOR_E_ALIGN;
     const size_t need = xnor::conv_mfma_chain_workspace_bytes(g);
@@ -334,7 +335,7 @@ int xnor_conv2d_fwd_chain(const uint32_t *Ipk, const uint32_t *Wpk, const float 
                           const xnor_shape *s, uint32_t *Opk, float *A_next, void *workspace,
                           size_t workspace_bytes, void *stream)
 {
-    if (!K) return XNOR_E_NULL;
+    if (!K || !Wpk) return XNOR_E_NULL;
     return conv_chain(Ipk, Wpk, K, nullptr, alpha, s, Opk, A_next, workspace, workspace_bytes, stream);
 }
 
@@ -342,8 +343,16 @@ int xnor_conv2d_fwd_chain_from_A(const uint32_t *Ipk, const uint32_t *Wpk, const
                                  const xnor_shape *s, uint32_t *Opk, float *A_next, void *workspace,
                                  size_t workspace_bytes, void *stream)
 {
-    if (!A) return XNOR_E_NULL;
+    if (!A || !Wpk) return XNOR_E_NULL;
     return conv_chain(Ipk, Wpk, nullptr, A, alpha, s, Opk, A_next, workspace, workspace_bytes, stream);
+}
+
+int xnor_conv2d_fwd_chain_expanded_from_A(const uint32_t *Ipk, const float *A, const float *alpha,
+                                          const xnor_shape *s, uint32_t *Opk, float *A_next, void *workspace,
+                                          size_t workspace_bytes, void *stream)
+{
+    if (!A) return XNOR_E_NULL;
+    return conv_chain(Ipk, nullptr, nullptr, A, alpha, s, Opk, A_next, workspace, workspace_bytes, stream);
 }
 
 int xnor_filter_expand(const uint32_t *Wpk, const xnor_shape *s, void *workspace,

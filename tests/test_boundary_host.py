@@ -115,6 +115,11 @@ def test_null_and_alignment_rejected(xb):
     assert L.xnor_conv2d_fwd_chain(ok, ok, ok, ok, sp, odd, ok, ok, cneed, None) == xb.E_ALIGN
     assert L.xnor_conv2d_fwd_chain_from_A(ok, ok, None, ok, sp, ok, ok, ok, cneed, None) == xb.E_NULL
     assert L.xnor_conv2d_fwd_chain_from_A(ok, ok, odd, ok, sp, ok, ok, ok, cneed, None) == xb.E_ALIGN
+    assert L.xnor_conv2d_fwd_chain_from_A(ok, None, ok, ok, sp, ok, ok, ok, cneed, None) == xb.E_NULL
+    assert L.xnor_conv2d_fwd_chain_expanded_from_A(ok, None, ok, sp, ok, ok, ok, cneed, None) == xb.E_NULL
+    assert L.xnor_conv2d_fwd_chain_expanded_from_A(ok, ok, ok, sp, ok, ok, None, cneed, None) == xb.E_NULL
+    assert L.xnor_conv2d_fwd_chain_expanded_from_A(ok, ok, ok, sp, ok, ok, ok, cneed - 1, None) == xb.E_WORKSPACE
+    assert L.xnor_conv2d_fwd_chain_expanded_from_A(ok, odd, ok, sp, ok, ok, ok, cneed, None) == xb.E_ALIGN
     assert L.xnor_conv2d_fwd_expanded_from_A(ok, ok, need, None, ok, sp, ok, None, None) == xb.E_NULL
     assert L.xnor_conv2d_fwd_expanded_from_A(ok, ok, need - 1, ok, ok, sp, ok, None, None) == xb.E_WORKSPACE
     assert L.xnor_box_filter_K(None, sp, ok, None) == xb.E_NULL

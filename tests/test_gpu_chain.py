@@ -60,8 +60,15 @@ def test_chain_outputs_vs_oracle(xb, shape):
     Opk, A_next = xb.xnor_conv2d_fwd_chain(Ipk, Wpk, K, alpha, s)
     # the form that takes the channel mean and forms K itself gives the same bits
     Opk2, A_next2 = xb.xnor_conv2d_fwd_chain_from_A(Ipk, Wpk, A, alpha, s)
+    # ... and so does the form whose filters were expanded beforehand, into the chain workspace
+    cws = torch.empty((xb.xnor_conv2d_chain_workspace_bytes(s),), dtype=torch.uint8, device="cuda")
+    xb.xnor_filter_expand(Wpk, s, cws)
+    Opk3, A_next3 = xb.xnor_conv2d_fwd_chain_expanded_from_A(Ipk, A, alpha, s, cws)
+    Opk4, A_next4 = xb.xnor_conv2d_fwd_chain_expanded_from_A(Ipk, A, alpha, s, cws)   # (the filters are only read)
     torch.cuda.synchronize()
     assert torch.equal(Opk, Opk2) and torch.equal(A_next, A_next2)
+    assert torch.equal(Opk, Opk3) and torch.equal(A_next, A_next3)
+    assert torch.equal(Opk, Opk4) and torch.equal(A_next, A_next4)
     d_ref, K_ref, a_ref, O_ref = oracle.forward(I, Wt, osh)
     assert np.array_equal(Opk.cpu().numpy().view(np.uint32), oracle.pack(O_ref)), "packed signs of the output"
     A_ref = oracle.channel_mean_abs(O_ref)
