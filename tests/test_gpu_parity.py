@@ -361,7 +361,9 @@ def test_conv_that_forms_K_itself(xb, shape):
 
 @pytest.mark.parametrize("shape", [(90, 256, 28, 28, 70, 3, 3, 1, 1, 1, 1),      # one launch for both sides
                                    (84, 288, 28, 28, 33, 5, 5, 1, 1, 2, 2),      # the same, ragged blocks, channel words 9
-                                   (2, 64, 13, 13, 40, 3, 3, 1, 1, 1, 1)],       # falls back to two launches
+                                   (2, 64, 13, 13, 40, 3, 3, 1, 1, 1, 1),        # one launch, one-pixel input pass (H*W odd)
+                                   (3, 96, 27, 27, 130, 5, 5, 1, 1, 2, 2),       # the same, three channel words, partial filter tile
+                                   (2, 16, 20, 20, 5, 9, 9, 1, 1, 4, 4)],        # more taps than a one-slice block has threads: separate launches
                          ids=lambda s: "x".join(map(str, s)))
 def test_prepare_both_sides_in_one_call(xb, shape):
     """xnor_prepare gives bit for bit what xnor_input_prepare and xnor_filter_prepare give."""
