@@ -1,14 +1,15 @@
 // XNOR convolution on the matrix cores (Sec. III-A steps 1b-1d and 3, Eq. 11).
 //
 // The sign dot product of Eq. 11 is a dense contraction over (tap, channel), so it maps onto MFMA.
-// CDNA4's block-scaled MFMA takes FP4 (E2M1) operands at twice the FP8/int8 rate; +1, -1 and 0 are
+// CDNA4's f8f6f4 MFMA takes FP4 (E2M1) operands at twice the FP8/int8 rate; +1, -1 and 0 are
 // exact in FP4 (codes 0x2, 0xA, 0x0) and the fp32 accumulator holds every partial sum (an integer
 // below 2^24) exactly, so the result equals N_valid - 2*popcount(Ipk xor Wpk) bit for bit.
 //   * bit 1 -> +1.0, bit 0 -> -1.0 (step 1c: a 0 bit stands for -1)
 //   * out-of-image taps, channels >= C and filters >= F are FP4 zeros: they add nothing, which is
 //     the zero padding of the +-1 tensor -- no border correction is needed
 //
-// v_mfma_scale_f32_32x32x64_f8f6f4, D[32x32] += A[32x64] * B[64x32], FP4 operands (4 VGPRs each):
+// v_mfma_f32_32x32x64_f8f6f4 (the form without block scales: no scale operands to read),
+// D[32x32] += A[32x64] * B[64x32], FP4 operands (cbsz:4 blgp:4, 4 VGPRs each):
 //   A: lane l holds row l%32, k = 32*(l/32) .. +31      -> one packed channel word of one filter
 //   B: lane l holds col l%32, k = 32*(l/32) .. +31      -> one packed channel word of one pixel
 //   D: lane l, register r holds row 8*(r/4) + 4*(l/32) + r%4, col l%32
@@ -41,7 +42,6 @@ constexpr int kWN = 4;            // 32-pixel tiles per wave (at most)
 constexpr int kBandPixels = 2 * 32 * kWN;   // 2 wave columns
 constexpr int kFilterTile = 2 * 32 * kWM;   // 2 wave rows
 constexpr int kRing = 4;          // register ring of filter operands: loads run kRing-1 steps ahead
-constexpr int kScaleOne = 0x7f7f7f7f;       // E8M0 exponent 127 = 2^0
 constexpr int kXcdShift = 3, kXcds = 1 << kXcdShift;   // MI355X: 8 XCDs of 32 CUs
 
 // q = n / d for n*d < 2^32 via one mul_hi.
@@ -409,11 +409,10 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
     constexpr int D = kRing;
     static_assert(D == 4, "the wait counts below are written for a ring of four");
     const int taps = p.kh * p.kw;
-    const int scale = kScaleOne;
 
 #define XNOR_MFMA(ACC, A, B)                                                                         \
-    asm volatile("v_mfma_scale_f32_32x32x64_f8f6f4 %0, %1, %2, %0, %3, %3 op_sel_hi:[0,0,0] cbsz:4 blgp:4" \
-                 : "+v"(ACC) : "v"(A), "v"(B), "v"(scale))
+    asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, %0 cbsz:4 blgp:4" \
+                 : "+v"(ACC) : "v"(A), "v"(B))
 #define XNOR_LDS128(DST, ADDR) asm volatile("ds_read_b128 %0, %1" : "=v"(DST) : "v"(ADDR))
 #define XNOR_LDS32(DST, ADDR, OFF) asm volatile("ds_read_b32 %0, %1 offset:" #OFF : "=v"(DST) : "v"(ADDR))
 #define XNOR_GLD(DST, VOFF, SBASE, OFF) \
