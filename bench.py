@@ -68,7 +68,7 @@ def parse():
                     help="skip the HIP-graph replay of the step (its time is reported beside the eager one)")
     ap.add_argument("--conv-events-every", type=int, default=1,
                     help="bracket the convolution launch with events on every n-th timed step only (0: never)")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--cpu-seconds", type=float, default=20.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
 
 
