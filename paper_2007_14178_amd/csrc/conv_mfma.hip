@@ -24,32 +24,16 @@
 // B operand for tap (ky,kx) then sits at its pixel's slot + (ky*Wp+kx) slots: no per-tap bounds
 // logic.  Filter words are expanded once per call into a workspace laid out in A-operand order
 // and stream from L2 straight into registers.
+#include <stdlib.h>
+
 #include <algorithm>
 #include <atomic>
 #include <type_traits>
 
-#include "fp4_expand.hpp"
-#include "xnor_internal.hpp"
+#include "conv_mfma_common.hpp"
 
 namespace xnor {
 namespace {
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef float v16f __attribute__((ext_vector_type(16)));
-
-constexpr int kWM = 2;            // 32-filter tiles per wave
-constexpr int kWN = 4;            // 32-pixel tiles per wave (at most)
-constexpr int kBandPixels = 2 * 32 * kWN;   // 2 wave columns
-constexpr int kFilterTile = 2 * 32 * kWM;   // 2 wave rows
-constexpr int kRing = 4;          // register ring of filter operands: loads run kRing-1 steps ahead
-constexpr int kXcdShift = 3, kXcds = 1 << kXcdShift;   // MI355X: 8 XCDs of 32 CUs
-
-// q = n / d for n*d < 2^32 via one mul_hi.
-struct FastDiv {
-    uint32_t mul, d;
-};
-FastDiv make_fastdiv(uint32_t d) { return FastDiv{d == 1 ? 0u : (uint32_t)(((1ull << 32) + d - 1) / d), d}; }
-__device__ inline uint32_t fdiv(uint32_t n, FastDiv f) { return f.d == 1 ? n : __umulhi(n, f.mul); }
 
 struct MfmaParams {
     const uint32_t *Ipk;
@@ -111,15 +95,6 @@ __global__ __launch_bounds__(256) void expand_filters_kernel(const uint32_t *__r
                            [&](int tap, int w) { return Wpk[((long long)f * taps + tap) * Cw + w]; });
     Wx[i] = e;
 }
-
-template <int VW>
-struct WordVec;
-template <>
-struct WordVec<1> { typedef uint32_t type; };
-template <>
-struct WordVec<2> { typedef uint32_t type __attribute__((ext_vector_type(2))); };
-template <>
-struct WordVec<4> { typedef uint32_t type __attribute__((ext_vector_type(4))); };
 
 // The kernel.  Per workgroup: the band's input words are expanded to FP4 into LDS one channel
 // chunk at a time, double-buffered: while the MFMA loop runs on chunk c, the words of chunk c+1
@@ -691,10 +666,6 @@ struct MfmaPlan {
     int f_tiles;   // workgroup rows of kFilterTile filters
 };
 
-constexpr size_t kKAlphaBytes = (kBandPixels + kFilterTile) * sizeof(float);
-constexpr size_t kLdsTwoPerCU = 80 * 1024;
-constexpr size_t kLdsMax = 160 * 1024;
-
 MfmaPlan make_plan(const Geom &g, const void *Ipk)
 {
     MfmaPlan pl{};
@@ -772,13 +743,24 @@ MfmaPlan make_plan(const Geom &g, const void *Ipk)
 
 }  // namespace
 
+// Which of the two kernels runs a layer (and so which workspace layout its filters take).
+static bool use_persistent(const Geom &g)
+{
+    static const bool enabled = [] {
+        const char *e = getenv("XNOR_MFMA_PERSISTENT");
+        return !e || e[0] != '0';
+    }();
+    return enabled && conv_mfma_persistent_supports(g);
+}
+
 bool conv_mfma_supports(const Geom &g)
 {
-    return make_plan(g, nullptr).ok;
+    return use_persistent(g) || make_plan(g, nullptr).ok;
 }
 
 ExpandLayout conv_mfma_expand_layout(const Geom &g)
 {
+    if (use_persistent(g)) return conv_mfma_persistent_expand_layout(g);
     const MfmaPlan pl = make_plan(g, nullptr);   // the workspace layout does not depend on alignment
     ExpandLayout L{};
     L.ok = pl.ok ? 1 : 0;
@@ -789,18 +771,18 @@ ExpandLayout conv_mfma_expand_layout(const Geom &g)
 
 size_t conv_mfma_workspace_bytes(const Geom &g)
 {
-    const MfmaPlan pl = make_plan(g, nullptr);
-    return pl.ok ? pl.ws_bytes : 0;
+    const ExpandLayout L = conv_mfma_expand_layout(g);
+    return L.ok ? L.ws_bytes : 0;
 }
 
 hipError_t launch_expand_filters(const uint32_t *Wpk, const Geom &g, void *workspace, hipStream_t st)
 {
-    const MfmaPlan pl = make_plan(g, nullptr);   // the workspace layout does not depend on alignment
-    if (!pl.ok) return hipErrorInvalidValue;
-    const long long wx_items = (long long)(pl.ws_bytes / sizeof(uint4));
+    const ExpandLayout L = conv_mfma_expand_layout(g);
+    if (!L.ok) return hipErrorInvalidValue;
+    const long long wx_items = (long long)(L.ws_bytes / sizeof(uint4));
     expand_filters_kernel<<<ceil_div(wx_items, 256), 256, 0, st>>>(
-        Wpk, static_cast<uint4 *>(workspace), g.F, g.C, g.Cw, g.kh * g.kw, pl.CH, pl.nchunks, pl.chunk_pad,
-        pl.tile_steps, 2 * pl.S2, wx_items);
+        Wpk, static_cast<uint4 *>(workspace), g.F, g.C, g.Cw, g.kh * g.kw, L.CH, L.nchunks, L.chunk_pad,
+        L.tile_steps, L.Cw2, wx_items);
     return hipGetLastError();
 }
 
@@ -808,6 +790,7 @@ static hipError_t launch_mfma(const uint32_t *Ipk, const float *K, const float *
                               const Geom &g, float *out, int32_t *dot, uint32_t *Opk, float *P,
                               const void *workspace, hipStream_t st)
 {
+    if (use_persistent(g)) return launch_conv_mfma_persistent(Ipk, K, A, alpha, g, out, dot, Opk, P, workspace, st);
     const MfmaPlan pl = make_plan(g, Ipk);
     if (!pl.ok) return hipErrorInvalidValue;
     const uint4 *Wx = static_cast<const uint4 *>(workspace);
@@ -884,7 +867,8 @@ hipError_t launch_conv_mfma_expanded_from_A(const uint32_t *Ipk, const float *A,
     return launch_mfma(Ipk, nullptr, A, alpha, g, out, dot, nullptr, nullptr, workspace, st);
 }
 
-// Eq. 10's channel mean for the next layer from the per-filter-tile sums: A[pix] = sum_t P[pix][t] / F
+// Eq. 10's channel mean for the next layer from the partial sums over groups of filters:
+// A[pix] = sum_t P[pix][t] / F
 __global__ __launch_bounds__(256) void chain_mean_kernel(const float *__restrict__ P, long long npix,
                                                          int f_tiles, int F, float *__restrict__ A)
 {
@@ -895,27 +879,33 @@ __global__ __launch_bounds__(256) void chain_mean_kernel(const float *__restrict
     A[i] = (float)(sum / (double)F);
 }
 
+// partial sums of |out| per pixel that the chained epilogue leaves for chain_mean_kernel
+static int chain_sum_parts(const Geom &g)
+{
+    return use_persistent(g) ? conv_mfma_persistent_sum_parts(g) : ceil_div(g.F, kFilterTile);
+}
+
 size_t conv_mfma_chain_workspace_bytes(const Geom &g)
 {
-    const MfmaPlan pl = make_plan(g, nullptr);
-    if (!pl.ok) return 0;
-    return pl.ws_bytes + (size_t)g.N * g.OH * g.OW * pl.f_tiles * sizeof(float);
+    const size_t ws = conv_mfma_workspace_bytes(g);
+    if (ws == 0) return 0;
+    return ws + (size_t)g.N * g.OH * g.OW * chain_sum_parts(g) * sizeof(float);
 }
 
 hipError_t launch_conv_mfma_chain(const uint32_t *Ipk, const uint32_t *Wpk, const float *K, const float *A,
                                   const float *alpha, const Geom &g, uint32_t *Opk, float *A_next,
                                   void *workspace, hipStream_t st)
 {
-    const MfmaPlan pl = make_plan(g, nullptr);
-    if (!pl.ok) return hipErrorInvalidValue;
-    float *P = reinterpret_cast<float *>(static_cast<char *>(workspace) + pl.ws_bytes);
+    const size_t ws = conv_mfma_workspace_bytes(g);
+    if (ws == 0) return hipErrorInvalidValue;
+    float *P = reinterpret_cast<float *>(static_cast<char *>(workspace) + ws);
     // (no Wpk: the caller has left the expanded filters at the start of the workspace)
     hipError_t e = Wpk ? launch_expand_filters(Wpk, g, workspace, st) : hipSuccess;
     if (e != hipSuccess) return e;
     e = launch_mfma(Ipk, K, A, alpha, g, nullptr, nullptr, Opk, P, workspace, st);   // K or A, the other null
     if (e != hipSuccess) return e;
     const long long npix = (long long)g.N * g.OH * g.OW;
-    chain_mean_kernel<<<ceil_div(npix, 256), 256, 0, st>>>(P, npix, pl.f_tiles, g.F, A_next);
+    chain_mean_kernel<<<ceil_div(npix, 256), 256, 0, st>>>(P, npix, chain_sum_parts(g), g.F, A_next);
     return hipGetLastError();
 }
 
