@@ -64,6 +64,9 @@ def parse():
                     help="the paper's own workload (Tables I-III): one channel, one 3x3 filter, zero padding, "
                          "square images of 256, 512, 1024 and 2048 pixels; one JSON line per size, latency in ms")
     ap.add_argument("--image-sides", default="256,512,1024,2048")
+    ap.add_argument("--k-in-conv", action="store_true",
+                    help="form K inside the convolution kernel from the channel mean (one launch less, a slower "
+                         "convolution) instead of with the box-filter launch of the prepare call")
     ap.add_argument("--no-graph", action="store_true",
                     help="skip the HIP-graph replay of the step (its time is reported beside the eager one)")
     ap.add_argument("--conv-events-every", type=int, default=1,
@@ -117,6 +120,7 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
     # with the matrix-core kernel the convolution is two calls, so that the timed "conv" stage is
     # that one kernel launch (what the roofline figures are about)
     two_phase = used_algo == xb.ALGO_MFMA and not args.chain
+    k_in_conv = two_phase and args.k_in_conv and not args.unfused
     if args.chain:
         xb.xnor_input_prepare(dI, s, Ipk, A, K)
         xb.xnor_filter_prepare(dW, Wpk, M, alpha)
@@ -166,16 +170,16 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
             # as the box-filter kernel, bit-identical output): one launch less per step
             if one_prepare:
                 # (with the matrix-core kernel the call also leaves the filters expanded in `ws`)
-                mark(); xb.xnor_prepare(dI, dW, s, Ipk, A, K, Wpk, M, alpha, want_K=not two_phase,
+                mark(); xb.xnor_prepare(dI, dW, s, Ipk, A, K, Wpk, M, alpha, want_K=not k_in_conv,
                                         workspace=ws if two_phase else None)
             else:
-                mark(); xb.xnor_input_prepare(dI, s, Ipk, A, K, want_K=not two_phase)
+                mark(); xb.xnor_input_prepare(dI, s, Ipk, A, K, want_K=not k_in_conv)
                 mark(); xb.xnor_filter_prepare(dW, Wpk, M, alpha)
         if two_phase:
             # per-model work ends with the filters in the matrix-core kernel's operand order
             if not one_prepare:
                 mark(); xb.xnor_filter_expand(Wpk, s, ws)
-            if args.unfused:
+            if not k_in_conv:
                 mark(); xb.xnor_conv2d_fwd_expanded(Ipk, ws, K, alpha, s, out=out)
             else:
                 mark(); xb.xnor_conv2d_fwd_expanded_from_A(Ipk, ws, A, alpha, s, out=out)
@@ -262,7 +266,7 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
     # plain 1 GiB copy): measured offline, see profiles/forward_c5_hbm_traffic_pmc.md; other
     # workloads / kernels have no counter run yet
     roof["traffic"] = MEASURED_CONV_TRAFFIC_BYTES.get((layer.name, xb.ALGO_NAMES[used_algo]))
-    roof["kernel"] = ("conv_mfma_kernel (xnor_conv2d_fwd_expanded" + ("" if args.unfused else "_from_A") + ")") if two_phase else f"xnor_conv2d_fwd[{xb.ALGO_NAMES[used_algo]}]"
+    roof["kernel"] = ("matrix-core convolution kernel (xnor_conv2d_fwd_expanded" + ("_from_A" if k_in_conv else "") + ")") if two_phase else f"xnor_conv2d_fwd[{xb.ALGO_NAMES[used_algo]}]"
     roof["kernel_ms"] = conv_ms                                # mean over the timed steps (what `achieved` uses)
     roof["kernel_ms_median"] = conv_times[len(conv_times) // 2]
     roof["kernel_ms_min"] = conv_times[0]

@@ -65,7 +65,10 @@ typedef enum {
     XNOR_ALGO_AUTO = 0,     /* pick per shape (what xnor_conv2d_fwd does)                         */
     XNOR_ALGO_DIRECT = 1,   /* one thread per output, v_xor + v_bcnt, any shape                   */
     XNOR_ALGO_TILED = 2,    /* LDS-staged packed halo, wave-uniform filter words, register tile   */
-    XNOR_ALGO_MFMA = 3      /* +-1 expanded to FP4 in LDS, v_mfma_scale_f32_32x32x64_f8f6f4       */
+    XNOR_ALGO_MFMA = 3,     /* +-1 expanded to FP4 in LDS, v_mfma_f32_32x32x64_f8f6f4: persistent
+                               workgroups where the shape allows, else as XNOR_ALGO_MFMA_BANDS    */
+    XNOR_ALGO_MFMA_BANDS = 4 /* the same arithmetic with one workgroup per band of output rows
+                               (xnor_conv2d_fwd_algo only; tests and measurements)                */
 } xnor_algo;
 
 /* Host helpers (no GPU work). */

@@ -24,8 +24,6 @@
 // B operand for tap (ky,kx) then sits at its pixel's slot + (ky*Wp+kx) slots: no per-tap bounds
 // logic.  Filter words are expanded once per call into a workspace laid out in A-operand order
 // and stream from L2 straight into registers.
-#include <stdlib.h>
-
 #include <algorithm>
 #include <atomic>
 #include <type_traits>
@@ -743,14 +741,11 @@ MfmaPlan make_plan(const Geom &g, const void *Ipk)
 
 }  // namespace
 
-// Which of the two kernels runs a layer (and so which workspace layout its filters take).
+// Which of the two kernels runs a layer (and so which workspace layout its filters take): the
+// persistent one where it takes the shape, this file's one-workgroup-per-band kernel otherwise.
 static bool use_persistent(const Geom &g)
 {
-    static const bool enabled = [] {
-        const char *e = getenv("XNOR_MFMA_PERSISTENT");
-        return !e || e[0] != '0';
-    }();
-    return enabled && conv_mfma_persistent_supports(g);
+    return conv_mfma_persistent_supports(g);
 }
 
 bool conv_mfma_supports(const Geom &g)
@@ -769,15 +764,33 @@ ExpandLayout conv_mfma_expand_layout(const Geom &g)
     return L;
 }
 
+static ExpandLayout bands_expand_layout(const Geom &g)
+{
+    const MfmaPlan pl = make_plan(g, nullptr);
+    ExpandLayout L{};
+    L.ok = pl.ok ? 1 : 0;
+    L.CH = pl.CH; L.nchunks = pl.nchunks; L.chunk_pad = pl.chunk_pad; L.tile_steps = pl.tile_steps;
+    L.Cw2 = 2 * pl.S2; L.ws_bytes = pl.ws_bytes;
+    return L;
+}
+
+bool conv_mfma_bands_supports(const Geom &g)
+{
+    return make_plan(g, nullptr).ok;
+}
+
+// (enough for either kernel, so that a caller's one workspace serves whatever variant it asks for)
 size_t conv_mfma_workspace_bytes(const Geom &g)
 {
     const ExpandLayout L = conv_mfma_expand_layout(g);
-    return L.ok ? L.ws_bytes : 0;
+    if (!L.ok) return 0;
+    const ExpandLayout Lb = bands_expand_layout(g);
+    return std::max(L.ws_bytes, Lb.ok ? Lb.ws_bytes : (size_t)0);
 }
 
-hipError_t launch_expand_filters(const uint32_t *Wpk, const Geom &g, void *workspace, hipStream_t st)
+static hipError_t launch_expand_with(const ExpandLayout &L, const uint32_t *Wpk, const Geom &g, void *workspace,
+                                     hipStream_t st)
 {
-    const ExpandLayout L = conv_mfma_expand_layout(g);
     if (!L.ok) return hipErrorInvalidValue;
     const long long wx_items = (long long)(L.ws_bytes / sizeof(uint4));
     expand_filters_kernel<<<ceil_div(wx_items, 256), 256, 0, st>>>(
@@ -786,11 +799,17 @@ hipError_t launch_expand_filters(const uint32_t *Wpk, const Geom &g, void *works
     return hipGetLastError();
 }
 
+hipError_t launch_expand_filters(const uint32_t *Wpk, const Geom &g, void *workspace, hipStream_t st)
+{
+    return launch_expand_with(conv_mfma_expand_layout(g), Wpk, g, workspace, st);
+}
+
 static hipError_t launch_mfma(const uint32_t *Ipk, const float *K, const float *A, const float *alpha,
                               const Geom &g, float *out, int32_t *dot, uint32_t *Opk, float *P,
-                              const void *workspace, hipStream_t st)
+                              const void *workspace, hipStream_t st, bool bands_kernel = false)
 {
-    if (use_persistent(g)) return launch_conv_mfma_persistent(Ipk, K, A, alpha, g, out, dot, Opk, P, workspace, st);
+    if (!bands_kernel && use_persistent(g))
+        return launch_conv_mfma_persistent(Ipk, K, A, alpha, g, out, dot, Opk, P, workspace, st);
     const MfmaPlan pl = make_plan(g, Ipk);
     if (!pl.ok) return hipErrorInvalidValue;
     const uint4 *Wx = static_cast<const uint4 *>(workspace);
@@ -920,6 +939,16 @@ hipError_t launch_conv_mfma(const uint32_t *Ipk, const uint32_t *Wpk, const floa
     // filters -> FP4 in A-operand order, then the convolution
     const hipError_t e = launch_expand_filters(Wpk, g, workspace, st);
     return e != hipSuccess ? e : launch_conv_mfma_expanded(Ipk, K, alpha, g, out, dot, workspace, st);
+}
+
+hipError_t launch_conv_mfma_bands(const uint32_t *Ipk, const uint32_t *Wpk, const float *K,
+                                  const float *alpha, const Geom &g, float *out, int32_t *dot,
+                                  void *workspace, hipStream_t st)
+{
+    // the same two steps with this file's kernel and its workspace layout, whatever the shape
+    const hipError_t e = launch_expand_with(bands_expand_layout(g), Wpk, g, workspace, st);
+    return e != hipSuccess ? e
+                           : launch_mfma(Ipk, K, nullptr, alpha, g, out, dot, nullptr, nullptr, workspace, st, true);
 }
 
 }  // namespace xnor

@@ -75,12 +75,10 @@ struct PParams {
                        // work is spread over twice as many groups
     int work_per_xcd;  // whole_items + 2 * (items_per_xcd - whole_items)
     int start_turn;  // the first group lets the second one start at this turn of its first item
-    int stagger;     // shader-clock cycles by which every second workgroup of an XCD starts late
     int prio_mask;   // the second group raises its issue priority in the turns t with (t & prio_mask) != 0
 #ifdef XNOR_TS_BUILD
     unsigned long long *ts;   // (measurement build) [workgroup][group][item < 8][8] shader-clock stamps
-    int dbg;                  // (measurement build) 1: no output stores, 2: second groups idle,
-                              // 4: filter operands from one address, 8: pixel operands from one address
+    int dbg;                  // (measurement build) 1: no output stores, 2: second groups idle
 #endif
 };
 
@@ -186,9 +184,7 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
 // one step: A operands (a0, a1), pixel operands b0..b3; reads the next step's pixel operands n0..n3
 // at table entry `bo_r`, the table entry two steps ahead into `bo_w` (table offset toff), and the
 // filter operands three steps ahead into (l0, l1) at ring offset goff
-// (an item that covers only one 32-filter tile per wave, %[onetile] != 0, skips the second tile's MFMAs;
-//  the loads stay, so the counts do)
-#define PX_STEP(a0, a1, b0, b1, b2, b3, n0, n1, n2, n3, bo_w, bo_r, toff, l0, l1, goff, TAG)               \
+#define PX_STEP_HEAD(a0, a1, b0, b1, b2, b3, n0, n1, n2, n3, bo_w, bo_r, toff)                          \
     "s_waitcnt vmcnt(5) lgkmcnt(3)\n\t"                                                                 \
     PX_MFMA(acc00, a0, b0)                                                                              \
     "ds_read_b32 " bo_w ", %[tab] offset:" toff "\n\t"                                                  \
@@ -205,22 +201,23 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
     PX_MFMA(acc03, a0, b3)                                                                              \
     "ds_read_b128 " n2 ", " RTMP2 "\n\t"                                                                \
     "v_add_u32 " RTMP3 ", %[bB3], " bo_r "\n\t"                                                         \
-    "s_waitcnt vmcnt(4)\n\t"                                                                            \
-    "s_cmp_eq_u32 %[onetile], 0\n\t"                                                                       \
-    "s_cbranch_scc0 Lha" TAG "%=\n\t"                                                                             \
+    "s_waitcnt vmcnt(4)\n\t"
+#define PX_STEP(a0, a1, b0, b1, b2, b3, n0, n1, n2, n3, bo_w, bo_r, toff, l0, l1, goff)                 \
+    PX_STEP_HEAD(a0, a1, b0, b1, b2, b3, n0, n1, n2, n3, bo_w, bo_r, toff)                              \
     PX_MFMA(acc10, a1, b0)                                                                              \
     "ds_read_b128 " n3 ", " RTMP3 "\n\t"                                                                \
     PX_MFMA(acc11, a1, b1)                                                                              \
     "global_load_dwordx4 " l0 ", %[aoff], %[Ab0] offset:" goff "\n\t"                                   \
     PX_MFMA(acc12, a1, b2)                                                                              \
     "global_load_dwordx4 " l1 ", %[aoff], %[Ab1] offset:" goff "\n\t"                                   \
-    PX_MFMA(acc13, a1, b3)                                                                              \
-    "s_branch Lhb" TAG "%=\n\t"                                                                                   \
-    "Lha" TAG "%=:\n\t"                                                                                            \
+    PX_MFMA(acc13, a1, b3)
+// the step of an item that covers only one 32-filter tile per wave (a half item): without the second
+// tile's MFMAs; the loads stay, so the counts do
+#define PX_STEP_HALF(a0, a1, b0, b1, b2, b3, n0, n1, n2, n3, bo_w, bo_r, toff, l0, l1, goff)            \
+    PX_STEP_HEAD(a0, a1, b0, b1, b2, b3, n0, n1, n2, n3, bo_w, bo_r, toff)                              \
     "ds_read_b128 " n3 ", " RTMP3 "\n\t"                                                                \
     "global_load_dwordx4 " l0 ", %[aoff], %[Ab0] offset:" goff "\n\t"                                   \
-    "global_load_dwordx4 " l1 ", %[aoff], %[Ab1] offset:" goff "\n\t"                                   \
-    "Lhb" TAG "%=:\n\t"
+    "global_load_dwordx4 " l1 ", %[aoff], %[Ab1] offset:" goff "\n\t"
 
 // one lane adds 1 to the counter at LDS address ADDR (ordered behind the wave's earlier LDS operations)
 #define PX_SIGNAL(ADDR)                  \
@@ -258,8 +255,8 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
 // starts %[st] bytes behind buffer 0: the ~100 instructions sit in the gaps between the MFMAs, which
 // a wave that issues 8 MFMAs per 256 cycles otherwise leaves empty.  The LDS writes in the queue are
 // younger than the pixel-operand reads the steps' counts wait for, so the counts stay right (stricter).
-// (generated by a script that lays the instructions of PX_COMMIT's expansion into the gaps of
-// the four PX_STEPs; 99 extra instructions)
+// (generated by a script that lays the instructions of the expansion into the gaps of four steps;
+//  the second form is the turn of a half item, without the second filter tile's MFMAs)
 #define PX_TURN_COMMIT \
     "s_waitcnt vmcnt(5) lgkmcnt(3)\n\t" \
     PX_MFMA(acc00, RA00, RB00) \
@@ -286,8 +283,6 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
     "v_perm_b32 v249, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 4, v240\n\t" \
     "s_waitcnt vmcnt(4)\n\t" \
-    "s_cmp_eq_u32 %[onetile], 0\n\t" \
-    "s_cbranch_scc0 Lca0%=\n\t" \
     PX_MFMA(acc10, RA01, RB00) \
     "ds_read_b128 " RB13 ", " RTMP3 "\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
@@ -312,29 +307,6 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
     "v_lshrrev_b32 " RT ", 6, v241\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v255, 0, %[tbl], " RT "\n\t" \
-    "s_branch Lcb0%=\n\t" \
-    "Lca0%=:\n\t" \
-    "ds_read_b128 " RB13 ", " RTMP3 "\n\t" \
-    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
-    "v_perm_b32 v250, 0, %[tbl], " RT "\n\t" \
-    "v_lshrrev_b32 " RT ", 6, v240\n\t" \
-    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
-    "global_load_dwordx4 " RA30 ", %[aoff], %[Ab0] offset:0\n\t" \
-    "v_perm_b32 v251, 0, %[tbl], " RT "\n\t" \
-    "ds_write_b128 " RPV ", " REA "\n\t" \
-    "v_and_b32 " RT ", %[m03], v241\n\t" \
-    "v_perm_b32 v252, 0, %[tbl], " RT "\n\t" \
-    "global_load_dwordx4 " RA31 ", %[aoff], %[Ab1] offset:0\n\t" \
-    "v_lshrrev_b32 " RT ", 2, v241\n\t" \
-    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
-    "v_perm_b32 v253, 0, %[tbl], " RT "\n\t" \
-    "v_lshrrev_b32 " RT ", 4, v241\n\t" \
-    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
-    "v_perm_b32 v254, 0, %[tbl], " RT "\n\t" \
-    "v_lshrrev_b32 " RT ", 6, v241\n\t" \
-    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
-    "v_perm_b32 v255, 0, %[tbl], " RT "\n\t" \
-    "Lcb0%=:\n\t" \
     "s_waitcnt vmcnt(5) lgkmcnt(3)\n\t" \
     PX_MFMA(acc00, RA10, RB10) \
     "ds_read_b32 " RBOFF1 ", %[tab] offset:4\n\t" \
@@ -360,8 +332,6 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
     "v_lshrrev_b32 " RT ", 4, v242\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "s_waitcnt vmcnt(4)\n\t" \
-    "s_cmp_eq_u32 %[onetile], 0\n\t" \
-    "s_cbranch_scc0 Lca1%=\n\t" \
     PX_MFMA(acc10, RA11, RB10) \
     "ds_read_b128 " RB03 ", " RTMP3 "\n\t" \
     "v_perm_b32 v250, 0, %[tbl], " RT "\n\t" \
@@ -386,29 +356,6 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v255, 0, %[tbl], " RT "\n\t" \
     "ds_write_b128 " RPV ", " REB " offset:48\n\t" \
-    "s_branch Lcb1%=\n\t" \
-    "Lca1%=:\n\t" \
-    "ds_read_b128 " RB03 ", " RTMP3 "\n\t" \
-    "v_perm_b32 v250, 0, %[tbl], " RT "\n\t" \
-    "v_lshrrev_b32 " RT ", 6, v242\n\t" \
-    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
-    "v_perm_b32 v251, 0, %[tbl], " RT "\n\t" \
-    "global_load_dwordx4 " RA00 ", %[aoff], %[Ab0] offset:1024\n\t" \
-    "ds_write_b128 " RPV ", " REA " offset:32\n\t" \
-    "v_and_b32 " RT ", %[m03], v243\n\t" \
-    "v_perm_b32 v252, 0, %[tbl], " RT "\n\t" \
-    "v_lshrrev_b32 " RT ", 2, v243\n\t" \
-    "global_load_dwordx4 " RA01 ", %[aoff], %[Ab1] offset:1024\n\t" \
-    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
-    "v_perm_b32 v253, 0, %[tbl], " RT "\n\t" \
-    "v_lshrrev_b32 " RT ", 4, v243\n\t" \
-    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
-    "v_perm_b32 v254, 0, %[tbl], " RT "\n\t" \
-    "v_lshrrev_b32 " RT ", 6, v243\n\t" \
-    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
-    "v_perm_b32 v255, 0, %[tbl], " RT "\n\t" \
-    "ds_write_b128 " RPV ", " REB " offset:48\n\t" \
-    "Lcb1%=:\n\t" \
     "s_waitcnt vmcnt(5) lgkmcnt(3)\n\t" \
     PX_MFMA(acc00, RA20, RB00) \
     "ds_read_b32 " RBOFF0 ", %[tab] offset:8\n\t" \
@@ -434,8 +381,6 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
     "v_lshrrev_b32 " RT ", 4, v244\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "s_waitcnt vmcnt(4)\n\t" \
-    "s_cmp_eq_u32 %[onetile], 0\n\t" \
-    "s_cbranch_scc0 Lca2%=\n\t" \
     PX_MFMA(acc10, RA21, RB00) \
     "ds_read_b128 " RB13 ", " RTMP3 "\n\t" \
     "v_perm_b32 v250, 0, %[tbl], " RT "\n\t" \
@@ -460,29 +405,6 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v255, 0, %[tbl], " RT "\n\t" \
     "ds_write_b128 " RPV ", " REB " offset:16\n\t" \
-    "s_branch Lcb2%=\n\t" \
-    "Lca2%=:\n\t" \
-    "ds_read_b128 " RB13 ", " RTMP3 "\n\t" \
-    "v_perm_b32 v250, 0, %[tbl], " RT "\n\t" \
-    "v_lshrrev_b32 " RT ", 6, v244\n\t" \
-    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
-    "v_perm_b32 v251, 0, %[tbl], " RT "\n\t" \
-    "global_load_dwordx4 " RA10 ", %[aoff], %[Ab0] offset:2048\n\t" \
-    "ds_write_b128 " RPV ", " REA "\n\t" \
-    "v_and_b32 " RT ", %[m03], v245\n\t" \
-    "v_perm_b32 v252, 0, %[tbl], " RT "\n\t" \
-    "v_lshrrev_b32 " RT ", 2, v245\n\t" \
-    "global_load_dwordx4 " RA11 ", %[aoff], %[Ab1] offset:2048\n\t" \
-    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
-    "v_perm_b32 v253, 0, %[tbl], " RT "\n\t" \
-    "v_lshrrev_b32 " RT ", 4, v245\n\t" \
-    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
-    "v_perm_b32 v254, 0, %[tbl], " RT "\n\t" \
-    "v_lshrrev_b32 " RT ", 6, v245\n\t" \
-    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
-    "v_perm_b32 v255, 0, %[tbl], " RT "\n\t" \
-    "ds_write_b128 " RPV ", " REB " offset:16\n\t" \
-    "Lcb2%=:\n\t" \
     "s_waitcnt vmcnt(5) lgkmcnt(3)\n\t" \
     PX_MFMA(acc00, RA30, RB10) \
     "ds_read_b32 " RBOFF1 ", %[tab] offset:12\n\t" \
@@ -508,8 +430,6 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v250, 0, %[tbl], " RT "\n\t" \
     "s_waitcnt vmcnt(4)\n\t" \
-    "s_cmp_eq_u32 %[onetile], 0\n\t" \
-    "s_cbranch_scc0 Lca3%=\n\t" \
     PX_MFMA(acc10, RA31, RB10) \
     "ds_read_b128 " RB03 ", " RTMP3 "\n\t" \
     "v_lshrrev_b32 " RT ", 6, v246\n\t" \
@@ -532,9 +452,169 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
     "v_lshrrev_b32 " RT ", 6, v247\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v255, 0, %[tbl], " RT "\n\t" \
+    "ds_write_b128 " RPV ", " REB " offset:48\n\t"
+
+#define PX_TURN_COMMIT_HALF \
+    "s_waitcnt vmcnt(5) lgkmcnt(3)\n\t" \
+    PX_MFMA(acc00, RA00, RB00) \
+    "ds_read_b32 " RBOFF0 ", %[tab] offset:0\n\t" \
+    "v_add_u32 " RTMP0 ", %[bB0], " RBOFF1 "\n\t" \
+    "s_waitcnt vmcnt(8)\n\t" \
+    "v_add_u32 " RPV ", %[st], %[sdst0]\n\t" \
+    "s_waitcnt lgkmcnt(3)\n\t" \
+    PX_MFMA(acc01, RA00, RB01) \
+    "ds_read_b128 " RB10 ", " RTMP0 "\n\t" \
+    "v_add_u32 " RTMP1 ", %[bB1], " RBOFF1 "\n\t" \
+    "v_and_b32 " RT ", %[m03], v240\n\t" \
+    "v_perm_b32 v248, 0, %[tbl], " RT "\n\t" \
+    "s_waitcnt lgkmcnt(3)\n\t" \
+    PX_MFMA(acc02, RA00, RB02) \
+    "ds_read_b128 " RB11 ", " RTMP1 "\n\t" \
+    "v_add_u32 " RTMP2 ", %[bB2], " RBOFF1 "\n\t" \
+    "v_lshrrev_b32 " RT ", 2, v240\n\t" \
+    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
+    "s_waitcnt lgkmcnt(3)\n\t" \
+    PX_MFMA(acc03, RA00, RB03) \
+    "ds_read_b128 " RB12 ", " RTMP2 "\n\t" \
+    "v_add_u32 " RTMP3 ", %[bB3], " RBOFF1 "\n\t" \
+    "v_perm_b32 v249, 0, %[tbl], " RT "\n\t" \
+    "v_lshrrev_b32 " RT ", 4, v240\n\t" \
+    "s_waitcnt vmcnt(4)\n\t" \
+    "ds_read_b128 " RB13 ", " RTMP3 "\n\t" \
+    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
+    "v_perm_b32 v250, 0, %[tbl], " RT "\n\t" \
+    "v_lshrrev_b32 " RT ", 6, v240\n\t" \
+    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
+    "global_load_dwordx4 " RA30 ", %[aoff], %[Ab0] offset:0\n\t" \
+    "v_perm_b32 v251, 0, %[tbl], " RT "\n\t" \
+    "ds_write_b128 " RPV ", " REA "\n\t" \
+    "v_and_b32 " RT ", %[m03], v241\n\t" \
+    "v_perm_b32 v252, 0, %[tbl], " RT "\n\t" \
+    "global_load_dwordx4 " RA31 ", %[aoff], %[Ab1] offset:0\n\t" \
+    "v_lshrrev_b32 " RT ", 2, v241\n\t" \
+    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
+    "v_perm_b32 v253, 0, %[tbl], " RT "\n\t" \
+    "v_lshrrev_b32 " RT ", 4, v241\n\t" \
+    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
+    "v_perm_b32 v254, 0, %[tbl], " RT "\n\t" \
+    "v_lshrrev_b32 " RT ", 6, v241\n\t" \
+    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
+    "v_perm_b32 v255, 0, %[tbl], " RT "\n\t" \
+    "s_waitcnt vmcnt(5) lgkmcnt(3)\n\t" \
+    PX_MFMA(acc00, RA10, RB10) \
+    "ds_read_b32 " RBOFF1 ", %[tab] offset:4\n\t" \
+    "v_add_u32 " RTMP0 ", %[bB0], " RBOFF0 "\n\t" \
+    "ds_write_b128 " RPV ", " REB " offset:16\n\t" \
+    "v_and_b32 " RT ", %[m03], v242\n\t" \
+    "s_waitcnt lgkmcnt(3)\n\t" \
+    PX_MFMA(acc01, RA10, RB11) \
+    "ds_read_b128 " RB00 ", " RTMP0 "\n\t" \
+    "v_add_u32 " RTMP1 ", %[bB1], " RBOFF0 "\n\t" \
+    "v_perm_b32 v248, 0, %[tbl], " RT "\n\t" \
+    "v_lshrrev_b32 " RT ", 2, v242\n\t" \
+    "s_waitcnt lgkmcnt(3)\n\t" \
+    PX_MFMA(acc02, RA10, RB12) \
+    "ds_read_b128 " RB01 ", " RTMP1 "\n\t" \
+    "v_add_u32 " RTMP2 ", %[bB2], " RBOFF0 "\n\t" \
+    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
+    "v_perm_b32 v249, 0, %[tbl], " RT "\n\t" \
+    "s_waitcnt lgkmcnt(3)\n\t" \
+    PX_MFMA(acc03, RA10, RB13) \
+    "ds_read_b128 " RB02 ", " RTMP2 "\n\t" \
+    "v_add_u32 " RTMP3 ", %[bB3], " RBOFF0 "\n\t" \
+    "v_lshrrev_b32 " RT ", 4, v242\n\t" \
+    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
+    "s_waitcnt vmcnt(4)\n\t" \
+    "ds_read_b128 " RB03 ", " RTMP3 "\n\t" \
+    "v_perm_b32 v250, 0, %[tbl], " RT "\n\t" \
+    "v_lshrrev_b32 " RT ", 6, v242\n\t" \
+    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
+    "v_perm_b32 v251, 0, %[tbl], " RT "\n\t" \
+    "global_load_dwordx4 " RA00 ", %[aoff], %[Ab0] offset:1024\n\t" \
+    "ds_write_b128 " RPV ", " REA " offset:32\n\t" \
+    "v_and_b32 " RT ", %[m03], v243\n\t" \
+    "v_perm_b32 v252, 0, %[tbl], " RT "\n\t" \
+    "v_lshrrev_b32 " RT ", 2, v243\n\t" \
+    "global_load_dwordx4 " RA01 ", %[aoff], %[Ab1] offset:1024\n\t" \
+    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
+    "v_perm_b32 v253, 0, %[tbl], " RT "\n\t" \
+    "v_lshrrev_b32 " RT ", 4, v243\n\t" \
+    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
+    "v_perm_b32 v254, 0, %[tbl], " RT "\n\t" \
+    "v_lshrrev_b32 " RT ", 6, v243\n\t" \
+    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
+    "v_perm_b32 v255, 0, %[tbl], " RT "\n\t" \
     "ds_write_b128 " RPV ", " REB " offset:48\n\t" \
-    "s_branch Lcb3%=\n\t" \
-    "Lca3%=:\n\t" \
+    "s_waitcnt vmcnt(5) lgkmcnt(3)\n\t" \
+    PX_MFMA(acc00, RA20, RB00) \
+    "ds_read_b32 " RBOFF0 ", %[tab] offset:8\n\t" \
+    "v_add_u32 " RTMP0 ", %[bB0], " RBOFF1 "\n\t" \
+    "v_add_u32 " RPV ", %[st], %[sdst1]\n\t" \
+    "v_and_b32 " RT ", %[m03], v244\n\t" \
+    "s_waitcnt lgkmcnt(3)\n\t" \
+    PX_MFMA(acc01, RA20, RB01) \
+    "ds_read_b128 " RB10 ", " RTMP0 "\n\t" \
+    "v_add_u32 " RTMP1 ", %[bB1], " RBOFF1 "\n\t" \
+    "v_perm_b32 v248, 0, %[tbl], " RT "\n\t" \
+    "v_lshrrev_b32 " RT ", 2, v244\n\t" \
+    "s_waitcnt lgkmcnt(3)\n\t" \
+    PX_MFMA(acc02, RA20, RB02) \
+    "ds_read_b128 " RB11 ", " RTMP1 "\n\t" \
+    "v_add_u32 " RTMP2 ", %[bB2], " RBOFF1 "\n\t" \
+    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
+    "v_perm_b32 v249, 0, %[tbl], " RT "\n\t" \
+    "s_waitcnt lgkmcnt(3)\n\t" \
+    PX_MFMA(acc03, RA20, RB03) \
+    "ds_read_b128 " RB12 ", " RTMP2 "\n\t" \
+    "v_add_u32 " RTMP3 ", %[bB3], " RBOFF1 "\n\t" \
+    "v_lshrrev_b32 " RT ", 4, v244\n\t" \
+    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
+    "s_waitcnt vmcnt(4)\n\t" \
+    "ds_read_b128 " RB13 ", " RTMP3 "\n\t" \
+    "v_perm_b32 v250, 0, %[tbl], " RT "\n\t" \
+    "v_lshrrev_b32 " RT ", 6, v244\n\t" \
+    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
+    "v_perm_b32 v251, 0, %[tbl], " RT "\n\t" \
+    "global_load_dwordx4 " RA10 ", %[aoff], %[Ab0] offset:2048\n\t" \
+    "ds_write_b128 " RPV ", " REA "\n\t" \
+    "v_and_b32 " RT ", %[m03], v245\n\t" \
+    "v_perm_b32 v252, 0, %[tbl], " RT "\n\t" \
+    "v_lshrrev_b32 " RT ", 2, v245\n\t" \
+    "global_load_dwordx4 " RA11 ", %[aoff], %[Ab1] offset:2048\n\t" \
+    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
+    "v_perm_b32 v253, 0, %[tbl], " RT "\n\t" \
+    "v_lshrrev_b32 " RT ", 4, v245\n\t" \
+    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
+    "v_perm_b32 v254, 0, %[tbl], " RT "\n\t" \
+    "v_lshrrev_b32 " RT ", 6, v245\n\t" \
+    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
+    "v_perm_b32 v255, 0, %[tbl], " RT "\n\t" \
+    "ds_write_b128 " RPV ", " REB " offset:16\n\t" \
+    "s_waitcnt vmcnt(5) lgkmcnt(3)\n\t" \
+    PX_MFMA(acc00, RA30, RB10) \
+    "ds_read_b32 " RBOFF1 ", %[tab] offset:12\n\t" \
+    "v_add_u32 " RTMP0 ", %[bB0], " RBOFF0 "\n\t" \
+    "v_and_b32 " RT ", %[m03], v246\n\t" \
+    "v_perm_b32 v248, 0, %[tbl], " RT "\n\t" \
+    "s_waitcnt lgkmcnt(3)\n\t" \
+    PX_MFMA(acc01, RA30, RB11) \
+    "ds_read_b128 " RB00 ", " RTMP0 "\n\t" \
+    "v_add_u32 " RTMP1 ", %[bB1], " RBOFF0 "\n\t" \
+    "v_lshrrev_b32 " RT ", 2, v246\n\t" \
+    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
+    "s_waitcnt lgkmcnt(3)\n\t" \
+    PX_MFMA(acc02, RA30, RB12) \
+    "ds_read_b128 " RB01 ", " RTMP1 "\n\t" \
+    "v_add_u32 " RTMP2 ", %[bB2], " RBOFF0 "\n\t" \
+    "v_perm_b32 v249, 0, %[tbl], " RT "\n\t" \
+    "v_lshrrev_b32 " RT ", 4, v246\n\t" \
+    "s_waitcnt lgkmcnt(3)\n\t" \
+    PX_MFMA(acc03, RA30, RB13) \
+    "ds_read_b128 " RB02 ", " RTMP2 "\n\t" \
+    "v_add_u32 " RTMP3 ", %[bB3], " RBOFF0 "\n\t" \
+    "v_and_b32 " RT ", %[m03], " RT "\n\t" \
+    "v_perm_b32 v250, 0, %[tbl], " RT "\n\t" \
+    "s_waitcnt vmcnt(4)\n\t" \
     "ds_read_b128 " RB03 ", " RTMP3 "\n\t" \
     "v_lshrrev_b32 " RT ", 6, v246\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
@@ -553,18 +633,10 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
     "v_lshrrev_b32 " RT ", 6, v247\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v255, 0, %[tbl], " RT "\n\t" \
-    "ds_write_b128 " RPV ", " REB " offset:48\n\t" \
-    "Lcb3%=:\n\t"
+    "ds_write_b128 " RPV ", " REB " offset:48\n\t"
 
-#ifdef XNOR_TS_BUILD
-#define PX_AINC "%[ainc]"
-#define PX_TINC "%[tinc]"
-#define PX_DBG_OPERANDS , [ainc] "s"((p.dbg & 4) ? 0 : 4096), [tinc] "s"((p.dbg & 8) ? 0 : 16)
-#else
 #define PX_AINC "0x1000"
 #define PX_TINC "16"
-#define PX_DBG_OPERANDS
-#endif
 
 #define PX_LOOP_ASM                                                                                      \
     /* scalar state */                                                                                   \
@@ -624,10 +696,12 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
     "Lpl%=:\n\t"                                                                                         \
     "s_setprio 0\n\t"                                                                                    \
     "Lpd%=:\n\t"                                                                                         \
-    PX_STEP(RA00, RA01, RB00, RB01, RB02, RB03, RB10, RB11, RB12, RB13, RBOFF0, RBOFF1, "0", RA30, RA31, "0", "0")     \
-    PX_STEP(RA10, RA11, RB10, RB11, RB12, RB13, RB00, RB01, RB02, RB03, RBOFF1, RBOFF0, "4", RA00, RA01, "1024", "1")  \
-    PX_STEP(RA20, RA21, RB00, RB01, RB02, RB03, RB10, RB11, RB12, RB13, RBOFF0, RBOFF1, "8", RA10, RA11, "2048", "2")  \
-    PX_STEP(RA30, RA31, RB10, RB11, RB12, RB13, RB00, RB01, RB02, RB03, RBOFF1, RBOFF0, "12", RA20, RA21, "3072", "3") \
+    "s_cmp_eq_u32 %[onetile], 0\n\t"                                                                     \
+    "s_cbranch_scc0 LturnH%=\n\t"                                                                        \
+    PX_STEP(RA00, RA01, RB00, RB01, RB02, RB03, RB10, RB11, RB12, RB13, RBOFF0, RBOFF1, "0", RA30, RA31, "0")     \
+    PX_STEP(RA10, RA11, RB10, RB11, RB12, RB13, RB00, RB01, RB02, RB03, RBOFF1, RBOFF0, "4", RA00, RA01, "1024")  \
+    PX_STEP(RA20, RA21, RB00, RB01, RB02, RB03, RB10, RB11, RB12, RB13, RBOFF0, RBOFF1, "8", RA10, RA11, "2048")  \
+    PX_STEP(RA30, RA31, RB10, RB11, RB12, RB13, RB00, RB01, RB02, RB03, RBOFF1, RBOFF0, "12", RA20, RA21, "3072") \
     "Ltail%=:\n\t"                                                                                       \
     "v_add_u32 %[aoff], " PX_AINC ", %[aoff]\n\t"                                                        \
     "v_add_u32 %[tab], " PX_TINC ", %[tab]\n\t"                                                          \
@@ -641,6 +715,13 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
     "s_nop 15\n\t"                                                                                       \
     "s_nop 15\n\t"                                                                                       \
     "s_branch Lend%=\n\t"                                                                                \
+    /* ---- the turn of a half item ---- */                                                              \
+    "LturnH%=:\n\t"                                                                                      \
+    PX_STEP_HALF(RA00, RA01, RB00, RB01, RB02, RB03, RB10, RB11, RB12, RB13, RBOFF0, RBOFF1, "0", RA30, RA31, "0")     \
+    PX_STEP_HALF(RA10, RA11, RB10, RB11, RB12, RB13, RB00, RB01, RB02, RB03, RBOFF1, RBOFF0, "4", RA00, RA01, "1024")  \
+    PX_STEP_HALF(RA20, RA21, RB00, RB01, RB02, RB03, RB10, RB11, RB12, RB13, RBOFF0, RBOFF1, "8", RA10, RA11, "2048")  \
+    PX_STEP_HALF(RA30, RA31, RB10, RB11, RB12, RB13, RB00, RB01, RB02, RB03, RBOFF1, RBOFF0, "12", RA20, RA21, "3072") \
+    "s_branch Ltail%=\n\t"                                                                               \
     /* ---- h1 ---- */                                                                                   \
     "Lh1%=:\n\t"                                                                                         \
     "s_cmp_eq_u32 %[hc], 0\n\t"                                                                          \
@@ -657,7 +738,10 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
     PX_WAIT(done, "a")                                                                                   \
     "s_and_b32 %[st], %[st], 1\n\t"                                                                      \
     "s_mul_i32 %[st], %[st], %[bufb]\n\t"                                                                \
+    "s_cmp_eq_u32 %[onetile], 0\n\t"                                                                     \
+    "s_cbranch_scc0 LcomH%=\n\t"                                                                         \
     PX_TURN_COMMIT                                                                                       \
+    "Lcom2%=:\n\t"                                                                                       \
     PX_SIGNAL(ready)                                                                                     \
     "s_add_u32 %[st], %[hc], 2\n\t"                                                                      \
     "s_cmp_lt_u32 %[st], %[nchunks]\n\t"                                                                 \
@@ -665,6 +749,9 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
     "s_mul_i32 %[st], %[st], %[csrc]\n\t"                                                                \
     PX_ISSUE                                                                                             \
     "s_branch Ltail%=\n\t"                                                                               \
+    "LcomH%=:\n\t"                                                                                       \
+    PX_TURN_COMMIT_HALF                                                                                  \
+    "s_branch Lcom2%=\n\t"                                                                               \
     /* ---- h3 ---- */                                                                                   \
     "Lh3%=:\n\t"                                                                                         \
     "s_add_u32 %[st], %[hc], 1\n\t"                                                                      \
@@ -748,8 +835,7 @@ __global__ __launch_bounds__(512) void conv_mfma_persistent_kernel(PParams p)
     // on a window of consecutive bands of one filter tile and few compute units get the odd item.
     const int xcd = blockIdx.x & (kXcds - 1);
     const int wi = blockIdx.x >> kXcdShift;
-    // (the even workgroups of an XCD come first: the odd ones start late, see below, and the groups
-    // with one item more than the others are among the first)
+    // (the even workgroups of an XCD come first)
     const int n_even = (p.wgs_per_xcd + 1) >> 1;
     const int slot = ((wi & 1) ? n_even + (wi >> 1) : (wi >> 1)) + grp * p.wgs_per_xcd;
 #ifdef XNOR_TS_BUILD
@@ -758,18 +844,6 @@ __global__ __launch_bounds__(512) void conv_mfma_persistent_kernel(PParams p)
 #else
     const int nslot = 2 * p.wgs_per_xcd;
 #endif
-
-    // All workgroups start together and an item takes every group about as long, so without this
-    // the whole chip would store its outputs in the same short windows (and fetch its inputs in
-    // others).  Every second workgroup starts a quarter of an item late: with the half-item offset
-    // between a workgroup's two groups that makes four evenly spaced phases.
-    if ((wi & 1) && p.stagger > 0) {
-        const unsigned long long t0 = __builtin_readcyclecounter();
-        for (int spin = 0; spin < kSpinLimit; ++spin) {
-            if (__builtin_readcyclecounter() - t0 >= (unsigned long long)p.stagger) break;
-            __builtin_amdgcn_s_sleep(8);
-        }
-    }
 
     // the first group releases the second one at turn `sturn` of its first item (-1: not, or done)
     int sturn = grp == 0 ? p.start_turn : -1;
@@ -893,25 +967,11 @@ __global__ __launch_bounds__(512) void conv_mfma_persistent_kernel(PParams p)
                 asm volatile("" : "+v"(v32[j]));
             }
             const char *ub = reinterpret_cast<const char *>(tile_base);
-#ifdef XNOR_TS_BUILD
-            if (p.dbg & 64) {   // timing only: every 128-byte run starts on a cache line (rounded down)
-                const uint32_t l4 = 4u * (uint32_t)(fresh_lane() & 31);
-#pragma unroll
-                for (int j = 0; j < kWN; ++j) v32[j] = ((v32[j] - l4) & ~127u) + l4;
-            }
-#endif
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-#ifdef XNOR_TS_BUILD
-                const char *ub_keep = ub;
-                if (p.dbg & 64) ub = reinterpret_cast<const char *>(reinterpret_cast<uintptr_t>(ub) & ~(uintptr_t)127);
-#endif
 #pragma unroll
                 for (int j = 0; j < kWN; ++j)
                     if (j < nfull) *(ptr_t)(ub + v32[j]) = value(j, r);
-#ifdef XNOR_TS_BUILD
-                ub = ub_keep;
-#endif
                 ub += (r & 3) == 3 ? plane5 : plane1;
             }
             first_slow = nfull;
@@ -1204,7 +1264,7 @@ __global__ __launch_bounds__(512) void conv_mfma_persistent_kernel(PParams p)
                            [nturns] "s"(p.nturns), [nchunks] "s"(p.nchunks), [csteps] "s"(p.chunk_steps),
                            [cbase] "s"(cbase), [csrc] "s"(p.CH * 4), [bufb] "s"(p.buf16 * 16),
                            [pmask] "s"(grp == 1 ? p.prio_mask : 0), [onetile] "s"(__builtin_amdgcn_readfirstlane(it.half < 0 ? 0 : 1)),
-                           [m03] "s"(0x03030303u), [tbl] "s"(0x222AA2AAu) PX_DBG_OPERANDS
+                           [m03] "s"(0x03030303u), [tbl] "s"(0x222AA2AAu)
                          : "memory", "vcc", "scc",
                            "v168", "v169", "v170", "v171", "v172", "v173", "v174", "v175", "v176", "v177", "v178",
                            "v179", "v180", "v181", "v182", "v183", "v184", "v185", "v186", "v187", "v188", "v189",
@@ -1420,7 +1480,6 @@ hipError_t launch_conv_mfma_persistent(const uint32_t *Ipk, const float *K, cons
         p.work_per_xcd = p.whole_items + 2 * (p.items_per_xcd - p.whole_items);
     }
     p.start_turn = pl.nturns / 2;
-    p.stagger = 0;
     p.prio_mask = 7;
 #ifdef XNOR_TS_BUILD
     {
@@ -1430,8 +1489,6 @@ hipError_t launch_conv_mfma_persistent(const uint32_t *Ipk, const float *K, cons
         p.dbg = d ? atoi(d) : 0;
         const char *st = getenv("XNOR_START_TURN");
         if (st) p.start_turn = atoi(st);
-        const char *sg = getenv("XNOR_STAGGER");
-        if (sg) p.stagger = atoi(sg);
         const char *pm = getenv("XNOR_PMASK");
         if (pm) p.prio_mask = atoi(pm);
         const char *wg = getenv("XNOR_WGS");

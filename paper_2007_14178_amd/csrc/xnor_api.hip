@@ -238,6 +238,11 @@ int xnor_conv2d_fwd_algo(const uint32_t *Ipk, const uint32_t *Wpk, const float *
             if (workspace_bytes < need) return XNOR_E_WORKSPACE;
             return hip_status(xnor::launch_conv_mfma(Ipk, Wpk, K, alpha, g, out, dot, workspace, st));
         }
+        case XNOR_ALGO_MFMA_BANDS: {
+            if (!xnor::conv_mfma_bands_supports(g)) return XNOR_E_UNSUPPORTED;
+            if (workspace_bytes < xnor::conv_mfma_workspace_bytes(g)) return XNOR_E_WORKSPACE;
+            return hip_status(xnor::launch_conv_mfma_bands(Ipk, Wpk, K, alpha, g, out, dot, workspace, st));
+        }
         default:
             return XNOR_E_UNSUPPORTED;
     }

@@ -73,5 +73,9 @@ hipError_t launch_conv_mfma_chain(const uint32_t *Ipk, const uint32_t *Wpk, cons
 hipError_t launch_conv_mfma(const uint32_t *Ipk, const uint32_t *Wpk, const float *K,
                             const float *alpha, const Geom &g, float *out, int32_t *dot,
                             void *workspace, hipStream_t st);
+bool conv_mfma_bands_supports(const Geom &g);
+hipError_t launch_conv_mfma_bands(const uint32_t *Ipk, const uint32_t *Wpk, const float *K,
+                                  const float *alpha, const Geom &g, float *out, int32_t *dot,
+                                  void *workspace, hipStream_t st);
 
 }  // namespace xnor

@@ -191,3 +191,88 @@ def test_matrix_core_kernel_with_outputs_spread_over_more_than_2_gib():
     torch.cuda.synchronize()
     assert torch.equal(out2, out)
     assert np.array_equal(dot2[:, fsel].cpu().numpy(), d_ref)
+
+
+def test_c5_whole_tensor_vs_oracle():
+    """The headline layer at full size, every element: the step bench.py times (xnor_prepare, then the
+    convolution on the expanded filters) against the oracle on all 128 images and all 512 filters --
+    binary dots bit-exact, fp32 outputs within 1e-5, zero pattern equal."""
+    from paper_2007_14178_amd import binding as xb
+    L = LAYERS["c5"]
+    print("case layer=c5 whole tensor", flush=True)
+    I, Wt = make_input(L), make_weights(L)
+    s = xb.Shape(L.N, L.C, L.H, L.W, L.F, L.kh, L.kw, L.sh, L.sw, L.ph, L.pw)
+    OH, OW = xb.xnor_out_dim(s)
+    dI, dW = torch.from_numpy(I).cuda(), torch.from_numpy(Wt).cuda()
+    Ipk = torch.empty((s.N, s.H, s.W, s.Cw), dtype=torch.int32, device="cuda")
+    Wpk = torch.empty((s.F, s.kh, s.kw, s.Cw), dtype=torch.int32, device="cuda")
+    A = torch.empty((s.N, s.H, s.W), dtype=torch.float32, device="cuda")
+    K = torch.empty((s.N, OH, OW), dtype=torch.float32, device="cuda")
+    M = torch.empty((s.F, s.kh, s.kw), dtype=torch.float32, device="cuda")
+    alpha = torch.empty((s.F,), dtype=torch.float32, device="cuda")
+    ws = torch.empty((xb.xnor_conv2d_workspace_bytes(s),), dtype=torch.uint8, device="cuda")
+    xb.xnor_prepare(dI, dW, s, Ipk, A, K, Wpk, M, alpha, want_K=True, workspace=ws)
+    out, dot = xb.xnor_conv2d_fwd_expanded(Ipk, ws, K, alpha, s, want_dot=True)
+    torch.cuda.synchronize()
+    step = 16
+    for n0 in range(0, L.N, step):
+        n1 = min(L.N, n0 + step)
+        sub = oracle.Shape(n1 - n0, L.C, L.H, L.W, L.F, L.kh, L.kw, L.sh, L.sw, L.ph, L.pw)
+        d_ref, _, _, O_ref = oracle.forward(I[n0:n1], Wt, sub)
+        assert np.array_equal(dot[n0:n1].cpu().numpy(), d_ref), f"dot, images {n0}..{n1 - 1}"
+        assert rel_ok(out[n0:n1].cpu().numpy(), O_ref), f"out, images {n0}..{n1 - 1}"
+        print(f"  images {n0}..{n1 - 1} ok", flush=True)
+
+
+def test_c5_repeated_steps_identical():
+    """The persistent kernel hands LDS buffers between its waves through counters; a mistake there
+    shows as a rare wrong pixel, not as a failure of every run.  The benchmark step is therefore
+    run many times, eagerly and as HIP-graph replays (no host gaps between the kernels), and every
+    output must equal the first one bit for bit."""
+    from paper_2007_14178_amd import binding as xb
+    L = LAYERS["c5"]
+    print("case layer=c5 repeated steps", flush=True)
+    s = xb.Shape(L.N, L.C, L.H, L.W, L.F, L.kh, L.kw, L.sh, L.sw, L.ph, L.pw)
+    OH, OW = xb.xnor_out_dim(s)
+    dI = torch.from_numpy(make_input(L)).cuda()
+    dW = torch.from_numpy(make_weights(L)).cuda()
+    Ipk = torch.empty((s.N, s.H, s.W, s.Cw), dtype=torch.int32, device="cuda")
+    Wpk = torch.empty((s.F, s.kh, s.kw, s.Cw), dtype=torch.int32, device="cuda")
+    A = torch.empty((s.N, s.H, s.W), dtype=torch.float32, device="cuda")
+    K = torch.empty((s.N, OH, OW), dtype=torch.float32, device="cuda")
+    M = torch.empty((s.F, s.kh, s.kw), dtype=torch.float32, device="cuda")
+    alpha = torch.empty((s.F,), dtype=torch.float32, device="cuda")
+    ws = torch.empty((xb.xnor_conv2d_workspace_bytes(s),), dtype=torch.uint8, device="cuda")
+    out = torch.empty((s.N, s.F, OH, OW), dtype=torch.float32, device="cuda")
+
+    def step(from_A):
+        xb.xnor_prepare(dI, dW, s, Ipk, A, K, Wpk, M, alpha, want_K=not from_A, workspace=ws)
+        if from_A:
+            xb.xnor_conv2d_fwd_expanded_from_A(Ipk, ws, A, alpha, s, out=out)
+        else:
+            xb.xnor_conv2d_fwd_expanded(Ipk, ws, K, alpha, s, out=out)
+
+    step(False)
+    torch.cuda.synchronize()
+    ref = out.clone()
+    for from_A in (False, True):
+        for it in range(25):
+            out.zero_()
+            step(from_A)
+            torch.cuda.synchronize()
+            assert torch.equal(out, ref), f"eager step {it} (K formed in the kernel: {from_A})"
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step(from_A)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                step(from_A)
+        torch.cuda.current_stream().wait_stream(side)
+        for it in range(10):
+            out.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, ref), f"graph replay {it} (K formed in the kernel: {from_A})"
+        del graph

@@ -106,18 +106,19 @@ def check_all(xb, layer, I, Wt, algo, key):
     assert_rel(M2.cpu().numpy(), oracle.channel_mean_abs(Wt), "mean_c |Wt| (one pass)")
 
 
-ALGOS = ["direct", "tiled", "mfma", "auto"]   # innermost parameter, so one oracle run serves all four
+ALGOS = ["direct", "tiled", "mfma", "mfma_bands", "auto"]   # innermost parameter, so one oracle run serves all
 
 
 def algo_id(xb, name):
-    return {"auto": xb.ALGO_AUTO, "direct": xb.ALGO_DIRECT, "tiled": xb.ALGO_TILED, "mfma": xb.ALGO_MFMA}[name]
+    return {"auto": xb.ALGO_AUTO, "direct": xb.ALGO_DIRECT, "tiled": xb.ALGO_TILED, "mfma": xb.ALGO_MFMA,
+            "mfma_bands": xb.ALGO_MFMA_BANDS}[name]
 
 
 def run_or_skip(xb, layer, I, Wt, algo, key):
     try:
         check_all(xb, layer, I, Wt, algo_id(xb, algo), key)
     except xb.XnorError as e:
-        if e.status == xb.E_UNSUPPORTED and algo in ("tiled", "mfma"):
+        if e.status == xb.E_UNSUPPORTED and algo in ("tiled", "mfma", "mfma_bands"):
             pytest.skip(f"{algo} does not take this shape")
         raise
 
@@ -182,7 +183,7 @@ def test_special_values(xb):
 def test_determinism(xb):
     layer = LAYERS["c3_s1"].with_batch(4)
     I, Wt = make_input(LAYERS["c3_s1"], 4), make_weights(LAYERS["c3_s1"])
-    for algo in ("direct", "tiled", "mfma"):
+    for algo in ("direct", "tiled", "mfma", "mfma_bands"):
         try:
             r1 = run_pipeline(xb, layer, I, Wt, algo_id(xb, algo))
             r2 = run_pipeline(xb, layer, I, Wt, algo_id(xb, algo))
@@ -208,7 +209,7 @@ def test_outputs_do_not_spill(xb):
         buf = torch.full((n + 2 * G,), -7777, dtype=dtype, device="cuda")
         return buf, buf[G:G + n]
 
-    for algo in ("direct", "tiled", "mfma"):
+    for algo in ("direct", "tiled", "mfma", "mfma_bands"):
         bI, vI = guarded(s.N * s.H * s.W * s.Cw, torch.int32)
         bW, vW = guarded(s.F * s.kh * s.kw * s.Cw, torch.int32)
         bA, vA = guarded(s.N * s.H * s.W, torch.float32)
@@ -236,7 +237,7 @@ def test_outputs_do_not_spill(xb):
 def test_dot_null_gives_same_out(xb):
     layer = LAYERS["c1"]
     I, Wt = make_input(layer), make_weights(layer)
-    for algo in ("direct", "tiled", "mfma"):
+    for algo in ("direct", "tiled", "mfma", "mfma_bands"):
         try:
             a = run_pipeline(xb, layer, I, Wt, algo_id(xb, algo), want_dot=True)
             b = run_pipeline(xb, layer, I, Wt, algo_id(xb, algo), want_dot=False)
@@ -320,7 +321,7 @@ def test_buffers_that_are_only_4_or_8_byte_aligned(xb, offset_words):
     assert np.array_equal(words(Ipk), oracle.pack(I)) and np.array_equal(words(Wpk), oracle.pack(Wt))
     assert_rel(K.cpu().numpy(), K_ref, "K")
     assert_rel(alpha.cpu().numpy(), a_ref, "alpha")
-    for algo in ("direct", "tiled", "mfma"):
+    for algo in ("direct", "tiled", "mfma", "mfma_bands"):
         out.zero_(); dot.zero_()
         xb.xnor_conv2d_fwd(Ipk, Wpk, K, alpha, s, out=out, dot=dot, algo=algo_id(xb, algo))
         torch.cuda.synchronize()
