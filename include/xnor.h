@@ -198,8 +198,8 @@ int xnor_conv2d_fwd_expanded_from_A(const uint32_t *Ipk, const void *workspace, 
                                     int32_t *dot, void *stream);
 
 /*
- * Chained layers (the paper's closing proposal, Sec. V: "passing the binary outputs to the next
- * kernel without integer conversion").  When the consumer of this layer's output O (Eq. 11) is
+ * Chained layers (the paper's closing proposal, Sec. V: hand the next kernel the binary outputs
+ * themselves, with no conversion to integers in between).  When the consumer of this layer's output O (Eq. 11) is
  * another binary convolution, all it needs of O is what xnor_input_prepare would compute from it:
  * the packed signs of O along its channels (= this layer's filters) and the channel mean of |O|
  * (Eq. 10).  xnor_conv2d_fwd_chain produces exactly these and never writes the fp32 O:
@@ -261,7 +261,7 @@ int xnor_forward_image(const float *I, const uint32_t *Wpk, const float *alpha, 
 
 /*
  * Binary-Weight-Network convolution (Sec. II-A, Eq. 1, with alpha from Eq. 5): real-valued input,
- * binary weights B = sign(W), "convolution without multiplication":
+ * binary weights B = sign(W), so the convolution needs no multiplications:
  *     out[n][f][oy][ox] = alpha[f] * sum over in-image taps and channels of (B = +1 ? +I : -I).
  * The input is not binarised and there is no K.  Zero padding, stride and cross-correlation as in
  * xnor_conv2d_fwd.

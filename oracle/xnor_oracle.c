@@ -209,7 +209,7 @@ void oracle_out(const int32_t *dot, const float *K, const float *alpha, int N, i
 
 /*
  * Binary-Weight-Network convolution (Sec. II-A, Eq. 1): the input keeps its real values, the
- * weights are B = sign(W), and the "convolution without multiplication" adds or subtracts each
+ * weights are B = sign(W), and the convolution, free of multiplications, adds or subtracts each
  * input value according to its weight's sign; the per-filter alpha of Eq. 5 scales the sum:
  *     O[n][f][oy][ox] = alpha[f] * sum_{in-image taps, c} (B = +1 ? +I : -I).
  * No K: the input is not binarised.  Same padding, stride and cross-correlation readings as the

@@ -841,34 +841,35 @@ static hipError_t launch_mfma(const uint32_t *Ipk, const float *K, const float *
     p.nbands = ceil_div(p.total_rows, pl.TH);
     p.bands_per_xcd = ceil_div(p.nbands, kXcds);
     const dim3 grid(kXcds * p.bands_per_xcd * pl.f_tiles);
-    auto launch = [&](auto kernel) -> hipError_t {
-        // raise the kernel's dynamic-LDS limit to the hardware maximum once per device (the call
-        // is slow on the host); one flag set per template instance
-        static std::atomic<unsigned long long> raised{0};
+    auto launch = [&](auto kernel, int slot) -> hipError_t {
+        // raise the kernel's dynamic-LDS limit to the hardware maximum once per device and kernel
+        // (the call is slow on the host); the six template instances share one function type, so
+        // each passes the slot of its own flag set
+        static std::atomic<unsigned long long> raised[6];
         int dev = 0;
         hipError_t err = hipGetDevice(&dev);
         if (err != hipSuccess) return err;
         const unsigned long long bit = 1ull << (dev & 63);
-        if (!(raised.load(std::memory_order_acquire) & bit)) {
+        if (!(raised[slot].load(std::memory_order_acquire) & bit)) {
             err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax);
             if (err != hipSuccess) return err;
-            raised.fetch_or(bit, std::memory_order_release);
+            raised[slot].fetch_or(bit, std::memory_order_release);
         }
         kernel<<<grid, 256, pl.lds_bytes, st>>>(p);
         return hipGetLastError();
     };
     if (Opk) {
         switch (pl.vw) {
-            case 4: return launch(conv_mfma_kernel<4, true>);
-            case 2: return launch(conv_mfma_kernel<2, true>);
-            default: return launch(conv_mfma_kernel<1, true>);
+            case 4: return launch(conv_mfma_kernel<4, true>, 0);
+            case 2: return launch(conv_mfma_kernel<2, true>, 1);
+            default: return launch(conv_mfma_kernel<1, true>, 2);
         }
     }
     switch (pl.vw) {
-        case 4: return launch(conv_mfma_kernel<4, false>);
-        case 2: return launch(conv_mfma_kernel<2, false>);
-        default: return launch(conv_mfma_kernel<1, false>);
+        case 4: return launch(conv_mfma_kernel<4, false>, 3);
+        case 2: return launch(conv_mfma_kernel<2, false>, 4);
+        default: return launch(conv_mfma_kernel<1, false>, 5);
     }
 }
 

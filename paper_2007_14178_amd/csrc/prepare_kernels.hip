@@ -524,19 +524,32 @@ static size_t filter_block_smem(int C, int taps, bool expand, int *CH_out)
            (expand ? (size_t)taps * Cw * sizeof(uint32_t) : 0);
 }
 
-bool prepare_both_supports(const float *x, int N, int C, int H, int W, int taps)
+// Which input pass a single launch for both sides can use: 4 (four pixels per lane), 1 (one pixel
+// per lane) or 0 (neither fits: the caller launches the two sides separately).  Either pass shares
+// its dynamic LDS (at most 64 KB) with the filter blocks' staging.
+static int prepare_both_pass(const float *x, int N, int C, int H, int W, int taps, bool expand)
 {
     const int Cw = (C + 31) / 32, Cwp = Cw | 1;
-    if (Cw > 512 || taps > 256) return false;
-    if (four_pixel_pass(x, N, C, H, W)) return true;
-    // (the one-pixel pass: its words of 64 pixels and the filter block's staging must fit 64 KB, and
-    // the filter block gives every tap a thread of its own)
+    if (Cw > 512 || taps > 256) return 0;
+    int CH;
+    const size_t smemf = filter_block_smem(C, taps, expand, &CH);
+    if (smemf > 64 * 1024) return 0;
+    if (four_pixel_pass(x, N, C, H, W)) {
+        const size_t smem4 = (size_t)kPack4Slices * 256 * sizeof(double) + (size_t)256 * Cwp * sizeof(uint32_t);
+        if (smem4 <= 64 * 1024) return 4;
+    }
+    // (the one-pixel pass: the filter block gives every tap a thread of its own)
     int S = 1;
     while (S < kPackMeanSlices && 2 * S <= Cw) S *= 2;
-    if (64 * S < taps) return false;
-    int CH;
+    if (64 * S < taps) return 0;
     const size_t smem1 = (size_t)kPackMeanSlices * 64 * sizeof(double) + (size_t)64 * Cwp * sizeof(uint32_t);
-    return std::max(smem1, filter_block_smem(C, taps, true, &CH)) <= 64 * 1024;
+    return smem1 <= 64 * 1024 ? 1 : 0;
+}
+
+bool prepare_both_supports(const float *x, int N, int C, int H, int W, int taps)
+{
+    // (with the filter expansion's LDS counted: the caller may ask for it)
+    return prepare_both_pass(x, N, C, H, W, taps, true) != 0;
 }
 
 // `Wx` (may be null): the matrix-core kernel's filter workspace, filled as by launch_expand_filters.
@@ -550,21 +563,21 @@ hipError_t launch_prepare_both(const float *x, int N, int C, int H, int W, uint3
     const long long NP = (long long)N * HW;
     int CH;
     const size_t smemf = filter_block_smem(C, taps, Wx != nullptr, &CH);
-    if (four_pixel_pass(x, N, C, H, W)) {
+    const int pass = prepare_both_pass(x, N, C, H, W, taps, Wx != nullptr);
+    if (pass == 4) {
         const size_t smem4 = (size_t)kPack4Slices * 256 * sizeof(double) + (size_t)256 * Cwp * sizeof(uint32_t);
         const size_t smem = std::max(smem4, smemf);
-        if (smem > 64 * 1024) return hipErrorInvalidValue;
         const long long blocks = (long long)F + ceil_div(NP, 256);
         if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
         prepare_both_kernel<<<dim3((unsigned)blocks), dim3(64, kPack4Slices), smem, st>>>(
             x, NP, C, HW, Cw, Cwp, packed, A, Wt, F, taps, CH, Wpk, M, alpha, static_cast<uint4 *>(Wx), L);
         return hipGetLastError();
     }
+    if (pass != 1) return hipErrorInvalidValue;   // (prepare_both_supports said no)
     int S = 1;
     while (S < kPackMeanSlices && 2 * S <= Cw) S *= 2;
     const size_t smem1 = (size_t)S * 64 * sizeof(double) + (size_t)64 * Cwp * sizeof(uint32_t);
     const size_t smem = std::max(smem1, smemf);
-    if (smem > 64 * 1024) return hipErrorInvalidValue;
     const long long blocks = (long long)F + ceil_div(NP, 64);
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     prepare_both1_kernel<<<dim3((unsigned)blocks), dim3(64, S), smem, st>>>(

@@ -364,7 +364,8 @@ def test_conv_that_forms_K_itself(xb, shape):
                                    (84, 288, 28, 28, 33, 5, 5, 1, 1, 2, 2),      # the same, ragged blocks, channel words 9
                                    (2, 64, 13, 13, 40, 3, 3, 1, 1, 1, 1),        # one launch, one-pixel input pass (H*W odd)
                                    (3, 96, 27, 27, 130, 5, 5, 1, 1, 2, 2),       # the same, three channel words, partial filter tile
-                                   (2, 16, 20, 20, 5, 9, 9, 1, 1, 4, 4)],        # more taps than a one-slice block has threads: separate launches
+                                   (2, 16, 20, 20, 5, 9, 9, 1, 1, 4, 4),         # more taps than a one-slice block has threads: separate launches
+                                   (1, 1552, 256, 256, 3, 3, 3, 1, 1, 1, 1)],    # 49 channel words: the four-pixel pass's LDS would pass 64 KB
                          ids=lambda s: "x".join(map(str, s)))
 def test_prepare_both_sides_in_one_call(xb, shape):
     """xnor_prepare gives bit for bit what xnor_input_prepare and xnor_filter_prepare give."""
@@ -389,7 +390,7 @@ def test_prepare_both_sides_in_one_call(xb, shape):
     assert nbytes > 0
     ws = torch.full((nbytes,), 0x5A, dtype=torch.uint8, device="cuda")
     xb.xnor_prepare(dI, dW, s, workspace=ws)
-    ws2 = xb.xnor_filter_expand(Wpk2, s)
+    ws2 = xb.xnor_filter_expand(Wpk2, s, workspace=torch.full((nbytes,), 0x5A, dtype=torch.uint8, device="cuda"))
     torch.cuda.synchronize()
     assert torch.equal(ws, ws2)
 
