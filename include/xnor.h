@@ -287,6 +287,22 @@ int xnor_conv2d_fwd_algo(const uint32_t *Ipk, const uint32_t *Wpk, const float *
                          const float *alpha, const xnor_shape *s, float *out, int32_t *dot,
                          void *workspace, size_t workspace_bytes, int algo, void *stream);
 
+/*
+ * For callers that cannot allocate device memory and have no workspace to hand in (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): xnor_conv2d_fwd_algo with
+ * XNOR_ALGO_MFMA, its workspace (the filters expanded to matrix-core operands) taken from an array
+ * of XNOR_STATIC_SCRATCH_BYTES that the library holds on every GPU it runs on until the process
+ * ends.  Same arguments, layouts and results as xnor_conv2d_fwd_algo; the call allocates nothing.
+ * Returns XNOR_E_UNSUPPORTED for shapes the matrix-core kernel does not take and XNOR_E_WORKSPACE
+ * for shapes whose expanded filters exceed the array (xnor_conv2d_workspace_bytes(s) >
+ * XNOR_STATIC_SCRATCH_BYTES).  All calls on one GPU share that GPU's array and each rewrites it:
+ * calls that overlap on one GPU (different streams, or threads) race; calls on one stream do not.
+ */
+#define XNOR_STATIC_SCRATCH_BYTES (4u << 20)
+int xnor_conv2d_fwd_static(const uint32_t *Ipk, const uint32_t *Wpk, const float *K,
+                           const float *alpha, const xnor_shape *s, float *out, int32_t *dot,
+                           void *stream);
+
 /* The algorithm XNOR_ALGO_AUTO resolves to for this shape when given `workspace_bytes` of
  * workspace (an xnor_algo), or a negative status. */
 int xnor_conv2d_pick_algo(const xnor_shape *s, size_t workspace_bytes);

@@ -87,6 +87,7 @@ def _load() -> ctypes.CDLL:
     L.xnor_prepare.argtypes = [vp, vp, sp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.xnor_conv2d_fwd.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, vp]
     L.xnor_conv2d_fwd_algo.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, ci, vp]
+    L.xnor_conv2d_fwd_static.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp]
     L.xnor_filter_expand.argtypes = [vp, sp, vp, sz, vp]
     L.xnor_conv2d_fwd_expanded.argtypes = [vp, vp, sz, vp, vp, sp, vp, vp, vp]
     L.xnor_conv2d_fwd_expanded_from_A.argtypes = [vp, vp, sz, vp, vp, sp, vp, vp, vp]
@@ -109,7 +110,7 @@ def _load() -> ctypes.CDLL:
                  "xnor_forward_image_supported", "xnor_forward_image",
                  "xnor_bwn_conv2d_fwd", "xnor_bwn_conv2d_fwd_algo",
                  "xnor_conv2d_fwd_expanded_from_A", "xnor_conv2d_fwd_chain_from_A",
-                 "xnor_conv2d_fwd_chain_expanded_from_A", "xnor_prepare"):
+                 "xnor_conv2d_fwd_chain_expanded_from_A", "xnor_prepare", "xnor_conv2d_fwd_static"):
         getattr(L, name).restype = ci
     return L
 
@@ -292,6 +293,25 @@ def xnor_conv2d_fwd(Ipk: torch.Tensor, Wpk: torch.Tensor, K: torch.Tensor, alpha
         ctypes.byref(s.c()), _dev(out, torch.float32, oshape, "out"),
         _dev(dot, torch.int32, oshape, "dot") if dot is not None else None,
         ws_ptr, ws_bytes, algo, _stream()), f"xnor_conv2d_fwd[{ALGO_NAMES.get(algo, algo)}]")
+    return out, dot
+
+
+STATIC_SCRATCH_BYTES = 4 << 20
+
+
+def xnor_conv2d_fwd_static(Ipk: torch.Tensor, Wpk: torch.Tensor, K: torch.Tensor, alpha: torch.Tensor,
+                           s: Shape, out: torch.Tensor, dot: torch.Tensor | None = None):
+    """The matrix-core convolution with its workspace in the library's own static array: neither
+    the call nor this wrapper allocates, so the caller brings ``out`` (and ``dot`` if wanted)."""
+    OH, OW = xnor_out_dim(s)
+    oshape = (s.N, s.F, OH, OW)
+    _ok(lib.xnor_conv2d_fwd_static(
+        _dev(Ipk, torch.int32, (s.N, s.H, s.W, s.Cw), "Ipk"),
+        _dev(Wpk, torch.int32, (s.F, s.kh, s.kw, s.Cw), "Wpk"),
+        _dev(K, torch.float32, (s.N, OH, OW), "K"), _dev(alpha, torch.float32, (s.F,), "alpha"),
+        ctypes.byref(s.c()), _dev(out, torch.float32, oshape, "out"),
+        _dev(dot, torch.int32, oshape, "dot") if dot is not None else None, _stream()),
+        "xnor_conv2d_fwd_static")
     return out, dot
 
 

@@ -1,5 +1,6 @@
 // Host side of the C ABI declared in xnor.h: argument validation, geometry, kernel choice.
 // Nothing here allocates or synchronises; every call enqueues on the caller's stream.
+#include <atomic>
 #include <stdio.h>
 #include <string.h>
 
@@ -49,6 +50,32 @@ int pick_algo(const xnor::Geom &g, size_t workspace_bytes)
     if (need > 0 && workspace_bytes >= need) return XNOR_ALGO_MFMA;
     if (xnor::conv_tiled_supports(g)) return XNOR_ALGO_TILED;
     return XNOR_ALGO_DIRECT;
+}
+
+// The expanded filters of xnor_conv2d_fwd_static live here instead of in a caller's workspace.
+// One copy per GPU, held until the process ends.  In host code the name is only a handle: the
+// memory's address on the current device comes from hipGetSymbolAddress, once per device.
+constexpr size_t kStaticScratchBytes = (size_t)XNOR_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+hipError_t static_scratch(void **ptr)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);   // (racing first calls store the same address)
+    }
+    *ptr = p;
+    return hipSuccess;
 }
 
 }  // namespace
@@ -246,6 +273,28 @@ int xnor_conv2d_fwd_algo(const uint32_t *Ipk, const uint32_t *Wpk, const float *
         default:
             return XNOR_E_UNSUPPORTED;
     }
+}
+
+int xnor_conv2d_fwd_static(const uint32_t *Ipk, const uint32_t *Wpk, const float *K,
+                           const float *alpha, const xnor_shape *s, float *out, int32_t *dot,
+                           void *stream)
+{
+    if (!Ipk || !Wpk || !K || !alpha || !s || !out) return XNOR_E_NULL;
+    xnor::Geom g;
+    const int rc = make_geom(s, &g);
+    if (rc) return rc;
+    if (!aligned(Ipk, 4) || !aligned(Wpk, 4) || !aligned(K, 4) || !aligned(alpha, 4) ||
+        !aligned(out, 4) || (dot && !aligned(dot, 4)))
+        return XNOR_E_ALIGN;
+    const size_t need = xnor::conv_mfma_workspace_bytes(g);
+    if (need == 0) return XNOR_E_UNSUPPORTED;
+    if (need > kStaticScratchBytes) return XNOR_E_WORKSPACE;
+    void *ws = nullptr;
+    const hipError_t e = static_scratch(&ws);
+    if (e != hipSuccess) return hip_status(e);
+    // every byte of the shape's filter layout is rewritten by the expansion that launch_conv_mfma
+    // starts with, so nothing of the previous call's contents is read
+    return hip_status(xnor::launch_conv_mfma(Ipk, Wpk, K, alpha, g, out, dot, ws, (hipStream_t)stream));
 }
 
 int xnor_box_filter_K(const float *A, const xnor_shape *s, float *K, void *stream)

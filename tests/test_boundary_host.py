@@ -98,6 +98,12 @@ def test_null_and_alignment_rejected(xb):
     assert need > 0 and need % 1024 == 0
     assert xb.xnor_conv2d_pick_algo(s, need) == xb.ALGO_MFMA
     assert xb.xnor_conv2d_pick_algo(s, need - 1) != xb.ALGO_MFMA
+    # the form with the workspace in the library's static array: argument checks come before any HIP call
+    assert L.xnor_conv2d_fwd_static(None, ok, ok, ok, sp, ok, None, None) == xb.E_NULL
+    assert L.xnor_conv2d_fwd_static(ok, ok, ok, ok, sp, odd, None, None) == xb.E_ALIGN
+    big = xb.Shape(1, 2048, 14, 14, 1024, 3, 3, 1, 1, 1, 1)
+    assert xb.xnor_conv2d_workspace_bytes(big) > xb.STATIC_SCRATCH_BYTES
+    assert L.xnor_conv2d_fwd_static(ok, ok, ok, ok, ctypes.byref(big.c()), ok, None, None) == xb.E_WORKSPACE
     # the two-call form of the matrix-core path
     assert L.xnor_filter_expand(None, sp, ok, need, None) == xb.E_NULL
     assert L.xnor_filter_expand(ok, sp, None, need, None) == xb.E_NULL
