@@ -15,7 +15,7 @@ Defaults follow the paper's timing protocol (Sec. IV: compute only, mean of 100 
 100 timed steps, buffers allocated and filled before the timed region and reused every step.
 Other modes: --sweep (all layers, both kernels, with HIP-graph replay times), --chain (chained
 layer), --image (the paper's single-channel workload, Tables I-III), --bwn (Binary-Weight-Network
-layer), --unfused (separate pre-stage calls).
+layer), --unfused (separate pre-stage calls), --peaks (the ceilings this GPU sustains).
 """
 from __future__ import annotations
 
@@ -35,7 +35,39 @@ PEAK_HBM_GBS = 8000.0
 # v_xor_b32 + v_bcnt_u32_b32 retire 32 binary MACs per lane: 256 CU x 4 SIMD x 16 lanes x 2.4 GHz
 # = 3.93e13 lane-ops/s -> 6.29e14 binary MAC/s -> 1258 T binary op/s counting 2 ops per MAC.
 PEAK_VALU_POPCOUNT_TOPS = 256 * 4 * 16 * 2.4e9 / 2 * 32 * 2 / 1e12
-MEASURED_CONV_TRAFFIC_BYTES = {("c5", "mfma"): 42.6e6 + 213.2e6}
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "forward_c5_hbm_traffic_pmc.md")
+CONV_SOURCES = ("conv_mfma_persistent.hip", "conv_mfma.hip", "conv_mfma_common.hpp")
+
+
+def conv_source_digest() -> str:
+    """Fingerprint of the matrix-core convolution's sources: a counter reading belongs to the kernel
+    it was taken on."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in CONV_SOURCES:
+        with open(os.path.join(ROOT, "paper_2007_14178_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_conv_traffic(layer_name: str, algo_name: str):
+    """HBM bytes per convolution launch from the tracked rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE runs, each scaled by a plain copy of known size).  The summary carries one line
+    `traffic: layer=<l> algo=<a> fetch_bytes=<n> write_bytes=<n> commit=<hash> conv_sources=<digest>`
+    per measured kernel; a reading taken on other kernel sources than the ones at hand is not
+    reported (None), and neither is a missing one."""
+    try:
+        with open(TRAFFIC_PROFILE) as f:
+            lines = [ln.strip() for ln in f if ln.strip().startswith("traffic:")]
+    except OSError:
+        return None, None
+    for ln in lines:
+        kv = dict(item.split("=", 1) for item in ln.split()[1:] if "=" in item)
+        if kv.get("layer") == layer_name and kv.get("algo") == algo_name:
+            if kv.get("conv_sources") != conv_source_digest():
+                return None, f"stale: measured at commit {kv.get('commit')} on other kernel sources"
+            return float(kv["fetch_bytes"]) + float(kv["write_bytes"]), f"measured at commit {kv.get('commit')}"
+    return None, None
 
 
 def parse():
@@ -71,12 +103,21 @@ def parse():
                     help="skip the HIP-graph replay of the step (its time is reported beside the eager one)")
     ap.add_argument("--conv-events-every", type=int, default=1,
                     help="bracket the convolution launch with events on every n-th timed step only (0: never)")
+    ap.add_argument("--peaks", action="store_true",
+                    help="not the benchmark line: the ceilings this GPU sustains (register-only FP4 matrix loop, "
+                         "v_xor + v_bcnt loop, plain copies of 64 MiB and 1 GiB), one JSON line")
+    ap.add_argument("--print-conv-digest", action="store_true",
+                    help="print the fingerprint of the convolution sources (for the traffic line of a counter summary)")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
 
 
-def cpu_baseline(layer, Wt, target_s: float):
-    """The oracle as it stands, on the host cores, on the first images of the same workload."""
+def cpu_baseline(layer, Wt, target_s: float, gpu_out=None, gpu_dot=None):
+    """The oracle as it stands, on the host cores, on the first images of the same workload.  Its
+    results are kept and the GPU's outputs for the same images (`gpu_out`, `gpu_dot`: device
+    tensors of the whole batch) are compared with them, element by element: the second value
+    returned is {"images", "elements", "dot_mismatches", "worst_rel", "outside_1e-5"}."""
+    import numpy as np
     import oracle
     from paper_2007_14178_amd.workloads import make_input
 
@@ -85,16 +126,32 @@ def cpu_baseline(layer, Wt, target_s: float):
         s = oracle.Shape(n, layer.C, layer.H, layer.W, layer.F, layer.kh, layer.kw,
                          layer.sh, layer.sw, layer.ph, layer.pw)
         t0 = time.perf_counter()
-        oracle.forward(I, Wt, s)
-        return time.perf_counter() - t0
+        res = oracle.forward(I, Wt, s)
+        return time.perf_counter() - t0, res
 
-    t1 = run(1)
+    t1, res = run(1)
     n = max(1, min(layer.N, int(target_s / max(t1, 1e-3))))
-    t = run(n) if n > 1 else t1
+    t = t1
+    if n > 1:
+        t, res = run(n)
     macs = layer.binary_macs // layer.N * n
-    return {"value": macs / t / 1e9, "unit": "binary GMAC/s", "cores": oracle.threads(), "kind": "oracle",
+    base = {"value": macs / t / 1e9, "unit": "binary GMAC/s", "cores": oracle.threads(), "kind": "oracle",
             "sample": f"first {n} of {layer.N} images of {layer.name}, all {layer.F} filters, whole forward "
                       f"pass (sign conv + K + alpha + rescale), {t:.2f} s"}
+    parity = None
+    if gpu_out is not None:
+        d_ref, _, _, O_ref = res
+        got = gpu_out[:n].cpu().numpy().astype(np.float64)
+        ref = O_ref.astype(np.float64)
+        err = np.abs(got - ref)
+        nz = ref != 0
+        rel = np.zeros_like(err)
+        rel[nz] = err[nz] / np.abs(ref[nz])
+        rel[~nz & (got != 0)] = np.inf
+        parity = {"images": n, "elements": int(ref.size),
+                  "dot_mismatches": int((gpu_dot[:n].cpu().numpy() != d_ref).sum()) if gpu_dot is not None else None,
+                  "worst_rel": float(rel.max()), "outside_1e-5": int((rel > 1e-5).sum())}
+    return base, parity
 
 
 def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
@@ -193,7 +250,7 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
         src = torch.empty((1 << 28,), dtype=torch.float32, device="cuda").normal_()
         dst = torch.empty_like(src)
         for _ in range(3):
-            dst.copy_(src)                     # 1 GiB read + 1 GiB written per copy
+            xb.xnor_probe_copy(src, dst)       # probe_copy_kernel: 1 GiB read + 1 GiB written per launch
         torch.cuda.synchronize()
         del src, dst
 
@@ -247,6 +304,19 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
         graph_ms = (time.perf_counter() - g0) / args.steps * 1e3
         del graph
 
+    # untimed: the convolution once more with the raw dot products as well (for the parity check
+    # against the oracle's sample; the step itself does not write them)
+    dot = None
+    if not args.sweep and not args.chain and not args.no_cpu_baseline:
+        dot = torch.empty((s.N, s.F, OH, OW), dtype=torch.int32, device="cuda")
+        step()
+        if two_phase:
+            xb.xnor_conv2d_fwd_expanded(Ipk, ws, K, alpha, s, out=out, dot=dot) if not k_in_conv else \
+                xb.xnor_conv2d_fwd_expanded_from_A(Ipk, ws, A, alpha, s, out=out, dot=dot)
+        else:
+            xb.xnor_conv2d_fwd(Ipk, Wpk, K, alpha, s, out=out, dot=dot, algo=algo, workspace=ws)
+        torch.cuda.synchronize()
+
     ms_per_step = elapsed / args.steps * 1e3
     stage_ms = {n: sum(m[i].elapsed_time(m[i + 1]) for m in events) / len(events) for i, n in enumerate(names)}
     conv_times = sorted(a.elapsed_time(b) for a, b in conv_events)
@@ -263,9 +333,9 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
         roof = {"bound": "alu", "achieved": achieved, "peak": PEAK_VALU_POPCOUNT_TOPS, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
     # HBM bytes per conv launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (scaled by a
-    # plain 1 GiB copy): measured offline, see profiles/forward_c5_hbm_traffic_pmc.md; other
-    # workloads / kernels have no counter run yet
-    roof["traffic"] = MEASURED_CONV_TRAFFIC_BYTES.get((layer.name, xb.ALGO_NAMES[used_algo]))
+    # plain copy of known size), read from the tracked summary; null where no reading of this
+    # kernel as it stands exists
+    roof["traffic"], roof["traffic_note"] = measured_conv_traffic(layer.name, xb.ALGO_NAMES[used_algo])
     roof["kernel"] = ("matrix-core convolution kernel (xnor_conv2d_fwd_expanded" + ("_from_A" if k_in_conv else "") + ")") if two_phase else f"xnor_conv2d_fwd[{xb.ALGO_NAMES[used_algo]}]"
     roof["kernel_ms"] = conv_ms                                # mean over the timed steps (what `achieved` uses)
     roof["kernel_ms_median"] = conv_times[len(conv_times) // 2]
@@ -276,6 +346,13 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
     conv_bytes = 4.0 * (Ipk.numel() + Wpk.numel() + K.numel() + alpha.numel() + out.numel())
     roof["hbm_gbs"] = conv_bytes / (conv_ms * 1e-3) / 1e9
     roof["hbm_frac"] = roof["hbm_gbs"] / PEAK_HBM_GBS
+
+    # the whole step against the HBM roof: the fp32 input read once, the packed input written and
+    # read once, the fp32 output written once (filters, K and alpha are under 3 % of that)
+    step_bytes = 4.0 * (dI.numel() + 2 * Ipk.numel() + out.numel())
+    step_roof = {"bound": "hbm", "achieved": step_bytes / (ms_per_step * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                 "unit": "GB/s", "algorithmic_bytes": step_bytes, "floor_ms": step_bytes / PEAK_HBM_GBS / 1e6}
+    step_roof["frac"] = step_roof["achieved"] / PEAK_HBM_GBS
 
     rec = {
         "metric": ("binary GMAC/s, chained layer (XNOR conv taking packed signs + channel mean and expanded filters, emitting packed signs + channel mean for the next layer)" if args.chain
@@ -294,9 +371,11 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
         "stage_ms": stage_ms,
         **({"graph_ms_per_step": graph_ms, "graph_replays_match_eager": graph_ok} if graph_ms is not None else {}),
         "roofline": roof,
+        **({} if args.chain else {"step_roofline": step_roof}),
     }
     rec["_Wt_host"] = Wt_host
-    del dI, out
+    rec["_out"], rec["_dot"] = (out, dot) if dot is not None else (None, None)
+    del dI
     return rec
 
 
@@ -474,8 +553,48 @@ def run_image(args, xb, torch, side):
     return rec
 
 
+def run_peaks(args, xb, torch):
+    """The ceilings this GPU sustains, each timed with events on the launch stream over repeated
+    launches: the FP4 matrix instruction in registers, the v_xor + v_bcnt pair in registers, and a
+    plain copy at a size the last-level cache holds and at one it does not."""
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e-3
+
+    sink_f = torch.zeros((4,), dtype=torch.float32, device="cuda")
+    sink_i = torch.zeros((4,), dtype=torch.int32, device="cuda")
+    out = {"metric": "measured ceilings of this GPU (not the benchmark line)", "n_gpus": 1}
+    for wgs in (512, 1024):      # two and four 4-wave workgroups per compute unit
+        flops = [0.0]
+        t = timed(lambda: flops.__setitem__(0, xb.xnor_probe_mfma_fp4(wgs, 4000, sink_f)), 5)
+        out[f"mfma_fp4_tflops_{wgs}wg"] = flops[0] / t / 1e12
+    out["mfma_fp4_published_tflops"] = PEAK_FP4_MFMA_TFLOPS
+    macs = [0.0]
+    t = timed(lambda: macs.__setitem__(0, xb.xnor_probe_xor_popcount(256 * 8, 20000, sink_i)), 5)
+    out["xor_popcount_binary_tops"] = 2.0 * macs[0] / t / 1e12
+    out["xor_popcount_derived_peak_tops"] = PEAK_VALU_POPCOUNT_TOPS
+    for mib in (64, 1024):
+        src = torch.empty((mib << 18,), dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        t = timed(lambda: xb.xnor_probe_copy(src, dst), 10)
+        out[f"copy_{mib}MiB_gbs_read_plus_write"] = 2.0 * (mib << 20) / t / 1e9
+        del src, dst
+    out["hbm_published_gbs"] = PEAK_HBM_GBS
+    return out
+
+
 def main():
     args = parse()
+    if args.print_conv_digest:
+        print(conv_source_digest())
+        return
     world = int(os.environ.get("WORLD_SIZE", "1"))
     if args.gpus != 1 or world != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -490,6 +609,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    if args.peaks:
+        print(json.dumps(run_peaks(args, xb, torch)), flush=True)
+        return
     if args.image:
         for side in (int(v) for v in args.image_sides.split(",")):
             print(json.dumps(run_image(args, xb, torch, side)), flush=True)
@@ -504,13 +626,14 @@ def main():
         for aname in algos:
             rec = run_layer(args, xb, torch, LAYERS[lname], aname, make_input, make_weights)
             Wt_host = rec.pop("_Wt_host")
+            gpu_out, gpu_dot = rec.pop("_out"), rec.pop("_dot")
             if args.sweep:
                 print(json.dumps(rec), flush=True)
     if args.sweep:
         return
     layer = LAYERS[args.layer]
     if not args.no_cpu_baseline:
-        rec["cpu_baseline"] = cpu_baseline(layer, Wt_host, args.cpu_seconds)
+        rec["cpu_baseline"], rec["parity"] = cpu_baseline(layer, Wt_host, args.cpu_seconds, gpu_out, gpu_dot)
     print(json.dumps(rec), flush=True)
 
 

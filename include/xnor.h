@@ -307,6 +307,27 @@ int xnor_conv2d_fwd_static(const uint32_t *Ipk, const uint32_t *Wpk, const float
  * workspace (an xnor_algo), or a negative status. */
 int xnor_conv2d_pick_algo(const xnor_shape *s, size_t workspace_bytes);
 
+/*
+ * Measurement probes (no part of the forward pass): what the GPU at hand sustains on the resources
+ * the kernels above are priced against, for reading a roofline fraction against a measured
+ * ceiling beside the published one.  Each enqueues one kernel on `stream` and returns; the caller
+ * times it with events.
+ *   xnor_probe_mfma_fp4      `workgroups` x 4 waves each run `iters` x 8 register-only
+ *                            v_mfma_f32_32x32x64_f8f6f4 (both operands FP4 +-1, the convolution's
+ *                            instruction); *flops receives the flops issued (2 per multiply-add)
+ *   xnor_probe_xor_popcount  `workgroups` x 256 lanes each run `iters` x 8 register-only
+ *                            v_xor_b32 + v_bcnt_u32_b32 pairs; *binary_macs receives 32 per lane
+ *                            and pair
+ *   xnor_probe_copy          copies `bytes` (a multiple of 16; both pointers 16-byte aligned) from
+ *                            src to dst, 16 bytes per lane
+ * `sink` (device, 4 bytes) is never written in practice; it keeps the loops alive.  `flops` and
+ * `binary_macs` are host pointers.  XNOR_E_SHAPE for counts <= 0 or beyond 2^20 workgroups /
+ * 2^24 iterations, or a byte count that is 0 or no multiple of 16.
+ */
+int xnor_probe_mfma_fp4(int workgroups, int iters, float *sink, double *flops, void *stream);
+int xnor_probe_xor_popcount(int workgroups, int iters, uint32_t *sink, double *binary_macs, void *stream);
+int xnor_probe_copy(const void *src, void *dst, size_t bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

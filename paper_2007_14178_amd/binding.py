@@ -89,6 +89,10 @@ def _load() -> ctypes.CDLL:
     L.xnor_conv2d_fwd_algo.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, ci, vp]
     L.xnor_conv2d_fwd_static.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp]
     L.xnor_filter_expand.argtypes = [vp, sp, vp, sz, vp]
+    dp = ctypes.POINTER(ctypes.c_double)
+    L.xnor_probe_mfma_fp4.argtypes = [ci, ci, vp, dp, vp]
+    L.xnor_probe_xor_popcount.argtypes = [ci, ci, vp, dp, vp]
+    L.xnor_probe_copy.argtypes = [vp, vp, sz, vp]
     L.xnor_conv2d_fwd_expanded.argtypes = [vp, vp, sz, vp, vp, sp, vp, vp, vp]
     L.xnor_conv2d_fwd_expanded_from_A.argtypes = [vp, vp, sz, vp, vp, sp, vp, vp, vp]
     L.xnor_box_filter_K.argtypes = [vp, sp, vp, vp]
@@ -110,7 +114,8 @@ def _load() -> ctypes.CDLL:
                  "xnor_forward_image_supported", "xnor_forward_image",
                  "xnor_bwn_conv2d_fwd", "xnor_bwn_conv2d_fwd_algo",
                  "xnor_conv2d_fwd_expanded_from_A", "xnor_conv2d_fwd_chain_from_A",
-                 "xnor_conv2d_fwd_chain_expanded_from_A", "xnor_prepare", "xnor_conv2d_fwd_static"):
+                 "xnor_conv2d_fwd_chain_expanded_from_A", "xnor_prepare", "xnor_conv2d_fwd_static",
+                 "xnor_probe_mfma_fp4", "xnor_probe_xor_popcount", "xnor_probe_copy"):
         getattr(L, name).restype = ci
     return L
 
@@ -313,6 +318,32 @@ def xnor_conv2d_fwd_static(Ipk: torch.Tensor, Wpk: torch.Tensor, K: torch.Tensor
         _dev(dot, torch.int32, oshape, "dot") if dot is not None else None, _stream()),
         "xnor_conv2d_fwd_static")
     return out, dot
+
+
+def xnor_probe_mfma_fp4(workgroups: int, iters: int, sink: torch.Tensor) -> float:
+    """Enqueues the register-only FP4 matrix-instruction loop; returns the flops it issues."""
+    n = ctypes.c_double(0.0)
+    _ok(lib.xnor_probe_mfma_fp4(workgroups, iters, _dev(sink, torch.float32, name="sink"), ctypes.byref(n), _stream()),
+        "xnor_probe_mfma_fp4")
+    return n.value
+
+
+def xnor_probe_xor_popcount(workgroups: int, iters: int, sink: torch.Tensor) -> float:
+    """Enqueues the register-only v_xor + v_bcnt loop; returns the binary multiply-accumulates it issues."""
+    n = ctypes.c_double(0.0)
+    _ok(lib.xnor_probe_xor_popcount(workgroups, iters, _dev(sink, torch.int32, name="sink"), ctypes.byref(n), _stream()),
+        "xnor_probe_xor_popcount")
+    return n.value
+
+
+def xnor_probe_copy(src: torch.Tensor, dst: torch.Tensor) -> int:
+    """Enqueues the plain copy kernel over the whole of ``src``; returns the bytes copied."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("xnor_probe_copy: src and dst differ in size")
+    _ok(lib.xnor_probe_copy(_dev(src, src.dtype, name="src"), _dev(dst, dst.dtype, name="dst"), nbytes, _stream()),
+        "xnor_probe_copy")
+    return nbytes
 
 
 def xnor_filter_expand(Wpk: torch.Tensor, s: Shape, workspace: torch.Tensor | None = None) -> torch.Tensor:

@@ -1,0 +1,123 @@
+// Measurement probes: what this GPU sustains on the three resources the forward pass is priced
+// against, so that a roofline fraction can be read against a measured ceiling next to the published
+// one.  None of them is part of the forward pass.
+//   * probe_mfma_fp4_kernel      register-only loop of the FP4 matrix instruction the convolution
+//                                uses (v_mfma_f32_32x32x64_f8f6f4, both operands FP4), eight
+//                                independent accumulators per wave, no memory traffic
+//   * probe_xor_popcount_kernel  register-only loop of v_xor_b32 + v_bcnt_u32_b32 pairs (32 binary
+//                                multiply-accumulates per lane and pair), eight independent chains
+//   * probe_copy_kernel          plain 16-byte-per-lane device copy
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "xnor.h"
+
+namespace {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int kMfmaPerIter = 8;      // two A operands x four B operands
+constexpr int kPairsPerIter = 8;
+
+// E2M1 nibbles: 0x2 = +1, 0xA = -1.  Every operand register holds +-1 values with lane-dependent
+// signs (the multiplier's inputs toggle as they do in the convolution, not constants).
+__global__ __launch_bounds__(256) void probe_mfma_fp4_kernel(int iters, float *sink)
+{
+    v16f acc[kMfmaPerIter];
+    for (int j = 0; j < kMfmaPerIter; ++j)
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+    unsigned x = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;
+    v8i A[2], B[4];
+    for (int i = 0; i < 2; ++i) {
+        A[i] = v8i{0, 0, 0, 0, 0, 0, 0, 0};
+        for (int w = 0; w < 4; ++w) { x = x * 1664525u + 1013904223u; A[i][w] = (int)(0x22222222u | (x & 0x88888888u)); }
+    }
+    for (int i = 0; i < 4; ++i) {
+        B[i] = v8i{0, 0, 0, 0, 0, 0, 0, 0};
+        for (int w = 0; w < 4; ++w) { x = x * 1664525u + 1013904223u; B[i][w] = (int)(0x22222222u | (x & 0x88888888u)); }
+    }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[i * 4 + j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                    A[i], B[j], acc[i * 4 + j], 4, 4, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+    }
+    float s = 0.f;
+    for (int j = 0; j < kMfmaPerIter; ++j)
+        for (int r = 0; r < 16; ++r) s += acc[j][r];
+    // (sums of +-1 products are integers: the store never happens, but the compiler cannot know)
+    if (s == 0.5f) sink[0] = s;
+}
+
+__global__ __launch_bounds__(256) void probe_xor_popcount_kernel(int iters, uint32_t *sink)
+{
+    uint32_t acc[kPairsPerIter], a[kPairsPerIter], w[kPairsPerIter];
+    uint32_t x = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 977u;
+    for (int j = 0; j < kPairsPerIter; ++j) {
+        acc[j] = 0;
+        x = x * 1664525u + 1013904223u; a[j] = x;
+        x = x * 1664525u + 1013904223u; w[j] = x;
+    }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < kPairsPerIter; ++j) {
+            uint32_t t;
+            asm volatile("v_xor_b32 %0, %2, %3\n\tv_bcnt_u32_b32 %1, %0, %1"
+                         : "=&v"(t), "+v"(acc[j])
+                         : "v"(a[j]), "v"(w[j]));
+        }
+    }
+    uint32_t s = 0;
+    for (int j = 0; j < kPairsPerIter; ++j) s += acc[j];
+    if (s == 0xffffffffu) sink[0] = s;   // (a count of at most 32 * iters * 8 per lane: never)
+}
+
+__global__ __launch_bounds__(256) void probe_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst,
+                                                         long long n16)
+{
+    const long long stride = (long long)gridDim.x * 256;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+int status(hipError_t e) { return e == hipSuccess ? XNOR_OK : XNOR_E_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+int xnor_probe_mfma_fp4(int workgroups, int iters, float *sink, double *flops, void *stream)
+{
+    if (!sink || !flops) return XNOR_E_NULL;
+    if (workgroups <= 0 || iters <= 0 || workgroups > (1 << 20) || iters > (1 << 24)) return XNOR_E_SHAPE;
+    probe_mfma_fp4_kernel<<<dim3(workgroups), dim3(256), 0, (hipStream_t)stream>>>(iters, sink);
+    // 4 waves per workgroup, 32 x 32 x 64 multiply-accumulates per instruction, 2 flops each
+    *flops = (double)workgroups * 4.0 * iters * kMfmaPerIter * (32.0 * 32.0 * 64.0) * 2.0;
+    return status(hipGetLastError());
+}
+
+int xnor_probe_xor_popcount(int workgroups, int iters, uint32_t *sink, double *binary_macs, void *stream)
+{
+    if (!sink || !binary_macs) return XNOR_E_NULL;
+    if (workgroups <= 0 || iters <= 0 || workgroups > (1 << 20) || iters > (1 << 24)) return XNOR_E_SHAPE;
+    probe_xor_popcount_kernel<<<dim3(workgroups), dim3(256), 0, (hipStream_t)stream>>>(iters, sink);
+    *binary_macs = (double)workgroups * 256.0 * iters * kPairsPerIter * 32.0;
+    return status(hipGetLastError());
+}
+
+int xnor_probe_copy(const void *src, void *dst, size_t bytes, void *stream)
+{
+    if (!src || !dst) return XNOR_E_NULL;
+    if (bytes == 0 || bytes % 16 != 0) return XNOR_E_SHAPE;
+    if (((uintptr_t)src | (uintptr_t)dst) & 15) return XNOR_E_ALIGN;
+    const long long n16 = (long long)(bytes / 16);
+    const long long want = (n16 + 255) / 256;
+    const int grid = (int)(want < 256 * 32 ? want : 256 * 32);   // up to 32 workgroups per compute unit, grid-stride beyond
+    probe_copy_kernel<<<dim3(grid), dim3(256), 0, (hipStream_t)stream>>>(static_cast<const uint4 *>(src),
+                                                                           static_cast<uint4 *>(dst), n16);
+    return status(hipGetLastError());
+}
+
+}  // extern "C"
