@@ -845,9 +845,10 @@ __global__ __launch_bounds__(512) void conv_mfma_persistent_kernel(PParams p)
     const int nslot = 2 * p.wgs_per_xcd;
 #endif
 
-    // the first group releases the second one at turn `sturn` of its first item (-1: not, or done)
+    // the first group releases the second one at turn `sturn` of its first item (-1: not, or done);
+    // with start_turn < 0 both start at once
     int sturn = grp == 0 ? p.start_turn : -1;
-    if (grp == 1) wait_count(start_addr, 1u);
+    if (grp == 1 && p.start_turn >= 0) wait_count(start_addr, 1u);
 
     typedef typename WordVec<VW>::type wvec;
     const int CHV = p.CH / VW;
@@ -873,6 +874,9 @@ __global__ __launch_bounds__(512) void conv_mfma_persistent_kernel(PParams p)
             int half;
             const int item = item_of(seq, half);
             const int ft = __builtin_amdgcn_readfirstlane(item / p.bands_per_xcd);
+            // an upper half without filters has nothing to write (the chained form's per-tile sums
+            // are read for every 32-filter tile, so there it writes its zeros)
+            if (!CHAIN && half == 1 && ft * kFilterTile + kFilterTile / 2 >= p.F) continue;
             if (xcd * p.bands_per_xcd + (item - ft * p.bands_per_xcd) < p.nbands) return seq;
         }
         return -1;
@@ -1469,17 +1473,27 @@ hipError_t launch_conv_mfma_persistent(const uint32_t *Ipk, const float *K, cons
     p.nbands = ceil_div(p.total_rows, pl.TH);
     p.bands_per_xcd = ceil_div(p.nbands, kXcds);
     p.items_per_xcd = p.bands_per_xcd * pl.f_tiles;
-    // one workgroup per compute unit; fewer where an XCD has less than one half item per group
+    // One workgroup per compute unit, two groups each: 2 * CUs slots per XCD.
     const int cus_per_xcd = std::max(1, compute_units(dev) / kXcds);
-    p.wgs_per_xcd = std::min(cus_per_xcd, p.items_per_xcd);
-    // the items beyond the last whole round of the XCD's groups go out as half items when that
-    // spreads them over more groups (the kernel's length is that of its busiest compute unit)
-    {
+    if (p.items_per_xcd < 2 * cus_per_xcd) {
+        // A layer that does not give every group an item: as many items as the slots allow go out
+        // as two half items, spread over the compute units first and over their second groups
+        // after that, and all groups start at once (the kernel's length is that of one unit).
+        p.whole_items = std::max(0, 2 * p.items_per_xcd - 2 * cus_per_xcd);
+        p.work_per_xcd = p.whole_items + 2 * (p.items_per_xcd - p.whole_items);
+        p.wgs_per_xcd = std::min(cus_per_xcd, p.work_per_xcd);
+        p.start_turn = -1;
+    } else {
+        // Several rounds: the items beyond the last whole round go out as half items when that
+        // spreads them over more groups (the kernel's length is that of its busiest compute
+        // unit), and the second groups start half an item late, so that one group's epilogue
+        // and set-up fall into the other's matrix loop.
+        p.wgs_per_xcd = cus_per_xcd;
         const int nslot = 2 * p.wgs_per_xcd, rem = p.items_per_xcd % nslot;
         p.whole_items = (rem > 0 && 2 * rem <= nslot) ? p.items_per_xcd - rem : p.items_per_xcd;
         p.work_per_xcd = p.whole_items + 2 * (p.items_per_xcd - p.whole_items);
+        p.start_turn = pl.nturns / 2;
     }
-    p.start_turn = pl.nturns / 2;
     p.prio_mask = 7;
 #ifdef XNOR_TS_BUILD
     {
