@@ -7,7 +7,8 @@ with ctypes and marshals numpy arrays.
 
 Function names follow the paper's pipeline (Sec. III-A step list): ``sign`` / ``pack`` (step 1a),
 ``dot`` (steps 1b-1d), ``scale_K`` (Eq. 10), ``alpha`` (Eq. 5), ``out`` / ``forward`` (Eq. 11);
-``bwn`` is the Binary-Weight-Network layer of Sec. II-A (Eq. 1).
+``bwn`` is the Binary-Weight-Network layer of Sec. II-A (Eq. 1); ``conv_fp32`` is the real-valued
+convolution that Table I (Sec. IV) compares the XNOR convolution with.
 """
 from __future__ import annotations
 
@@ -88,6 +89,8 @@ def _load():
         lib.oracle_out.restype = None
         lib.oracle_bwn.argtypes = [fp, fp, sp, fp, fp, dp]
         lib.oracle_bwn.restype = ci
+        lib.oracle_conv_fp32.argtypes = [fp, fp, sp, fp, dp]
+        lib.oracle_conv_fp32.restype = ci
         _lib = lib
     return _lib
 
@@ -208,5 +211,21 @@ def bwn(I, Wt, s: Shape, want_scale: bool = False):
     if _load().oracle_bwn(_ptr(I, ctypes.c_float), _ptr(Wt, ctypes.c_float), ctypes.byref(s.c()),
                           _ptr(a, ctypes.c_float), _ptr(O, ctypes.c_float),
                           _ptr(S, ctypes.c_double) if want_scale else None):
+        raise ValueError(f"bad shape {s}")
+    return (O, S) if want_scale else O
+
+
+def conv_fp32(I, Wt, s: Shape, want_scale: bool = False):
+    """Real-valued convolution (the float comparison of Table I, Sec. IV): O = sum I * Wt over channels
+    and in-image taps, fp32 [N][F][OH][OW], summed in double.
+
+    With ``want_scale`` also returns S[N][F][OH][OW] = sum |I * Wt| over the same terms (double)."""
+    I, Wt = _f32(I), _f32(Wt)
+    _check(I, Wt, s)
+    OH, OW = out_dims(s)
+    O = np.empty((s.N, s.F, OH, OW), dtype=np.float32)
+    S = np.empty((s.N, s.F, OH, OW), dtype=np.float64) if want_scale else None
+    if _load().oracle_conv_fp32(_ptr(I, ctypes.c_float), _ptr(Wt, ctypes.c_float), ctypes.byref(s.c()),
+                                _ptr(O, ctypes.c_float), _ptr(S, ctypes.c_double) if want_scale else None):
         raise ValueError(f"bad shape {s}")
     return (O, S) if want_scale else O

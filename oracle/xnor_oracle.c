@@ -18,6 +18,8 @@
  *   - bit encoding: bit 1 <=> +1, bit 0 <=> -1         : Sec. III-A step 1c
  *   - Binary-Weight-Network layer, real input and
  *     binary weights: (I (+) B) alpha, B = sign(W)     : Sec. II-A, Eq. 1 (with Eq. 5 for alpha)
+ *   - real-valued convolution, the float comparison
+ *     of the timings (sum of I * W, nothing binarised) : Sec. IV, Table I
  *
  * The method reaches its target exactly (the bit encoding is a trick, not an approximation of the
  * sign convolution), so the oracle is the plain definition: a direct float convolution on +-1
@@ -250,19 +252,43 @@ int oracle_bwn(const float *I, const float *Wt, const oracle_shape *s, const flo
     return 0;
 }
 
-/* Whole forward pass in the pipeline's order; any of dot/K/alpha/O may be NULL except dot, K and
- * alpha when O is wanted.  Returns 0, or -1 on a bad shape. */
-int oracle_forward(const float *I, const float *Wt, const oracle_shape *s, double *A_scratch,
-                   int32_t *dot, float *K, float *alpha, float *O)
+/*
+ * Real-valued ("vanilla") convolution: the float comparison that Sec. IV's Table I sets the XNOR
+ * convolution against.  Input and weights keep their values:
+ *     O[n][f][oy][ox] = sum_{c, in-image taps} I[n][c][iy][ix] * Wt[f][c][ky][kx],
+ * cross-correlation (no kernel flip), zero padding and stride as in the XNOR path, no alpha and no
+ * K.  Every product of two floats is exact in double; they are added in double in the plain loop
+ * order (c, ky, kx) and the sum is rounded once to float.  S (optional) receives sum |I * Wt| over
+ * the same terms, in double: the scale against which a float implementation's summation error is
+ * measured.
+ */
+int oracle_conv_fp32(const float *I, const float *Wt, const oracle_shape *s, float *O, double *S)
 {
     int OH, OW;
     if (oracle_out_dims(s, &OH, &OW)) return -1;
-    if (dot && oracle_dot(I, Wt, s, dot)) return -1;
-    if (K && oracle_K(I, s, A_scratch, K)) return -1;
-    if (alpha) oracle_alpha(Wt, s->F, s->C, s->kh, s->kw, alpha);
-    if (O) {
-        if (!dot || !K || !alpha) return -1;
-        oracle_out(dot, K, alpha, s->N, s->F, OH, OW, O);
-    }
+    const int N = s->N, C = s->C, H = s->H, W = s->W, F = s->F, kh = s->kh, kw = s->kw;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int f = 0; f < F; ++f)
+            for (int oy = 0; oy < OH; ++oy)
+                for (int ox = 0; ox < OW; ++ox) {
+                    double acc = 0.0, mag = 0.0;
+                    for (int c = 0; c < C; ++c)
+                        for (int ky = 0; ky < kh; ++ky) {
+                            const int iy = oy * s->sh - s->ph + ky;
+                            if (iy < 0 || iy >= H) continue;
+                            for (int kx = 0; kx < kw; ++kx) {
+                                const int ix = ox * s->sw - s->pw + kx;
+                                if (ix < 0 || ix >= W) continue;
+                                const double t = (double)I[(((size_t)n * C + c) * H + iy) * W + ix] *
+                                                 (double)Wt[(((size_t)f * C + c) * kh + ky) * kw + kx];
+                                acc += t;
+                                mag += t < 0.0 ? -t : t;
+                            }
+                        }
+                    const size_t o = (((size_t)n * F + f) * OH + oy) * OW + ox;
+                    O[o] = (float)acc;
+                    if (S) S[o] = mag;
+                }
     return 0;
 }

@@ -125,6 +125,7 @@ def test_hand_worked_fixture(case):
     np.testing.assert_allclose(K, np.array(case["K"]), rtol=1e-7)
     np.testing.assert_allclose(O, np.array(case["O"]), rtol=2e-7)
     assert np.array_equal(oracle.bwn(I, Wt, s), np.array(case["O_bwn"], dtype=np.float32))
+    assert np.array_equal(oracle.conv_fp32(I, Wt, s), np.array(case["O_conv"], dtype=np.float32))
 
 
 # ----------------------------------------------------------------------------------------------
@@ -414,3 +415,95 @@ def test_bwn_closed_forms_and_invariants():
     assert (np.abs(lhs - rhs) <= 2.0 ** -21 * scale).all()
     # |O| <= alpha * sum |I| over the window
     assert (np.abs(O) <= a * l1 * (1 + 1e-6)).all()
+
+
+# ----------------------------------------------------------------------------------------------
+# real-valued convolution (the float comparison of Table I)
+# ----------------------------------------------------------------------------------------------
+def window_l1_products(I, Wt, s: Shape):
+    """sum |I * Wt| over each output's terms: unfold |I| and multiply by |Wt| (double)."""
+    OH, OW = out_hw(s)
+    P = np.zeros((s.N, s.C, s.H + 2 * s.ph, s.W + 2 * s.pw))
+    P[:, :, s.ph:s.ph + s.H, s.pw:s.pw + s.W] = np.abs(I.astype(np.float64))
+    cols = np.empty((s.N, OH, OW, s.C, s.kh, s.kw))
+    for oy in range(OH):
+        for ox in range(OW):
+            cols[:, oy, ox] = P[:, :, oy * s.sh:oy * s.sh + s.kh, ox * s.sw:ox * s.sw + s.kw]
+    M = cols.reshape(s.N * OH * OW, -1) @ np.abs(Wt.astype(np.float64)).reshape(s.F, -1).T
+    return M.reshape(s.N, OH, OW, s.F).transpose(0, 3, 1, 2)
+
+
+@pytest.mark.parametrize("s", ASYM_SHAPES, ids=str)
+def test_conv_fp32_against_torch_cpu(s):
+    """torch's fp64 conv2d is an independent library routine of the same definition."""
+    I, Wt = rand_case(_h(("conv", s)), s)
+    ref = torch.nn.functional.conv2d(torch.from_numpy(I.astype(np.float64)), torch.from_numpy(Wt.astype(np.float64)),
+                                     stride=(s.sh, s.sw), padding=(s.ph, s.pw)).numpy()
+    O, S = oracle.conv_fp32(I, Wt, s, want_scale=True)
+    l1 = window_l1_products(I, Wt, s)
+    np.testing.assert_allclose(S, l1, rtol=1e-12, atol=1e-300)
+    # both sides sum in double; what differs is the order and the oracle's final rounding to fp32
+    assert (np.abs(O - ref) <= 2.0 ** -23 * np.abs(ref) + 1e-13 * l1).all()
+
+
+def test_conv_fp32_brute_force_tiny():
+    """Every output of a tiny case from the definition, in exact rational arithmetic."""
+    from fractions import Fraction
+    s = Shape(2, 3, 4, 5, 2, 3, 2, 2, 1, 1, 1)
+    I, Wt = rand_case(11, s)
+    OH, OW = out_hw(s)
+    O = oracle.conv_fp32(I, Wt, s)
+    for n, f, oy, ox in itertools.product(range(s.N), range(s.F), range(OH), range(OW)):
+        acc = Fraction(0)
+        for c, ky, kx in itertools.product(range(s.C), range(s.kh), range(s.kw)):
+            iy, ix = oy * s.sh - s.ph + ky, ox * s.sw - s.pw + kx
+            if 0 <= iy < s.H and 0 <= ix < s.W:
+                acc += Fraction(float(I[n, c, iy, ix])) * Fraction(float(Wt[f, c, ky, kx]))
+        assert abs(float(O[n, f, oy, ox]) - float(acc)) <= 2.0 ** -23 * abs(float(acc)) + 1e-30
+
+
+def test_conv_fp32_reduces_to_the_other_two_convolutions():
+    """On +-1 inputs and weights it is the sign convolution (Eq. 11's first factor); with weights
+    alpha * sign(W) it is the Binary-Weight-Network layer (Eq. 1)."""
+    s = Shape(2, 37, 6, 5, 4, 3, 2, 2, 1, 1, 1)
+    I, Wt = rand_case(78, s, zeros=False)
+    Ib = np.where(I >= 0, 1.0, -1.0).astype(np.float32)
+    Wb = np.where(Wt >= 0, 1.0, -1.0).astype(np.float32)
+    assert np.array_equal(oracle.conv_fp32(Ib, Wb, s), oracle.dot(I, Wt, s).astype(np.float32))
+    a = oracle.alpha(Wt)
+    Wa = (Wb * a[:, None, None, None]).astype(np.float32)       # exact: +-alpha
+    O = oracle.conv_fp32(I, Wa, s).astype(np.float64)
+    B = oracle.bwn(I, Wt, s).astype(np.float64)
+    assert (np.abs(O - B) <= 2.0 ** -22 * np.abs(B) + 1e-12).all()
+
+
+def test_conv_fp32_closed_forms_and_invariants():
+    s = Shape(2, 5, 6, 7, 3, 3, 3, 1, 1, 1, 1)
+    OH, OW = out_hw(s)
+    taps = np_K(np.ones((s.N, s.C, s.H, s.W), dtype=np.float32), s) * 9     # number of in-image taps
+    cI = np.full((s.N, s.C, s.H, s.W), 2.5, dtype=np.float32)
+    cW = np.full((s.F, s.C, s.kh, s.kw), -0.75, dtype=np.float32)
+    want = np.broadcast_to((2.5 * -0.75 * s.C * taps)[:, None], (s.N, s.F, OH, OW)).astype(np.float32)
+    assert np.array_equal(oracle.conv_fp32(cI, cW, s), want)
+    # a filter that is 1 at one tap of one channel copies that channel, shifted (cross-correlation:
+    # tap (ky, kx) reads the pixel at (oy - ph + ky, ox - pw + kx)); outside the image it reads zero
+    I, Wt = rand_case(12, s)
+    d = np.zeros_like(Wt); d[0, 3, 0, 2] = 1.0                   # filter 0: channel 3, tap (0, 2)
+    O = oracle.conv_fp32(I, d, s)
+    shifted = np.zeros((s.N, OH, OW), dtype=np.float32)
+    shifted[:, 1:, :-1] = I[:, 3, :-1, 1:]
+    assert np.array_equal(O[:, 0], shifted) and not O[:, 1:].any()
+    # linear in the input and in the weights; filters are independent of each other
+    I2, W2 = rand_case(13, s)
+    l1 = window_l1_products(I, Wt, s) + window_l1_products(I2, Wt, s) + window_l1_products(I, W2, s)
+    base = oracle.conv_fp32(I, Wt, s).astype(np.float64)
+    lhs = oracle.conv_fp32((2 * I + 0.5 * I2).astype(np.float32), Wt, s).astype(np.float64)
+    assert (np.abs(lhs - (2 * base + 0.5 * oracle.conv_fp32(I2, Wt, s))) <= 2.0 ** -20 * l1).all()
+    lhs = oracle.conv_fp32(I, (Wt - 4 * W2).astype(np.float32), s).astype(np.float64)
+    assert (np.abs(lhs - (base - 4 * oracle.conv_fp32(I, W2, s))) <= 2.0 ** -19 * l1).all()
+    Wp = Wt[[2, 0, 1]]
+    assert np.array_equal(oracle.conv_fp32(I, Wp, s), oracle.conv_fp32(I, Wt, s)[:, [2, 0, 1]])
+    # transposing image and filter transposes the output (a swapped ky / kx index would not)
+    st = Shape(s.N, s.C, s.W, s.H, s.F, s.kw, s.kh, s.sw, s.sh, s.pw, s.ph)
+    Ot = oracle.conv_fp32(np.ascontiguousarray(I.transpose(0, 1, 3, 2)), np.ascontiguousarray(Wt.transpose(0, 1, 3, 2)), st)
+    assert np.array_equal(Ot.transpose(0, 1, 3, 2), oracle.conv_fp32(I, Wt, s))
