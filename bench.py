@@ -15,7 +15,7 @@ Defaults follow the paper's timing protocol (Sec. IV: compute only, mean of 100 
 100 timed steps, buffers allocated and filled before the timed region and reused every step.
 Other modes: --sweep (all layers, both kernels, with HIP-graph replay times), --chain (chained
 layer), --image (the paper's single-channel workload, Tables I-III), --bwn (Binary-Weight-Network
-layer), --unfused (separate pre-stage calls), --peaks (the ceilings this GPU sustains).
+layer), --unfused (separate pre-stage calls), --peaks (the ceilings this GPU sustains), --vanilla (the real-valued convolution beside the XNOR one).
 """
 from __future__ import annotations
 
@@ -96,6 +96,10 @@ def parse():
                     help="the paper's own workload (Tables I-III): one channel, one 3x3 filter, zero padding, "
                          "square images of 256, 512, 1024 and 2048 pixels; one JSON line per size, latency in ms")
     ap.add_argument("--image-sides", default="256,512,1024,2048")
+    ap.add_argument("--vanilla", action="store_true",
+                    help="not the benchmark line: the real-valued fp32 convolution (Table I's comparison column) on "
+                         "--layer beside the XNOR forward pass of the same layer, and on the paper's single-channel "
+                         "images (--image-sides); one JSON line each, with the XNOR-vs-float ratio")
     ap.add_argument("--k-in-conv", action="store_true",
                     help="form K inside the convolution kernel from the channel mean (one launch less, a slower "
                          "convolution) instead of with the box-filter launch of the prepare call")
@@ -454,6 +458,130 @@ def run_bwn(args, xb, torch, layer, make_input, make_weights):
     return rec
 
 
+# Table I (GTX 1080 Ti, mean of 100 runs, compute only), ms: vanilla convolution and XNOR convolution
+PAPER_GPU_VANILLA_MS = {256: 0.062, 512: 0.186, 1024: 0.671, 2048: 2.641}
+
+
+def time_call(torch, fn, warmup, steps):
+    """Mean time of one call in ms, by events on the launch stream, after `warmup` calls."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def run_vanilla_layer(args, xb, torch, layer, make_input, make_weights):
+    """The float comparison on a benchmark layer: xnor_conv2d_fp32_fwd on the fp32 input and weights
+    (nothing to prepare), beside the whole XNOR forward pass of the same layer."""
+    import numpy as np
+    import oracle
+
+    s = xb.Shape(layer.N, layer.C, layer.H, layer.W, layer.F, layer.kh, layer.kw,
+                 layer.sh, layer.sw, layer.ph, layer.pw)
+    OH, OW = xb.xnor_out_dim(s)
+    Wt_host = make_weights(layer)
+    dI = torch.from_numpy(make_input(layer)).cuda()
+    dW = torch.from_numpy(Wt_host).cuda()
+    out = torch.empty((s.N, s.F, OH, OW), dtype=torch.float32, device="cuda")
+    ms = time_call(torch, lambda: xb.xnor_conv2d_fp32_fwd(dI, dW, s, out=out), args.warmup, args.steps)
+    macs = layer.binary_macs                      # the same count of multiply-accumulates, now real-valued
+    achieved = 2.0 * macs / (ms * 1e-3) / 1e12
+    rec = {
+        "metric": "GMAC/s, real-valued fp32 convolution (the float comparison of Table I)",
+        "value": macs / (ms * 1e-3) / 1e9, "unit": "GMAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp32 input and weights, fp32 accumulate (v_mfma_f32_32x32x2_f32)",
+        "data": "synthetic (seeded; shapes and value distributions of the benchmark layer)",
+        "config": {"workload": f"{layer.name} as a real-valued layer: N={layer.N} C={layer.C} {layer.H}x{layer.W} "
+                               f"F={layer.F} {layer.kh}x{layer.kw} stride {layer.sh} pad {layer.ph}", "macs": macs},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                     "kernel": "bwn_mfma_kernel<.., real weights> (xnor_conv2d_fp32_fwd)", "kernel_ms": ms},
+    }
+    if not args.no_cpu_baseline:
+        def run(n):
+            I = make_input(layer, n)
+            osh = oracle.Shape(n, layer.C, layer.H, layer.W, layer.F, layer.kh, layer.kw,
+                               layer.sh, layer.sw, layer.ph, layer.pw)
+            t0 = time.perf_counter()
+            res = oracle.conv_fp32(I, Wt_host, osh, want_scale=True)
+            return time.perf_counter() - t0, res
+        t1, res = run(1)
+        n = max(1, min(layer.N, int(args.cpu_seconds / max(t1, 1e-3))))
+        t = t1
+        if n > 1:
+            t, res = run(n)
+        rec["cpu_baseline"] = {"value": macs // layer.N * n / t / 1e9, "unit": "GMAC/s", "cores": oracle.threads(),
+                               "kind": "oracle", "sample": f"first {n} of {layer.N} images of {layer.name}, all "
+                                                           f"{layer.F} filters, oracle.conv_fp32, {t:.2f} s"}
+        O_ref, S = res
+        err = np.abs(out[:n].cpu().numpy().astype(np.float64) - O_ref.astype(np.float64))
+        rec["parity"] = {"images": n, "elements": int(err.size), "worst_err_over_scale": float((err / np.maximum(S, 1e-300)).max()),
+                         "outside_1e-5_of_scale": int((err > 1e-5 * S).sum()),
+                         "scale": "sum |I * Wt| over the output's terms"}
+    del dI, dW, out
+    # the XNOR forward pass of the same layer (all of it: binarisation, K, alpha, convolution, rescale)
+    sub = argparse.Namespace(**{**vars(args), "no_cpu_baseline": True, "sweep": True, "chain": False})
+    x = run_layer(sub, xb, torch, layer, "auto", make_input, make_weights)
+    rec["xnor_vs_float"] = {"float_conv_ms": ms, "xnor_step_ms": x["ms_per_step"], "xnor_conv_kernel_ms": x["stage_ms"]["conv"],
+                            "speedup_whole_step": ms / x["ms_per_step"], "speedup_conv_only": ms / x["stage_ms"]["conv"],
+                            "paper": "2.57x to 2.69x (Table I: one channel, 3x3, GTX 1080 Ti; another machine and shape, context only)"}
+    return rec
+
+
+def run_vanilla_image(args, xb, torch, side):
+    """The paper's own shape (Table I): one channel, one 3x3 filter, pad 1; the float convolution
+    beside xnor_forward_image on the same image."""
+    import numpy as np
+
+    rng = np.random.default_rng(20200714 * 100 + side)
+    I = rng.standard_normal(size=(1, 1, side, side), dtype=np.float32)
+    Wt = rng.standard_normal(size=(1, 1, 3, 3), dtype=np.float32)
+    s = xb.Shape(1, 1, side, side, 1, 3, 3, 1, 1, 1, 1)
+    dI, dW = torch.from_numpy(I).cuda(), torch.from_numpy(Wt).cuda()
+    out = torch.empty((1, 1, side, side), dtype=torch.float32, device="cuda")
+    Wpk, alpha, _ = xb.xnor_filter_prepare(dW)
+    # both kernels are shorter than a launch: 20 back-to-back launches per HIP-graph replay
+    reps = 20
+    res = {}
+    for name, fn in (("float", lambda: xb.xnor_conv2d_fp32_fwd(dI, dW, s, out=out)),
+                     ("xnor", lambda: xb.xnor_forward_image(dI, Wpk, alpha, s, out=out))):
+        fn()
+        torch.cuda.synchronize()
+        side_stream = torch.cuda.Stream()
+        side_stream.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side_stream):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side_stream):
+                for _ in range(reps):
+                    fn()
+        torch.cuda.current_stream().wait_stream(side_stream)
+        res[name] = time_call(torch, g.replay, 3, args.steps) / reps
+        del g
+    gbs = 8.0 * side * side / (res["float"] * 1e-3) / 1e9
+    return {
+        "metric": "real-valued fp32 convolution latency, one image (the float comparison of Table I)",
+        "value": res["float"], "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["float"], "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": res["float"] / PAPER_GPU_VANILLA_MS[side] if side in PAPER_GPU_VANILLA_MS else None,
+        "baseline_note": "Table I, vanilla column (GTX 1080 Ti, compute only, mean of 100 runs): another machine, context only",
+        "dtype": "fp32", "data": "synthetic (seeded N(0,1) image and filter)",
+        "config": {"workload": f"image {side}x{side}: N=1 C=1 F=1 3x3 stride 1 pad 1 (Table I)", "macs": 9 * side * side},
+        "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+                     "traffic": None, "kernel": "conv_fp32_direct_kernel (xnor_conv2d_fp32_fwd)", "kernel_ms": res["float"],
+                     "timing": f"{reps} back-to-back launches per graph replay, events on the launch stream"},
+        "xnor_vs_float": {"float_conv_ms": res["float"], "xnor_image_kernel_ms": res["xnor"],
+                          "speedup": res["float"] / res["xnor"],
+                          "paper": f"{PAPER_GPU_VANILLA_MS.get(side)} ms vs {PAPER_GPU_XNOR_MS.get(side)} ms on a GTX 1080 Ti (Table I)"},
+    }
+
+
 # Table III's "GPU" column for the XNOR convolution (GTX 1080 Ti, mean of 100 runs, compute only), ms
 PAPER_GPU_XNOR_MS = {256: 0.0237, 512: 0.0692, 1024: 0.2519, 2048: 0.9859}
 
@@ -611,6 +739,11 @@ def main():
     torch.cuda.set_device(0)
     if args.peaks:
         print(json.dumps(run_peaks(args, xb, torch)), flush=True)
+        return
+    if args.vanilla:
+        print(json.dumps(run_vanilla_layer(args, xb, torch, LAYERS[args.layer], make_input, make_weights)), flush=True)
+        for side in (int(v) for v in args.image_sides.split(",")):
+            print(json.dumps(run_vanilla_image(args, xb, torch, side)), flush=True)
         return
     if args.image:
         for side in (int(v) for v in args.image_sides.split(",")):

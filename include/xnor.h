@@ -280,6 +280,26 @@ int xnor_bwn_conv2d_fwd(const float *I, const uint32_t *Wpk, const float *alpha,
 int xnor_bwn_conv2d_fwd_algo(const float *I, const uint32_t *Wpk, const float *alpha,
                              const xnor_shape *s, float *out, int algo, void *stream);
 
+/*
+ * Real-valued ("vanilla") convolution: the float comparison that the paper's timings set the XNOR
+ * convolution against (Sec. IV, Table I).  Nothing is binarised and there are no scaling factors:
+ *     out[n][f][oy][ox] = sum over in-image taps and channels of I * Wt
+ * with zero padding, stride and cross-correlation as in xnor_conv2d_fwd.
+ *   I      in   fp32 [N][C][H][W]
+ *   Wt     in   fp32 [F][C][kh][kw]
+ *   out    out  fp32 [N][F][OH][OW]
+ * Products and sums are fp32 (fp32 matrix-core accumulation, or chains of fp32 partial sums in the
+ * one-thread-per-output kernel); the rounding error is relative to sum |I * Wt| over the window,
+ * not to |out|.  No workspace.  xnor_conv2d_fp32_fwd_algo: XNOR_ALGO_AUTO (the matrix-core kernel
+ * where it takes the shape and the layer has at least 8 filters and 4 channels), XNOR_ALGO_DIRECT
+ * (any shape) or XNOR_ALGO_MFMA (XNOR_E_UNSUPPORTED where the staged input rows and the chunk's
+ * weights, kh*kw x 8 channels x 128 filters, do not fit in 128 KB of LDS, or kh*kw > 64); other
+ * values XNOR_E_UNSUPPORTED.
+ */
+int xnor_conv2d_fp32_fwd(const float *I, const float *Wt, const xnor_shape *s, float *out, void *stream);
+int xnor_conv2d_fp32_fwd_algo(const float *I, const float *Wt, const xnor_shape *s, float *out, int algo,
+                              void *stream);
+
 /* Same as xnor_conv2d_fwd, with the kernel chosen by the caller (tests and measurements run every
  * variant).  Returns XNOR_E_UNSUPPORTED if `algo` cannot run this shape, XNOR_E_WORKSPACE if it
  * needs more workspace than given; XNOR_ALGO_DIRECT runs every shape without workspace. */

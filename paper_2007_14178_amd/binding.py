@@ -104,6 +104,8 @@ def _load() -> ctypes.CDLL:
     L.xnor_forward_image.argtypes = [vp, vp, vp, sp, vp, vp, vp]
     L.xnor_bwn_conv2d_fwd.argtypes = [vp, vp, vp, sp, vp, vp]
     L.xnor_bwn_conv2d_fwd_algo.argtypes = [vp, vp, vp, sp, vp, ci, vp]
+    L.xnor_conv2d_fp32_fwd.argtypes = [vp, vp, sp, vp, vp]
+    L.xnor_conv2d_fp32_fwd_algo.argtypes = [vp, vp, sp, vp, ci, vp]
     L.xnor_conv2d_pick_algo.argtypes = [sp, sz]
     L.xnor_conv2d_workspace_bytes.argtypes = [sp, ctypes.POINTER(sz)]
     for name in ("xnor_out_dim", "xnor_packed_words", "xnor_binarize_pack", "xnor_scale_K",
@@ -115,7 +117,8 @@ def _load() -> ctypes.CDLL:
                  "xnor_bwn_conv2d_fwd", "xnor_bwn_conv2d_fwd_algo",
                  "xnor_conv2d_fwd_expanded_from_A", "xnor_conv2d_fwd_chain_from_A",
                  "xnor_conv2d_fwd_chain_expanded_from_A", "xnor_prepare", "xnor_conv2d_fwd_static",
-                 "xnor_probe_mfma_fp4", "xnor_probe_xor_popcount", "xnor_probe_copy"):
+                 "xnor_probe_mfma_fp4", "xnor_probe_xor_popcount", "xnor_probe_copy",
+                 "xnor_conv2d_fp32_fwd", "xnor_conv2d_fp32_fwd_algo"):
         getattr(L, name).restype = ci
     return L
 
@@ -409,6 +412,20 @@ def xnor_bwn_conv2d_fwd(I: torch.Tensor, Wpk: torch.Tensor, alpha: torch.Tensor,
         _dev(I, torch.float32, (s.N, s.C, s.H, s.W), "I"), _dev(Wpk, torch.int32, (s.F, s.kh, s.kw, s.Cw), "Wpk"),
         _dev(alpha, torch.float32, (s.F,), "alpha"), ctypes.byref(s.c()), _dev(out, torch.float32, oshape, "out"),
         algo, _stream()), f"xnor_bwn_conv2d_fwd[{ALGO_NAMES.get(algo, algo)}]")
+    return out
+
+
+def xnor_conv2d_fp32_fwd(I: torch.Tensor, Wt: torch.Tensor, s: Shape, out: torch.Tensor | None = None,
+                         algo: int = ALGO_AUTO) -> torch.Tensor:
+    """Real-valued convolution (the float comparison of Table I): fp32 input and weights. Returns out."""
+    OH, OW = xnor_out_dim(s)
+    oshape = (s.N, s.F, OH, OW)
+    if out is None:
+        out = torch.empty(oshape, dtype=torch.float32, device=I.device)
+    _ok(lib.xnor_conv2d_fp32_fwd_algo(
+        _dev(I, torch.float32, (s.N, s.C, s.H, s.W), "I"), _dev(Wt, torch.float32, (s.F, s.C, s.kh, s.kw), "Wt"),
+        ctypes.byref(s.c()), _dev(out, torch.float32, oshape, "out"), algo, _stream()),
+        f"xnor_conv2d_fp32_fwd[{ALGO_NAMES.get(algo, algo)}]")
     return out
 
 

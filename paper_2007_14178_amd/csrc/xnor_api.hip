@@ -356,6 +356,33 @@ int xnor_bwn_conv2d_fwd(const float *I, const uint32_t *Wpk, const float *alpha,
     return xnor_bwn_conv2d_fwd_algo(I, Wpk, alpha, s, out, XNOR_ALGO_AUTO, stream);
 }
 
+int xnor_conv2d_fp32_fwd_algo(const float *I, const float *Wt, const xnor_shape *s, float *out, int algo,
+                              void *stream)
+{
+    if (!I || !Wt || !s || !out) return XNOR_E_NULL;
+    xnor::Geom g;
+    const int rc = make_geom(s, &g);
+    if (rc) return rc;
+    if (!aligned(I, 4) || !aligned(Wt, 4) || !aligned(out, 4)) return XNOR_E_ALIGN;
+    // (a few channels or filters leave the matrix tiles mostly empty: one thread per output then)
+    if (algo == XNOR_ALGO_AUTO)
+        algo = (xnor::conv_fp32_mfma_supports(g) && g.F >= 8 && g.C >= 4) ? XNOR_ALGO_MFMA : XNOR_ALGO_DIRECT;
+    switch (algo) {
+        case XNOR_ALGO_DIRECT:
+            return hip_status(xnor::launch_conv_fp32_direct(I, Wt, g, out, (hipStream_t)stream));
+        case XNOR_ALGO_MFMA:
+            if (!xnor::conv_fp32_mfma_supports(g)) return XNOR_E_UNSUPPORTED;
+            return hip_status(xnor::launch_conv_fp32_mfma(I, Wt, g, out, (hipStream_t)stream));
+        default:
+            return XNOR_E_UNSUPPORTED;
+    }
+}
+
+int xnor_conv2d_fp32_fwd(const float *I, const float *Wt, const xnor_shape *s, float *out, void *stream)
+{
+    return xnor_conv2d_fp32_fwd_algo(I, Wt, s, out, XNOR_ALGO_AUTO, stream);
+}
+
 int xnor_conv2d_chain_workspace_bytes(const xnor_shape *s, size_t *bytes)
 {
     if (!s || !bytes) return XNOR_E_NULL;
