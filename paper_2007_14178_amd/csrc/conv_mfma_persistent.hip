@@ -181,43 +181,82 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
 
 #define PX_MFMA(ACC, A, B) "v_mfma_f32_32x32x64_f8f6f4 %[" #ACC "], " A ", " B ", %[" #ACC "] cbsz:4 blgp:4\n\t"
 
-// one step: A operands (a0, a1), pixel operands b0..b3; reads the next step's pixel operands n0..n3
-// at table entry `bo_r`, the table entry two steps ahead into `bo_w` (table offset toff), and the
-// filter operands three steps ahead into (l0, l1) at ring offset goff
-#define PX_STEP_HEAD(a0, a1, b0, b1, b2, b3, n0, n1, n2, n3, bo_w, bo_r, toff)                          \
-    "s_waitcnt vmcnt(5) lgkmcnt(3)\n\t"                                                                 \
-    PX_MFMA(acc00, a0, b0)                                                                              \
-    "ds_read_b32 " bo_w ", %[tab] offset:" toff "\n\t"                                                  \
-    "v_add_u32 " RTMP0 ", %[bB0], " bo_r "\n\t"                                                         \
-    "s_waitcnt lgkmcnt(3)\n\t"                                                                          \
-    PX_MFMA(acc01, a0, b1)                                                                              \
-    "ds_read_b128 " n0 ", " RTMP0 "\n\t"                                                                \
-    "v_add_u32 " RTMP1 ", %[bB1], " bo_r "\n\t"                                                         \
-    "s_waitcnt lgkmcnt(3)\n\t"                                                                          \
-    PX_MFMA(acc02, a0, b2)                                                                              \
-    "ds_read_b128 " n1 ", " RTMP1 "\n\t"                                                                \
-    "v_add_u32 " RTMP2 ", %[bB2], " bo_r "\n\t"                                                         \
-    "s_waitcnt lgkmcnt(3)\n\t"                                                                          \
-    PX_MFMA(acc03, a0, b3)                                                                              \
-    "ds_read_b128 " n2 ", " RTMP2 "\n\t"                                                                \
-    "v_add_u32 " RTMP3 ", %[bB3], " bo_r "\n\t"                                                         \
-    "s_waitcnt vmcnt(4)\n\t"
-#define PX_STEP(a0, a1, b0, b1, b2, b3, n0, n1, n2, n3, bo_w, bo_r, toff, l0, l1, goff)                 \
-    PX_STEP_HEAD(a0, a1, b0, b1, b2, b3, n0, n1, n2, n3, bo_w, bo_r, toff)                              \
-    PX_MFMA(acc10, a1, b0)                                                                              \
-    "ds_read_b128 " n3 ", " RTMP3 "\n\t"                                                                \
-    PX_MFMA(acc11, a1, b1)                                                                              \
+// One step s: filter operands (a0, a1) from ring slot s % 4, pixel operands x0..x3 from operand
+// buffer s % 2.  Everything a step fetches is for later steps:
+//   * the pixel operands of step s + 2 go into this step's own buffer, each register one matrix
+//     instruction after its last use (x0 after the instruction behind acc10, ..., x3 at the head of
+//     step s + 1, from the address left in RTMP3): an LDS read has two steps to arrive, and a
+//     16-byte read of 8 waves at once needs more than one;
+//   * their table entry E(s + 2) sits in `bo_x`, read one and a half steps before; the entry
+//     E(s + 3) is read into `bo_y` once y3's address has been formed from E(s + 1) there;
+//   * the filter operands of step s + 3 go into ring slot (l0, l1), free since step s - 1.
+// LDS operations complete in order; in flight at the head are, oldest first, R0 R1 R2 (step s - 2),
+// R3 (s - 2), T (s - 1), R0 R1 R2 (s - 1): the counts below follow from that list.
+// (G2 .. G7: further instructions for the gaps behind the third to eighth matrix instruction; the
+//  last step of a turn carries the loop's bookkeeping there, where it costs no issue time)
+#define PX_STEP_HEAD(a0, a1, x0, x1, x2, x3, y3, bo_x, bo_y, toff, l0, l1, goff, G2, G3)                \
+    "s_waitcnt vmcnt(5) lgkmcnt(7)\n\t"                                                                 \
+    PX_MFMA(acc00, a0, x0)                                                                              \
+    "ds_read_b128 " y3 ", " RTMP3 "\n\t"                                                                \
+    "ds_read_b32 " bo_y ", %[tab] offset:" toff "\n\t"                                                  \
     "global_load_dwordx4 " l0 ", %[aoff], %[Ab0] offset:" goff "\n\t"                                   \
-    PX_MFMA(acc12, a1, b2)                                                                              \
+    "s_waitcnt lgkmcnt(8)\n\t"                                                                          \
+    PX_MFMA(acc01, a0, x1)                                                                              \
     "global_load_dwordx4 " l1 ", %[aoff], %[Ab1] offset:" goff "\n\t"                                   \
-    PX_MFMA(acc13, a1, b3)
+    "s_waitcnt lgkmcnt(7)\n\t"                                                                          \
+    PX_MFMA(acc02, a0, x2)                                                                              \
+    G2                                                                                                  \
+    "s_waitcnt lgkmcnt(6)\n\t"                                                                          \
+    PX_MFMA(acc03, a0, x3)                                                                              \
+    G3                                                                                                  \
+    "s_waitcnt vmcnt(6) lgkmcnt(5)\n\t"
+#define PX_STEPG(a0, a1, x0, x1, x2, x3, y3, bo_x, bo_y, toff, l0, l1, goff, G2, G3, G4, G5, G6, G7)    \
+    PX_STEP_HEAD(a0, a1, x0, x1, x2, x3, y3, bo_x, bo_y, toff, l0, l1, goff, G2, G3)                    \
+    PX_MFMA(acc10, a1, x0)                                                                              \
+    "v_add_u32 " RTMP0 ", %[bB0], " bo_x "\n\t"                                                         \
+    G4                                                                                                  \
+    PX_MFMA(acc11, a1, x1)                                                                              \
+    "ds_read_b128 " x0 ", " RTMP0 "\n\t"                                                                \
+    "v_add_u32 " RTMP1 ", %[bB1], " bo_x "\n\t"                                                         \
+    G5                                                                                                  \
+    PX_MFMA(acc12, a1, x2)                                                                              \
+    "ds_read_b128 " x1 ", " RTMP1 "\n\t"                                                                \
+    "v_add_u32 " RTMP2 ", %[bB2], " bo_x "\n\t"                                                         \
+    G6                                                                                                  \
+    PX_MFMA(acc13, a1, x3)                                                                              \
+    "ds_read_b128 " x2 ", " RTMP2 "\n\t"                                                                \
+    "v_add_u32 " RTMP3 ", %[bB3], " bo_x "\n\t"                                                         \
+    G7
+#define PX_STEP(a0, a1, x0, x1, x2, x3, y3, bo_x, bo_y, toff, l0, l1, goff)                             \
+    PX_STEPG(a0, a1, x0, x1, x2, x3, y3, bo_x, bo_y, toff, l0, l1, goff, "", "", "", "", "", "")
 // the step of an item that covers only one 32-filter tile per wave (a half item): without the second
 // tile's MFMAs; the loads stay, so the counts do
-#define PX_STEP_HALF(a0, a1, b0, b1, b2, b3, n0, n1, n2, n3, bo_w, bo_r, toff, l0, l1, goff)            \
-    PX_STEP_HEAD(a0, a1, b0, b1, b2, b3, n0, n1, n2, n3, bo_w, bo_r, toff)                              \
-    "ds_read_b128 " n3 ", " RTMP3 "\n\t"                                                                \
-    "global_load_dwordx4 " l0 ", %[aoff], %[Ab0] offset:" goff "\n\t"                                   \
-    "global_load_dwordx4 " l1 ", %[aoff], %[Ab1] offset:" goff "\n\t"
+#define PX_STEP_HALFG(a0, a1, x0, x1, x2, x3, y3, bo_x, bo_y, toff, l0, l1, goff, G2, G3, G4, G5, G6, G7) \
+    PX_STEP_HEAD(a0, a1, x0, x1, x2, x3, y3, bo_x, bo_y, toff, l0, l1, goff, G2, G3)                    \
+    "v_add_u32 " RTMP0 ", %[bB0], " bo_x "\n\t"                                                         \
+    "ds_read_b128 " x0 ", " RTMP0 "\n\t"                                                                \
+    "v_add_u32 " RTMP1 ", %[bB1], " bo_x "\n\t"                                                         \
+    G4                                                                                                  \
+    "ds_read_b128 " x1 ", " RTMP1 "\n\t"                                                                \
+    "v_add_u32 " RTMP2 ", %[bB2], " bo_x "\n\t"                                                         \
+    G5                                                                                                  \
+    "ds_read_b128 " x2 ", " RTMP2 "\n\t"                                                                \
+    "v_add_u32 " RTMP3 ", %[bB3], " bo_x "\n\t"                                                         \
+    G6 G7
+#define PX_STEP_HALF(a0, a1, x0, x1, x2, x3, y3, bo_x, bo_y, toff, l0, l1, goff)                        \
+    PX_STEP_HALFG(a0, a1, x0, x1, x2, x3, y3, bo_x, bo_y, toff, l0, l1, goff, "", "", "", "", "", "")
+
+// The bookkeeping of a turn, laid into the gaps of its last step: the ring and table offsets move on
+// (behind the step's own last uses of them), the turn counter goes up, and `ev` says whether the next
+// turn has anything to do before it starts (a hook of the chunk hand-over, the release of the second
+// group, a change of issue priority); if not, the turn's end branches straight back to its start.
+#define PX_CTL2 "v_add_u32 %[aoff], " PX_AINC ", %[aoff]\n\t" "v_add_u32 %[tab], " PX_TINC ", %[tab]\n\t" \
+                "s_add_u32 %[gi], %[gi], 1\n\t"
+#define PX_CTL3 "s_cmp_eq_u32 %[gi], %[t1]\n\t" "s_cselect_b32 %[ev], 1, 0\n\t" "s_cmp_eq_u32 %[gi], %[t2]\n\t"
+#define PX_CTL4 "s_cselect_b32 %[st2], 1, 0\n\t" "s_or_b32 %[ev], %[ev], %[st2]\n\t" "s_cmp_eq_u32 %[gi], %[t3]\n\t"
+#define PX_CTL5 "s_cselect_b32 %[st2], 1, 0\n\t" "s_or_b32 %[ev], %[ev], %[st2]\n\t" "s_cmp_eq_u32 %[gi], %[sturn]\n\t"
+#define PX_CTL6 "s_cselect_b32 %[st2], 1, 0\n\t" "s_or_b32 %[ev], %[ev], %[st2]\n\t" "s_and_b32 %[st2], %[gi], %[pmask]\n\t"
+#define PX_CTL7 "s_cmp_lt_u32 %[st2], 2\n\t" "s_cselect_b32 %[st2], %[pmask], 0\n\t" "s_or_b32 %[ev], %[ev], %[st2]\n\t"
 
 // one lane adds 1 to the counter at LDS address ADDR (ordered behind the wave's earlier LDS operations)
 #define PX_SIGNAL(ADDR)                  \
@@ -258,378 +297,378 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
 // (generated by a script that lays the instructions of the expansion into the gaps of four steps;
 //  the second form is the turn of a half item, without the second filter tile's MFMAs)
 #define PX_TURN_COMMIT \
-    "s_waitcnt vmcnt(5) lgkmcnt(3)\n\t" \
+    "s_waitcnt vmcnt(5) lgkmcnt(7)\n\t" \
     PX_MFMA(acc00, RA00, RB00) \
-    "ds_read_b32 " RBOFF0 ", %[tab] offset:0\n\t" \
-    "v_add_u32 " RTMP0 ", %[bB0], " RBOFF1 "\n\t" \
+    "ds_read_b128 " RB13 ", " RTMP3 "\n\t" \
+    "ds_read_b32 " RBOFF1 ", %[tab] offset:0\n\t" \
+    "global_load_dwordx4 " RA30 ", %[aoff], %[Ab0] offset:0\n\t" \
     "s_waitcnt vmcnt(8)\n\t" \
     "v_add_u32 " RPV ", %[st], %[sdst0]\n\t" \
-    "s_waitcnt lgkmcnt(3)\n\t" \
+    "s_waitcnt lgkmcnt(8)\n\t" \
     PX_MFMA(acc01, RA00, RB01) \
-    "ds_read_b128 " RB10 ", " RTMP0 "\n\t" \
-    "v_add_u32 " RTMP1 ", %[bB1], " RBOFF1 "\n\t" \
+    "global_load_dwordx4 " RA31 ", %[aoff], %[Ab1] offset:0\n\t" \
     "v_and_b32 " RT ", %[m03], v240\n\t" \
     "v_perm_b32 v248, 0, %[tbl], " RT "\n\t" \
-    "s_waitcnt lgkmcnt(3)\n\t" \
+    "s_waitcnt lgkmcnt(7)\n\t" \
     PX_MFMA(acc02, RA00, RB02) \
-    "ds_read_b128 " RB11 ", " RTMP1 "\n\t" \
-    "v_add_u32 " RTMP2 ", %[bB2], " RBOFF1 "\n\t" \
     "v_lshrrev_b32 " RT ", 2, v240\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
-    "s_waitcnt lgkmcnt(3)\n\t" \
+    "s_waitcnt lgkmcnt(6)\n\t" \
     PX_MFMA(acc03, RA00, RB03) \
-    "ds_read_b128 " RB12 ", " RTMP2 "\n\t" \
-    "v_add_u32 " RTMP3 ", %[bB3], " RBOFF1 "\n\t" \
     "v_perm_b32 v249, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 4, v240\n\t" \
-    "s_waitcnt vmcnt(4)\n\t" \
+    "s_waitcnt vmcnt(6) lgkmcnt(5)\n\t" \
     PX_MFMA(acc10, RA01, RB00) \
-    "ds_read_b128 " RB13 ", " RTMP3 "\n\t" \
+    "v_add_u32 " RTMP0 ", %[bB0], " RBOFF0 "\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v250, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 6, v240\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     PX_MFMA(acc11, RA01, RB01) \
-    "global_load_dwordx4 " RA30 ", %[aoff], %[Ab0] offset:0\n\t" \
+    "ds_read_b128 " RB00 ", " RTMP0 "\n\t" \
+    "v_add_u32 " RTMP1 ", %[bB1], " RBOFF0 "\n\t" \
     "v_perm_b32 v251, 0, %[tbl], " RT "\n\t" \
     "ds_write_b128 " RPV ", " REA "\n\t" \
     "v_and_b32 " RT ", %[m03], v241\n\t" \
     "v_perm_b32 v252, 0, %[tbl], " RT "\n\t" \
     PX_MFMA(acc12, RA01, RB02) \
-    "global_load_dwordx4 " RA31 ", %[aoff], %[Ab1] offset:0\n\t" \
+    "ds_read_b128 " RB01 ", " RTMP1 "\n\t" \
+    "v_add_u32 " RTMP2 ", %[bB2], " RBOFF0 "\n\t" \
     "v_lshrrev_b32 " RT ", 2, v241\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v253, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 4, v241\n\t" \
     PX_MFMA(acc13, RA01, RB03) \
+    "ds_read_b128 " RB02 ", " RTMP2 "\n\t" \
+    "v_add_u32 " RTMP3 ", %[bB3], " RBOFF0 "\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v254, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 6, v241\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v255, 0, %[tbl], " RT "\n\t" \
-    "s_waitcnt vmcnt(5) lgkmcnt(3)\n\t" \
+    "s_waitcnt vmcnt(5) lgkmcnt(7)\n\t" \
     PX_MFMA(acc00, RA10, RB10) \
-    "ds_read_b32 " RBOFF1 ", %[tab] offset:4\n\t" \
-    "v_add_u32 " RTMP0 ", %[bB0], " RBOFF0 "\n\t" \
+    "ds_read_b128 " RB03 ", " RTMP3 "\n\t" \
+    "ds_read_b32 " RBOFF0 ", %[tab] offset:4\n\t" \
+    "global_load_dwordx4 " RA00 ", %[aoff], %[Ab0] offset:1024\n\t" \
     "ds_write_b128 " RPV ", " REB " offset:16\n\t" \
     "v_and_b32 " RT ", %[m03], v242\n\t" \
-    "s_waitcnt lgkmcnt(3)\n\t" \
+    "s_waitcnt lgkmcnt(8)\n\t" \
     PX_MFMA(acc01, RA10, RB11) \
-    "ds_read_b128 " RB00 ", " RTMP0 "\n\t" \
-    "v_add_u32 " RTMP1 ", %[bB1], " RBOFF0 "\n\t" \
+    "global_load_dwordx4 " RA01 ", %[aoff], %[Ab1] offset:1024\n\t" \
     "v_perm_b32 v248, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 2, v242\n\t" \
-    "s_waitcnt lgkmcnt(3)\n\t" \
+    "s_waitcnt lgkmcnt(7)\n\t" \
     PX_MFMA(acc02, RA10, RB12) \
-    "ds_read_b128 " RB01 ", " RTMP1 "\n\t" \
-    "v_add_u32 " RTMP2 ", %[bB2], " RBOFF0 "\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v249, 0, %[tbl], " RT "\n\t" \
-    "s_waitcnt lgkmcnt(3)\n\t" \
+    "s_waitcnt lgkmcnt(6)\n\t" \
     PX_MFMA(acc03, RA10, RB13) \
-    "ds_read_b128 " RB02 ", " RTMP2 "\n\t" \
-    "v_add_u32 " RTMP3 ", %[bB3], " RBOFF0 "\n\t" \
     "v_lshrrev_b32 " RT ", 4, v242\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
-    "s_waitcnt vmcnt(4)\n\t" \
+    "s_waitcnt vmcnt(6) lgkmcnt(5)\n\t" \
     PX_MFMA(acc10, RA11, RB10) \
-    "ds_read_b128 " RB03 ", " RTMP3 "\n\t" \
+    "v_add_u32 " RTMP0 ", %[bB0], " RBOFF1 "\n\t" \
     "v_perm_b32 v250, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 6, v242\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v251, 0, %[tbl], " RT "\n\t" \
     PX_MFMA(acc11, RA11, RB11) \
-    "global_load_dwordx4 " RA00 ", %[aoff], %[Ab0] offset:1024\n\t" \
+    "ds_read_b128 " RB10 ", " RTMP0 "\n\t" \
+    "v_add_u32 " RTMP1 ", %[bB1], " RBOFF1 "\n\t" \
     "ds_write_b128 " RPV ", " REA " offset:32\n\t" \
     "v_and_b32 " RT ", %[m03], v243\n\t" \
     "v_perm_b32 v252, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 2, v243\n\t" \
     PX_MFMA(acc12, RA11, RB12) \
-    "global_load_dwordx4 " RA01 ", %[aoff], %[Ab1] offset:1024\n\t" \
+    "ds_read_b128 " RB11 ", " RTMP1 "\n\t" \
+    "v_add_u32 " RTMP2 ", %[bB2], " RBOFF1 "\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v253, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 4, v243\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     PX_MFMA(acc13, RA11, RB13) \
+    "ds_read_b128 " RB12 ", " RTMP2 "\n\t" \
+    "v_add_u32 " RTMP3 ", %[bB3], " RBOFF1 "\n\t" \
     "v_perm_b32 v254, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 6, v243\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v255, 0, %[tbl], " RT "\n\t" \
     "ds_write_b128 " RPV ", " REB " offset:48\n\t" \
-    "s_waitcnt vmcnt(5) lgkmcnt(3)\n\t" \
+    "s_waitcnt vmcnt(5) lgkmcnt(7)\n\t" \
     PX_MFMA(acc00, RA20, RB00) \
-    "ds_read_b32 " RBOFF0 ", %[tab] offset:8\n\t" \
-    "v_add_u32 " RTMP0 ", %[bB0], " RBOFF1 "\n\t" \
+    "ds_read_b128 " RB13 ", " RTMP3 "\n\t" \
+    "ds_read_b32 " RBOFF1 ", %[tab] offset:8\n\t" \
+    "global_load_dwordx4 " RA10 ", %[aoff], %[Ab0] offset:2048\n\t" \
     "v_add_u32 " RPV ", %[st], %[sdst1]\n\t" \
     "v_and_b32 " RT ", %[m03], v244\n\t" \
-    "s_waitcnt lgkmcnt(3)\n\t" \
+    "s_waitcnt lgkmcnt(8)\n\t" \
     PX_MFMA(acc01, RA20, RB01) \
-    "ds_read_b128 " RB10 ", " RTMP0 "\n\t" \
-    "v_add_u32 " RTMP1 ", %[bB1], " RBOFF1 "\n\t" \
+    "global_load_dwordx4 " RA11 ", %[aoff], %[Ab1] offset:2048\n\t" \
     "v_perm_b32 v248, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 2, v244\n\t" \
-    "s_waitcnt lgkmcnt(3)\n\t" \
+    "s_waitcnt lgkmcnt(7)\n\t" \
     PX_MFMA(acc02, RA20, RB02) \
-    "ds_read_b128 " RB11 ", " RTMP1 "\n\t" \
-    "v_add_u32 " RTMP2 ", %[bB2], " RBOFF1 "\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v249, 0, %[tbl], " RT "\n\t" \
-    "s_waitcnt lgkmcnt(3)\n\t" \
+    "s_waitcnt lgkmcnt(6)\n\t" \
     PX_MFMA(acc03, RA20, RB03) \
-    "ds_read_b128 " RB12 ", " RTMP2 "\n\t" \
-    "v_add_u32 " RTMP3 ", %[bB3], " RBOFF1 "\n\t" \
     "v_lshrrev_b32 " RT ", 4, v244\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
-    "s_waitcnt vmcnt(4)\n\t" \
+    "s_waitcnt vmcnt(6) lgkmcnt(5)\n\t" \
     PX_MFMA(acc10, RA21, RB00) \
-    "ds_read_b128 " RB13 ", " RTMP3 "\n\t" \
+    "v_add_u32 " RTMP0 ", %[bB0], " RBOFF0 "\n\t" \
     "v_perm_b32 v250, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 6, v244\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v251, 0, %[tbl], " RT "\n\t" \
     PX_MFMA(acc11, RA21, RB01) \
-    "global_load_dwordx4 " RA10 ", %[aoff], %[Ab0] offset:2048\n\t" \
+    "ds_read_b128 " RB00 ", " RTMP0 "\n\t" \
+    "v_add_u32 " RTMP1 ", %[bB1], " RBOFF0 "\n\t" \
     "ds_write_b128 " RPV ", " REA "\n\t" \
     "v_and_b32 " RT ", %[m03], v245\n\t" \
     "v_perm_b32 v252, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 2, v245\n\t" \
     PX_MFMA(acc12, RA21, RB02) \
-    "global_load_dwordx4 " RA11 ", %[aoff], %[Ab1] offset:2048\n\t" \
+    "ds_read_b128 " RB01 ", " RTMP1 "\n\t" \
+    "v_add_u32 " RTMP2 ", %[bB2], " RBOFF0 "\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v253, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 4, v245\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     PX_MFMA(acc13, RA21, RB03) \
+    "ds_read_b128 " RB02 ", " RTMP2 "\n\t" \
+    "v_add_u32 " RTMP3 ", %[bB3], " RBOFF0 "\n\t" \
     "v_perm_b32 v254, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 6, v245\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v255, 0, %[tbl], " RT "\n\t" \
     "ds_write_b128 " RPV ", " REB " offset:16\n\t" \
-    "s_waitcnt vmcnt(5) lgkmcnt(3)\n\t" \
+    "s_waitcnt vmcnt(5) lgkmcnt(7)\n\t" \
     PX_MFMA(acc00, RA30, RB10) \
-    "ds_read_b32 " RBOFF1 ", %[tab] offset:12\n\t" \
-    "v_add_u32 " RTMP0 ", %[bB0], " RBOFF0 "\n\t" \
+    "ds_read_b128 " RB03 ", " RTMP3 "\n\t" \
+    "ds_read_b32 " RBOFF0 ", %[tab] offset:12\n\t" \
+    "global_load_dwordx4 " RA20 ", %[aoff], %[Ab0] offset:3072\n\t" \
     "v_and_b32 " RT ", %[m03], v246\n\t" \
     "v_perm_b32 v248, 0, %[tbl], " RT "\n\t" \
-    "s_waitcnt lgkmcnt(3)\n\t" \
+    "s_waitcnt lgkmcnt(8)\n\t" \
     PX_MFMA(acc01, RA30, RB11) \
-    "ds_read_b128 " RB00 ", " RTMP0 "\n\t" \
-    "v_add_u32 " RTMP1 ", %[bB1], " RBOFF0 "\n\t" \
+    "global_load_dwordx4 " RA21 ", %[aoff], %[Ab1] offset:3072\n\t" \
     "v_lshrrev_b32 " RT ", 2, v246\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
-    "s_waitcnt lgkmcnt(3)\n\t" \
+    "s_waitcnt lgkmcnt(7)\n\t" \
     PX_MFMA(acc02, RA30, RB12) \
-    "ds_read_b128 " RB01 ", " RTMP1 "\n\t" \
-    "v_add_u32 " RTMP2 ", %[bB2], " RBOFF0 "\n\t" \
     "v_perm_b32 v249, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 4, v246\n\t" \
-    "s_waitcnt lgkmcnt(3)\n\t" \
+    "s_waitcnt lgkmcnt(6)\n\t" \
     PX_MFMA(acc03, RA30, RB13) \
-    "ds_read_b128 " RB02 ", " RTMP2 "\n\t" \
-    "v_add_u32 " RTMP3 ", %[bB3], " RBOFF0 "\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v250, 0, %[tbl], " RT "\n\t" \
-    "s_waitcnt vmcnt(4)\n\t" \
+    "s_waitcnt vmcnt(6) lgkmcnt(5)\n\t" \
     PX_MFMA(acc10, RA31, RB10) \
-    "ds_read_b128 " RB03 ", " RTMP3 "\n\t" \
+    "v_add_u32 " RTMP0 ", %[bB0], " RBOFF1 "\n\t" \
     "v_lshrrev_b32 " RT ", 6, v246\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v251, 0, %[tbl], " RT "\n\t" \
     "ds_write_b128 " RPV ", " REA " offset:32\n\t" \
     PX_MFMA(acc11, RA31, RB11) \
-    "global_load_dwordx4 " RA20 ", %[aoff], %[Ab0] offset:3072\n\t" \
+    "ds_read_b128 " RB10 ", " RTMP0 "\n\t" \
+    "v_add_u32 " RTMP1 ", %[bB1], " RBOFF1 "\n\t" \
     "v_and_b32 " RT ", %[m03], v247\n\t" \
     "v_perm_b32 v252, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 2, v247\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     PX_MFMA(acc12, RA31, RB12) \
-    "global_load_dwordx4 " RA21 ", %[aoff], %[Ab1] offset:3072\n\t" \
+    "ds_read_b128 " RB11 ", " RTMP1 "\n\t" \
+    "v_add_u32 " RTMP2 ", %[bB2], " RBOFF1 "\n\t" \
     "v_perm_b32 v253, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 4, v247\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v254, 0, %[tbl], " RT "\n\t" \
     PX_MFMA(acc13, RA31, RB13) \
+    "ds_read_b128 " RB12 ", " RTMP2 "\n\t" \
+    "v_add_u32 " RTMP3 ", %[bB3], " RBOFF1 "\n\t" \
     "v_lshrrev_b32 " RT ", 6, v247\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v255, 0, %[tbl], " RT "\n\t" \
     "ds_write_b128 " RPV ", " REB " offset:48\n\t"
 
 #define PX_TURN_COMMIT_HALF \
-    "s_waitcnt vmcnt(5) lgkmcnt(3)\n\t" \
+    "s_waitcnt vmcnt(5) lgkmcnt(7)\n\t" \
     PX_MFMA(acc00, RA00, RB00) \
-    "ds_read_b32 " RBOFF0 ", %[tab] offset:0\n\t" \
-    "v_add_u32 " RTMP0 ", %[bB0], " RBOFF1 "\n\t" \
+    "ds_read_b128 " RB13 ", " RTMP3 "\n\t" \
+    "ds_read_b32 " RBOFF1 ", %[tab] offset:0\n\t" \
+    "global_load_dwordx4 " RA30 ", %[aoff], %[Ab0] offset:0\n\t" \
     "s_waitcnt vmcnt(8)\n\t" \
     "v_add_u32 " RPV ", %[st], %[sdst0]\n\t" \
-    "s_waitcnt lgkmcnt(3)\n\t" \
+    "s_waitcnt lgkmcnt(8)\n\t" \
     PX_MFMA(acc01, RA00, RB01) \
-    "ds_read_b128 " RB10 ", " RTMP0 "\n\t" \
-    "v_add_u32 " RTMP1 ", %[bB1], " RBOFF1 "\n\t" \
+    "global_load_dwordx4 " RA31 ", %[aoff], %[Ab1] offset:0\n\t" \
     "v_and_b32 " RT ", %[m03], v240\n\t" \
     "v_perm_b32 v248, 0, %[tbl], " RT "\n\t" \
-    "s_waitcnt lgkmcnt(3)\n\t" \
+    "s_waitcnt lgkmcnt(7)\n\t" \
     PX_MFMA(acc02, RA00, RB02) \
-    "ds_read_b128 " RB11 ", " RTMP1 "\n\t" \
-    "v_add_u32 " RTMP2 ", %[bB2], " RBOFF1 "\n\t" \
     "v_lshrrev_b32 " RT ", 2, v240\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
-    "s_waitcnt lgkmcnt(3)\n\t" \
+    "s_waitcnt lgkmcnt(6)\n\t" \
     PX_MFMA(acc03, RA00, RB03) \
-    "ds_read_b128 " RB12 ", " RTMP2 "\n\t" \
-    "v_add_u32 " RTMP3 ", %[bB3], " RBOFF1 "\n\t" \
     "v_perm_b32 v249, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 4, v240\n\t" \
-    "s_waitcnt vmcnt(4)\n\t" \
-    "ds_read_b128 " RB13 ", " RTMP3 "\n\t" \
+    "s_waitcnt vmcnt(6) lgkmcnt(5)\n\t" \
+    "v_add_u32 " RTMP0 ", %[bB0], " RBOFF0 "\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v250, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 6, v240\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
-    "global_load_dwordx4 " RA30 ", %[aoff], %[Ab0] offset:0\n\t" \
+    "ds_read_b128 " RB00 ", " RTMP0 "\n\t" \
+    "v_add_u32 " RTMP1 ", %[bB1], " RBOFF0 "\n\t" \
     "v_perm_b32 v251, 0, %[tbl], " RT "\n\t" \
     "ds_write_b128 " RPV ", " REA "\n\t" \
     "v_and_b32 " RT ", %[m03], v241\n\t" \
     "v_perm_b32 v252, 0, %[tbl], " RT "\n\t" \
-    "global_load_dwordx4 " RA31 ", %[aoff], %[Ab1] offset:0\n\t" \
+    "ds_read_b128 " RB01 ", " RTMP1 "\n\t" \
+    "v_add_u32 " RTMP2 ", %[bB2], " RBOFF0 "\n\t" \
     "v_lshrrev_b32 " RT ", 2, v241\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v253, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 4, v241\n\t" \
+    "ds_read_b128 " RB02 ", " RTMP2 "\n\t" \
+    "v_add_u32 " RTMP3 ", %[bB3], " RBOFF0 "\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v254, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 6, v241\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v255, 0, %[tbl], " RT "\n\t" \
-    "s_waitcnt vmcnt(5) lgkmcnt(3)\n\t" \
+    "s_waitcnt vmcnt(5) lgkmcnt(7)\n\t" \
     PX_MFMA(acc00, RA10, RB10) \
-    "ds_read_b32 " RBOFF1 ", %[tab] offset:4\n\t" \
-    "v_add_u32 " RTMP0 ", %[bB0], " RBOFF0 "\n\t" \
+    "ds_read_b128 " RB03 ", " RTMP3 "\n\t" \
+    "ds_read_b32 " RBOFF0 ", %[tab] offset:4\n\t" \
+    "global_load_dwordx4 " RA00 ", %[aoff], %[Ab0] offset:1024\n\t" \
     "ds_write_b128 " RPV ", " REB " offset:16\n\t" \
     "v_and_b32 " RT ", %[m03], v242\n\t" \
-    "s_waitcnt lgkmcnt(3)\n\t" \
+    "s_waitcnt lgkmcnt(8)\n\t" \
     PX_MFMA(acc01, RA10, RB11) \
-    "ds_read_b128 " RB00 ", " RTMP0 "\n\t" \
-    "v_add_u32 " RTMP1 ", %[bB1], " RBOFF0 "\n\t" \
+    "global_load_dwordx4 " RA01 ", %[aoff], %[Ab1] offset:1024\n\t" \
     "v_perm_b32 v248, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 2, v242\n\t" \
-    "s_waitcnt lgkmcnt(3)\n\t" \
+    "s_waitcnt lgkmcnt(7)\n\t" \
     PX_MFMA(acc02, RA10, RB12) \
-    "ds_read_b128 " RB01 ", " RTMP1 "\n\t" \
-    "v_add_u32 " RTMP2 ", %[bB2], " RBOFF0 "\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v249, 0, %[tbl], " RT "\n\t" \
-    "s_waitcnt lgkmcnt(3)\n\t" \
+    "s_waitcnt lgkmcnt(6)\n\t" \
     PX_MFMA(acc03, RA10, RB13) \
-    "ds_read_b128 " RB02 ", " RTMP2 "\n\t" \
-    "v_add_u32 " RTMP3 ", %[bB3], " RBOFF0 "\n\t" \
     "v_lshrrev_b32 " RT ", 4, v242\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
-    "s_waitcnt vmcnt(4)\n\t" \
-    "ds_read_b128 " RB03 ", " RTMP3 "\n\t" \
+    "s_waitcnt vmcnt(6) lgkmcnt(5)\n\t" \
+    "v_add_u32 " RTMP0 ", %[bB0], " RBOFF1 "\n\t" \
     "v_perm_b32 v250, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 6, v242\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v251, 0, %[tbl], " RT "\n\t" \
-    "global_load_dwordx4 " RA00 ", %[aoff], %[Ab0] offset:1024\n\t" \
+    "ds_read_b128 " RB10 ", " RTMP0 "\n\t" \
+    "v_add_u32 " RTMP1 ", %[bB1], " RBOFF1 "\n\t" \
     "ds_write_b128 " RPV ", " REA " offset:32\n\t" \
     "v_and_b32 " RT ", %[m03], v243\n\t" \
     "v_perm_b32 v252, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 2, v243\n\t" \
-    "global_load_dwordx4 " RA01 ", %[aoff], %[Ab1] offset:1024\n\t" \
+    "ds_read_b128 " RB11 ", " RTMP1 "\n\t" \
+    "v_add_u32 " RTMP2 ", %[bB2], " RBOFF1 "\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v253, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 4, v243\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
+    "ds_read_b128 " RB12 ", " RTMP2 "\n\t" \
+    "v_add_u32 " RTMP3 ", %[bB3], " RBOFF1 "\n\t" \
     "v_perm_b32 v254, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 6, v243\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v255, 0, %[tbl], " RT "\n\t" \
     "ds_write_b128 " RPV ", " REB " offset:48\n\t" \
-    "s_waitcnt vmcnt(5) lgkmcnt(3)\n\t" \
+    "s_waitcnt vmcnt(5) lgkmcnt(7)\n\t" \
     PX_MFMA(acc00, RA20, RB00) \
-    "ds_read_b32 " RBOFF0 ", %[tab] offset:8\n\t" \
-    "v_add_u32 " RTMP0 ", %[bB0], " RBOFF1 "\n\t" \
+    "ds_read_b128 " RB13 ", " RTMP3 "\n\t" \
+    "ds_read_b32 " RBOFF1 ", %[tab] offset:8\n\t" \
+    "global_load_dwordx4 " RA10 ", %[aoff], %[Ab0] offset:2048\n\t" \
     "v_add_u32 " RPV ", %[st], %[sdst1]\n\t" \
     "v_and_b32 " RT ", %[m03], v244\n\t" \
-    "s_waitcnt lgkmcnt(3)\n\t" \
+    "s_waitcnt lgkmcnt(8)\n\t" \
     PX_MFMA(acc01, RA20, RB01) \
-    "ds_read_b128 " RB10 ", " RTMP0 "\n\t" \
-    "v_add_u32 " RTMP1 ", %[bB1], " RBOFF1 "\n\t" \
+    "global_load_dwordx4 " RA11 ", %[aoff], %[Ab1] offset:2048\n\t" \
     "v_perm_b32 v248, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 2, v244\n\t" \
-    "s_waitcnt lgkmcnt(3)\n\t" \
+    "s_waitcnt lgkmcnt(7)\n\t" \
     PX_MFMA(acc02, RA20, RB02) \
-    "ds_read_b128 " RB11 ", " RTMP1 "\n\t" \
-    "v_add_u32 " RTMP2 ", %[bB2], " RBOFF1 "\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v249, 0, %[tbl], " RT "\n\t" \
-    "s_waitcnt lgkmcnt(3)\n\t" \
+    "s_waitcnt lgkmcnt(6)\n\t" \
     PX_MFMA(acc03, RA20, RB03) \
-    "ds_read_b128 " RB12 ", " RTMP2 "\n\t" \
-    "v_add_u32 " RTMP3 ", %[bB3], " RBOFF1 "\n\t" \
     "v_lshrrev_b32 " RT ", 4, v244\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
-    "s_waitcnt vmcnt(4)\n\t" \
-    "ds_read_b128 " RB13 ", " RTMP3 "\n\t" \
+    "s_waitcnt vmcnt(6) lgkmcnt(5)\n\t" \
+    "v_add_u32 " RTMP0 ", %[bB0], " RBOFF0 "\n\t" \
     "v_perm_b32 v250, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 6, v244\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v251, 0, %[tbl], " RT "\n\t" \
-    "global_load_dwordx4 " RA10 ", %[aoff], %[Ab0] offset:2048\n\t" \
+    "ds_read_b128 " RB00 ", " RTMP0 "\n\t" \
+    "v_add_u32 " RTMP1 ", %[bB1], " RBOFF0 "\n\t" \
     "ds_write_b128 " RPV ", " REA "\n\t" \
     "v_and_b32 " RT ", %[m03], v245\n\t" \
     "v_perm_b32 v252, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 2, v245\n\t" \
-    "global_load_dwordx4 " RA11 ", %[aoff], %[Ab1] offset:2048\n\t" \
+    "ds_read_b128 " RB01 ", " RTMP1 "\n\t" \
+    "v_add_u32 " RTMP2 ", %[bB2], " RBOFF0 "\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v253, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 4, v245\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
+    "ds_read_b128 " RB02 ", " RTMP2 "\n\t" \
+    "v_add_u32 " RTMP3 ", %[bB3], " RBOFF0 "\n\t" \
     "v_perm_b32 v254, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 6, v245\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v255, 0, %[tbl], " RT "\n\t" \
     "ds_write_b128 " RPV ", " REB " offset:16\n\t" \
-    "s_waitcnt vmcnt(5) lgkmcnt(3)\n\t" \
+    "s_waitcnt vmcnt(5) lgkmcnt(7)\n\t" \
     PX_MFMA(acc00, RA30, RB10) \
-    "ds_read_b32 " RBOFF1 ", %[tab] offset:12\n\t" \
-    "v_add_u32 " RTMP0 ", %[bB0], " RBOFF0 "\n\t" \
+    "ds_read_b128 " RB03 ", " RTMP3 "\n\t" \
+    "ds_read_b32 " RBOFF0 ", %[tab] offset:12\n\t" \
+    "global_load_dwordx4 " RA20 ", %[aoff], %[Ab0] offset:3072\n\t" \
     "v_and_b32 " RT ", %[m03], v246\n\t" \
     "v_perm_b32 v248, 0, %[tbl], " RT "\n\t" \
-    "s_waitcnt lgkmcnt(3)\n\t" \
+    "s_waitcnt lgkmcnt(8)\n\t" \
     PX_MFMA(acc01, RA30, RB11) \
-    "ds_read_b128 " RB00 ", " RTMP0 "\n\t" \
-    "v_add_u32 " RTMP1 ", %[bB1], " RBOFF0 "\n\t" \
+    "global_load_dwordx4 " RA21 ", %[aoff], %[Ab1] offset:3072\n\t" \
     "v_lshrrev_b32 " RT ", 2, v246\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
-    "s_waitcnt lgkmcnt(3)\n\t" \
+    "s_waitcnt lgkmcnt(7)\n\t" \
     PX_MFMA(acc02, RA30, RB12) \
-    "ds_read_b128 " RB01 ", " RTMP1 "\n\t" \
-    "v_add_u32 " RTMP2 ", %[bB2], " RBOFF0 "\n\t" \
     "v_perm_b32 v249, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 4, v246\n\t" \
-    "s_waitcnt lgkmcnt(3)\n\t" \
+    "s_waitcnt lgkmcnt(6)\n\t" \
     PX_MFMA(acc03, RA30, RB13) \
-    "ds_read_b128 " RB02 ", " RTMP2 "\n\t" \
-    "v_add_u32 " RTMP3 ", %[bB3], " RBOFF0 "\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v250, 0, %[tbl], " RT "\n\t" \
-    "s_waitcnt vmcnt(4)\n\t" \
-    "ds_read_b128 " RB03 ", " RTMP3 "\n\t" \
+    "s_waitcnt vmcnt(6) lgkmcnt(5)\n\t" \
+    "v_add_u32 " RTMP0 ", %[bB0], " RBOFF1 "\n\t" \
     "v_lshrrev_b32 " RT ", 6, v246\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v251, 0, %[tbl], " RT "\n\t" \
     "ds_write_b128 " RPV ", " REA " offset:32\n\t" \
-    "global_load_dwordx4 " RA20 ", %[aoff], %[Ab0] offset:3072\n\t" \
+    "ds_read_b128 " RB10 ", " RTMP0 "\n\t" \
+    "v_add_u32 " RTMP1 ", %[bB1], " RBOFF1 "\n\t" \
     "v_and_b32 " RT ", %[m03], v247\n\t" \
     "v_perm_b32 v252, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 2, v247\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
-    "global_load_dwordx4 " RA21 ", %[aoff], %[Ab1] offset:3072\n\t" \
+    "ds_read_b128 " RB11 ", " RTMP1 "\n\t" \
+    "v_add_u32 " RTMP2 ", %[bB2], " RBOFF1 "\n\t" \
     "v_perm_b32 v253, 0, %[tbl], " RT "\n\t" \
     "v_lshrrev_b32 " RT ", 4, v247\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v254, 0, %[tbl], " RT "\n\t" \
+    "ds_read_b128 " RB12 ", " RTMP2 "\n\t" \
+    "v_add_u32 " RTMP3 ", %[bB3], " RBOFF1 "\n\t" \
     "v_lshrrev_b32 " RT ", 6, v247\n\t" \
     "v_and_b32 " RT ", %[m03], " RT "\n\t" \
     "v_perm_b32 v255, 0, %[tbl], " RT "\n\t" \
@@ -660,10 +699,14 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
     "global_load_dwordx4 " RA20 ", %[aoff], %[Ab0] offset:2048\n\t"                                      \
     "global_load_dwordx4 " RA21 ", %[aoff], %[Ab1] offset:2048\n\t"                                      \
     "v_add_u32 %[aoff], 0xc00, %[aoff]\n\t"                                                              \
-    /* table entries 0 and 1, then the pixel operands of step 0 */                                       \
+    /* chunk 0 is complete in its buffer (all four waves have committed their part): waited for  */ \
+    /* here, with the ring's first operands on their way                                          */ \
+    "s_add_u32 %[tg], %[cbase], 4\n\t"                                                                   \
+    PX_WAIT(ready, "p")                                                                                  \
+    /* table entries 0 and 1; the pixel operands of step 0, entry 2, the first three operands of   */ \
+    /* step 1 and the address of the fourth: the order in which the steps will issue them          */ \
     "ds_read_b32 " RBOFF0 ", %[tab]\n\t"                                                                 \
     "ds_read_b32 " RBOFF1 ", %[tab] offset:4\n\t"                                                        \
-    "v_add_u32 %[tab], 8, %[tab]\n\t"                                                                    \
     "s_waitcnt lgkmcnt(0)\n\t"                                                                           \
     "v_add_u32 " RTMP0 ", %[bB0], " RBOFF0 "\n\t"                                                        \
     "ds_read_b128 " RB00 ", " RTMP0 "\n\t"                                                               \
@@ -673,6 +716,15 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
     "ds_read_b128 " RB02 ", " RTMP2 "\n\t"                                                               \
     "v_add_u32 " RTMP3 ", %[bB3], " RBOFF0 "\n\t"                                                        \
     "ds_read_b128 " RB03 ", " RTMP3 "\n\t"                                                               \
+    "ds_read_b32 " RBOFF0 ", %[tab] offset:8\n\t"                                                        \
+    "v_add_u32 %[tab], 12, %[tab]\n\t"                                                                   \
+    "v_add_u32 " RTMP0 ", %[bB0], " RBOFF1 "\n\t"                                                        \
+    "ds_read_b128 " RB10 ", " RTMP0 "\n\t"                                                               \
+    "v_add_u32 " RTMP1 ", %[bB1], " RBOFF1 "\n\t"                                                        \
+    "ds_read_b128 " RB11 ", " RTMP1 "\n\t"                                                               \
+    "v_add_u32 " RTMP2 ", %[bB2], " RBOFF1 "\n\t"                                                        \
+    "ds_read_b128 " RB12 ", " RTMP2 "\n\t"                                                               \
+    "v_add_u32 " RTMP3 ", %[bB3], " RBOFF1 "\n\t"                                                        \
     /* ---- the loop over ring turns ---- */                                                             \
     "Ltop%=:\n\t"                                                                                        \
     "s_cmp_eq_u32 %[gi], %[sturn]\n\t"                                                                   \
@@ -698,16 +750,25 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
     "Lpd%=:\n\t"                                                                                         \
     "s_cmp_eq_u32 %[onetile], 0\n\t"                                                                     \
     "s_cbranch_scc0 LturnH%=\n\t"                                                                        \
-    PX_STEP(RA00, RA01, RB00, RB01, RB02, RB03, RB10, RB11, RB12, RB13, RBOFF0, RBOFF1, "0", RA30, RA31, "0")     \
-    PX_STEP(RA10, RA11, RB10, RB11, RB12, RB13, RB00, RB01, RB02, RB03, RBOFF1, RBOFF0, "4", RA00, RA01, "1024")  \
-    PX_STEP(RA20, RA21, RB00, RB01, RB02, RB03, RB10, RB11, RB12, RB13, RBOFF0, RBOFF1, "8", RA10, RA11, "2048")  \
-    PX_STEP(RA30, RA31, RB10, RB11, RB12, RB13, RB00, RB01, RB02, RB03, RBOFF1, RBOFF0, "12", RA20, RA21, "3072") \
+    "LturnW%=:\n\t"                                                                                      \
+    PX_STEP(RA00, RA01, RB00, RB01, RB02, RB03, RB13, RBOFF0, RBOFF1, "0", RA30, RA31, "0")      \
+    PX_STEP(RA10, RA11, RB10, RB11, RB12, RB13, RB03, RBOFF1, RBOFF0, "4", RA00, RA01, "1024")   \
+    PX_STEP(RA20, RA21, RB00, RB01, RB02, RB03, RB13, RBOFF0, RBOFF1, "8", RA10, RA11, "2048")   \
+    PX_STEPG(RA30, RA31, RB10, RB11, RB12, RB13, RB03, RBOFF1, RBOFF0, "12", RA20, RA21, "3072", \
+             PX_CTL2, PX_CTL3, PX_CTL4, PX_CTL5, PX_CTL6, PX_CTL7)                               \
+    "s_cmp_lt_u32 %[gi], %[nturns]\n\t"                                                                  \
+    "s_cbranch_scc0 Lexit%=\n\t"                                                                         \
+    "s_cmp_eq_u32 %[ev], 0\n\t"                                                                          \
+    "s_cbranch_scc1 LturnW%=\n\t"                                                                        \
+    "s_branch Ltop%=\n\t"                                                                                \
+    /* the end of a turn that kept its bookkeeping for here (the turns that expand a chunk) */           \
     "Ltail%=:\n\t"                                                                                       \
     "v_add_u32 %[aoff], " PX_AINC ", %[aoff]\n\t"                                                        \
     "v_add_u32 %[tab], " PX_TINC ", %[tab]\n\t"                                                          \
     "s_add_u32 %[gi], %[gi], 1\n\t"                                                                      \
     "s_cmp_lt_u32 %[gi], %[nturns]\n\t"                                                                  \
     "s_cbranch_scc1 Ltop%=\n\t"                                                                          \
+    "Lexit%=:\n\t"                                                                                       \
     /* the reads ahead of the item's end have landed; this wave has read the last of the last chunk */   \
     "s_waitcnt vmcnt(0) lgkmcnt(0)\n\t"                                                                  \
     "s_setprio 0\n\t"                                                                                    \
@@ -717,11 +778,16 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
     "s_branch Lend%=\n\t"                                                                                \
     /* ---- the turn of a half item ---- */                                                              \
     "LturnH%=:\n\t"                                                                                      \
-    PX_STEP_HALF(RA00, RA01, RB00, RB01, RB02, RB03, RB10, RB11, RB12, RB13, RBOFF0, RBOFF1, "0", RA30, RA31, "0")     \
-    PX_STEP_HALF(RA10, RA11, RB10, RB11, RB12, RB13, RB00, RB01, RB02, RB03, RBOFF1, RBOFF0, "4", RA00, RA01, "1024")  \
-    PX_STEP_HALF(RA20, RA21, RB00, RB01, RB02, RB03, RB10, RB11, RB12, RB13, RBOFF0, RBOFF1, "8", RA10, RA11, "2048")  \
-    PX_STEP_HALF(RA30, RA31, RB10, RB11, RB12, RB13, RB00, RB01, RB02, RB03, RBOFF1, RBOFF0, "12", RA20, RA21, "3072") \
-    "s_branch Ltail%=\n\t"                                                                               \
+    PX_STEP_HALF(RA00, RA01, RB00, RB01, RB02, RB03, RB13, RBOFF0, RBOFF1, "0", RA30, RA31, "0")      \
+    PX_STEP_HALF(RA10, RA11, RB10, RB11, RB12, RB13, RB03, RBOFF1, RBOFF0, "4", RA00, RA01, "1024")   \
+    PX_STEP_HALF(RA20, RA21, RB00, RB01, RB02, RB03, RB13, RBOFF0, RBOFF1, "8", RA10, RA11, "2048")   \
+    PX_STEP_HALFG(RA30, RA31, RB10, RB11, RB12, RB13, RB03, RBOFF1, RBOFF0, "12", RA20, RA21, "3072", \
+                  PX_CTL2, PX_CTL3, PX_CTL4, PX_CTL5, PX_CTL6, PX_CTL7)                               \
+    "s_cmp_lt_u32 %[gi], %[nturns]\n\t"                                                                  \
+    "s_cbranch_scc0 Lexit%=\n\t"                                                                         \
+    "s_cmp_eq_u32 %[ev], 0\n\t"                                                                          \
+    "s_cbranch_scc1 LturnH%=\n\t"                                                                        \
+    "s_branch Ltop%=\n\t"                                                                                \
     /* ---- h1 ---- */                                                                                   \
     "Lh1%=:\n\t"                                                                                         \
     "s_cmp_eq_u32 %[hc], 0\n\t"                                                                          \
@@ -1245,14 +1311,13 @@ __global__ __launch_bounds__(512) void conv_mfma_persistent_kernel(PParams p)
             for (int j = 0; j < kWN; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-        wait_count(ready_addr, cbase + 4u);
         XNOR_STAMP_K(kitem, 3);
 
         // ---- contract ----
         {
             uint32_t a_off = (uint32_t)fresh_lane() * 16u;   // byte offset of this lane's filter operand, step 0
             uint32_t tab_addr = tab_base;
-            int gi, hc, t1, t2, t3, st, st2, sp, tg;
+            int gi, hc, t1, t2, t3, st, st2, sp, tg, ev;
             unsigned long long sx;
             asm volatile(PX_LOOP_ASM
                          : [acc00] "+v"(acc[0][0]), [acc01] "+v"(acc[0][1]), [acc02] "+v"(acc[0][2]),
@@ -1260,7 +1325,7 @@ __global__ __launch_bounds__(512) void conv_mfma_persistent_kernel(PParams p)
                            [acc12] "+v"(acc[1][2]), [acc13] "+v"(acc[1][3]), [aoff] "+v"(a_off),
                            [tab] "+v"(tab_addr), [sturn] "+s"(sturn), [gi] "=&s"(gi), [hc] "=&s"(hc),
                            [t1] "=&s"(t1), [t2] "=&s"(t2), [t3] "=&s"(t3), [st] "=&s"(st), [st2] "=&s"(st2),
-                           [sp] "=&s"(sp), [tg] "=&s"(tg), [sx] "=&s"(sx)
+                           [sp] "=&s"(sp), [tg] "=&s"(tg), [sx] "=&s"(sx), [ev] "=&s"(ev)
                          : [bB0] "v"(bB[0]), [bB1] "v"(bB[1]), [bB2] "v"(bB[2]), [bB3] "v"(bB[3]),
                            [soff0] "v"(soff[0]), [soff1] "v"(soff[1]), [sdst0] "v"(sdst[0]), [sdst1] "v"(sdst[1]),
                            [ready] "v"(ready_addr), [done] "v"(done_addr), [start] "v"(start_addr),
