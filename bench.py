@@ -102,7 +102,10 @@ def parse():
                          "images (--image-sides); one JSON line each, with the XNOR-vs-float ratio")
     ap.add_argument("--k-in-conv", action="store_true",
                     help="form K inside the convolution kernel from the channel mean (one launch less, a slower "
-                         "convolution) instead of with the box-filter launch of the prepare call")
+                         "convolution) instead of with the box-filter launch of the prepare call; by default this is "
+                         "done where the layer is one round of the matrix-core kernel's items (there a launch costs "
+                         "more than the kernel gains)")
+    ap.add_argument("--k-in-prepare", action="store_true", help="form K with the box-filter launch on every layer")
     ap.add_argument("--no-graph", action="store_true",
                     help="skip the HIP-graph replay of the step (its time is reported beside the eager one)")
     ap.add_argument("--conv-events-every", type=int, default=1,
@@ -181,7 +184,10 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
     # with the matrix-core kernel the convolution is two calls, so that the timed "conv" stage is
     # that one kernel launch (what the roofline figures are about)
     two_phase = used_algo == xb.ALGO_MFMA and not args.chain
-    k_in_conv = two_phase and args.k_in_conv and not args.unfused
+    # (items of the matrix-core kernel: bands of up to 256 output pixels x tiles of 128 filters; one
+    #  round = two per compute unit)
+    items = -(-(s.N * OH) // max(1, 256 // OW)) * -(-s.F // 128)
+    k_in_conv = two_phase and not args.unfused and not args.k_in_prepare and (args.k_in_conv or items <= 512)
     if args.chain:
         xb.xnor_input_prepare(dI, s, Ipk, A, K)
         xb.xnor_filter_prepare(dW, Wpk, M, alpha)

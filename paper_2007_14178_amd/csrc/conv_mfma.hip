@@ -742,10 +742,12 @@ MfmaPlan make_plan(const Geom &g, const void *Ipk)
 }  // namespace
 
 // Which of the two kernels runs a layer (and so which workspace layout its filters take): the
-// persistent one where it takes the shape, this file's one-workgroup-per-band kernel otherwise.
+// persistent one where it takes the shape and its rounds of items come out even enough (or this
+// file's kernel does not take the shape), this file's one-workgroup-per-band kernel otherwise.
 static bool use_persistent(const Geom &g)
 {
-    return conv_mfma_persistent_supports(g);
+    if (!conv_mfma_persistent_supports(g)) return false;
+    return conv_mfma_persistent_preferred(g) || !make_plan(g, nullptr).ok;
 }
 
 bool conv_mfma_supports(const Geom &g)

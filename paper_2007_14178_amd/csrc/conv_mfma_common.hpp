@@ -44,6 +44,7 @@ constexpr size_t kLdsMax = 160 * 1024;
 // layer to it where it takes the shape.  `P` of the chained form holds
 // conv_mfma_persistent_sum_parts() partial sums per pixel.
 bool conv_mfma_persistent_supports(const Geom &g);
+bool conv_mfma_persistent_preferred(const Geom &g);   // ... and is expected to be the faster kernel
 ExpandLayout conv_mfma_persistent_expand_layout(const Geom &g);
 int conv_mfma_persistent_sum_parts(const Geom &g);
 hipError_t launch_conv_mfma_persistent(const uint32_t *Ipk, const float *K, const float *A, const float *alpha,

@@ -1490,6 +1490,22 @@ bool conv_mfma_persistent_supports(const Geom &g)
     return make_pplan(g, nullptr).ok;
 }
 
+bool conv_mfma_persistent_preferred(const Geom &g)
+{
+    // Items come in rounds of one per wave group (two groups per compute unit).  Up to one round the
+    // kernel's length is that of one (half) item; from three rounds on the uneven last round is a
+    // small part of the whole.  In between (measured at 1.5 rounds) one workgroup per band, handed
+    // out by the hardware as compute units fall free, ends sooner.
+    const PPlan pl = make_pplan(g, nullptr);
+    if (!pl.ok) return false;
+    int dev = 0;
+    const int cus = hipGetDevice(&dev) == hipSuccess ? compute_units(dev) : 256;
+    const long long bands = ceil_div((long long)g.N * g.OH, pl.TH);
+    const long long items_per_xcd = ceil_div(bands, kXcds) * pl.f_tiles;
+    const long long nslot = 2LL * std::max(1, cus / kXcds);
+    return items_per_xcd <= nslot || items_per_xcd >= 3 * nslot;
+}
+
 ExpandLayout conv_mfma_persistent_expand_layout(const Geom &g)
 {
     const PPlan pl = make_pplan(g, nullptr);   // the workspace layout does not depend on alignment
