@@ -169,6 +169,7 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
 #define RBOFF0 "v232"
 #define RBOFF1 "v233"
 #define RTMP0 "v234"
+#define RTMPQ "v[234:237]"
 #define RTMP1 "v235"
 #define RTMP2 "v236"
 #define RTMP3 "v237"
@@ -180,6 +181,9 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
 #define RT "v239"
 
 #define PX_MFMA(ACC, A, B) "v_mfma_f32_32x32x64_f8f6f4 %[" #ACC "], " A ", " B ", %[" #ACC "] cbsz:4 blgp:4\n\t"
+// an accumulator set to zero by the matrix pipe (0 x 0 + 0; RTMP0..3 hold zeros): eight of these take
+// the pipe 256 cycles while the wave goes on, where 128 v_mov would take the wave 512
+#define PX_ZERO(ACC) "v_mfma_f32_32x32x64_f8f6f4 %[" #ACC "], " RTMPQ ", " RTMPQ ", 0 cbsz:4 blgp:4\n\t"
 
 // One step s: filter operands (a0, a1) from ring slot s % 4, pixel operands x0..x3 from operand
 // buffer s % 2.  Everything a step fetches is for later steps:
@@ -250,9 +254,16 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
 // (behind the step's own last uses of them), the turn counter goes up, and `ev` says whether the next
 // turn has anything to do before it starts (a hook of the chunk hand-over, the release of the second
 // group, a change of issue priority); if not, the turn's end branches straight back to its start.
+// The step also reads the group's two hand-over counters into RPV (ready) and RT (done): issued
+// here, ahead of the step's last three operand reads, they have arrived when a hook at the next
+// turn's start has waited for lgkmcnt(3), and in the common case (the other waves are within a turn
+// of this one) they already show the count the hook waits for, which then costs no drain of the LDS
+// queue.  `pv` says that the two registers hold such a reading (the turns that expand a chunk use
+// them for other things).
 #define PX_CTL2 "v_add_u32 %[aoff], " PX_AINC ", %[aoff]\n\t" "v_add_u32 %[tab], " PX_TINC ", %[tab]\n\t" \
                 "s_add_u32 %[gi], %[gi], 1\n\t"
-#define PX_CTL3 "s_cmp_eq_u32 %[gi], %[t1]\n\t" "s_cselect_b32 %[ev], 1, 0\n\t" "s_cmp_eq_u32 %[gi], %[t2]\n\t"
+#define PX_CTL3 "ds_read_b32 " RPV ", %[ready]\n\t" "ds_read_b32 " RT ", %[done]\n\t" "s_mov_b32 %[pv], 1\n\t" \
+                "s_cmp_eq_u32 %[gi], %[t1]\n\t" "s_cselect_b32 %[ev], 1, 0\n\t" "s_cmp_eq_u32 %[gi], %[t2]\n\t"
 #define PX_CTL4 "s_cselect_b32 %[st2], 1, 0\n\t" "s_or_b32 %[ev], %[ev], %[st2]\n\t" "s_cmp_eq_u32 %[gi], %[t3]\n\t"
 #define PX_CTL5 "s_cselect_b32 %[st2], 1, 0\n\t" "s_or_b32 %[ev], %[ev], %[st2]\n\t" "s_cmp_eq_u32 %[gi], %[sturn]\n\t"
 #define PX_CTL6 "s_cselect_b32 %[st2], 1, 0\n\t" "s_or_b32 %[ev], %[ev], %[st2]\n\t" "s_and_b32 %[st2], %[gi], %[pmask]\n\t"
@@ -680,6 +691,7 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
 #define PX_LOOP_ASM                                                                                      \
     /* scalar state */                                                                                   \
     "s_mov_b32 %[gi], 0\n\t"                                                                             \
+    "s_mov_b32 %[pv], 0\n\t"                                                                             \
     "s_mov_b32 %[hc], 0\n\t"                                                                             \
     "s_mov_b32 %[t1], 0\n\t"                                                                             \
     "s_mov_b32 %[t2], 1\n\t"                                                                             \
@@ -699,6 +711,14 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
     "global_load_dwordx4 " RA20 ", %[aoff], %[Ab0] offset:2048\n\t"                                      \
     "global_load_dwordx4 " RA21 ", %[aoff], %[Ab1] offset:2048\n\t"                                      \
     "v_add_u32 %[aoff], 0xc00, %[aoff]\n\t"                                                              \
+    /* the accumulators start at zero */                                                                 \
+    "v_mov_b32 " RTMP0 ", 0\n\t"                                                                         \
+    "v_mov_b32 " RTMP1 ", 0\n\t"                                                                         \
+    "v_mov_b32 " RTMP2 ", 0\n\t"                                                                         \
+    "v_mov_b32 " RTMP3 ", 0\n\t"                                                                         \
+    "s_nop 4\n\t"                                                                                        \
+    PX_ZERO(acc00) PX_ZERO(acc01) PX_ZERO(acc02) PX_ZERO(acc03)                                          \
+    PX_ZERO(acc10) PX_ZERO(acc11) PX_ZERO(acc12) PX_ZERO(acc13)                                          \
     /* chunk 0 is complete in its buffer (all four waves have committed their part): waited for  */ \
     /* here, with the ring's first operands on their way                                          */ \
     "s_add_u32 %[tg], %[cbase], 4\n\t"                                                                   \
@@ -727,6 +747,8 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
     "v_add_u32 " RTMP3 ", %[bB3], " RBOFF1 "\n\t"                                                        \
     /* ---- the loop over ring turns ---- */                                                             \
     "Ltop%=:\n\t"                                                                                        \
+    /* (the counter readings of the turn before have landed: the hooks use their registers) */           \
+    "s_waitcnt lgkmcnt(3)\n\t"                                                                           \
     "s_cmp_eq_u32 %[gi], %[sturn]\n\t"                                                                   \
     "s_cbranch_scc1 Lhs%=\n\t"                                                                           \
     "Lhk%=:\n\t"                                                                                         \
@@ -763,6 +785,7 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
     "s_branch Ltop%=\n\t"                                                                                \
     /* the end of a turn that kept its bookkeeping for here (the turns that expand a chunk) */           \
     "Ltail%=:\n\t"                                                                                       \
+    "s_mov_b32 %[pv], 0\n\t"                                                                             \
     "v_add_u32 %[aoff], " PX_AINC ", %[aoff]\n\t"                                                        \
     "v_add_u32 %[tab], " PX_TINC ", %[tab]\n\t"                                                          \
     "s_add_u32 %[gi], %[gi], 1\n\t"                                                                      \
@@ -801,7 +824,15 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
     "s_cbranch_scc0 Lturn%=\n\t"                                                                         \
     "s_lshl_b32 %[tg], %[hc], 2\n\t"                                                                     \
     "s_add_u32 %[tg], %[tg], %[cbase]\n\t"                                                               \
+    "s_cmp_eq_u32 %[pv], 0\n\t"                                                                          \
+    "s_cbranch_scc1 Lh2s%=\n\t"                                                                          \
+    "v_readfirstlane_b32 %[st2], " RT "\n\t"                                                             \
+    "s_sub_u32 %[st2], %[st2], %[tg]\n\t"                                                                \
+    "s_cmp_ge_i32 %[st2], 0\n\t"                                                                         \
+    "s_cbranch_scc1 Lh2d%=\n\t"                                                                          \
+    "Lh2s%=:\n\t"                                                                                        \
     PX_WAIT(done, "a")                                                                                   \
+    "Lh2d%=:\n\t"                                                                                        \
     "s_and_b32 %[st], %[st], 1\n\t"                                                                      \
     "s_mul_i32 %[st], %[st], %[bufb]\n\t"                                                                \
     "s_cmp_eq_u32 %[onetile], 0\n\t"                                                                     \
@@ -826,7 +857,15 @@ __device__ __forceinline__ bool wait_count(uint32_t lds_addr, uint32_t target)
     "s_add_u32 %[tg], %[hc], 2\n\t"                                                                      \
     "s_lshl_b32 %[tg], %[tg], 2\n\t"                                                                     \
     "s_add_u32 %[tg], %[tg], %[cbase]\n\t"                                                               \
+    "s_cmp_eq_u32 %[pv], 0\n\t"                                                                          \
+    "s_cbranch_scc1 Lh3s%=\n\t"                                                                          \
+    "v_readfirstlane_b32 %[st2], " RPV "\n\t"                                                            \
+    "s_sub_u32 %[st2], %[st2], %[tg]\n\t"                                                                \
+    "s_cmp_ge_i32 %[st2], 0\n\t"                                                                         \
+    "s_cbranch_scc1 Lh3d%=\n\t"                                                                          \
+    "Lh3s%=:\n\t"                                                                                        \
     PX_WAIT(ready, "b")                                                                                  \
+    "Lh3d%=:\n\t"                                                                                        \
     "s_mov_b32 %[hc], %[st]\n\t"                                                                         \
     "s_add_u32 %[t1], %[t3], 1\n\t"                                                                      \
     "s_add_u32 %[t2], %[t3], 2\n\t"                                                                      \
@@ -1305,27 +1344,21 @@ __global__ __launch_bounds__(512) void conv_mfma_persistent_kernel(PParams p)
 
         // ---- the item becomes the current one ----
         cur = it;
-#pragma unroll
-        for (int i = 0; i < kWM; ++i)
-#pragma unroll
-            for (int j = 0; j < kWN; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
         XNOR_STAMP_K(kitem, 3);
 
         // ---- contract ----
         {
             uint32_t a_off = (uint32_t)fresh_lane() * 16u;   // byte offset of this lane's filter operand, step 0
             uint32_t tab_addr = tab_base;
-            int gi, hc, t1, t2, t3, st, st2, sp, tg, ev;
+            int gi, hc, t1, t2, t3, st, st2, sp, tg, ev, pv;
             unsigned long long sx;
             asm volatile(PX_LOOP_ASM
-                         : [acc00] "+v"(acc[0][0]), [acc01] "+v"(acc[0][1]), [acc02] "+v"(acc[0][2]),
-                           [acc03] "+v"(acc[0][3]), [acc10] "+v"(acc[1][0]), [acc11] "+v"(acc[1][1]),
-                           [acc12] "+v"(acc[1][2]), [acc13] "+v"(acc[1][3]), [aoff] "+v"(a_off),
+                         : [acc00] "=&v"(acc[0][0]), [acc01] "=&v"(acc[0][1]), [acc02] "=&v"(acc[0][2]),
+                           [acc03] "=&v"(acc[0][3]), [acc10] "=&v"(acc[1][0]), [acc11] "=&v"(acc[1][1]),
+                           [acc12] "=&v"(acc[1][2]), [acc13] "=&v"(acc[1][3]), [aoff] "+v"(a_off),
                            [tab] "+v"(tab_addr), [sturn] "+s"(sturn), [gi] "=&s"(gi), [hc] "=&s"(hc),
                            [t1] "=&s"(t1), [t2] "=&s"(t2), [t3] "=&s"(t3), [st] "=&s"(st), [st2] "=&s"(st2),
-                           [sp] "=&s"(sp), [tg] "=&s"(tg), [sx] "=&s"(sx), [ev] "=&s"(ev)
+                           [sp] "=&s"(sp), [tg] "=&s"(tg), [sx] "=&s"(sx), [ev] "=&s"(ev), [pv] "=&s"(pv)
                          : [bB0] "v"(bB[0]), [bB1] "v"(bB[1]), [bB2] "v"(bB[2]), [bB3] "v"(bB[3]),
                            [soff0] "v"(soff[0]), [soff1] "v"(soff[1]), [sdst0] "v"(sdst[0]), [sdst1] "v"(sdst[1]),
                            [ready] "v"(ready_addr), [done] "v"(done_addr), [start] "v"(start_addr),

@@ -49,9 +49,13 @@ def test_contraction_is_one_asm_region(asm_text, vw, chain):
     start = next(m.start() for m in re.finditer(r"^_ZN\S*" + name + r"\S*:", asm_text, re.M))
     lines = asm_text[start:asm_text.index("s_endpgm", start)].split("\n")
     mfma = [i for i, l in enumerate(lines) if l.strip().startswith("v_mfma")]
-    # the normal turn, the half-item turn, and the two turns that carry the chunk expansion
+    # the eight that set the accumulators to zero (0 x 0 + 0), the normal turn, the half-item turn,
+    # and the two turns that carry the chunk expansion
+    zeroing = [i for i in mfma if re.search(r"\], 0 cbsz", lines[i])]
+    assert len(zeroing) == 8 and zeroing == mfma[:8]
+    mfma = mfma[8:]
     assert len(mfma) == 32 + 16 + 32 + 16
-    begin = max(i for i in range(mfma[0]) if "ASMSTART" in lines[i])
+    begin = max(i for i in range(zeroing[0]) if "ASMSTART" in lines[i])
     end = min(i for i in range(mfma[-1], len(lines)) if "ASMEND" in lines[i])
     inside = lines[begin + 1:end]
     assert not any("ASMSTART" in l or "ASMEND" in l for l in inside), "the MFMAs lie in more than one asm statement"
