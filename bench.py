@@ -583,7 +583,7 @@ def run_vanilla_image(args, xb, torch, side):
         "dtype": "fp32", "data": "synthetic (seeded N(0,1) image and filter)",
         "config": {"workload": f"image {side}x{side}: N=1 C=1 F=1 3x3 stride 1 pad 1 (Table I)", "macs": 9 * side * side},
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
-                     "traffic": None, "kernel": "conv_fp32_direct_kernel (xnor_conv2d_fp32_fwd)", "kernel_ms": res["float"],
+                     "traffic": None, "kernel": "conv_fp32_rows_kernel (xnor_conv2d_fp32_fwd)", "kernel_ms": res["float"],
                      "timing": f"{reps} back-to-back launches per graph replay, events on the launch stream"},
         "xnor_vs_float": {"float_conv_ms": res["float"], "xnor_image_kernel_ms": res["xnor"],
                           "speedup": res["float"] / res["xnor"],

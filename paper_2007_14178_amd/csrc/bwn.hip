@@ -452,6 +452,58 @@ __global__ __launch_bounds__(256) void conv_fp32_direct_kernel(const float *__re
     out[o] = acc;
 }
 
+// Real-valued convolution for images of few channels (the shape of Tables I-III), unit stride
+// along x: a thread owns four consecutive outputs of one row of one filter plane, reads the KW + 3
+// inputs under them once per (channel, filter row) and stores 16 bytes.  The arithmetic is two
+// orders of magnitude below the memory traffic at these shapes; what matters is one coalesced
+// pass over the image and one over the output.
+template <int KW>
+__global__ __launch_bounds__(256) void conv_fp32_rows_kernel(const float *__restrict__ I,
+                                                             const float *__restrict__ Wt, Geom g,
+                                                             int xgroups, long long total,
+                                                             float *__restrict__ out)
+{
+    const long long o = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (o >= total) return;
+    const int xg = (int)(o % xgroups);
+    long long t = o / xgroups;
+    const int oy = (int)(t % g.OH);
+    t /= g.OH;
+    const int f = (int)(t % g.F);
+    const long long n = t / g.F;
+    const int ox0 = 4 * xg, ix0 = ox0 - g.pw;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < g.C; ++c) {
+        const float *plane = I + (n * g.C + c) * (long long)g.H * g.W;
+        const float *w = Wt + ((long long)f * g.C + c) * g.kh * KW;
+        for (int ky = 0; ky < g.kh; ++ky) {
+            const int iy = oy * g.sh - g.ph + ky;
+            if (iy < 0 || iy >= g.H) continue;
+            const float *row = plane + (long long)iy * g.W;
+            float v[KW + 3];
+#pragma unroll
+            for (int i = 0; i < KW + 3; ++i) {
+                const int ix = ix0 + i;
+                v[i] = (ix >= 0 && ix < g.W) ? row[ix] : 0.f;
+            }
+#pragma unroll
+            for (int kx = 0; kx < KW; ++kx) {
+                const float wk = w[ky * KW + kx];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[i] += v[i + kx] * wk;
+            }
+        }
+    }
+    float *dst = out + ((n * g.F + f) * g.OH + oy) * (long long)g.OW + ox0;
+    if (ox0 + 3 < g.OW && (g.OW & 3) == 0) {
+        *reinterpret_cast<float4 *>(dst) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (ox0 + i < g.OW) dst[i] = acc[i];
+    }
+}
+
 struct Plan {
     bool ok, ahead;
     int tiles, chan, rows_max, pitch;
@@ -577,6 +629,21 @@ hipError_t launch_conv_fp32_mfma(const float *I, const float *Wt, const Geom &g,
 
 hipError_t launch_conv_fp32_direct(const float *I, const float *Wt, const Geom &g, float *out, hipStream_t st)
 {
+    // few channels, unit stride along x, an odd window of up to 7 columns, output 16-byte aligned:
+    // four outputs per thread
+    if (g.C <= 4 && g.sw == 1 && (g.kw == 1 || g.kw == 3 || g.kw == 5 || g.kw == 7) &&
+        (reinterpret_cast<uintptr_t>(out) & 15) == 0) {
+        const int xgroups = ceil_div(g.OW, 4);
+        const long long total4 = (long long)g.N * g.F * g.OH * xgroups;
+        const unsigned blocks = (unsigned)ceil_div(total4, 256);
+        switch (g.kw) {
+            case 1: conv_fp32_rows_kernel<1><<<blocks, 256, 0, st>>>(I, Wt, g, xgroups, total4, out); break;
+            case 3: conv_fp32_rows_kernel<3><<<blocks, 256, 0, st>>>(I, Wt, g, xgroups, total4, out); break;
+            case 5: conv_fp32_rows_kernel<5><<<blocks, 256, 0, st>>>(I, Wt, g, xgroups, total4, out); break;
+            default: conv_fp32_rows_kernel<7><<<blocks, 256, 0, st>>>(I, Wt, g, xgroups, total4, out); break;
+        }
+        return hipGetLastError();
+    }
     const long long total = (long long)g.N * g.F * g.OH * g.OW;
     conv_fp32_direct_kernel<<<ceil_div(total, 256), 256, 0, st>>>(I, Wt, g, total, out);
     return hipGetLastError();

@@ -82,6 +82,9 @@ SHAPES = [
     (2, 40, 1, 1, 5, 1, 1, 1, 1, 0, 0),          # a staged plane of a single value
     (1, 24, 6, 500, 5, 3, 3, 1, 1, 1, 1),        # rows too wide to be fetched a chunk ahead
     (1, 1, 256, 256, 1, 3, 3, 1, 1, 1, 1),       # the paper's own workload shape (Table I)
+    (2, 3, 17, 19, 3, 5, 5, 2, 1, 2, 2),         # few channels: four outputs per thread, ragged row ends, row stride 2
+    (1, 4, 30, 44, 2, 7, 7, 1, 1, 3, 3),         # the same with the widest window and 16-byte stores
+    (1, 2, 9, 8, 5, 3, 1, 1, 1, 0, 0),           # one-column window
 ]
 
 
