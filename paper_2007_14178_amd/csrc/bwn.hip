@@ -23,6 +23,7 @@
 // Table I sets the XNOR convolution against: the A operand is then the fp32 weight itself, staged
 // per channel chunk in LDS as [tap][channel][filter] next to the input rows, and there is no alpha.
 //   conv_fp32_direct_kernel: one thread per output, any shape.
+//   conv_fp32_rows_kernel: few channels, unit stride along x: four outputs per thread.
 #include <algorithm>
 #include <atomic>
 
