@@ -1128,6 +1128,16 @@ __global__ __launch_bounds__(512) void conv_mfma_persistent_kernel(PParams p)
         const int lane_e = fresh_lane();
         const int l32e = lane_e & 31, kge = lane_e >> 5;
         const float *Alc = k_alpha_copy(kitem - 1) + kBandPixels;
+        // the lane's sixteen alphas of each of the wave's filter tiles (0 for filters that do not exist)
+        float al[kWM][16];
+        int t32s[kWM];
+#pragma unroll
+        for (int i = 0; i < kWM; ++i) {
+            t32s[i] = tile32_of(cur, cur.half >= 0 ? 0 : i);
+            const float *Alt = Alc + (t32s[i] - cur.ftile * (2 * kWM)) * 32;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) al[i][r] = Alt[8 * (r >> 2) + 4 * kge + (r & 3)];
+        }
 #pragma unroll
         for (int j = 0; j < kWN; ++j) {
             if (j >= cur.my_nt) break;
@@ -1138,20 +1148,22 @@ __global__ __launch_bounds__(512) void conv_mfma_persistent_kernel(PParams p)
 #pragma unroll
             for (int i = 0; i < kWM; ++i) {
                 if (i > 0 && cur.half >= 0) break;
-                const int t32 = tile32_of(cur, i);
-                const float *Alt = Alc + (t32 - cur.ftile * (2 * kWM)) * 32;
+                const int t32 = t32s[i];
                 uint32_t w = 0;
-                double asum = 0.0;
+                // |o| of the lane's 16 filters summed in fp32 (positive terms: within 16 * 2^-24 of
+                // their sum), the two half-words' sums added in double
+                float asum32 = 0.0f;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int row = 8 * (r >> 2) + 4 * kge + (r & 3);
-                    const float o = acc[i][j][r] * (kv * Alt[row]);
+                    const float o = acc[i][j][r] * (kv * al[i][r]);
                     if (t32 * 32 + row < p.F) {              // bits and sums of filters that exist only
                         w |= (o >= 0.0f ? 1u : 0u) << row;
-                        asum += (double)fabsf(o);
+                        asum32 += fabsf(o);
                     }
                 }
                 w |= (uint32_t)__shfl_xor((int)w, 32);
+                double asum = (double)asum32;
                 asum += __shfl_xor(asum, 32);
                 if (valid && kge == 0) {
                     if (t32 < p.Cwn) p.Opk[pix * p.Cwn + t32] = w;
