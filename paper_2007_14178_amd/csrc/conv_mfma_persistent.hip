@@ -1075,14 +1075,26 @@ __global__ __launch_bounds__(512) void conv_mfma_persistent_kernel(PParams p)
                 v32[j] = (uint32_t)lane_b[j];
                 asm volatile("" : "+v"(v32[j]));
             }
-            const char *ub = reinterpret_cast<const char *>(tile_base);
+            // (one copy of the 16 x NF stores per count of whole tiles: a test of `j < nfull` around
+            //  every store costs the wave two scalar instructions and a branch per store)
+            auto planes = [&](auto nf) {
+                constexpr int NF = decltype(nf)::value;
+                const char *ub = reinterpret_cast<const char *>(tile_base);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
+                for (int r = 0; r < 16; ++r) {
 #pragma unroll
-                for (int j = 0; j < kWN; ++j)
-                    if (j < nfull) *(ptr_t)(ub + v32[j]) = value(j, r);
-                ub += (r & 3) == 3 ? plane5 : plane1;
+                    for (int j = 0; j < NF; ++j) *(ptr_t)(ub + v32[j]) = value(j, r);
+                    ub += (r & 3) == 3 ? plane5 : plane1;
+                }
+            };
+            switch (nfull) {
+                case 4: planes(std::integral_constant<int, 4>{}); break;
+                case 3: planes(std::integral_constant<int, 3>{}); break;
+                case 2: planes(std::integral_constant<int, 2>{}); break;
+                case 1: planes(std::integral_constant<int, 1>{}); break;
+                default: break;
             }
+            static_assert(kWN == 4, "one case per count of whole tiles");
             first_slow = nfull;
         }
 #pragma unroll
