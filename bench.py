@@ -111,8 +111,10 @@ def parse():
     ap.add_argument("--k-in-prepare", action="store_true", help="form K with the box-filter launch on every layer")
     ap.add_argument("--no-graph", action="store_true",
                     help="skip the HIP-graph replay of the step (its time is reported beside the eager one)")
-    ap.add_argument("--conv-events-every", type=int, default=1,
-                    help="bracket the convolution launch with events on every n-th timed step only (0: never)")
+    ap.add_argument("--conv-events-every", type=int, default=-1,
+                    help="bracket the convolution launch with events on every n-th timed step only (0: never; "
+                         "default: about 250 of the timed steps, evenly spread: on the small layers two event "
+                         "records per step cost the host more than the step costs the GPU)")
     ap.add_argument("--peaks", action="store_true",
                     help="not the benchmark line: the ceilings this GPU sustains (register-only FP4 matrix loop, "
                          "v_xor + v_bcnt loop, plain copies of 64 MiB and 1 GiB), one JSON line")
@@ -270,13 +272,14 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # Timed region: K steps, with one pair of events per step around the convolution launch (the
-    # roofline figure).  The other stages' times come from a second, untimed pass with an event
+    # Timed region: K steps, with a pair of events around the convolution launch on about 250 of
+    # them, evenly spread (the roofline figure).  The other stages' times come from a second, untimed pass with an event
     # after every call: five event records per step cost the host about as much as the launches.
     events: list = []
+    every = args.conv_events_every if args.conv_events_every >= 0 else max(1, args.steps // 250)
     t0 = time.perf_counter()
     for k in range(args.steps):
-        if args.conv_events_every and k % args.conv_events_every == 0:
+        if every and k % every == 0:
             step(events, conv_only=True)
         else:
             step()
@@ -284,7 +287,7 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
     elapsed = time.perf_counter() - t0
     conv_events = [(m[-2], m[-1]) for m in events]
     events = []
-    for _ in range(args.steps):
+    for _ in range(min(args.steps, 250)):
         step(events)
     torch.cuda.synchronize()
 
