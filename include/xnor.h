@@ -67,8 +67,10 @@ typedef enum {
     XNOR_ALGO_TILED = 2,    /* LDS-staged packed halo, wave-uniform filter words, register tile   */
     XNOR_ALGO_MFMA = 3,     /* +-1 expanded to FP4 in LDS, v_mfma_f32_32x32x64_f8f6f4: persistent
                                workgroups where the shape allows, else as XNOR_ALGO_MFMA_BANDS    */
-    XNOR_ALGO_MFMA_BANDS = 4 /* the same arithmetic with one workgroup per band of output rows
+    XNOR_ALGO_MFMA_BANDS = 4, /* the same arithmetic with one workgroup per band of output rows
                                (xnor_conv2d_fwd_algo only; tests and measurements)                */
+    XNOR_ALGO_MFMA_SPLIT = 5 /* xnor_bwn_conv2d_fwd_algo only: the fp32 input split exactly into
+                               three bf16 terms, v_mfma_f32_32x32x16_bf16 against +-1 weights     */
 } xnor_algo;
 
 /* Host helpers (no GPU work). */
@@ -271,9 +273,15 @@ int xnor_forward_image(const float *I, const uint32_t *Wpk, const float *alpha, 
  *   out    out  fp32 [N][F][OH][OW]
  * The sum is formed in fp32 (fp32 matrix-core accumulation, or a short chain of fp32 partial sums
  * in the one-thread-per-output kernel); its rounding error is relative to alpha * sum |I| over the
- * window, not to |out|.  No workspace.  xnor_bwn_conv2d_fwd_algo: XNOR_ALGO_AUTO, XNOR_ALGO_DIRECT
- * (any shape) or XNOR_ALGO_MFMA (XNOR_E_UNSUPPORTED where the input rows under 32 output pixels do not
- * fit in 128 KB of LDS, or kh*kw > 64); other values XNOR_E_UNSUPPORTED.
+ * window, not to |out|.  No workspace.  xnor_bwn_conv2d_fwd_algo: XNOR_ALGO_AUTO (the first of
+ * MFMA_SPLIT, MFMA, DIRECT that takes the shape), XNOR_ALGO_DIRECT (any shape), XNOR_ALGO_MFMA (fp32
+ * matrix instruction with +-1.0 as one operand; XNOR_E_UNSUPPORTED where the input rows under 32
+ * output pixels do not fit in 128 KB of LDS, or kh*kw > 64) or XNOR_ALGO_MFMA_SPLIT (every input
+ * value split into three bf16 terms whose sum is the value, bf16 matrix instruction with +-1
+ * weights, fp32 accumulation: the same products, three instructions at 16 times the rate instead of
+ * eight; an input that is not finite gives NaN, not an infinity, and terms below 2^-133 are
+ * dropped; XNOR_E_UNSUPPORTED where 16 channels of the rows under the workgroup's pixels, as
+ * 6 bytes per value, do not fit in 64 KB of LDS, or kh*kw > 64); other values XNOR_E_UNSUPPORTED.
  */
 int xnor_bwn_conv2d_fwd(const float *I, const uint32_t *Wpk, const float *alpha, const xnor_shape *s,
                         float *out, void *stream);

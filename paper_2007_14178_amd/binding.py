@@ -16,9 +16,9 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libxnor_hip.so")
 
-ALGO_AUTO, ALGO_DIRECT, ALGO_TILED, ALGO_MFMA, ALGO_MFMA_BANDS = 0, 1, 2, 3, 4
+ALGO_AUTO, ALGO_DIRECT, ALGO_TILED, ALGO_MFMA, ALGO_MFMA_BANDS, ALGO_MFMA_SPLIT = 0, 1, 2, 3, 4, 5
 ALGO_NAMES = {ALGO_AUTO: "auto", ALGO_DIRECT: "direct", ALGO_TILED: "tiled", ALGO_MFMA: "mfma",
-              ALGO_MFMA_BANDS: "mfma_bands"}
+              ALGO_MFMA_BANDS: "mfma_bands", ALGO_MFMA_SPLIT: "mfma_split"}
 E_NULL, E_SHAPE, E_ALIGN, E_HIP, E_UNSUPPORTED, E_WORKSPACE = -1, -2, -3, -4, -5, -6
 
 

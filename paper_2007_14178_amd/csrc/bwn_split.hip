@@ -1,0 +1,364 @@
+// Binary-Weight-Network convolution (Sec. II-A, Eq. 1) on the bf16 matrix instruction, exact in its
+// operands: every fp32 input value x is split into three bf16 terms x = hi + mid + lo (each term
+// the leading eight significand bits of what the terms before it left over: the three differences
+// are exact in fp32 and 3 x 8 bits are the whole significand), the weights are +-1 (exact in bf16),
+// so the products are exact and the sum is accumulated in fp32 by v_mfma_f32_32x32x16_bf16: three
+// matrix instructions per 16 channels where the fp32 matrix instruction needs eight, at 16 times
+// its rate.
+//
+//   bwn_split_kernel: a workgroup (4 waves) owns 128 filters x up to 6 tiles of 32 consecutive
+//   output pixels of one image; wave = 64 filters (two filter tiles) x half of the pixel tiles.
+//   Per chunk of 16 channels the input rows under the pixels are fetched a chunk ahead (eight
+//   channels of one position per granule), split, and staged in LDS as
+//   [position][term][16 channels] bf16 (112 bytes per position: sixteen lanes' 16-byte reads or
+//   writes at consecutive positions touch distinct banks), zeros where the image ends (that is the
+//   zero padding).  The B operand of a matrix instruction is one 16-byte LDS read per lane (lane =
+//   pixel, eight channels), used for both filter tiles; the A operand (lane = filter, eight
+//   channels) is made in registers from eight bits of the filter's packed word.
+//   Inputs that are not finite give NaN where the fp32 sum would give an infinity (inf - inf in the
+//   split); what a term leaves below the bf16 subnormal range (2^-133) is dropped.
+#include <algorithm>
+
+#include "xnor_internal.hpp"
+
+namespace xnor {
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int kThreads = 256;
+constexpr int kFiltersPerWg = 128;     // 2 wave columns x 2 filter tiles x 32
+constexpr int kMaxTiles = 6;           // pixel tiles per workgroup: 2 wave rows x 3
+constexpr int kChan = 16;              // channels per chunk = the reduction length of one matrix instruction
+constexpr int kPosBytes = 112;         // 3 terms x 32 bytes + 16: see above
+constexpr int kGran = 3;               // granules (8 channels of one position) a thread fetches ahead per chunk
+constexpr int kPreWords = 8;           // filter words a thread fetches ahead per chunk (kh*kw <= 16)
+constexpr size_t kLdsBudget = 64 * 1024;
+
+struct SplitParams {
+    const float *I;
+    const uint32_t *Wpk;
+    const float *alpha;
+    float *out;
+    int N, C, H, W, F, kh, kw, sh, sw, ph, pw, OH, OW, Cw;
+    int tiles, groups, fgroups;
+    int rows_max, pitch, npos;     // staged rows, positions per row (W + 2*pw), rows_max * pitch
+    uint32_t inv_pitch;            // ceil(2^32 / pitch), 0 for pitch 1
+};
+
+__device__ inline uint32_t quot(uint32_t n, uint32_t inv) { return inv == 0 ? n : __umulhi(n, inv); }
+uint32_t reciprocal(unsigned long long d) { return d == 1 ? 0u : (uint32_t)(((1ULL << 32) + d - 1) / d); }
+
+// x = hi + mid + lo, each the top 16 bits of an fp32 (a bf16): the leading bits by truncation, the
+// rest by an exact subtraction
+__device__ inline void split3(float x, uint32_t &hi, uint32_t &mid, uint32_t &lo)
+{
+    hi = __float_as_uint(x) & 0xffff0000u;
+    const float r1 = x - __uint_as_float(hi);
+    mid = __float_as_uint(r1) & 0xffff0000u;
+    const float r2 = r1 - __uint_as_float(mid);
+    lo = __float_as_uint(r2) & 0xffff0000u;
+}
+// the low 16 bits of x in both halves of a dword
+__device__ inline uint32_t both_halves(uint32_t x) { return (x & 0xffffu) | (x << 16); }
+// two bf16 (given as the top halves of a and b) in one dword, a in the low half
+__device__ inline uint32_t pair16(uint32_t a, uint32_t b) { return (a >> 16) | b; }
+
+typedef unsigned short ushortx2 __attribute__((ext_vector_type(2)));
+
+// Sixteen inverted filter signs (1 = -1.0), the same in both halves of `w2`, -> the eight bf16 +-1.0
+// of this lane's channels: dword k holds channels 8*half + 2k (low) and 8*half + 2k + 1 (high).
+// One packed 16-bit shift brings the two sign bits to bits 15 and 31; `sh[k]` holds the two counts
+// (15 - 8*half - 2k in the low half, one less in the high half).
+__device__ inline bf16x8 signs_to_bf16(uint32_t w2, const uint32_t (&sh)[4])
+{
+    uint32_t d[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const ushortx2 y = __builtin_bit_cast(ushortx2, w2) << __builtin_bit_cast(ushortx2, sh[k]);
+        d[k] = 0x3F803F80u | (__builtin_bit_cast(uint32_t, y) & 0x80008000u);
+    }
+    return __builtin_bit_cast(bf16x8, make_uint4(d[0], d[1], d[2], d[3]));
+}
+
+// The work of one wave with NT pixel tiles (0: it only takes part in the staging).
+template <int NT>
+__device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, int n, int fbase, int p0,
+                                                          int p1, int tile0, int wf)
+{
+    extern __shared__ unsigned char lds_raw[];
+    unsigned char *tile = lds_raw;                                             // [npos][3][16] bf16, 112-byte pitch
+    // [taps][128]: the chunk's sixteen filter signs, inverted, in both halves of a dword
+    uint32_t *fw = reinterpret_cast<uint32_t *>(lds_raw + (size_t)p.npos * kPosBytes);
+
+    const int lane = threadIdx.x & 63;
+    const int col = lane & 31, half = lane >> 5;
+    const int OHW = p.OH * p.OW;
+    const int oy0 = p0 / p.OW, oy1 = (p1 - 1) / p.OW;
+    const int iy0 = oy0 * p.sh - p.ph;
+    const int rows = (oy1 - oy0) * p.sh + p.kh;         // <= rows_max
+    const int taps = p.kh * p.kw;
+
+    // per pixel tile: the lane's LDS byte offset of tap (0,0), its eight channels
+    int base[NT > 0 ? NT : 1];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+        const int px = min(p0 + 32 * (tile0 + j) + col, p1 - 1);
+        const int oy = px / p.OW, ox = px - oy * p.OW;
+        base[j] = ((oy - oy0) * p.sh * p.pitch + ox * p.sw) * kPosBytes + half * 16;
+    }
+
+    uint32_t shifts[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint32_t lo = (uint32_t)(15 - 8 * half - 2 * k);
+        shifts[k] = lo | ((lo - 1) << 16);
+    }
+
+    floatx16 acc[2][NT > 0 ? NT : 1];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int nchunks = (p.C + kChan - 1) / kChan;
+    const float *img = p.I + (size_t)n * p.C * p.H * p.W;
+    const int HW = p.H * p.W;
+    const int ngran = 2 * p.npos;                          // <= kGran * kThreads (the host's plan sees to it)
+    const bool words_ahead = taps * kFiltersPerWg <= kPreWords * kThreads;
+
+    float nxt[kGran][8];
+    uint32_t nxw[kPreWords];
+    // (the thread index passes through an empty asm in each call: otherwise the per-granule offsets,
+    // which do not change from chunk to chunk, are all kept in registers across the matrix loop)
+    auto prefetch = [&](int ch) __attribute__((always_inline)) {
+        const int c0 = ch * kChan;
+        int t0 = threadIdx.x;
+        asm volatile("" : "+v"(t0));
+#pragma unroll
+        for (int q = 0; q < kGran; ++q) {
+            if (q * kThreads >= ngran) break;                  // uniform
+            const int e = q * kThreads + t0;
+            const int o = e >= p.npos ? 1 : 0;
+            const uint32_t pos = (uint32_t)(e - o * p.npos);
+            const uint32_t r = quot(pos, p.inv_pitch);
+            const int xw = (int)(pos - r * (uint32_t)p.pitch);
+            const int iy = iy0 + (int)r, ix = xw - p.pw;
+            const bool ok = e < ngran && (int)r < rows && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
+            const int cg0 = c0 + 8 * o;
+            const unsigned at = (unsigned)((cg0 * p.H + iy) * p.W + ix);   // one image: below 2^30 floats
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const bool okk = ok && cg0 + k < p.C;
+                const float v = img[okk ? at + (unsigned)(k * HW) : 0u];
+                nxt[q][k] = okk ? v : 0.f;
+            }
+        }
+        if (words_ahead) {
+            const int cw = c0 >> 5, bit0 = c0 & 31;
+#pragma unroll
+            for (int q = 0; q < kPreWords; ++q) {
+                const int i = q * kThreads + t0;
+                const int t = i / kFiltersPerWg, f = fbase + (i - t * kFiltersPerWg);
+                nxw[q] = (i < taps * kFiltersPerWg && f < p.F)
+                             ? both_halves(~(p.Wpk[((size_t)f * taps + t) * p.Cw + cw] >> bit0)) : 0u;
+            }
+        }
+    };
+    auto commit = [&](int ch) __attribute__((always_inline)) {
+        int t0 = threadIdx.x;
+        asm volatile("" : "+v"(t0));
+#pragma unroll
+        for (int q = 0; q < kGran; ++q) {
+            if (q * kThreads >= ngran) break;                  // uniform
+            const int e = q * kThreads + t0;
+            if (e < ngran) {
+                const int o = e >= p.npos ? 1 : 0;
+                const int pos = e - o * p.npos;
+                uint32_t h[8], m[8], l[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) split3(nxt[q][k], h[k], m[k], l[k]);
+                uint4 *dst = reinterpret_cast<uint4 *>(tile + (size_t)pos * kPosBytes + o * 16);
+                dst[0] = make_uint4(pair16(h[0], h[1]), pair16(h[2], h[3]), pair16(h[4], h[5]), pair16(h[6], h[7]));
+                dst[2] = make_uint4(pair16(m[0], m[1]), pair16(m[2], m[3]), pair16(m[4], m[5]), pair16(m[6], m[7]));
+                dst[4] = make_uint4(pair16(l[0], l[1]), pair16(l[2], l[3]), pair16(l[4], l[5]), pair16(l[6], l[7]));
+            }
+        }
+        if (words_ahead) {
+#pragma unroll
+            for (int q = 0; q < kPreWords; ++q) {
+                const int i = q * kThreads + t0;
+                if (i < taps * kFiltersPerWg) fw[i] = nxw[q];
+            }
+        } else {
+            const int c0 = ch * kChan;
+            const int cw = c0 >> 5, bit0 = c0 & 31;
+            for (int i = threadIdx.x; i < taps * kFiltersPerWg; i += kThreads) {
+                const int t = i / kFiltersPerWg, f = fbase + (i - t * kFiltersPerWg);
+                fw[i] = f < p.F ? both_halves(~(p.Wpk[((size_t)f * taps + t) * p.Cw + cw] >> bit0)) : 0u;
+            }
+        }
+    };
+    auto read3 = [&](uint4 (&b)[3], int byte_off) __attribute__((always_inline)) {
+        const uint4 *src = reinterpret_cast<const uint4 *>(tile + byte_off);
+        b[0] = src[0];
+        b[1] = src[2];
+        b[2] = src[4];
+    };
+
+    prefetch(0);
+    for (int ch = 0; ch < nchunks; ++ch) {
+        __syncthreads();                                 // the previous chunk has been read
+        commit(ch);
+        __syncthreads();
+        if (ch + 1 < nchunks) prefetch(ch + 1);
+
+        if (NT > 0) {
+            // the flat sequence of (tap, pixel tile) steps; a step's three B operands are read one
+            // step ahead, the tap's two filter words one tap ahead
+            const uint32_t *wsrc = fw + wf * 64 + col;
+            uint32_t w0 = wsrc[0], w1 = wsrc[32];
+            uint4 bc[3], bn[3];
+            read3(bc, base[0]);
+            int toff = 0, kx = 0;
+            for (int tap = 0; tap < taps; ++tap) {
+                const bf16x8 a0 = signs_to_bf16(w0, shifts);
+                const bf16x8 a1 = signs_to_bf16(w1, shifts);
+                const int tn = min(tap + 1, taps - 1);
+                w0 = wsrc[tn * kFiltersPerWg];
+                w1 = wsrc[tn * kFiltersPerWg + 32];
+                // the next tap's offset: one position to the right, or to the start of the next window row
+                int toff_n = toff;
+                if (tap + 1 < taps) {
+                    if (kx + 1 == p.kw) toff_n += (p.pitch - p.kw + 1) * kPosBytes;
+                    else toff_n += kPosBytes;
+                }
+#pragma unroll
+                for (int j = 0; j < NT; ++j) {
+                    if (j + 1 < NT) read3(bn, base[j + 1] + toff);
+                    else read3(bn, base[0] + toff_n);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int t = 0; t < 3; ++t) {
+                        const bf16x8 b = __builtin_bit_cast(bf16x8, bc[t]);
+                        acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc[0][j], 0, 0, 0);
+                        acc[1][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc[1][j], 0, 0, 0);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int t = 0; t < 3; ++t) bc[t] = bn[t];
+                }
+                toff = toff_n;
+                kx = kx + 1 == p.kw ? 0 : kx + 1;
+            }
+        }
+    }
+
+    // accumulator register r of a lane: filter row 8*(r/4) + 4*half + r%4 of the filter tile,
+    // pixel column `col`
+    float *dst = p.out + (size_t)n * p.F * OHW;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        float al[16];
+        int fr[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            fr[r] = fbase + wf * 64 + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+            al[r] = fr[r] < p.F ? p.alpha[fr[r]] : 0.f;
+        }
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            const int px = p0 + 32 * (tile0 + j) + col;
+            if (px < p1) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (fr[r] < p.F) dst[(size_t)fr[r] * OHW + px] = acc[i][j][r] * al[r];
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads, 2) void bwn_split_kernel(SplitParams p)
+{
+    int b = blockIdx.x;
+    const int h = b % p.fgroups; b /= p.fgroups;
+    const int g = b % p.groups;
+    const int n = b / p.groups;
+    const int p0 = g * p.tiles * 32;
+    const int p1 = min(p.OH * p.OW, p0 + p.tiles * 32);
+    const int fbase = h * kFiltersPerWg;
+    const int nt = (p1 - p0 + 31) >> 5;                  // tiles this workgroup really has (1..6)
+    // wave -> (filter half, pixel half); the first pixel half takes the odd tile.  Every wave passes
+    // the same barriers whichever instance it runs (they count arrivals, not places in the code).
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const int wf = wave & 1, wp = wave >> 1;
+    const int first = (nt + 1) >> 1;
+    const int tile0 = wp ? first : 0;
+    int my_nt = wp ? nt - first : first;
+    if (fbase + wf * 64 >= p.F) my_nt = 0;                // no filters for this wave: staging only
+    switch (my_nt) {
+        case 0: split_wave<0>(p, n, fbase, p0, p1, tile0, wf); break;
+        case 1: split_wave<1>(p, n, fbase, p0, p1, tile0, wf); break;
+        case 2: split_wave<2>(p, n, fbase, p0, p1, tile0, wf); break;
+        default: split_wave<3>(p, n, fbase, p0, p1, tile0, wf); break;
+    }
+}
+
+struct SplitPlan {
+    bool ok;
+    int tiles, rows_max, pitch;
+    size_t lds;
+};
+
+SplitPlan make_split_plan(const Geom &g)
+{
+    SplitPlan pl{};
+    const long long OHW = (long long)g.OH * g.OW;
+    if (g.kh * g.kw > 64 || OHW > (1 << 24) || (long long)g.C * g.H * g.W >= (1LL << 30)) return pl;
+    pl.pitch = g.W + 2 * g.pw;
+    // Pixel tiles per workgroup, shared out evenly over the image's workgroups (as few workgroups
+    // per image as the tile limit allows: every workgroup stages its own input rows).
+    const int total = (int)((OHW + 31) / 32);
+    for (int most = std::min(kMaxTiles, total); most >= 1; --most) {
+        const int groups = ceil_div(total, most), tiles = ceil_div(total, groups);
+        // 32*tiles consecutive pixels span at most this many output rows
+        const int orows = (int)std::min<long long>(g.OH, (32LL * tiles + g.OW - 2) / g.OW + 1);
+        const int rows = (orows - 1) * g.sh + g.kh;
+        const long long npos = (long long)rows * pl.pitch;
+        const size_t lds = (size_t)npos * kPosBytes + (size_t)g.kh * g.kw * kFiltersPerWg * 4;
+        if (2 * npos <= (long long)kGran * kThreads && lds <= kLdsBudget) {
+            pl.ok = true; pl.tiles = tiles; pl.rows_max = rows; pl.lds = lds;
+            return pl;
+        }
+    }
+    return pl;
+}
+
+}  // namespace
+
+bool bwn_split_supports(const Geom &g) { return make_split_plan(g).ok; }
+
+hipError_t launch_bwn_split(const float *I, const uint32_t *Wpk, const float *alpha, const Geom &g,
+                            float *out, hipStream_t st)
+{
+    const SplitPlan pl = make_split_plan(g);
+    if (!pl.ok) return hipErrorInvalidValue;
+    SplitParams p;
+    p.I = I; p.Wpk = Wpk; p.alpha = alpha; p.out = out;
+    p.N = g.N; p.C = g.C; p.H = g.H; p.W = g.W; p.F = g.F; p.kh = g.kh; p.kw = g.kw;
+    p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw; p.OH = g.OH; p.OW = g.OW; p.Cw = g.Cw;
+    p.tiles = pl.tiles; p.rows_max = pl.rows_max; p.pitch = pl.pitch; p.npos = pl.rows_max * pl.pitch;
+    p.inv_pitch = reciprocal((unsigned long long)pl.pitch);
+    const long long OHW = (long long)g.OH * g.OW;
+    p.groups = ceil_div(OHW, 32LL * pl.tiles);
+    p.fgroups = ceil_div(g.F, kFiltersPerWg);
+    const long long blocks = (long long)g.N * p.groups * p.fgroups;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    bwn_split_kernel<<<dim3((unsigned)blocks), dim3(kThreads), pl.lds, st>>>(p);
+    return hipGetLastError();
+}
+
+}  // namespace xnor

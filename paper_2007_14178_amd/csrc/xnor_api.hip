@@ -338,10 +338,15 @@ int xnor_bwn_conv2d_fwd_algo(const float *I, const uint32_t *Wpk, const float *a
     const int rc = make_geom(s, &g);
     if (rc) return rc;
     if (!aligned(I, 4) || !aligned(Wpk, 4) || !aligned(alpha, 4) || !aligned(out, 4)) return XNOR_E_ALIGN;
-    if (algo == XNOR_ALGO_AUTO) algo = xnor::bwn_mfma_supports(g) ? XNOR_ALGO_MFMA : XNOR_ALGO_DIRECT;
+    if (algo == XNOR_ALGO_AUTO)
+        algo = xnor::bwn_split_supports(g) ? XNOR_ALGO_MFMA_SPLIT
+               : xnor::bwn_mfma_supports(g) ? XNOR_ALGO_MFMA : XNOR_ALGO_DIRECT;
     switch (algo) {
         case XNOR_ALGO_DIRECT:
             return hip_status(xnor::launch_bwn_direct(I, Wpk, alpha, g, out, (hipStream_t)stream));
+        case XNOR_ALGO_MFMA_SPLIT:
+            if (!xnor::bwn_split_supports(g)) return XNOR_E_UNSUPPORTED;
+            return hip_status(xnor::launch_bwn_split(I, Wpk, alpha, g, out, (hipStream_t)stream));
         case XNOR_ALGO_MFMA:
             if (!xnor::bwn_mfma_supports(g)) return XNOR_E_UNSUPPORTED;
             return hip_status(xnor::launch_bwn_mfma(I, Wpk, alpha, g, out, (hipStream_t)stream));

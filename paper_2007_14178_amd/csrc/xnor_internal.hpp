@@ -51,6 +51,9 @@ hipError_t launch_conv_image(const float *I, const uint32_t *Wpk, const float *a
                              float *out, int32_t *dot, hipStream_t st);
 
 bool bwn_mfma_supports(const Geom &g);
+bool bwn_split_supports(const Geom &g);
+hipError_t launch_bwn_split(const float *I, const uint32_t *Wpk, const float *alpha, const Geom &g,
+                            float *out, hipStream_t st);
 bool conv_fp32_mfma_supports(const Geom &g);
 hipError_t launch_conv_fp32_mfma(const float *I, const float *Wt, const Geom &g, float *out, hipStream_t st);
 hipError_t launch_conv_fp32_direct(const float *I, const float *Wt, const Geom &g, float *out, hipStream_t st);

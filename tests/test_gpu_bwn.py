@@ -45,11 +45,11 @@ def check(xb, full, I, Wt, algo, key):
     s = xb.Shape(*full)
     O_ref, S, a = oracle_bwn(key, I, Wt, oracle.Shape(*full))
     Wpk, alpha, _ = xb.xnor_filter_prepare(dev(Wt))
-    algo_id = {"auto": xb.ALGO_AUTO, "direct": xb.ALGO_DIRECT, "mfma": xb.ALGO_MFMA}[algo]
+    algo_id = {"auto": xb.ALGO_AUTO, "direct": xb.ALGO_DIRECT, "mfma": xb.ALGO_MFMA, "split": xb.ALGO_MFMA_SPLIT}[algo]
     try:
         out = xb.xnor_bwn_conv2d_fwd(dev(I), Wpk, alpha, s, algo=algo_id)
     except xb.XnorError as e:
-        if e.status == xb.E_UNSUPPORTED and algo == "mfma":
+        if e.status == xb.E_UNSUPPORTED and algo in ("mfma", "split"):
             pytest.skip("the matrix-core kernel does not take this shape")
         raise
     torch.cuda.synchronize()
@@ -85,7 +85,7 @@ SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("algo", ["direct", "mfma", "auto"])
+@pytest.mark.parametrize("algo", ["direct", "mfma", "split", "auto"])
 @pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(map(str, s)))
 def test_bwn_shapes_vs_oracle(xb, shape, algo):
     print(f"case bwn shape={shape} algo={algo}", flush=True)
@@ -102,9 +102,11 @@ def test_bwn_benchmark_layers_two_images(xb, name):
     I, Wt = make_input(L, n), make_weights(L)
     full = (n, L.C, L.H, L.W, L.F, L.kh, L.kw, L.sh, L.sw, L.ph, L.pw)
     out_m = check(xb, full, I, Wt, "mfma", name)
+    out_s = check(xb, full, I, Wt, "split", name)
     out_d = check(xb, full, I, Wt, "direct", name)
-    # the two kernels differ only in summation order
+    # the kernels differ only in summation order
     assert torch.allclose(out_m, out_d, rtol=0, atol=float(2e-5 * out_d.abs().max()))
+    assert torch.allclose(out_s, out_d, rtol=0, atol=float(2e-5 * out_d.abs().max()))
 
 
 def test_bwn_on_binary_input_equals_the_xnor_path(xb):
@@ -120,7 +122,7 @@ def test_bwn_on_binary_input_equals_the_xnor_path(xb):
     Wpk, alpha, _ = xb.xnor_filter_prepare(dev(Wt))
     Ipk, K, _ = xb.xnor_input_prepare(dI, s)
     _, dot = xb.xnor_conv2d_fwd(Ipk, Wpk, K, alpha, s, want_dot=True)
-    for algo in (xb.ALGO_DIRECT, xb.ALGO_MFMA):
+    for algo in (xb.ALGO_DIRECT, xb.ALGO_MFMA, xb.ALGO_MFMA_SPLIT):
         out = xb.xnor_bwn_conv2d_fwd(dI, Wpk, alpha, s, algo=algo)
         torch.cuda.synchronize()
         assert torch.equal(out, dot.float() * alpha[None, :, None, None])
