@@ -185,8 +185,11 @@ __device__ __attribute__((always_inline)) void bwn_workgroup(const BwnParams &p,
             for (int q = 0; q < kPreWords; ++q) {
                 const int i = q * kThreads + t0;
                 const int t = i / kFiltersPerWg, f = fbase + (i - t * kFiltersPerWg);
-                nxw[q] = (i < taps * kFiltersPerWg && f < p.F)
-                             ? p.Wpk[((size_t)f * taps + t) * p.Cw + cw] >> bit0 : 0u;
+                // (loaded unconditionally, from word 0 where there is no such filter or tap: a load
+                //  under a condition is waited for before the next one is issued)
+                const bool live = i < taps * kFiltersPerWg && f < p.F;
+                const uint32_t w = p.Wpk[live ? ((size_t)f * taps + t) * p.Cw + cw : 0];
+                nxw[q] = live ? w >> bit0 : 0u;
             }
         }
     };

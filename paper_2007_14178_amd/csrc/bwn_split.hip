@@ -132,8 +132,25 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
 
     float nxt[kGran][8];
     uint32_t nxw[kPreWords];
-    // (the thread index passes through an empty asm in each call: otherwise the per-granule offsets,
-    // which do not change from chunk to chunk, are all kept in registers across the matrix loop)
+    // Granule q of this thread in the chunk that starts at channel c0: its staged position and octet
+    // of channels, whether the position lies in the image and under the band's rows, and the offset
+    // of its first value in the image.  (The thread index passes through an empty asm in each use:
+    // otherwise the per-granule offsets, which do not change from chunk to chunk, are all kept in
+    // registers across the matrix loop.)
+    auto granule = [&](int q, int t0, int c0, int &pos, int &o, unsigned &at) __attribute__((always_inline)) -> bool {
+        const int e = q * kThreads + t0;
+        o = e >= p.npos ? 1 : 0;
+        pos = e - o * p.npos;
+        const uint32_t r = quot((uint32_t)pos, p.inv_pitch);
+        const int xw = (int)((uint32_t)pos - r * (uint32_t)p.pitch);
+        const int iy = iy0 + (int)r, ix = xw - p.pw;
+        at = (unsigned)(((c0 + 8 * o) * p.H + iy) * p.W + ix);   // one image: below 2^30 floats
+        return e < ngran && (int)r < rows && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
+    };
+    // Every load of the prefetch is unconditional (from the image's or the filters' first element
+    // where there is nothing to fetch) and nothing is done with its result here: what is not there
+    // becomes zero on commit.  (A select behind each load makes the compiler wait for each load
+    // before it issues the next.)
     auto prefetch = [&](int ch) __attribute__((always_inline)) {
         const int c0 = ch * kChan;
         int t0 = threadIdx.x;
@@ -141,46 +158,39 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
 #pragma unroll
         for (int q = 0; q < kGran; ++q) {
             if (q * kThreads >= ngran) break;                  // uniform
-            const int e = q * kThreads + t0;
-            const int o = e >= p.npos ? 1 : 0;
-            const uint32_t pos = (uint32_t)(e - o * p.npos);
-            const uint32_t r = quot(pos, p.inv_pitch);
-            const int xw = (int)(pos - r * (uint32_t)p.pitch);
-            const int iy = iy0 + (int)r, ix = xw - p.pw;
-            const bool ok = e < ngran && (int)r < rows && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
-            const int cg0 = c0 + 8 * o;
-            const unsigned at = (unsigned)((cg0 * p.H + iy) * p.W + ix);   // one image: below 2^30 floats
+            int pos, o;
+            unsigned at;
+            const bool ok = granule(q, t0, c0, pos, o, at);
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const bool okk = ok && cg0 + k < p.C;
-                const float v = img[okk ? at + (unsigned)(k * HW) : 0u];
-                nxt[q][k] = okk ? v : 0.f;
-            }
+            for (int k = 0; k < 8; ++k)
+                nxt[q][k] = img[(ok && c0 + 8 * o + k < p.C) ? at + (unsigned)(k * HW) : 0u];
         }
         if (words_ahead) {
-            const int cw = c0 >> 5, bit0 = c0 & 31;
+            const int cw = c0 >> 5;
 #pragma unroll
             for (int q = 0; q < kPreWords; ++q) {
                 const int i = q * kThreads + t0;
                 const int t = i / kFiltersPerWg, f = fbase + (i - t * kFiltersPerWg);
-                nxw[q] = (i < taps * kFiltersPerWg && f < p.F)
-                             ? both_halves(~(p.Wpk[((size_t)f * taps + t) * p.Cw + cw] >> bit0)) : 0u;
+                nxw[q] = p.Wpk[(i < taps * kFiltersPerWg && f < p.F) ? ((size_t)f * taps + t) * p.Cw + cw : 0];
             }
         }
     };
     auto commit = [&](int ch) __attribute__((always_inline)) {
+        const int c0 = ch * kChan;
+        const int cw = c0 >> 5, bit0 = c0 & 31;
         int t0 = threadIdx.x;
         asm volatile("" : "+v"(t0));
 #pragma unroll
         for (int q = 0; q < kGran; ++q) {
             if (q * kThreads >= ngran) break;                  // uniform
-            const int e = q * kThreads + t0;
-            if (e < ngran) {
-                const int o = e >= p.npos ? 1 : 0;
-                const int pos = e - o * p.npos;
+            int pos, o;
+            unsigned at;
+            const bool ok = granule(q, t0, c0, pos, o, at);
+            if (q * kThreads + t0 < ngran) {
                 uint32_t h[8], m[8], l[8];
 #pragma unroll
-                for (int k = 0; k < 8; ++k) split3(nxt[q][k], h[k], m[k], l[k]);
+                for (int k = 0; k < 8; ++k)
+                    split3((ok && c0 + 8 * o + k < p.C) ? nxt[q][k] : 0.f, h[k], m[k], l[k]);
                 uint4 *dst = reinterpret_cast<uint4 *>(tile + (size_t)pos * kPosBytes + o * 16);
                 dst[0] = make_uint4(pair16(h[0], h[1]), pair16(h[2], h[3]), pair16(h[4], h[5]), pair16(h[6], h[7]));
                 dst[2] = make_uint4(pair16(m[0], m[1]), pair16(m[2], m[3]), pair16(m[4], m[5]), pair16(m[6], m[7]));
@@ -191,11 +201,10 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
 #pragma unroll
             for (int q = 0; q < kPreWords; ++q) {
                 const int i = q * kThreads + t0;
-                if (i < taps * kFiltersPerWg) fw[i] = nxw[q];
+                const int t = i / kFiltersPerWg, f = fbase + (i - t * kFiltersPerWg);
+                if (i < taps * kFiltersPerWg) fw[i] = f < p.F ? both_halves(~(nxw[q] >> bit0)) : 0u;
             }
         } else {
-            const int c0 = ch * kChan;
-            const int cw = c0 >> 5, bit0 = c0 & 31;
             for (int i = threadIdx.x; i < taps * kFiltersPerWg; i += kThreads) {
                 const int t = i / kFiltersPerWg, f = fbase + (i - t * kFiltersPerWg);
                 fw[i] = f < p.F ? both_halves(~(p.Wpk[((size_t)f * taps + t) * p.Cw + cw] >> bit0)) : 0u;
@@ -217,42 +226,65 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
         if (ch + 1 < nchunks) prefetch(ch + 1);
 
         if (NT > 0) {
-            // the flat sequence of (tap, pixel tile) steps; a step's three B operands are read one
-            // step ahead, the tap's two filter words one tap ahead
+            // The flat sequence of (tap, pixel tile) steps, six matrix instructions each.  A step's
+            // three B operands are read two steps ahead, a tap's two filter words two taps ahead, and
+            // a tap's A operands are made among the matrix instructions of the tap before it.
             const uint32_t *wsrc = fw + wf * 64 + col;
-            uint32_t w0 = wsrc[0], w1 = wsrc[32];
-            uint4 bc[3], bn[3];
-            read3(bc, base[0]);
-            int toff = 0, kx = 0;
+            // (off, kx): byte offset and window column of tap `tap` -> of the tap after it: one position
+            // to the right, or to the start of the next window row; the last tap stays (reads beyond
+            // it are not used)
+            // (selects, no branches: the loop body stays one block for the instruction order below)
+            const int row_step = (p.pitch - p.kw + 1) * kPosBytes;
+            auto tap_after = [&](int &off, int &kx, int tap) {
+                const bool more = tap + 1 < taps, wrap = kx + 1 == p.kw;
+                off += more ? (wrap ? row_step : kPosBytes) : 0;
+                kx = more ? (wrap ? 0 : kx + 1) : kx;
+            };
+            int off0 = 0;
+            int off1 = 0, kx1 = 0;
+            tap_after(off1, kx1, 0);
+            int off2 = off1, kx2 = kx1;
+            tap_after(off2, kx2, 1);
+            const int t1 = min(1, taps - 1);
+            uint32_t wn0 = wsrc[t1 * kFiltersPerWg], wn1 = wsrc[t1 * kFiltersPerWg + 32];
+            bf16x8 a0 = signs_to_bf16(wsrc[0], shifts), a1 = signs_to_bf16(wsrc[32], shifts);
+            uint4 bc[3], bn[3], bf[3];
+            read3(bc, base[0] + off0);
+            read3(bn, NT > 1 ? base[NT > 1 ? 1 : 0] + off0 : base[0] + off1);   // (step 1: the second tile, or the second tap)
             for (int tap = 0; tap < taps; ++tap) {
-                const bf16x8 a0 = signs_to_bf16(w0, shifts);
-                const bf16x8 a1 = signs_to_bf16(w1, shifts);
-                const int tn = min(tap + 1, taps - 1);
-                w0 = wsrc[tn * kFiltersPerWg];
-                w1 = wsrc[tn * kFiltersPerWg + 32];
-                // the next tap's offset: one position to the right, or to the start of the next window row
-                int toff_n = toff;
-                if (tap + 1 < taps) {
-                    if (kx + 1 == p.kw) toff_n += (p.pitch - p.kw + 1) * kPosBytes;
-                    else toff_n += kPosBytes;
-                }
+                const int t2 = min(tap + 2, taps - 1);
+                const uint32_t wf0 = wsrc[t2 * kFiltersPerWg], wf1 = wsrc[t2 * kFiltersPerWg + 32];
+                bf16x8 a0n = a0, a1n = a1;
 #pragma unroll
                 for (int j = 0; j < NT; ++j) {
-                    if (j + 1 < NT) read3(bn, base[j + 1] + toff);
-                    else read3(bn, base[0] + toff_n);
-                    __builtin_amdgcn_sched_barrier(0);
+                    const int j2 = (j + 2) % NT, ahead = (j + 2) / NT;      // (constants once unrolled)
+                    read3(bf, base[j2] + (ahead == 0 ? off0 : ahead == 1 ? off1 : off2));
+                    if (j == 0) {
+                        a0n = signs_to_bf16(wn0, shifts);
+                        a1n = signs_to_bf16(wn1, shifts);
+                    }
 #pragma unroll
                     for (int t = 0; t < 3; ++t) {
                         const bf16x8 b = __builtin_bit_cast(bf16x8, bc[t]);
                         acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc[0][j], 0, 0, 0);
                         acc[1][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc[1][j], 0, 0, 0);
                     }
+                    // the order inside the step: the three reads, then the matrix instructions with the
+                    // vector instructions of the A operands between them
+                    __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+#pragma unroll
+                    for (int m = 0; m < 6; ++m) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        if (j == 0) __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int t = 0; t < 3; ++t) bc[t] = bn[t];
+                    for (int t = 0; t < 3; ++t) { bc[t] = bn[t]; bn[t] = bf[t]; }
                 }
-                toff = toff_n;
-                kx = kx + 1 == p.kw ? 0 : kx + 1;
+                a0 = a0n; a1 = a1n;
+                wn0 = wf0; wn1 = wf1;
+                off0 = off1; off1 = off2;
+                tap_after(off2, kx2, tap + 2);
             }
         }
     }
@@ -291,11 +323,13 @@ __global__ __launch_bounds__(kThreads, 2) void bwn_split_kernel(SplitParams p)
     const int p1 = min(p.OH * p.OW, p0 + p.tiles * 32);
     const int fbase = h * kFiltersPerWg;
     const int nt = (p1 - p0 + 31) >> 5;                  // tiles this workgroup really has (1..6)
-    // wave -> (filter half, pixel half); the first pixel half takes the odd tile.  Every wave passes
+    // wave -> (filter half, pixel half).  Every wave passes
     // the same barriers whichever instance it runs (they count arrivals, not places in the code).
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
     const int wf = wave & 1, wp = wave >> 1;
-    const int first = (nt + 1) >> 1;
+    // (which half takes the odd tile alternates between the workgroups that share a compute unit:
+    //  workgroup ids go round the 8 XCDs first)
+    const int first = (nt + 1 - (int)((blockIdx.x >> 3) & 1)) >> 1;
     const int tile0 = wp ? first : 0;
     int my_nt = wp ? nt - first : first;
     if (fbase + wf * 64 >= p.F) my_nt = 0;                // no filters for this wave: staging only
