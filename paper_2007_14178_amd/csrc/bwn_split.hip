@@ -51,33 +51,36 @@ __device__ inline uint32_t quot(uint32_t n, uint32_t inv) { return inv == 0 ? n 
 uint32_t reciprocal(unsigned long long d) { return d == 1 ? 0u : (uint32_t)(((1ULL << 32) + d - 1) / d); }
 
 // x = hi + mid + lo, each the top 16 bits of an fp32 (a bf16): the leading bits by truncation, the
-// rest by an exact subtraction
-__device__ inline void split3(float x, uint32_t &hi, uint32_t &mid, uint32_t &lo)
+// rest by an exact subtraction.  Returned are x, x - hi and x - hi - mid: the terms are their top
+// halves, which is all that pair16 takes of them.
+__device__ inline void split3(float x, uint32_t &t0, uint32_t &t1, uint32_t &t2)
 {
-    hi = __float_as_uint(x) & 0xffff0000u;
-    const float r1 = x - __uint_as_float(hi);
-    mid = __float_as_uint(r1) & 0xffff0000u;
-    const float r2 = r1 - __uint_as_float(mid);
-    lo = __float_as_uint(r2) & 0xffff0000u;
+    t0 = __float_as_uint(x);
+    const float r1 = x - __uint_as_float(t0 & 0xffff0000u);
+    t1 = __float_as_uint(r1);
+    const float r2 = r1 - __uint_as_float(t1 & 0xffff0000u);
+    t2 = __float_as_uint(r2);
 }
 // the low 16 bits of x in both halves of a dword
-__device__ inline uint32_t both_halves(uint32_t x) { return (x & 0xffffu) | (x << 16); }
-// two bf16 (given as the top halves of a and b) in one dword, a in the low half
-__device__ inline uint32_t pair16(uint32_t a, uint32_t b) { return (a >> 16) | b; }
+__device__ inline uint32_t both_halves(uint32_t x) { return __builtin_amdgcn_perm(x, x, 0x01000100u); }
+// the top halves of a and b in one dword, a's in the low half (one v_perm_b32)
+__device__ inline uint32_t pair16(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
 
 typedef unsigned short ushortx2 __attribute__((ext_vector_type(2)));
 
 // Sixteen inverted filter signs (1 = -1.0), the same in both halves of `w2`, -> the eight bf16 +-1.0
 // of this lane's channels: dword k holds channels 8*half + 2k (low) and 8*half + 2k + 1 (high).
 // One packed 16-bit shift brings the two sign bits to bits 15 and 31; `sh[k]` holds the two counts
-// (15 - 8*half - 2k in the low half, one less in the high half).
-__device__ inline bf16x8 signs_to_bf16(uint32_t w2, const uint32_t (&sh)[4])
+// (15 - 8*half - 2k in the low half, one less in the high half); `sign_mask` is 0x80008000 in a
+// scalar and `ones` 0x3F803F80 in a vector register (an instruction takes one literal or one scalar
+// register), so that the merge is one v_and_or_b32.
+__device__ inline bf16x8 signs_to_bf16(uint32_t w2, const uint32_t (&sh)[4], uint32_t sign_mask, uint32_t ones)
 {
     uint32_t d[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const ushortx2 y = __builtin_bit_cast(ushortx2, w2) << __builtin_bit_cast(ushortx2, sh[k]);
-        d[k] = 0x3F803F80u | (__builtin_bit_cast(uint32_t, y) & 0x80008000u);
+        d[k] = (__builtin_bit_cast(uint32_t, y) & sign_mask) | ones;
     }
     return __builtin_bit_cast(bf16x8, make_uint4(d[0], d[1], d[2], d[3]));
 }
@@ -109,6 +112,10 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
         base[j] = ((oy - oy0) * p.sh * p.pitch + ox * p.sw) * kPosBytes + half * 16;
     }
 
+    uint32_t sign_mask;
+    asm volatile("s_mov_b32 %0, 0x80008000" : "=s"(sign_mask));
+    uint32_t ones;
+    asm volatile("v_mov_b32 %0, 0x3f803f80" : "=v"(ones));
     uint32_t shifts[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
@@ -127,87 +134,87 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
     const int nchunks = (p.C + kChan - 1) / kChan;
     const float *img = p.I + (size_t)n * p.C * p.H * p.W;
     const int HW = p.H * p.W;
-    const int ngran = 2 * p.npos;                          // <= kGran * kThreads (the host's plan sees to it)
-    const bool words_ahead = taps * kFiltersPerWg <= kPreWords * kThreads;
 
-    float nxt[kGran][8];
-    uint32_t nxw[kPreWords];
-    // Granule q of this thread in the chunk that starts at channel c0: its staged position and octet
-    // of channels, whether the position lies in the image and under the band's rows, and the offset
-    // of its first value in the image.  (The thread index passes through an empty asm in each use:
-    // otherwise the per-granule offsets, which do not change from chunk to chunk, are all kept in
-    // registers across the matrix loop.)
-    auto granule = [&](int q, int t0, int c0, int &pos, int &o, unsigned &at) __attribute__((always_inline)) -> bool {
-        const int e = q * kThreads + t0;
-        o = e >= p.npos ? 1 : 0;
-        pos = e - o * p.npos;
+    // Staging.  A granule is eight channels of one staged position: thread t takes the positions
+    // q * 128 + t % 128 (q < kGran) of channel octet t / 128, which is the same for a whole wave, so
+    // the address of a value is a scalar base (the channel's plane) plus a lane offset that does
+    // not change from chunk to chunk (kept in registers, with one flag bit per granule: the position
+    // lies in the image and under the band's rows).  Every load is unconditional (offset 0, channel
+    // 0 where there is nothing to fetch) and nothing is done with its result until the commit, where
+    // what is not there becomes zero: a select behind each load would make the compiler wait for it
+    // before issuing the next.
+    const int tl = threadIdx.x & 127;
+    const int oct = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 7);
+    uint32_t voff[kGran];
+    uint32_t okbits = 0;
+#pragma unroll
+    for (int q = 0; q < kGran; ++q) {
+        const int pos = q * 128 + tl;
         const uint32_t r = quot((uint32_t)pos, p.inv_pitch);
         const int xw = (int)((uint32_t)pos - r * (uint32_t)p.pitch);
         const int iy = iy0 + (int)r, ix = xw - p.pw;
-        at = (unsigned)(((c0 + 8 * o) * p.H + iy) * p.W + ix);   // one image: below 2^30 floats
-        return e < ngran && (int)r < rows && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
-    };
-    // Every load of the prefetch is unconditional (from the image's or the filters' first element
-    // where there is nothing to fetch) and nothing is done with its result here: what is not there
-    // becomes zero on commit.  (A select behind each load makes the compiler wait for each load
-    // before it issues the next.)
+        const bool ok = pos < p.npos && (int)r < rows && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
+        voff[q] = ok ? (uint32_t)(iy * p.W + ix) * 4u : 0u;
+        okbits |= ok ? 1u << q : 0u;
+    }
+    // filter words: word i = q * 256 + t of [taps][128] is tap 2q + t / 128 (uniform) of filter t % 128
+    const bool words_ahead = taps * kFiltersPerWg <= kPreWords * kThreads;
+    const uint32_t woff = (uint32_t)min(fbase + tl, p.F - 1) * (uint32_t)(taps * p.Cw) * 4u;   // (below 2^31: the plan sees to it)
+
+    float nxt[kGran][8];
+    uint32_t nxw[kPreWords];
     auto prefetch = [&](int ch) __attribute__((always_inline)) {
-        const int c0 = ch * kChan;
-        int t0 = threadIdx.x;
-        asm volatile("" : "+v"(t0));
+        const int c0 = ch * kChan + 8 * oct;
 #pragma unroll
-        for (int q = 0; q < kGran; ++q) {
-            if (q * kThreads >= ngran) break;                  // uniform
-            int pos, o;
-            unsigned at;
-            const bool ok = granule(q, t0, c0, pos, o, at);
+        for (int k = 0; k < 8; ++k) {
+            const int c = c0 + k < p.C ? c0 + k : 0;                             // (scalar)
+            const char *plane_c = reinterpret_cast<const char *>(img + (size_t)c * HW);
 #pragma unroll
-            for (int k = 0; k < 8; ++k)
-                nxt[q][k] = img[(ok && c0 + 8 * o + k < p.C) ? at + (unsigned)(k * HW) : 0u];
+            for (int q = 0; q < kGran; ++q) {
+                if (q * 128 >= p.npos) break;                                    // uniform
+                nxt[q][k] = *reinterpret_cast<const float *>(plane_c + voff[q]);
+            }
         }
         if (words_ahead) {
-            const int cw = c0 >> 5;
+            const int cw = (ch * kChan) >> 5;
 #pragma unroll
             for (int q = 0; q < kPreWords; ++q) {
-                const int i = q * kThreads + t0;
-                const int t = i / kFiltersPerWg, f = fbase + (i - t * kFiltersPerWg);
-                nxw[q] = p.Wpk[(i < taps * kFiltersPerWg && f < p.F) ? ((size_t)f * taps + t) * p.Cw + cw : 0];
+                const int t = 2 * q + oct;                                       // (scalar)
+                if (t >= taps) break;
+                const char *wbase = reinterpret_cast<const char *>(p.Wpk + (size_t)t * p.Cw + cw);
+                nxw[q] = *reinterpret_cast<const uint32_t *>(wbase + woff);
             }
         }
     };
     auto commit = [&](int ch) __attribute__((always_inline)) {
-        const int c0 = ch * kChan;
-        const int cw = c0 >> 5, bit0 = c0 & 31;
-        int t0 = threadIdx.x;
-        asm volatile("" : "+v"(t0));
+        const int c0 = ch * kChan + 8 * oct;
+        const int cw = (ch * kChan) >> 5, bit0 = (ch * kChan) & 31;
 #pragma unroll
         for (int q = 0; q < kGran; ++q) {
-            if (q * kThreads >= ngran) break;                  // uniform
-            int pos, o;
-            unsigned at;
-            const bool ok = granule(q, t0, c0, pos, o, at);
-            if (q * kThreads + t0 < ngran) {
+            if (q * 128 >= p.npos) break;                      // uniform
+            const int pos = q * 128 + tl;
+            if (pos < p.npos) {
+                const bool ok = (okbits >> q) & 1u;
                 uint32_t h[8], m[8], l[8];
 #pragma unroll
-                for (int k = 0; k < 8; ++k)
-                    split3((ok && c0 + 8 * o + k < p.C) ? nxt[q][k] : 0.f, h[k], m[k], l[k]);
-                uint4 *dst = reinterpret_cast<uint4 *>(tile + (size_t)pos * kPosBytes + o * 16);
+                for (int k = 0; k < 8; ++k) split3((ok && c0 + k < p.C) ? nxt[q][k] : 0.f, h[k], m[k], l[k]);
+                uint4 *dst = reinterpret_cast<uint4 *>(tile + (size_t)pos * kPosBytes + oct * 16);
                 dst[0] = make_uint4(pair16(h[0], h[1]), pair16(h[2], h[3]), pair16(h[4], h[5]), pair16(h[6], h[7]));
                 dst[2] = make_uint4(pair16(m[0], m[1]), pair16(m[2], m[3]), pair16(m[4], m[5]), pair16(m[6], m[7]));
                 dst[4] = make_uint4(pair16(l[0], l[1]), pair16(l[2], l[3]), pair16(l[4], l[5]), pair16(l[6], l[7]));
             }
         }
         if (words_ahead) {
+            // (a filter past the last one holds the last one's signs: its outputs are not stored)
 #pragma unroll
             for (int q = 0; q < kPreWords; ++q) {
-                const int i = q * kThreads + t0;
-                const int t = i / kFiltersPerWg, f = fbase + (i - t * kFiltersPerWg);
-                if (i < taps * kFiltersPerWg) fw[i] = f < p.F ? both_halves(~(nxw[q] >> bit0)) : 0u;
+                if (2 * q + oct >= taps) break;                // uniform
+                fw[q * kThreads + (int)threadIdx.x] = both_halves(~(nxw[q] >> bit0));
             }
         } else {
             for (int i = threadIdx.x; i < taps * kFiltersPerWg; i += kThreads) {
-                const int t = i / kFiltersPerWg, f = fbase + (i - t * kFiltersPerWg);
-                fw[i] = f < p.F ? both_halves(~(p.Wpk[((size_t)f * taps + t) * p.Cw + cw] >> bit0)) : 0u;
+                const int t = i / kFiltersPerWg, f = min(fbase + (i - t * kFiltersPerWg), p.F - 1);
+                fw[i] = both_halves(~(p.Wpk[((size_t)f * taps + t) * p.Cw + cw] >> bit0));
             }
         }
     };
@@ -247,7 +254,7 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
             tap_after(off2, kx2, 1);
             const int t1 = min(1, taps - 1);
             uint32_t wn0 = wsrc[t1 * kFiltersPerWg], wn1 = wsrc[t1 * kFiltersPerWg + 32];
-            bf16x8 a0 = signs_to_bf16(wsrc[0], shifts), a1 = signs_to_bf16(wsrc[32], shifts);
+            bf16x8 a0 = signs_to_bf16(wsrc[0], shifts, sign_mask, ones), a1 = signs_to_bf16(wsrc[32], shifts, sign_mask, ones);
             uint4 bc[3], bn[3], bf[3];
             read3(bc, base[0] + off0);
             read3(bn, NT > 1 ? base[NT > 1 ? 1 : 0] + off0 : base[0] + off1);   // (step 1: the second tile, or the second tap)
@@ -260,8 +267,8 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
                     const int j2 = (j + 2) % NT, ahead = (j + 2) / NT;      // (constants once unrolled)
                     read3(bf, base[j2] + (ahead == 0 ? off0 : ahead == 1 ? off1 : off2));
                     if (j == 0) {
-                        a0n = signs_to_bf16(wn0, shifts);
-                        a1n = signs_to_bf16(wn1, shifts);
+                        a0n = signs_to_bf16(wn0, shifts, sign_mask, ones);
+                        a1n = signs_to_bf16(wn1, shifts, sign_mask, ones);
                     }
 #pragma unroll
                     for (int t = 0; t < 3; ++t) {
@@ -352,6 +359,7 @@ SplitPlan make_split_plan(const Geom &g)
     SplitPlan pl{};
     const long long OHW = (long long)g.OH * g.OW;
     if (g.kh * g.kw > 64 || OHW > (1 << 24) || (long long)g.C * g.H * g.W >= (1LL << 30)) return pl;
+    if ((long long)g.F * g.kh * g.kw * g.Cw >= (1LL << 29)) return pl;     // (32-bit byte offsets into Wpk)
     pl.pitch = g.W + 2 * g.pw;
     // Pixel tiles per workgroup, shared out evenly over the image's workgroups (as few workgroups
     // per image as the tile limit allows: every workgroup stages its own input rows).
