@@ -18,6 +18,9 @@
 //   Inputs that are not finite give NaN where the fp32 sum would give an infinity (inf - inf in the
 //   split); what a term leaves below the bf16 subnormal range (2^-133) is dropped.
 #include <algorithm>
+#ifndef SPLIT_EXP
+#define SPLIT_EXP 0
+#endif
 
 #include "xnor_internal.hpp"
 
@@ -227,12 +230,18 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
 
     prefetch(0);
     for (int ch = 0; ch < nchunks; ++ch) {
+#if SPLIT_EXP == 1 || SPLIT_EXP >= 3
+        if (ch == 0) {
+#endif
         __syncthreads();                                 // the previous chunk has been read
         commit(ch);
         __syncthreads();
         if (ch + 1 < nchunks) prefetch(ch + 1);
+#if SPLIT_EXP == 1 || SPLIT_EXP >= 3
+        }
+#endif
 
-        if (NT > 0) {
+        if (NT > 0 && SPLIT_EXP != 2) {
             // The flat sequence of (tap, pixel tile) steps, six matrix instructions each.  A step's
             // three B operands are read two steps ahead, a tap's two filter words two taps ahead, and
             // a tap's A operands are made among the matrix instructions of the tap before it.
@@ -265,8 +274,11 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
 #pragma unroll
                 for (int j = 0; j < NT; ++j) {
                     const int j2 = (j + 2) % NT, ahead = (j + 2) / NT;      // (constants once unrolled)
+#if SPLIT_EXP == 3 || SPLIT_EXP == 5
+                    if (tap == 0 && ch == 0)
+#endif
                     read3(bf, base[j2] + (ahead == 0 ? off0 : ahead == 1 ? off1 : off2));
-                    if (j == 0) {
+                    if (j == 0 && SPLIT_EXP < 4) {
                         a0n = signs_to_bf16(wn0, shifts, sign_mask, ones);
                         a1n = signs_to_bf16(wn1, shifts, sign_mask, ones);
                     }
@@ -361,8 +373,10 @@ SplitPlan make_split_plan(const Geom &g)
     if (g.kh * g.kw > 64 || OHW > (1 << 24) || (long long)g.C * g.H * g.W >= (1LL << 30)) return pl;
     if ((long long)g.F * g.kh * g.kw * g.Cw >= (1LL << 29)) return pl;     // (32-bit byte offsets into Wpk)
     pl.pitch = g.W + 2 * g.pw;
-    // Pixel tiles per workgroup, shared out evenly over the image's workgroups (as few workgroups
-    // per image as the tile limit allows: every workgroup stages its own input rows).
+    // Pixel tiles per workgroup: as few workgroups per image as the tile limit, the prefetch
+    // registers and the LDS allow (every workgroup stages its own input rows), the tiles shared out
+    // evenly over them.  (Workgroups of six tiles and a short last one measured no faster at
+    // 28 x 28 outputs and slower at 14 x 14.)
     const int total = (int)((OHW + 31) / 32);
     for (int most = std::min(kMaxTiles, total); most >= 1; --most) {
         const int groups = ceil_div(total, most), tiles = ceil_div(total, groups);
@@ -371,7 +385,7 @@ SplitPlan make_split_plan(const Geom &g)
         const int rows = (orows - 1) * g.sh + g.kh;
         const long long npos = (long long)rows * pl.pitch;
         const size_t lds = (size_t)npos * kPosBytes + (size_t)g.kh * g.kw * kFiltersPerWg * 4;
-        if (2 * npos <= (long long)kGran * kThreads && lds <= kLdsBudget) {
+        if (npos <= (long long)kGran * 128 && lds <= kLdsBudget) {
             pl.ok = true; pl.tiles = tiles; pl.rows_max = rows; pl.lds = lds;
             return pl;
         }
