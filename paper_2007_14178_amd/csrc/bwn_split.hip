@@ -18,9 +18,8 @@
 //   Inputs that are not finite give NaN where the fp32 sum would give an infinity (inf - inf in the
 //   split); what a term leaves below the bf16 subnormal range (2^-133) is dropped.
 #include <algorithm>
-#ifndef SPLIT_EXP
-#define SPLIT_EXP 0
-#endif
+#include <atomic>
+#include <type_traits>
 
 #include "xnor_internal.hpp"
 
@@ -36,8 +35,9 @@ constexpr int kMaxTiles = 6;           // pixel tiles per workgroup: 2 wave rows
 constexpr int kChan = 16;              // channels per chunk = the reduction length of one matrix instruction
 constexpr int kPosBytes = 112;         // 3 terms x 32 bytes + 16: see above
 constexpr int kGran = 3;               // granules (8 channels of one position) a thread fetches ahead per chunk
-constexpr int kPreWords = 8;           // filter words a thread fetches ahead per chunk (kh*kw <= 16)
-constexpr size_t kLdsBudget = 64 * 1024;
+constexpr int kPreWords = 8;           // filter words a thread fetches per chunk: half of the taps of a 32-channel word (kh*kw <= 32)
+constexpr int kDumpBytes = 1024;       // 64 lanes x 8 bytes, the three terms 32 bytes apart
+constexpr size_t kLdsBudget = 160 * 1024;  // all buffers of a workgroup (up to 80 KB: two workgroups per compute unit)
 
 struct SplitParams {
     const float *I;
@@ -93,10 +93,15 @@ template <int NT>
 __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, int n, int fbase, int p0,
                                                           int p1, int tile0, int wf)
 {
+    // LDS: two input buffers, taken in turn by the chunks, each [npos][3][16] bf16 at a 112-byte
+    // pitch followed by a dump slot for the staging writes of threads without a position; then two
+    // filter-word buffers, taken in turn by the 32-channel words (a word serves two chunks), each
+    // [taps][128] packed words as they come.
     extern __shared__ unsigned char lds_raw[];
-    unsigned char *tile = lds_raw;                                             // [npos][3][16] bf16, 112-byte pitch
-    // [taps][128]: the chunk's sixteen filter signs, inverted, in both halves of a dword
-    uint32_t *fw = reinterpret_cast<uint32_t *>(lds_raw + (size_t)p.npos * kPosBytes);
+    const int tile_bytes = p.npos * kPosBytes + kDumpBytes;
+    const int words_bytes = p.kh * p.kw * kFiltersPerWg * 4;
+    unsigned char *const words_lds = lds_raw + 2 * tile_bytes;
+    const int dump_off = p.npos * kPosBytes;
 
     const int lane = threadIdx.x & 63;
     const int col = lane & 31, half = lane >> 5;
@@ -149,10 +154,12 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
     const int tl = threadIdx.x & 127;
     const int oct = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 7);
     uint32_t voff[kGran];
+    int wr_off[kGran];         // where the granule goes in a buffer (a position past the last: the dump slot)
     uint32_t okbits = 0;
 #pragma unroll
     for (int q = 0; q < kGran; ++q) {
         const int pos = q * 128 + tl;
+        wr_off[q] = pos < p.npos ? pos * kPosBytes + oct * 16 : dump_off + (int)(threadIdx.x & 63) * 8;
         const uint32_t r = quot((uint32_t)pos, p.inv_pitch);
         const int xw = (int)((uint32_t)pos - r * (uint32_t)p.pitch);
         const int iy = iy0 + (int)r, ix = xw - p.pw;
@@ -161,7 +168,6 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
         okbits |= ok ? 1u << q : 0u;
     }
     // filter words: word i = q * 256 + t of [taps][128] is tap 2q + t / 128 (uniform) of filter t % 128
-    const bool words_ahead = taps * kFiltersPerWg <= kPreWords * kThreads;
     const uint32_t woff = (uint32_t)min(fbase + tl, p.F - 1) * (uint32_t)(taps * p.Cw) * 4u;   // (below 2^31: the plan sees to it)
 
     float nxt[kGran][8];
@@ -178,83 +184,112 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
                 nxt[q][k] = *reinterpret_cast<const float *>(plane_c + voff[q]);
             }
         }
-        if (words_ahead) {
-            const int cw = (ch * kChan) >> 5;
+    };
+    // Filter words.  Word cw (32 channels) serves chunks 2cw and 2cw + 1 and is staged while word
+    // cw - 1 is in use, half of its taps per chunk: part h = taps 16h .. 16h + 15, thread t takes
+    // tap 16h + 2q + t / 128 (q < 8; the same for a whole wave) of filter t % 128.
+    auto words_load = [&](int cw, int h) __attribute__((always_inline)) {
+        if (cw >= p.Cw) return;
 #pragma unroll
-            for (int q = 0; q < kPreWords; ++q) {
-                const int t = 2 * q + oct;                                       // (scalar)
-                if (t >= taps) break;
-                const char *wbase = reinterpret_cast<const char *>(p.Wpk + (size_t)t * p.Cw + cw);
-                nxw[q] = *reinterpret_cast<const uint32_t *>(wbase + woff);
-            }
+        for (int q = 0; q < kPreWords; ++q) {
+            const int t = 16 * h + 2 * q + oct;                                  // (scalar)
+            if (t >= taps) break;
+            const char *wbase = reinterpret_cast<const char *>(p.Wpk + (size_t)t * p.Cw + cw);
+            nxw[q] = *reinterpret_cast<const uint32_t *>(wbase + woff);
         }
     };
-    auto commit = [&](int ch) __attribute__((always_inline)) {
-        const int c0 = ch * kChan + 8 * oct;
-        const int cw = (ch * kChan) >> 5, bit0 = (ch * kChan) & 31;
+    // (a filter past the last one holds the last one's signs: its outputs are not stored)
+    auto words_commit = [&](int cw, int h) __attribute__((always_inline)) {
+        if (cw >= p.Cw) return;
+        uint32_t *fw_w = reinterpret_cast<uint32_t *>(words_lds + (cw & 1) * words_bytes) + h * (16 * kFiltersPerWg);
 #pragma unroll
-        for (int q = 0; q < kGran; ++q) {
-            if (q * 128 >= p.npos) break;                      // uniform
-            const int pos = q * 128 + tl;
-            if (pos < p.npos) {
-                const bool ok = (okbits >> q) & 1u;
-                uint32_t h[8], m[8], l[8];
-#pragma unroll
-                for (int k = 0; k < 8; ++k) split3((ok && c0 + k < p.C) ? nxt[q][k] : 0.f, h[k], m[k], l[k]);
-                uint4 *dst = reinterpret_cast<uint4 *>(tile + (size_t)pos * kPosBytes + oct * 16);
-                dst[0] = make_uint4(pair16(h[0], h[1]), pair16(h[2], h[3]), pair16(h[4], h[5]), pair16(h[6], h[7]));
-                dst[2] = make_uint4(pair16(m[0], m[1]), pair16(m[2], m[3]), pair16(m[4], m[5]), pair16(m[6], m[7]));
-                dst[4] = make_uint4(pair16(l[0], l[1]), pair16(l[2], l[3]), pair16(l[4], l[5]), pair16(l[6], l[7]));
-            }
+        for (int q = 0; q < kPreWords; ++q) {
+            if (16 * h + 2 * q + oct >= taps) break;                             // uniform
+            fw_w[q * kThreads + (int)threadIdx.x] = nxw[q];
         }
-        if (words_ahead) {
-            // (a filter past the last one holds the last one's signs: its outputs are not stored)
+    };
+    // The commit of chunk `ch` into buffer ch % 2 comes in kPieces pieces, so that each can be laid
+    // among the matrix instructions of one step of the chunk before: pieces 0 .. 2*kGran - 1 split
+    // and write one half (four channels) of granule s / 2, the last piece writes the filter words
+    // fetched a chunk ago, fetches the next ones and issues the loads of chunk ch + 1 into the
+    // registers just freed.
+    constexpr int kPieces = 2 * kGran + 1;
+    auto commit_piece = [&](auto piece_c, int ch) __attribute__((always_inline)) {
+        constexpr int S = decltype(piece_c)::value;
+        unsigned char *tile_w = lds_raw + (ch & 1) * tile_bytes;
+        if constexpr (S < 2 * kGran) {
+            constexpr int q = S >> 1, hf = S & 1;
+            const int c0 = ch * kChan + 8 * oct + 4 * hf;
+            // (no branch, uniform or not: the piece has to stay in the block of the step's matrix
+            //  instructions; a position past the last one goes to the dump slot)
+            const bool ok = (okbits >> q) & 1u;
+            uint32_t h[4], m[4], l[4];
 #pragma unroll
-            for (int q = 0; q < kPreWords; ++q) {
-                if (2 * q + oct >= taps) break;                // uniform
-                fw[q * kThreads + (int)threadIdx.x] = both_halves(~(nxw[q] >> bit0));
-            }
+            for (int k = 0; k < 4; ++k)
+                split3((ok && c0 + k < p.C) ? nxt[q][4 * hf + k] : 0.f, h[k], m[k], l[k]);
+            uint2 *dst = reinterpret_cast<uint2 *>(tile_w + wr_off[q] + hf * 8);
+            dst[0] = make_uint2(pair16(h[0], h[1]), pair16(h[2], h[3]));
+            dst[4] = make_uint2(pair16(m[0], m[1]), pair16(m[2], m[3]));
+            dst[8] = make_uint2(pair16(l[0], l[1]), pair16(l[2], l[3]));
         } else {
-            for (int i = threadIdx.x; i < taps * kFiltersPerWg; i += kThreads) {
-                const int t = i / kFiltersPerWg, f = min(fbase + (i - t * kFiltersPerWg), p.F - 1);
-                fw[i] = both_halves(~(p.Wpk[((size_t)f * taps + t) * p.Cw + cw] >> bit0));
-            }
+            // while chunk ch - 1 runs: the part of word (ch - 1) / 2 + 1 fetched a chunk ago is written,
+            // the next part is fetched
+            const int cw_next = ((ch - 1) >> 1) + 1, h = (ch - 1) & 1;
+            words_commit(cw_next, h);
+            if (h == 0) words_load(cw_next, 1);
+            else words_load(cw_next + 1, 0);
+            if (ch + 1 < nchunks) prefetch(ch + 1);
         }
     };
-    auto read3 = [&](uint4 (&b)[3], int byte_off) __attribute__((always_inline)) {
-        const uint4 *src = reinterpret_cast<const uint4 *>(tile + byte_off);
-        b[0] = src[0];
-        b[1] = src[2];
-        b[2] = src[4];
+    // pieces `from` .. kPieces - 1 of chunk ch, one after the other
+    auto commit_rest = [&](int from, int ch, bool last_too = true) __attribute__((always_inline)) {
+        if (from <= 0) commit_piece(std::integral_constant<int, 0>{}, ch);
+        if (from <= 1) commit_piece(std::integral_constant<int, 1>{}, ch);
+        if (from <= 2) commit_piece(std::integral_constant<int, 2>{}, ch);
+        if (from <= 3) commit_piece(std::integral_constant<int, 3>{}, ch);
+        if (from <= 4) commit_piece(std::integral_constant<int, 4>{}, ch);
+        if (from <= 5) commit_piece(std::integral_constant<int, 5>{}, ch);
+        if (from <= 6 && last_too) commit_piece(std::integral_constant<int, 6>{}, ch);
+        static_assert(kPieces == 7, "one line per piece");
     };
 
+    // before the first chunk: word 0 whole, chunk 0, and in flight: the first part of word 1 and chunk 1
+    words_load(0, 0);
     prefetch(0);
+    words_commit(0, 0);
+    words_load(0, 1);
+    commit_rest(0, 0, false);
+    words_commit(0, 1);
+    words_load(1, 0);
+    if (nchunks > 1) prefetch(1);
+    __syncthreads();
     for (int ch = 0; ch < nchunks; ++ch) {
-#if SPLIT_EXP == 1 || SPLIT_EXP >= 3
-        if (ch == 0) {
-#endif
-        __syncthreads();                                 // the previous chunk has been read
-        commit(ch);
-        __syncthreads();
-        if (ch + 1 < nchunks) prefetch(ch + 1);
-#if SPLIT_EXP == 1 || SPLIT_EXP >= 3
-        }
-#endif
-
-        if (NT > 0 && SPLIT_EXP != 2) {
+        const bool more = ch + 1 < nchunks;
+        int pc = more ? 0 : kPieces;                     // the next piece of chunk ch + 1 to commit
+        if constexpr (NT > 0) {
             // The flat sequence of (tap, pixel tile) steps, six matrix instructions each.  A step's
-            // three B operands are read two steps ahead, a tap's two filter words two taps ahead, and
-            // a tap's A operands are made among the matrix instructions of the tap before it.
-            const uint32_t *wsrc = fw + wf * 64 + col;
+            // three B operands are read two steps ahead, a tap's two filter words two taps ahead, a
+            // tap's A operands are made among the matrix instructions of the tap before it, and
+            // each of the chunk's first steps carries one piece of the next chunk's commit.
+            const unsigned char *tile_r = lds_raw + (ch & 1) * tile_bytes;
+            const uint32_t *wsrc = reinterpret_cast<const uint32_t *>(words_lds + ((ch >> 1) & 1) * words_bytes) + wf * 64 + col;
+            const int bit0 = (ch & 1) * 16;              // the chunk's sixteen signs within the word
+            // sixteen signs, inverted (1 = -1.0), in both halves of a dword
+            auto signs2 = [&](uint32_t w) -> uint32_t { return both_halves(~(w >> bit0)); };
+            auto read3 = [&](uint4 (&b)[3], int byte_off) __attribute__((always_inline)) {
+                const uint4 *src = reinterpret_cast<const uint4 *>(tile_r + byte_off);
+                b[0] = src[0];
+                b[1] = src[2];
+                b[2] = src[4];
+            };
             // (off, kx): byte offset and window column of tap `tap` -> of the tap after it: one position
             // to the right, or to the start of the next window row; the last tap stays (reads beyond
-            // it are not used)
-            // (selects, no branches: the loop body stays one block for the instruction order below)
+            // it are not used).  (Selects, no branches.)
             const int row_step = (p.pitch - p.kw + 1) * kPosBytes;
             auto tap_after = [&](int &off, int &kx, int tap) {
-                const bool more = tap + 1 < taps, wrap = kx + 1 == p.kw;
-                off += more ? (wrap ? row_step : kPosBytes) : 0;
-                kx = more ? (wrap ? 0 : kx + 1) : kx;
+                const bool further = tap + 1 < taps, wrap = kx + 1 == p.kw;
+                off += further ? (wrap ? row_step : kPosBytes) : 0;
+                kx = further ? (wrap ? 0 : kx + 1) : kx;
             };
             int off0 = 0;
             int off1 = 0, kx1 = 0;
@@ -263,49 +298,72 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
             tap_after(off2, kx2, 1);
             const int t1 = min(1, taps - 1);
             uint32_t wn0 = wsrc[t1 * kFiltersPerWg], wn1 = wsrc[t1 * kFiltersPerWg + 32];
-            bf16x8 a0 = signs_to_bf16(wsrc[0], shifts, sign_mask, ones), a1 = signs_to_bf16(wsrc[32], shifts, sign_mask, ones);
+            bf16x8 a0 = signs_to_bf16(signs2(wsrc[0]), shifts, sign_mask, ones), a1 = signs_to_bf16(signs2(wsrc[32]), shifts, sign_mask, ones);
+            bf16x8 a0n = a0, a1n = a1;
             uint4 bc[3], bn[3], bf[3];
             read3(bc, base[0] + off0);
             read3(bn, NT > 1 ? base[NT > 1 ? 1 : 0] + off0 : base[0] + off1);   // (step 1: the second tile, or the second tap)
-            for (int tap = 0; tap < taps; ++tap) {
+            // one step: tile j of the current tap, with piece S of the commit (-1: none)
+            auto step = [&](auto piece_c, int j) __attribute__((always_inline)) {
+                constexpr int S = decltype(piece_c)::value;
+                const int j2 = (j + 2) % NT, ahead = (j + 2) / NT;          // (constants once unrolled)
+                read3(bf, base[j2] + (ahead == 0 ? off0 : ahead == 1 ? off1 : off2));
+                if (j == 0) {
+                    a0n = signs_to_bf16(signs2(wn0), shifts, sign_mask, ones);
+                    a1n = signs_to_bf16(signs2(wn1), shifts, sign_mask, ones);
+                }
+                if constexpr (S >= 0) commit_piece(piece_c, ch + 1);
+#pragma unroll
+                for (int t = 0; t < 3; ++t) {
+                    const bf16x8 b = __builtin_bit_cast(bf16x8, bc[t]);
+                    acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc[0][j], 0, 0, 0);
+                    acc[1][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc[1][j], 0, 0, 0);
+                }
+                // the order inside the step: the three reads, then the matrix instructions with the
+                // step's vector instructions between them
+                __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+#pragma unroll
+                for (int m = 0; m < 6; ++m) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    if (j == 0 || S >= 0) __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int t = 0; t < 3; ++t) { bc[t] = bn[t]; bn[t] = bf[t]; }
+            };
+            // one tap: its NT steps, the first of them with piece FIRST of the commit (-1: no pieces)
+            auto tap_body = [&](auto first_c, int tap) __attribute__((always_inline)) {
+                constexpr int FIRST = decltype(first_c)::value;
                 const int t2 = min(tap + 2, taps - 1);
                 const uint32_t wf0 = wsrc[t2 * kFiltersPerWg], wf1 = wsrc[t2 * kFiltersPerWg + 32];
-                bf16x8 a0n = a0, a1n = a1;
-#pragma unroll
-                for (int j = 0; j < NT; ++j) {
-                    const int j2 = (j + 2) % NT, ahead = (j + 2) / NT;      // (constants once unrolled)
-#if SPLIT_EXP == 3 || SPLIT_EXP == 5
-                    if (tap == 0 && ch == 0)
-#endif
-                    read3(bf, base[j2] + (ahead == 0 ? off0 : ahead == 1 ? off1 : off2));
-                    if (j == 0 && SPLIT_EXP < 4) {
-                        a0n = signs_to_bf16(wn0, shifts, sign_mask, ones);
-                        a1n = signs_to_bf16(wn1, shifts, sign_mask, ones);
-                    }
-#pragma unroll
-                    for (int t = 0; t < 3; ++t) {
-                        const bf16x8 b = __builtin_bit_cast(bf16x8, bc[t]);
-                        acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc[0][j], 0, 0, 0);
-                        acc[1][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc[1][j], 0, 0, 0);
-                    }
-                    // the order inside the step: the three reads, then the matrix instructions with the
-                    // vector instructions of the A operands between them
-                    __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
-#pragma unroll
-                    for (int m = 0; m < 6; ++m) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                        if (j == 0) __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int t = 0; t < 3; ++t) { bc[t] = bn[t]; bn[t] = bf[t]; }
-                }
+                step(std::integral_constant<int, (FIRST >= 0 && FIRST < kPieces) ? FIRST : -1>{}, 0);
+                if constexpr (NT > 1) step(std::integral_constant<int, (FIRST >= 0 && FIRST + 1 < kPieces) ? FIRST + 1 : -1>{}, 1);
+                if constexpr (NT > 2) step(std::integral_constant<int, (FIRST >= 0 && FIRST + 2 < kPieces) ? FIRST + 2 : -1>{}, 2);
+                static_assert(NT <= 3, "one line per step");
                 a0 = a0n; a1 = a1n;
                 wn0 = wf0; wn1 = wf1;
                 off0 = off1; off1 = off2;
                 tap_after(off2, kx2, tap + 2);
+            };
+            // the chunk's first taps carry the pieces (their code is laid out once per tap), the
+            // other taps run in a loop
+            int tap = 0;
+            if (more) {
+                if (tap < taps) { tap_body(std::integral_constant<int, 0>{}, tap); ++tap; }
+                if constexpr (1 * NT < kPieces) if (tap < taps) { tap_body(std::integral_constant<int, 1 * NT>{}, tap); ++tap; }
+                if constexpr (2 * NT < kPieces) if (tap < taps) { tap_body(std::integral_constant<int, 2 * NT>{}, tap); ++tap; }
+                if constexpr (3 * NT < kPieces) if (tap < taps) { tap_body(std::integral_constant<int, 3 * NT>{}, tap); ++tap; }
+                if constexpr (4 * NT < kPieces) if (tap < taps) { tap_body(std::integral_constant<int, 4 * NT>{}, tap); ++tap; }
+                if constexpr (5 * NT < kPieces) if (tap < taps) { tap_body(std::integral_constant<int, 5 * NT>{}, tap); ++tap; }
+                if constexpr (6 * NT < kPieces) if (tap < taps) { tap_body(std::integral_constant<int, 6 * NT>{}, tap); ++tap; }
+                static_assert(kPieces <= 7, "one line per tap that carries pieces");
+                pc = min(tap * NT, kPieces);
             }
+            for (; tap < taps; ++tap) tap_body(std::integral_constant<int, -1>{}, tap);
         }
+        // what the chunk's steps did not carry (few steps, or a wave without tiles)
+        if (pc < kPieces) commit_rest(pc, ch + 1);
+        __syncthreads();                                 // chunk ch has been read, chunk ch + 1 is written
     }
 
     // accumulator register r of a lane: filter row 8*(r/4) + 4*half + r%4 of the filter tile,
@@ -370,7 +428,7 @@ SplitPlan make_split_plan(const Geom &g)
 {
     SplitPlan pl{};
     const long long OHW = (long long)g.OH * g.OW;
-    if (g.kh * g.kw > 64 || OHW > (1 << 24) || (long long)g.C * g.H * g.W >= (1LL << 30)) return pl;
+    if (g.kh * g.kw > 4 * kPreWords || OHW > (1 << 24) || (long long)g.C * g.H * g.W >= (1LL << 30)) return pl;
     if ((long long)g.F * g.kh * g.kw * g.Cw >= (1LL << 29)) return pl;     // (32-bit byte offsets into Wpk)
     pl.pitch = g.W + 2 * g.pw;
     // Pixel tiles per workgroup: as few workgroups per image as the tile limit, the prefetch
@@ -384,7 +442,7 @@ SplitPlan make_split_plan(const Geom &g)
         const int orows = (int)std::min<long long>(g.OH, (32LL * tiles + g.OW - 2) / g.OW + 1);
         const int rows = (orows - 1) * g.sh + g.kh;
         const long long npos = (long long)rows * pl.pitch;
-        const size_t lds = (size_t)npos * kPosBytes + (size_t)g.kh * g.kw * kFiltersPerWg * 4;
+        const size_t lds = 2 * ((size_t)npos * kPosBytes + kDumpBytes + (size_t)g.kh * g.kw * kFiltersPerWg * 4);
         if (npos <= (long long)kGran * 128 && lds <= kLdsBudget) {
             pl.ok = true; pl.tiles = tiles; pl.rows_max = rows; pl.lds = lds;
             return pl;
@@ -413,6 +471,19 @@ hipError_t launch_bwn_split(const float *I, const uint32_t *Wpk, const float *al
     p.fgroups = ceil_div(g.F, kFiltersPerWg);
     const long long blocks = (long long)g.N * p.groups * p.fgroups;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (pl.lds > 64 * 1024) {
+        // raise the kernel's dynamic-LDS limit once per device
+        static std::atomic<unsigned long long> raised{0};
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return hipGetLastError();
+        const unsigned long long bit = 1ull << (dev & 63);
+        if (!(raised.load() & bit)) {
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&bwn_split_kernel),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget);
+            if (e != hipSuccess) return e;
+            raised.fetch_or(bit);
+        }
+    }
     bwn_split_kernel<<<dim3((unsigned)blocks), dim3(kThreads), pl.lds, st>>>(p);
     return hipGetLastError();
 }
