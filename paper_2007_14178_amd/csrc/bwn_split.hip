@@ -77,15 +77,15 @@ typedef unsigned short ushortx2 __attribute__((ext_vector_type(2)));
 // (15 - 8*half - 2k in the low half, one less in the high half); `sign_mask` is 0x80008000 in a
 // scalar and `ones` 0x3F803F80 in a vector register (an instruction takes one literal or one scalar
 // register), so that the merge is one v_and_or_b32.
+__device__ inline uint32_t sign_dword(uint32_t w2, uint32_t sh_k, uint32_t sign_mask, uint32_t ones)
+{
+    const ushortx2 y = __builtin_bit_cast(ushortx2, w2) << __builtin_bit_cast(ushortx2, sh_k);
+    return (__builtin_bit_cast(uint32_t, y) & sign_mask) | ones;
+}
 __device__ inline bf16x8 signs_to_bf16(uint32_t w2, const uint32_t (&sh)[4], uint32_t sign_mask, uint32_t ones)
 {
-    uint32_t d[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const ushortx2 y = __builtin_bit_cast(ushortx2, w2) << __builtin_bit_cast(ushortx2, sh[k]);
-        d[k] = (__builtin_bit_cast(uint32_t, y) & sign_mask) | ones;
-    }
-    return __builtin_bit_cast(bf16x8, make_uint4(d[0], d[1], d[2], d[3]));
+    return __builtin_bit_cast(bf16x8, make_uint4(sign_dword(w2, sh[0], sign_mask, ones), sign_dword(w2, sh[1], sign_mask, ones),
+                                                  sign_dword(w2, sh[2], sign_mask, ones), sign_dword(w2, sh[3], sign_mask, ones)));
 }
 
 // The work of one wave with NT pixel tiles (0: it only takes part in the staging).
@@ -214,24 +214,26 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
     // fetched a chunk ago, fetches the next ones and issues the loads of chunk ch + 1 into the
     // registers just freed.
     constexpr int kPieces = 2 * kGran + 1;
-    auto commit_piece = [&](auto piece_c, int ch) __attribute__((always_inline)) {
-        constexpr int S = decltype(piece_c)::value;
+    uint32_t th[4], tm[4], tl3[4];     // the three terms of a piece's four values, between its units
+    auto commit_unit = [&](auto piece_c, auto unit_c, int ch) __attribute__((always_inline)) {
+        constexpr int S = decltype(piece_c)::value, U = decltype(unit_c)::value;
         unsigned char *tile_w = lds_raw + (ch & 1) * tile_bytes;
         if constexpr (S < 2 * kGran) {
             constexpr int q = S >> 1, hf = S & 1;
             const int c0 = ch * kChan + 8 * oct + 4 * hf;
             // (no branch, uniform or not: the piece has to stay in the block of the step's matrix
-            //  instructions; a position past the last one goes to the dump slot)
-            const bool ok = (okbits >> q) & 1u;
-            uint32_t h[4], m[4], l[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k)
-                split3((ok && c0 + k < p.C) ? nxt[q][4 * hf + k] : 0.f, h[k], m[k], l[k]);
-            uint2 *dst = reinterpret_cast<uint2 *>(tile_w + wr_off[q] + hf * 8);
-            dst[0] = make_uint2(pair16(h[0], h[1]), pair16(h[2], h[3]));
-            dst[4] = make_uint2(pair16(m[0], m[1]), pair16(m[2], m[3]));
-            dst[8] = make_uint2(pair16(l[0], l[1]), pair16(l[2], l[3]));
-        } else {
+            //  instructions; a position past the last one goes to the dump slot).  Units 0-3 split one
+            // value each, unit 4 packs and writes: the caller lays one unit behind each matrix instruction.
+            if constexpr (U < 4) {
+                const bool ok = (okbits >> q) & 1u;
+                split3((ok && c0 + U < p.C) ? nxt[q][4 * hf + U] : 0.f, th[U], tm[U], tl3[U]);
+            } else if constexpr (U == 4) {
+                uint2 *dst = reinterpret_cast<uint2 *>(tile_w + wr_off[q] + hf * 8);
+                dst[0] = make_uint2(pair16(th[0], th[1]), pair16(th[2], th[3]));
+                dst[4] = make_uint2(pair16(tm[0], tm[1]), pair16(tm[2], tm[3]));
+                dst[8] = make_uint2(pair16(tl3[0], tl3[1]), pair16(tl3[2], tl3[3]));
+            }
+        } else if constexpr (U == 0) {
             // while chunk ch - 1 runs: the part of word (ch - 1) / 2 + 1 fetched a chunk ago is written,
             // the next part is fetched
             const int cw_next = ((ch - 1) >> 1) + 1, h = (ch - 1) & 1;
@@ -240,6 +242,13 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
             else words_load(cw_next + 1, 0);
             if (ch + 1 < nchunks) prefetch(ch + 1);
         }
+    };
+    auto commit_piece = [&](auto piece_c, int ch) __attribute__((always_inline)) {
+        commit_unit(piece_c, std::integral_constant<int, 0>{}, ch);
+        commit_unit(piece_c, std::integral_constant<int, 1>{}, ch);
+        commit_unit(piece_c, std::integral_constant<int, 2>{}, ch);
+        commit_unit(piece_c, std::integral_constant<int, 3>{}, ch);
+        commit_unit(piece_c, std::integral_constant<int, 4>{}, ch);
     };
     // pieces `from` .. kPieces - 1 of chunk ch, one after the other
     auto commit_rest = [&](int from, int ch, bool last_too = true) __attribute__((always_inline)) {
@@ -299,35 +308,39 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
             const int t1 = min(1, taps - 1);
             uint32_t wn0 = wsrc[t1 * kFiltersPerWg], wn1 = wsrc[t1 * kFiltersPerWg + 32];
             bf16x8 a0 = signs_to_bf16(signs2(wsrc[0]), shifts, sign_mask, ones), a1 = signs_to_bf16(signs2(wsrc[32]), shifts, sign_mask, ones);
-            bf16x8 a0n = a0, a1n = a1;
             uint4 bc[3], bn[3], bf[3];
             read3(bc, base[0] + off0);
             read3(bn, NT > 1 ? base[NT > 1 ? 1 : 0] + off0 : base[0] + off1);   // (step 1: the second tile, or the second tap)
             // one step: tile j of the current tap, with piece S of the commit (-1: none)
+            // Behind each of its six matrix instructions a step lays one unit of the other work
+            // (a fence after each keeps the order): a tap's first step the A operands of the next
+            // tap, a step with a piece the piece's units.
+            uint32_t an[2][4];
+            uint32_t sg0 = 0, sg1 = 0;
             auto step = [&](auto piece_c, int j) __attribute__((always_inline)) {
                 constexpr int S = decltype(piece_c)::value;
                 const int j2 = (j + 2) % NT, ahead = (j + 2) / NT;          // (constants once unrolled)
                 read3(bf, base[j2] + (ahead == 0 ? off0 : ahead == 1 ? off1 : off2));
-                if (j == 0) {
-                    a0n = signs_to_bf16(signs2(wn0), shifts, sign_mask, ones);
-                    a1n = signs_to_bf16(signs2(wn1), shifts, sign_mask, ones);
-                }
-                if constexpr (S >= 0) commit_piece(piece_c, ch + 1);
-#pragma unroll
-                for (int t = 0; t < 3; ++t) {
-                    const bf16x8 b = __builtin_bit_cast(bf16x8, bc[t]);
-                    acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc[0][j], 0, 0, 0);
-                    acc[1][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc[1][j], 0, 0, 0);
-                }
-                // the order inside the step: the three reads, then the matrix instructions with the
-                // step's vector instructions between them
-                __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
-#pragma unroll
-                for (int m = 0; m < 6; ++m) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    if (j == 0 || S >= 0) __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
-                }
                 __builtin_amdgcn_sched_barrier(0);
+                auto unit = [&](auto m_c) __attribute__((always_inline)) {
+                    constexpr int M = decltype(m_c)::value;
+                    const bf16x8 b = __builtin_bit_cast(bf16x8, bc[M >> 1]);
+                    acc[M & 1][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16((M & 1) ? a1 : a0, b, acc[M & 1][j], 0, 0, 0);
+                    if (j == 0) {
+                        if constexpr (M == 0) { sg0 = signs2(wn0); an[0][0] = sign_dword(sg0, shifts[0], sign_mask, ones); an[0][1] = sign_dword(sg0, shifts[1], sign_mask, ones); }
+                        if constexpr (M == 1) { an[0][2] = sign_dword(sg0, shifts[2], sign_mask, ones); an[0][3] = sign_dword(sg0, shifts[3], sign_mask, ones); }
+                        if constexpr (M == 2) { sg1 = signs2(wn1); an[1][0] = sign_dword(sg1, shifts[0], sign_mask, ones); an[1][1] = sign_dword(sg1, shifts[1], sign_mask, ones); }
+                        if constexpr (M == 3) { an[1][2] = sign_dword(sg1, shifts[2], sign_mask, ones); an[1][3] = sign_dword(sg1, shifts[3], sign_mask, ones); }
+                    }
+                    if constexpr (S >= 0 && M < 5) commit_unit(piece_c, std::integral_constant<int, M>{}, ch + 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                };
+                unit(std::integral_constant<int, 0>{});
+                unit(std::integral_constant<int, 1>{});
+                unit(std::integral_constant<int, 2>{});
+                unit(std::integral_constant<int, 3>{});
+                unit(std::integral_constant<int, 4>{});
+                unit(std::integral_constant<int, 5>{});
 #pragma unroll
                 for (int t = 0; t < 3; ++t) { bc[t] = bn[t]; bn[t] = bf[t]; }
             };
@@ -340,7 +353,8 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
                 if constexpr (NT > 1) step(std::integral_constant<int, (FIRST >= 0 && FIRST + 1 < kPieces) ? FIRST + 1 : -1>{}, 1);
                 if constexpr (NT > 2) step(std::integral_constant<int, (FIRST >= 0 && FIRST + 2 < kPieces) ? FIRST + 2 : -1>{}, 2);
                 static_assert(NT <= 3, "one line per step");
-                a0 = a0n; a1 = a1n;
+                a0 = __builtin_bit_cast(bf16x8, make_uint4(an[0][0], an[0][1], an[0][2], an[0][3]));
+                a1 = __builtin_bit_cast(bf16x8, make_uint4(an[1][0], an[1][1], an[1][2], an[1][3]));
                 wn0 = wf0; wn1 = wf1;
                 off0 = off1; off1 = off2;
                 tap_after(off2, kx2, tap + 2);
