@@ -741,6 +741,13 @@ def run_peaks(args, xb, torch):
         t = timed(lambda: flops.__setitem__(0, xb.xnor_probe_mfma_fp4(wgs, 4000, sink_f)), 20)
         out[f"mfma_fp4_tflops_{wgs}wg"] = flops[0] / t / 1e12
     out["mfma_fp4_published_tflops"] = PEAK_FP4_MFMA_TFLOPS
+    # the bf16 instruction of the Binary-Weight-Network kernel: +-1.0 against +-1.0, and +-1.0 against
+    # values with random significands (two workgroups per compute unit, as the kernel runs)
+    for name, rnd in (("pm1", False), ("random", True)):
+        flops = [0.0]
+        t = timed(lambda: flops.__setitem__(0, xb.xnor_probe_mfma_bf16(512, 8000, rnd, sink_f)), 20)
+        out[f"mfma_bf16_tflops_b_{name}"] = flops[0] / t / 1e12
+    out["mfma_bf16_published_tflops"] = PEAK_BF16_MFMA_TFLOPS
     macs = [0.0]
     t = timed(lambda: macs.__setitem__(0, xb.xnor_probe_xor_popcount(256 * 8, 20000, sink_i)), 10)
     out["xor_popcount_binary_tops"] = 2.0 * macs[0] / t / 1e12

@@ -279,8 +279,8 @@ int xnor_forward_image(const float *I, const uint32_t *Wpk, const float *alpha, 
  * output pixels do not fit in 128 KB of LDS, or kh*kw > 64) or XNOR_ALGO_MFMA_SPLIT (every input
  * value split into three bf16 terms whose sum is the value, bf16 matrix instruction with +-1
  * weights, fp32 accumulation: the same products, three instructions at 16 times the rate instead of
- * eight; an input that is not finite gives NaN, not an infinity, and terms below 2^-133 are
- * dropped; XNOR_E_UNSUPPORTED where 16 channels of the rows under the workgroup's pixels, as
+ * eight; an input that is not finite gives NaN, not an infinity, and a term below the normal range
+ * is flushed, which adds at most alpha * 2^-125 per input value under the window to the error; XNOR_E_UNSUPPORTED where 16 channels of the rows under the workgroup's pixels, as
  * 6 bytes per value, do not fit in 64 KB of LDS, or kh*kw > 64); other values XNOR_E_UNSUPPORTED.
  */
 int xnor_bwn_conv2d_fwd(const float *I, const uint32_t *Wpk, const float *alpha, const xnor_shape *s,
@@ -343,6 +343,10 @@ int xnor_conv2d_pick_algo(const xnor_shape *s, size_t workspace_bytes);
  *   xnor_probe_mfma_fp4      `workgroups` x 4 waves each run `iters` x 8 register-only
  *                            v_mfma_f32_32x32x64_f8f6f4 (both operands FP4 +-1, the convolution's
  *                            instruction); *flops receives the flops issued (2 per multiply-add)
+ *   xnor_probe_mfma_bf16     the same with `iters` x 6 v_mfma_f32_32x32x16_bf16 (the Binary-Weight-
+ *                            Network kernel's instruction): A operands +-1.0, B operands +-1.0
+ *                            (random_b = 0) or bf16 values with random significands (random_b != 0;
+ *                            the rate the chip holds depends on the operand values)
  *   xnor_probe_xor_popcount  `workgroups` x 256 lanes each run `iters` x 8 register-only
  *                            v_xor_b32 + v_bcnt_u32_b32 pairs; *binary_macs receives 32 per lane
  *                            and pair
@@ -353,6 +357,7 @@ int xnor_conv2d_pick_algo(const xnor_shape *s, size_t workspace_bytes);
  * 2^24 iterations, or a byte count that is 0 or no multiple of 16.
  */
 int xnor_probe_mfma_fp4(int workgroups, int iters, float *sink, double *flops, void *stream);
+int xnor_probe_mfma_bf16(int workgroups, int iters, int random_b, float *sink, double *flops, void *stream);
 int xnor_probe_xor_popcount(int workgroups, int iters, uint32_t *sink, double *binary_macs, void *stream);
 int xnor_probe_copy(const void *src, void *dst, size_t bytes, void *stream);
 

@@ -91,6 +91,7 @@ def _load() -> ctypes.CDLL:
     L.xnor_filter_expand.argtypes = [vp, sp, vp, sz, vp]
     dp = ctypes.POINTER(ctypes.c_double)
     L.xnor_probe_mfma_fp4.argtypes = [ci, ci, vp, dp, vp]
+    L.xnor_probe_mfma_bf16.argtypes = [ci, ci, ci, vp, dp, vp]
     L.xnor_probe_xor_popcount.argtypes = [ci, ci, vp, dp, vp]
     L.xnor_probe_copy.argtypes = [vp, vp, sz, vp]
     L.xnor_conv2d_fwd_expanded.argtypes = [vp, vp, sz, vp, vp, sp, vp, vp, vp]
@@ -117,7 +118,7 @@ def _load() -> ctypes.CDLL:
                  "xnor_bwn_conv2d_fwd", "xnor_bwn_conv2d_fwd_algo",
                  "xnor_conv2d_fwd_expanded_from_A", "xnor_conv2d_fwd_chain_from_A",
                  "xnor_conv2d_fwd_chain_expanded_from_A", "xnor_prepare", "xnor_conv2d_fwd_static",
-                 "xnor_probe_mfma_fp4", "xnor_probe_xor_popcount", "xnor_probe_copy",
+                 "xnor_probe_mfma_fp4", "xnor_probe_mfma_bf16", "xnor_probe_xor_popcount", "xnor_probe_copy",
                  "xnor_conv2d_fp32_fwd", "xnor_conv2d_fp32_fwd_algo"):
         getattr(L, name).restype = ci
     return L
@@ -328,6 +329,14 @@ def xnor_probe_mfma_fp4(workgroups: int, iters: int, sink: torch.Tensor) -> floa
     n = ctypes.c_double(0.0)
     _ok(lib.xnor_probe_mfma_fp4(workgroups, iters, _dev(sink, torch.float32, name="sink"), ctypes.byref(n), _stream()),
         "xnor_probe_mfma_fp4")
+    return n.value
+
+
+def xnor_probe_mfma_bf16(workgroups: int, iters: int, random_b: bool, sink: torch.Tensor) -> float:
+    """Enqueue the register-only bf16 matrix-instruction loop; returns the flops it issues."""
+    n = ctypes.c_double()
+    _ok(lib.xnor_probe_mfma_bf16(workgroups, iters, int(bool(random_b)), _dev(sink, torch.float32, name="sink"),
+                                 ctypes.byref(n), _stream()), "xnor_probe_mfma_bf16")
     return n.value
 
 

@@ -16,7 +16,8 @@
 //   pixel, eight channels), used for both filter tiles; the A operand (lane = filter, eight
 //   channels) is made in registers from eight bits of the filter's packed word.
 //   Inputs that are not finite give NaN where the fp32 sum would give an infinity (inf - inf in the
-//   split); what a term leaves below the bf16 subnormal range (2^-133) is dropped.
+//   split); the matrix instruction flushes a term below the normal range (2^-126), so an input value
+//   contributes an error of up to 2^-125 (two of its terms) on top of the fp32 summation's.
 #include <algorithm>
 #include <atomic>
 #include <type_traits>

@@ -4,6 +4,10 @@
 //   * probe_mfma_fp4_kernel      register-only loop of the FP4 matrix instruction the convolution
 //                                uses (v_mfma_f32_32x32x64_f8f6f4, both operands FP4), eight
 //                                independent accumulators per wave, no memory traffic
+//   * probe_mfma_bf16_kernel     register-only loop of v_mfma_f32_32x32x16_bf16 (what the
+//                                Binary-Weight-Network kernel uses), +-1.0 as the A operand and
+//                                either +-1.0 or values with random significands as the B operand:
+//                                the rate the chip holds depends on how much the operands toggle
 //   * probe_xor_popcount_kernel  register-only loop of v_xor_b32 + v_bcnt_u32_b32 pairs (32 binary
 //                                multiply-accumulates per lane and pair), eight independent chains
 //   * probe_copy_kernel          plain 16-byte-per-lane device copy
@@ -52,6 +56,49 @@ __global__ __launch_bounds__(256) void probe_mfma_fp4_kernel(int iters, float *s
     if (s == 0.5f) sink[0] = s;
 }
 
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+constexpr int kBf16PerIter = 6;      // two A operands x three B operands
+
+// A: +-1.0 with lane-dependent signs.  B: the same (random_b = 0), or bf16 values in +-[0.5, 4) with
+// random significand bits.
+__global__ __launch_bounds__(256) void probe_mfma_bf16_kernel(int iters, int random_b, float *sink)
+{
+    v16f acc[kBf16PerIter];
+    for (int j = 0; j < kBf16PerIter; ++j)
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+    unsigned x = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;
+    uint4 A[2], B[3];
+    for (int i = 0; i < 2; ++i) {
+        uint32_t w[4];
+        for (int q = 0; q < 4; ++q) { x = x * 1664525u + 1013904223u; w[q] = 0x3f803f80u ^ (x & 0x80008000u); }
+        A[i] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    for (int i = 0; i < 3; ++i) {
+        uint32_t w[4];
+        for (int q = 0; q < 4; ++q) {
+            uint32_t h[2];
+            for (int e = 0; e < 2; ++e) {
+                x = x * 1664525u + 1013904223u;
+                h[e] = random_b ? (((x >> 3) & 0x807fu) | (0x3f00u + ((x >> 20) & 0x180u))) : (0x3f80u | ((x >> 5) & 0x8000u));
+            }
+            w[q] = h[0] | (h[1] << 16);
+        }
+        B[i] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int t = 0; t < 3; ++t)
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                acc[t * 2 + i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, A[i]), __builtin_bit_cast(v8bf, B[t]),
+                                                                         acc[t * 2 + i], 0, 0, 0);
+    }
+    float s = 0.f;
+    for (int j = 0; j < kBf16PerIter; ++j)
+        for (int r = 0; r < 16; ++r) s += acc[j][r];
+    if (s == 0.4375f) sink[0] = s;   // (practically never; the compiler cannot know)
+}
+
 __global__ __launch_bounds__(256) void probe_xor_popcount_kernel(int iters, uint32_t *sink)
 {
     uint32_t acc[kPairsPerIter], a[kPairsPerIter], w[kPairsPerIter];
@@ -95,6 +142,16 @@ int xnor_probe_mfma_fp4(int workgroups, int iters, float *sink, double *flops, v
     probe_mfma_fp4_kernel<<<dim3(workgroups), dim3(256), 0, (hipStream_t)stream>>>(iters, sink);
     // 4 waves per workgroup, 32 x 32 x 64 multiply-accumulates per instruction, 2 flops each
     *flops = (double)workgroups * 4.0 * iters * kMfmaPerIter * (32.0 * 32.0 * 64.0) * 2.0;
+    return status(hipGetLastError());
+}
+
+int xnor_probe_mfma_bf16(int workgroups, int iters, int random_b, float *sink, double *flops, void *stream)
+{
+    if (!sink || !flops) return XNOR_E_NULL;
+    if (workgroups <= 0 || iters <= 0 || workgroups > (1 << 20) || iters > (1 << 24)) return XNOR_E_SHAPE;
+    probe_mfma_bf16_kernel<<<dim3(workgroups), dim3(256), 0, (hipStream_t)stream>>>(iters, random_b != 0, sink);
+    // 4 waves per workgroup, 32 x 32 x 16 multiply-accumulates per instruction, 2 flops each
+    *flops = (double)workgroups * 4.0 * iters * kBf16PerIter * (32.0 * 32.0 * 16.0) * 2.0;
     return status(hipGetLastError());
 }
 

@@ -56,6 +56,9 @@ def check(xb, full, I, Wt, algo, key):
     got = out.cpu().numpy().astype(np.float64)
     assert got.shape == O_ref.shape
     bar = RTOL * a[None, :, None, None] * S[:, None]
+    if algo in ("split", "auto"):
+        # the three-term bf16 kernel flushes terms below the normal range: at most 2^-125 per input value
+        bar = bar + a[None, :, None, None] * (full[1] * full[5] * full[6]) * 2.0 ** -125
     err = np.abs(got - O_ref)
     assert (err <= bar).all(), f"{(err > bar).sum()} of {err.size} outside the bar; worst err/bar {np.nanmax(err / np.maximum(bar, 1e-300)):.3g}"
     # typical accuracy is far inside the bar: a coarser arithmetic (bf16, fp16) would not pass this
@@ -107,6 +110,29 @@ def test_bwn_benchmark_layers_two_images(xb, name):
     # the kernels differ only in summation order
     assert torch.allclose(out_m, out_d, rtol=0, atol=float(2e-5 * out_d.abs().max()))
     assert torch.allclose(out_s, out_d, rtol=0, atol=float(2e-5 * out_d.abs().max()))
+
+
+def test_bwn_tiny_inputs_stay_within_the_flush_floor(xb):
+    """Inputs at the bottom of the fp32 range: the fp32 kernels carry them exactly (sums of a few
+    denormals are exact), the three-term bf16 kernel may flush each term below 2^-126."""
+    shape = (2, 20, 9, 9, 12, 3, 3, 1, 1, 1, 1)
+    print(f"case bwn-tiny shape={shape}", flush=True)
+    rng = np.random.default_rng(5)
+    _, I, Wt = random_layer(rng, "t", *shape)
+    tiny = np.float32(1e-41) * rng.integers(-200, 200, size=I.shape).astype(np.float32)
+    small = (I * np.float32(1e-35)).astype(np.float32)
+    I = np.where(rng.random(I.shape) < 0.5, tiny, small).astype(np.float32)
+    s = xb.Shape(*shape)
+    O_ref, S = oracle.bwn(I, Wt, oracle.Shape(*shape), want_scale=True)
+    a = oracle.alpha(Wt).astype(np.float64)
+    Wpk, alpha, _ = xb.xnor_filter_prepare(dev(Wt))
+    nred = shape[1] * shape[5] * shape[6]
+    for algo, floor in ((xb.ALGO_DIRECT, 0.0), (xb.ALGO_MFMA, 0.0), (xb.ALGO_MFMA_SPLIT, 2.0 ** -125), (xb.ALGO_AUTO, 2.0 ** -125)):
+        out = xb.xnor_bwn_conv2d_fwd(dev(I), Wpk, alpha, s, algo=algo)
+        torch.cuda.synchronize()
+        err = np.abs(out.cpu().numpy().astype(np.float64) - O_ref.astype(np.float64))
+        bar = RTOL * a[None, :, None, None] * S[:, None] + a[None, :, None, None] * nred * floor + 2.0 ** -149
+        assert (err <= bar).all(), f"algo {algo}: {(err > bar).sum()} of {err.size} outside the bar"
 
 
 def test_bwn_on_binary_input_equals_the_xnor_path(xb):
