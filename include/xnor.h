@@ -113,7 +113,7 @@ int xnor_alpha(const float *Wt, int F, int C, int kh, int kw, float *alpha, void
  *   Ipk     out  uint32 [N][H][W][ceil(C/32)]
  *   A_work  out  fp32 [N][H][W]   caller-owned workspace; holds A on return
  *   K       out  fp32 [N][OH][OW], or NULL: then only Ipk and A are produced (for
- *                xnor_conv2d_fwd_expanded_from_A, which forms K itself)
+ *                xnor_conv2d_fwd_expanded given A, which forms K itself)
  */
 int xnor_input_prepare(const float *I, const xnor_shape *s, uint32_t *Ipk, float *A_work, float *K,
                        void *stream);
@@ -180,24 +180,22 @@ int xnor_conv2d_workspace_bytes(const xnor_shape *s, size_t *bytes);
  *                             `workspace` (xnor_conv2d_workspace_bytes bytes, 16-byte aligned);
  *                             the contents stay valid for this shape until overwritten.
  *   xnor_conv2d_fwd_expanded  reads that workspace instead of Wpk; it must have been filled for the
- *                             same shape.  Other arguments as in xnor_conv2d_fwd.
+ *                             same shape.  Exactly one of K and A is given (the other NULL, else
+ *                             XNOR_E_NULL): K [N][OH][OW] as in xnor_conv2d_fwd, or the channel mean
+ *                             A [N][H][W] (Eq. 10, first half), from which each workgroup forms the
+ *                             K of its own output pixels while its first operands are on their way
+ *                             (same sum, order and rounding as xnor_box_filter_K, so the outputs
+ *                             are bit-identical), which saves the box-filter launch between the
+ *                             input pass and the convolution.  Other arguments as in
+ *                             xnor_conv2d_fwd.
  * Both return XNOR_E_UNSUPPORTED where xnor_conv2d_workspace_bytes reports 0 and XNOR_E_WORKSPACE
  * for a workspace that is too small.
  */
 int xnor_filter_expand(const uint32_t *Wpk, const xnor_shape *s, void *workspace,
                        size_t workspace_bytes, void *stream);
 int xnor_conv2d_fwd_expanded(const uint32_t *Ipk, const void *workspace, size_t workspace_bytes,
-                             const float *K, const float *alpha, const xnor_shape *s, float *out,
-                             int32_t *dot, void *stream);
-/*
- * The same convolution taking the channel mean A [N][H][W] (Eq. 10, first half) instead of K: each
- * workgroup forms the K of its own output pixels from A while its first operands are on their way
- * (same sum, order and rounding as xnor_box_filter_K, so the outputs are bit-identical), which
- * saves the box-filter launch between the input pass and the convolution.
- */
-int xnor_conv2d_fwd_expanded_from_A(const uint32_t *Ipk, const void *workspace, size_t workspace_bytes,
-                                    const float *A, const float *alpha, const xnor_shape *s, float *out,
-                                    int32_t *dot, void *stream);
+                             const float *K, const float *A, const float *alpha, const xnor_shape *s,
+                             float *out, int32_t *dot, void *stream);
 
 /*
  * Chained layers (the paper's closing proposal, Sec. V: hand the next kernel the binary outputs
@@ -210,28 +208,27 @@ int xnor_conv2d_fwd_expanded_from_A(const uint32_t *Ipk, const void *workspace, 
  *   A_next  out  fp32   [N][OH][OW]              = (1/F) sum_f |O[n][f][oy][ox]|
  *   workspace    caller-owned, 16-byte aligned, xnor_conv2d_chain_workspace_bytes bytes (filter
  *                expansion plus per-filter-tile partial sums); contents mean nothing afterwards.
- * The next layer continues with xnor_box_filter_K(A_next, its shape, K) and a convolution on Opk.
+ *   K, A         exactly one is given (the other NULL, else XNOR_E_NULL): K [N][OH][OW], or this
+ *                layer's channel mean A [N][H][W] (what the previous chained layer left as its
+ *                A_next), from which K is formed inside the kernel as in xnor_conv2d_fwd_expanded,
+ *                so that a chain of layers needs no xnor_box_filter_K calls in between.
+ *                Bit-identical results.
+ *   Wpk          the packed filters, expanded into the workspace by a launch of this call; or NULL
+ *                for filters that do not change from call to call (every layer of a chained
+ *                network at inference): the caller has run xnor_filter_expand (or xnor_prepare) on
+ *                this same workspace, whose first xnor_conv2d_workspace_bytes bytes therefore hold
+ *                the expanded filters and are only read here; the rest (up to
+ *                xnor_conv2d_chain_workspace_bytes) is the scratch for the per-filter-tile sums.
+ *                Same results bit for bit, one launch less per layer.
+ * The next layer continues with A_next as its A (or with xnor_box_filter_K(A_next, its shape, K))
+ * and a convolution on Opk.
  * Runs on the matrix-core kernel only: XNOR_E_UNSUPPORTED where
  * xnor_conv2d_chain_workspace_bytes reports 0, XNOR_E_WORKSPACE for a workspace that is too small.
  */
 int xnor_conv2d_chain_workspace_bytes(const xnor_shape *s, size_t *bytes);
-int xnor_conv2d_fwd_chain(const uint32_t *Ipk, const uint32_t *Wpk, const float *K, const float *alpha,
-                          const xnor_shape *s, uint32_t *Opk, float *A_next, void *workspace,
-                          size_t workspace_bytes, void *stream);
-/* The same, taking this layer's channel mean A [N][H][W] (what the previous chained layer left as
- * its A_next) instead of K: K is formed inside the kernel as in xnor_conv2d_fwd_expanded_from_A, so
- * a chain of layers needs no xnor_box_filter_K calls in between.  Bit-identical results. */
-int xnor_conv2d_fwd_chain_from_A(const uint32_t *Ipk, const uint32_t *Wpk, const float *A, const float *alpha,
-                                 const xnor_shape *s, uint32_t *Opk, float *A_next, void *workspace,
-                                 size_t workspace_bytes, void *stream);
-/* xnor_conv2d_fwd_chain_from_A for filters that do not change from call to call (every layer of a
- * chained network at inference): the caller has run xnor_filter_expand (or xnor_prepare) on this
- * same workspace, whose first xnor_conv2d_workspace_bytes bytes therefore hold the expanded filters
- * and are only read here; the rest (up to xnor_conv2d_chain_workspace_bytes) is the scratch for the
- * per-filter-tile sums.  Same results bit for bit, one launch less per layer. */
-int xnor_conv2d_fwd_chain_expanded_from_A(const uint32_t *Ipk, const float *A, const float *alpha,
-                                          const xnor_shape *s, uint32_t *Opk, float *A_next, void *workspace,
-                                          size_t workspace_bytes, void *stream);
+int xnor_conv2d_fwd_chain(const uint32_t *Ipk, const uint32_t *Wpk, const float *K, const float *A,
+                          const float *alpha, const xnor_shape *s, uint32_t *Opk, float *A_next,
+                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Second half of Eq. 10 on its own: K = box filter of a given A (taps 1/(kh*kw), zero outside the

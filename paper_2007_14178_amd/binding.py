@@ -94,13 +94,10 @@ def _load() -> ctypes.CDLL:
     L.xnor_probe_mfma_bf16.argtypes = [ci, ci, ci, vp, dp, vp]
     L.xnor_probe_xor_popcount.argtypes = [ci, ci, vp, dp, vp]
     L.xnor_probe_copy.argtypes = [vp, vp, sz, vp]
-    L.xnor_conv2d_fwd_expanded.argtypes = [vp, vp, sz, vp, vp, sp, vp, vp, vp]
-    L.xnor_conv2d_fwd_expanded_from_A.argtypes = [vp, vp, sz, vp, vp, sp, vp, vp, vp]
+    L.xnor_conv2d_fwd_expanded.argtypes = [vp, vp, sz, vp, vp, vp, sp, vp, vp, vp]
     L.xnor_box_filter_K.argtypes = [vp, sp, vp, vp]
     L.xnor_conv2d_chain_workspace_bytes.argtypes = [sp, ctypes.POINTER(sz)]
-    L.xnor_conv2d_fwd_chain.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, vp]
-    L.xnor_conv2d_fwd_chain_from_A.argtypes = [vp, vp, vp, vp, sp, vp, vp, vp, sz, vp]
-    L.xnor_conv2d_fwd_chain_expanded_from_A.argtypes = [vp, vp, vp, sp, vp, vp, vp, sz, vp]
+    L.xnor_conv2d_fwd_chain.argtypes = [vp, vp, vp, vp, vp, sp, vp, vp, vp, sz, vp]
     L.xnor_forward_image_supported.argtypes = [sp]
     L.xnor_forward_image.argtypes = [vp, vp, vp, sp, vp, vp, vp]
     L.xnor_bwn_conv2d_fwd.argtypes = [vp, vp, vp, sp, vp, vp]
@@ -116,8 +113,7 @@ def _load() -> ctypes.CDLL:
                  "xnor_conv2d_chain_workspace_bytes", "xnor_conv2d_fwd_chain",
                  "xnor_forward_image_supported", "xnor_forward_image",
                  "xnor_bwn_conv2d_fwd", "xnor_bwn_conv2d_fwd_algo",
-                 "xnor_conv2d_fwd_expanded_from_A", "xnor_conv2d_fwd_chain_from_A",
-                 "xnor_conv2d_fwd_chain_expanded_from_A", "xnor_prepare", "xnor_conv2d_fwd_static",
+                 "xnor_prepare", "xnor_conv2d_fwd_static",
                  "xnor_probe_mfma_fp4", "xnor_probe_mfma_bf16", "xnor_probe_xor_popcount", "xnor_probe_copy",
                  "xnor_conv2d_fp32_fwd", "xnor_conv2d_fp32_fwd_algo"):
         getattr(L, name).restype = ci
@@ -368,10 +364,11 @@ def xnor_filter_expand(Wpk: torch.Tensor, s: Shape, workspace: torch.Tensor | No
     return workspace
 
 
-def xnor_conv2d_fwd_expanded(Ipk: torch.Tensor, workspace: torch.Tensor, K: torch.Tensor, alpha: torch.Tensor,
+def xnor_conv2d_fwd_expanded(Ipk: torch.Tensor, workspace: torch.Tensor, K: torch.Tensor | None, alpha: torch.Tensor,
                              s: Shape, out: torch.Tensor | None = None, dot: torch.Tensor | None = None,
-                             want_dot: bool = False):
-    """Per-input half: the convolution on a workspace filled by xnor_filter_expand for this shape."""
+                             want_dot: bool = False, A: torch.Tensor | None = None):
+    """Per-input half: the convolution on a workspace filled by xnor_filter_expand for this shape.
+    Exactly one of K [N][OH][OW] and A [N][H][W] (K is then formed inside the kernel) is given."""
     OH, OW = xnor_out_dim(s)
     oshape = (s.N, s.F, OH, OW)
     if out is None:
@@ -380,7 +377,9 @@ def xnor_conv2d_fwd_expanded(Ipk: torch.Tensor, workspace: torch.Tensor, K: torc
         dot = torch.empty(oshape, dtype=torch.int32, device=Ipk.device)
     _ok(lib.xnor_conv2d_fwd_expanded(
         _dev(Ipk, torch.int32, (s.N, s.H, s.W, s.Cw), "Ipk"), _dev(workspace, torch.uint8, name="workspace"),
-        workspace.numel(), _dev(K, torch.float32, (s.N, OH, OW), "K"), _dev(alpha, torch.float32, (s.F,), "alpha"),
+        workspace.numel(), _dev(K, torch.float32, (s.N, OH, OW), "K") if K is not None else None,
+        _dev(A, torch.float32, (s.N, s.H, s.W), "A") if A is not None else None,
+        _dev(alpha, torch.float32, (s.F,), "alpha"),
         ctypes.byref(s.c()), _dev(out, torch.float32, oshape, "out"),
         _dev(dot, torch.int32, oshape, "dot") if dot is not None else None, _stream()), "xnor_conv2d_fwd_expanded")
     return out, dot
@@ -438,24 +437,6 @@ def xnor_conv2d_fp32_fwd(I: torch.Tensor, Wt: torch.Tensor, s: Shape, out: torch
     return out
 
 
-def xnor_conv2d_fwd_expanded_from_A(Ipk: torch.Tensor, workspace: torch.Tensor, A: torch.Tensor, alpha: torch.Tensor,
-                                    s: Shape, out: torch.Tensor | None = None, dot: torch.Tensor | None = None,
-                                    want_dot: bool = False):
-    """xnor_conv2d_fwd_expanded with K formed inside the kernel from the channel mean A [N][H][W]."""
-    OH, OW = xnor_out_dim(s)
-    oshape = (s.N, s.F, OH, OW)
-    if out is None:
-        out = torch.empty(oshape, dtype=torch.float32, device=Ipk.device)
-    if dot is None and want_dot:
-        dot = torch.empty(oshape, dtype=torch.int32, device=Ipk.device)
-    _ok(lib.xnor_conv2d_fwd_expanded_from_A(
-        _dev(Ipk, torch.int32, (s.N, s.H, s.W, s.Cw), "Ipk"), _dev(workspace, torch.uint8, name="workspace"),
-        workspace.numel(), _dev(A, torch.float32, (s.N, s.H, s.W), "A"), _dev(alpha, torch.float32, (s.F,), "alpha"),
-        ctypes.byref(s.c()), _dev(out, torch.float32, oshape, "out"),
-        _dev(dot, torch.int32, oshape, "dot") if dot is not None else None, _stream()), "xnor_conv2d_fwd_expanded_from_A")
-    return out, dot
-
-
 def xnor_box_filter_K(A: torch.Tensor, s: Shape, K: torch.Tensor | None = None) -> torch.Tensor:
     """K [N][OH][OW] from a given A [N][H][W] (second half of Eq. 10)."""
     OH, OW = xnor_out_dim(s)
@@ -472,10 +453,12 @@ def xnor_conv2d_chain_workspace_bytes(s: Shape) -> int:
     return n.value
 
 
-def xnor_conv2d_fwd_chain(Ipk: torch.Tensor, Wpk: torch.Tensor, K: torch.Tensor, alpha: torch.Tensor, s: Shape,
-                          Opk: torch.Tensor | None = None, A_next: torch.Tensor | None = None,
-                          workspace: torch.Tensor | None = None):
-    """Returns (Opk int32-typed words [N][OH][OW][ceil(F/32)], A_next fp32 [N][OH][OW])."""
+def xnor_conv2d_fwd_chain(Ipk: torch.Tensor, Wpk: torch.Tensor | None, K: torch.Tensor | None, alpha: torch.Tensor,
+                          s: Shape, Opk: torch.Tensor | None = None, A_next: torch.Tensor | None = None,
+                          workspace: torch.Tensor | None = None, A: torch.Tensor | None = None):
+    """Returns (Opk int32-typed words [N][OH][OW][ceil(F/32)], A_next fp32 [N][OH][OW]).  Exactly one of
+    K and A (this layer's channel mean) is given; Wpk None: the filters are already expanded at the
+    start of `workspace` (xnor_filter_expand / xnor_prepare on a buffer of xnor_conv2d_chain_workspace_bytes)."""
     OH, OW = xnor_out_dim(s)
     Cwn = (s.F + 31) // 32
     if Opk is None:
@@ -483,50 +466,15 @@ def xnor_conv2d_fwd_chain(Ipk: torch.Tensor, Wpk: torch.Tensor, K: torch.Tensor,
     if A_next is None:
         A_next = torch.empty((s.N, OH, OW), dtype=torch.float32, device=Ipk.device)
     if workspace is None:
+        if Wpk is None:
+            raise ValueError("xnor_conv2d_fwd_chain: without Wpk the workspace with the expanded filters is needed")
         workspace = torch.empty((xnor_conv2d_chain_workspace_bytes(s),), dtype=torch.uint8, device=Ipk.device)
     _ok(lib.xnor_conv2d_fwd_chain(
-        _dev(Ipk, torch.int32, (s.N, s.H, s.W, s.Cw), "Ipk"), _dev(Wpk, torch.int32, (s.F, s.kh, s.kw, s.Cw), "Wpk"),
-        _dev(K, torch.float32, (s.N, OH, OW), "K"), _dev(alpha, torch.float32, (s.F,), "alpha"), ctypes.byref(s.c()),
-        _dev(Opk, torch.int32, (s.N, OH, OW, Cwn), "Opk"), _dev(A_next, torch.float32, (s.N, OH, OW), "A_next"),
-        _dev(workspace, torch.uint8, name="workspace"), workspace.numel(), _stream()), "xnor_conv2d_fwd_chain")
-    return Opk, A_next
-
-
-def xnor_conv2d_fwd_chain_from_A(Ipk: torch.Tensor, Wpk: torch.Tensor, A: torch.Tensor, alpha: torch.Tensor, s: Shape,
-                                 Opk: torch.Tensor | None = None, A_next: torch.Tensor | None = None,
-                                 workspace: torch.Tensor | None = None):
-    """xnor_conv2d_fwd_chain taking this layer's channel mean A [N][H][W] instead of K."""
-    OH, OW = xnor_out_dim(s)
-    Cwn = (s.F + 31) // 32
-    if Opk is None:
-        Opk = torch.empty((s.N, OH, OW, Cwn), dtype=torch.int32, device=Ipk.device)
-    if A_next is None:
-        A_next = torch.empty((s.N, OH, OW), dtype=torch.float32, device=Ipk.device)
-    if workspace is None:
-        workspace = torch.empty((xnor_conv2d_chain_workspace_bytes(s),), dtype=torch.uint8, device=Ipk.device)
-    _ok(lib.xnor_conv2d_fwd_chain_from_A(
-        _dev(Ipk, torch.int32, (s.N, s.H, s.W, s.Cw), "Ipk"), _dev(Wpk, torch.int32, (s.F, s.kh, s.kw, s.Cw), "Wpk"),
-        _dev(A, torch.float32, (s.N, s.H, s.W), "A"), _dev(alpha, torch.float32, (s.F,), "alpha"), ctypes.byref(s.c()),
-        _dev(Opk, torch.int32, (s.N, OH, OW, Cwn), "Opk"), _dev(A_next, torch.float32, (s.N, OH, OW), "A_next"),
-        _dev(workspace, torch.uint8, name="workspace"), workspace.numel(), _stream()), "xnor_conv2d_fwd_chain_from_A")
-    return Opk, A_next
-
-
-def xnor_conv2d_fwd_chain_expanded_from_A(Ipk: torch.Tensor, A: torch.Tensor, alpha: torch.Tensor, s: Shape,
-                                          workspace: torch.Tensor, Opk: torch.Tensor | None = None,
-                                          A_next: torch.Tensor | None = None):
-    """xnor_conv2d_fwd_chain_from_A with the filters already expanded at the start of `workspace`
-    (xnor_filter_expand / xnor_prepare on a buffer of xnor_conv2d_chain_workspace_bytes bytes)."""
-    OH, OW = xnor_out_dim(s)
-    Cwn = (s.F + 31) // 32
-    if Opk is None:
-        Opk = torch.empty((s.N, OH, OW, Cwn), dtype=torch.int32, device=Ipk.device)
-    if A_next is None:
-        A_next = torch.empty((s.N, OH, OW), dtype=torch.float32, device=Ipk.device)
-    _ok(lib.xnor_conv2d_fwd_chain_expanded_from_A(
-        _dev(Ipk, torch.int32, (s.N, s.H, s.W, s.Cw), "Ipk"), _dev(A, torch.float32, (s.N, s.H, s.W), "A"),
+        _dev(Ipk, torch.int32, (s.N, s.H, s.W, s.Cw), "Ipk"),
+        _dev(Wpk, torch.int32, (s.F, s.kh, s.kw, s.Cw), "Wpk") if Wpk is not None else None,
+        _dev(K, torch.float32, (s.N, OH, OW), "K") if K is not None else None,
+        _dev(A, torch.float32, (s.N, s.H, s.W), "A") if A is not None else None,
         _dev(alpha, torch.float32, (s.F,), "alpha"), ctypes.byref(s.c()),
         _dev(Opk, torch.int32, (s.N, OH, OW, Cwn), "Opk"), _dev(A_next, torch.float32, (s.N, OH, OW), "A_next"),
-        _dev(workspace, torch.uint8, name="workspace"), workspace.numel(), _stream()),
-        "xnor_conv2d_fwd_chain_expanded_from_A")
+        _dev(workspace, torch.uint8, name="workspace"), workspace.numel(), _stream()), "xnor_conv2d_fwd_chain")
     return Opk, A_next

@@ -398,12 +398,12 @@ int xnor_conv2d_chain_workspace_bytes(const xnor_shape *s, size_t *bytes)
     return XNOR_OK;
 }
 
-// (Wpk null: the expanded form, whose filters are already in the workspace)
-static int conv_chain(const uint32_t *Ipk, const uint32_t *Wpk, const float *K, const float *A, const float *alpha,
-                          const xnor_shape *s, uint32_t *Opk, float *A_next, void *workspace,
-                          size_t workspace_bytes, void *stream)
+// (Wpk null: the filters are already expanded in the workspace; exactly one of K, A)
+int xnor_conv2d_fwd_chain(const uint32_t *Ipk, const uint32_t *Wpk, const float *K, const float *A,
+                          const float *alpha, const xnor_shape *s, uint32_t *Opk, float *A_next,
+                          void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (!Ipk || (!K && !A) || !alpha || !s || !Opk || !A_next || !workspace) return XNOR_E_NULL;
+    if (!Ipk || (!K == !A) || !alpha || !s || !Opk || !A_next || !workspace) return XNOR_E_NULL;
     xnor::Geom g;
     const int rc = make_geom(s, &g);
     if (rc) return rc;
@@ -415,30 +415,6 @@ static int conv_chain(const uint32_t *Ipk, const uint32_t *Wpk, const float *K, 
     if (workspace_bytes < need) return XNOR_E_WORKSPACE;
     return hip_status(xnor::launch_conv_mfma_chain(Ipk, Wpk, K, A, alpha, g, Opk, A_next, workspace,
                                                    (hipStream_t)stream));
-}
-
-int xnor_conv2d_fwd_chain(const uint32_t *Ipk, const uint32_t *Wpk, const float *K, const float *alpha,
-                          const xnor_shape *s, uint32_t *Opk, float *A_next, void *workspace,
-                          size_t workspace_bytes, void *stream)
-{
-    if (!K || !Wpk) return XNOR_E_NULL;
-    return conv_chain(Ipk, Wpk, K, nullptr, alpha, s, Opk, A_next, workspace, workspace_bytes, stream);
-}
-
-int xnor_conv2d_fwd_chain_from_A(const uint32_t *Ipk, const uint32_t *Wpk, const float *A, const float *alpha,
-                                 const xnor_shape *s, uint32_t *Opk, float *A_next, void *workspace,
-                                 size_t workspace_bytes, void *stream)
-{
-    if (!A || !Wpk) return XNOR_E_NULL;
-    return conv_chain(Ipk, Wpk, nullptr, A, alpha, s, Opk, A_next, workspace, workspace_bytes, stream);
-}
-
-int xnor_conv2d_fwd_chain_expanded_from_A(const uint32_t *Ipk, const float *A, const float *alpha,
-                                          const xnor_shape *s, uint32_t *Opk, float *A_next, void *workspace,
-                                          size_t workspace_bytes, void *stream)
-{
-    if (!A) return XNOR_E_NULL;
-    return conv_chain(Ipk, nullptr, nullptr, A, alpha, s, Opk, A_next, workspace, workspace_bytes, stream);
 }
 
 int xnor_filter_expand(const uint32_t *Wpk, const xnor_shape *s, void *workspace,
@@ -456,36 +432,20 @@ int xnor_filter_expand(const uint32_t *Wpk, const xnor_shape *s, void *workspace
 }
 
 int xnor_conv2d_fwd_expanded(const uint32_t *Ipk, const void *workspace, size_t workspace_bytes,
-                             const float *K, const float *alpha, const xnor_shape *s, float *out,
-                             int32_t *dot, void *stream)
+                             const float *K, const float *A, const float *alpha, const xnor_shape *s,
+                             float *out, int32_t *dot, void *stream)
 {
-    if (!Ipk || !workspace || !K || !alpha || !s || !out) return XNOR_E_NULL;
+    if (!Ipk || !workspace || (!K == !A) || !alpha || !s || !out) return XNOR_E_NULL;   // (exactly one of K, A)
     xnor::Geom g;
     const int rc = make_geom(s, &g);
     if (rc) return rc;
-    if (!aligned(Ipk, 4) || !aligned(K, 4) || !aligned(alpha, 4) || !aligned(out, 4) ||
+    if (!aligned(Ipk, 4) || (K && !aligned(K, 4)) || (A && !aligned(A, 4)) || !aligned(alpha, 4) || !aligned(out, 4) ||
         (dot && !aligned(dot, 4)) || !aligned(workspace, 16))
         return XNOR_E_ALIGN;
     const size_t need = xnor::conv_mfma_workspace_bytes(g);
     if (need == 0) return XNOR_E_UNSUPPORTED;
     if (workspace_bytes < need) return XNOR_E_WORKSPACE;
-    return hip_status(xnor::launch_conv_mfma_expanded(Ipk, K, alpha, g, out, dot, workspace, (hipStream_t)stream));
-}
-
-int xnor_conv2d_fwd_expanded_from_A(const uint32_t *Ipk, const void *workspace, size_t workspace_bytes,
-                                    const float *A, const float *alpha, const xnor_shape *s, float *out,
-                                    int32_t *dot, void *stream)
-{
-    if (!Ipk || !workspace || !A || !alpha || !s || !out) return XNOR_E_NULL;
-    xnor::Geom g;
-    const int rc = make_geom(s, &g);
-    if (rc) return rc;
-    if (!aligned(Ipk, 4) || !aligned(A, 4) || !aligned(alpha, 4) || !aligned(out, 4) ||
-        (dot && !aligned(dot, 4)) || !aligned(workspace, 16))
-        return XNOR_E_ALIGN;
-    const size_t need = xnor::conv_mfma_workspace_bytes(g);
-    if (need == 0) return XNOR_E_UNSUPPORTED;
-    if (workspace_bytes < need) return XNOR_E_WORKSPACE;
+    if (K) return hip_status(xnor::launch_conv_mfma_expanded(Ipk, K, alpha, g, out, dot, workspace, (hipStream_t)stream));
     return hip_status(xnor::launch_conv_mfma_expanded_from_A(Ipk, A, alpha, g, out, dot, workspace,
                                                              (hipStream_t)stream));
 }

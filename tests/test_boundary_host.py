@@ -109,25 +109,29 @@ def test_null_and_alignment_rejected(xb):
     assert L.xnor_filter_expand(ok, sp, None, need, None) == xb.E_NULL
     assert L.xnor_filter_expand(ok, sp, ctypes.c_void_p(0x1008), need, None) == xb.E_ALIGN
     assert L.xnor_filter_expand(ok, sp, ok, need - 1, None) == xb.E_WORKSPACE
-    assert L.xnor_conv2d_fwd_expanded(ok, None, need, ok, ok, sp, ok, None, None) == xb.E_NULL
-    assert L.xnor_conv2d_fwd_expanded(ok, ok, need - 1, ok, ok, sp, ok, None, None) == xb.E_WORKSPACE
-    assert L.xnor_conv2d_fwd_expanded(odd, ok, need, ok, ok, sp, ok, None, None) == xb.E_ALIGN
-    # chained form
+    # (Ipk, workspace, bytes, K, A, alpha, shape, out, dot, stream): exactly one of K, A
+    assert L.xnor_conv2d_fwd_expanded(ok, None, need, ok, None, ok, sp, ok, None, None) == xb.E_NULL
+    assert L.xnor_conv2d_fwd_expanded(ok, ok, need, None, None, ok, sp, ok, None, None) == xb.E_NULL
+    assert L.xnor_conv2d_fwd_expanded(ok, ok, need, ok, ok, ok, sp, ok, None, None) == xb.E_NULL
+    assert L.xnor_conv2d_fwd_expanded(ok, ok, need - 1, ok, None, ok, sp, ok, None, None) == xb.E_WORKSPACE
+    assert L.xnor_conv2d_fwd_expanded(ok, ok, need - 1, None, ok, ok, sp, ok, None, None) == xb.E_WORKSPACE
+    assert L.xnor_conv2d_fwd_expanded(odd, ok, need, ok, None, ok, sp, ok, None, None) == xb.E_ALIGN
+    assert L.xnor_conv2d_fwd_expanded(ok, ok, need, None, odd, ok, sp, ok, None, None) == xb.E_ALIGN
+    # chained form: (Ipk, Wpk or NULL, K, A, alpha, shape, Opk, A_next, workspace, bytes, stream)
     cneed = xb.xnor_conv2d_chain_workspace_bytes(s)
     assert cneed > need
-    assert L.xnor_conv2d_fwd_chain(ok, ok, ok, ok, sp, None, ok, ok, cneed, None) == xb.E_NULL
-    assert L.xnor_conv2d_fwd_chain(ok, ok, ok, ok, sp, ok, ok, None, cneed, None) == xb.E_NULL
-    assert L.xnor_conv2d_fwd_chain(ok, ok, ok, ok, sp, ok, ok, ok, cneed - 1, None) == xb.E_WORKSPACE
-    assert L.xnor_conv2d_fwd_chain(ok, ok, ok, ok, sp, odd, ok, ok, cneed, None) == xb.E_ALIGN
-    assert L.xnor_conv2d_fwd_chain_from_A(ok, ok, None, ok, sp, ok, ok, ok, cneed, None) == xb.E_NULL
-    assert L.xnor_conv2d_fwd_chain_from_A(ok, ok, odd, ok, sp, ok, ok, ok, cneed, None) == xb.E_ALIGN
-    assert L.xnor_conv2d_fwd_chain_from_A(ok, None, ok, ok, sp, ok, ok, ok, cneed, None) == xb.E_NULL
-    assert L.xnor_conv2d_fwd_chain_expanded_from_A(ok, None, ok, sp, ok, ok, ok, cneed, None) == xb.E_NULL
-    assert L.xnor_conv2d_fwd_chain_expanded_from_A(ok, ok, ok, sp, ok, ok, None, cneed, None) == xb.E_NULL
-    assert L.xnor_conv2d_fwd_chain_expanded_from_A(ok, ok, ok, sp, ok, ok, ok, cneed - 1, None) == xb.E_WORKSPACE
-    assert L.xnor_conv2d_fwd_chain_expanded_from_A(ok, odd, ok, sp, ok, ok, ok, cneed, None) == xb.E_ALIGN
-    assert L.xnor_conv2d_fwd_expanded_from_A(ok, ok, need, None, ok, sp, ok, None, None) == xb.E_NULL
-    assert L.xnor_conv2d_fwd_expanded_from_A(ok, ok, need - 1, ok, ok, sp, ok, None, None) == xb.E_WORKSPACE
+    assert L.xnor_conv2d_fwd_chain(ok, ok, ok, None, ok, sp, None, ok, ok, cneed, None) == xb.E_NULL
+    assert L.xnor_conv2d_fwd_chain(ok, ok, ok, None, ok, sp, ok, ok, None, cneed, None) == xb.E_NULL
+    assert L.xnor_conv2d_fwd_chain(ok, ok, None, None, ok, sp, ok, ok, ok, cneed, None) == xb.E_NULL
+    assert L.xnor_conv2d_fwd_chain(ok, ok, ok, ok, ok, sp, ok, ok, ok, cneed, None) == xb.E_NULL
+    assert L.xnor_conv2d_fwd_chain(ok, ok, ok, None, ok, sp, ok, ok, ok, cneed - 1, None) == xb.E_WORKSPACE
+    assert L.xnor_conv2d_fwd_chain(ok, ok, ok, None, ok, sp, odd, ok, ok, cneed, None) == xb.E_ALIGN
+    assert L.xnor_conv2d_fwd_chain(ok, ok, None, odd, ok, sp, ok, ok, ok, cneed, None) == xb.E_ALIGN
+    assert L.xnor_conv2d_fwd_chain(ok, odd, None, ok, ok, sp, ok, ok, ok, cneed, None) == xb.E_ALIGN
+    # (no Wpk: the filters are already expanded in the workspace)
+    assert L.xnor_conv2d_fwd_chain(ok, None, None, ok, ok, sp, ok, ok, None, cneed, None) == xb.E_NULL
+    assert L.xnor_conv2d_fwd_chain(ok, None, None, ok, ok, sp, ok, ok, ok, cneed - 1, None) == xb.E_WORKSPACE
+    assert L.xnor_conv2d_fwd_chain(ok, None, None, odd, ok, sp, ok, ok, ok, cneed, None) == xb.E_ALIGN
     assert L.xnor_box_filter_K(None, sp, ok, None) == xb.E_NULL
     assert L.xnor_box_filter_K(ok, sp, odd, None) == xb.E_ALIGN
     # the one-kernel pass for few-channel images: this 64-channel shape is not its business

@@ -59,12 +59,12 @@ def test_chain_outputs_vs_oracle(xb, shape):
     Wpk, alpha, _ = xb.xnor_filter_prepare(dev(Wt))
     Opk, A_next = xb.xnor_conv2d_fwd_chain(Ipk, Wpk, K, alpha, s)
     # the form that takes the channel mean and forms K itself gives the same bits
-    Opk2, A_next2 = xb.xnor_conv2d_fwd_chain_from_A(Ipk, Wpk, A, alpha, s)
+    Opk2, A_next2 = xb.xnor_conv2d_fwd_chain(Ipk, Wpk, None, alpha, s, A=A)
     # ... and so does the form whose filters were expanded beforehand, into the chain workspace
     cws = torch.empty((xb.xnor_conv2d_chain_workspace_bytes(s),), dtype=torch.uint8, device="cuda")
     xb.xnor_filter_expand(Wpk, s, cws)
-    Opk3, A_next3 = xb.xnor_conv2d_fwd_chain_expanded_from_A(Ipk, A, alpha, s, cws)
-    Opk4, A_next4 = xb.xnor_conv2d_fwd_chain_expanded_from_A(Ipk, A, alpha, s, cws)   # (the filters are only read)
+    Opk3, A_next3 = xb.xnor_conv2d_fwd_chain(Ipk, None, None, alpha, s, workspace=cws, A=A)
+    Opk4, A_next4 = xb.xnor_conv2d_fwd_chain(Ipk, None, None, alpha, s, workspace=cws, A=A)   # (the filters are only read)
     torch.cuda.synchronize()
     assert torch.equal(Opk, Opk2) and torch.equal(A_next, A_next2)
     assert torch.equal(Opk, Opk3) and torch.equal(A_next, A_next3)

@@ -187,7 +187,7 @@ def test_matrix_core_kernel_with_outputs_spread_over_more_than_2_gib():
     assert rel_ok(out[:, fsel].cpu().numpy(), O_ref)
     # the same through the form that makes K itself, with the raw dots
     ws = xb.xnor_filter_expand(Wpk, s)
-    out2, dot2 = xb.xnor_conv2d_fwd_expanded_from_A(Ipk, ws, A, alpha, s, want_dot=True)
+    out2, dot2 = xb.xnor_conv2d_fwd_expanded(Ipk, ws, None, alpha, s, want_dot=True, A=A)
     torch.cuda.synchronize()
     assert torch.equal(out2, out)
     assert np.array_equal(dot2[:, fsel].cpu().numpy(), d_ref)
@@ -248,7 +248,7 @@ def test_c5_repeated_steps_identical():
     def step(from_A):
         xb.xnor_prepare(dI, dW, s, Ipk, A, K, Wpk, M, alpha, want_K=not from_A, workspace=ws)
         if from_A:
-            xb.xnor_conv2d_fwd_expanded_from_A(Ipk, ws, A, alpha, s, out=out)
+            xb.xnor_conv2d_fwd_expanded(Ipk, ws, None, alpha, s, out=out, A=A)
         else:
             xb.xnor_conv2d_fwd_expanded(Ipk, ws, K, alpha, s, out=out)
 

@@ -339,7 +339,7 @@ def test_buffers_that_are_only_4_or_8_byte_aligned(xb, offset_words):
                                    (2, 32, 20, 31, 33, 3, 3, 2, 2, 1, 1), (1, 128, 9, 9, 64, 3, 3, 1, 1, 3, 3)],
                          ids=lambda s: "x".join(map(str, s)))
 def test_conv_that_forms_K_itself(xb, shape):
-    """xnor_input_prepare without K + xnor_conv2d_fwd_expanded_from_A: the workgroups form K from A
+    """xnor_input_prepare without K + xnor_conv2d_fwd_expanded given A: the workgroups form K from A
     with the box filter's own arithmetic, so dots and outputs equal the staged path bit for bit."""
     print(f"case K-from-A shape={shape}", flush=True)
     rng = np.random.default_rng(zlib.crc32(("fromA" + str(shape)).encode()))
@@ -350,7 +350,7 @@ def test_conv_that_forms_K_itself(xb, shape):
     assert none is None
     Wpk, alpha, _ = xb.xnor_filter_prepare(dev(Wt))
     ws = xb.xnor_filter_expand(Wpk, s)
-    out, dot = xb.xnor_conv2d_fwd_expanded_from_A(Ipk, ws, A, alpha, s, want_dot=True)
+    out, dot = xb.xnor_conv2d_fwd_expanded(Ipk, ws, None, alpha, s, want_dot=True, A=A)
     _, K, _ = xb.xnor_input_prepare(dI, s)
     out2, dot2 = xb.xnor_conv2d_fwd_expanded(Ipk, ws, K, alpha, s, want_dot=True)
     torch.cuda.synchronize()
@@ -420,8 +420,8 @@ def test_step_replays_from_a_hip_graph(xb):
 
     def step():
         xb.xnor_prepare(dI, dW, s, Ipk, A, None, Wpk, M, alpha, want_K=False, workspace=ws)
-        xb.xnor_conv2d_fwd_expanded_from_A(Ipk, ws, A, alpha, s, out=out)
-        xb.xnor_conv2d_fwd_chain_from_A(Ipk, Wpk, A, alpha, s, Opk, A_next, cws)
+        xb.xnor_conv2d_fwd_expanded(Ipk, ws, None, alpha, s, out=out, A=A)
+        xb.xnor_conv2d_fwd_chain(Ipk, Wpk, None, alpha, s, Opk, A_next, cws, A=A)
         xb.xnor_forward_image(img, iWpk, ialpha, ishape, out=img_out)
         xb.xnor_bwn_conv2d_fwd(dI, Wpk, alpha, s, out=bwn_out)
 
@@ -469,7 +469,7 @@ def test_two_streams_at_once(xb):
 
         def run(dI=dI, dW=dW, s=s, Ipk=Ipk, A=A, Wpk=Wpk, M=M, alpha=alpha, ws=ws, out=out, bwn=bwn):
             xb.xnor_prepare(dI, dW, s, Ipk, A, None, Wpk, M, alpha, want_K=False, workspace=ws)
-            xb.xnor_conv2d_fwd_expanded_from_A(Ipk, ws, A, alpha, s, out=out)
+            xb.xnor_conv2d_fwd_expanded(Ipk, ws, None, alpha, s, out=out, A=A)
             xb.xnor_bwn_conv2d_fwd(dI, Wpk, alpha, s, out=bwn)
 
         run()

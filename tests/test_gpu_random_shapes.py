@@ -122,7 +122,7 @@ def test_random_shape_all_forms(xb, shape):
     if nbytes > 0:
         ws = torch.empty((nbytes,), dtype=torch.uint8, device="cuda")
         Ipk2, K2, A2, Wpk2, alpha2, _ = xb.xnor_prepare(dI, dW, s, want_K=False, workspace=ws)
-        out2, dot2 = xb.xnor_conv2d_fwd_expanded_from_A(Ipk2, ws, A2, alpha2, s, want_dot=True)
+        out2, dot2 = xb.xnor_conv2d_fwd_expanded(Ipk2, ws, None, alpha2, s, want_dot=True, A=A2)
         torch.cuda.synchronize()
         assert K2 is None
         assert torch.equal(Ipk2, Ipk) and torch.equal(Wpk2, Wpk), "packed words (fused prepare)"
@@ -130,7 +130,7 @@ def test_random_shape_all_forms(xb, shape):
         assert_rel(out2.cpu().numpy(), O_ref, "out (fused step)", out_floor(d_ref, a_ref))
 
         # chained form: packed signs and channel mean of the output
-        Opk, A_next = xb.xnor_conv2d_fwd_chain_from_A(Ipk, Wpk, A, alpha, s)
+        Opk, A_next = xb.xnor_conv2d_fwd_chain(Ipk, Wpk, None, alpha, s, A=A)
         torch.cuda.synchronize()
         assert np.array_equal(Opk.cpu().numpy().view(np.uint32), oracle.pack(O_ref)), "packed signs of the output"
         An_ref = oracle.channel_mean_abs(O_ref)
