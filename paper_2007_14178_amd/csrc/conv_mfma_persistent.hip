@@ -76,6 +76,7 @@ struct PParams {
     int work_per_xcd;  // whole_items + 2 * (items_per_xcd - whole_items)
     int start_turn;  // the first group lets the second one start at this turn of its first item
     int prio_mask;   // the second group raises its issue priority in the turns t with (t & prio_mask) != 0
+    int stagger;     // the odd workgroups of an XCD start this many times 1024 cycles late (0: all at once)
 #ifdef XNOR_TS_BUILD
     unsigned long long *ts;   // (measurement build) [workgroup][group][item < 8][8] shader-clock stamps
     int dbg;                  // (measurement build) 1: no output stores, 2: second groups idle
@@ -950,6 +951,12 @@ __global__ __launch_bounds__(512) void conv_mfma_persistent_kernel(PParams p)
     const int nslot = 2 * p.wgs_per_xcd;
 #endif
 
+    // Every group stores an item's outputs in one burst, and groups that start together stay
+    // together: the workgroups without a unit of the last, partial round (the odd ones of an XCD)
+    // start a quarter of an item's time late, so that the chip sees four bursts of stores per item
+    // time instead of two (their second groups wait for the first ones anyway).
+    if (grp == 0 && (wi & 1))
+        for (int i = 0; i < p.stagger; ++i) __builtin_amdgcn_s_sleep(16);
     // the first group releases the second one at turn `sturn` of its first item (-1: not, or done);
     // with start_turn < 0 both start at once
     int sturn = grp == 0 ? p.start_turn : -1;
@@ -1611,6 +1618,7 @@ hipError_t launch_conv_mfma_persistent(const uint32_t *Ipk, const float *K, cons
     p.nbands = ceil_div(p.total_rows, pl.TH);
     p.bands_per_xcd = ceil_div(p.nbands, kXcds);
     p.items_per_xcd = p.bands_per_xcd * pl.f_tiles;
+    p.stagger = 0;
     // One workgroup per compute unit, two groups each: 2 * CUs slots per XCD.
     const int cus_per_xcd = std::max(1, compute_units(dev) / kXcds);
     if (p.items_per_xcd < 2 * cus_per_xcd) {
@@ -1631,6 +1639,10 @@ hipError_t launch_conv_mfma_persistent(const uint32_t *Ipk, const float *K, cons
         p.whole_items = (rem > 0 && 2 * rem <= nslot) ? p.items_per_xcd - rem : p.items_per_xcd;
         p.work_per_xcd = p.whole_items + 2 * (p.items_per_xcd - p.whole_items);
         p.start_turn = pl.nturns / 2;
+        // (an item's time is about 2.5 times its matrix instructions': 8 x 32 cycles per step; the
+        //  late workgroups have the time: they are the ones without a half item at the end)
+        if (p.whole_items < p.items_per_xcd && p.work_per_xcd - p.whole_items <= p.wgs_per_xcd)
+            p.stagger = (int)(0.625 * pl.nturns * 4 * 256 / 1024);
     }
     p.prio_mask = 7;
 #ifdef XNOR_TS_BUILD
@@ -1643,6 +1655,8 @@ hipError_t launch_conv_mfma_persistent(const uint32_t *Ipk, const float *K, cons
         if (st) p.start_turn = atoi(st);
         const char *pm = getenv("XNOR_PMASK");
         if (pm) p.prio_mask = atoi(pm);
+        const char *sg = getenv("XNOR_STAGGER");
+        if (sg) p.stagger = atoi(sg);
         const char *wg = getenv("XNOR_WGS");
         if (wg) p.wgs_per_xcd = std::min(p.wgs_per_xcd, atoi(wg));
     }
