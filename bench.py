@@ -118,7 +118,8 @@ def parse():
                          "records per step cost the host more than the step costs the GPU)")
     ap.add_argument("--peaks", action="store_true",
                     help="not the benchmark line: the ceilings this GPU sustains (register-only FP4 matrix loop, "
-                         "v_xor + v_bcnt loop, plain copies of 64 MiB and 1 GiB), one JSON line")
+                         "bf16 matrix loop, v_xor + v_bcnt loop, plain copies of 64 MiB and 1 GiB) and the cost of replaying "
+                         "a HIP graph of one or two tiny kernels, one JSON line")
     ap.add_argument("--print-conv-digest", action="store_true",
                     help="print the fingerprint of the convolution sources (for the traffic line of a counter summary)")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="target CPU time of the oracle sample")
@@ -759,6 +760,30 @@ def run_peaks(args, xb, torch):
         out[f"copy_{mib}MiB_gbs_read_plus_write"] = 2.0 * (mib << 20) / t / 1e9
         del src, dst
     out["hbm_published_gbs"] = PEAK_HBM_GBS
+    # what one replay of a captured HIP graph costs when the graph holds next to nothing (one or two
+    # 256-byte copies): the floor under every graph-replayed step time
+    a = torch.zeros((64,), dtype=torch.float32, device="cuda")
+    b = torch.zeros_like(a)
+    for n in (1, 2):
+        def tiny():
+            xb.xnor_probe_copy(a, b)
+            if n == 2:
+                xb.xnor_probe_copy(b, a)
+        stream = torch.cuda.Stream()
+        with torch.cuda.stream(stream):
+            tiny()
+            stream.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                tiny()
+            for _ in range(200):
+                graph.replay()
+            stream.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(2000):
+                graph.replay()
+            stream.synchronize()
+            out[f"graph_replay_us_{n}_tiny_kernels"] = (time.perf_counter() - t0) / 2000 * 1e6
     return out
 
 
