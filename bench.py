@@ -758,6 +758,8 @@ def run_peaks(args, xb, torch):
         dst = torch.empty_like(src)
         t = timed(lambda: xb.xnor_probe_copy(src, dst), 10)
         out[f"copy_{mib}MiB_gbs_read_plus_write"] = 2.0 * (mib << 20) / t / 1e9
+        t = timed(lambda: xb.xnor_probe_read(src, sink_i), 10)
+        out[f"read_{mib}MiB_gbs"] = (mib << 20) / t / 1e9
         del src, dst
     out["hbm_published_gbs"] = PEAK_HBM_GBS
     # what one replay of a captured HIP graph costs when the graph holds next to nothing (one or two

@@ -349,6 +349,8 @@ int xnor_conv2d_pick_algo(const xnor_shape *s, size_t workspace_bytes);
  *                            and pair
  *   xnor_probe_copy          copies `bytes` (a multiple of 16; both pointers 16-byte aligned) from
  *                            src to dst, 16 bytes per lane
+ *   xnor_probe_read          reads `bytes` (a multiple of 16, 16-byte aligned) of src, 16 bytes per
+ *                            lane, and writes nothing
  * `sink` (device, 4 bytes) is never written in practice; it keeps the loops alive.  `flops` and
  * `binary_macs` are host pointers.  XNOR_E_SHAPE for counts <= 0 or beyond 2^20 workgroups /
  * 2^24 iterations, or a byte count that is 0 or no multiple of 16.
@@ -357,6 +359,7 @@ int xnor_probe_mfma_fp4(int workgroups, int iters, float *sink, double *flops, v
 int xnor_probe_mfma_bf16(int workgroups, int iters, int random_b, float *sink, double *flops, void *stream);
 int xnor_probe_xor_popcount(int workgroups, int iters, uint32_t *sink, double *binary_macs, void *stream);
 int xnor_probe_copy(const void *src, void *dst, size_t bytes, void *stream);
+int xnor_probe_read(const void *src, size_t bytes, uint32_t *sink, void *stream);
 
 #ifdef __cplusplus
 }

@@ -94,6 +94,7 @@ def _load() -> ctypes.CDLL:
     L.xnor_probe_mfma_bf16.argtypes = [ci, ci, ci, vp, dp, vp]
     L.xnor_probe_xor_popcount.argtypes = [ci, ci, vp, dp, vp]
     L.xnor_probe_copy.argtypes = [vp, vp, sz, vp]
+    L.xnor_probe_read.argtypes = [vp, sz, vp, vp]
     L.xnor_conv2d_fwd_expanded.argtypes = [vp, vp, sz, vp, vp, vp, sp, vp, vp, vp]
     L.xnor_box_filter_K.argtypes = [vp, sp, vp, vp]
     L.xnor_conv2d_chain_workspace_bytes.argtypes = [sp, ctypes.POINTER(sz)]
@@ -114,7 +115,7 @@ def _load() -> ctypes.CDLL:
                  "xnor_forward_image_supported", "xnor_forward_image",
                  "xnor_bwn_conv2d_fwd", "xnor_bwn_conv2d_fwd_algo",
                  "xnor_prepare", "xnor_conv2d_fwd_static",
-                 "xnor_probe_mfma_fp4", "xnor_probe_mfma_bf16", "xnor_probe_xor_popcount", "xnor_probe_copy",
+                 "xnor_probe_mfma_fp4", "xnor_probe_mfma_bf16", "xnor_probe_xor_popcount", "xnor_probe_copy", "xnor_probe_read",
                  "xnor_conv2d_fp32_fwd", "xnor_conv2d_fp32_fwd_algo"):
         getattr(L, name).restype = ci
     return L
@@ -351,6 +352,14 @@ def xnor_probe_copy(src: torch.Tensor, dst: torch.Tensor) -> int:
         raise ValueError("xnor_probe_copy: src and dst differ in size")
     _ok(lib.xnor_probe_copy(_dev(src, src.dtype, name="src"), _dev(dst, dst.dtype, name="dst"), nbytes, _stream()),
         "xnor_probe_copy")
+    return nbytes
+
+
+def xnor_probe_read(src: torch.Tensor, sink: torch.Tensor) -> int:
+    """Enqueue a plain 16-byte-per-lane read of `src`; returns the bytes it reads."""
+    nbytes = src.numel() * src.element_size()
+    _ok(lib.xnor_probe_read(_dev(src, src.dtype, name="src"), nbytes, _dev(sink, torch.int32, name="sink"), _stream()),
+        "xnor_probe_read")
     return nbytes
 
 

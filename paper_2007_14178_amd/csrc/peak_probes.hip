@@ -11,6 +11,8 @@
 //   * probe_xor_popcount_kernel  register-only loop of v_xor_b32 + v_bcnt_u32_b32 pairs (32 binary
 //                                multiply-accumulates per lane and pair), eight independent chains
 //   * probe_copy_kernel          plain 16-byte-per-lane device copy
+//   * probe_read_kernel          plain 16-byte-per-lane read of a buffer (what a kernel that reads far
+//                                more than it writes, like the input pass, can be held against)
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -129,6 +131,17 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(const uint4 *__restrict
     for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
+__global__ __launch_bounds__(256) void probe_read_kernel(const uint4 *__restrict__ src, long long n16, uint32_t *sink)
+{
+    const long long stride = (long long)gridDim.x * 256;
+    uint32_t acc = 0;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) {
+        const uint4 v = src[i];
+        acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+    if (acc == 0x9e3779b9u) sink[0] = acc;   // (practically never; the compiler cannot know)
+}
+
 int status(hipError_t e) { return e == hipSuccess ? XNOR_OK : XNOR_E_HIP; }
 
 }  // namespace
@@ -174,6 +187,18 @@ int xnor_probe_copy(const void *src, void *dst, size_t bytes, void *stream)
     const int grid = (int)(want < 256 * 32 ? want : 256 * 32);   // up to 32 workgroups per compute unit, grid-stride beyond
     probe_copy_kernel<<<dim3(grid), dim3(256), 0, (hipStream_t)stream>>>(static_cast<const uint4 *>(src),
                                                                            static_cast<uint4 *>(dst), n16);
+    return status(hipGetLastError());
+}
+
+int xnor_probe_read(const void *src, size_t bytes, uint32_t *sink, void *stream)
+{
+    if (!src || !sink) return XNOR_E_NULL;
+    if (bytes == 0 || bytes % 16 != 0) return XNOR_E_SHAPE;
+    if ((uintptr_t)src & 15) return XNOR_E_ALIGN;
+    const long long n16 = (long long)(bytes / 16);
+    const long long want = (n16 + 255) / 256;
+    const int grid = (int)(want < 256 * 32 ? want : 256 * 32);
+    probe_read_kernel<<<dim3(grid), dim3(256), 0, (hipStream_t)stream>>>(static_cast<const uint4 *>(src), n16, sink);
     return status(hipGetLastError());
 }
 

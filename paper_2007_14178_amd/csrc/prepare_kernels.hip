@@ -5,6 +5,7 @@
 // All three read fp32 once and write far less than they read, so each is laid out for coalesced
 // 256-byte wavefront reads along the image's fastest axis with many loads in flight per lane.
 #include <algorithm>
+#include <atomic>
 
 #include "xnor_internal.hpp"
 
@@ -208,15 +209,18 @@ constexpr int kPack4Batch = 8;      // channels whose loads are in flight togeth
 
 __device__ __attribute__((always_inline)) void pack_and_mean4_block(
     const float *__restrict__ x, long long NP, int C, int HW, int Cw, int Cwp,
-    uint32_t *__restrict__ packed, float *__restrict__ A, long long block, double *pm_smem)
+    uint32_t *__restrict__ packed, float *__restrict__ A, long long block, int ppb, double *pm_smem)
 {
+    // `ppb`: pixels per block, a multiple of 4 up to 256 (lanes beyond it idle): the host picks it so
+    // that the blocks share out evenly over the compute units
     const int lane = threadIdx.x, s = threadIdx.y, S = blockDim.y;
     double *part = pm_smem;                                               // [S][4][64]
     uint32_t *words = reinterpret_cast<uint32_t *>(pm_smem + S * 256);    // [4][64][Cwp], Cwp odd
-    const long long p0 = block * 256;
+    const long long p0 = block * ppb;
     const long long p = p0 + 4 * lane;
+    const bool mine = 4 * lane < ppb && p < NP;
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
-    if (p < NP) {
+    if (mine) {
         const long long n = p / HW;
         const int hw = (int)(p - n * HW);
         const float *src = x + (n * C) * (long long)HW + hw;
@@ -281,13 +285,13 @@ __device__ __attribute__((always_inline)) void pack_and_mean4_block(
     __syncthreads();
     // pixel 4*lane + k: slice k % S adds up the slices' sums (fixed order) when S >= 4
     for (int k = s; k < 4; k += S) {
-        if (p + k < NP) {
+        if (mine && p + k < NP) {
             double sum = part[k * 64 + lane];
             for (int t = 1; t < S; ++t) sum += part[(t * 4 + k) * 64 + lane];
             A[p + k] = (float)(sum / (double)C);
         }
     }
-    const int npx = (int)min((long long)256, NP - p0);
+    const int npx = (int)min((long long)ppb, NP - p0);
     const int nwords = npx * Cw;
     uint32_t *dst = packed + p0 * Cw;
     for (int i = s * 64 + lane; i < nwords; i += 64 * S) {
@@ -298,10 +302,33 @@ __device__ __attribute__((always_inline)) void pack_and_mean4_block(
 
 __global__ __launch_bounds__(64 * kPack4Slices) void pack_and_mean4_kernel(
     const float *__restrict__ x, long long NP, int C, int HW, int Cw, int Cwp,
-    uint32_t *__restrict__ packed, float *__restrict__ A)
+    uint32_t *__restrict__ packed, float *__restrict__ A, int ppb)
 {
     extern __shared__ double pm_smem[];
-    pack_and_mean4_block(x, NP, C, HW, Cw, Cwp, packed, A, blockIdx.x, pm_smem);
+    pack_and_mean4_block(x, NP, C, HW, Cw, Cwp, packed, A, blockIdx.x, ppb, pm_smem);
+}
+
+// Pixels per block of the four-pixel pass.  A compute unit pulls from HBM at a rate of its own
+// (outstanding misses, not lanes, are what it runs out of: measured, a second block on the same unit
+// halves the first one's rate), so a launch is as long as its busiest unit: the pixels are shared out
+// as equal blocks over a multiple of the units instead of as 256-pixel blocks that leave the last
+// round partly empty.
+static int pixels_per_block4(long long NP)
+{
+    static std::atomic<int> cus_cached{0};
+    int cus = cus_cached.load(std::memory_order_relaxed);
+    if (cus <= 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
+        cus_cached.store(cus, std::memory_order_relaxed);
+    }
+    const long long quads = (NP + 3) / 4;
+    for (long long k = 1;; ++k) {
+        const long long per = (quads + cus * k - 1) / (cus * k);
+        if (per <= 64) return (int)std::max<long long>(per, 16) * 4;   // (at least a quarter of the lanes busy)
+    }
 }
 
 bool pack_and_mean_supports(int C) { return (C + 31) / 32 <= 512; }
@@ -316,8 +343,9 @@ hipError_t launch_pack_and_mean(const float *x, int N, int C, int H, int W, uint
         while (S4 < kPack4Slices && 2 * S4 <= Cw) S4 *= 2;
         const size_t smem4 = (size_t)S4 * 256 * sizeof(double) + (size_t)256 * Cwp * sizeof(uint32_t);
         if (smem4 <= 64 * 1024) {
-            pack_and_mean4_kernel<<<dim3(ceil_div(NP, 256)), dim3(64, S4), smem4, st>>>(x, NP, C, HW, Cw,
-                                                                                      Cwp, packed, A);
+            const int ppb = pixels_per_block4(NP);
+            pack_and_mean4_kernel<<<dim3(ceil_div(NP, ppb)), dim3(64, S4), smem4, st>>>(x, NP, C, HW, Cw,
+                                                                                      Cwp, packed, A, ppb);
             return hipGetLastError();
         }
     }
@@ -453,22 +481,21 @@ __global__ __launch_bounds__(256) void filter_pack_mean_kernel(
     filter_pack_mean_block(Wt, C, taps, Cw, CH, Wpk, M, alpha, blockIdx.x, threadIdx.x, 256, fp_smem);
 }
 
-// Input side and filter side of a layer in ONE launch: the first blocks each pack 256 pixels of the
-// input (pack_and_mean4_block), the last F blocks each prepare one filter (filter_pack_mean_block).
-// The two sides do not depend on each other.  A compute unit holds one of these 512-thread blocks
-// at a time, and the input blocks rarely fill a whole number of rounds (c5: 392 blocks on 256
-// units): the filter blocks, dispatched last, run on the units the last round leaves idle instead
-// of costing another launch in front of the convolution.
+// Input side and filter side of a layer in ONE launch: the first blocks each pack up to 256 pixels
+// of the input (pack_and_mean4_block; the pixels are shared out evenly over a multiple of the compute
+// units, see pixels_per_block4), the last F blocks each prepare one filter (filter_pack_mean_block).
+// The two sides do not depend on each other; the filter blocks, dispatched last, cost no launch of
+// their own in front of the convolution.
 __global__ __launch_bounds__(64 * kPack4Slices) void prepare_both_kernel(
     const float *__restrict__ x, long long NP, int C, int HW, int Cw, int Cwp,
     uint32_t *__restrict__ packed, float *__restrict__ A,
     const float *__restrict__ Wt, int F, int taps, int CH, uint32_t *__restrict__ Wpk,
-    float *__restrict__ M, float *__restrict__ alpha, uint4 *__restrict__ Wx, ExpandLayout L)
+    float *__restrict__ M, float *__restrict__ alpha, uint4 *__restrict__ Wx, ExpandLayout L, int ppb)
 {
     extern __shared__ double both_smem[];
-    const long long nb_in = (NP + 255) / 256;
+    const long long nb_in = (NP + ppb - 1) / ppb;
     if ((long long)blockIdx.x < nb_in)
-        pack_and_mean4_block(x, NP, C, HW, Cw, Cwp, packed, A, blockIdx.x, both_smem);
+        pack_and_mean4_block(x, NP, C, HW, Cw, Cwp, packed, A, blockIdx.x, ppb, both_smem);
     else
         filter_pack_mean_block(Wt, C, taps, Cw, CH, Wpk, M, alpha, (int)(blockIdx.x - nb_in),
                                threadIdx.y * 64 + threadIdx.x, 64 * blockDim.y, both_smem, Wx, L, F);
@@ -567,10 +594,11 @@ hipError_t launch_prepare_both(const float *x, int N, int C, int H, int W, uint3
     if (pass == 4) {
         const size_t smem4 = (size_t)kPack4Slices * 256 * sizeof(double) + (size_t)256 * Cwp * sizeof(uint32_t);
         const size_t smem = std::max(smem4, smemf);
-        const long long blocks = (long long)F + ceil_div(NP, 256);
+        const int ppb = pixels_per_block4(NP);
+        const long long blocks = (long long)F + ceil_div(NP, ppb);
         if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
         prepare_both_kernel<<<dim3((unsigned)blocks), dim3(64, kPack4Slices), smem, st>>>(
-            x, NP, C, HW, Cw, Cwp, packed, A, Wt, F, taps, CH, Wpk, M, alpha, static_cast<uint4 *>(Wx), L);
+            x, NP, C, HW, Cw, Cwp, packed, A, Wt, F, taps, CH, Wpk, M, alpha, static_cast<uint4 *>(Wx), L, ppb);
         return hipGetLastError();
     }
     if (pass != 1) return hipErrorInvalidValue;   // (prepare_both_supports said no)
