@@ -447,21 +447,41 @@ SplitPlan make_split_plan(const Geom &g)
     if ((long long)g.F * g.kh * g.kw * g.Cw >= (1LL << 29)) return pl;     // (32-bit byte offsets into Wpk)
     pl.pitch = g.W + 2 * g.pw;
     // Pixel tiles per workgroup: as few workgroups per image as the tile limit, the prefetch
-    // registers and the LDS allow (every workgroup stages its own input rows), the tiles shared out
-    // evenly over them.  (Workgroups of six tiles and a short last one measured no faster at
-    // 28 x 28 outputs and slower at 14 x 14.)
+    // registers and the LDS allow (every workgroup stages its own input rows).  Two ways to share
+    // the image's tiles out over them: evenly, or as full workgroups and a short last one; a
+    // workgroup's matrix time is that of its busier pixel half, ceil(tiles / 2), and the way with
+    // the smaller sum over the image is taken, evenly on a tie (28 x 28 outputs, 25 tiles, limit 6:
+    // 6,6,6,6,1 = 13 half-tiles against 5 x 5 = 15, measured 2 % faster; 14 x 14, 7 tiles: 6,1
+    // measured slower than 4,3 at the same sum).  (The kernel gives every workgroup `tiles` tiles and
+    // the last one the rest.)
     const int total = (int)((OHW + 31) / 32);
-    for (int most = std::min(kMaxTiles, total); most >= 1; --most) {
-        const int groups = ceil_div(total, most), tiles = ceil_div(total, groups);
+    auto fits = [&](int tiles, int &rows, size_t &lds) {
         // 32*tiles consecutive pixels span at most this many output rows
         const int orows = (int)std::min<long long>(g.OH, (32LL * tiles + g.OW - 2) / g.OW + 1);
-        const int rows = (orows - 1) * g.sh + g.kh;
+        rows = (orows - 1) * g.sh + g.kh;
         const long long npos = (long long)rows * pl.pitch;
-        const size_t lds = 2 * ((size_t)npos * kPosBytes + kDumpBytes + (size_t)g.kh * g.kw * kFiltersPerWg * 4);
-        if (npos <= (long long)kGran * 128 && lds <= kLdsBudget) {
-            pl.ok = true; pl.tiles = tiles; pl.rows_max = rows; pl.lds = lds;
+        lds = 2 * ((size_t)npos * kPosBytes + kDumpBytes + (size_t)g.kh * g.kw * kFiltersPerWg * 4);
+        return npos <= (long long)kGran * 128 && lds <= kLdsBudget;
+    };
+    for (int most = std::min(kMaxTiles, total); most >= 1; --most) {
+        const int groups = ceil_div(total, most), even = ceil_div(total, groups);
+        int rows;
+        size_t lds;
+        if (!fits(most, rows, lds)) {
+            if (even == most || !fits(even, rows, lds)) continue;
+            pl.ok = true; pl.tiles = even; pl.rows_max = rows; pl.lds = lds;
             return pl;
         }
+        // both fit (`most` does, and `even` is no larger)
+        // (workgroups of T tiles and one with the rest)
+        auto half_tiles = [&](int T) {
+            const int n = ceil_div(total, T), last = total - (n - 1) * T;
+            return (n - 1) * ((T + 1) / 2) + (last + 1) / 2;
+        };
+        const int tiles = half_tiles(most) < half_tiles(even) ? most : even;
+        fits(tiles, rows, lds);
+        pl.ok = true; pl.tiles = tiles; pl.rows_max = rows; pl.lds = lds;
+        return pl;
     }
     return pl;
 }
