@@ -156,6 +156,31 @@ def test_null_and_alignment_rejected(xb):
     assert L.xnor_bwn_conv2d_fwd_algo(ok, ok, ok, sp, ok, 99, None) == xb.E_UNSUPPORTED
     wide = xb.Shape(1, 64, 8, 4000, 8, 3, 3, 1, 1, 1, 1)      # rows too wide for the matrix-core kernel's LDS band
     assert L.xnor_bwn_conv2d_fwd_algo(ok, ok, ok, ctypes.byref(wide.c()), ok, xb.ALGO_MFMA, None) == xb.E_UNSUPPORTED
+    # the three-term bf16 kernel: up to 32 taps, and rows that fit its staging
+    assert L.xnor_bwn_conv2d_fwd_algo(ok, ok, ok, ctypes.byref(wide.c()), ok, xb.ALGO_MFMA_SPLIT, None) == xb.E_UNSUPPORTED
+    seven = xb.Shape(1, 64, 16, 16, 8, 7, 7, 1, 1, 3, 3)
+    assert L.xnor_bwn_conv2d_fwd_algo(ok, ok, ok, ctypes.byref(seven.c()), ok, xb.ALGO_MFMA_SPLIT, None) == xb.E_UNSUPPORTED
+    assert L.xnor_bwn_conv2d_fwd_algo(None, ok, ok, sp, ok, xb.ALGO_MFMA_SPLIT, None) == xb.E_NULL
+
+
+def test_probe_arguments_rejected(xb):
+    """The measurement probes check their arguments before any HIP call."""
+    L = xb.lib
+    ok = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1004)
+    x = ctypes.c_double()
+    assert L.xnor_probe_mfma_fp4(256, 10, None, ctypes.byref(x), None) == xb.E_NULL
+    assert L.xnor_probe_mfma_fp4(0, 10, ok, ctypes.byref(x), None) == xb.E_SHAPE
+    assert L.xnor_probe_mfma_fp4(256, 0, ok, ctypes.byref(x), None) == xb.E_SHAPE
+    assert L.xnor_probe_mfma_bf16(256, 10, 1, ok, None, None) == xb.E_NULL
+    assert L.xnor_probe_mfma_bf16((1 << 20) + 1, 10, 0, ok, ctypes.byref(x), None) == xb.E_SHAPE
+    assert L.xnor_probe_xor_popcount(256, (1 << 24) + 1, ok, ctypes.byref(x), None) == xb.E_SHAPE
+    assert L.xnor_probe_copy(None, ok, 1024, None) == xb.E_NULL
+    assert L.xnor_probe_copy(ok, ok, 1000, None) == xb.E_SHAPE
+    assert L.xnor_probe_copy(ok, odd, 1024, None) == xb.E_ALIGN
+    assert L.xnor_probe_read(ok, 0, ok, None) == xb.E_SHAPE
+    assert L.xnor_probe_read(odd, 1024, ok, None) == xb.E_ALIGN
+    assert L.xnor_probe_read(ok, 1024, None, None) == xb.E_NULL
 
 
 def test_binding_refuses_cpu_tensors(xb):

@@ -152,3 +152,21 @@ def test_bwn_on_binary_input_equals_the_xnor_path(xb):
         out = xb.xnor_bwn_conv2d_fwd(dI, Wpk, alpha, s, algo=algo)
         torch.cuda.synchronize()
         assert torch.equal(out, dot.float() * alpha[None, :, None, None])
+
+
+def test_measurement_probes_run(xb):
+    """The probes of bench.py --peaks: each enqueues its kernel and reports the work it issued."""
+    print("case probes", flush=True)
+    sink_f = torch.zeros((4,), dtype=torch.float32, device="cuda")
+    sink_i = torch.zeros((4,), dtype=torch.int32, device="cuda")
+    assert xb.xnor_probe_mfma_fp4(256, 10, sink_f) == 256 * 4 * 10 * 8 * 32 * 32 * 64 * 2
+    assert xb.xnor_probe_mfma_bf16(256, 10, False, sink_f) == 256 * 4 * 10 * 6 * 32 * 32 * 16 * 2
+    assert xb.xnor_probe_mfma_bf16(256, 10, True, sink_f) == 256 * 4 * 10 * 6 * 32 * 32 * 16 * 2
+    assert xb.xnor_probe_xor_popcount(256, 10, sink_i) == 256 * 256 * 10 * 8 * 32
+    src = torch.arange(1 << 16, dtype=torch.float32, device="cuda")
+    dst = torch.zeros_like(src)
+    assert xb.xnor_probe_copy(src, dst) == src.numel() * 4
+    assert xb.xnor_probe_read(src, sink_i) == src.numel() * 4
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    assert float(sink_f.abs().sum()) == 0.0 and int(sink_i.abs().sum()) == 0
