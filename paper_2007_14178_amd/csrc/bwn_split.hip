@@ -35,8 +35,8 @@ constexpr int kFiltersPerWg = 128;     // 2 wave columns x 2 filter tiles x 32
 constexpr int kMaxTiles = 6;           // pixel tiles per workgroup: 2 wave rows x 3
 constexpr int kChan = 16;              // channels per chunk = the reduction length of one matrix instruction
 constexpr int kPosBytes = 112;         // 3 terms x 32 bytes + 16: see above
-constexpr int kGran = 3;               // granules (8 channels of one position) a thread fetches ahead per chunk
-constexpr int kPreWords = 8;           // filter words a thread fetches per chunk: half of the taps of a 32-channel word (kh*kw <= 32)
+constexpr int kGran = 4;               // granules (8 channels of one position) a thread fetches ahead per chunk
+constexpr int kMaxTaps = 64;
 constexpr int kDumpBytes = 1024;       // 64 lanes x 8 bytes, the three terms 32 bytes apart
 constexpr size_t kLdsBudget = 160 * 1024;  // all buffers of a workgroup (up to 80 KB: two workgroups per compute unit)
 
@@ -169,10 +169,8 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
         okbits |= ok ? 1u << q : 0u;
     }
     // filter words: word i = q * 256 + t of [taps][128] is tap 2q + t / 128 (uniform) of filter t % 128
-    const uint32_t woff = (uint32_t)min(fbase + tl, p.F - 1) * (uint32_t)(taps * p.Cw) * 4u;   // (below 2^31: the plan sees to it)
 
     float nxt[kGran][8];
-    uint32_t nxw[kPreWords];
     auto prefetch = [&](int ch) __attribute__((always_inline)) {
         const int c0 = ch * kChan + 8 * oct;
 #pragma unroll
@@ -186,27 +184,27 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
             }
         }
     };
-    // Filter words.  Word cw (32 channels) serves chunks 2cw and 2cw + 1 and is staged while word
-    // cw - 1 is in use, half of its taps per chunk: part h = taps 16h .. 16h + 15, thread t takes
-    // tap 16h + 2q + t / 128 (q < 8; the same for a whole wave) of filter t % 128.
-    auto words_load = [&](int cw, int h) __attribute__((always_inline)) {
+    // Filter words.  Word cw (32 channels) serves chunks 2cw and 2cw + 1 and is brought in while
+    // word cw - 1 is in use, straight from memory into its LDS buffer (global_load_lds_dword: a wave
+    // instruction puts its 64 lanes' dwords side by side at the LDS address in M0, no registers in
+    // between): instruction e of the 2 * taps of a word is tap e / 2, filters 64 * (e % 2) + lane;
+    // wave w issues e = w, w + 4, ...  The loads are waited for before the barrier that ends the
+    // chunk they were issued in.  (A filter past the last one gets the last one's signs: its outputs
+    // are not stored.)
+    auto words_stage = [&](int cw) __attribute__((always_inline)) {
         if (cw >= p.Cw) return;
+        const int wave4 = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+        const int lane64 = threadIdx.x & 63;
+        unsigned char *buf = words_lds + (cw & 1) * words_bytes;
+        uint32_t off[2];
 #pragma unroll
-        for (int q = 0; q < kPreWords; ++q) {
-            const int t = 16 * h + 2 * q + oct;                                  // (scalar)
-            if (t >= taps) break;
+        for (int j = 0; j < 2; ++j)
+            off[j] = (uint32_t)min(fbase + 64 * j + lane64, p.F - 1) * (uint32_t)(taps * p.Cw) * 4u;   // (below 2^31: the plan sees to it)
+        for (int e = wave4; e < 2 * taps; e += 4) {
+            const int t = e >> 1;                                               // (scalar)
             const char *wbase = reinterpret_cast<const char *>(p.Wpk + (size_t)t * p.Cw + cw);
-            nxw[q] = *reinterpret_cast<const uint32_t *>(wbase + woff);
-        }
-    };
-    // (a filter past the last one holds the last one's signs: its outputs are not stored)
-    auto words_commit = [&](int cw, int h) __attribute__((always_inline)) {
-        if (cw >= p.Cw) return;
-        uint32_t *fw_w = reinterpret_cast<uint32_t *>(words_lds + (cw & 1) * words_bytes) + h * (16 * kFiltersPerWg);
-#pragma unroll
-        for (int q = 0; q < kPreWords; ++q) {
-            if (16 * h + 2 * q + oct >= taps) break;                             // uniform
-            fw_w[q * kThreads + (int)threadIdx.x] = nxw[q];
+            const uint32_t *src = reinterpret_cast<const uint32_t *>(wbase + off[e & 1]);
+            __builtin_amdgcn_global_load_lds(src, (__attribute__((address_space(3))) void *)(buf + e * 256), 4, 0, 0);
         }
     };
     // The commit of chunk `ch` into buffer ch % 2 comes in kPieces pieces, so that each can be laid
@@ -235,12 +233,8 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
                 dst[8] = make_uint2(pair16(tl3[0], tl3[1]), pair16(tl3[2], tl3[3]));
             }
         } else if constexpr (U == 0) {
-            // while chunk ch - 1 runs: the part of word (ch - 1) / 2 + 1 fetched a chunk ago is written,
-            // the next part is fetched
-            const int cw_next = ((ch - 1) >> 1) + 1, h = (ch - 1) & 1;
-            words_commit(cw_next, h);
-            if (h == 0) words_load(cw_next, 1);
-            else words_load(cw_next + 1, 0);
+            // while an even chunk ch - 1 runs: the word after its own is brought in
+            if (((ch - 1) & 1) == 0) words_stage(((ch - 1) >> 1) + 1);
             if (ch + 1 < nchunks) prefetch(ch + 1);
         }
     };
@@ -259,19 +253,18 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
         if (from <= 3) commit_piece(std::integral_constant<int, 3>{}, ch);
         if (from <= 4) commit_piece(std::integral_constant<int, 4>{}, ch);
         if (from <= 5) commit_piece(std::integral_constant<int, 5>{}, ch);
-        if (from <= 6 && last_too) commit_piece(std::integral_constant<int, 6>{}, ch);
-        static_assert(kPieces == 7, "one line per piece");
+        if (from <= 6) commit_piece(std::integral_constant<int, 6>{}, ch);
+        if (from <= 7) commit_piece(std::integral_constant<int, 7>{}, ch);
+        if (from <= 8 && last_too) commit_piece(std::integral_constant<int, 8>{}, ch);
+        static_assert(kPieces == 9, "one line per piece");
     };
 
-    // before the first chunk: word 0 whole, chunk 0, and in flight: the first part of word 1 and chunk 1
-    words_load(0, 0);
+    // before the first chunk: word 0, chunk 0, and in flight: chunk 1
+    words_stage(0);
     prefetch(0);
-    words_commit(0, 0);
-    words_load(0, 1);
     commit_rest(0, 0, false);
-    words_commit(0, 1);
-    words_load(1, 0);
     if (nchunks > 1) prefetch(1);
+    __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): the words are in LDS
     __syncthreads();
     for (int ch = 0; ch < nchunks; ++ch) {
         const bool more = ch + 1 < nchunks;
@@ -371,13 +364,24 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
                 if constexpr (4 * NT < kPieces) if (tap < taps) { tap_body(std::integral_constant<int, 4 * NT>{}, tap); ++tap; }
                 if constexpr (5 * NT < kPieces) if (tap < taps) { tap_body(std::integral_constant<int, 5 * NT>{}, tap); ++tap; }
                 if constexpr (6 * NT < kPieces) if (tap < taps) { tap_body(std::integral_constant<int, 6 * NT>{}, tap); ++tap; }
-                static_assert(kPieces <= 7, "one line per tap that carries pieces");
+                if constexpr (7 * NT < kPieces) if (tap < taps) { tap_body(std::integral_constant<int, 7 * NT>{}, tap); ++tap; }
+                if constexpr (8 * NT < kPieces) if (tap < taps) { tap_body(std::integral_constant<int, 8 * NT>{}, tap); ++tap; }
+                static_assert(kPieces <= 9, "one line per tap that carries pieces");
                 pc = min(tap * NT, kPieces);
             }
             for (; tap < taps; ++tap) tap_body(std::integral_constant<int, -1>{}, tap);
         }
         // what the chunk's steps did not carry (few steps, or a wave without tiles)
         if (pc < kPieces) commit_rest(pc, ch + 1);
+        // the words brought in during this chunk are in LDS once all but the loads issued after them
+        // (the next prefetch: eight per granule in use) have come back
+        if (more && (ch & 1) == 0 && (ch >> 1) + 1 < p.Cw) {
+            if (ch + 2 >= nchunks) __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0): no prefetch followed
+            else if (p.npos <= 128) __builtin_amdgcn_s_waitcnt(0x0F78);          // vmcnt(8)
+            else if (p.npos <= 256) __builtin_amdgcn_s_waitcnt(0x4F70);          // vmcnt(16)
+            else if (p.npos <= 384) __builtin_amdgcn_s_waitcnt(0x4F78);          // vmcnt(24)
+            else __builtin_amdgcn_s_waitcnt(0x8F70);                             // vmcnt(32)
+        }
         __syncthreads();                                 // chunk ch has been read, chunk ch + 1 is written
     }
 
@@ -443,7 +447,7 @@ SplitPlan make_split_plan(const Geom &g)
 {
     SplitPlan pl{};
     const long long OHW = (long long)g.OH * g.OW;
-    if (g.kh * g.kw > 4 * kPreWords || OHW > (1 << 24) || (long long)g.C * g.H * g.W >= (1LL << 30)) return pl;
+    if (g.kh * g.kw > kMaxTaps || OHW > (1 << 24) || (long long)g.C * g.H * g.W >= (1LL << 30)) return pl;
     if ((long long)g.F * g.kh * g.kw * g.Cw >= (1LL << 29)) return pl;     // (32-bit byte offsets into Wpk)
     pl.pitch = g.W + 2 * g.pw;
     // Pixel tiles per workgroup: as few workgroups per image as the tile limit, the prefetch
