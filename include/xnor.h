@@ -277,8 +277,10 @@ int xnor_forward_image(const float *I, const uint32_t *Wpk, const float *alpha, 
  * value split into three bf16 terms whose sum is the value, bf16 matrix instruction with +-1
  * weights, fp32 accumulation: the same products, three instructions at 16 times the rate instead of
  * eight; an input that is not finite gives NaN, not an infinity, and a term below the normal range
- * is flushed, which adds at most alpha * 2^-125 per input value under the window to the error; XNOR_E_UNSUPPORTED where 16 channels of the rows under the workgroup's pixels, as
- * 6 bytes per value, do not fit in 64 KB of LDS, or kh*kw > 64); other values XNOR_E_UNSUPPORTED.
+ * is flushed, which adds at most alpha * 2^-125 per input value under the window to the error;
+ * XNOR_E_UNSUPPORTED where the input rows under 32 output pixels are more than 512 staged
+ * positions or do not fit, twice over and with two sets of filter words, in 160 KB of LDS, or
+ * kh*kw > 64); other values XNOR_E_UNSUPPORTED.
  */
 int xnor_bwn_conv2d_fwd(const float *I, const uint32_t *Wpk, const float *alpha, const xnor_shape *s,
                         float *out, void *stream);

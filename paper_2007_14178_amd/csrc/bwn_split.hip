@@ -14,7 +14,8 @@
 //   writes at consecutive positions touch distinct banks), zeros where the image ends (that is the
 //   zero padding).  The B operand of a matrix instruction is one 16-byte LDS read per lane (lane =
 //   pixel, eight channels), used for both filter tiles; the A operand (lane = filter, eight
-//   channels) is made in registers from eight bits of the filter's packed word.
+//   channels) is made in registers from eight bits of the filter's packed word (the words of the
+//   next 32 channels come straight from memory into LDS while the current ones are in use).
 //   Inputs that are not finite give NaN where the fp32 sum would give an infinity (inf - inf in the
 //   split); the matrix instruction flushes a term below the normal range (2^-126), so an input value
 //   contributes an error of up to 2^-125 (two of its terms) on top of the fp32 summation's.

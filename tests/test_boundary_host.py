@@ -156,10 +156,10 @@ def test_null_and_alignment_rejected(xb):
     assert L.xnor_bwn_conv2d_fwd_algo(ok, ok, ok, sp, ok, 99, None) == xb.E_UNSUPPORTED
     wide = xb.Shape(1, 64, 8, 4000, 8, 3, 3, 1, 1, 1, 1)      # rows too wide for the matrix-core kernel's LDS band
     assert L.xnor_bwn_conv2d_fwd_algo(ok, ok, ok, ctypes.byref(wide.c()), ok, xb.ALGO_MFMA, None) == xb.E_UNSUPPORTED
-    # the three-term bf16 kernel: up to 32 taps, and rows that fit its staging
+    # the three-term bf16 kernel: up to 64 taps, and rows that fit its staging
     assert L.xnor_bwn_conv2d_fwd_algo(ok, ok, ok, ctypes.byref(wide.c()), ok, xb.ALGO_MFMA_SPLIT, None) == xb.E_UNSUPPORTED
-    seven = xb.Shape(1, 64, 16, 16, 8, 7, 7, 1, 1, 3, 3)
-    assert L.xnor_bwn_conv2d_fwd_algo(ok, ok, ok, ctypes.byref(seven.c()), ok, xb.ALGO_MFMA_SPLIT, None) == xb.E_UNSUPPORTED
+    nine = xb.Shape(1, 64, 16, 16, 8, 9, 9, 1, 1, 4, 4)
+    assert L.xnor_bwn_conv2d_fwd_algo(ok, ok, ok, ctypes.byref(nine.c()), ok, xb.ALGO_MFMA_SPLIT, None) == xb.E_UNSUPPORTED
     assert L.xnor_bwn_conv2d_fwd_algo(None, ok, ok, sp, ok, xb.ALGO_MFMA_SPLIT, None) == xb.E_NULL
 
 
