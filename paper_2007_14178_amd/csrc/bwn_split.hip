@@ -451,42 +451,49 @@ SplitPlan make_split_plan(const Geom &g)
     if (g.kh * g.kw > kMaxTaps || OHW > (1 << 24) || (long long)g.C * g.H * g.W >= (1LL << 30)) return pl;
     if ((long long)g.F * g.kh * g.kw * g.Cw >= (1LL << 29)) return pl;     // (32-bit byte offsets into Wpk)
     pl.pitch = g.W + 2 * g.pw;
-    // Pixel tiles per workgroup: as few workgroups per image as the tile limit, the prefetch
-    // registers and the LDS allow (every workgroup stages its own input rows).  Two ways to share
-    // the image's tiles out over them: evenly, or as full workgroups and a short last one; a
-    // workgroup's matrix time is that of its busier pixel half, ceil(tiles / 2), and the way with
-    // the smaller sum over the image is taken, evenly on a tie (28 x 28 outputs, 25 tiles, limit 6:
-    // 6,6,6,6,1 = 13 half-tiles against 5 x 5 = 15, measured 2 % faster; 14 x 14, 7 tiles: 6,1
-    // measured slower than 4,3 at the same sum).  (The kernel gives every workgroup `tiles` tiles and
-    // the last one the rest.)
+    // Pixel tiles per workgroup T (the kernel gives every workgroup of an image T tiles and the last
+    // one the rest).  A workgroup's time is about that of its busier pixel half, ceil(T / 2) tile
+    // times, plus half a tile time of staging and epilogue, a tenth less where two workgroups fit a
+    // compute unit (<= 80 KB of LDS each) and fill each other's gaps; a launch takes as many of those
+    // as its busiest compute unit has workgroups.  Take the T with the smallest product; on a tie the
+    // one with the smaller sum of busier halves over an image, then the larger one.  (Measured: 28 x
+    // 28 outputs, 25 tiles, 6,6,6,6,1 against 5 x 5: 2 % faster; 56 x 56 with 16 images and 128
+    // filters: 272 workgroups of six tiles are two rounds of one workgroup per unit, the second
+    // nearly empty.)
     const int total = (int)((OHW + 31) / 32);
-    auto fits = [&](int tiles, int &rows, size_t &lds) {
-        // 32*tiles consecutive pixels span at most this many output rows
-        const int orows = (int)std::min<long long>(g.OH, (32LL * tiles + g.OW - 2) / g.OW + 1);
-        rows = (orows - 1) * g.sh + g.kh;
-        const long long npos = (long long)rows * pl.pitch;
-        lds = 2 * ((size_t)npos * kPosBytes + kDumpBytes + (size_t)g.kh * g.kw * kFiltersPerWg * 4);
-        return npos <= (long long)kGran * 128 && lds <= kLdsBudget;
-    };
-    for (int most = std::min(kMaxTiles, total); most >= 1; --most) {
-        const int groups = ceil_div(total, most), even = ceil_div(total, groups);
-        int rows;
-        size_t lds;
-        if (!fits(most, rows, lds)) {
-            if (even == most || !fits(even, rows, lds)) continue;
-            pl.ok = true; pl.tiles = even; pl.rows_max = rows; pl.lds = lds;
-            return pl;
+    static std::atomic<int> cus_cached{0};
+    int cus = cus_cached.load(std::memory_order_relaxed);
+    if (cus <= 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
+            (void)hipGetLastError();
+            cus = 256;
+        } else {
+            cus_cached.store(cus, std::memory_order_relaxed);
         }
-        // both fit (`most` does, and `even` is no larger)
-        // (workgroups of T tiles and one with the rest)
-        auto half_tiles = [&](int T) {
-            const int n = ceil_div(total, T), last = total - (n - 1) * T;
-            return (n - 1) * ((T + 1) / 2) + (last + 1) / 2;
-        };
-        const int tiles = half_tiles(most) < half_tiles(even) ? most : even;
-        fits(tiles, rows, lds);
-        pl.ok = true; pl.tiles = tiles; pl.rows_max = rows; pl.lds = lds;
-        return pl;
+    }
+    auto half_tiles = [&](int T) {
+        const int n = ceil_div(total, T), last = total - (n - 1) * T;
+        return (n - 1) * ((T + 1) / 2) + (last + 1) / 2;
+    };
+    double best = -1.0;
+    for (int T = std::min(kMaxTiles, total); T >= 1; --T) {
+        // 32*T consecutive pixels span at most this many output rows
+        const int orows = (int)std::min<long long>(g.OH, (32LL * T + g.OW - 2) / g.OW + 1);
+        const int rows = (orows - 1) * g.sh + g.kh;
+        const long long npos = (long long)rows * pl.pitch;
+        const size_t lds = 2 * ((size_t)npos * kPosBytes + kDumpBytes + (size_t)g.kh * g.kw * kFiltersPerWg * 4);
+        if (npos > (long long)kGran * 128 || lds > kLdsBudget) continue;
+        const long long wgs = (long long)g.N * ceil_div(g.F, kFiltersPerWg) * ceil_div(total, T);
+        const double per_wg = ((T + 1) / 2 + 0.5) * (lds <= kLdsBudget / 2 ? 0.9 : 1.0);
+        const double cost = (double)((wgs + cus - 1) / cus) * per_wg;
+        const bool better = best < 0.0 || cost < best * (1.0 - 1e-9) ||
+                            (cost <= best * (1.0 + 1e-9) && half_tiles(T) < half_tiles(pl.tiles));
+        if (better) {
+            best = std::min(best < 0.0 ? cost : best, cost);
+            pl.ok = true; pl.tiles = T; pl.rows_max = rows; pl.lds = lds;
+        }
     }
     return pl;
 }
