@@ -313,7 +313,12 @@ __global__ __launch_bounds__(64 * kPack4Slices) void pack_and_mean4_kernel(
 // halves the first one's rate), so a launch is as long as its busiest unit: the pixels are shared out
 // as equal blocks over a multiple of the units instead of as 256-pixel blocks that leave the last
 // round partly empty.
-static int pixels_per_block4(long long NP)
+// `filter_blocks`: short blocks launched behind the input blocks in the same grid (the one-launch
+// prepare): where the last round of 256-pixel blocks leaves enough units idle for them (a filter
+// block takes about a fifth of an input block's time), that layout is the better one: the filter
+// side then costs nothing (measured at 128 images of 28 x 28, 392 + 512 blocks: the step 2.4 us
+// shorter than with 512 equal input blocks and the filter blocks after them).
+static int pixels_per_block4(long long NP, int filter_blocks = 0)
 {
     static std::atomic<int> cus_cached{0};
     int cus = cus_cached.load(std::memory_order_relaxed);
@@ -323,6 +328,10 @@ static int pixels_per_block4(long long NP)
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
             cus = 256;
         cus_cached.store(cus, std::memory_order_relaxed);
+    }
+    if (filter_blocks > 0) {
+        const long long rem = ((NP + 255) / 256) % cus, idle = rem ? cus - rem : 0;
+        if (idle > 0 && filter_blocks <= 5 * idle) return 256;
     }
     const long long quads = (NP + 3) / 4;
     for (long long k = 1;; ++k) {
@@ -594,7 +603,7 @@ hipError_t launch_prepare_both(const float *x, int N, int C, int H, int W, uint3
     if (pass == 4) {
         const size_t smem4 = (size_t)kPack4Slices * 256 * sizeof(double) + (size_t)256 * Cwp * sizeof(uint32_t);
         const size_t smem = std::max(smem4, smemf);
-        const int ppb = pixels_per_block4(NP);
+        const int ppb = pixels_per_block4(NP, F);
         const long long blocks = (long long)F + ceil_div(NP, ppb);
         if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
         prepare_both_kernel<<<dim3((unsigned)blocks), dim3(64, kPack4Slices), smem, st>>>(
