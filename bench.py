@@ -358,6 +358,28 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
     roof["kernel_ms"] = conv_ms                                # mean over the timed steps (what `achieved` uses)
     roof["kernel_ms_median"] = conv_times[len(conv_times) // 2]
     roof["kernel_ms_min"] = conv_times[0]
+    # what a pair of events reads with nothing between them, and with a tiny kernel between them:
+    # the part of kernel_ms that is the bracket's own (reported, not subtracted)
+    a16 = torch.zeros((64,), dtype=torch.float32, device="cuda")
+    b16 = torch.zeros_like(a16)
+    pairs = []
+    for tiny in (False, True):
+        evs = []
+        for _ in range(200):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            if tiny:
+                xb.xnor_probe_copy(a16, b16)
+            e1.record()
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        pairs.append(sum(a.elapsed_time(b) for a, b in evs[50:]) / len(evs[50:]))
+    roof["event_pair_ms_empty"], roof["event_pair_ms_tiny_kernel"] = pairs
+    # (`achieved` and `frac` stay on the raw event time; net of the empty bracket the launch is what
+    #  the kernel trace of the same command shows)
+    if two_phase and conv_ms > pairs[0]:
+        roof["kernel_ms_net_of_empty_pair"] = conv_ms - pairs[0]
+        roof["frac_net_of_empty_pair"] = roof["frac"] * conv_ms / (conv_ms - pairs[0])
     roof["binary_gmacs"] = macs / (conv_ms * 1e-3) / 1e9
     roof["frac_of_valu_popcount_peak"] = achieved / PEAK_VALU_POPCOUNT_TOPS
     # the same launch against the HBM roof: packed operands in, fp32 out
