@@ -48,6 +48,8 @@ struct SplitParams {
     float *out;
     int N, C, H, W, F, kh, kw, sh, sw, ph, pw, OH, OW, Cw;
     int tiles, groups, fgroups;
+    int tpr;                       // 0: a tile is 32 consecutive pixels of the image; else tiles per output row: a
+                                   // tile is a 32-pixel segment of one row (the row's last one may be short)
     int rows_max, pitch, npos;     // staged rows, positions per row (W + 2*pw), rows_max * pitch
     uint32_t inv_pitch;            // ceil(2^32 / pitch), 0 for pitch 1
 };
@@ -92,8 +94,8 @@ __device__ inline bf16x8 signs_to_bf16(uint32_t w2, const uint32_t (&sh)[4], uin
 
 // The work of one wave with NT pixel tiles (0: it only takes part in the staging).
 template <int NT>
-__device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, int n, int fbase, int p0,
-                                                          int p1, int tile0, int wf)
+__device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, int n, int fbase, int t0,
+                                                          int oy0, int oy1, int tile0, int wf)
 {
     // LDS: two input buffers, taken in turn by the chunks, each [npos][3][16] bf16 at a 112-byte
     // pitch followed by a dump slot for the staging writes of threads without a position; then two
@@ -108,7 +110,20 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
     const int lane = threadIdx.x & 63;
     const int col = lane & 31, half = lane >> 5;
     const int OHW = p.OH * p.OW;
-    const int oy0 = p0 / p.OW, oy1 = (p1 - 1) / p.OW;
+    // the pixel of lane `col` in tile t of the image: its row and column (clamped to the image for
+    // the reads) and whether it exists
+    auto pixel_of = [&](int t, int &oy, int &ox) -> bool {
+        if (p.tpr == 0) {
+            const int px = t * 32 + col, pxc = min(px, OHW - 1);
+            oy = pxc / p.OW;
+            ox = pxc - oy * p.OW;
+            return px < OHW;
+        }
+        oy = t / p.tpr;
+        const int x = (t - oy * p.tpr) * 32 + col;
+        ox = min(x, p.OW - 1);
+        return x < p.OW;
+    };
     const int iy0 = oy0 * p.sh - p.ph;
     const int rows = (oy1 - oy0) * p.sh + p.kh;         // <= rows_max
     const int taps = p.kh * p.kw;
@@ -117,8 +132,8 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
     int base[NT > 0 ? NT : 1];
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
-        const int px = min(p0 + 32 * (tile0 + j) + col, p1 - 1);
-        const int oy = px / p.OW, ox = px - oy * p.OW;
+        int oy, ox;
+        pixel_of(t0 + tile0 + j, oy, ox);
         base[j] = ((oy - oy0) * p.sh * p.pitch + ox * p.sw) * kPosBytes + half * 16;
     }
 
@@ -400,8 +415,9 @@ __device__ __attribute__((always_inline)) void split_wave(const SplitParams &p, 
         }
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
-            const int px = p0 + 32 * (tile0 + j) + col;
-            if (px < p1) {
+            int oy, ox;
+            if (pixel_of(t0 + tile0 + j, oy, ox)) {
+                const int px = oy * p.OW + ox;
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
                     if (fr[r] < p.F) dst[(size_t)fr[r] * OHW + px] = acc[i][j][r] * al[r];
@@ -416,10 +432,13 @@ __global__ __launch_bounds__(kThreads, 2) void bwn_split_kernel(SplitParams p)
     const int h = b % p.fgroups; b /= p.fgroups;
     const int g = b % p.groups;
     const int n = b / p.groups;
-    const int p0 = g * p.tiles * 32;
-    const int p1 = min(p.OH * p.OW, p0 + p.tiles * 32);
+    const int OHW = p.OH * p.OW;
+    const int total = p.tpr ? p.OH * p.tpr : (OHW + 31) >> 5;
+    const int t0 = g * p.tiles, t1 = min(total, t0 + p.tiles);
+    const int nt = t1 - t0;                              // tiles this workgroup really has (1..6)
+    const int oy0 = p.tpr ? t0 / p.tpr : (t0 * 32) / p.OW;
+    const int oy1 = p.tpr ? (t1 - 1) / p.tpr : (min(OHW, t1 * 32) - 1) / p.OW;
     const int fbase = h * kFiltersPerWg;
-    const int nt = (p1 - p0 + 31) >> 5;                  // tiles this workgroup really has (1..6)
     // wave -> (filter half, pixel half).  Every wave passes
     // the same barriers whichever instance it runs (they count arrivals, not places in the code).
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
@@ -431,16 +450,16 @@ __global__ __launch_bounds__(kThreads, 2) void bwn_split_kernel(SplitParams p)
     int my_nt = wp ? nt - first : first;
     if (fbase + wf * 64 >= p.F) my_nt = 0;                // no filters for this wave: staging only
     switch (my_nt) {
-        case 0: split_wave<0>(p, n, fbase, p0, p1, tile0, wf); break;
-        case 1: split_wave<1>(p, n, fbase, p0, p1, tile0, wf); break;
-        case 2: split_wave<2>(p, n, fbase, p0, p1, tile0, wf); break;
-        default: split_wave<3>(p, n, fbase, p0, p1, tile0, wf); break;
+        case 0: split_wave<0>(p, n, fbase, t0, oy0, oy1, tile0, wf); break;
+        case 1: split_wave<1>(p, n, fbase, t0, oy0, oy1, tile0, wf); break;
+        case 2: split_wave<2>(p, n, fbase, t0, oy0, oy1, tile0, wf); break;
+        default: split_wave<3>(p, n, fbase, t0, oy0, oy1, tile0, wf); break;
     }
 }
 
 struct SplitPlan {
     bool ok;
-    int tiles, rows_max, pitch;
+    int tiles, rows_max, pitch, tpr, total;
     size_t lds;
 };
 
@@ -460,7 +479,6 @@ SplitPlan make_split_plan(const Geom &g)
     // 28 outputs, 25 tiles, 6,6,6,6,1 against 5 x 5: 2 % faster; 56 x 56 with 16 images and 128
     // filters: 272 workgroups of six tiles are two rounds of one workgroup per unit, the second
     // nearly empty.)
-    const int total = (int)((OHW + 31) / 32);
     static std::atomic<int> cus_cached{0};
     int cus = cus_cached.load(std::memory_order_relaxed);
     if (cus <= 0) {
@@ -473,26 +491,44 @@ SplitPlan make_split_plan(const Geom &g)
             cus_cached.store(cus, std::memory_order_relaxed);
         }
     }
-    auto half_tiles = [&](int T) {
-        const int n = ceil_div(total, T), last = total - (n - 1) * T;
-        return (n - 1) * ((T + 1) / 2) + (last + 1) / 2;
-    };
+    // Two ways to cut an image into tiles: 32 consecutive pixels (no pixel slot idle but in an image's
+    // last tile; a workgroup's pixels straddle rows, which costs a staged row), or 32-pixel segments
+    // of single rows (the last segment of a row short; whole rows per workgroup, which on wide rows
+    // lets more tiles share the staged rows).  Both go through the same cost.
     double best = -1.0;
-    for (int T = std::min(kMaxTiles, total); T >= 1; --T) {
-        // 32*T consecutive pixels span at most this many output rows
-        const int orows = (int)std::min<long long>(g.OH, (32LL * T + g.OW - 2) / g.OW + 1);
-        const int rows = (orows - 1) * g.sh + g.kh;
-        const long long npos = (long long)rows * pl.pitch;
-        const size_t lds = 2 * ((size_t)npos * kPosBytes + kDumpBytes + (size_t)g.kh * g.kw * kFiltersPerWg * 4);
-        if (npos > (long long)kGran * 128 || lds > kLdsBudget) continue;
-        const long long wgs = (long long)g.N * ceil_div(g.F, kFiltersPerWg) * ceil_div(total, T);
-        const double per_wg = ((T + 1) / 2 + 0.5) * (lds <= kLdsBudget / 2 ? 0.9 : 1.0);
-        const double cost = (double)((wgs + cus - 1) / cus) * per_wg;
-        const bool better = best < 0.0 || cost < best * (1.0 - 1e-9) ||
-                            (cost <= best * (1.0 + 1e-9) && half_tiles(T) < half_tiles(pl.tiles));
-        if (better) {
-            best = std::min(best < 0.0 ? cost : best, cost);
-            pl.ok = true; pl.tiles = T; pl.rows_max = rows; pl.lds = lds;
+    int best_half = 0;
+    const int tpr_rows = ceil_div(g.OW, 32);
+    for (int mode = 0; mode < 2; ++mode) {
+        const int tpr = mode ? tpr_rows : 0;
+        const int total = mode ? g.OH * tpr_rows : (int)((OHW + 31) / 32);
+        if (mode && (long long)g.OH * tpr_rows > (1 << 24)) continue;
+        auto half_tiles = [&](int T) {
+            const int n = ceil_div(total, T), last = total - (n - 1) * T;
+            return (n - 1) * ((T + 1) / 2) + (last + 1) / 2;
+        };
+        for (int T = std::min(kMaxTiles, total); T >= 1; --T) {
+            // the output rows T tiles span at most
+            int orows;
+            if (!mode) orows = (int)((32LL * T + g.OW - 2) / g.OW + 1);
+            else if (T % tpr == 0) orows = T / tpr;
+            else if (tpr % T == 0) orows = 1;
+            else orows = (T + tpr - 2) / tpr + 1;
+            orows = std::min(orows, g.OH);
+            const int rows = (orows - 1) * g.sh + g.kh;
+            const long long npos = (long long)rows * pl.pitch;
+            const size_t lds = 2 * ((size_t)npos * kPosBytes + kDumpBytes + (size_t)g.kh * g.kw * kFiltersPerWg * 4);
+            if (npos > (long long)kGran * 128 || lds > kLdsBudget) continue;
+            const long long wgs = (long long)g.N * ceil_div(g.F, kFiltersPerWg) * ceil_div(total, T);
+            const double per_wg = ((T + 1) / 2 + 0.5) * (lds <= kLdsBudget / 2 ? 0.9 : 1.0);
+            const double cost = (double)((wgs + cus - 1) / cus) * per_wg;
+            const int ht = half_tiles(T);
+            const bool better = best < 0.0 || cost < best * (1.0 - 1e-9) ||
+                                (!mode && cost <= best * (1.0 + 1e-9) && ht < best_half);
+            if (better) {
+                best = cost;
+                best_half = ht;
+                pl.ok = true; pl.tiles = T; pl.rows_max = rows; pl.lds = lds; pl.tpr = tpr; pl.total = total;
+            }
         }
     }
     return pl;
@@ -513,8 +549,8 @@ hipError_t launch_bwn_split(const float *I, const uint32_t *Wpk, const float *al
     p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw; p.OH = g.OH; p.OW = g.OW; p.Cw = g.Cw;
     p.tiles = pl.tiles; p.rows_max = pl.rows_max; p.pitch = pl.pitch; p.npos = pl.rows_max * pl.pitch;
     p.inv_pitch = reciprocal((unsigned long long)pl.pitch);
-    const long long OHW = (long long)g.OH * g.OW;
-    p.groups = ceil_div(OHW, 32LL * pl.tiles);
+    p.tpr = pl.tpr;
+    p.groups = ceil_div(pl.total, pl.tiles);
     p.fgroups = ceil_div(g.F, kFiltersPerWg);
     const long long blocks = (long long)g.N * p.groups * p.fgroups;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
