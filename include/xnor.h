@@ -287,6 +287,24 @@ int xnor_bwn_conv2d_fwd(const float *I, const uint32_t *Wpk, const float *alpha,
 int xnor_bwn_conv2d_fwd_algo(const float *I, const uint32_t *Wpk, const float *alpha,
                              const xnor_shape *s, float *out, int algo, void *stream);
 
+/* The algorithm XNOR_ALGO_AUTO resolves to in xnor_bwn_conv2d_fwd_algo for this shape (an
+ * xnor_algo), or a negative status.  Host only. */
+int xnor_bwn_pick_algo(const xnor_shape *s);
+
+/*
+ * The launch XNOR_ALGO_MFMA_SPLIT makes for this shape on a GPU of `compute_units` units (0: the
+ * current device's, 256 where there is none).  Host only; for tests and for reading a timing.
+ *   *tiles         32-pixel tiles of one image a workgroup takes (1..6; an image's last workgroup
+ *                  the rest)
+ *   *row_segments  0: a tile is 32 consecutive output pixels; k > 0: a tile is one of the k
+ *                  32-pixel segments of one output row (the row's last one short)
+ *   *lds_bytes     dynamic LDS per workgroup (<= 160 KB; <= 80 KB lets two share a unit)
+ *   *workgroups    the grid: N x ceil(F/128) x ceil(tiles of an image / *tiles)
+ * XNOR_E_UNSUPPORTED where XNOR_ALGO_MFMA_SPLIT would return it; XNOR_E_SHAPE for compute_units < 0.
+ */
+int xnor_bwn_split_plan(const xnor_shape *s, int compute_units, int *tiles, int *row_segments,
+                        size_t *lds_bytes, long long *workgroups);
+
 /*
  * Real-valued ("vanilla") convolution: the float comparison that the paper's timings set the XNOR
  * convolution against (Sec. IV, Table I).  Nothing is binarised and there are no scaling factors:

@@ -106,6 +106,9 @@ def _load() -> ctypes.CDLL:
     L.xnor_conv2d_fp32_fwd.argtypes = [vp, vp, sp, vp, vp]
     L.xnor_conv2d_fp32_fwd_algo.argtypes = [vp, vp, sp, vp, ci, vp]
     L.xnor_conv2d_pick_algo.argtypes = [sp, sz]
+    L.xnor_bwn_pick_algo.argtypes = [sp]
+    L.xnor_bwn_split_plan.argtypes = [sp, ci, ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(sz),
+                                      ctypes.POINTER(ctypes.c_longlong)]
     L.xnor_conv2d_workspace_bytes.argtypes = [sp, ctypes.POINTER(sz)]
     for name in ("xnor_out_dim", "xnor_packed_words", "xnor_binarize_pack", "xnor_scale_K",
                  "xnor_alpha", "xnor_conv2d_fwd", "xnor_conv2d_fwd_algo", "xnor_conv2d_pick_algo",
@@ -416,6 +419,23 @@ def xnor_forward_image(I: torch.Tensor, Wpk: torch.Tensor, alpha: torch.Tensor, 
         _dev(alpha, torch.float32, (s.F,), "alpha"), ctypes.byref(s.c()), _dev(out, torch.float32, oshape, "out"),
         _dev(dot, torch.int32, oshape, "dot") if dot is not None else None, _stream()), "xnor_forward_image")
     return out, dot
+
+
+def xnor_bwn_pick_algo(s: Shape) -> int:
+    r = lib.xnor_bwn_pick_algo(ctypes.byref(s.c()))
+    if r < 0:
+        raise XnorError(r, "xnor_bwn_pick_algo")
+    return r
+
+
+def xnor_bwn_split_plan(s: Shape, compute_units: int = 0) -> dict:
+    """The launch ALGO_MFMA_SPLIT makes for this shape: tiles per workgroup, row segments (0 =
+    tiles of consecutive pixels), LDS bytes per workgroup, workgroups."""
+    t, r = ctypes.c_int(), ctypes.c_int()
+    b, w = ctypes.c_size_t(), ctypes.c_longlong()
+    _ok(lib.xnor_bwn_split_plan(ctypes.byref(s.c()), compute_units, ctypes.byref(t), ctypes.byref(r),
+                                ctypes.byref(b), ctypes.byref(w)), "xnor_bwn_split_plan")
+    return {"tiles": t.value, "row_segments": r.value, "lds_bytes": b.value, "workgroups": w.value}
 
 
 def xnor_bwn_conv2d_fwd(I: torch.Tensor, Wpk: torch.Tensor, alpha: torch.Tensor, s: Shape,

@@ -463,7 +463,7 @@ struct SplitPlan {
     size_t lds;
 };
 
-SplitPlan make_split_plan(const Geom &g)
+SplitPlan make_split_plan(const Geom &g, int cus = 0)
 {
     SplitPlan pl{};
     const long long OHW = (long long)g.OH * g.OW;
@@ -480,7 +480,7 @@ SplitPlan make_split_plan(const Geom &g)
     // filters: 272 workgroups of six tiles are two rounds of one workgroup per unit, the second
     // nearly empty.)
     static std::atomic<int> cus_cached{0};
-    int cus = cus_cached.load(std::memory_order_relaxed);
+    if (cus <= 0) cus = cus_cached.load(std::memory_order_relaxed);
     if (cus <= 0) {
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
@@ -537,6 +537,18 @@ SplitPlan make_split_plan(const Geom &g)
 }  // namespace
 
 bool bwn_split_supports(const Geom &g) { return make_split_plan(g).ok; }
+
+bool bwn_split_plan(const Geom &g, int compute_units, int *tiles, int *row_segments, size_t *lds_bytes,
+                    long long *workgroups)
+{
+    const SplitPlan pl = make_split_plan(g, compute_units);
+    if (!pl.ok) return false;
+    *tiles = pl.tiles;
+    *row_segments = pl.tpr;
+    *lds_bytes = pl.lds;
+    *workgroups = (long long)g.N * ceil_div(g.F, kFiltersPerWg) * ceil_div(pl.total, pl.tiles);
+    return true;
+}
 
 hipError_t launch_bwn_split(const float *I, const uint32_t *Wpk, const float *alpha, const Geom &g,
                             float *out, hipStream_t st)

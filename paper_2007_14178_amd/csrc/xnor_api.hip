@@ -338,9 +338,7 @@ int xnor_bwn_conv2d_fwd_algo(const float *I, const uint32_t *Wpk, const float *a
     const int rc = make_geom(s, &g);
     if (rc) return rc;
     if (!aligned(I, 4) || !aligned(Wpk, 4) || !aligned(alpha, 4) || !aligned(out, 4)) return XNOR_E_ALIGN;
-    if (algo == XNOR_ALGO_AUTO)
-        algo = xnor::bwn_split_supports(g) ? XNOR_ALGO_MFMA_SPLIT
-               : xnor::bwn_mfma_supports(g) ? XNOR_ALGO_MFMA : XNOR_ALGO_DIRECT;
+    if (algo == XNOR_ALGO_AUTO) algo = xnor_bwn_pick_algo(s);
     switch (algo) {
         case XNOR_ALGO_DIRECT:
             return hip_status(xnor::launch_bwn_direct(I, Wpk, alpha, g, out, (hipStream_t)stream));
@@ -353,6 +351,28 @@ int xnor_bwn_conv2d_fwd_algo(const float *I, const uint32_t *Wpk, const float *a
         default:
             return XNOR_E_UNSUPPORTED;
     }
+}
+
+int xnor_bwn_pick_algo(const xnor_shape *s)
+{
+    if (!s) return XNOR_E_NULL;
+    xnor::Geom g;
+    const int rc = make_geom(s, &g);
+    if (rc) return rc;
+    return xnor::bwn_split_supports(g) ? XNOR_ALGO_MFMA_SPLIT
+           : xnor::bwn_mfma_supports(g) ? XNOR_ALGO_MFMA : XNOR_ALGO_DIRECT;
+}
+
+int xnor_bwn_split_plan(const xnor_shape *s, int compute_units, int *tiles, int *row_segments,
+                        size_t *lds_bytes, long long *workgroups)
+{
+    if (!s || !tiles || !row_segments || !lds_bytes || !workgroups) return XNOR_E_NULL;
+    if (compute_units < 0) return XNOR_E_SHAPE;
+    xnor::Geom g;
+    const int rc = make_geom(s, &g);
+    if (rc) return rc;
+    return xnor::bwn_split_plan(g, compute_units, tiles, row_segments, lds_bytes, workgroups)
+               ? XNOR_OK : XNOR_E_UNSUPPORTED;
 }
 
 int xnor_bwn_conv2d_fwd(const float *I, const uint32_t *Wpk, const float *alpha, const xnor_shape *s,

@@ -52,6 +52,8 @@ hipError_t launch_conv_image(const float *I, const uint32_t *Wpk, const float *a
 
 bool bwn_mfma_supports(const Geom &g);
 bool bwn_split_supports(const Geom &g);
+bool bwn_split_plan(const Geom &g, int compute_units, int *tiles, int *row_segments, size_t *lds_bytes,
+                    long long *workgroups);
 hipError_t launch_bwn_split(const float *I, const uint32_t *Wpk, const float *alpha, const Geom &g,
                             float *out, hipStream_t st);
 bool conv_fp32_mfma_supports(const Geom &g);

@@ -163,6 +163,72 @@ def test_null_and_alignment_rejected(xb):
     assert L.xnor_bwn_conv2d_fwd_algo(None, ok, ok, sp, ok, xb.ALGO_MFMA_SPLIT, None) == xb.E_NULL
 
 
+def _rows_spanned(OH, OW, tiles, row_segments):
+    """Most output rows any workgroup's tiles touch, by walking every workgroup's tiles."""
+    worst = 0
+    if row_segments:
+        total = OH * row_segments
+        for t0 in range(0, total, tiles):
+            t1 = min(total, t0 + tiles)
+            worst = max(worst, (t1 - 1) // row_segments - t0 // row_segments + 1)
+    else:
+        total = (OH * OW + 31) // 32
+        for t0 in range(0, total, tiles):
+            last = min(OH * OW, min(total, t0 + tiles) * 32) - 1
+            worst = max(worst, last // OW - (t0 * 32) // OW + 1)
+    return worst, total
+
+
+def test_bwn_split_plan_holds_what_its_tiles_need(xb):
+    """The launch plan of the three-term bf16 kernel, on the benchmark layers and on seeded random
+    shapes, for several unit counts: the staged positions it sizes the LDS for cover the input rows
+    under the output rows that any workgroup's tiles really touch (walked tile by tile here), within
+    the kernel's limits, and the grid is N x filter groups x tile groups."""
+    import numpy as np
+    from paper_2007_14178_amd.workloads import LAYERS
+    shapes = [(L.N, L.C, L.H, L.W, L.F, L.kh, L.kw, L.sh, L.sw, L.ph, L.pw) for L in LAYERS.values()]
+    rng = np.random.default_rng(77)
+    for _ in range(300):
+        kh, kw = int(rng.integers(1, 8)), int(rng.integers(1, 8))
+        H, W = int(rng.integers(kh, 90)), int(rng.integers(kw, 140))
+        shapes.append((int(rng.integers(1, 20)), int(rng.integers(1, 200)), H, W, int(rng.integers(1, 400)),
+                       kh, kw, int(rng.integers(1, 4)), int(rng.integers(1, 4)),
+                       int(rng.integers(0, kh)), int(rng.integers(0, kw))))
+    seen_modes = set()
+    for full in shapes:
+        s = xb.Shape(*full)
+        N, C, H, W, F, kh, kw, sh, sw, ph, pw = full
+        OH, OW = (H + 2 * ph - kh) // sh + 1, (W + 2 * pw - kw) // sw + 1
+        for cus in (256, 64, 1):
+            try:
+                pl = xb.xnor_bwn_split_plan(s, cus)
+            except xb.XnorError as e:
+                assert e.status == xb.E_UNSUPPORTED, full
+                assert xb.xnor_bwn_pick_algo(s) != xb.ALGO_MFMA_SPLIT
+                continue
+            assert xb.xnor_bwn_pick_algo(s) == xb.ALGO_MFMA_SPLIT
+            T, seg, lds = pl["tiles"], pl["row_segments"], pl["lds_bytes"]
+            assert 1 <= T <= 6 and lds <= 160 * 1024, (full, pl)
+            assert seg in (0, (OW + 31) // 32), (full, pl)
+            seen_modes.add(bool(seg))
+            body = lds // 2 - 1024 - kh * kw * 128 * 4       # per tile buffer: positions x 112 bytes
+            assert lds % 2 == 0 and body > 0 and body % 112 == 0, (full, pl)
+            npos = body // 112
+            assert npos <= 512, (full, pl)
+            rows_out, total = _rows_spanned(OH, OW, T, seg)
+            need = ((rows_out - 1) * sh + kh) * (W + 2 * pw)
+            assert npos >= need, (full, pl, rows_out)
+            assert pl["workgroups"] == N * ((F + 127) // 128) * ((total + T - 1) // T), (full, pl)
+    assert seen_modes == {False, True}
+    # the two measured cases that motivated the row segments: 56 x 56 outputs, 16 images, 128 filters
+    k7 = xb.xnor_bwn_split_plan(xb.Shape(16, 128, 56, 56, 128, 7, 7, 1, 1, 3, 3), 256)
+    assert k7["row_segments"] == 2 and k7["tiles"] == 4
+    with pytest.raises(xb.XnorError):
+        xb.xnor_bwn_split_plan(xb.Shape(1, 64, 8, 4000, 8, 3, 3, 1, 1, 1, 1), 256)
+    assert xb.lib.xnor_bwn_split_plan(None, 0, None, None, None, None) == xb.E_NULL
+    assert xb.lib.xnor_bwn_pick_algo(None) == xb.E_NULL
+
+
 def test_probe_arguments_rejected(xb):
     """The measurement probes check their arguments before any HIP call."""
     L = xb.lib

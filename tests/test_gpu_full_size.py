@@ -80,7 +80,7 @@ def test_full_size_layer(name):
         assert 0.8 < float(interior.var()) / L.n_red < 1.25
 
 
-@pytest.mark.parametrize("name", ["c5", "c4_conv2", "c2_k7"])
+@pytest.mark.parametrize("name", ["c5", "c4_conv2", "c2_k7", "c2_k3"])
 def test_full_size_bwn_layer(name):
     """The Binary-Weight-Network layer at full size, as bench.py --bwn launches it: sampled (image,
     filter) planes against the oracle at the bar |got - ref| <= 1e-5 * alpha * sum|I| over the window;
