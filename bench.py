@@ -380,6 +380,21 @@ def run_layer(args, xb, torch, layer, algo_name, make_input, make_weights):
     if two_phase and conv_ms > pairs[0]:
         roof["kernel_ms_net_of_empty_pair"] = conv_ms - pairs[0]
         roof["frac_net_of_empty_pair"] = roof["frac"] * conv_ms / (conv_ms - pairs[0])
+    if two_phase:
+        # the same launch 200 times in a row inside ONE pair of events (the bracket's cost spread
+        # over 200 launches, the dispatch gap between two of them included): how long the launch
+        # is when nothing else runs between two of them.  Not the step's conditions: there the
+        # HBM-bound prepare launches sit between two convolutions.
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(200):
+            if not k_in_conv:
+                xb.xnor_conv2d_fwd_expanded(Ipk, ws, K, alpha, s, out=out)
+            else:
+                xb.xnor_conv2d_fwd_expanded(Ipk, ws, None, alpha, s, out=out, A=A)
+        e1.record()
+        torch.cuda.synchronize()
+        roof["kernel_ms_back_to_back"] = e0.elapsed_time(e1) / 200
     roof["binary_gmacs"] = macs / (conv_ms * 1e-3) / 1e9
     roof["frac_of_valu_popcount_peak"] = achieved / PEAK_VALU_POPCOUNT_TOPS
     # the same launch against the HBM roof: packed operands in, fp32 out
