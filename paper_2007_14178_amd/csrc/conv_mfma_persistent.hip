@@ -77,6 +77,8 @@ struct PParams {
     int start_turn;  // the first group lets the second one start at this turn of its first item
     int prio_mask;   // the second group raises its issue priority in the turns t with (t & prio_mask) != 0
     int stagger;     // the odd workgroups of an XCD start this many times 1024 cycles late (0: all at once)
+    int scr16;       // start of the eight waves' 2 KB store scratch (16-byte units), if quad is set
+    int quad;        // the fp32 outputs leave as 16-byte stores of four consecutive pixels (through scr16)
 #ifdef XNOR_TS_BUILD
     unsigned long long *ts;   // (measurement build) [workgroup][group][item < 8][8] shader-clock stamps
     int dbg;                  // (measurement build) 1: no output stores, 2: second groups idle
@@ -1116,6 +1118,54 @@ __global__ __launch_bounds__(512) void conv_mfma_persistent_kernel(PParams p)
             }
         }
     };
+    // The same filter tile as 16-byte stores: a wave cannot have more than 64 vector-memory
+    // operations in flight, so 128 dword stores per item hold it until the first ones are
+    // acknowledged; 32 stores of 16 bytes it issues and leaves behind.  The accumulators go through
+    // a 2 KB LDS scratch of the wave's own (no other wave touches it, LDS operations of a wave
+    // execute in order): a stage is two registers of all four pixel tiles written as they lie (2
+    // registers x 2 planes x 128 pixels), read back as four consecutive pixels per lane (32 lanes per
+    // plane) and stored, plane by plane as above.
+    auto store_filter_tile_quads = [&](float *tile_base, auto value) {
+        typedef float __attribute__((may_alias)) fa_t;
+        typedef float __attribute__((ext_vector_type(4), may_alias)) f4a_t;
+        typedef float __attribute__((ext_vector_type(4))) f4_t;
+        typedef __attribute__((address_space(1))) f4_t *ptr4_t;
+        const int lane_s = fresh_lane();
+        const int l32s = lane_s & 31, kgs = lane_s >> 5;
+        // The lane as a writer of four consecutive pixels of its half-wave's plane (the host has
+        // checked that such a quad never straddles two images and is 16-byte aligned).  Where the
+        // wave's last tile is ragged the lanes past the last quad store that last quad once more
+        // (the same bytes to the same place): no store is predicated.  (Formed here, per filter
+        // tile, rather than kept in registers from the start of the phase.)
+        const int nq = min(8 * cur.my_nt, (cur.npix - cur.tile0 * 32) >> 2);   // quads of the wave's own tiles (uniform, > 0)
+        const int ql = min(l32s, nq - 1);
+        const int q4 = cur.tile0 * 32 + 4 * ql;
+        const int Rl = (int)fdiv((uint32_t)q4, p.dOW), ox = q4 - Rl * p.OW;
+        const int dn = (int)fdiv((uint32_t)(cur.oy0 + Rl), p.dOH);
+        const int oy = cur.oy0 + Rl - dn * p.OH;
+        uint32_t vq = (uint32_t)((((long long)dn * p.F + 4 * kgs) * OHW + oy * p.OW + ox) * 4);
+        float *const scr = reinterpret_cast<float *>(lds + p.scr16) + wave8 * 512;
+        fa_t *const wr = scr + kgs * 128 + l32s;
+        const f4a_t *const rd = reinterpret_cast<const f4a_t *>(scr + kgs * 128 + 4 * ql);
+        const long long plane1 = (long long)OHW * 4, plane5 = 5 * plane1;
+        asm volatile("" : "+v"(vq));
+        const char *ub = reinterpret_cast<const char *>(tile_base);
+#pragma unroll
+        for (int sgi = 0; sgi < 8; ++sgi) {
+#pragma unroll
+            for (int e = 0; e < 2; ++e)
+#pragma unroll
+                for (int j = 0; j < kWN; ++j) wr[e * 256 + 32 * j] = value(j, 2 * sgi + e);
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int r = 2 * sgi + e;
+                const f4a_t va = rd[(e * 256) / 4];
+                const f4_t v = {va[0], va[1], va[2], va[3]};
+                *(ptr4_t)(ub + vq) = v;
+                ub += (r & 3) == 3 ? plane5 : plane1;
+            }
+        }
+    };
     auto store_outputs = [&]() {
 #pragma unroll
         for (int i = 0; i < kWM; ++i) {
@@ -1129,6 +1179,12 @@ __global__ __launch_bounds__(512) void conv_mfma_persistent_kernel(PParams p)
             float al[16];
 #pragma unroll
             for (int r = 0; r < 16; ++r) al[r] = Al[8 * (r >> 2) + (r & 3)];
+            if (p.quad && nfilt >= 32) {
+                if (cur.my_nt > 0 && cur.npix > cur.tile0 * 32)
+                    store_filter_tile_quads(p.out + tile_el,
+                                        [&](int j, int r) -> float { return acc[i][j][r] * (kvs[j] * al[r]); });
+                continue;      // (p.quad is not set when dot is wanted)
+            }
             store_filter_tile(p.out + tile_el, nfilt,
                               [&](int j, int r) -> float { return acc[i][j][r] * (kvs[j] * al[r]); });
             if (p.dot)
@@ -1426,6 +1482,7 @@ struct PPlan {
     bool ok;
     int TH, Wp, RHfull, S2, CH, nchunks, pitch16, buf16, ka16, dump16, grp16, shared16, tab_len, vw;
     int chunk_steps, T, nturns, tile_steps, f_tiles;
+    int scr16;       // start of the waves' store scratch (16-byte units), 0 if the LDS has no room for it
     size_t lds_bytes, ws_bytes;
 };
 
@@ -1487,6 +1544,12 @@ PPlan make_pplan(const Geom &g, const void *Ipk)
         pl.T = T;
         pl.nturns = nturns;
         pl.lds_bytes = 2 * group + shared;
+        // 2 KB per wave for the 16-byte output stores, where there is room
+        pl.scr16 = 0;
+        if (pl.lds_bytes + 8 * 2048 <= kLdsMax) {
+            pl.scr16 = (int)(pl.lds_bytes / 16);
+            pl.lds_bytes += 8 * 2048;
+        }
         found = true;
     }
     if (!found) return pl;
@@ -1610,6 +1673,12 @@ hipError_t launch_conv_mfma_persistent(const uint32_t *Ipk, const float *K, cons
     // a band touches at most TH/OH + 2 images; a lane's offset also spans the tile's 32 planes
     p.near_out = ((long long)(pl.TH / g.OH + 2) * g.F + 32) * g.OH * g.OW * 4 < (1LL << 31);
     p.tile_steps = pl.tile_steps;
+    // 16-byte output stores: four consecutive pixels of the batch's (n, oy, ox) order must be four
+    // consecutive, 16-byte aligned floats of one plane: images and bands are whole quads
+    p.scr16 = pl.scr16;
+    p.quad = pl.scr16 > 0 && p.near_out && !dot && !Opk && out &&
+             (reinterpret_cast<uintptr_t>(out) & 15) == 0 &&
+             ((long long)g.OH * g.OW) % 4 == 0 && ((long long)pl.TH * g.OW) % 4 == 0;
     p.dCHV = make_fastdiv(pl.CH / pl.vw);
     p.dWp = make_fastdiv(pl.Wp);
     p.dRH = make_fastdiv(pl.RHfull);
@@ -1629,6 +1698,9 @@ hipError_t launch_conv_mfma_persistent(const uint32_t *Ipk, const float *K, cons
         p.work_per_xcd = p.whole_items + 2 * (p.items_per_xcd - p.whole_items);
         p.wgs_per_xcd = std::min(cus_per_xcd, p.work_per_xcd);
         p.start_turn = -1;
+        // (all groups store at once at the end and no matrix loop runs beside the stores: the
+        //  one-pixel stores are as fast there, without the pass through the LDS)
+        p.quad = 0;
     } else {
         // Several rounds: the items beyond the last whole round go out as half items when that
         // spreads them over more groups (the kernel's length is that of its busiest compute
@@ -1657,6 +1729,8 @@ hipError_t launch_conv_mfma_persistent(const uint32_t *Ipk, const float *K, cons
         if (pm) p.prio_mask = atoi(pm);
         const char *sg = getenv("XNOR_STAGGER");
         if (sg) p.stagger = atoi(sg);
+        const char *qd = getenv("XNOR_NOQUAD");
+        if (qd && atoi(qd)) p.quad = 0;
         const char *wg = getenv("XNOR_WGS");
         if (wg) p.wgs_per_xcd = std::min(p.wgs_per_xcd, atoi(wg));
     }

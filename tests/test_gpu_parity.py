@@ -248,6 +248,52 @@ def test_dot_null_gives_same_out(xb):
         assert b[-1] is None and torch.equal(a[-2], b[-2])
 
 
+@pytest.mark.parametrize("misalign", [0, 1])
+@pytest.mark.parametrize("shape", [(3, 64, 28, 28, 160, 3, 3, 1, 1, 1, 1),     # last band ragged (84 of 252 pixels)
+                                   (5, 64, 14, 14, 150, 3, 3, 1, 1, 1, 1),     # bands span images; last filter tile partial
+                                   (2, 32, 30, 30, 64, 5, 5, 1, 1, 2, 2),      # 240-pixel bands, half a tile idle
+                                   (2, 64, 26, 12, 96, 3, 3, 1, 1, 1, 1),      # 12-pixel rows
+                                   (2, 64, 56, 56, 64, 3, 3, 2, 2, 1, 1),      # stride 2
+                                   (2, 64, 13, 13, 64, 3, 3, 1, 1, 1, 1),      # 169 pixels per plane: no quads
+                                   (44, 32, 28, 28, 512, 3, 3, 1, 1, 1, 1),    # more than one round of items, ragged end
+                                   (130, 64, 14, 14, 256, 3, 3, 1, 1, 1, 1)],  # one round, bands span images
+                         ids=lambda s: "x".join(map(str, s)) if isinstance(s, tuple) else str(s))
+def test_fp32_output_alone_through_16_byte_stores(xb, shape, misalign):
+    """Without the dot output, where planes and bands are whole groups of four pixels, `out` is
+    16-byte aligned and the layer is more than one round of the kernel's items, the matrix-core
+    kernel writes four consecutive pixels per lane through an LDS transposition.  Same bits as the run that also returns the dot products (whose stores are one
+    pixel per lane), the oracle's values, every element written and nothing outside the tensor;
+    with `out` only 4-byte aligned the one-pixel path runs and gives the same."""
+    print(f"case quad stores shape={shape} misalign={misalign}", flush=True)
+    rng = np.random.default_rng(zlib.crc32(repr(shape).encode()))
+    layer, I, Wt = random_layer(rng, "t", *shape)
+    s = xb.Shape(*shape)
+    OH, OW = xb.xnor_out_dim(s)
+    dI, dW = dev(I), dev(Wt)
+    Ipk, Wpk = xb.xnor_binarize_pack(dI), xb.xnor_binarize_pack(dW)
+    K, _ = xb.xnor_scale_K(dI, s)
+    alpha = xb.xnor_alpha(dW)
+    try:
+        ref, dot = xb.xnor_conv2d_fwd(Ipk, Wpk, K, alpha, s, want_dot=True, algo=xb.ALGO_MFMA)
+    except xb.XnorError as e:
+        if e.status == xb.E_UNSUPPORTED:
+            pytest.skip("shape not taken by the matrix-core kernel")
+        raise
+    n = s.N * s.F * OH * OW
+    guard = 4096
+    buf = torch.full((n + 2 * guard + 4,), float("nan"), dtype=torch.float32, device="cuda")
+    out = buf[guard + misalign:guard + misalign + n].view(s.N, s.F, OH, OW)
+    assert out.data_ptr() % 16 == 4 * misalign
+    xb.xnor_conv2d_fwd(Ipk, Wpk, K, alpha, s, out=out, algo=xb.ALGO_MFMA)
+    torch.cuda.synchronize()
+    assert not bool(torch.isnan(out).any())
+    assert bool(torch.isnan(buf[:guard + misalign]).all()) and bool(torch.isnan(buf[guard + misalign + n:]).all())
+    assert torch.equal(out, ref)
+    d_ref, _, a_ref, O_ref = oracle.forward(I, Wt, oshape(layer))
+    assert np.array_equal(dot.cpu().numpy(), d_ref)
+    assert_rel(out.cpu().numpy(), O_ref, "out", out_floor(d_ref, a_ref))
+
+
 @pytest.mark.parametrize("shape", [(2, 96, 27, 27, 40, 5, 5, 1, 1, 2, 2), (3, 512, 14, 14, 130, 3, 3, 1, 1, 1, 1),
                                    (1, 64, 32, 32, 64, 3, 3, 2, 2, 1, 1)], ids=lambda s: "x".join(map(str, s)))
 def test_two_call_matrix_core_path(xb, shape):
