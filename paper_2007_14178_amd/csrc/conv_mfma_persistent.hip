@@ -1150,20 +1150,54 @@ __global__ __launch_bounds__(512) void conv_mfma_persistent_kernel(PParams p)
         const long long plane1 = (long long)OHW * 4, plane5 = 5 * plane1;
         asm volatile("" : "+v"(vq));
         const char *ub = reinterpret_cast<const char *>(tile_base);
+        // software-pipelined by one stage: stage s+1 is written and read back (behind stage s's reads
+        // in the LDS's queue, so nothing is overwritten early) before stage s's values are stored,
+        // and a stage's LDS round trip runs under the previous stage's stores
+        auto put = [&](int sgi) {
+#ifdef XNOR_TS_BUILD
+            if (p.dbg & 8) {     // (timing only) the values formed, nothing written
 #pragma unroll
-        for (int sgi = 0; sgi < 8; ++sgi) {
+                for (int e = 0; e < 2; ++e)
+#pragma unroll
+                    for (int j = 0; j < kWN; ++j) { float t = value(j, 2 * sgi + e); asm volatile("" :: "v"(t)); }
+                return;
+            }
+#endif
 #pragma unroll
             for (int e = 0; e < 2; ++e)
 #pragma unroll
                 for (int j = 0; j < kWN; ++j) wr[e * 256 + 32 * j] = value(j, 2 * sgi + e);
+        };
+        auto get = [&](f4_t (&v)[2]) {
+#ifdef XNOR_TS_BUILD
+            if (p.dbg & 8) { v[0] = f4_t{0, 0, 0, 0}; v[1] = v[0]; return; }
+#endif
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const f4a_t va = rd[(e * 256) / 4];
+                v[e] = f4_t{va[0], va[1], va[2], va[3]};
+            }
+        };
+        f4_t cur_v[2], nxt_v[2];
+        put(0);
+        get(cur_v);
+#pragma unroll
+        for (int sgi = 0; sgi < 8; ++sgi) {
+            if (sgi < 7) {
+                put(sgi + 1);
+                get(nxt_v);
+            }
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
                 const int r = 2 * sgi + e;
-                const f4a_t va = rd[(e * 256) / 4];
-                const f4_t v = {va[0], va[1], va[2], va[3]};
-                *(ptr4_t)(ub + vq) = v;
+#ifdef XNOR_TS_BUILD
+                if (p.dbg & 12) { asm volatile("" :: "v"(cur_v[e])); } else   // (timing only) no global store
+#endif
+                *(ptr4_t)(ub + vq) = cur_v[e];
                 ub += (r & 3) == 3 ? plane5 : plane1;
             }
+            cur_v[0] = nxt_v[0];
+            cur_v[1] = nxt_v[1];
         }
     };
     auto store_outputs = [&]() {
