@@ -823,6 +823,22 @@ def run_peaks(args, xb, torch):
                 graph.replay()
             stream.synchronize()
             out[f"graph_replay_us_{n}_tiny_kernels"] = (time.perf_counter() - t0) / 2000 * 1e6
+    # what the stores of a convolution item (128 KB per four waves) cost a wave group while the
+    # other four waves of its compute unit run matrix instructions: shader-clock cycles per 128 KB,
+    # mean over the storing waves, one workgroup per compute unit and 16 workgroups on the chip
+    reps = 8
+    sink = torch.zeros((4,), dtype=torch.float32, device="cuda")
+    for wgs in (16, 256):
+        dst = torch.empty((wgs * reps * 32768,), dtype=torch.float32, device="cuda")
+        cycles = torch.zeros((wgs, 4), dtype=torch.int64, device="cuda")
+        for wide in (False, True):
+            for loop, name in ((0, "alone"), (1, "beside_back_to_back_mfma"), (2, "beside_mfma_with_pipe_idle_an_eighth")):
+                for _ in range(2):
+                    xb.xnor_probe_store_beside_mfma(wgs, reps, wide, loop, dst, cycles, sink)
+                torch.cuda.synchronize()
+                out[f"store_cycles_per_128KB_{'16B' if wide else '4B'}_stores_{name}_{wgs}wg"] = \
+                    float(cycles.to(torch.float64).mean()) / reps
+        del dst
     return out
 
 

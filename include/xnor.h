@@ -371,15 +371,27 @@ int xnor_conv2d_pick_algo(const xnor_shape *s, size_t workspace_bytes);
  *                            src to dst, 16 bytes per lane
  *   xnor_probe_read          reads `bytes` (a multiple of 16, 16-byte aligned) of src, 16 bytes per
  *                            lane, and writes nothing
+ *   xnor_probe_store_beside_mfma   what a wave's global stores cost while another wave of its SIMD
+ *                            runs matrix instructions (the convolution's epilogue beside the other
+ *                            wave group's loop): `workgroups` x 8 waves; waves 0-3 of each run a
+ *                            register-only FP4 matrix loop (matrix_loop 1: back to back, 2: the pipe
+ *                            idle an eighth of the time, 0: no loop), waves 4-7 each store `reps` x
+ *                            32 KB to dst as 16-byte (wide != 0) or 4-byte stores per lane and write
+ *                            the shader-clock cycles they took to cycles[workgroup][4] (device,
+ *                            8-byte aligned).  dst (device, 16-byte aligned) holds workgroups x reps
+ *                            x 128 KB, every byte of which is written; sink here is 8 bytes
  * `sink` (device, 4 bytes) is never written in practice; it keeps the loops alive.  `flops` and
  * `binary_macs` are host pointers.  XNOR_E_SHAPE for counts <= 0 or beyond 2^20 workgroups /
- * 2^24 iterations, or a byte count that is 0 or no multiple of 16.
+ * 2^24 iterations (store probe: 4096 workgroups, 64 repetitions, matrix_loop outside 0..2, dst_bytes
+ * too small), or a byte count that is 0 or no multiple of 16.
  */
 int xnor_probe_mfma_fp4(int workgroups, int iters, float *sink, double *flops, void *stream);
 int xnor_probe_mfma_bf16(int workgroups, int iters, int random_b, float *sink, double *flops, void *stream);
 int xnor_probe_xor_popcount(int workgroups, int iters, uint32_t *sink, double *binary_macs, void *stream);
 int xnor_probe_copy(const void *src, void *dst, size_t bytes, void *stream);
 int xnor_probe_read(const void *src, size_t bytes, uint32_t *sink, void *stream);
+int xnor_probe_store_beside_mfma(int workgroups, int reps, int wide, int matrix_loop, float *dst, size_t dst_bytes,
+                                 unsigned long long *cycles, float *sink, void *stream);
 
 #ifdef __cplusplus
 }

@@ -95,6 +95,7 @@ def _load() -> ctypes.CDLL:
     L.xnor_probe_xor_popcount.argtypes = [ci, ci, vp, dp, vp]
     L.xnor_probe_copy.argtypes = [vp, vp, sz, vp]
     L.xnor_probe_read.argtypes = [vp, sz, vp, vp]
+    L.xnor_probe_store_beside_mfma.argtypes = [ci, ci, ci, ci, vp, sz, vp, vp, vp]
     L.xnor_conv2d_fwd_expanded.argtypes = [vp, vp, sz, vp, vp, vp, sp, vp, vp, vp]
     L.xnor_box_filter_K.argtypes = [vp, sp, vp, vp]
     L.xnor_conv2d_chain_workspace_bytes.argtypes = [sp, ctypes.POINTER(sz)]
@@ -364,6 +365,17 @@ def xnor_probe_read(src: torch.Tensor, sink: torch.Tensor) -> int:
     _ok(lib.xnor_probe_read(_dev(src, src.dtype, name="src"), nbytes, _dev(sink, torch.int32, name="sink"), _stream()),
         "xnor_probe_read")
     return nbytes
+
+
+def xnor_probe_store_beside_mfma(workgroups: int, reps: int, wide: bool, matrix_loop: int, dst: torch.Tensor,
+                                 cycles: torch.Tensor, sink: torch.Tensor) -> None:
+    """Enqueue the store-beside-a-matrix-loop probe; `cycles` (int64 [workgroups][4]) receives the
+    storing waves' shader-clock times, `dst` (fp32, workgroups x reps x 128 KB) is written in full."""
+    _ok(lib.xnor_probe_store_beside_mfma(workgroups, reps, 1 if wide else 0, matrix_loop,
+                                         _dev(dst, torch.float32, name="dst"), dst.numel() * 4,
+                                         _dev(cycles, torch.int64, (workgroups, 4), "cycles"),
+                                         _dev(sink, torch.float32, name="sink"), _stream()),
+        "xnor_probe_store_beside_mfma")
 
 
 def xnor_filter_expand(Wpk: torch.Tensor, s: Shape, workspace: torch.Tensor | None = None) -> torch.Tensor:

@@ -146,6 +146,76 @@ int status(hipError_t e) { return e == hipSuccess ? XNOR_OK : XNOR_E_HIP; }
 
 }  // namespace
 
+// Stores beside a matrix loop.  One workgroup of 8 waves per compute unit, two waves per SIMD:
+// waves 0-3 run a register-only loop of the FP4 matrix instruction (LOOP 1: back to back, LOOP 2:
+// an s_nop 7 behind every second one, LOOP 0: they exit at once), waves 4-7 each store 32 KB per
+// repetition (together the 128 KB of one convolution item) as 32 stores of 16 bytes per lane
+// (WIDE) or 128 dword stores, two multiplies per stored value as in the epilogue, and write the
+// shader-clock time they took to `cycles`.  The matrix loop is long enough to outlast the stores.
+typedef float probe_f4 __attribute__((ext_vector_type(4)));
+template <bool WIDE, int LOOP>
+__global__ __launch_bounds__(512) void probe_store_beside_mfma_kernel(float *__restrict__ dst, int reps,
+                                                                      unsigned long long *__restrict__ cycles,
+                                                                      float *__restrict__ sink)
+{
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if (wave < 4) {
+        if (LOOP != 0) {
+            v16f acc[8];
+            for (int j = 0; j < 8; ++j)
+                for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+            uint32_t x = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;
+            v8i A[2], B[4];
+            for (int i = 0; i < 2; ++i)
+                for (int w = 0; w < 8; ++w) { x = x * 1664525u + 1013904223u; A[i][w] = w < 4 ? (int)(0x22222222u | (x & 0x88888888u)) : 0; }
+            for (int i = 0; i < 4; ++i)
+                for (int w = 0; w < 8; ++w) { x = x * 1664525u + 1013904223u; B[i][w] = w < 4 ? (int)(0x22222222u | (x & 0x88888888u)) : 0; }
+            for (int it = 0; it < reps * 160; ++it) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    acc[j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A[j & 1], B[j & 3], acc[j], 4, 4, 0, 0x7f7f7f7f, 0,
+                                                                             0x7f7f7f7f);
+                    if (LOOP == 2 && (j & 1)) asm volatile("s_nop 7");
+                }
+            }
+            float s = 0.f;
+            for (int j = 0; j < 8; ++j)
+                for (int r = 0; r < 16; ++r) s += acc[j][r];
+            if (s == 0.5f) sink[0] = s;
+        }
+        return;
+    }
+    float *base = dst + (long long)blockIdx.x * reps * 32768 + (wave - 4) * 8192;
+    probe_f4 v = {(float)lane, 1.f, 2.f, 3.f};
+    const float m = 1.0f + lane * 1e-6f;
+    const unsigned long long t0 = __builtin_readcyclecounter();
+    for (int r = 0; r < reps; ++r) {
+        float *p = base + (long long)r * 32768;
+        if (WIDE) {
+#pragma unroll 8
+            for (int i = 0; i < 32; ++i) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    asm volatile("v_mul_f32 %0, %0, %1" : "+v"(v[q]) : "v"(m));
+                    asm volatile("v_mul_f32 %0, %0, %1" : "+v"(v[q]) : "v"(m));
+                }
+                *reinterpret_cast<probe_f4 *>(p + i * 256 + lane * 4) = v;
+            }
+        } else {
+#pragma unroll 16
+            for (int i = 0; i < 128; ++i) {
+                asm volatile("v_mul_f32 %0, %0, %1" : "+v"(v[0]) : "v"(m));
+                asm volatile("v_mul_f32 %0, %0, %1" : "+v"(v[1]) : "v"(m));
+                p[i * 64 + lane] = v[0];
+            }
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)");
+    const unsigned long long t1 = __builtin_readcyclecounter();
+    if (lane == 0) cycles[blockIdx.x * 4 + (wave - 4)] = t1 - t0;
+    if (v[0] + v[1] + v[2] + v[3] == 0.123f) sink[1] = v[0];
+}
+
 extern "C" {
 
 int xnor_probe_mfma_fp4(int workgroups, int iters, float *sink, double *flops, void *stream)
@@ -199,6 +269,30 @@ int xnor_probe_read(const void *src, size_t bytes, uint32_t *sink, void *stream)
     const long long want = (n16 + 255) / 256;
     const int grid = (int)(want < 256 * 32 ? want : 256 * 32);
     probe_read_kernel<<<dim3(grid), dim3(256), 0, (hipStream_t)stream>>>(static_cast<const uint4 *>(src), n16, sink);
+    return status(hipGetLastError());
+}
+
+int xnor_probe_store_beside_mfma(int workgroups, int reps, int wide, int matrix_loop, float *dst, size_t dst_bytes,
+                                 unsigned long long *cycles, float *sink, void *stream)
+{
+    if (!dst || !cycles || !sink) return XNOR_E_NULL;
+    if (workgroups <= 0 || workgroups > 4096 || reps <= 0 || reps > 64 || matrix_loop < 0 || matrix_loop > 2)
+        return XNOR_E_SHAPE;
+    if (dst_bytes < (size_t)workgroups * reps * 131072) return XNOR_E_SHAPE;
+    if (((uintptr_t)dst & 15) || ((uintptr_t)cycles & 7)) return XNOR_E_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    const dim3 grid(workgroups), block(512);
+#define XNOR_PROBE_SBM(W, L) probe_store_beside_mfma_kernel<W, L><<<grid, block, 0, st>>>(dst, reps, cycles, sink)
+    if (wide) {
+        if (matrix_loop == 0) XNOR_PROBE_SBM(true, 0);
+        else if (matrix_loop == 1) XNOR_PROBE_SBM(true, 1);
+        else XNOR_PROBE_SBM(true, 2);
+    } else {
+        if (matrix_loop == 0) XNOR_PROBE_SBM(false, 0);
+        else if (matrix_loop == 1) XNOR_PROBE_SBM(false, 1);
+        else XNOR_PROBE_SBM(false, 2);
+    }
+#undef XNOR_PROBE_SBM
     return status(hipGetLastError());
 }
 

@@ -247,6 +247,13 @@ def test_probe_arguments_rejected(xb):
     assert L.xnor_probe_read(ok, 0, ok, None) == xb.E_SHAPE
     assert L.xnor_probe_read(odd, 1024, ok, None) == xb.E_ALIGN
     assert L.xnor_probe_read(ok, 1024, None, None) == xb.E_NULL
+    big = 256 * 8 * 131072
+    assert L.xnor_probe_store_beside_mfma(256, 8, 1, 1, None, big, ok, ok, None) == xb.E_NULL
+    assert L.xnor_probe_store_beside_mfma(256, 8, 1, 1, ok, big - 1, ok, ok, None) == xb.E_SHAPE     # dst too small
+    assert L.xnor_probe_store_beside_mfma(256, 65, 1, 1, ok, 256 * 65 * 131072, ok, ok, None) == xb.E_SHAPE
+    assert L.xnor_probe_store_beside_mfma(4097, 1, 1, 1, ok, 4097 * 131072, ok, ok, None) == xb.E_SHAPE
+    assert L.xnor_probe_store_beside_mfma(256, 8, 0, 3, ok, big, ok, ok, None) == xb.E_SHAPE
+    assert L.xnor_probe_store_beside_mfma(256, 8, 0, 0, odd, big, ok, ok, None) == xb.E_ALIGN
 
 
 def test_binding_refuses_cpu_tensors(xb):

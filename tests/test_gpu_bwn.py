@@ -170,3 +170,15 @@ def test_measurement_probes_run(xb):
     torch.cuda.synchronize()
     assert torch.equal(src, dst)
     assert float(sink_f.abs().sum()) == 0.0 and int(sink_i.abs().sum()) == 0
+    # the store probe writes every byte of its destination and nothing else, and reports a time per wave
+    wgs, reps = 8, 2
+    n = wgs * reps * 32768
+    for wide in (False, True):
+        for loop in (0, 1, 2):
+            buf = torch.full((n + 64,), float("nan"), dtype=torch.float32, device="cuda")
+            cycles = torch.zeros((wgs, 4), dtype=torch.int64, device="cuda")
+            xb.xnor_probe_store_beside_mfma(wgs, reps, wide, loop, buf[:n], cycles, sink_f)
+            torch.cuda.synchronize()
+            assert not bool(torch.isnan(buf[:n]).any()) and bool(torch.isnan(buf[n:]).all())
+            assert bool((cycles > 0).all())
+    assert float(sink_f.abs().sum()) == 0.0
